@@ -1,0 +1,281 @@
+"""CPU oracle for the RTPurbo sparse-attention hot path.
+
+THIS IS TEST INFRASTRUCTURE, NOT PRODUCT CODE.  Only the test-suite, the smoke
+check and the benchmark's CPU-baseline leg may import it.  It shares no code
+with the HIP library and never calls it.
+
+Everything here is plain numpy in float64, written from the definitions in the
+paper (Section 3.2 "Adaptive Sparse Attention Mechanism" and Section 4.2
+"Sparsity Analysis"), one function per step, with no blocking, fusion or
+re-ordering.  bf16 tensors travel as uint16 bit patterns and are widened
+exactly to float64 before any arithmetic.
+
+Steps (one attention layer, query position m of a sequence, head h):
+
+  retrieval head  (h in H_ret)
+    index_project   qI = bf16( W^Q_h q^pre_{m,h} )                 Sec. 3.2, indexer equation
+    index_score     s_n = scale * <qI, kI_{n,h}>  for every candidate n        (same equation)
+    topp_select     S = Top-P(s, p): the shortest prefix of the candidates in
+                    descending score order whose softmax mass reaches p        Sec. 3.2, sparse-attention equation
+    attend          O = sum_{n in S} softmax_S(q.k_n / sqrt(d_h)) v_n          (same equation)
+  local head      (h in H_loc)
+    local_set       sink tokens + sliding window                               Sec. 3.2 first sentence; Sec. 4.2
+    attend          softmax attention over that set
+  dense reference   attend over every causal candidate                         Sec. 3.2 (prefill rule)
+
+Readings taken where the paper is silent:
+  * the indexer softmax has scale 1 unless the caller passes another scale;
+  * ties in score are ordered by ascending token index;
+  * "reaches p" means cumulative mass >= p * Z; p >= 1 keeps every candidate;
+    at least one token is always kept;
+  * the window of a local head is the `window` most recent positions,
+    the query's own position included; sinks are positions 0..sink-1;
+  * GQA: query head h reads KV head h // (Hq // Hkv);
+  * decode candidates are all ctx_len cached tokens; prefill candidates are
+    the causal ones, n <= m.
+
+Parity status: every function below is pinned by tests/test_oracle_pins.py
+(brute-force dense attention, hand-worked exact-binary top-p cases, closed
+forms, invariants).  Agreement with the paper's real-model statistics
+(the top-p token counts of its tables) is "parity unpinned": they cannot be
+re-derived without the model's activations.
+"""
+from __future__ import annotations
+
+import numpy as np
+
+__all__ = [
+    "bf16_to_f64", "f64_to_bf16_bits", "index_project", "index_score",
+    "topp_from_weights", "topp_select", "attend", "local_set", "kv_head_of",
+    "decode_layer", "prefill_rows", "dense_rows",
+]
+
+
+# --------------------------------------------------------------------------
+# number formats
+# --------------------------------------------------------------------------
+def bf16_to_f64(bits) -> np.ndarray:
+    """Widen bf16 bit patterns (uint16) to float64; exact."""
+    b = np.asarray(bits)
+    if b.dtype != np.uint16:
+        raise TypeError("bf16 tensors are passed as uint16 bit patterns")
+    return (b.astype(np.uint32) << np.uint32(16)).view(np.float32).astype(np.float64)
+
+
+def f64_to_bf16_bits(x) -> np.ndarray:
+    """Round float64 to bf16, round-to-nearest-even, in ONE rounding step.
+
+    (Going through float32 first would round twice.)  Only normal-range
+    values are supported, which is all the indexer produces.
+    """
+    x = np.asarray(x, dtype=np.float64)
+    out = np.zeros(x.shape, dtype=np.float64)
+    nz = x != 0.0
+    _, e = np.frexp(x[nz])                    # |x| = f * 2**e, f in [0.5, 1)
+    ulp = np.ldexp(1.0, e - 8)                # bf16 keeps 8 significant bits
+    out[nz] = np.rint(x[nz] / ulp) * ulp      # rint = half-to-even; the scaling is exact
+    f32 = out.astype(np.float32)              # exact: 8 significant bits fit
+    if not np.all(f32.astype(np.float64) == out):
+        raise OverflowError("value outside the bf16 normal range")
+    bits32 = f32.view(np.uint32)
+    assert np.all((bits32 & np.uint32(0xFFFF)) == 0)
+    return (bits32 >> np.uint32(16)).astype(np.uint16)
+
+
+# --------------------------------------------------------------------------
+# indexer  (Sec. 3.2, indexer equation)
+# --------------------------------------------------------------------------
+def index_project(W, x_pre_bits) -> np.ndarray:
+    """qI = bf16( W x ), W float32 [r, d], x bf16 [..., d]  ->  uint16 [..., r].
+
+    The sum over d runs in float64 (every product bf16*fp32 is exact there)
+    and is rounded to bf16 once.
+    """
+    W64 = np.asarray(W, dtype=np.float32).astype(np.float64)
+    x64 = bf16_to_f64(x_pre_bits)
+    return f64_to_bf16_bits(x64 @ W64.T)
+
+
+def index_score(qI_bits, kI_bits, index_scale: float = 1.0) -> np.ndarray:
+    """s_n = index_scale * sum_i qI[i] * kI[n, i];  qI [r], kI [N, r] -> float64 [N]."""
+    q = bf16_to_f64(qI_bits)
+    k = bf16_to_f64(kI_bits)
+    return float(index_scale) * (k @ q)
+
+
+# --------------------------------------------------------------------------
+# top-p  (Sec. 3.2: S = Top-P(s, p); Sec. 3.4: "cumulative attention mass reaches p")
+# --------------------------------------------------------------------------
+def topp_from_weights(w, p: float, key=None):
+    """Shortest descending prefix whose weight reaches p * sum(w).
+
+    w   : non-negative weights, one per candidate.
+    key : what "descending" refers to (defaults to w); ties go to the lower
+          candidate index.
+    Returns (selected indices in rank order, rank order of all candidates,
+             cumulative weights in rank order, Z).
+    """
+    w = np.asarray(w, dtype=np.float64)
+    n = w.shape[0]
+    if n == 0:
+        raise ValueError("top-p needs at least one candidate")
+    if not (p > 0.0):
+        raise ValueError("p must be positive")
+    key = w if key is None else np.asarray(key, dtype=np.float64)
+    order = np.lexsort((np.arange(n), -key))      # key descending, index ascending
+    cum = np.cumsum(w[order])
+    Z = float(np.sum(w))
+    if p >= 1.0:
+        k = n
+    else:
+        reached = np.nonzero(cum >= p * Z)[0]
+        k = int(reached[0]) + 1 if reached.size else n
+    return order[:k], order, cum, Z
+
+
+def topp_select(scores, p: float) -> dict:
+    """Top-P over the softmax of `scores` (float64 [N]).
+
+    Returns dict(idx=selected token ids in rank order, count, tau=score of the
+    last selected token, mass=selected softmax mass, Z=sum exp(s - max)).
+    """
+    s = np.asarray(scores, dtype=np.float64)
+    w = np.exp(s - np.max(s))
+    sel, order, cum, Z = topp_from_weights(w, p, key=s)
+    k = sel.shape[0]
+    return dict(idx=sel, count=k, tau=float(s[sel[-1]]), mass=float(cum[k - 1] / Z),
+                Z=Z, smax=float(np.max(s)))
+
+
+# --------------------------------------------------------------------------
+# attention over a token set  (Sec. 3.2, sparse-attention equation)
+# --------------------------------------------------------------------------
+def attend(q_bits, K_bits, V_bits, token_ids, softmax_scale: float):
+    """O = sum_{n in S} softmax_S(scale * q.k_n) v_n  and its log-sum-exp.
+
+    q [d] bf16 bits; K, V [N, d] bf16 bits (one KV head of one sequence);
+    token_ids: the set S.  Returns (O float64 [d], lse float64).
+    """
+    ids = np.asarray(token_ids, dtype=np.int64)
+    q = bf16_to_f64(q_bits)
+    k = bf16_to_f64(K_bits[ids])
+    v = bf16_to_f64(V_bits[ids])
+    logits = float(softmax_scale) * (k @ q)
+    mx = np.max(logits)
+    a = np.exp(logits - mx)
+    denom = np.sum(a)
+    return (a @ v) / denom, float(mx + np.log(denom))
+
+
+def local_set(m: int, sink: int, window: int) -> np.ndarray:
+    """Tokens a local head at query position m may see: sinks + sliding window."""
+    lo = max(sink, m - window + 1)
+    head = np.arange(0, min(sink, m + 1), dtype=np.int64)
+    tail = np.arange(lo, m + 1, dtype=np.int64)
+    return np.concatenate([head, tail])
+
+
+def kv_head_of(h: int, n_q_heads: int, n_kv_heads: int) -> int:
+    return h // (n_q_heads // n_kv_heads)
+
+
+# --------------------------------------------------------------------------
+# layer drivers (loops over sequences / heads / query rows, nothing else)
+# --------------------------------------------------------------------------
+def _scale(softmax_scale, d):
+    return (1.0 / np.sqrt(float(d))) if not softmax_scale else float(softmax_scale)
+
+
+def decode_layer(*, q_bits, K_bits, V_bits, kI_bits, seq_start, ctx_len,
+                 n_q_heads, n_kv_heads, ret_heads, sink, window, p_rows,
+                 qI_bits=None, WQ=None, q_pre_bits=None,
+                 softmax_scale=0.0, index_scale=0.0, dense=False):
+    """One decode step of one layer.
+
+    q_bits [B, Hq, d]; K_bits, V_bits [Hkv, T_tot, d]; kI_bits [n_ret, T_tot, r];
+    seq_start/ctx_len [B]; p_rows [B * n_ret] (row = b * n_ret + j).
+    Either qI_bits [B, n_ret, r] or (WQ [n_ret, r, d], q_pre_bits [B, Hq, d]).
+    Returns dict(out float64 [B, Hq, d], lse [B, Hq], scores (list per row),
+    sel (list of dicts per row), qI_bits).  With dense=True every head attends
+    to the whole context (the comparison system) and no selection happens.
+    """
+    B, Hq, d = q_bits.shape
+    ret_heads = list(ret_heads)
+    n_ret = len(ret_heads)
+    sc = _scale(softmax_scale, d)
+    isc = 1.0 if not index_scale else float(index_scale)
+    out = np.zeros((B, Hq, d))
+    lse = np.zeros((B, Hq))
+    scores, sels = [], []
+    if qI_bits is None and not dense:
+        qI_bits = np.stack([np.stack([index_project(WQ[j], q_pre_bits[b, h])
+                                      for j, h in enumerate(ret_heads)]) for b in range(B)])
+    for b in range(B):
+        t0, n = int(seq_start[b]), int(ctx_len[b])
+        m = n - 1
+        for h in range(Hq):
+            kvh = kv_head_of(h, Hq, n_kv_heads)
+            Kb, Vb = K_bits[kvh, t0:t0 + n], V_bits[kvh, t0:t0 + n]
+            if dense:
+                ids = np.arange(n)
+            elif h in ret_heads:
+                j = ret_heads.index(h)
+                s = index_score(qI_bits[b, j], kI_bits[j, t0:t0 + n], isc)
+                sel = topp_select(s, float(p_rows[b * n_ret + j]))
+                scores.append(s)
+                sels.append(sel)
+                ids = sel["idx"]
+            else:
+                ids = local_set(m, sink, window)
+            out[b, h], lse[b, h] = attend(q_bits[b, h], Kb, Vb, ids, sc)
+    return dict(out=out, lse=lse, scores=scores, sel=sels, qI_bits=qI_bits)
+
+
+def prefill_rows(*, rows, q_bits, K_bits, V_bits, kI_bits, chunk_start,
+                 n_q_heads, n_kv_heads, ret_heads, sink, window, p,
+                 qI_bits=None, WQ=None, q_pre_bits=None,
+                 softmax_scale=0.0, index_scale=0.0):
+    """Selected (t, h) rows of one causal prefill chunk of ONE sequence.
+
+    q_bits [T, Hq, d] holds the chunk's queries, query t sits at position
+    m = chunk_start + t; K_bits, V_bits [Hkv, >= m + 1, d]; kI_bits [n_ret, >=, r];
+    qI_bits [n_ret, T, r] or (WQ, q_pre_bits [T, Hq, d]).
+    Retrieval heads: causal candidates n <= m, Top-P, attention over the set.
+    Local heads: sink + window.  Returns a list of dicts, one per row.
+    """
+    T, Hq, d = q_bits.shape
+    ret_heads = list(ret_heads)
+    sc = _scale(softmax_scale, d)
+    isc = 1.0 if not index_scale else float(index_scale)
+    res = []
+    for (t, h) in rows:
+        m = int(chunk_start) + int(t)
+        kvh = kv_head_of(h, Hq, n_kv_heads)
+        Kb, Vb = K_bits[kvh, :m + 1], V_bits[kvh, :m + 1]
+        r = dict(t=t, h=h, m=m)
+        if h in ret_heads:
+            j = ret_heads.index(h)
+            qi = qI_bits[j, t] if qI_bits is not None else index_project(WQ[j], q_pre_bits[t, h])
+            s = index_score(qi, kI_bits[j, :m + 1], isc)
+            sel = topp_select(s, p)
+            ids = sel["idx"]
+            r.update(scores=s, sel=sel, qI_bits=qi)
+        else:
+            ids = local_set(m, sink, window)
+        r["out"], r["lse"] = attend(q_bits[t, h], Kb, Vb, ids, sc)
+        res.append(r)
+    return res
+
+
+def dense_rows(*, rows, q_bits, K_bits, V_bits, chunk_start, n_q_heads, n_kv_heads,
+               softmax_scale=0.0):
+    """Dense causal attention for selected (t, h) rows of a prefill chunk."""
+    T, Hq, d = q_bits.shape
+    sc = _scale(softmax_scale, d)
+    res = []
+    for (t, h) in rows:
+        m = int(chunk_start) + int(t)
+        kvh = kv_head_of(h, Hq, n_kv_heads)
+        o, l = attend(q_bits[t, h], K_bits[kvh, :m + 1], V_bits[kvh, :m + 1], np.arange(m + 1), sc)
+        res.append(dict(t=t, h=h, m=m, out=o, lse=l))
+    return res

@@ -1,0 +1,410 @@
+"""Pins for the CPU oracle: every check here compares the oracle with something
+that is NOT the oracle -- exact rational arithmetic, pure-Python brute force,
+closed forms, hand-worked cases, or invariants of the definition -- so that a
+dropped term, a wrong sign or index, or a transposed operand fails a test.
+
+Citations are to the paper's Section 3.2 (indexer equation, sparse-attention
+equation, Top-P active set), Section 3.4 (mass "reaches p") and Section 4.2
+(sink + window rule for local heads).
+"""
+import math
+import os
+from fractions import Fraction
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import rtp_oracle as orc
+
+GOLD = os.path.join(os.path.dirname(__file__), "golden")
+
+
+# ---------------------------------------------------------------- helpers (independent of the oracle)
+def f32_to_bf16_bits_by_torch(x_f32: np.ndarray) -> np.ndarray:
+    t = torch.from_numpy(np.asarray(x_f32, dtype=np.float32)).to(torch.bfloat16)
+    return t.view(torch.int16).numpy().view(np.uint16)
+
+
+def bf16_fraction(bits: int) -> Fraction:
+    """Exact rational value of one bf16 bit pattern (normal numbers and zero)."""
+    sign = -1 if bits & 0x8000 else 1
+    e = (bits >> 7) & 0xFF
+    man = bits & 0x7F
+    if e == 0:
+        return Fraction(sign * man, 1 << 133)          # subnormal: man * 2^-7 * 2^-126
+    return sign * Fraction(128 + man, 128) * (Fraction(2) ** (e - 127))
+
+
+def rand_bf16(rng, shape, std=1.0):
+    return f32_to_bf16_bits_by_torch(rng.standard_normal(shape).astype(np.float32) * std)
+
+
+def brute_attention(q, K, V, ids, scale):
+    """Textbook two-pass softmax attention in pure Python floats."""
+    logits = [scale * sum(q[c] * K[n][c] for c in range(len(q))) for n in ids]
+    mx = max(logits)
+    ex = [math.exp(l - mx) for l in logits]
+    den = sum(ex)
+    out = [sum(ex[i] * V[n][c] for i, n in enumerate(ids)) / den for c in range(len(q))]
+    return out, mx + math.log(den)
+
+
+def online_attention(q, K, V, ids, scale):
+    """The same quantity a second way: one pass with a running max (online softmax)."""
+    m, l, acc = -math.inf, 0.0, [0.0] * len(q)
+    for n in ids:
+        s = scale * sum(q[c] * K[n][c] for c in range(len(q)))
+        m_new = max(m, s)
+        corr = math.exp(m - m_new) if m != -math.inf else 0.0
+        pw = math.exp(s - m_new)
+        l = l * corr + pw
+        acc = [a * corr + pw * V[n][c] for c, a in enumerate(acc)]
+        m = m_new
+    return [a / l for a in acc], m + math.log(l)
+
+
+# ---------------------------------------------------------------- number formats
+def test_bf16_widening_known_patterns():
+    bits = np.array([0x3F80, 0xBF80, 0x4000, 0x3F00, 0x0000, 0x4049, 0x3F81], dtype=np.uint16)
+    want = [1.0, -1.0, 2.0, 0.5, 0.0, 3.140625, 1.0078125]
+    assert orc.bf16_to_f64(bits).tolist() == want
+
+
+def test_bf16_widening_matches_exact_rationals():
+    rng = np.random.default_rng(0)
+    bits = rand_bf16(rng, (200,), 3.0)
+    got = orc.bf16_to_f64(bits)
+    for b, g in zip(bits.tolist(), got.tolist()):
+        assert Fraction(g) == bf16_fraction(b)
+
+
+def test_bf16_rounding_ties_to_even_and_single_rounding():
+    x = np.array([1.0,
+                  1.0 + 2.0 ** -8,               # tie between 0x3F80 and 0x3F81 -> even
+                  1.0 + 3 * 2.0 ** -8,           # tie between 0x3F81 and 0x3F82 -> even
+                  1.0 + 2.0 ** -8 + 2.0 ** -40,  # just above the tie: must round UP (a detour
+                                                 # through float32 would drop 2^-40 and tie down)
+                  -(1.0 + 2.0 ** -8 + 2.0 ** -40),
+                  0.0, 255.5, 1e-3])
+    got = orc.f64_to_bf16_bits(x)
+    assert got[0] == 0x3F80 and got[1] == 0x3F80 and got[2] == 0x3F82
+    assert got[3] == 0x3F81 and got[4] == 0xBF81 and got[5] == 0
+    assert got[6] == 0x4380            # 255.5 -> 256 (tie to even mantissa, carries into the exponent)
+    # float32-representable inputs: one rounding == torch's RNE conversion
+    rng = np.random.default_rng(1)
+    y = (rng.standard_normal(5000) * np.exp(rng.uniform(-6, 6, 5000))).astype(np.float32)
+    assert np.array_equal(orc.f64_to_bf16_bits(y.astype(np.float64)), f32_to_bf16_bits_by_torch(y))
+
+
+# ---------------------------------------------------------------- indexer (Sec. 3.2, indexer equation)
+def test_index_score_exact_against_rationals():
+    rng = np.random.default_rng(2)
+    q = rand_bf16(rng, (16,))
+    k = rand_bf16(rng, (37, 16))
+    got = orc.index_score(q, k, 1.0)
+    for n in range(37):
+        exact = sum(bf16_fraction(int(q[i])) * bf16_fraction(int(k[n, i])) for i in range(16))
+        assert abs(Fraction(float(got[n])) - exact) <= abs(exact) * Fraction(1, 10 ** 14) + Fraction(1, 10 ** 18)
+
+
+def test_index_score_unit_query_returns_key_column_and_scale():
+    rng = np.random.default_rng(3)
+    k = rand_bf16(rng, (50, 16))
+    for i in (0, 7, 15):
+        e = np.zeros(16, dtype=np.uint16)
+        e[i] = 0x3F80
+        assert np.array_equal(orc.index_score(e, k, 1.0), orc.bf16_to_f64(k[:, i]))
+        assert np.array_equal(orc.index_score(e, k, 0.5), 0.5 * orc.bf16_to_f64(k[:, i]))
+
+
+def test_index_project_exact_against_rationals():
+    rng = np.random.default_rng(4)
+    W = (rng.standard_normal((16, 128)) / math.sqrt(128)).astype(np.float32)
+    x = rand_bf16(rng, (3, 128))
+    got = orc.index_project(W, x)
+    assert got.shape == (3, 16) and got.dtype == np.uint16
+    for b in range(3):
+        for i in range(16):
+            exact = sum(Fraction(float(W[i, c])) * bf16_fraction(int(x[b, c])) for c in range(128))
+            g = bf16_fraction(int(got[b, i]))
+            ulp = Fraction(2) ** (math.floor(math.log2(abs(float(exact)))) - 7)
+            assert abs(g - exact) <= ulp / 2          # correctly rounded to 8 significant bits
+
+
+def test_index_project_is_not_transposed():
+    W = np.zeros((16, 128), dtype=np.float32)
+    W[3, 100] = 2.0
+    x = np.zeros((128,), dtype=np.uint16)
+    x[100] = 0x3FC0                                    # 1.5
+    got = orc.bf16_to_f64(orc.index_project(W, x))
+    want = np.zeros(16)
+    want[3] = 3.0
+    assert np.array_equal(got, want)
+
+
+# ---------------------------------------------------------------- top-p (Sec. 3.2 Top-P, Sec. 3.4)
+def _read_hand_cases():
+    cases = []
+    with open(os.path.join(GOLD, "topp_hand_cases.txt")) as f:
+        for line in f:
+            line = line.strip()
+            if not line or line.startswith("#"):
+                continue
+            w, p, ids = [x.strip() for x in line.split(";")]
+            cases.append(([float(v) for v in w.split()], float(p), [int(v) for v in ids.split()]))
+    return cases
+
+
+@pytest.mark.parametrize("w,p,want", _read_hand_cases())
+def test_topp_hand_worked_cases(w, p, want):
+    sel, _, _, Z = orc.topp_from_weights(np.array(w), p)
+    assert sel.tolist() == want
+    assert Z == sum(w)
+    # the same cases through the score interface: s = log2-exact weights are powers of two
+    if all(v > 0 and math.log2(v).is_integer() for v in w):
+        s = np.array([math.log(v) for v in w])
+        r = orc.topp_select(s, p)
+        assert sorted(r["idx"].tolist()) == sorted(want)
+
+
+def brute_topp(scores, p):
+    """O(N^2)-free but independent reference: python sort + python accumulation."""
+    n = len(scores)
+    mx = max(scores)
+    w = [math.exp(s - mx) for s in scores]
+    Z = math.fsum(w)
+    order = sorted(range(n), key=lambda i: (-scores[i], i))
+    if p >= 1.0:
+        return order
+    acc, out = 0.0, []
+    for i in order:
+        out.append(i)
+        acc += w[i]
+        if acc >= p * Z:
+            break
+    return out
+
+
+@pytest.mark.parametrize("seed", range(6))
+def test_topp_matches_python_brute_force(seed):
+    rng = np.random.default_rng(100 + seed)
+    n = int(rng.integers(5, 400))
+    s = rng.standard_normal(n) * rng.uniform(0.2, 4.0)
+    p = float(rng.uniform(0.3, 0.99))
+    got = orc.topp_select(s, p)
+    want = brute_topp(s.tolist(), p)
+    # python's sequential accumulation and numpy's cumsum agree to rounding; allow the
+    # one-token difference only if the boundary is within rounding of p*Z
+    if got["idx"].tolist() != want:
+        assert abs(len(want) - got["count"]) == 1
+        assert abs(got["mass"] - p) < 1e-12
+    else:
+        assert got["count"] == len(want)
+
+
+def test_topp_closed_form_all_equal():
+    for n, p in [(8, 0.875), (8, 0.5), (64, 0.75), (1000, 0.9), (1000, 0.901), (7, 1.0), (1, 0.3)]:
+        r = orc.topp_select(np.full(n, 1.2345), p)
+        # n*p is computed exactly enough for these pairs (0.9*1000 = 900.0000000000001 > 900 though:
+        # the definition is cum_k >= p*Z with cum_k = k exactly, so k = ceil(p*n) in floating point)
+        assert r["count"] == math.ceil(p * n)
+        assert r["idx"].tolist() == list(range(r["count"]))          # ties: lowest index first
+
+
+def test_topp_closed_form_one_spike():
+    # one token with gap g over N-1 equal others: alone iff 1/(1+(N-1)e^-g) >= p
+    for n, g, p in [(1000, 12.0, 0.9), (1000, 5.0, 0.9), (50, 3.0, 0.25), (50, 3.0, 0.3)]:
+        s = np.zeros(n)
+        s[n // 3] = g
+        r = orc.topp_select(s, p)
+        alone = 1.0 / (1.0 + (n - 1) * math.exp(-g)) >= p
+        assert (r["count"] == 1) == alone
+        assert r["idx"][0] == n // 3
+        if not alone:
+            share0 = 1.0 / (1.0 + (n - 1) * math.exp(-g))
+            each = math.exp(-g) / (1.0 + (n - 1) * math.exp(-g))
+            k = 1 + math.ceil((p - share0) / each - 1e-9)
+            assert abs(r["count"] - k) <= 1 and r["mass"] >= p
+
+
+def test_topp_closed_form_geometric():
+    # s_n = -n ln 2  ->  weights 2^-n (exact); mass of the first k = (1-2^-k)/(1-2^-N)
+    n = 40
+    s = -np.arange(n) * math.log(2.0)
+    for p in (0.5, 0.75, 0.9, 0.99, 0.999999):
+        r = orc.topp_select(s, p)
+        k = next(k for k in range(1, n + 1) if (1 - 2.0 ** -k) / (1 - 2.0 ** -n) >= p)
+        assert r["count"] == k and r["idx"].tolist() == list(range(k))
+
+
+@pytest.mark.parametrize("seed", range(8))
+def test_topp_invariants(seed):
+    rng = np.random.default_rng(seed)
+    n = int(rng.integers(50, 3000))
+    s = rng.standard_normal(n) * rng.uniform(0.3, 3.0)
+    s[rng.integers(0, n, 5)] += rng.uniform(3, 9)
+    p1, p2 = sorted(rng.uniform(0.2, 0.995, 2).tolist())
+    a, b = orc.topp_select(s, p1), orc.topp_select(s, p2)
+    w = np.exp(s - s.max())
+    Z = w.sum()
+    for r, p in ((a, p1), (b, p2)):
+        ids = r["idx"]
+        assert w[ids].sum() / Z >= p - 1e-15                       # mass reaches p ...
+        assert w[ids[:-1]].sum() / Z < p                            # ... and not without the last (smallest) token
+        assert s[ids].min() == r["tau"] == s[ids[-1]]
+        rest = np.setdiff1d(np.arange(n), ids)
+        assert rest.size == 0 or s[rest].max() <= r["tau"]          # upward closed in score
+        assert abs(r["mass"] - w[ids].sum() / Z) < 1e-12
+    assert set(a["idx"].tolist()) <= set(b["idx"].tolist())         # monotone in p
+    c = orc.topp_select(s + 3.75, p1)                               # shift invariance (3.75 keeps sums close)
+    assert abs(c["count"] - a["count"]) <= 1
+    perm = rng.permutation(n)                                       # permutation equivariance
+    d = orc.topp_select(s[perm], p1)
+    assert set(perm[d["idx"]].tolist()) == set(a["idx"].tolist())
+    assert orc.topp_select(s, 1.0)["count"] == n
+
+
+def test_topp_rejects_bad_p_and_empty():
+    with pytest.raises(ValueError):
+        orc.topp_select(np.zeros(4), 0.0)
+    with pytest.raises(ValueError):
+        orc.topp_select(np.zeros(4), float("nan"))
+    with pytest.raises(ValueError):
+        orc.topp_from_weights(np.zeros(0), 0.5)
+
+
+# ---------------------------------------------------------------- attention (Sec. 3.2) and local rule (Sec. 4.2)
+def test_local_set_cases():
+    assert orc.local_set(0, 4, 8).tolist() == [0]
+    assert orc.local_set(2, 4, 8).tolist() == [0, 1, 2]
+    assert orc.local_set(11, 4, 8).tolist() == list(range(12))            # m+1 == sink+window: dense
+    assert orc.local_set(12, 4, 8).tolist() == [0, 1, 2, 3] + list(range(5, 13))
+    s = orc.local_set(1000, 4, 512)
+    assert len(s) == 516 and s[-1] == 1000 and s[4] == 489 and 488 not in s
+    assert orc.local_set(5, 0, 3).tolist() == [3, 4, 5]
+    for m in range(0, 40):
+        ids = orc.local_set(m, 3, 7)
+        assert len(set(ids.tolist())) == len(ids) and ids.max() == m
+        assert len(ids) == min(m + 1, 3 + 7) if m + 1 <= 10 else len(ids) == 10
+
+
+def _tiny(seed, n=23, d=128):
+    rng = np.random.default_rng(seed)
+    return rand_bf16(rng, (d,)), rand_bf16(rng, (n, d)), rand_bf16(rng, (n, d)), rng
+
+
+@pytest.mark.parametrize("seed", range(3))
+def test_attend_matches_brute_force_two_ways(seed):
+    qb, Kb, Vb, rng = _tiny(seed)
+    ids = sorted(rng.choice(23, size=9, replace=False).tolist())
+    q = orc.bf16_to_f64(qb).tolist()
+    K = orc.bf16_to_f64(Kb).tolist()
+    V = orc.bf16_to_f64(Vb).tolist()
+    sc = 1.0 / math.sqrt(128)
+    o, lse = orc.attend(qb, Kb, Vb, ids, sc)
+    o1, l1 = brute_attention(q, K, V, ids, sc)
+    o2, l2 = online_attention(q, K, V, ids, sc)
+    assert np.allclose(o, o1, rtol=0, atol=1e-13) and np.allclose(o, o2, rtol=0, atol=1e-13)
+    assert abs(lse - l1) < 1e-13 and abs(lse - l2) < 1e-13
+    # order of the set does not matter; K and V are not interchangeable
+    o3, _ = orc.attend(qb, Kb, Vb, ids[::-1], sc)
+    assert np.allclose(o, o3, rtol=0, atol=1e-13)
+    o4, _ = orc.attend(qb, Vb, Kb, ids, sc)
+    assert not np.allclose(o, o4, atol=1e-3)
+
+
+def test_attend_single_token_and_convex_hull():
+    qb, Kb, Vb, rng = _tiny(7)
+    o, _ = orc.attend(qb, Kb, Vb, [5], 0.3)
+    assert np.array_equal(o, orc.bf16_to_f64(Vb[5]))
+    ids = [1, 4, 9, 20]
+    o, _ = orc.attend(qb, Kb, Vb, ids, 0.3)
+    v = orc.bf16_to_f64(Vb[ids])
+    assert np.all(o <= v.max(0) + 1e-15) and np.all(o >= v.min(0) - 1e-15)
+
+
+def _tiny_layer(seed, ctx=(40, 17), Hq=4, Hkv=2, d=128, r=16):
+    rng = np.random.default_rng(seed)
+    T = sum(ctx)
+    return dict(q_bits=rand_bf16(rng, (len(ctx), Hq, d)), K_bits=rand_bf16(rng, (Hkv, T, d)),
+                V_bits=rand_bf16(rng, (Hkv, T, d)), kI_bits=rand_bf16(rng, (2, T, r)),
+                qI_bits=rand_bf16(rng, (len(ctx), 2, r)),
+                seq_start=[0, ctx[0]], ctx_len=list(ctx), n_q_heads=Hq, n_kv_heads=Hkv)
+
+
+def test_decode_layer_p1_and_wide_window_reproduce_dense():
+    """p = 1 and sink + window >= N must collapse every head to dense attention,
+    which is checked against the pure-Python brute force (not against the oracle)."""
+    L = _tiny_layer(5)
+    r = orc.decode_layer(**L, ret_heads=[1, 2], sink=4, window=64, p_rows=np.ones(4))
+    dn = orc.decode_layer(**L, ret_heads=[1, 2], sink=4, window=64, p_rows=np.ones(4), dense=True)
+    assert np.array_equal(r["out"][:, [0, 3]], dn["out"][:, [0, 3]])          # local == dense, same op order
+    assert np.allclose(r["out"], dn["out"], rtol=0, atol=1e-14)               # retrieval: same set, other order
+    sc = 1.0 / math.sqrt(128)
+    for b in range(2):
+        t0, n = L["seq_start"][b], L["ctx_len"][b]
+        for h in range(4):
+            kvh = h // 2
+            K = orc.bf16_to_f64(L["K_bits"][kvh, t0:t0 + n]).tolist()
+            V = orc.bf16_to_f64(L["V_bits"][kvh, t0:t0 + n]).tolist()
+            q = orc.bf16_to_f64(L["q_bits"][b, h]).tolist()
+            o, lse = brute_attention(q, K, V, list(range(n)), sc)
+            assert np.allclose(r["out"][b, h], o, rtol=0, atol=1e-13)
+            assert abs(r["lse"][b, h] - lse) < 1e-13
+
+
+def test_decode_layer_routes_heads_and_sequences():
+    """Small p and a narrow window: each head must use ITS set, KV head and sequence."""
+    L = _tiny_layer(6)
+    r = orc.decode_layer(**L, ret_heads=[1, 2], sink=2, window=5, p_rows=np.array([0.5, 0.6, 0.7, 0.8]))
+    sc = 1.0 / math.sqrt(128)
+    row = 0
+    for b in range(2):
+        t0, n = L["seq_start"][b], L["ctx_len"][b]
+        for h in range(4):
+            kvh = h // 2
+            K = orc.bf16_to_f64(L["K_bits"][kvh, t0:t0 + n]).tolist()
+            V = orc.bf16_to_f64(L["V_bits"][kvh, t0:t0 + n]).tolist()
+            q = orc.bf16_to_f64(L["q_bits"][b, h]).tolist()
+            if h in (1, 2):
+                j = (1, 2).index(h)
+                qi = orc.bf16_to_f64(L["qI_bits"][b, j]).tolist()
+                ki = orc.bf16_to_f64(L["kI_bits"][j, t0:t0 + n]).tolist()
+                s = [sum(a * c for a, c in zip(qi, kn)) for kn in ki]
+                ids = brute_topp(s, [0.5, 0.6, 0.7, 0.8][b * 2 + j])
+                assert sorted(ids) == sorted(r["sel"][row]["idx"].tolist())
+                row += 1
+            else:
+                ids = [i for i in range(n) if i < 2 or i >= max(2, n - 5)]
+            o, _ = brute_attention(q, K, V, ids, sc)
+            assert np.allclose(r["out"][b, h], o, rtol=0, atol=1e-13)
+
+
+def test_prefill_rows_causal_and_dense_limit():
+    rng = np.random.default_rng(9)
+    T, Hq, Hkv, d, N0 = 6, 4, 2, 128, 30
+    q = rand_bf16(rng, (T, Hq, d))
+    K, V = rand_bf16(rng, (Hkv, N0 + T, d)), rand_bf16(rng, (Hkv, N0 + T, d))
+    kI, qI = rand_bf16(rng, (1, N0 + T, 16)), rand_bf16(rng, (1, T, 16))
+    rows = [(t, h) for t in range(T) for h in range(Hq)]
+    common = dict(rows=rows, q_bits=q, K_bits=K, V_bits=V, chunk_start=N0, n_q_heads=Hq, n_kv_heads=Hkv)
+    full = orc.prefill_rows(**common, kI_bits=kI, qI_bits=qI, ret_heads=[2], sink=4, window=64, p=1.0)
+    dn = orc.dense_rows(**common)
+    sc = 1.0 / math.sqrt(d)
+    for a, b in zip(full, dn):
+        assert np.allclose(a["out"], b["out"], rtol=0, atol=1e-14)
+        m = N0 + a["t"]
+        kvh = a["h"] // 2
+        o, _ = brute_attention(orc.bf16_to_f64(q[a["t"], a["h"]]).tolist(),
+                               orc.bf16_to_f64(K[kvh, :m + 1]).tolist(),
+                               orc.bf16_to_f64(V[kvh, :m + 1]).tolist(), list(range(m + 1)), sc)
+        assert np.allclose(a["out"], o, rtol=0, atol=1e-13)          # causal: never sees n > m
+    sp = orc.prefill_rows(**common, kI_bits=kI, qI_bits=qI, ret_heads=[2], sink=1, window=3, p=0.5)
+    for a in sp:
+        m = N0 + a["t"]
+        if a["h"] == 2:
+            assert a["sel"]["idx"].max() <= m and a["sel"]["mass"] >= 0.5
+            s = [sum(x * y for x, y in zip(orc.bf16_to_f64(qI[0, a["t"]]).tolist(), kn))
+                 for kn in orc.bf16_to_f64(kI[0, :m + 1]).tolist()]
+            assert sorted(brute_topp(s, 0.5)) == sorted(a["sel"]["idx"].tolist())
