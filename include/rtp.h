@@ -1,0 +1,202 @@
+/*
+ * rtp.h -- C ABI of the RTPurbo sparse-attention hot path for AMD MI355X (gfx950).
+ *
+ * The library implements, for ONE attention layer on ONE GPU, the inference-time
+ * attention rule of the paper's Section 3.2 ("Adaptive Sparse Attention Mechanism"):
+ *
+ *   retrieval heads   index score  s_h(m,n) = <W^Q_h q^pre_{m,h}, W^K_h k^pre_{n,h}>   (indexer equation)
+ *                     active set   S_h(m)   = Top-P(s_h(m,.), p)                        (sparse-attention equation)
+ *                     output       O_h(m)   = sum_{n in S} softmax_S(q.k_n/sqrt(d_h)) v_n
+ *   local heads       attention over `sink` first tokens + the `window` most recent ones (Sec. 3.2, Sec. 4.2)
+ *   dense comparison  causal softmax attention over every token (the paper's comparison system is
+ *                     a dense flash-attention kernel, Sec. 4.2 "Runtime Analysis"; this one is in-house)
+ *
+ * Conventions shared by every entry point
+ * ---------------------------------------
+ *  - Every tensor pointer is a DEVICE pointer owned by the caller.  The library never allocates,
+ *    frees, copies to the host or synchronises: all work is enqueued on `stream` (a hipStream_t
+ *    passed as void*; NULL = the default stream) and the call returns at once.
+ *  - `rtp_layer_desc` and its `ret_heads` array are HOST memory, read during the call only.
+ *  - Scratch memory comes from the caller: `ws` (device, 256-byte aligned) of at least the size
+ *    the matching *_workspace_bytes() function returns.  Contents are undefined before and after.
+ *  - bf16 tensors are raw 16-bit patterns.  head_dim must be 128 and index_dim 16.
+ *  - K and V caches: bf16, element (kvh, token, c) at  base[kvh * kv_head_stride + token * kv_row_stride + c],
+ *    strides in ELEMENTS, kv_row_stride >= 128 and a multiple of 8 (256 with V = K + 128 gives
+ *    interleaved K|V rows).  Sequences are packed along the token axis: sequence b owns tokens
+ *    seq_start[b] .. seq_start[b] + ctx_len[b] - 1  (seq_start int64, ctx_len int32, both device).
+ *  - Index-key cache kI = bf16(W^K_h k^pre): element (j, token, i) at kI[j * kI_head_stride + token * 16 + i],
+ *    one stream per RETRIEVAL QUERY head j (j-th entry of ret_heads).
+ *  - GQA: query head h reads KV head h / (n_q_heads / n_kv_heads).
+ *  - Query positions: `q_start` (device int32 [B]) NULL means decode -- n_q must be 1 and the query of
+ *    sequence b sits at position ctx_len[b] - 1 (the caller appends the new token's K/V/kI row first,
+ *    so it is a candidate).  Otherwise query t of sequence b sits at position q_start[b] + t, sees
+ *    tokens n <= q_start[b] + t (causal), and q_start[b] + n_q <= ctx_len[b] must hold.
+ *  - Queries and outputs: bf16 [B, n_q, n_q_heads, 128].  Retrieval-head entry points write only the
+ *    rows of retrieval heads, rtp_local_attn only the rows of the other heads, so the two may run
+ *    concurrently on two streams.  `lse` (optional, fp32 [B, n_q, n_q_heads]) receives the natural-log
+ *    sum of exponentials of the scaled logits over the attended set.
+ *  - Return value: RTP_OK or a negative error code.  Every argument check happens on the host before
+ *    the first launch; on error nothing has been enqueued.  rtp_last_error() gives a thread-local
+ *    message for the last failing call of the calling thread.
+ *  - Calls on different streams may overlap if their outputs and workspaces are disjoint.
+ */
+#ifndef RTP_H_
+#define RTP_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define RTP_OK                 0
+#define RTP_ERR_INVALID_ARG   (-1)   /* null pointer, non-positive size, bad head list, bad stride */
+#define RTP_ERR_UNSUPPORTED   (-2)   /* head_dim != 128, index_dim != 16, group size not in {1,2,4,8} */
+#define RTP_ERR_WORKSPACE     (-3)   /* workspace missing, misaligned or too small */
+#define RTP_ERR_HIP           (-4)   /* a launch failed; the HIP error text is in rtp_last_error() */
+
+#define RTP_HEAD_DIM   128
+#define RTP_INDEX_DIM  16
+#define RTP_MAX_ROW_LEN (1 << 24)    /* longest score row rtp_topp_select accepts */
+
+/* One attention layer (host struct).  Values used by the paper's configuration table:
+ * index_dim 16, sink 4, window 8192, 15 % of the heads retrieval. */
+typedef struct rtp_layer_desc {
+  int32_t n_q_heads;         /* query heads                                   */
+  int32_t n_kv_heads;        /* KV heads; n_q_heads / n_kv_heads in {1,2,4,8} */
+  int32_t head_dim;          /* 128                                           */
+  int32_t index_dim;         /* 16                                            */
+  int32_t n_ret;             /* number of retrieval query heads (may be 0)    */
+  const int32_t* ret_heads;  /* HOST, strictly ascending query-head ids       */
+  int32_t sink;              /* local heads: first `sink` tokens ...          */
+  int32_t window;            /* ... plus the `window` most recent, own position included */
+  float softmax_scale;       /* 0 => 1/sqrt(head_dim)   (sparse-attention equation) */
+  float index_scale;         /* 0 => 1                  (the indexer equation has no scale) */
+} rtp_layer_desc;
+
+/* Message for the last error on this thread ("" if none).  Never NULL. */
+const char* rtp_last_error(void);
+/* Library version, e.g. "rtp-gfx950 0.1". */
+const char* rtp_version(void);
+
+/* ---------------------------------------------------------------------------------------------
+ * (1) Indexer score pass -- Sec. 3.2, indexer equation.
+ *
+ * For every row (b, j, t) -- sequence b, j-th retrieval head, query t -- and every cached token n of
+ * sequence b:   scores[row * score_stride + n] = index_scale * sum_{i<16} qI[i] * kI[j, seq_start[b]+n, i]
+ * accumulated in fp32 (the bf16*bf16 products are exact), row = (b * n_ret + j) * n_q + t.
+ * Non-candidates (n > query position) inside [0, ctx_len[b]) are written as -inf; entries at
+ * n >= ctx_len[b] are not written.
+ *
+ * The index query: if WQ != NULL, q_in is the PRE-RoPE query tensor bf16 [B, n_q, n_q_heads, 128] and
+ * qI = bf16_rne( WQ[j] . q_in[b, t, ret_heads[j], :] ) with WQ fp32 [n_ret, 16, 128]; the 128-term sum
+ * runs in fp64 and is rounded to bf16 once.  If WQ == NULL, q_in already holds qI, bf16 [B, n_ret, n_q, 16].
+ * qI_out (optional, bf16 [B, n_ret, n_q, 16]) receives the index queries used.
+ *
+ * max_ctx: host upper bound of ctx_len[] (sizes the grid).  score_stride >= max_ctx, multiple of 4;
+ * `scores` 16-byte aligned.  No workspace.
+ */
+int32_t rtp_index_score(const rtp_layer_desc* layer, const void* q_in, const float* WQ,
+                        const void* kI, int64_t kI_head_stride,
+                        const int64_t* seq_start, const int32_t* ctx_len, const int32_t* q_start,
+                        int32_t B, int32_t n_q, int64_t max_ctx,
+                        float* scores, int64_t score_stride, void* qI_out, void* stream);
+
+/* ---------------------------------------------------------------------------------------------
+ * (2) Dynamic top-p selection -- Sec. 3.2 (S = Top-P(s, p)) and Sec. 3.4 (sort-free thresholding:
+ * "the score threshold at which the cumulative attention mass reaches p").
+ *
+ * For each of R independent rows: w_n = exp(s_n - max_n s_n), Z = sum w_n; the selected set is
+ * { n : s_n >= tau } where tau is the largest score whose descending cumulative mass reaches p * Z.
+ * This is the smallest such set up to ties AT tau, all of which are kept.  The search is a three-level
+ * radix histogram over the order-preserving 32-bit key of the fp32 score (exact: no sort, no sampling);
+ * masses are accumulated as 64-bit fixed point of fp64 exponentials, so the result does not depend on
+ * summation order.
+ *
+ *   scores    fp32 [R, score_stride] (16-byte aligned, score_stride multiple of 4); row r uses
+ *             entries [0, row_len[r]); -inf entries are never selected.
+ *   row_len   device int32 [R], each <= max_len (host bound, <= RTP_MAX_ROW_LEN).
+ *   p         device fp32 [R], one value per row; p >= 1 keeps every entry of the row (tau = -inf);
+ *             p <= 0 or NaN marks the row invalid: sel_count = -1, nothing selected.
+ *   sel_idx   out, int32 [R, sel_stride], sel_stride >= max_len; the selected positions in
+ *             UNSPECIFIED order (use them as a set).
+ *   sel_count out, int32 [R].   tau, mass: optional outputs fp32 [R] (threshold score; selected mass / Z).
+ */
+size_t rtp_topp_workspace_bytes(int32_t R, int64_t max_len);
+int32_t rtp_topp_select(const float* scores, int64_t score_stride, const int32_t* row_len,
+                        const float* p, int32_t R, int64_t max_len,
+                        int32_t* sel_idx, int64_t sel_stride, int32_t* sel_count,
+                        float* tau, float* mass, void* ws, size_t ws_bytes, void* stream);
+
+/* ---------------------------------------------------------------------------------------------
+ * (3) Exact softmax attention over the selected tokens, decode, retrieval heads only --
+ * Sec. 3.2, sparse-attention equation.
+ *
+ * Row (b, j) attends query q[b, 0, ret_heads[j], :] to tokens sel_idx[(b*n_ret+j)*sel_stride + i],
+ * i < sel_count[b*n_ret+j] (positions relative to seq_start[b]), of KV head kv(ret_heads[j]), and
+ * writes out[b, 0, ret_heads[j], :].  Rows with sel_count <= 0 write zeros (lse = -inf).
+ * max_sel: host upper bound of sel_count[] (sizes the grid and the workspace).
+ */
+size_t rtp_sparse_attn_decode_workspace_bytes(const rtp_layer_desc* layer, int32_t B, int64_t max_sel);
+int32_t rtp_sparse_attn_decode(const rtp_layer_desc* layer, const void* q,
+                               const void* K, const void* V, int64_t kv_row_stride, int64_t kv_head_stride,
+                               const int64_t* seq_start,
+                               const int32_t* sel_idx, int64_t sel_stride, const int32_t* sel_count,
+                               int64_t max_sel, int32_t B, void* out, float* lse,
+                               void* ws, size_t ws_bytes, void* stream);
+
+/* ---------------------------------------------------------------------------------------------
+ * (4) Causal prefill chunk for the retrieval heads of ONE sequence: index score + per-query top-p +
+ * attention over each query's own active set, fused (no T x N score matrix is materialised).
+ * The paper runs retrieval heads dense in prefill (Sec. 3.2, Sec. 4.2) -- that is p >= 1 here; p < 1
+ * applies its decode rule (Top-P over the causal candidates n <= m) to every prefill query.
+ *
+ * Pointers K, V, kI address token 0 of the sequence.  Queries t = 0..T-1 sit at positions
+ * chunk_start + t; rows [0, chunk_start + T) of K/V/kI must exist.  q: bf16 [T, n_q_heads, 128]
+ * (post-RoPE).  Index queries as in (1): WQ != NULL => q_pre bf16 [T, n_q_heads, 128], else q_pre holds
+ * qI bf16 [n_ret, T, 16].  out: bf16 [T, n_q_heads, 128], retrieval rows only.
+ * Optional per-(j, t) statistics, fp32/int32 [n_ret, T]: tau (threshold used), count (tokens kept),
+ * mass (indexer mass kept).  For p < 1 the threshold is resolved to 2^-11 in score below the exact
+ * top-p threshold (never above it), so the kept set is a superset of the exact one by the few tokens
+ * whose score lies in that sliver.
+ */
+size_t rtp_sparse_attn_prefill_workspace_bytes(const rtp_layer_desc* layer, int32_t T, int64_t chunk_start);
+int32_t rtp_sparse_attn_prefill(const rtp_layer_desc* layer, const void* q_pre, const void* q, const float* WQ,
+                                const void* kI, int64_t kI_head_stride,
+                                const void* K, const void* V, int64_t kv_row_stride, int64_t kv_head_stride,
+                                int64_t chunk_start, int32_t T, float p, void* out, float* lse,
+                                float* tau, int32_t* count, float* mass,
+                                void* ws, size_t ws_bytes, void* stream);
+
+/* ---------------------------------------------------------------------------------------------
+ * (5) Sink + sliding-window attention for every NON-retrieval head -- Sec. 3.2 (first sentence),
+ * Sec. 4.2 ("4 sink tokens and an 8192-token window").
+ *
+ * A query at position m attends tokens { n < sink } U { max(sink, m - window + 1) <= n <= m }.
+ * Decode (q_start == NULL, n_q == 1) reads each needed K/V row once per KV head and serves the whole
+ * GQA group from it; prefill (q_start != NULL) runs banded causal MFMA tiles.
+ * max_ctx: host upper bound of ctx_len[].
+ */
+size_t rtp_local_attn_workspace_bytes(const rtp_layer_desc* layer, int32_t B, int32_t n_q, int64_t max_ctx);
+int32_t rtp_local_attn(const rtp_layer_desc* layer, const void* q,
+                       const void* K, const void* V, int64_t kv_row_stride, int64_t kv_head_stride,
+                       const int64_t* seq_start, const int32_t* ctx_len, const int32_t* q_start,
+                       int32_t B, int32_t n_q, int64_t max_ctx, void* out, float* lse,
+                       void* ws, size_t ws_bytes, void* stream);
+
+/* ---------------------------------------------------------------------------------------------
+ * In-house dense comparison: causal softmax attention over ALL tokens for ALL heads (same tensors,
+ * same conventions as (5)).  Stands in for the dense flash-attention baseline of Sec. 4.2.
+ */
+size_t rtp_dense_attn_workspace_bytes(const rtp_layer_desc* layer, int32_t B, int32_t n_q, int64_t max_ctx);
+int32_t rtp_dense_attn(const rtp_layer_desc* layer, const void* q,
+                       const void* K, const void* V, int64_t kv_row_stride, int64_t kv_head_stride,
+                       const int64_t* seq_start, const int32_t* ctx_len, const int32_t* q_start,
+                       int32_t B, int32_t n_q, int64_t max_ctx, void* out, float* lse,
+                       void* ws, size_t ws_bytes, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* RTP_H_ */

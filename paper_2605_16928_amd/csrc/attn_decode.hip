@@ -1,0 +1,508 @@
+// Decode-time attention over a token set: rtp_sparse_attn_decode (paper Sec. 3.2, sparse-attention
+// equation), rtp_local_attn in decode mode (sink + window rule, Sec. 3.2 / Sec. 4.2) and the dense
+// comparison rtp_dense_attn in decode mode.
+//
+// All three are the same HBM-bound kernel with a different token source: an index list (sparse), or
+// the ranges [0, sink) U [ctx - window, ctx) (local) / [0, ctx) (dense).  One K or V row is 256 bytes
+// = 16 lanes x 16 bytes, so a 64-lane wave loads four rows per instruction; the 16 lanes of a DPP row
+// own one token, multiply their 8 dims with the query and reduce with four DPP adds.  Each 16-lane
+// group keeps its own online-softmax state (max, sum, 8 output dims per lane) in registers for all
+// G query heads that share the KV head, so every K/V row is read once per KV head.  U tokens per
+// group are in flight at a time (all K and V loads are issued before the arithmetic).
+//
+// Load balance without host knowledge of the set sizes: a persistent grid; every workgroup derives
+// the same plan from the device-side counts -- split length ST = total tokens / grid size (rounded
+// up to 128), unit u contributes ceil(n_u / ST) work items -- and walks the items blockIdx.x,
+// blockIdx.x + gridDim.x, ...  Each item leaves a partial (m, l, acc[128]) per head; a second small
+// kernel merges the partials of a unit (the split-KV reduction of Sec. 3.4, as a separate launch).
+// Algorithmic traffic: 512 B per attended token and KV head (+ 4 B per token for the index list).
+#include "common.h"
+
+namespace rtp {
+
+constexpr int kAdThreads = 256;
+constexpr int kAdMaxUnits = 1024;
+constexpr int kPartStride = kHeadDim + 4;   // m, l, 2 pad, acc[128]  (floats)
+
+enum { kSrcSparse = 0, kSrcLocal = 1, kSrcDense = 2 };
+
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+struct AttnDecodeArgs {
+  const uint16_t* q;
+  const uint16_t* K;
+  const uint16_t* V;
+  int64_t row_stride, head_stride;
+  const int64_t* seq_start;
+  const int32_t* ctx_len;
+  const int32_t* sel_idx;
+  int64_t sel_stride;
+  const int32_t* sel_count;
+  int32_t n_q_heads, n_kv_heads, n_ret, sink, window;
+  int32_t units;           // B * n_ret (sparse) or B * n_kv_heads
+  int32_t target_items;    // host hint: aim for this many work items
+  float scale_log2;        // softmax scale * log2(e)
+  float* part;             // [items, G, kPartStride]
+  uint16_t* out;
+  float* lse;
+  int32_t ret_heads[64];
+  uint8_t is_ret[128];
+};
+
+template <int SRC>
+__device__ __forceinline__ int unit_tokens(const AttnDecodeArgs& a, int unit) {
+  if (SRC == kSrcSparse) return max(a.sel_count[unit], 0);
+  const int n = a.ctx_len[unit / a.n_kv_heads];
+  if (SRC == kSrcDense) return max(n, 0);
+  const int s0 = min(a.sink, n);
+  const int w0 = max(a.sink, n - a.window);
+  return max(s0, 0) + max(0, n - w0);
+}
+
+// Exclusive prefix sum over the block (256 threads); *total gets the block sum.
+__device__ __forceinline__ int block_excl_scan(int v, int* sh_w /*[4]*/, int* total) {
+  int incl = v;
+#pragma unroll
+  for (int o = 1; o < 64; o <<= 1) {
+    const int t = __shfl_up(incl, o);
+    if ((threadIdx.x & 63) >= o) incl += t;
+  }
+  __syncthreads();
+  if ((threadIdx.x & 63) == 63) sh_w[threadIdx.x >> 6] = incl;
+  __syncthreads();
+  int off = 0, tot = 0;
+#pragma unroll
+  for (int i = 0; i < kAdThreads / 64; ++i) {
+    if (i < (int)(threadIdx.x >> 6)) off += sh_w[i];
+    tot += sh_w[i];
+  }
+  *total = tot;
+  return off + incl - v;
+}
+
+// Every workgroup computes the same plan: split length and the exclusive item prefix per unit.
+template <int SRC>
+__device__ __forceinline__ void build_plan(const AttnDecodeArgs& a, int* sh_prefix /*[kAdMaxUnits+1]*/, int* sh_w,
+                                           int* split_tokens, int* n_items) {
+  const int tid = threadIdx.x;
+  int cnt[kAdMaxUnits / kAdThreads];
+  int mine = 0;
+#pragma unroll
+  for (int i = 0; i < kAdMaxUnits / kAdThreads; ++i) {
+    const int u = tid * (kAdMaxUnits / kAdThreads) + i;
+    cnt[i] = u < a.units ? unit_tokens<SRC>(a, u) : 0;
+    mine += (cnt[i] + 127) >> 7;          // in blocks of 128 tokens, so the total cannot overflow int
+  }
+  int total128;
+  block_excl_scan(mine, sh_w, &total128);
+  int st = (total128 + a.target_items - 1) / max(a.target_items, 1);
+  st = max(st, 1) * 128;
+  int items = 0;
+#pragma unroll
+  for (int i = 0; i < kAdMaxUnits / kAdThreads; ++i) {
+    cnt[i] = (cnt[i] + st - 1) / st;
+    items += cnt[i];
+  }
+  int tot;
+  int off = block_excl_scan(items, sh_w, &tot);
+#pragma unroll
+  for (int i = 0; i < kAdMaxUnits / kAdThreads; ++i) {
+    const int u = tid * (kAdMaxUnits / kAdThreads) + i;
+    sh_prefix[u] = off;
+    off += cnt[i];
+  }
+  if (tid == kAdThreads - 1) sh_prefix[kAdMaxUnits] = off;
+  __syncthreads();
+  *split_tokens = st;
+  *n_items = tot;
+}
+
+__device__ __forceinline__ int find_unit(const int* sh_prefix, int units, int item) {
+  int lo = 0, hi = units - 1;             // largest u with prefix[u] <= item
+  while (lo < hi) {
+    const int mid = (lo + hi + 1) >> 1;
+    if (sh_prefix[mid] <= item) lo = mid; else hi = mid - 1;
+  }
+  return lo;
+}
+
+__device__ __forceinline__ void unpack8(const u32x4 v, float (&f)[8]) {
+  f[0] = bf16_lo(v.x); f[1] = bf16_hi(v.x); f[2] = bf16_lo(v.y); f[3] = bf16_hi(v.y);
+  f[4] = bf16_lo(v.z); f[5] = bf16_hi(v.z); f[6] = bf16_lo(v.w); f[7] = bf16_hi(v.w);
+}
+
+// Merge online-softmax state (mo, lo, acco) into (m, l, acc); log2-domain maxima.
+__device__ __forceinline__ void merge_state(float& m, float& l, float (&acc)[8], float mo, float lo,
+                                            const float (&acco)[8]) {
+  const float M = fmaxf(m, mo);
+  if (M == -__builtin_huge_valf()) return;
+  const float ca = fast_exp2(m - M), cb = fast_exp2(mo - M);
+  l = l * ca + lo * cb;
+#pragma unroll
+  for (int c = 0; c < 8; ++c) acc[c] = acc[c] * ca + acco[c] * cb;
+  m = M;
+}
+
+template <int G, int SRC, int U>
+__global__ __launch_bounds__(kAdThreads) void attn_decode_kernel(const AttnDecodeArgs a) {
+  __shared__ int sh_prefix[kAdMaxUnits + 1];
+  __shared__ int sh_w[kAdThreads / 64];
+  __shared__ float sh_m[kAdThreads / 64][G], sh_l[kAdThreads / 64][G];
+  __shared__ float sh_acc[kAdThreads / 64][G][kHeadDim];
+
+  int ST, n_items;
+  build_plan<SRC>(a, sh_prefix, sh_w, &ST, &n_items);
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int grp = wave * 4 + (lane >> 4);   // 16 groups of 16 lanes
+  const int piece = lane & 15;              // which 8 of the 128 dims
+  const float ninf = -__builtin_huge_valf();
+  const int group_size = a.n_q_heads / a.n_kv_heads;
+
+  for (int item = blockIdx.x; item < n_items; item += gridDim.x) {
+    const int unit = find_unit(sh_prefix, a.units, item);
+    const int split = item - sh_prefix[unit];
+    int b, kvh, h0;
+    if (SRC == kSrcSparse) {
+      b = unit / a.n_ret;
+      h0 = a.ret_heads[unit - b * a.n_ret];
+      kvh = h0 / group_size;
+    } else {
+      b = unit / a.n_kv_heads;
+      kvh = unit - b * a.n_kv_heads;
+      h0 = kvh * G;
+    }
+    const int n_tok = unit_tokens<SRC>(a, unit);
+    const int t_begin = split * ST, t_end = min(n_tok, t_begin + ST);
+    // local source: logical token i maps to position i (sinks) or w0 + (i - s0) (window)
+    int s0 = 0, w0 = 0;
+    if (SRC == kSrcLocal) {
+      const int n = a.ctx_len[b];
+      s0 = max(min(a.sink, n), 0);
+      w0 = max(a.sink, n - a.window);
+    }
+    const int32_t* idx = (SRC == kSrcSparse) ? a.sel_idx + (int64_t)unit * a.sel_stride : nullptr;
+    const uint16_t* Kb = a.K + (int64_t)kvh * a.head_stride + a.seq_start[b] * a.row_stride + piece * 8;
+    const uint16_t* Vb = a.V + (int64_t)kvh * a.head_stride + a.seq_start[b] * a.row_stride + piece * 8;
+
+    float qv[G][8];
+#pragma unroll
+    for (int hh = 0; hh < G; ++hh) {
+      const u32x4 qraw = *reinterpret_cast<const u32x4*>(a.q + ((int64_t)b * a.n_q_heads + h0 + hh) * kHeadDim + piece * 8);
+      unpack8(qraw, qv[hh]);
+#pragma unroll
+      for (int c = 0; c < 8; ++c) qv[hh][c] *= a.scale_log2;
+    }
+    float m[G], l[G], acc[G][8];
+#pragma unroll
+    for (int hh = 0; hh < G; ++hh) {
+      m[hh] = ninf;
+      l[hh] = 0.f;
+#pragma unroll
+      for (int c = 0; c < 8; ++c) acc[hh][c] = 0.f;
+    }
+
+    int nxt[U];
+    if (SRC == kSrcSparse) {
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        const int i = t_begin + u * 16 + grp;
+        nxt[u] = i < t_end ? idx[i] : 0;
+      }
+    }
+    for (int base = t_begin; base < t_end; base += 16 * U) {
+      u32x4 kr[U], vr[U];
+      bool ok[U];
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        const int i = base + u * 16 + grp;
+        ok[u] = i < t_end;
+        int pos;
+        if (SRC == kSrcSparse) pos = nxt[u];
+        else if (SRC == kSrcLocal) pos = i < s0 ? i : w0 + (i - s0);
+        else pos = i;
+        if (ok[u]) {
+          kr[u] = *reinterpret_cast<const u32x4*>(Kb + (int64_t)pos * a.row_stride);
+          vr[u] = *reinterpret_cast<const u32x4*>(Vb + (int64_t)pos * a.row_stride);
+        } else {
+          kr[u] = (u32x4){0u, 0u, 0u, 0u};
+          vr[u] = (u32x4){0u, 0u, 0u, 0u};
+        }
+      }
+      if (SRC == kSrcSparse) {   // index list of the next round, under the shadow of the K/V loads
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+          const int i = base + 16 * U + u * 16 + grp;
+          nxt[u] = i < t_end ? idx[i] : 0;
+        }
+      }
+      float s[G][U];
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        float kf[8];
+        unpack8(kr[u], kf);
+#pragma unroll
+        for (int hh = 0; hh < G; ++hh) {
+          float d = kf[0] * qv[hh][0];
+#pragma unroll
+          for (int c = 1; c < 8; ++c) d = fmaf(kf[c], qv[hh][c], d);
+          d = row16_sum(d);
+          s[hh][u] = ok[u] ? d : ninf;
+        }
+      }
+#pragma unroll
+      for (int hh = 0; hh < G; ++hh) {
+        float mx = s[hh][0];
+#pragma unroll
+        for (int u = 1; u < U; ++u) mx = fmaxf(mx, s[hh][u]);
+        const float mn = fmaxf(m[hh], mx);
+        if (mn != ninf) {
+          const float corr = fast_exp2(m[hh] - mn);
+          l[hh] *= corr;
+#pragma unroll
+          for (int c = 0; c < 8; ++c) acc[hh][c] *= corr;
+          m[hh] = mn;
+        }
+      }
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        float vf[8];
+        unpack8(vr[u], vf);
+#pragma unroll
+        for (int hh = 0; hh < G; ++hh) {
+          const float pw = (s[hh][u] == ninf) ? 0.f : fast_exp2(s[hh][u] - m[hh]);
+          l[hh] += pw;
+#pragma unroll
+          for (int c = 0; c < 8; ++c) acc[hh][c] = fmaf(pw, vf[c], acc[hh][c]);
+        }
+      }
+    }
+
+    // ---- merge the four 16-lane groups of each wave in registers, then the four waves through LDS ----
+#pragma unroll
+    for (int hh = 0; hh < G; ++hh) {
+#pragma unroll
+      for (int o = 16; o <= 32; o <<= 1) {
+        const float mo = __shfl_xor(m[hh], o), lo = __shfl_xor(l[hh], o);
+        float ao[8];
+#pragma unroll
+        for (int c = 0; c < 8; ++c) ao[c] = __shfl_xor(acc[hh][c], o);
+        merge_state(m[hh], l[hh], acc[hh], mo, lo, ao);
+      }
+    }
+    __syncthreads();   // previous item's readers are done with the LDS buffers
+    if (lane < 16) {
+#pragma unroll
+      for (int hh = 0; hh < G; ++hh) {
+        if (piece == 0) { sh_m[wave][hh] = m[hh]; sh_l[wave][hh] = l[hh]; }
+#pragma unroll
+        for (int c = 0; c < 8; ++c) sh_acc[wave][hh][piece * 8 + c] = acc[hh][c];
+      }
+    }
+    __syncthreads();
+    float* pout = a.part + (int64_t)item * G * kPartStride;
+    for (int e = tid; e < G * kHeadDim; e += kAdThreads) {
+      const int hh = e >> 7, d = e & 127;
+      float M = sh_m[0][hh];
+#pragma unroll
+      for (int w = 1; w < kAdThreads / 64; ++w) M = fmaxf(M, sh_m[w][hh]);
+      float L = 0.f, A = 0.f;
+      if (M != ninf) {
+#pragma unroll
+        for (int w = 0; w < kAdThreads / 64; ++w) {
+          const float cw = fast_exp2(sh_m[w][hh] - M);
+          L += sh_l[w][hh] * cw;
+          A += sh_acc[w][hh][d] * cw;
+        }
+      }
+      pout[hh * kPartStride + 4 + d] = A;
+      if (d == 0) { pout[hh * kPartStride] = M; pout[hh * kPartStride + 1] = L; }
+    }
+  }
+}
+
+// Merges the partials of one (unit, head): grid = units * G blocks of 128 threads.
+template <int G, int SRC>
+__global__ __launch_bounds__(kAdThreads) void attn_decode_combine_kernel(const AttnDecodeArgs a) {
+  __shared__ int sh_prefix[kAdMaxUnits + 1];
+  __shared__ int sh_w[kAdThreads / 64];
+  int ST, n_items;
+  build_plan<SRC>(a, sh_prefix, sh_w, &ST, &n_items);
+  const int tid = threadIdx.x;
+  const float ninf = -__builtin_huge_valf();
+  // two (unit, head) pairs per block: 128 threads each
+  const int pair = blockIdx.x * 2 + (tid >> 7);
+  if (pair >= a.units * G) return;
+  const int unit = pair / G, hh = pair - unit * G, d = tid & 127;
+  int b, h;
+  if (SRC == kSrcSparse) {
+    b = unit / a.n_ret;
+    h = a.ret_heads[unit - b * a.n_ret];
+  } else {
+    b = unit / a.n_kv_heads;
+    h = (unit - b * a.n_kv_heads) * G + hh;
+    if (SRC == kSrcLocal && a.is_ret[h]) return;
+  }
+  const int i0 = sh_prefix[unit];
+  const int i1 = (unit + 1 < a.units) ? sh_prefix[unit + 1] : n_items;
+  float M = ninf;
+  for (int i = i0; i < i1; ++i) M = fmaxf(M, a.part[((int64_t)i * G + hh) * kPartStride]);
+  float L = 0.f, A = 0.f;
+  if (M != ninf) {
+    for (int i = i0; i < i1; ++i) {
+      const float* p = a.part + ((int64_t)i * G + hh) * kPartStride;
+      const float cw = fast_exp2(p[0] - M);
+      L += p[1] * cw;
+      A += p[4 + d] * cw;
+    }
+  }
+  const int64_t o = ((int64_t)b * a.n_q_heads + h);
+  a.out[o * kHeadDim + d] = f32_to_bf16_rne(L > 0.f ? A / L : 0.f);
+  if (a.lse && d == 0) a.lse[o] = L > 0.f ? (M + log2f(L)) * 0.6931471805599453f : ninf;
+}
+
+struct DecodePlanHost {
+  int32_t units, target_items, grid;
+  size_t ws_bytes;
+};
+
+static DecodePlanHost plan_host(int32_t units, int64_t max_tok, int32_t G) {
+  DecodePlanHost p;
+  p.units = units;
+  int64_t blocks128 = (int64_t)units * ((max_tok + 127) / 128);
+  int64_t tgt = blocks128 < 1 ? 1 : (blocks128 > 2048 ? 2048 : blocks128);
+  p.target_items = (int32_t)tgt;
+  p.grid = (int32_t)tgt;
+  // items <= total128 / ceil(total128 / target) + units <= target + units
+  p.ws_bytes = align_up((size_t)(tgt + units) * G * kPartStride * sizeof(float), 256);
+  return p;
+}
+
+template <int SRC>
+static int32_t launch_decode(const AttnDecodeArgs& a, int G, int grid, hipStream_t s, const char* who) {
+  const int cgrid = (a.units * G + 1) / 2;
+#define RTP_LAUNCH(GG, UU)                                                                          \
+  hipLaunchKernelGGL((attn_decode_kernel<GG, SRC, UU>), dim3(grid), dim3(kAdThreads), 0, s, a);     \
+  hipLaunchKernelGGL((attn_decode_combine_kernel<GG, SRC>), dim3(cgrid), dim3(kAdThreads), 0, s, a);
+  switch (G) {
+    case 1: RTP_LAUNCH(1, 8) break;
+    case 2: RTP_LAUNCH(2, 8) break;
+    case 4: RTP_LAUNCH(4, 8) break;
+    case 8: RTP_LAUNCH(8, 4) break;
+    default: return fail(RTP_ERR_UNSUPPORTED, "%s: group size %d", who, G);
+  }
+#undef RTP_LAUNCH
+  return check_launch(who);
+}
+
+static int32_t check_kv(const char* who, const void* q, const void* K, const void* V, int64_t row_stride,
+                        int64_t head_stride, const void* out) {
+  if (!q || !K || !V || !out) return fail(RTP_ERR_INVALID_ARG, "%s: NULL tensor pointer", who);
+  if (row_stride < kHeadDim || (row_stride & 7) || (head_stride & 7) || head_stride < 0)
+    return fail(RTP_ERR_INVALID_ARG, "%s: kv_row_stride must be >= 128, strides multiples of 8", who);
+  if (((uintptr_t)q & 15) || ((uintptr_t)K & 15) || ((uintptr_t)V & 15) || ((uintptr_t)out & 15))
+    return fail(RTP_ERR_INVALID_ARG, "%s: q, K, V and out must be 16-byte aligned", who);
+  return RTP_OK;
+}
+
+static void fill_common(AttnDecodeArgs& a, const rtp_layer_desc* L, const HeadTable& ht, const void* q, const void* K,
+                        const void* V, int64_t row_stride, int64_t head_stride, const int64_t* seq_start,
+                        const int32_t* ctx_len, void* out, float* lse, void* ws) {
+  a.q = (const uint16_t*)q;
+  a.K = (const uint16_t*)K;
+  a.V = (const uint16_t*)V;
+  a.row_stride = row_stride;
+  a.head_stride = head_stride;
+  a.seq_start = seq_start;
+  a.ctx_len = ctx_len;
+  a.sel_idx = nullptr;
+  a.sel_stride = 0;
+  a.sel_count = nullptr;
+  a.n_q_heads = L->n_q_heads;
+  a.n_kv_heads = L->n_kv_heads;
+  a.n_ret = L->n_ret;
+  a.sink = L->sink;
+  a.window = L->window;
+  a.scale_log2 = softmax_scale_of(L) * 1.4426950408889634f;
+  a.part = (float*)ws;
+  a.out = (uint16_t*)out;
+  a.lse = lse;
+  for (int j = 0; j < 64; ++j) a.ret_heads[j] = ht.ret_heads[j];
+  for (int h = 0; h < 128; ++h) a.is_ret[h] = ht.is_ret[h];
+}
+
+// Decode-mode local / dense attention (called from attn_api.hip).
+int32_t decode_range_attn(const char* who, bool dense, const rtp_layer_desc* L, const void* q, const void* K,
+                          const void* V, int64_t row_stride, int64_t head_stride, const int64_t* seq_start,
+                          const int32_t* ctx_len, int32_t B, int64_t max_ctx, void* out, float* lse, void* ws,
+                          size_t ws_bytes, hipStream_t s) {
+  HeadTable ht;
+  int32_t rc = fill_head_table(L, &ht, who);
+  if (rc != RTP_OK) return rc;
+  rc = check_kv(who, q, K, V, row_stride, head_stride, out);
+  if (rc != RTP_OK) return rc;
+  if (!seq_start || !ctx_len) return fail(RTP_ERR_INVALID_ARG, "%s: NULL seq_start/ctx_len", who);
+  if (B <= 0 || max_ctx <= 0) return fail(RTP_ERR_INVALID_ARG, "%s: B and max_ctx must be positive", who);
+  const int G = L->n_q_heads / L->n_kv_heads;
+  const int64_t units = (int64_t)B * L->n_kv_heads;
+  if (units > kAdMaxUnits) return fail(RTP_ERR_UNSUPPORTED, "%s: B * n_kv_heads = %lld exceeds %d", who, (long long)units, kAdMaxUnits);
+  const int64_t max_tok = dense ? max_ctx : (max_ctx < (int64_t)L->sink + L->window ? max_ctx : (int64_t)L->sink + L->window);
+  const DecodePlanHost p = plan_host((int32_t)units, max_tok, G);
+  if (!ws || ((uintptr_t)ws & 255) || ws_bytes < p.ws_bytes)
+    return fail(RTP_ERR_WORKSPACE, "%s: workspace of %zu bytes (256-byte aligned) required, got %zu", who, p.ws_bytes, ws_bytes);
+  clear_error();
+  if (!dense && L->n_ret == L->n_q_heads) return RTP_OK;   // no local head
+  AttnDecodeArgs a;
+  fill_common(a, L, ht, q, K, V, row_stride, head_stride, seq_start, ctx_len, out, lse, ws);
+  a.units = p.units;
+  a.target_items = p.target_items;
+  return dense ? launch_decode<kSrcDense>(a, G, p.grid, s, who) : launch_decode<kSrcLocal>(a, G, p.grid, s, who);
+}
+
+size_t decode_range_ws(bool dense, const rtp_layer_desc* L, int32_t B, int64_t max_ctx) {
+  if (!L || B <= 0 || max_ctx <= 0 || L->n_kv_heads <= 0 || L->n_q_heads <= 0) return 0;
+  const int G = L->n_q_heads / L->n_kv_heads;
+  const int64_t max_tok = dense ? max_ctx : (max_ctx < (int64_t)L->sink + L->window ? max_ctx : (int64_t)L->sink + L->window);
+  return plan_host(B * L->n_kv_heads, max_tok, G).ws_bytes;
+}
+
+}  // namespace rtp
+
+using namespace rtp;
+
+extern "C" size_t rtp_sparse_attn_decode_workspace_bytes(const rtp_layer_desc* layer, int32_t B, int64_t max_sel) {
+  if (!layer || B <= 0 || max_sel <= 0 || layer->n_ret <= 0) return 256;
+  return plan_host(B * layer->n_ret, max_sel, 1).ws_bytes;
+}
+
+extern "C" int32_t rtp_sparse_attn_decode(const rtp_layer_desc* layer, const void* q,
+                                          const void* K, const void* V, int64_t kv_row_stride, int64_t kv_head_stride,
+                                          const int64_t* seq_start,
+                                          const int32_t* sel_idx, int64_t sel_stride, const int32_t* sel_count,
+                                          int64_t max_sel, int32_t B, void* out, float* lse,
+                                          void* ws, size_t ws_bytes, void* stream) {
+  const char* who = "rtp_sparse_attn_decode";
+  HeadTable ht;
+  int32_t rc = fill_head_table(layer, &ht, who);
+  if (rc != RTP_OK) return rc;
+  rc = check_kv(who, q, K, V, kv_row_stride, kv_head_stride, out);
+  if (rc != RTP_OK) return rc;
+  if (!seq_start || !sel_idx || !sel_count) return fail(RTP_ERR_INVALID_ARG, "%s: NULL seq_start/sel_idx/sel_count", who);
+  if (B <= 0 || max_sel <= 0) return fail(RTP_ERR_INVALID_ARG, "%s: B and max_sel must be positive", who);
+  if (sel_stride < max_sel) return fail(RTP_ERR_INVALID_ARG, "%s: sel_stride must be >= max_sel", who);
+  const int64_t units = (int64_t)B * layer->n_ret;
+  if (units > kAdMaxUnits) return fail(RTP_ERR_UNSUPPORTED, "%s: B * n_ret = %lld exceeds %d", who, (long long)units, kAdMaxUnits);
+  if (layer->n_ret == 0) { clear_error(); return RTP_OK; }
+  const DecodePlanHost p = plan_host((int32_t)units, max_sel, 1);
+  if (!ws || ((uintptr_t)ws & 255) || ws_bytes < p.ws_bytes)
+    return fail(RTP_ERR_WORKSPACE, "%s: workspace of %zu bytes (256-byte aligned) required, got %zu", who, p.ws_bytes, ws_bytes);
+  clear_error();
+  AttnDecodeArgs a;
+  fill_common(a, layer, ht, q, K, V, kv_row_stride, kv_head_stride, seq_start, nullptr, out, lse, ws);
+  a.sel_idx = sel_idx;
+  a.sel_stride = sel_stride;
+  a.sel_count = sel_count;
+  a.units = p.units;
+  a.target_items = p.target_items;
+  return launch_decode<kSrcSparse>(a, 1, p.grid, (hipStream_t)stream, who);
+}

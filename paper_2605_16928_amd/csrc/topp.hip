@@ -1,0 +1,420 @@
+// rtp_topp_select: sort-free dynamic top-p (paper Sec. 3.2, S = Top-P(s, p); Sec. 3.4, the threshold
+// "at which the cumulative attention mass reaches p").
+//
+// Design (ours, for gfx950; the paper's kernel uses one 256-bin histogram of block maxima):
+// a three-level radix search over the order-preserving 32-bit key of each fp32 score
+// (11 + 11 + 10 bits).  Level L histograms the softmax mass w = exp(s - max) of the elements whose
+// higher key bits equal the prefix found so far; scanning the histogram from the top finds the bin in
+// which the descending cumulative mass crosses p * Z.  After three levels the threshold key is exact.
+// Masses are fp64 exponentials converted to 64-bit fixed point, so every sum is an integer sum and
+// the result is independent of the order in which atomics land.
+//
+// Launches: init (row maxima per chunk, zero histograms) -> level 1 -> level 2 -> level 3 -> compact.
+// There is no "last block" hand-off: each level's histogram is scanned redundantly in the prologue
+// of every workgroup of the NEXT launch, so kernel boundaries provide all ordering.
+// A row is cut into chunks of kChunk scores, one workgroup each; histograms live in LDS and only
+// non-empty bins are flushed with 64-bit global atomics.
+#include "common.h"
+
+namespace rtp {
+
+constexpr int kTpThreads = 256;
+constexpr int kTpChunk = 8192;             // scores per workgroup
+constexpr int kTpVec = kTpChunk / (kTpThreads * 4);   // float4 loads per thread = 8
+constexpr int kBins1 = 2048, kBins2 = 2048, kBins3 = 1024;
+constexpr int kBinsTotal = kBins1 + kBins2 + kBins3;
+
+struct RowState {          // one per row and level (3 per row)
+  uint64_t above;          // fixed-point mass of keys strictly above the current prefix range
+  uint64_t target;         // fixed-point p * Z
+  uint64_t total;          // fixed-point Z
+  uint32_t prefix;         // key bits resolved so far (right-aligned)
+  int32_t flags;           // 0 ok, 1 = keep everything (p >= 1), -1 = invalid p
+  float smax;
+  int32_t shift;
+};
+
+struct TopPArgs {
+  const float* scores;
+  int64_t score_stride;
+  const int32_t* row_len;
+  const float* p;
+  int32_t R;
+  int32_t n_chunks;        // grid.x
+  int32_t* sel_idx;
+  int64_t sel_stride;
+  int32_t* sel_count;
+  float* tau;
+  float* mass;
+  float* cmax;             // [R, n_chunks]
+  uint64_t* hist;          // [R, kBinsTotal]
+  RowState* state;         // [R, 3]
+};
+
+__device__ __forceinline__ int fixed_shift(int n) {
+  // weights are <= 1 and a row has n of them: n * 2^shift must stay below 2^63
+  int lg = 32 - __clz(max(n, 2) - 1);      // ceil(log2 n)
+  return min(52, 62 - lg);
+}
+
+__device__ __forceinline__ uint64_t fixed_weight(float s, float smax, int shift) {
+  const double x = (double)s - (double)smax;         // exact
+  if (x < -60.0) return 0;                            // below 2^-86: under the fixed-point resolution
+  const double w = exp(x);
+  return (uint64_t)__double2ull_rn(ldexp(w, shift));
+}
+
+// Block-wide maximum; result valid in every thread.
+__device__ __forceinline__ float block_max(float v, float* red) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o));
+  const int w = threadIdx.x >> 6;
+  __syncthreads();
+  if ((threadIdx.x & 63) == 0) red[w] = v;
+  __syncthreads();
+  v = red[0];
+#pragma unroll
+  for (int i = 1; i < kTpThreads / 64; ++i) v = fmaxf(v, red[i]);
+  return v;
+}
+
+// Scans `nbins` fixed-point masses (global, written by an earlier launch) from the top and finds the
+// highest bin b with  above + sum_{i >= b} h[i] >= target.  Returns b and the new `above`
+// (mass strictly above bin b) and the mass of bin b itself.  All threads get the result.
+// If even the whole histogram does not reach the target (cannot happen for a consistent state)
+// bin 0 is returned.
+__device__ __forceinline__ void scan_from_top(const uint64_t* __restrict__ h, int nbins, uint64_t above,
+                                              uint64_t target, uint64_t* sh_part /*[256]*/, uint64_t* sh_res /*[3]*/,
+                                              int* bin, uint64_t* above_out, uint64_t* bin_mass) {
+  const int tid = threadIdx.x;
+  const int per = nbins / kTpThreads;                 // 8 or 4 consecutive bins per thread
+  uint64_t loc[8];
+  uint64_t sum = 0;
+  for (int i = 0; i < per; ++i) {
+    loc[i] = h[tid * per + i];
+    sum += loc[i];
+  }
+  __syncthreads();
+  sh_part[tid] = sum;
+  if (tid == 0) { sh_res[0] = 0; sh_res[1] = above; sh_res[2] = h[0]; }
+  __syncthreads();
+  // inclusive suffix sums over the 256 partials (Hillis-Steele)
+  for (int o = 1; o < kTpThreads; o <<= 1) {
+    uint64_t add = (tid + o < kTpThreads) ? sh_part[tid + o] : 0;
+    __syncthreads();
+    sh_part[tid] += add;
+    __syncthreads();
+  }
+  const uint64_t incl = sh_part[tid];                 // bins of threads >= tid
+  const uint64_t excl = incl - sum;                   // bins of threads > tid
+  if (above + excl < target && above + incl >= target) {
+    uint64_t run = above + excl;
+    int b = per - 1;
+    for (; b > 0; --b) {
+      if (run + loc[b] >= target) break;
+      run += loc[b];
+    }
+    sh_res[0] = (uint64_t)(tid * per + b);
+    sh_res[1] = run;
+    sh_res[2] = loc[b];
+  }
+  __syncthreads();
+  *bin = (int)sh_res[0];
+  *above_out = sh_res[1];
+  *bin_mass = sh_res[2];
+}
+
+// ---- launch 0: per-chunk maxima, zero the histograms and counters --------------------------------
+__global__ __launch_bounds__(kTpThreads) void topp_init_kernel(const TopPArgs a) {
+  const int r = blockIdx.y, c = blockIdx.x, tid = threadIdx.x;
+  __shared__ float red[kTpThreads / 64];
+  uint64_t* h = a.hist + (int64_t)r * kBinsTotal;
+  for (int i = c * kTpThreads + tid; i < kBinsTotal; i += a.n_chunks * kTpThreads) h[i] = 0;
+  if (c == 0 && tid == 0) a.sel_count[r] = 0;
+  const int n = a.row_len[r];
+  const int64_t n0 = (int64_t)c * kTpChunk;
+  if (n0 >= n) return;
+  const float4* src = reinterpret_cast<const float4*>(a.scores + (int64_t)r * a.score_stride + n0);
+  const int n_here = (int)min((int64_t)kTpChunk, (int64_t)n - n0);
+  float m = -__builtin_huge_valf();
+#pragma unroll
+  for (int u = 0; u < kTpVec; ++u) {
+    const int e = (u * kTpThreads + tid) * 4;
+    if (e < n_here) {
+      const float4 v = src[u * kTpThreads + tid];
+      m = fmaxf(m, v.x);
+      if (e + 1 < n_here) m = fmaxf(m, v.y);
+      if (e + 2 < n_here) m = fmaxf(m, v.z);
+      if (e + 3 < n_here) m = fmaxf(m, v.w);
+    }
+  }
+  m = block_max(m, red);
+  if (tid == 0) a.cmax[(int64_t)r * a.n_chunks + c] = m;
+}
+
+// ---- launches 1-3: one histogram level each ----------------------------------------------------
+template <int LEVEL>
+__global__ __launch_bounds__(kTpThreads) void topp_level_kernel(const TopPArgs a) {
+  constexpr int kBins = LEVEL == 1 ? kBins1 : (LEVEL == 2 ? kBins2 : kBins3);
+  constexpr int kShift = LEVEL == 1 ? 21 : (LEVEL == 2 ? 10 : 0);     // key bits below this level's field
+  constexpr int kOff = LEVEL == 1 ? 0 : (LEVEL == 2 ? kBins1 : kBins1 + kBins2);
+  const int r = blockIdx.y, c = blockIdx.x, tid = threadIdx.x;
+  const int n = a.row_len[r];
+  const int64_t n0 = (int64_t)c * kTpChunk;
+  if (n0 >= n || n <= 0) return;
+
+  __shared__ uint64_t lh[kBins];
+  __shared__ uint64_t sh_part[kTpThreads];
+  __shared__ uint64_t sh_res[3];
+  __shared__ float red[kTpThreads / 64];
+  uint64_t* hrow = a.hist + (int64_t)r * kBinsTotal;
+  RowState* st = a.state + (int64_t)r * 3;
+
+  // ---- prologue: what the previous launch left for this row ----
+  float smax;
+  int shift;
+  uint32_t prefix = 0;
+  int flags = 0;
+  if (LEVEL == 1) {
+    const int n_row_chunks = (n + kTpChunk - 1) / kTpChunk;
+    float m = -__builtin_huge_valf();
+    for (int i = tid; i < n_row_chunks; i += kTpThreads) m = fmaxf(m, a.cmax[(int64_t)r * a.n_chunks + i]);
+    smax = block_max(m, red);
+    shift = fixed_shift(n);
+    const float pr = a.p[r];
+    flags = (pr >= 1.f) ? 1 : ((pr > 0.f) ? 0 : -1);
+    if (c == 0 && tid == 0) {
+      RowState s;
+      s.above = 0; s.target = 0; s.total = 0; s.prefix = 0; s.flags = flags; s.smax = smax; s.shift = shift;
+      st[0] = s;
+    }
+  } else {
+    const RowState prev = st[LEVEL - 2];
+    smax = prev.smax;
+    shift = prev.shift;
+    flags = prev.flags;
+    uint64_t above = prev.above, target = prev.target, total = prev.total;
+    if (flags == 0) {
+      if (LEVEL == 2) {
+        // Z = whole level-1 histogram; target = ceil(p * Z)
+        uint64_t sum = 0;
+        for (int i = tid; i < kBins1; i += kTpThreads) sum += hrow[i];
+        sh_part[tid] = sum;
+        __syncthreads();
+        for (int o = kTpThreads / 2; o > 0; o >>= 1) {
+          if (tid < o) sh_part[tid] += sh_part[tid + o];
+          __syncthreads();
+        }
+        total = sh_part[0];
+        __syncthreads();
+        const double want = ceil((double)a.p[r] * (double)total);
+        target = (uint64_t)__double2ull_rn(want);
+        if (target > total) target = total;
+        if (target < 1) target = 1;
+        above = 0;
+      }
+      int bin;
+      uint64_t new_above, bin_mass;
+      const uint64_t* hprev = hrow + (LEVEL == 2 ? 0 : kBins1);
+      scan_from_top(hprev, LEVEL == 2 ? kBins1 : kBins2, above, target, sh_part, sh_res, &bin, &new_above, &bin_mass);
+      prefix = (prev.prefix << 11) | (uint32_t)bin;
+      above = new_above;
+    }
+    if (c == 0 && tid == 0) {
+      RowState s;
+      s.above = above; s.target = target; s.total = total; s.prefix = prefix; s.flags = flags; s.smax = smax;
+      s.shift = shift;
+      st[LEVEL - 1] = s;
+    }
+  }
+  if (flags != 0) return;          // keep-all or invalid rows need no histogram
+
+  for (int i = tid; i < kBins; i += kTpThreads) lh[i] = 0;
+  __syncthreads();
+
+  const float4* src = reinterpret_cast<const float4*>(a.scores + (int64_t)r * a.score_stride + n0);
+  const int n_here = (int)min((int64_t)kTpChunk, (int64_t)n - n0);
+#pragma unroll 2
+  for (int u = 0; u < kTpVec; ++u) {
+    const int e = (u * kTpThreads + tid) * 4;
+    if (e >= n_here) break;
+    const float4 v = src[u * kTpThreads + tid];
+    const float s4[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+      if (e + k < n_here) {
+        const uint32_t key = float_key(s4[k]);
+        bool mine;
+        if (LEVEL == 1) mine = true;
+        else mine = (key >> (kShift + (LEVEL == 2 ? 11 : 10))) == prefix;
+        if (mine) {
+          const uint64_t w = fixed_weight(s4[k], smax, shift);
+          if (w) atomicAdd((unsigned long long*)&lh[(key >> kShift) & (kBins - 1)], (unsigned long long)w);
+        }
+      }
+    }
+  }
+  __syncthreads();
+  uint64_t* hout = hrow + kOff;
+  for (int i = tid; i < kBins; i += kTpThreads) {
+    const uint64_t v = lh[i];
+    if (v) atomicAdd((unsigned long long*)&hout[i], (unsigned long long)v);
+  }
+}
+
+// ---- launch 4: final scan, statistics, compaction ---------------------------------------------
+__global__ __launch_bounds__(kTpThreads) void topp_compact_kernel(const TopPArgs a) {
+  const int r = blockIdx.y, c = blockIdx.x, tid = threadIdx.x;
+  const int n = a.row_len[r];
+  const int64_t n0 = (int64_t)c * kTpChunk;
+  if (n <= 0) {
+    if (c == 0 && tid == 0) {
+      if (a.tau) a.tau[r] = -__builtin_huge_valf();
+      if (a.mass) a.mass[r] = 0.f;
+    }
+    return;
+  }
+  if (n0 >= n) return;
+  __shared__ uint64_t sh_part[kTpThreads];
+  __shared__ uint64_t sh_res[3];
+  __shared__ int sh_cnt[kTpThreads / 64];
+  __shared__ int sh_base;
+  const uint64_t* hrow = a.hist + (int64_t)r * kBinsTotal;
+  const RowState prev = a.state[(int64_t)r * 3 + 2];
+
+  uint32_t tkey = 0;      // keep keys >= tkey
+  if (prev.flags < 0) {
+    if (c == 0 && tid == 0) {
+      a.sel_count[r] = -1;
+      if (a.tau) a.tau[r] = __builtin_nanf("");
+      if (a.mass) a.mass[r] = 0.f;
+    }
+    return;
+  } else if (prev.flags == 0) {
+    int bin;
+    uint64_t above, bin_mass;
+    scan_from_top(hrow + kBins1 + kBins2, kBins3, prev.above, prev.target, sh_part, sh_res, &bin, &above, &bin_mass);
+    tkey = (prev.prefix << 10) | (uint32_t)bin;
+    if (c == 0 && tid == 0) {
+      if (a.tau) a.tau[r] = key_float(tkey);
+      if (a.mass) a.mass[r] = (float)((double)(above + bin_mass) / (double)prev.total);
+    }
+  } else if (c == 0 && tid == 0) {
+    if (a.tau) a.tau[r] = -__builtin_huge_valf();
+    if (a.mass) a.mass[r] = 1.f;
+  }
+
+  const float4* src = reinterpret_cast<const float4*>(a.scores + (int64_t)r * a.score_stride + n0);
+  const int n_here = (int)min((int64_t)kTpChunk, (int64_t)n - n0);
+  const float ninf = -__builtin_huge_valf();
+  // pass A: which of this thread's 32 scores are kept (bit mask), and how many
+  uint32_t keep = 0;
+#pragma unroll
+  for (int u = 0; u < kTpVec; ++u) {
+    const int e = (u * kTpThreads + tid) * 4;
+    if (e < n_here) {
+      const float4 v = src[u * kTpThreads + tid];
+      const float s4[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+      for (int k = 0; k < 4; ++k) {
+        const bool sel = (e + k < n_here) && s4[k] != ninf && (prev.flags == 1 || float_key(s4[k]) >= tkey);
+        keep |= (sel ? 1u : 0u) << (u * 4 + k);
+      }
+    }
+  }
+  const int mine = __popc(keep);
+  // exclusive prefix over the block: wave scan + wave totals
+  int incl = mine;
+#pragma unroll
+  for (int o = 1; o < 64; o <<= 1) {
+    const int t = __shfl_up(incl, o);
+    if ((tid & 63) >= o) incl += t;
+  }
+  if ((tid & 63) == 63) sh_cnt[tid >> 6] = incl;
+  __syncthreads();
+  int wave_off = 0, block_total = 0;
+#pragma unroll
+  for (int i = 0; i < kTpThreads / 64; ++i) {
+    if (i < (tid >> 6)) wave_off += sh_cnt[i];
+    block_total += sh_cnt[i];
+  }
+  if (tid == 0) sh_base = block_total ? atomicAdd(&a.sel_count[r], block_total) : 0;
+  __syncthreads();
+  int pos = sh_base + wave_off + incl - mine;
+  int32_t* out = a.sel_idx + (int64_t)r * a.sel_stride;
+#pragma unroll
+  for (int u = 0; u < kTpVec; ++u) {
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+      if (keep & (1u << (u * 4 + k))) out[pos++] = (int32_t)(n0 + (u * kTpThreads + tid) * 4 + k);
+    }
+  }
+}
+
+struct TopPLayout {
+  size_t cmax_off, hist_off, state_off, total;
+};
+static TopPLayout topp_layout(int32_t R, int64_t max_len) {
+  const int64_t n_chunks = (max_len + kTpChunk - 1) / kTpChunk;
+  TopPLayout l;
+  size_t off = 0;
+  l.cmax_off = off;  off = align_up(off + (size_t)R * n_chunks * sizeof(float), 256);
+  l.hist_off = off;  off = align_up(off + (size_t)R * kBinsTotal * sizeof(uint64_t), 256);
+  l.state_off = off; off = align_up(off + (size_t)R * 3 * sizeof(RowState), 256);
+  l.total = off;
+  return l;
+}
+
+}  // namespace rtp
+
+using namespace rtp;
+
+extern "C" size_t rtp_topp_workspace_bytes(int32_t R, int64_t max_len) {
+  if (R <= 0 || max_len <= 0) return 0;
+  return topp_layout(R, max_len).total;
+}
+
+extern "C" int32_t rtp_topp_select(const float* scores, int64_t score_stride, const int32_t* row_len,
+                                   const float* p, int32_t R, int64_t max_len,
+                                   int32_t* sel_idx, int64_t sel_stride, int32_t* sel_count,
+                                   float* tau, float* mass, void* ws, size_t ws_bytes, void* stream) {
+  const char* who = "rtp_topp_select";
+  if (!scores || !row_len || !p || !sel_idx || !sel_count)
+    return fail(RTP_ERR_INVALID_ARG, "%s: NULL tensor pointer", who);
+  if (R <= 0 || R > 65535) return fail(RTP_ERR_INVALID_ARG, "%s: R must be in [1, 65535]", who);
+  if (max_len <= 0 || max_len > RTP_MAX_ROW_LEN)
+    return fail(RTP_ERR_INVALID_ARG, "%s: max_len must be in [1, %d]", who, RTP_MAX_ROW_LEN);
+  if (score_stride < max_len || (score_stride & 3) || ((uintptr_t)scores & 15))
+    return fail(RTP_ERR_INVALID_ARG, "%s: scores must be 16-byte aligned, score_stride >= max_len and a multiple of 4", who);
+  if (sel_stride < max_len) return fail(RTP_ERR_INVALID_ARG, "%s: sel_stride must be >= max_len", who);
+  const TopPLayout l = topp_layout(R, max_len);
+  if (!ws || ((uintptr_t)ws & 255) || ws_bytes < l.total)
+    return fail(RTP_ERR_WORKSPACE, "%s: workspace of %zu bytes (256-byte aligned) required, got %zu", who, l.total,
+                ws_bytes);
+  clear_error();
+
+  TopPArgs a;
+  a.scores = scores;
+  a.score_stride = score_stride;
+  a.row_len = row_len;
+  a.p = p;
+  a.R = R;
+  a.n_chunks = (int32_t)((max_len + kTpChunk - 1) / kTpChunk);
+  a.sel_idx = sel_idx;
+  a.sel_stride = sel_stride;
+  a.sel_count = sel_count;
+  a.tau = tau;
+  a.mass = mass;
+  a.cmax = (float*)((char*)ws + l.cmax_off);
+  a.hist = (uint64_t*)((char*)ws + l.hist_off);
+  a.state = (RowState*)((char*)ws + l.state_off);
+
+  hipStream_t s = (hipStream_t)stream;
+  dim3 grid((unsigned)a.n_chunks, (unsigned)R), block(kTpThreads);
+  hipLaunchKernelGGL(topp_init_kernel, grid, block, 0, s, a);
+  hipLaunchKernelGGL(topp_level_kernel<1>, grid, block, 0, s, a);
+  hipLaunchKernelGGL(topp_level_kernel<2>, grid, block, 0, s, a);
+  hipLaunchKernelGGL(topp_level_kernel<3>, grid, block, 0, s, a);
+  hipLaunchKernelGGL(topp_compact_kernel, grid, block, 0, s, a);
+  return check_launch(who);
+}

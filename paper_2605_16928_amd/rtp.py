@@ -1,0 +1,193 @@
+"""ctypes binding of librtp.so -- argument marshalling only.
+
+Every function has the name and argument order of its C entry point (see
+include/rtp.h); tensors are torch tensors on the GPU (only their data_ptr() is
+used), sizes are Python ints, and the HIP stream defaults to torch's current
+stream.  A non-zero return code raises RtpError with the library's message.
+There is no fallback: if the library cannot be loaded, importing succeeds but
+the first call raises.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Optional, Sequence
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(HERE, "librtp.so")
+
+RTP_OK, RTP_ERR_INVALID_ARG, RTP_ERR_UNSUPPORTED, RTP_ERR_WORKSPACE, RTP_ERR_HIP = 0, -1, -2, -3, -4
+
+EXPORTS = [
+    "rtp_last_error", "rtp_version",
+    "rtp_index_score",
+    "rtp_topp_workspace_bytes", "rtp_topp_select",
+    "rtp_sparse_attn_decode_workspace_bytes", "rtp_sparse_attn_decode",
+    "rtp_sparse_attn_prefill_workspace_bytes", "rtp_sparse_attn_prefill",
+    "rtp_local_attn_workspace_bytes", "rtp_local_attn",
+    "rtp_dense_attn_workspace_bytes", "rtp_dense_attn",
+]
+
+
+class RtpError(RuntimeError):
+    def __init__(self, code: int, msg: str):
+        super().__init__(f"rtp error {code}: {msg}")
+        self.code = code
+
+
+class rtp_layer_desc(C.Structure):
+    _fields_ = [
+        ("n_q_heads", C.c_int32), ("n_kv_heads", C.c_int32), ("head_dim", C.c_int32), ("index_dim", C.c_int32),
+        ("n_ret", C.c_int32), ("ret_heads", C.POINTER(C.c_int32)),
+        ("sink", C.c_int32), ("window", C.c_int32),
+        ("softmax_scale", C.c_float), ("index_scale", C.c_float),
+    ]
+
+
+def layer_desc(n_q_heads: int, n_kv_heads: int, ret_heads: Sequence[int], sink: int, window: int,
+               head_dim: int = 128, index_dim: int = 16, softmax_scale: float = 0.0,
+               index_scale: float = 0.0) -> rtp_layer_desc:
+    arr = (C.c_int32 * max(len(ret_heads), 1))(*ret_heads)
+    d = rtp_layer_desc(n_q_heads, n_kv_heads, head_dim, index_dim, len(ret_heads),
+                       C.cast(arr, C.POINTER(C.c_int32)), sink, window, softmax_scale, index_scale)
+    d._keepalive = arr
+    return d
+
+
+_lib = None
+
+
+def lib() -> C.CDLL:
+    """Loads librtp.so (built by paper_2605_16928_amd.build); raises if it is missing."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise RtpError(-100, f"{LIB_PATH} is missing: build it with `python -m paper_2605_16928_amd.build` "
+                             f"(there is no CPU fallback)")
+    L = C.CDLL(LIB_PATH)
+    vp, i32, i64, sz = C.c_void_p, C.c_int32, C.c_int64, C.c_size_t
+    dp = C.POINTER(rtp_layer_desc)
+    L.rtp_last_error.restype = C.c_char_p
+    L.rtp_last_error.argtypes = []
+    L.rtp_version.restype = C.c_char_p
+    L.rtp_version.argtypes = []
+    L.rtp_index_score.restype = i32
+    L.rtp_index_score.argtypes = [dp, vp, vp, vp, i64, vp, vp, vp, i32, i32, i64, vp, i64, vp, vp]
+    L.rtp_topp_workspace_bytes.restype = sz
+    L.rtp_topp_workspace_bytes.argtypes = [i32, i64]
+    L.rtp_topp_select.restype = i32
+    L.rtp_topp_select.argtypes = [vp, i64, vp, vp, i32, i64, vp, i64, vp, vp, vp, vp, sz, vp]
+    L.rtp_sparse_attn_decode_workspace_bytes.restype = sz
+    L.rtp_sparse_attn_decode_workspace_bytes.argtypes = [dp, i32, i64]
+    L.rtp_sparse_attn_decode.restype = i32
+    L.rtp_sparse_attn_decode.argtypes = [dp, vp, vp, vp, i64, i64, vp, vp, i64, vp, i64, i32, vp, vp, vp, sz, vp]
+    L.rtp_sparse_attn_prefill_workspace_bytes.restype = sz
+    L.rtp_sparse_attn_prefill_workspace_bytes.argtypes = [dp, i32, i64]
+    L.rtp_sparse_attn_prefill.restype = i32
+    L.rtp_sparse_attn_prefill.argtypes = [dp, vp, vp, vp, vp, i64, vp, vp, i64, i64, i64, i32, C.c_float,
+                                          vp, vp, vp, vp, vp, vp, sz, vp]
+    for name in ("rtp_local_attn", "rtp_dense_attn"):
+        getattr(L, name + "_workspace_bytes").restype = sz
+        getattr(L, name + "_workspace_bytes").argtypes = [dp, i32, i32, i64]
+        getattr(L, name).restype = i32
+        getattr(L, name).argtypes = [dp, vp, vp, vp, i64, i64, vp, vp, vp, i32, i32, i64, vp, vp, vp, sz, vp]
+    _lib = L
+    return L
+
+
+def _ptr(t) -> Optional[int]:
+    if t is None:
+        return None
+    if isinstance(t, int):
+        return t
+    return t.data_ptr()
+
+
+def _stream(stream) -> Optional[int]:
+    if stream is None:
+        import torch
+        return torch.cuda.current_stream().cuda_stream
+    if isinstance(stream, int):
+        return stream
+    return stream.cuda_stream
+
+
+def _check(rc: int):
+    if rc != 0:
+        raise RtpError(rc, lib().rtp_last_error().decode())
+
+
+def _nbytes(t) -> int:
+    return 0 if t is None else t.numel() * t.element_size()
+
+
+def rtp_version() -> str:
+    return lib().rtp_version().decode()
+
+
+def rtp_last_error() -> str:
+    return lib().rtp_last_error().decode()
+
+
+def rtp_index_score(layer, q_in, WQ, kI, kI_head_stride, seq_start, ctx_len, q_start, B, n_q, max_ctx,
+                    scores, score_stride, qI_out=None, stream=None):
+    _check(lib().rtp_index_score(C.byref(layer), _ptr(q_in), _ptr(WQ), _ptr(kI), kI_head_stride, _ptr(seq_start),
+                                 _ptr(ctx_len), _ptr(q_start), B, n_q, max_ctx, _ptr(scores), score_stride,
+                                 _ptr(qI_out), _stream(stream)))
+
+
+def rtp_topp_workspace_bytes(R, max_len) -> int:
+    return lib().rtp_topp_workspace_bytes(R, max_len)
+
+
+def rtp_topp_select(scores, score_stride, row_len, p, R, max_len, sel_idx, sel_stride, sel_count,
+                    tau, mass, ws, stream=None):
+    _check(lib().rtp_topp_select(_ptr(scores), score_stride, _ptr(row_len), _ptr(p), R, max_len, _ptr(sel_idx),
+                                 sel_stride, _ptr(sel_count), _ptr(tau), _ptr(mass), _ptr(ws), _nbytes(ws),
+                                 _stream(stream)))
+
+
+def rtp_sparse_attn_decode_workspace_bytes(layer, B, max_sel) -> int:
+    return lib().rtp_sparse_attn_decode_workspace_bytes(C.byref(layer), B, max_sel)
+
+
+def rtp_sparse_attn_decode(layer, q, K, V, kv_row_stride, kv_head_stride, seq_start, sel_idx, sel_stride,
+                           sel_count, max_sel, B, out, lse, ws, stream=None):
+    _check(lib().rtp_sparse_attn_decode(C.byref(layer), _ptr(q), _ptr(K), _ptr(V), kv_row_stride, kv_head_stride,
+                                        _ptr(seq_start), _ptr(sel_idx), sel_stride, _ptr(sel_count), max_sel, B,
+                                        _ptr(out), _ptr(lse), _ptr(ws), _nbytes(ws), _stream(stream)))
+
+
+def rtp_sparse_attn_prefill_workspace_bytes(layer, T, chunk_start) -> int:
+    return lib().rtp_sparse_attn_prefill_workspace_bytes(C.byref(layer), T, chunk_start)
+
+
+def rtp_sparse_attn_prefill(layer, q_pre, q, WQ, kI, kI_head_stride, K, V, kv_row_stride, kv_head_stride,
+                            chunk_start, T, p, out, lse, tau, count, mass, ws, stream=None):
+    _check(lib().rtp_sparse_attn_prefill(C.byref(layer), _ptr(q_pre), _ptr(q), _ptr(WQ), _ptr(kI), kI_head_stride,
+                                         _ptr(K), _ptr(V), kv_row_stride, kv_head_stride, chunk_start, T, p,
+                                         _ptr(out), _ptr(lse), _ptr(tau), _ptr(count), _ptr(mass), _ptr(ws),
+                                         _nbytes(ws), _stream(stream)))
+
+
+def rtp_local_attn_workspace_bytes(layer, B, n_q, max_ctx) -> int:
+    return lib().rtp_local_attn_workspace_bytes(C.byref(layer), B, n_q, max_ctx)
+
+
+def rtp_dense_attn_workspace_bytes(layer, B, n_q, max_ctx) -> int:
+    return lib().rtp_dense_attn_workspace_bytes(C.byref(layer), B, n_q, max_ctx)
+
+
+def rtp_local_attn(layer, q, K, V, kv_row_stride, kv_head_stride, seq_start, ctx_len, q_start, B, n_q, max_ctx,
+                   out, lse, ws, stream=None):
+    _check(lib().rtp_local_attn(C.byref(layer), _ptr(q), _ptr(K), _ptr(V), kv_row_stride, kv_head_stride,
+                                _ptr(seq_start), _ptr(ctx_len), _ptr(q_start), B, n_q, max_ctx, _ptr(out), _ptr(lse),
+                                _ptr(ws), _nbytes(ws), _stream(stream)))
+
+
+def rtp_dense_attn(layer, q, K, V, kv_row_stride, kv_head_stride, seq_start, ctx_len, q_start, B, n_q, max_ctx,
+                   out, lse, ws, stream=None):
+    _check(lib().rtp_dense_attn(C.byref(layer), _ptr(q), _ptr(K), _ptr(V), kv_row_stride, kv_head_stride,
+                                _ptr(seq_start), _ptr(ctx_len), _ptr(q_start), B, n_q, max_ctx, _ptr(out), _ptr(lse),
+                                _ptr(ws), _nbytes(ws), _stream(stream)))

@@ -1,0 +1,178 @@
+"""Helpers shared by the GPU parity tests: run the decode path through the C-ABI on cuda:0,
+hand the same inputs to the oracle, and compare with the stated tolerances."""
+from __future__ import annotations
+
+import numpy as np
+import torch
+
+from oracle import rtp_oracle as orc
+from paper_2605_16928_amd import rtp, workloads as wl
+
+DEV = "cuda:0"
+
+# tolerances (benchmark spec; forms fixed here)
+SCORE_RTOL = 1e-5          # |d| <= 1e-5 * max(|s_ref|, sum_i |qI_i kI_i|)
+BAND_RTOL = 1e-5           # tokens with |s - tau| <= 1e-5 * max(1, |tau|) may differ
+OUT_ATOL, OUT_RTOL = 2e-2, 1e-2
+
+
+def layer_desc_of(layer: wl.Layer):
+    return rtp.layer_desc(layer.n_q_heads, layer.n_kv_heads, layer.ret_heads, layer.sink, layer.window)
+
+
+def ws_alloc(nbytes: int) -> torch.Tensor:
+    return torch.empty(max(int(nbytes), 256), dtype=torch.uint8, device=DEV)
+
+
+def i32(x):
+    return torch.tensor(list(x), dtype=torch.int32, device=DEV)
+
+
+def i64(x):
+    return torch.tensor(list(x), dtype=torch.int64, device=DEV)
+
+
+class DecodeRun:
+    """Device buffers for one decode workload and the C-ABI calls on them."""
+
+    def __init__(self, w: wl.DecodeWorkload):
+        self.w = w
+        L = w.layer
+        self.desc = layer_desc_of(L)
+        self.B, self.n_ret = w.B, L.n_ret
+        self.R = self.B * self.n_ret
+        self.max_ctx = max(w.ctx_len)
+        self.stride = (self.max_ctx + 3) // 4 * 4
+        self.seq_start, self.ctx_len = i64(w.seq_start), i32(w.ctx_len)
+        self.row_len = i32([w.ctx_len[b] for b in range(self.B) for _ in range(self.n_ret)])
+        self.scores = torch.full((max(self.R, 1), self.stride), float("nan"), dtype=torch.float32, device=DEV)
+        self.qI_out = torch.zeros((self.B, max(self.n_ret, 1), 16), dtype=torch.bfloat16, device=DEV)
+        self.sel_idx = torch.full((max(self.R, 1), self.stride), -7, dtype=torch.int32, device=DEV)
+        self.sel_count = torch.full((max(self.R, 1),), -7, dtype=torch.int32, device=DEV)
+        self.tau = torch.zeros((max(self.R, 1),), dtype=torch.float32, device=DEV)
+        self.mass = torch.zeros((max(self.R, 1),), dtype=torch.float32, device=DEV)
+        self.out = torch.zeros((self.B, L.n_q_heads, 128), dtype=torch.bfloat16, device=DEV)
+        self.lse = torch.zeros((self.B, L.n_q_heads), dtype=torch.float32, device=DEV)
+        self.ws_topp = ws_alloc(rtp.rtp_topp_workspace_bytes(max(self.R, 1), self.max_ctx))
+        self.ws_sparse = ws_alloc(rtp.rtp_sparse_attn_decode_workspace_bytes(self.desc, self.B, self.max_ctx))
+        self.ws_local = ws_alloc(rtp.rtp_local_attn_workspace_bytes(self.desc, self.B, 1, self.max_ctx))
+        self.ws_dense = ws_alloc(rtp.rtp_dense_attn_workspace_bytes(self.desc, self.B, 1, self.max_ctx))
+        self.T_tot = w.T_tot
+
+    # ---- the five calls -------------------------------------------------------------------
+    def index_score(self):
+        w = self.w
+        q_in = w.q_pre if w.WQ is not None else w.qI
+        rtp.rtp_index_score(self.desc, q_in, w.WQ, w.kI, self.T_tot * 16, self.seq_start, self.ctx_len, None,
+                            self.B, 1, self.max_ctx, self.scores, self.stride, self.qI_out)
+
+    def topp(self, scores=None, p_rows=None):
+        s = self.scores if scores is None else scores
+        p = self.w.p_rows if p_rows is None else p_rows
+        rtp.rtp_topp_select(s, self.stride, self.row_len, p, self.R, self.max_ctx, self.sel_idx, self.stride,
+                            self.sel_count, self.tau, self.mass, self.ws_topp)
+
+    def sparse_attn(self, sel_idx=None, sel_count=None, max_sel=None):
+        w = self.w
+        rtp.rtp_sparse_attn_decode(self.desc, w.q, w.K, w.V, 128, self.T_tot * 128, self.seq_start,
+                                   self.sel_idx if sel_idx is None else sel_idx, self.stride,
+                                   self.sel_count if sel_count is None else sel_count,
+                                   self.max_ctx if max_sel is None else max_sel, self.B, self.out, self.lse,
+                                   self.ws_sparse)
+
+    def local_attn(self):
+        w = self.w
+        rtp.rtp_local_attn(self.desc, w.q, w.K, w.V, 128, self.T_tot * 128, self.seq_start, self.ctx_len, None,
+                           self.B, 1, self.max_ctx, self.out, self.lse, self.ws_local)
+
+    def dense_attn(self, out=None, lse=None):
+        w = self.w
+        rtp.rtp_dense_attn(self.desc, w.q, w.K, w.V, 128, self.T_tot * 128, self.seq_start, self.ctx_len, None,
+                           self.B, 1, self.max_ctx, self.out if out is None else out,
+                           self.lse if lse is None else lse, self.ws_dense)
+
+    def step(self):
+        self.index_score()
+        self.topp()
+        self.sparse_attn()
+        self.local_attn()
+
+    # ---- results as numpy -----------------------------------------------------------------
+    def sel_sets(self):
+        torch.cuda.synchronize()
+        cnt = self.sel_count.cpu().numpy()
+        idx = self.sel_idx.cpu().numpy()
+        return [np.sort(idx[r, :max(cnt[r], 0)]) for r in range(self.R)], cnt
+
+    def out_f64(self):
+        torch.cuda.synchronize()
+        return self.out.float().cpu().numpy().astype(np.float64)
+
+
+def oracle_inputs(w: wl.DecodeWorkload) -> dict:
+    L = w.layer
+    d = dict(q_bits=wl.bf16_bits(w.q), K_bits=wl.bf16_bits(w.K), V_bits=wl.bf16_bits(w.V),
+             kI_bits=wl.bf16_bits(w.kI), seq_start=w.seq_start, ctx_len=w.ctx_len,
+             n_q_heads=L.n_q_heads, n_kv_heads=L.n_kv_heads, ret_heads=L.ret_heads, sink=L.sink,
+             window=L.window, p_rows=w.p_rows.cpu().numpy().astype(np.float64))
+    if w.WQ is not None:
+        d.update(WQ=w.WQ.cpu().numpy(), q_pre_bits=wl.bf16_bits(w.q_pre))
+    else:
+        d.update(qI_bits=wl.bf16_bits(w.qI))
+    return d
+
+
+# ---- comparators ------------------------------------------------------------------------------
+def check_scores(s_gpu: np.ndarray, s_ref: np.ndarray, qI_bits, kI_bits, what=""):
+    q = orc.bf16_to_f64(qI_bits)
+    k = orc.bf16_to_f64(kI_bits)
+    mag = np.abs(k) @ np.abs(q)
+    tol = SCORE_RTOL * np.maximum(np.abs(s_ref), mag)
+    bad = np.abs(s_gpu.astype(np.float64) - s_ref) > tol
+    assert not bad.any(), f"{what}: {bad.sum()} scores outside 1e-5 relative; worst {np.abs(s_gpu - s_ref).max()}"
+
+
+def check_selection(sel_gpu: np.ndarray, s: np.ndarray, ref: dict, p: float, what=""):
+    """`s`: the float64 scores the reference selection `ref` was computed from."""
+    tau = ref["tau"]
+    band = np.abs(s - tau) <= BAND_RTOL * max(1.0, abs(tau))
+    g = np.zeros(s.shape[0], dtype=bool)
+    g[sel_gpu] = True
+    r = np.zeros(s.shape[0], dtype=bool)
+    r[ref["idx"]] = True
+    diff = (g != r) & ~band
+    assert not diff.any(), (f"{what}: {diff.sum()} tokens outside the threshold band differ "
+                            f"(gpu {g.sum()} vs ref {r.sum()} tokens, tau {tau})")
+    w = np.exp(s - s.max())
+    Z = w.sum()
+    assert w[g].sum() / Z >= p - 1e-6, f"{what}: selected mass {w[g].sum() / Z} below p={p}"
+    assert w[g & ~band].sum() / Z < p + 1e-6, f"{what}: selection is not minimal"
+    assert len(np.unique(sel_gpu)) == len(sel_gpu), f"{what}: duplicate indices"
+
+
+def check_selection_valid(sel_gpu: np.ndarray, s: np.ndarray, p: float, slack: float, what=""):
+    """End-to-end form: the GPU chose its set from ITS fp32 scores, `s` are the oracle's fp64 scores
+    (they differ by up to `slack`).  The set must still be a top-p set of `s` up to that slack:
+    upward closed in score, mass >= p, and not reaching p without its lowest-scored band."""
+    g = np.zeros(s.shape[0], dtype=bool)
+    g[sel_gpu] = True
+    tau_g = s[g].min()
+    band = BAND_RTOL * max(1.0, abs(tau_g)) + 2.0 * slack
+    missing = (~g) & (s > tau_g + band)
+    assert not missing.any(), f"{what}: {missing.sum()} tokens above the threshold band are not selected"
+    w = np.exp(s - s.max())
+    Z = w.sum()
+    assert w[g].sum() / Z >= p - 1e-6, f"{what}: selected mass {w[g].sum() / Z} below p={p}"
+    assert w[g & (s > tau_g + band)].sum() / Z < p + 1e-6, f"{what}: selection is not minimal"
+
+
+def check_out(o_gpu: np.ndarray, o_ref: np.ndarray, what="", tight=True):
+    """The stated bar is 2e-2 absolute + 1e-2 relative; `tight` additionally holds the kernels to what
+    fp32 accumulation + one bf16 rounding of the output should give (1e-3 + 3e-3*|ref|)."""
+    err = np.abs(o_gpu - o_ref)
+    tol = OUT_ATOL + OUT_RTOL * np.abs(o_ref)
+    assert (err <= tol).all(), f"{what}: max abs err {err.max()} (tolerance 2e-2 + 1e-2*|ref|)"
+    if tight:
+        tol = 1e-3 + 3e-3 * np.abs(o_ref)
+        assert (err <= tol).all(), f"{what}: max abs err {err.max()} exceeds the bf16-rounding budget"
+    return float(err.max())

@@ -1,0 +1,144 @@
+"""Host-side checks of the C-ABI library that need no GPU: it loads, exports every symbol the
+public header declares, and rejects bad arguments before launching anything."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+from paper_2605_16928_amd import rtp
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+A = 0x10000  # a fake, well-aligned, non-NULL "device pointer": argument checks fail before any use
+
+
+def declared_symbols():
+    text = open(os.path.join(ROOT, "include", "rtp.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(rtp_[a-z_0-9]+)\s*\(", text)))
+
+
+def test_library_loads_and_exports_every_declared_symbol():
+    L = rtp.lib()
+    names = declared_symbols()
+    assert len(names) >= 12
+    for n in names:
+        assert hasattr(L, n), f"{n} is declared in include/rtp.h but not exported"
+    assert sorted(rtp.EXPORTS) == names
+    assert rtp.rtp_version().startswith("rtp-gfx950")
+
+
+def test_binding_has_one_function_per_entry_point():
+    for n in declared_symbols():
+        assert callable(getattr(rtp, n))
+
+
+def _layer(**kw):
+    d = dict(n_q_heads=8, n_kv_heads=2, ret_heads=[0, 4], sink=4, window=64)
+    d.update(kw)
+    return rtp.layer_desc(**d)
+
+
+def _expect(code, fn, *a, **k):
+    with pytest.raises(rtp.RtpError) as e:
+        fn(*a, **k)
+    assert e.value.code == code, str(e.value)
+    assert rtp.rtp_last_error() != ""
+    return str(e.value)
+
+
+def test_layer_descriptor_checks():
+    good = dict(q_in=A, WQ=None, kI=A, kI_head_stride=16 * 64, seq_start=A, ctx_len=A, q_start=None, B=1, n_q=1,
+                max_ctx=64, scores=A, score_stride=64, qI_out=None, stream=0)
+    call = lambda layer: rtp.rtp_index_score(layer, **good)
+    assert "head_dim" in _expect(rtp.RTP_ERR_UNSUPPORTED, call, _layer(head_dim=64))
+    assert "index_dim" in _expect(rtp.RTP_ERR_UNSUPPORTED, call, _layer(index_dim=32))
+    _expect(rtp.RTP_ERR_INVALID_ARG, call, _layer(n_q_heads=6, n_kv_heads=4))
+    _expect(rtp.RTP_ERR_UNSUPPORTED, call, _layer(n_q_heads=32, n_kv_heads=2))       # group of 16
+    assert "ascending" in _expect(rtp.RTP_ERR_INVALID_ARG, call, _layer(ret_heads=[4, 0]))
+    _expect(rtp.RTP_ERR_INVALID_ARG, call, _layer(ret_heads=[0, 8]))
+    _expect(rtp.RTP_ERR_INVALID_ARG, call, _layer(sink=0, window=0))
+    _expect(rtp.RTP_ERR_INVALID_ARG, call, _layer(sink=-1))
+
+
+def test_index_score_argument_checks():
+    L = _layer()
+    good = dict(q_in=A, WQ=None, kI=A, kI_head_stride=16 * 64, seq_start=A, ctx_len=A, q_start=None, B=1, n_q=1,
+                max_ctx=64, scores=A, score_stride=64, qI_out=None, stream=0)
+    for k, v in [("q_in", None), ("kI", None), ("scores", None), ("B", 0), ("max_ctx", 0), ("n_q", 2),
+                 ("score_stride", 63), ("score_stride", 66), ("scores", A + 4), ("kI_head_stride", 12),
+                 ("max_ctx", (1 << 24) + 1)]:
+        bad = dict(good)
+        bad[k] = v
+        if k == "max_ctx" and v > 64:
+            bad["score_stride"] = v + 3
+        _expect(rtp.RTP_ERR_INVALID_ARG, rtp.rtp_index_score, L, **bad)
+
+
+def test_topp_argument_and_workspace_checks():
+    need = rtp.rtp_topp_workspace_bytes(4, 1000)
+    assert need > 0 and need % 256 == 0
+    assert rtp.rtp_topp_workspace_bytes(8, 1000) > need
+    lib = rtp.lib()
+    vp = C.c_void_p
+
+    def call(scores=A, stride=1000, row_len=A, p=A, R=4, max_len=1000, sel=A, sel_stride=1000, cnt=A, ws=A,
+             ws_bytes=need):
+        return lib.rtp_topp_select(vp(scores), stride, vp(row_len), vp(p), R, max_len, vp(sel), sel_stride, vp(cnt),
+                                   None, None, vp(ws), ws_bytes, None)
+
+    assert call(scores=None) == rtp.RTP_ERR_INVALID_ARG
+    assert call(R=0) == rtp.RTP_ERR_INVALID_ARG
+    assert call(stride=999) == rtp.RTP_ERR_INVALID_ARG
+    assert call(stride=1002) == rtp.RTP_ERR_INVALID_ARG
+    assert call(sel_stride=999) == rtp.RTP_ERR_INVALID_ARG
+    assert call(max_len=(1 << 24) + 4, stride=(1 << 24) + 4, sel_stride=(1 << 24) + 4) == rtp.RTP_ERR_INVALID_ARG
+    assert call(ws=None) == rtp.RTP_ERR_WORKSPACE
+    assert call(ws=A + 8) == rtp.RTP_ERR_WORKSPACE
+    assert call(ws_bytes=need - 1) == rtp.RTP_ERR_WORKSPACE
+    assert b"workspace" in lib.rtp_last_error()
+
+
+def test_attention_argument_and_workspace_checks():
+    lib = rtp.lib()
+    L = _layer()
+    vp = C.c_void_p
+    need = rtp.rtp_sparse_attn_decode_workspace_bytes(L, 2, 4096)
+    assert need > 0 and need % 256 == 0
+
+    def sparse(q=A, K=A, V=A, rs=128, hs=128 * 100, sel_stride=4096, max_sel=4096, B=2, ws=A, wsb=need, layer=L):
+        return lib.rtp_sparse_attn_decode(C.byref(layer), vp(q), vp(K), vp(V), rs, hs, vp(A), vp(A), sel_stride, vp(A),
+                                          max_sel, B, vp(A), None, vp(ws), wsb, None)
+
+    assert sparse(q=None) == rtp.RTP_ERR_INVALID_ARG
+    assert sparse(rs=64) == rtp.RTP_ERR_INVALID_ARG
+    assert sparse(rs=132) == rtp.RTP_ERR_INVALID_ARG
+    assert sparse(K=A + 2) == rtp.RTP_ERR_INVALID_ARG
+    assert sparse(sel_stride=100) == rtp.RTP_ERR_INVALID_ARG
+    assert sparse(B=0) == rtp.RTP_ERR_INVALID_ARG
+    assert sparse(wsb=need - 256) == rtp.RTP_ERR_WORKSPACE
+    assert sparse(ws=None) == rtp.RTP_ERR_WORKSPACE
+    assert sparse(B=1000, wsb=1 << 40) == rtp.RTP_ERR_UNSUPPORTED          # more rows than one plan holds
+
+    for name in ("rtp_local_attn", "rtp_dense_attn"):
+        fn = getattr(lib, name)
+        need2 = getattr(rtp, name + "_workspace_bytes")(L, 2, 1, 4096)
+        assert need2 > 0 and need2 % 256 == 0
+
+        def rng(q=A, n_q=1, q_start=None, ws=A, wsb=need2, max_ctx=4096, ctx=A):
+            return fn(C.byref(L), vp(q), vp(A), vp(A), 128, 128 * 100, vp(A), vp(ctx), vp(q_start), 2, n_q, max_ctx,
+                      vp(A), None, vp(ws), wsb, None)
+
+        assert rng(q=None) == rtp.RTP_ERR_INVALID_ARG
+        assert rng(n_q=2) == rtp.RTP_ERR_INVALID_ARG           # decode mode takes one query per sequence
+        assert rng(n_q=0) == rtp.RTP_ERR_INVALID_ARG
+        assert rng(ctx=None) == rtp.RTP_ERR_INVALID_ARG
+        assert rng(max_ctx=0) == rtp.RTP_ERR_INVALID_ARG
+        assert rng(wsb=0) == rtp.RTP_ERR_WORKSPACE
+
+
+def test_missing_library_is_an_error_not_a_fallback(monkeypatch):
+    monkeypatch.setattr(rtp, "_lib", None)
+    monkeypatch.setattr(rtp, "LIB_PATH", "/nonexistent/librtp.so")
+    with pytest.raises(rtp.RtpError):
+        rtp.rtp_version()

@@ -1,0 +1,237 @@
+"""GPU parity of the decode path (index score -> top-p -> sparse attention, local attention, dense
+comparison) against the CPU oracle, element by element, through the C-ABI."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import rtp_oracle as orc
+from paper_2605_16928_amd import rtp, workloads as wl
+from gpu_util import DEV, DecodeRun, oracle_inputs, check_scores, check_selection, check_selection_valid, check_out, i32
+
+pytestmark = pytest.mark.gpu
+
+
+def _cases():
+    return {
+        # ragged batch, two retrieval heads on one KV head, G = 4, contexts below and above sink+window
+        "small": lambda: wl.small_decode(DEV),
+        # fp32 projections (index query computed by the library), G = 4
+        "small_proj": lambda: wl.small_decode(DEV, seed=12, index_mode="proj", ctx=(515, 2300, 129)),
+        # G = 1 and G = 2
+        "g1": lambda: wl.small_decode(DEV, seed=13, n_q_heads=4, n_kv_heads=4, ret_heads=(1, 3), ctx=(300, 9000)),
+        "g2": lambda: wl.small_decode(DEV, seed=14, n_q_heads=8, n_kv_heads=4, ret_heads=(0, 1, 6), ctx=(4100, 77)),
+        # configuration 1 at full size
+        "c1": lambda: wl.c1(DEV),
+        # configuration 2, shrunk: several top-p chunks and a ragged tail
+        "c2_small": lambda: wl.c2(DEV, ctx=20000, batch=3, p=0.9),
+        # configuration 5, shrunk: G = 8, ragged lengths, per-row p, flat and peaked rows
+        "c5_small": lambda: wl.c5(DEV, batch=5, lo=3000, hi=40000),
+    }
+
+
+@pytest.mark.parametrize("name", list(_cases()))
+def test_decode_path_matches_oracle(name):
+    print(f"[case] decode {name}", flush=True)
+    w = _cases()[name]()
+    run = DecodeRun(w)
+    L = w.layer
+    oi = oracle_inputs(w)
+    ref = orc.decode_layer(**oi)
+
+    # ---- stage 1: index query and scores ----
+    run.index_score()
+    torch.cuda.synchronize()
+    qI_gpu = wl.bf16_bits(run.qI_out)
+    assert np.array_equal(qI_gpu, ref["qI_bits"]), "index query bits differ"
+    s_gpu = run.scores.cpu().numpy()
+    row = 0
+    for b in range(w.B):
+        t0, n = w.seq_start[b], w.ctx_len[b]
+        for j in range(L.n_ret):
+            check_scores(s_gpu[row, :n], ref["scores"][row], ref["qI_bits"][b, j], oi["kI_bits"][j, t0:t0 + n],
+                         f"{name} row {row}")
+            row += 1
+
+    # ---- stage 2: top-p on the GPU's own scores (isolates the selector) ----
+    run.topp()
+    sets, cnt = run.sel_sets()
+    tau, mass = run.tau.cpu().numpy(), run.mass.cpu().numpy()
+    for r in range(run.R):
+        n = w.ctx_len[r // L.n_ret]
+        p = float(w.p_rows[r])
+        s64 = s_gpu[r, :n].astype(np.float64)
+        rr = orc.topp_select(s64, p)
+        check_selection(sets[r], s64, rr, p, f"{name} row {r} (same scores)")
+        assert abs(tau[r] - rr["tau"]) <= 1e-5 * max(1.0, abs(rr["tau"]))
+        assert abs(mass[r] - rr["mass"]) <= 1e-4
+        # and end to end against the oracle's own scores
+        slack = float(np.abs(s64 - ref["scores"][r]).max())
+        check_selection_valid(sets[r], ref["scores"][r], p, slack, f"{name} row {r} (end to end)")
+        assert abs(cnt[r] - ref["sel"][r]["count"]) <= 2 + int(1e-3 * ref["sel"][r]["count"])
+
+    # ---- stage 3: sparse attention over the GPU's sets vs the oracle over the same sets ----
+    run.sparse_attn()
+    run.local_attn()
+    out = run.out_f64()
+    lse = run.lse.cpu().numpy()
+    sc = 1.0 / np.sqrt(128.0)
+    for b in range(w.B):
+        t0, n = w.seq_start[b], w.ctx_len[b]
+        for j, h in enumerate(L.ret_heads):
+            kvh = h // (L.n_q_heads // L.n_kv_heads)
+            o, l = orc.attend(oi["q_bits"][b, h], oi["K_bits"][kvh, t0:t0 + n], oi["V_bits"][kvh, t0:t0 + n],
+                              sets[b * L.n_ret + j], sc)
+            check_out(out[b, h], o, f"{name} sparse b{b} h{h}")
+            assert abs(lse[b, h] - l) < 2e-3
+
+    # ---- stage 4: whole layer (retrieval + local rows) against the oracle end to end ----
+    check_out(out, ref["out"], f"{name} layer")
+    assert np.allclose(lse, ref["lse"], atol=2e-3, rtol=0)
+
+    # ---- dense comparison kernel ----
+    dout = torch.zeros_like(run.out)
+    dlse = torch.zeros_like(run.lse)
+    run.dense_attn(dout, dlse)
+    torch.cuda.synchronize()
+    dref = orc.decode_layer(**oi, dense=True)
+    check_out(dout.float().cpu().numpy().astype(np.float64), dref["out"], f"{name} dense")
+    assert np.allclose(dlse.cpu().numpy(), dref["lse"], atol=2e-3, rtol=0)
+
+
+def test_topp_edge_rows():
+    """Hand-made score rows: ties at the threshold, uniform rows, p = 1, invalid p, -inf entries,
+    a single element, lengths that are not multiples of 4."""
+    print("[case] topp edge rows", flush=True)
+    rng = np.random.default_rng(3)
+    n_max = 9001
+    stride = 9004
+    rows, ps = [], []
+
+    def add(s, p):
+        rows.append(np.asarray(s, dtype=np.float32))
+        ps.append(p)
+
+    add(np.log(np.array([8, 4, 2, 1, 1], dtype=np.float64)), 0.9)       # tie at the threshold: both kept
+    add(np.log(np.array([8, 4, 2, 1, 1], dtype=np.float64)), 0.45)
+    add(np.log(np.array([8, 4, 2, 1, 1], dtype=np.float64)), 0.7)
+    add(np.full(8, 0.25), 0.875)                                        # uniform: every entry ties
+    add(np.full(9001, -3.0), 0.3)
+    add(rng.standard_normal(9001), 1.0)                                 # keep everything
+    add(rng.standard_normal(5000), 0.0)                                 # invalid p
+    add(rng.standard_normal(5000), float("nan"))
+    add([1.5], 0.9)                                                     # single element
+    s = rng.standard_normal(8191) * 2
+    s[100:200] = -np.inf                                                # masked entries are never selected
+    add(s, 0.999)
+    add(rng.standard_normal(8193) * 0.01, 0.5)                          # flat
+    add(np.concatenate([[30.0], rng.standard_normal(3000)]), 0.9)       # one spike
+    add(-np.arange(40) * np.log(2.0), 0.999)                            # geometric
+    add(np.concatenate([rng.standard_normal(4097), [np.float32(-0.0), np.float32(0.0)]]), 0.7)
+    R = len(rows)
+    sc = torch.full((R, stride), float("nan"), dtype=torch.float32)
+    for r, s in enumerate(rows):
+        sc[r, :len(s)] = torch.from_numpy(s)
+    sc = sc.to(DEV)
+    row_len = i32([len(s) for s in rows])
+    p = torch.tensor(ps, dtype=torch.float32, device=DEV)
+    sel = torch.full((R, stride), -1, dtype=torch.int32, device=DEV)
+    cnt = torch.full((R,), -9, dtype=torch.int32, device=DEV)
+    tau = torch.zeros(R, device=DEV)
+    mass = torch.zeros(R, device=DEV)
+    ws = torch.empty(rtp.rtp_topp_workspace_bytes(R, n_max), dtype=torch.uint8, device=DEV)
+    for rep in range(2):                      # twice: the workspace is reused dirty
+        rtp.rtp_topp_select(sc, stride, row_len, p, R, n_max, sel, stride, cnt, tau, mass, ws)
+        torch.cuda.synchronize()
+        c = cnt.cpu().numpy()
+        idx = sel.cpu().numpy()
+        t = tau.cpu().numpy()
+        for r, s in enumerate(rows):
+            pr = ps[r]
+            if not (pr > 0):
+                assert c[r] == -1
+                continue
+            got = np.sort(idx[r, :c[r]])
+            s64 = s.astype(np.float64)
+            finite = np.isfinite(s64)
+            if pr >= 1:
+                assert np.array_equal(got, np.nonzero(finite)[0])
+                continue
+            ref = orc.topp_select(np.where(finite, s64, -1e30), pr)
+            # the library keeps ALL ties at the threshold
+            want = np.nonzero(finite & (s64 >= ref["tau"]))[0]
+            assert np.array_equal(got, want), f"row {r}: {len(got)} vs {len(want)}"
+            assert t[r] == np.float32(ref["tau"])
+    assert c[0] == 5 and c[1] == 1 and c[2] == 2 and c[3] == 8 and c[8] == 1
+    assert c[4] == 9001                        # all-equal row: every entry ties with the threshold
+
+
+def test_sparse_attn_degenerate_sets():
+    """Empty sets, single-token sets, a set that is the whole context, unsorted index lists."""
+    print("[case] sparse degenerate sets", flush=True)
+    w = wl.small_decode(DEV, seed=21, ctx=(300, 1000, 50))
+    run = DecodeRun(w)
+    L = w.layer
+    oi = oracle_inputs(w)
+    rng = np.random.default_rng(5)
+    sets = []
+    for r in range(run.R):
+        n = w.ctx_len[r // L.n_ret]
+        kind = r % 5
+        if kind == 0:
+            s = np.array([], dtype=np.int64)
+        elif kind == 1:
+            s = np.array([n - 1])
+        elif kind == 2:
+            s = rng.permutation(n)                         # everything, shuffled
+        elif kind == 3:
+            s = rng.choice(n, size=min(n, 129), replace=False)
+        else:
+            s = np.arange(0, n, 3)
+        sets.append(s)
+    idx = torch.zeros((run.R, run.stride), dtype=torch.int32)
+    for r, s in enumerate(sets):
+        idx[r, :len(s)] = torch.from_numpy(s.astype(np.int32))
+    cnt = i32([len(s) for s in sets])
+    run.out.fill_(7.0)
+    run.sparse_attn(idx.to(DEV), cnt)
+    out = run.out_f64()
+    lse = run.lse.cpu().numpy()
+    sc = 1.0 / np.sqrt(128.0)
+    for b in range(w.B):
+        t0, n = w.seq_start[b], w.ctx_len[b]
+        for j, h in enumerate(L.ret_heads):
+            r = b * L.n_ret + j
+            kvh = h // (L.n_q_heads // L.n_kv_heads)
+            if len(sets[r]) == 0:
+                assert np.all(out[b, h] == 0) and lse[b, h] == -np.inf
+                continue
+            o, l = orc.attend(oi["q_bits"][b, h], oi["K_bits"][kvh, t0:t0 + n], oi["V_bits"][kvh, t0:t0 + n], sets[r], sc)
+            check_out(out[b, h], o, f"row {r}")
+            if len(sets[r]) == 1:
+                assert np.array_equal(out[b, h], orc.bf16_to_f64(oi["V_bits"][kvh, t0 + sets[r][0]]))
+        for h in range(L.n_q_heads):
+            if h not in L.ret_heads:
+                assert np.all(out[b, h] == 7.0)            # local rows are not touched by the sparse call
+
+
+def test_local_attn_short_contexts_and_interleaved_kv():
+    """Contexts of 1, below sink, exactly sink+window, and K|V interleaved rows (row stride 256)."""
+    print("[case] local short contexts / interleaved KV", flush=True)
+    w = wl.small_decode(DEV, seed=31, ctx=(1, 3, 100, 101, 5000), sink=4, window=96, p=(0.9,) * 5, n_planted=0)
+    L = w.layer
+    oi = oracle_inputs(w)
+    ref = orc.decode_layer(**oi)
+    run = DecodeRun(w)
+    run.step()
+    check_out(run.out_f64(), ref["out"], "short contexts")
+    # interleave K and V rows: element (kvh, t, :) of K at kv[kvh, t, 0:128], of V at kv[kvh, t, 128:256]
+    kv = torch.cat([w.K, w.V], dim=2).contiguous()
+    T = w.T_tot
+    out2 = torch.zeros_like(run.out)
+    Kp, Vp = kv.data_ptr(), kv.data_ptr() + 256
+    rtp.rtp_local_attn(run.desc, w.q, Kp, Vp, 256, T * 256, run.seq_start, run.ctx_len, None, w.B, 1, run.max_ctx,
+                       out2, None, run.ws_local)
+    rtp.rtp_sparse_attn_decode(run.desc, w.q, Kp, Vp, 256, T * 256, run.seq_start, run.sel_idx, run.stride,
+                               run.sel_count, run.max_ctx, w.B, out2, None, run.ws_sparse)
+    torch.cuda.synchronize()
+    assert torch.equal(out2, run.out)
