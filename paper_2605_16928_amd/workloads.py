@@ -244,6 +244,7 @@ def small_decode(device="cpu", seed: int = 11, ctx=(700, 1531, 64, 2048), *, n_q
     several sequences of unequal length, two retrieval heads sharing a KV head,
     contexts shorter and longer than sink + window."""
     layer = Layer(n_q_heads, n_kv_heads, list(ret_heads), sink=sink, window=window)
+    p = [p[i % len(p)] for i in range(len(ctx))]          # one p per sequence, cycling the given ones
     return make_decode("small", layer, list(ctx), list(p), seed, device, index_mode=index_mode,
                        n_planted=n_planted, planted_frac=0.6)
 

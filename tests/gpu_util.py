@@ -168,11 +168,11 @@ def check_selection_valid(sel_gpu: np.ndarray, s: np.ndarray, p: float, slack: f
 
 def check_out(o_gpu: np.ndarray, o_ref: np.ndarray, what="", tight=True):
     """The stated bar is 2e-2 absolute + 1e-2 relative; `tight` additionally holds the kernels to what
-    fp32 accumulation + one bf16 rounding of the output should give (1e-3 + 3e-3*|ref|)."""
+    fp32 accumulation + one bf16 rounding of the output should give (1e-3 + 2^-8*|ref|)."""
     err = np.abs(o_gpu - o_ref)
     tol = OUT_ATOL + OUT_RTOL * np.abs(o_ref)
     assert (err <= tol).all(), f"{what}: max abs err {err.max()} (tolerance 2e-2 + 1e-2*|ref|)"
     if tight:
-        tol = 1e-3 + 3e-3 * np.abs(o_ref)
+        tol = 1e-3 + 2.0 ** -8 * np.abs(o_ref)
         assert (err <= tol).all(), f"{what}: max abs err {err.max()} exceeds the bf16-rounding budget"
     return float(err.max())
