@@ -120,7 +120,7 @@ int32_t rtp_index_score(const rtp_layer_desc* layer, const void* q_in, const flo
  *   p         device fp32 [R], one value per row; p >= 1 keeps every entry of the row (tau = -inf);
  *             p <= 0 or NaN marks the row invalid: sel_count = -1, nothing selected.
  *   sel_idx   out, int32 [R, sel_stride], sel_stride >= max_len; the selected positions in
- *             UNSPECIFIED order (use them as a set).
+ *             ascending order (the result is deterministic: same inputs, same bits).
  *   sel_count out, int32 [R].   tau, mass: optional outputs fp32 [R] (threshold score; selected mass / Z).
  */
 size_t rtp_topp_workspace_bytes(int32_t R, int64_t max_len);

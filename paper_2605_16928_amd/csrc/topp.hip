@@ -9,7 +9,8 @@
 // Masses are fp64 exponentials converted to 64-bit fixed point, so every sum is an integer sum and
 // the result is independent of the order in which atomics land.
 //
-// Launches: init (row maxima per chunk, zero histograms) -> level 1 -> level 2 -> level 3 -> compact.
+// Launches: init (row maxima per chunk, zero histograms) -> level 1 -> level 2 -> level 3 -> count -> write.
+// The selected positions come out in ascending order (deterministic, and friendly to the K/V gather).
 // There is no "last block" hand-off: each level's histogram is scanned redundantly in the prologue
 // of every workgroup of the NEXT launch, so kernel boundaries provide all ordering.
 // A row is cut into chunks of kChunk scores, one workgroup each; histograms live in LDS and only
@@ -47,8 +48,9 @@ struct TopPArgs {
   float* tau;
   float* mass;
   float* cmax;             // [R, n_chunks]
+  int32_t* chunk_cnt;      // [R, n_chunks]
   uint64_t* hist;          // [R, kBinsTotal]
-  RowState* state;         // [R, 3]
+  RowState* state;         // [R, 4]
 };
 
 __device__ __forceinline__ int fixed_shift(int n) {
@@ -130,7 +132,6 @@ __global__ __launch_bounds__(kTpThreads) void topp_init_kernel(const TopPArgs a)
   __shared__ float red[kTpThreads / 64];
   uint64_t* h = a.hist + (int64_t)r * kBinsTotal;
   for (int i = c * kTpThreads + tid; i < kBinsTotal; i += a.n_chunks * kTpThreads) h[i] = 0;
-  if (c == 0 && tid == 0) a.sel_count[r] = 0;
   const int n = a.row_len[r];
   const int64_t n0 = (int64_t)c * kTpChunk;
   if (n0 >= n) return;
@@ -168,7 +169,7 @@ __global__ __launch_bounds__(kTpThreads) void topp_level_kernel(const TopPArgs a
   __shared__ uint64_t sh_res[3];
   __shared__ float red[kTpThreads / 64];
   uint64_t* hrow = a.hist + (int64_t)r * kBinsTotal;
-  RowState* st = a.state + (int64_t)r * 3;
+  RowState* st = a.state + (int64_t)r * 4;
 
   // ---- prologue: what the previous launch left for this row ----
   float smax;
@@ -262,15 +263,38 @@ __global__ __launch_bounds__(kTpThreads) void topp_level_kernel(const TopPArgs a
   }
 }
 
-// ---- launch 4: final scan, statistics, compaction ---------------------------------------------
-__global__ __launch_bounds__(kTpThreads) void topp_compact_kernel(const TopPArgs a) {
+// ---- launches 4 and 5: final scan + per-chunk counts, then ordered compaction ---------------------
+// Bit u*4+k of the result says whether score (u * 256 + tid) * 4 + k of the chunk is kept.
+__device__ __forceinline__ uint32_t keep_mask(const float4* __restrict__ src, int n_here, int tid, bool all,
+                                              uint32_t tkey) {
+  const float ninf = -__builtin_huge_valf();
+  uint32_t keep = 0;
+#pragma unroll
+  for (int u = 0; u < kTpVec; ++u) {
+    const int e = (u * kTpThreads + tid) * 4;
+    if (e < n_here) {
+      const float4 v = src[u * kTpThreads + tid];
+      const float s4[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+      for (int k = 0; k < 4; ++k) {
+        const bool sel = (e + k < n_here) && s4[k] != ninf && (all || float_key(s4[k]) >= tkey);
+        keep |= (sel ? 1u : 0u) << (u * 4 + k);
+      }
+    }
+  }
+  return keep;
+}
+
+__global__ __launch_bounds__(kTpThreads) void topp_count_kernel(const TopPArgs a) {
   const int r = blockIdx.y, c = blockIdx.x, tid = threadIdx.x;
   const int n = a.row_len[r];
   const int64_t n0 = (int64_t)c * kTpChunk;
+  RowState* st = a.state + (int64_t)r * 4;
   if (n <= 0) {
     if (c == 0 && tid == 0) {
       if (a.tau) a.tau[r] = -__builtin_huge_valf();
       if (a.mass) a.mass[r] = 0.f;
+      a.sel_count[r] = 0;
     }
     return;
   }
@@ -278,9 +302,8 @@ __global__ __launch_bounds__(kTpThreads) void topp_compact_kernel(const TopPArgs
   __shared__ uint64_t sh_part[kTpThreads];
   __shared__ uint64_t sh_res[3];
   __shared__ int sh_cnt[kTpThreads / 64];
-  __shared__ int sh_base;
   const uint64_t* hrow = a.hist + (int64_t)r * kBinsTotal;
-  const RowState prev = a.state[(int64_t)r * 3 + 2];
+  const RowState prev = st[2];
 
   uint32_t tkey = 0;      // keep keys >= tkey
   if (prev.flags < 0) {
@@ -288,6 +311,8 @@ __global__ __launch_bounds__(kTpThreads) void topp_compact_kernel(const TopPArgs
       a.sel_count[r] = -1;
       if (a.tau) a.tau[r] = __builtin_nanf("");
       if (a.mass) a.mass[r] = 0.f;
+      RowState s = prev;
+      st[3] = s;
     }
     return;
   } else if (prev.flags == 0) {
@@ -303,64 +328,114 @@ __global__ __launch_bounds__(kTpThreads) void topp_compact_kernel(const TopPArgs
     if (a.tau) a.tau[r] = -__builtin_huge_valf();
     if (a.mass) a.mass[r] = 1.f;
   }
+  if (c == 0 && tid == 0) {
+    RowState s = prev;
+    s.prefix = tkey;
+    st[3] = s;
+  }
 
   const float4* src = reinterpret_cast<const float4*>(a.scores + (int64_t)r * a.score_stride + n0);
   const int n_here = (int)min((int64_t)kTpChunk, (int64_t)n - n0);
-  const float ninf = -__builtin_huge_valf();
-  // pass A: which of this thread's 32 scores are kept (bit mask), and how many
-  uint32_t keep = 0;
+  int cnt = __popc(keep_mask(src, n_here, tid, prev.flags == 1, tkey));
 #pragma unroll
-  for (int u = 0; u < kTpVec; ++u) {
-    const int e = (u * kTpThreads + tid) * 4;
-    if (e < n_here) {
-      const float4 v = src[u * kTpThreads + tid];
-      const float s4[4] = {v.x, v.y, v.z, v.w};
+  for (int o = 32; o > 0; o >>= 1) cnt += __shfl_xor(cnt, o);
+  if ((tid & 63) == 0) sh_cnt[tid >> 6] = cnt;
+  __syncthreads();
+  if (tid == 0) {
+    int tot = 0;
 #pragma unroll
-      for (int k = 0; k < 4; ++k) {
-        const bool sel = (e + k < n_here) && s4[k] != ninf && (prev.flags == 1 || float_key(s4[k]) >= tkey);
-        keep |= (sel ? 1u : 0u) << (u * 4 + k);
-      }
-    }
+    for (int i = 0; i < kTpThreads / 64; ++i) tot += sh_cnt[i];
+    a.chunk_cnt[(int64_t)r * a.n_chunks + c] = tot;
   }
-  const int mine = __popc(keep);
-  // exclusive prefix over the block: wave scan + wave totals
-  int incl = mine;
+}
+
+// Writes the kept positions of the row in ascending order: chunk bases come from the per-chunk
+// counts of the previous launch, positions inside a chunk from block-wide prefix sums.
+__global__ __launch_bounds__(kTpThreads) void topp_write_kernel(const TopPArgs a) {
+  const int r = blockIdx.y, c = blockIdx.x, tid = threadIdx.x;
+  const int n = a.row_len[r];
+  const int64_t n0 = (int64_t)c * kTpChunk;
+  if (n <= 0 || n0 >= n) return;
+  const RowState st = a.state[(int64_t)r * 4 + 3];
+  if (st.flags < 0) return;
+  __shared__ int sh_red[kTpThreads / 64][2];
+  __shared__ uint64_t sh_tot[kTpThreads / 64][2];
+
+  // ---- base of this chunk = kept count of the chunks before it; chunk 0 also publishes the total ----
+  const int n_row_chunks = (n + kTpChunk - 1) / kTpChunk;
+  int before = 0, total = 0;
+  for (int i = tid; i < n_row_chunks; i += kTpThreads) {
+    const int v = a.chunk_cnt[(int64_t)r * a.n_chunks + i];
+    total += v;
+    if (i < c) before += v;
+  }
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) {
+    before += __shfl_xor(before, o);
+    total += __shfl_xor(total, o);
+  }
+  if ((tid & 63) == 0) { sh_red[tid >> 6][0] = before; sh_red[tid >> 6][1] = total; }
+  __syncthreads();
+  before = 0;
+  total = 0;
+#pragma unroll
+  for (int i = 0; i < kTpThreads / 64; ++i) { before += sh_red[i][0]; total += sh_red[i][1]; }
+  if (c == 0 && tid == 0) a.sel_count[r] = total;
+
+  const float4* src = reinterpret_cast<const float4*>(a.scores + (int64_t)r * a.score_stride + n0);
+  const int n_here = (int)min((int64_t)kTpChunk, (int64_t)n - n0);
+  const uint32_t keep = keep_mask(src, n_here, tid, st.flags == 1, st.prefix);
+
+  // ---- rank inside the chunk: element order is (load round u, thread, k) ----
+  // per-round counts (0..4) packed as 16-bit fields of two 64-bit words
+  uint64_t lo = 0, hi = 0;
+#pragma unroll
+  for (int u = 0; u < 4; ++u) {
+    lo |= (uint64_t)__popc((keep >> (u * 4)) & 0xFu) << (16 * u);
+    hi |= (uint64_t)__popc((keep >> (16 + u * 4)) & 0xFu) << (16 * u);
+  }
+  uint64_t ilo = lo, ihi = hi;       // inclusive wave scans
 #pragma unroll
   for (int o = 1; o < 64; o <<= 1) {
-    const int t = __shfl_up(incl, o);
-    if ((tid & 63) >= o) incl += t;
+    const uint64_t tl = __shfl_up(ilo, o), th = __shfl_up(ihi, o);
+    if ((tid & 63) >= o) { ilo += tl; ihi += th; }
   }
-  if ((tid & 63) == 63) sh_cnt[tid >> 6] = incl;
+  if ((tid & 63) == 63) { sh_tot[tid >> 6][0] = ilo; sh_tot[tid >> 6][1] = ihi; }
   __syncthreads();
-  int wave_off = 0, block_total = 0;
-#pragma unroll
-  for (int i = 0; i < kTpThreads / 64; ++i) {
-    if (i < (tid >> 6)) wave_off += sh_cnt[i];
-    block_total += sh_cnt[i];
-  }
-  if (tid == 0) sh_base = block_total ? atomicAdd(&a.sel_count[r], block_total) : 0;
-  __syncthreads();
-  int pos = sh_base + wave_off + incl - mine;
   int32_t* out = a.sel_idx + (int64_t)r * a.sel_stride;
+  int round_base = before;
 #pragma unroll
   for (int u = 0; u < kTpVec; ++u) {
+    const int sh = 16 * (u & 3);
+    int wave_before = 0, round_total = 0;
+#pragma unroll
+    for (int i = 0; i < kTpThreads / 64; ++i) {
+      const int t = (int)((sh_tot[i][u >> 2] >> sh) & 0xFFFFu);
+      if (i < (tid >> 6)) wave_before += t;
+      round_total += t;
+    }
+    const int incl = (int)(((u < 4 ? ilo : ihi) >> sh) & 0xFFFFu);
+    const int mine = (int)(((u < 4 ? lo : hi) >> sh) & 0xFFFFu);
+    int pos = round_base + wave_before + incl - mine;
 #pragma unroll
     for (int k = 0; k < 4; ++k) {
       if (keep & (1u << (u * 4 + k))) out[pos++] = (int32_t)(n0 + (u * kTpThreads + tid) * 4 + k);
     }
+    round_base += round_total;
   }
 }
 
 struct TopPLayout {
-  size_t cmax_off, hist_off, state_off, total;
+  size_t cmax_off, ccnt_off, hist_off, state_off, total;
 };
 static TopPLayout topp_layout(int32_t R, int64_t max_len) {
   const int64_t n_chunks = (max_len + kTpChunk - 1) / kTpChunk;
   TopPLayout l;
   size_t off = 0;
   l.cmax_off = off;  off = align_up(off + (size_t)R * n_chunks * sizeof(float), 256);
+  l.ccnt_off = off;  off = align_up(off + (size_t)R * n_chunks * sizeof(int32_t), 256);
   l.hist_off = off;  off = align_up(off + (size_t)R * kBinsTotal * sizeof(uint64_t), 256);
-  l.state_off = off; off = align_up(off + (size_t)R * 3 * sizeof(RowState), 256);
+  l.state_off = off; off = align_up(off + (size_t)R * 4 * sizeof(RowState), 256);
   l.total = off;
   return l;
 }
@@ -406,6 +481,7 @@ extern "C" int32_t rtp_topp_select(const float* scores, int64_t score_stride, co
   a.tau = tau;
   a.mass = mass;
   a.cmax = (float*)((char*)ws + l.cmax_off);
+  a.chunk_cnt = (int32_t*)((char*)ws + l.ccnt_off);
   a.hist = (uint64_t*)((char*)ws + l.hist_off);
   a.state = (RowState*)((char*)ws + l.state_off);
 
@@ -415,6 +491,7 @@ extern "C" int32_t rtp_topp_select(const float* scores, int64_t score_stride, co
   hipLaunchKernelGGL(topp_level_kernel<1>, grid, block, 0, s, a);
   hipLaunchKernelGGL(topp_level_kernel<2>, grid, block, 0, s, a);
   hipLaunchKernelGGL(topp_level_kernel<3>, grid, block, 0, s, a);
-  hipLaunchKernelGGL(topp_compact_kernel, grid, block, 0, s, a);
+  hipLaunchKernelGGL(topp_count_kernel, grid, block, 0, s, a);
+  hipLaunchKernelGGL(topp_write_kernel, grid, block, 0, s, a);
   return check_launch(who);
 }

@@ -55,6 +55,9 @@ def test_decode_path_matches_oracle(name):
     # ---- stage 2: top-p on the GPU's own scores (isolates the selector) ----
     run.topp()
     sets, cnt = run.sel_sets()
+    raw = run.sel_idx.cpu().numpy()
+    for r in range(run.R):
+        assert np.array_equal(raw[r, :cnt[r]], sets[r]), "selected positions must come out ascending"
     tau, mass = run.tau.cpu().numpy(), run.mass.cpu().numpy()
     for r in range(run.R):
         n = w.ctx_len[r // L.n_ret]
