@@ -37,6 +37,7 @@ def main() -> int:
     ap.add_argument("--batch", type=int, default=8)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-graph", action="store_true", help="time eager launches instead of HIP graph replays")
+    ap.add_argument("--one-stream", action="store_true", help="keep the local heads on the main stream")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build is single-GPU by design (no collectives, no sharding); run with --gpus 1",
@@ -76,8 +77,16 @@ def main() -> int:
         return e0.elapsed_time(e1) * 1e3 / iters
 
     # ---- the step: eager, and captured in one HIP graph per copy ----
+    side2 = torch.cuda.Stream()
+
+    def run_step(r):
+        if args.one_stream:
+            r.step()
+        else:
+            r.step_two_streams(side2)
+
     for r in runs:
-        r.step()
+        run_step(r)
     torch.cuda.synchronize()
     sel_counts = runs[0].sel_count.cpu().numpy().astype(np.int64)
     graphs = []
@@ -86,7 +95,7 @@ def main() -> int:
         for r in runs:
             g = torch.cuda.CUDAGraph()
             with torch.cuda.graph(g, stream=side):
-                r.step()
+                run_step(r)
             graphs.append(g)
         # every replay must reproduce the eager result
         ref_out = [r.out.clone() for r in runs]
@@ -101,7 +110,7 @@ def main() -> int:
         if graphs:
             graphs[i % len(graphs)].replay()
         else:
-            runs[i % len(runs)].step()
+            run_step(runs[i % len(runs)])
 
     # ---- the timed region: exactly K steps, synchronise on both sides ----
     for i in range(args.warmup):
@@ -124,7 +133,7 @@ def main() -> int:
         "local_attn": timed(lambda i: runs[i % len(runs)].local_attn(), it, wu),
     }
     dense_us = timed(lambda i: runs[i % len(runs)].dense_attn(runs[i % len(runs)].out), max(10, it // 10), 2)
-    eager_us = timed(lambda i: runs[i % len(runs)].step(), it, wu)
+    eager_us = timed(lambda i: run_step(runs[i % len(runs)]), it, wu)
 
     # ---- algorithmic bytes per step (design notes: per-unit figures x units) ----
     sel_total = int(sel_counts.sum())
@@ -195,7 +204,8 @@ def main() -> int:
         "data": "synthetic",
         "config": {"workload": f"c2: decode step, batch {B} x context {N}, 32 query / 8 KV heads, head_dim 128, "
                                f"4 retrieval heads (index dim 16, top-p {args.p}), local heads 4 sink + 2048 window",
-                   "copies_cycled": args.copies, "launch": "hip-graph replay" if graphs else "eager"},
+                   "copies_cycled": args.copies, "launch": "hip-graph replay" if graphs else "eager",
+                   "streams": 1 if args.one_stream else 2},
         "roofline": roofline,
         "cpu_baseline": cpu,
         "extra": {

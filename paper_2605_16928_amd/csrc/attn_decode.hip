@@ -18,6 +18,8 @@
 // Algorithmic traffic: 512 B per attended token and KV head (+ 4 B per token for the index list).
 #include "common.h"
 
+#include <stdlib.h>
+
 namespace rtp {
 
 constexpr int kAdThreads = 256;
@@ -40,7 +42,9 @@ struct AttnDecodeArgs {
   const int32_t* sel_count;
   int32_t n_q_heads, n_kv_heads, n_ret, sink, window;
   int32_t units;           // B * n_ret (sparse) or B * n_kv_heads
-  int32_t target_items;    // host hint: aim for this many work items
+  int32_t target_items;    // sparse: host hint, aim for this many work items
+  int32_t split_tokens;    // local / dense: tokens per work item, fixed by the host
+  int32_t n_splits;        // local / dense: work items per unit
   float scale_log2;        // softmax scale * log2(e)
   float* part;             // [items, G, kPartStride]
   uint16_t* out;
@@ -151,7 +155,12 @@ __global__ __launch_bounds__(kAdThreads) void attn_decode_kernel(const AttnDecod
   __shared__ float sh_acc[kAdThreads / 64][G][kHeadDim];
 
   int ST, n_items;
-  build_plan<SRC>(a, sh_prefix, sh_w, &ST, &n_items);
+  if (SRC == kSrcSparse) {
+    build_plan<SRC>(a, sh_prefix, sh_w, &ST, &n_items);
+  } else {
+    ST = a.split_tokens;
+    n_items = a.units * a.n_splits;
+  }
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int grp = wave * 4 + (lane >> 4);   // 16 groups of 16 lanes
@@ -160,8 +169,14 @@ __global__ __launch_bounds__(kAdThreads) void attn_decode_kernel(const AttnDecod
   const int group_size = a.n_q_heads / a.n_kv_heads;
 
   for (int item = blockIdx.x; item < n_items; item += gridDim.x) {
-    const int unit = find_unit(sh_prefix, a.units, item);
-    const int split = item - sh_prefix[unit];
+    int unit, split;
+    if (SRC == kSrcSparse) {
+      unit = find_unit(sh_prefix, a.units, item);
+      split = item - sh_prefix[unit];
+    } else {
+      unit = item / a.n_splits;
+      split = item - unit * a.n_splits;
+    }
     int b, kvh, h0;
     if (SRC == kSrcSparse) {
       b = unit / a.n_ret;
@@ -174,6 +189,7 @@ __global__ __launch_bounds__(kAdThreads) void attn_decode_kernel(const AttnDecod
     }
     const int n_tok = unit_tokens<SRC>(a, unit);
     const int t_begin = split * ST, t_end = min(n_tok, t_begin + ST);
+    if (t_begin >= n_tok) continue;        // (fixed plan only) this split lies beyond the unit's tokens
     // local source: logical token i maps to position i (sinks) or w0 + (i - s0) (window)
     int s0 = 0, w0 = 0;
     if (SRC == kSrcLocal) {
@@ -321,75 +337,130 @@ __global__ __launch_bounds__(kAdThreads) void attn_decode_kernel(const AttnDecod
   }
 }
 
-// Merges the partials of one (unit, head): grid = units * G blocks of 128 threads.
+// Merges the partials of one (unit, head) per workgroup: 8 slices of 32 lanes, each lane owns 4 of the
+// 128 output dims and walks the unit's work items slice, slice + 8, ...; LDS merges the 8 slices.
 template <int G, int SRC>
 __global__ __launch_bounds__(kAdThreads) void attn_decode_combine_kernel(const AttnDecodeArgs a) {
-  __shared__ int sh_prefix[kAdMaxUnits + 1];
+  __shared__ int sh_prefix[SRC == kSrcSparse ? kAdMaxUnits + 1 : 1];
   __shared__ int sh_w[kAdThreads / 64];
-  int ST, n_items;
-  build_plan<SRC>(a, sh_prefix, sh_w, &ST, &n_items);
+  __shared__ float sh_m[8], sh_l[8];
+  __shared__ float sh_acc[8][kHeadDim];
   const int tid = threadIdx.x;
   const float ninf = -__builtin_huge_valf();
-  // two (unit, head) pairs per block: 128 threads each
-  const int pair = blockIdx.x * 2 + (tid >> 7);
-  if (pair >= a.units * G) return;
-  const int unit = pair / G, hh = pair - unit * G, d = tid & 127;
-  int b, h;
+  const int unit = blockIdx.x / G, hh = blockIdx.x - unit * G;
+  int b, h, i0, i1;
   if (SRC == kSrcSparse) {
+    int ST, n_items;
+    build_plan<SRC>(a, sh_prefix, sh_w, &ST, &n_items);
     b = unit / a.n_ret;
     h = a.ret_heads[unit - b * a.n_ret];
+    i0 = sh_prefix[unit];
+    i1 = (unit + 1 < a.units) ? sh_prefix[unit + 1] : n_items;
   } else {
     b = unit / a.n_kv_heads;
     h = (unit - b * a.n_kv_heads) * G + hh;
     if (SRC == kSrcLocal && a.is_ret[h]) return;
+    i0 = unit * a.n_splits;
+    i1 = i0 + (unit_tokens<SRC>(a, unit) + a.split_tokens - 1) / a.split_tokens;
   }
-  const int i0 = sh_prefix[unit];
-  const int i1 = (unit + 1 < a.units) ? sh_prefix[unit + 1] : n_items;
-  float M = ninf;
-  for (int i = i0; i < i1; ++i) M = fmaxf(M, a.part[((int64_t)i * G + hh) * kPartStride]);
-  float L = 0.f, A = 0.f;
-  if (M != ninf) {
-    for (int i = i0; i < i1; ++i) {
-      const float* p = a.part + ((int64_t)i * G + hh) * kPartStride;
-      const float cw = fast_exp2(p[0] - M);
-      L += p[1] * cw;
-      A += p[4 + d] * cw;
+  const int d4 = tid & 31, slice = tid >> 5;
+  float M = ninf, L = 0.f;
+  float4 A = make_float4(0.f, 0.f, 0.f, 0.f);
+  for (int i = i0 + slice; i < i1; i += 8) {
+    const float* p = a.part + ((int64_t)i * G + hh) * kPartStride;
+    const float m = p[0], l = p[1];
+    const float4 v = *reinterpret_cast<const float4*>(p + 4 + d4 * 4);
+    const float Mn = fmaxf(M, m);
+    if (Mn != ninf) {
+      const float c0 = fast_exp2(M - Mn), c1 = fast_exp2(m - Mn);
+      L = L * c0 + l * c1;
+      A.x = A.x * c0 + v.x * c1; A.y = A.y * c0 + v.y * c1;
+      A.z = A.z * c0 + v.z * c1; A.w = A.w * c0 + v.w * c1;
+      M = Mn;
     }
   }
-  const int64_t o = ((int64_t)b * a.n_q_heads + h);
-  a.out[o * kHeadDim + d] = f32_to_bf16_rne(L > 0.f ? A / L : 0.f);
-  if (a.lse && d == 0) a.lse[o] = L > 0.f ? (M + log2f(L)) * 0.6931471805599453f : ninf;
+  if (d4 == 0) { sh_m[slice] = M; sh_l[slice] = L; }
+  *reinterpret_cast<float4*>(&sh_acc[slice][d4 * 4]) = A;
+  __syncthreads();
+  if (tid < kHeadDim) {
+    float Mt = sh_m[0];
+#pragma unroll
+    for (int s = 1; s < 8; ++s) Mt = fmaxf(Mt, sh_m[s]);
+    float Lt = 0.f, At = 0.f;
+    if (Mt != ninf) {
+#pragma unroll
+      for (int s = 0; s < 8; ++s) {
+        const float cw = fast_exp2(sh_m[s] - Mt);
+        Lt += sh_l[s] * cw;
+        At += sh_acc[s][tid] * cw;
+      }
+    }
+    const int64_t o = ((int64_t)b * a.n_q_heads + h);
+    a.out[o * kHeadDim + tid] = f32_to_bf16_rne(Lt > 0.f ? At / Lt : 0.f);
+    if (a.lse && tid == 0) a.lse[o] = Lt > 0.f ? (Mt + log2f(Lt)) * 0.6931471805599453f : ninf;
+  }
 }
 
 struct DecodePlanHost {
-  int32_t units, target_items, grid;
+  int32_t units, target_items, grid, split_tokens, n_splits;
   size_t ws_bytes;
 };
 
-static DecodePlanHost plan_host(int32_t units, int64_t max_tok, int32_t G) {
-  DecodePlanHost p;
+static int tune(const char* name, int dflt) {
+  const char* e = getenv(name);
+  return e ? atoi(e) : dflt;
+}
+
+// Sparse: the set sizes are only known on the device, so the host gives a target item count and a
+// persistent grid; the device derives the split length from the actual counts.
+static DecodePlanHost plan_host_sparse(int32_t units, int64_t max_tok) {
+  DecodePlanHost p = {};
   p.units = units;
+  const int64_t cap = tune("RTP_TUNE_SPARSE_ITEMS", 2048);
   int64_t blocks128 = (int64_t)units * ((max_tok + 127) / 128);
-  int64_t tgt = blocks128 < 1 ? 1 : (blocks128 > 2048 ? 2048 : blocks128);
+  int64_t tgt = blocks128 < 1 ? 1 : (blocks128 > cap ? cap : blocks128);
   p.target_items = (int32_t)tgt;
   p.grid = (int32_t)tgt;
   // items <= total128 / ceil(total128 / target) + units <= target + units
-  p.ws_bytes = align_up((size_t)(tgt + units) * G * kPartStride * sizeof(float), 256);
+  p.ws_bytes = align_up((size_t)(tgt + units) * kPartStride * sizeof(float), 256);
+  return p;
+}
+
+// Local / dense: every unit has at most max_tok tokens, so the split is fixed on the host.
+static DecodePlanHost plan_host_range(int32_t units, int64_t max_tok, int32_t G) {
+  DecodePlanHost p = {};
+  p.units = units;
+  const int64_t cap = tune("RTP_TUNE_RANGE_ITEMS", 2048);
+  const int64_t blocks = (max_tok + 127) / 128;
+  int64_t ns = cap / units;
+  if (ns < 1) ns = 1;
+  if (ns > blocks) ns = blocks;
+  int64_t st = ((max_tok + ns - 1) / ns + 127) / 128 * 128;
+  ns = (max_tok + st - 1) / st;
+  p.split_tokens = (int32_t)st;
+  p.n_splits = (int32_t)ns;
+  p.grid = (int32_t)(units * ns);
+  p.ws_bytes = align_up((size_t)units * ns * G * kPartStride * sizeof(float), 256);
   return p;
 }
 
 template <int SRC>
 static int32_t launch_decode(const AttnDecodeArgs& a, int G, int grid, hipStream_t s, const char* who) {
-  const int cgrid = (a.units * G + 1) / 2;
+  const int cgrid = a.units * G;
 #define RTP_LAUNCH(GG, UU)                                                                          \
   hipLaunchKernelGGL((attn_decode_kernel<GG, SRC, UU>), dim3(grid), dim3(kAdThreads), 0, s, a);     \
   hipLaunchKernelGGL((attn_decode_combine_kernel<GG, SRC>), dim3(cgrid), dim3(kAdThreads), 0, s, a);
-  switch (G) {
-    case 1: RTP_LAUNCH(1, 8) break;
-    case 2: RTP_LAUNCH(2, 8) break;
-    case 4: RTP_LAUNCH(4, 8) break;
-    case 8: RTP_LAUNCH(8, 4) break;
-    default: return fail(RTP_ERR_UNSUPPORTED, "%s: group size %d", who, G);
+  if (SRC == kSrcSparse) {
+    RTP_LAUNCH(1, 8)
+  } else {
+    const int u4 = tune("RTP_TUNE_G4_U", 8);
+    switch (G) {
+      case 1: RTP_LAUNCH(1, 8) break;
+      case 2: RTP_LAUNCH(2, 8) break;
+      case 4: if (u4 == 4) { RTP_LAUNCH(4, 4) } else { RTP_LAUNCH(4, 8) } break;
+      case 8: RTP_LAUNCH(8, 4) break;
+      default: return fail(RTP_ERR_UNSUPPORTED, "%s: group size %d", who, G);
+    }
   }
 #undef RTP_LAUNCH
   return check_launch(who);
@@ -447,7 +518,7 @@ int32_t decode_range_attn(const char* who, bool dense, const rtp_layer_desc* L, 
   const int64_t units = (int64_t)B * L->n_kv_heads;
   if (units > kAdMaxUnits) return fail(RTP_ERR_UNSUPPORTED, "%s: B * n_kv_heads = %lld exceeds %d", who, (long long)units, kAdMaxUnits);
   const int64_t max_tok = dense ? max_ctx : (max_ctx < (int64_t)L->sink + L->window ? max_ctx : (int64_t)L->sink + L->window);
-  const DecodePlanHost p = plan_host((int32_t)units, max_tok, G);
+  const DecodePlanHost p = plan_host_range((int32_t)units, max_tok, G);
   if (!ws || ((uintptr_t)ws & 255) || ws_bytes < p.ws_bytes)
     return fail(RTP_ERR_WORKSPACE, "%s: workspace of %zu bytes (256-byte aligned) required, got %zu", who, p.ws_bytes, ws_bytes);
   clear_error();
@@ -455,7 +526,9 @@ int32_t decode_range_attn(const char* who, bool dense, const rtp_layer_desc* L, 
   AttnDecodeArgs a;
   fill_common(a, L, ht, q, K, V, row_stride, head_stride, seq_start, ctx_len, out, lse, ws);
   a.units = p.units;
-  a.target_items = p.target_items;
+  a.target_items = 0;
+  a.split_tokens = p.split_tokens;
+  a.n_splits = p.n_splits;
   return dense ? launch_decode<kSrcDense>(a, G, p.grid, s, who) : launch_decode<kSrcLocal>(a, G, p.grid, s, who);
 }
 
@@ -463,7 +536,7 @@ size_t decode_range_ws(bool dense, const rtp_layer_desc* L, int32_t B, int64_t m
   if (!L || B <= 0 || max_ctx <= 0 || L->n_kv_heads <= 0 || L->n_q_heads <= 0) return 0;
   const int G = L->n_q_heads / L->n_kv_heads;
   const int64_t max_tok = dense ? max_ctx : (max_ctx < (int64_t)L->sink + L->window ? max_ctx : (int64_t)L->sink + L->window);
-  return plan_host(B * L->n_kv_heads, max_tok, G).ws_bytes;
+  return plan_host_range(B * L->n_kv_heads, max_tok, G).ws_bytes;
 }
 
 }  // namespace rtp
@@ -472,7 +545,7 @@ using namespace rtp;
 
 extern "C" size_t rtp_sparse_attn_decode_workspace_bytes(const rtp_layer_desc* layer, int32_t B, int64_t max_sel) {
   if (!layer || B <= 0 || max_sel <= 0 || layer->n_ret <= 0) return 256;
-  return plan_host(B * layer->n_ret, max_sel, 1).ws_bytes;
+  return plan_host_sparse(B * layer->n_ret, max_sel).ws_bytes;
 }
 
 extern "C" int32_t rtp_sparse_attn_decode(const rtp_layer_desc* layer, const void* q,
@@ -493,7 +566,7 @@ extern "C" int32_t rtp_sparse_attn_decode(const rtp_layer_desc* layer, const voi
   const int64_t units = (int64_t)B * layer->n_ret;
   if (units > kAdMaxUnits) return fail(RTP_ERR_UNSUPPORTED, "%s: B * n_ret = %lld exceeds %d", who, (long long)units, kAdMaxUnits);
   if (layer->n_ret == 0) { clear_error(); return RTP_OK; }
-  const DecodePlanHost p = plan_host((int32_t)units, max_sel, 1);
+  const DecodePlanHost p = plan_host_sparse((int32_t)units, max_sel);
   if (!ws || ((uintptr_t)ws & 255) || ws_bytes < p.ws_bytes)
     return fail(RTP_ERR_WORKSPACE, "%s: workspace of %zu bytes (256-byte aligned) required, got %zu", who, p.ws_bytes, ws_bytes);
   clear_error();
@@ -504,5 +577,7 @@ extern "C" int32_t rtp_sparse_attn_decode(const rtp_layer_desc* layer, const voi
   a.sel_count = sel_count;
   a.units = p.units;
   a.target_items = p.target_items;
+  a.split_tokens = 0;
+  a.n_splits = 0;
   return launch_decode<kSrcSparse>(a, 1, p.grid, (hipStream_t)stream, who);
 }

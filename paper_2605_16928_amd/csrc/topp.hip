@@ -59,11 +59,22 @@ __device__ __forceinline__ int fixed_shift(int n) {
   return min(52, 62 - lg);
 }
 
-__device__ __forceinline__ uint64_t fixed_weight(float s, float smax, int shift) {
+// exp(s - smax) * 2^shift as an integer.  exp is evaluated in fp64 as 2^n * T[j] * P(t):
+// y = x * log2(e) = n + j/256 + f, T[j] = 2^(j/256) from an LDS table, P a degree-4 polynomial in
+// t = f * ln 2 < 2.8e-3 (truncation error ~1e-15 relative).
+__device__ __forceinline__ uint64_t fixed_weight(float s, float smax, int shift, const double* __restrict__ tab) {
   const double x = (double)s - (double)smax;         // exact
-  if (x < -60.0) return 0;                            // below 2^-86: under the fixed-point resolution
-  const double w = exp(x);
-  return (uint64_t)__double2ull_rn(ldexp(w, shift));
+  if (!(x >= -60.0)) return 0;                        // below 2^-86: under the fixed-point resolution
+  const double y = x * 1.4426950408889634;
+  const double n = floor(y);
+  const double f = y - n;                             // [0, 1)
+  const int j = min((int)(f * 256.0), 255);
+  const double t = (f - (double)j * 0.00390625) * 0.6931471805599453;
+  double pl = fma(t, 1.0 / 24.0, 1.0 / 6.0);
+  pl = fma(t, pl, 0.5);
+  pl = fma(t, pl, 1.0);
+  pl = fma(t, pl, 1.0);
+  return (uint64_t)__double2ull_rn(ldexp(tab[j] * pl, shift + (int)n));
 }
 
 // Block-wide maximum; result valid in every thread.
@@ -80,50 +91,76 @@ __device__ __forceinline__ float block_max(float v, float* red) {
   return v;
 }
 
-// Scans `nbins` fixed-point masses (global, written by an earlier launch) from the top and finds the
-// highest bin b with  above + sum_{i >= b} h[i] >= target.  Returns b and the new `above`
-// (mass strictly above bin b) and the mass of bin b itself.  All threads get the result.
-// If even the whole histogram does not reach the target (cannot happen for a consistent state)
-// bin 0 is returned.
-__device__ __forceinline__ void scan_from_top(const uint64_t* __restrict__ h, int nbins, uint64_t above,
-                                              uint64_t target, uint64_t* sh_part /*[256]*/, uint64_t* sh_res /*[3]*/,
-                                              int* bin, uint64_t* above_out, uint64_t* bin_mass) {
-  const int tid = threadIdx.x;
-  const int per = nbins / kTpThreads;                 // 8 or 4 consecutive bins per thread
-  uint64_t loc[8];
+struct ScanResult {
+  int bin;             // highest bin b with  above + sum_{i >= b} h[i] >= target
+  uint64_t above;      // mass strictly above bin b (including the incoming `above`)
+  uint64_t bin_mass;   // h[b]
+  uint64_t target;     // the target used
+  uint64_t total;      // sum of the whole histogram
+};
+
+// Scans NBINS fixed-point masses (global, written by an earlier launch) from the top.  With
+// derive_target the histogram is the level-1 one: its total is Z and the target becomes ceil(p * Z).
+// Every thread gets the result.  Two block barriers; wave-level suffix sums run on shuffles.
+template <int NBINS>
+__device__ __forceinline__ ScanResult scan_from_top(const uint64_t* __restrict__ h, uint64_t above, uint64_t target,
+                                                    bool derive_target, float p, uint64_t* sh_w /*[4]*/,
+                                                    uint64_t* sh_res /*[3]*/) {
+  constexpr int per = NBINS / kTpThreads;             // consecutive bins per thread
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  uint64_t loc[per];
   uint64_t sum = 0;
+#pragma unroll
   for (int i = 0; i < per; ++i) {
     loc[i] = h[tid * per + i];
     sum += loc[i];
   }
-  __syncthreads();
-  sh_part[tid] = sum;
-  if (tid == 0) { sh_res[0] = 0; sh_res[1] = above; sh_res[2] = h[0]; }
-  __syncthreads();
-  // inclusive suffix sums over the 256 partials (Hillis-Steele)
-  for (int o = 1; o < kTpThreads; o <<= 1) {
-    uint64_t add = (tid + o < kTpThreads) ? sh_part[tid + o] : 0;
-    __syncthreads();
-    sh_part[tid] += add;
-    __syncthreads();
+  uint64_t incl = sum;                                // suffix sum inside the wave (lanes >= lane)
+#pragma unroll
+  for (int o = 1; o < 64; o <<= 1) {
+    const uint64_t t = __shfl_down(incl, o);
+    if (lane + o < 64) incl += t;
   }
-  const uint64_t incl = sh_part[tid];                 // bins of threads >= tid
+  if (lane == 0) sh_w[wave] = incl;
+  if (tid == 0) { sh_res[0] = 0; sh_res[1] = above; sh_res[2] = loc[0]; }
+  __syncthreads();
+  uint64_t total = 0, after = 0;
+#pragma unroll
+  for (int w = 0; w < kTpThreads / 64; ++w) {
+    const uint64_t t = sh_w[w];
+    total += t;
+    if (w > wave) after += t;
+  }
+  if (derive_target) {
+    target = (uint64_t)__double2ull_rn(ceil((double)p * (double)total));
+    if (target > total) target = total;
+    if (target < 1) target = 1;
+  }
+  incl += after;                                      // bins of threads >= tid
   const uint64_t excl = incl - sum;                   // bins of threads > tid
   if (above + excl < target && above + incl >= target) {
     uint64_t run = above + excl;
     int b = per - 1;
-    for (; b > 0; --b) {
-      if (run + loc[b] >= target) break;
-      run += loc[b];
+#pragma unroll
+    for (int i = per - 1; i > 0; --i) {
+      if (b == i && run + loc[i] < target) { run += loc[i]; b = i - 1; }
     }
+    uint64_t lb = loc[0];
+#pragma unroll
+    for (int i = 1; i < per; ++i) if (b == i) lb = loc[i];
     sh_res[0] = (uint64_t)(tid * per + b);
     sh_res[1] = run;
-    sh_res[2] = loc[b];
+    sh_res[2] = lb;
   }
   __syncthreads();
-  *bin = (int)sh_res[0];
-  *above_out = sh_res[1];
-  *bin_mass = sh_res[2];
+  ScanResult r;
+  r.bin = (int)sh_res[0];
+  r.above = sh_res[1];
+  r.bin_mass = sh_res[2];
+  r.target = target;
+  r.total = total;
+  __syncthreads();                                    // sh_w / sh_res may be reused by the caller
+  return r;
 }
 
 // ---- launch 0: per-chunk maxima, zero the histograms and counters --------------------------------
@@ -165,9 +202,11 @@ __global__ __launch_bounds__(kTpThreads) void topp_level_kernel(const TopPArgs a
   if (n0 >= n || n <= 0) return;
 
   __shared__ uint64_t lh[kBins];
-  __shared__ uint64_t sh_part[kTpThreads];
+  __shared__ uint64_t sh_part[kTpThreads / 64];
   __shared__ uint64_t sh_res[3];
   __shared__ float red[kTpThreads / 64];
+  __shared__ double tab[256];
+  tab[tid] = exp2((double)tid * 0.00390625);
   uint64_t* hrow = a.hist + (int64_t)r * kBinsTotal;
   RowState* st = a.state + (int64_t)r * 4;
 
@@ -196,30 +235,12 @@ __global__ __launch_bounds__(kTpThreads) void topp_level_kernel(const TopPArgs a
     flags = prev.flags;
     uint64_t above = prev.above, target = prev.target, total = prev.total;
     if (flags == 0) {
-      if (LEVEL == 2) {
-        // Z = whole level-1 histogram; target = ceil(p * Z)
-        uint64_t sum = 0;
-        for (int i = tid; i < kBins1; i += kTpThreads) sum += hrow[i];
-        sh_part[tid] = sum;
-        __syncthreads();
-        for (int o = kTpThreads / 2; o > 0; o >>= 1) {
-          if (tid < o) sh_part[tid] += sh_part[tid + o];
-          __syncthreads();
-        }
-        total = sh_part[0];
-        __syncthreads();
-        const double want = ceil((double)a.p[r] * (double)total);
-        target = (uint64_t)__double2ull_rn(want);
-        if (target > total) target = total;
-        if (target < 1) target = 1;
-        above = 0;
-      }
-      int bin;
-      uint64_t new_above, bin_mass;
       const uint64_t* hprev = hrow + (LEVEL == 2 ? 0 : kBins1);
-      scan_from_top(hprev, LEVEL == 2 ? kBins1 : kBins2, above, target, sh_part, sh_res, &bin, &new_above, &bin_mass);
-      prefix = (prev.prefix << 11) | (uint32_t)bin;
-      above = new_above;
+      const ScanResult sr = scan_from_top<(LEVEL == 2 ? kBins1 : kBins2)>(hprev, LEVEL == 2 ? 0 : above, target,
+                                                                         LEVEL == 2, a.p[r], sh_part, sh_res);
+      if (LEVEL == 2) { target = sr.target; total = sr.total; }
+      prefix = (prev.prefix << 11) | (uint32_t)sr.bin;
+      above = sr.above;
     }
     if (c == 0 && tid == 0) {
       RowState s;
@@ -249,7 +270,7 @@ __global__ __launch_bounds__(kTpThreads) void topp_level_kernel(const TopPArgs a
         if (LEVEL == 1) mine = true;
         else mine = (key >> (kShift + (LEVEL == 2 ? 11 : 10))) == prefix;
         if (mine) {
-          const uint64_t w = fixed_weight(s4[k], smax, shift);
+          const uint64_t w = fixed_weight(s4[k], smax, shift, tab);
           if (w) atomicAdd((unsigned long long*)&lh[(key >> kShift) & (kBins - 1)], (unsigned long long)w);
         }
       }
@@ -299,7 +320,7 @@ __global__ __launch_bounds__(kTpThreads) void topp_count_kernel(const TopPArgs a
     return;
   }
   if (n0 >= n) return;
-  __shared__ uint64_t sh_part[kTpThreads];
+  __shared__ uint64_t sh_part[kTpThreads / 64];
   __shared__ uint64_t sh_res[3];
   __shared__ int sh_cnt[kTpThreads / 64];
   const uint64_t* hrow = a.hist + (int64_t)r * kBinsTotal;
@@ -316,13 +337,12 @@ __global__ __launch_bounds__(kTpThreads) void topp_count_kernel(const TopPArgs a
     }
     return;
   } else if (prev.flags == 0) {
-    int bin;
-    uint64_t above, bin_mass;
-    scan_from_top(hrow + kBins1 + kBins2, kBins3, prev.above, prev.target, sh_part, sh_res, &bin, &above, &bin_mass);
-    tkey = (prev.prefix << 10) | (uint32_t)bin;
+    const ScanResult sr = scan_from_top<kBins3>(hrow + kBins1 + kBins2, prev.above, prev.target, false, 0.f,
+                                                sh_part, sh_res);
+    tkey = (prev.prefix << 10) | (uint32_t)sr.bin;
     if (c == 0 && tid == 0) {
       if (a.tau) a.tau[r] = key_float(tkey);
-      if (a.mass) a.mass[r] = (float)((double)(above + bin_mass) / (double)prev.total);
+      if (a.mass) a.mass[r] = (float)((double)(sr.above + sr.bin_mass) / (double)prev.total);
     }
   } else if (c == 0 && tid == 0) {
     if (a.tau) a.tau[r] = -__builtin_huge_valf();

@@ -97,6 +97,21 @@ class DecodeRun:
         self.sparse_attn()
         self.local_attn()
 
+    def step_two_streams(self, side: "torch.cuda.Stream"):
+        """The same step with the local heads on a second stream: they do not depend on the
+        indexer / top-p chain and write disjoint output rows."""
+        main = torch.cuda.current_stream()
+        fork, join = torch.cuda.Event(), torch.cuda.Event()
+        fork.record(main)
+        side.wait_event(fork)
+        with torch.cuda.stream(side):
+            self.local_attn()
+            join.record(side)
+        self.index_score()
+        self.topp()
+        self.sparse_attn()
+        main.wait_event(join)
+
     # ---- results as numpy -----------------------------------------------------------------
     def sel_sets(self):
         torch.cuda.synchronize()
