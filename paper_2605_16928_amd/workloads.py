@@ -256,3 +256,117 @@ def bf16_bits(t: torch.Tensor):
     """bf16 tensor -> numpy uint16 array of its bit patterns (a copy on the host)."""
     import numpy as np
     return t.detach().contiguous().view(torch.int16).cpu().numpy().view(np.uint16)
+
+
+# ---------------------------------------------------------------------------
+# prefill workloads (one sequence, one chunk of queries)
+# ---------------------------------------------------------------------------
+@dataclass
+class PrefillWorkload:
+    name: str
+    layer: Layer
+    N: int                          # cached tokens, the chunk's own tokens included (= chunk_start + T)
+    chunk_start: int
+    T: int
+    p: float
+    q: torch.Tensor                 # bf16 [T, Hq, D]      post-RoPE queries of the chunk
+    K: torch.Tensor                 # bf16 [Hkv, N, D]
+    V: torch.Tensor                 # bf16 [Hkv, N, D]
+    kI: torch.Tensor                # bf16 [n_ret, N, r]
+    qI: Optional[torch.Tensor] = None      # bf16 [n_ret, T, r]
+    WQ: Optional[torch.Tensor] = None      # fp32 [n_ret, r, D]
+    q_pre: Optional[torch.Tensor] = None   # bf16 [T, Hq, D]
+    cluster_start: Optional[torch.Tensor] = None
+    cluster_size: Optional[torch.Tensor] = None
+
+
+def make_prefill(name: str, layer: Layer, chunk_start: int, T: int, p: float, seed: int, device="cpu", *,
+                 index_mode: str = "direct", tokens_per_cluster: int = 1024, cluster_len=32,
+                 own_frac: float = 0.8, q_noise: float = 0.3, zipf: float = 0.0, max_cluster: int = 4096,
+                 ) -> PrefillWorkload:
+    """One causal prefill chunk: queries at positions chunk_start .. chunk_start+T-1 of a sequence
+    whose first chunk_start+T tokens are cached.
+
+    Index side ("direct"): N / tokens_per_cluster planted clusters, each a run of consecutive tokens
+    (length cluster_len, or Zipf(zipf)-distributed in [1, max_cluster]) whose index keys are
+    a * u_c + N(0, sb^2 I) for a random unit direction u_c; background keys are N(0, sb^2 I).  Query m
+    picks one cluster that starts before m (probability proportional to its size) and gets
+    qI = g * u_c + N(0, q_noise^2 I).  g = a and sb are set so that background scores have unit
+    variance and the own cluster holds about own_frac of the indexer mass at the full context; the
+    other clusters (random directions, cosine std 1/4) supply the tail.
+    "proj": fp32 projections and pre-RoPE queries, index keys plain N(0, I) (no planted structure).
+    """
+    dev = torch.device(device)
+    g = _gen(seed, dev)
+    Hq, Hkv, D, r, n_ret = layer.n_q_heads, layer.n_kv_heads, layer.head_dim, layer.index_dim, layer.n_ret
+    N = int(chunk_start) + int(T)
+    K = _randn_bf16((Hkv, N, D), g, dev)
+    V = _randn_bf16((Hkv, N, D), g, dev)
+    q = _randn_bf16((T, Hq, D), g, dev)
+    WQ = q_pre = qI = cstart = csize = None
+    if index_mode == "proj":
+        WQ = torch.randn((n_ret, r, D), generator=g, device=dev, dtype=torch.float32) * (D ** -0.5)
+        q_pre = _randn_bf16((T, Hq, D), g, dev)
+        kI = _randn_bf16((n_ret, N, r), g, dev, std=0.6)
+    else:
+        n_cl = max(1, N // tokens_per_cluster)
+        if zipf > 0.0:
+            ranks = torch.arange(1, max_cluster + 1, device=dev, dtype=torch.float64)
+            pmf = ranks ** (-zipf)
+            csize = torch.multinomial((pmf / pmf.sum()).float(), n_cl, replacement=True, generator=g) + 1
+        else:
+            csize = torch.full((n_cl,), int(cluster_len), device=dev, dtype=torch.long)
+        csize = csize.clamp(max=max(1, N // 2))
+        cstart = (torch.rand((n_cl,), generator=g, device=dev) * (N - csize).clamp(min=1).float()).long()
+        mean_len = float(csize.float().mean())
+        ga = math.log(own_frac / (1.0 - own_frac) * N * math.exp(0.5) / max(mean_len, 1.0))
+        a_lvl = math.sqrt(max(ga, 1.0))
+        sb = 1.0 / math.sqrt(a_lvl * a_lvl + r * q_noise * q_noise)
+        kI = torch.empty((n_ret, N, r), dtype=torch.bfloat16, device=dev)
+        qI = torch.empty((n_ret, T, r), dtype=torch.bfloat16, device=dev)
+        pos = chunk_start + torch.arange(T, device=dev)
+        for j in range(n_ret):
+            u = _unit(torch.randn((n_cl, r), generator=g, device=dev, dtype=torch.float32))
+            rows = torch.randn((N, r), generator=g, device=dev, dtype=torch.float32) * sb
+            # cluster membership: later clusters overwrite earlier ones where runs overlap
+            owner = torch.full((N,), -1, device=dev, dtype=torch.long)
+            for cidx in range(n_cl):
+                s0, ln = int(cstart[cidx]), int(csize[cidx])
+                owner[s0:s0 + ln] = cidx
+            member = owner >= 0
+            rows[member] += a_lvl * u[owner[member]]
+            kI[j] = rows.to(torch.bfloat16)
+            # each query picks a cluster that starts before it (weight = size); none -> cluster 0
+            w = csize.float()[None, :] * (cstart[None, :] < pos[:, None]).float()
+            w[:, 0] += 1e-6
+            pick = torch.multinomial(w, 1, generator=g).squeeze(1)
+            qq = a_lvl * u[pick] + q_noise * torch.randn((T, r), generator=g, device=dev, dtype=torch.float32)
+            qI[j] = qq.to(torch.bfloat16)
+    return PrefillWorkload(name=name, layer=layer, N=N, chunk_start=int(chunk_start), T=int(T), p=float(p),
+                           q=q, K=K, V=V, kI=kI, qI=qI, WQ=WQ, q_pre=q_pre, cluster_start=cstart,
+                           cluster_size=csize)
+
+
+def c3_chunk(device="cpu", seed: int = 2, chunk: int = 31, N_total: int = 131072, T: int = 4096,
+             p: float = 0.9) -> PrefillWorkload:
+    """Chunked prefill, configuration 3: one 4096-query chunk of a 131072-token sequence (chunk index
+    0..31; the last one sees the whole context), 32 query / 8 KV heads, 4 retrieval heads, clusters of
+    32 relevant tokens, top-p 0.9, local heads 4 sink + 2048 window."""
+    layer = Layer(32, 8, [0, 8, 16, 24], sink=4, window=2048)
+    return make_prefill("c3", layer, chunk * T, T, p, seed, device, cluster_len=32)
+
+
+def c4_chunk(device="cpu", seed: int = 3, chunk: int = 127, T: int = 8192, p: float = 0.9) -> PrefillWorkload:
+    """Configuration 4: one 8192-query chunk of a 1,048,576-token prefill (chunk index 0..127),
+    4 retrieval heads over the full cache, local heads 4 sink + 4096 window, cluster sizes
+    Zipf(1.1) in [1, 4096]."""
+    layer = Layer(32, 8, [0, 8, 16, 24], sink=4, window=4096)
+    return make_prefill("c4", layer, chunk * T, T, p, seed, device, zipf=1.1)
+
+
+def small_prefill(device="cpu", seed: int = 41, chunk_start: int = 700, T: int = 200, p: float = 0.9, *,
+                  n_q_heads=8, n_kv_heads=2, ret_heads=(0, 5), sink=4, window=160, index_mode="direct",
+                  tokens_per_cluster=128, cluster_len=8, zipf=0.0) -> PrefillWorkload:
+    layer = Layer(n_q_heads, n_kv_heads, list(ret_heads), sink=sink, window=window)
+    return make_prefill("small_prefill", layer, chunk_start, T, p, seed, device, index_mode=index_mode,
+                        tokens_per_cluster=tokens_per_cluster, cluster_len=cluster_len, zipf=zipf, max_cluster=64)

@@ -1,0 +1,111 @@
+"""GPU parity of the prefill path (MFMA tiles): local sink+window attention, the dense comparison,
+and the retrieval heads' chunk kernel, against the CPU oracle row by row."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import rtp_oracle as orc
+from paper_2605_16928_amd import rtp, workloads as wl
+from gpu_util import DEV, PrefillRun, prefill_oracle_inputs, check_out, i32, i64, layer_desc_of, ws_alloc
+
+pytestmark = pytest.mark.gpu
+
+
+def _cases():
+    return {
+        # two query tiles with a ragged tail, band crossing several key tiles, sinks outside the band
+        "small": dict(),
+        # first chunk of a sequence: queries below the sink count, below one key tile
+        "first_chunk": dict(chunk_start=0, T=130, seed=42),
+        # window narrower than a key tile, no sinks
+        "narrow": dict(chunk_start=300, T=100, sink=0, window=30, seed=43),
+        # more sinks than one key tile holds
+        "many_sinks": dict(chunk_start=900, T=64, sink=70, window=100, seed=44),
+        # window wider than the context: local == dense
+        "wide": dict(chunk_start=200, T=129, sink=4, window=4096, seed=45),
+        # group sizes 1 and 8
+        "g1": dict(n_q_heads=4, n_kv_heads=4, ret_heads=(2,), chunk_start=257, T=65, seed=46),
+        "g8": dict(n_q_heads=16, n_kv_heads=2, ret_heads=(0, 8), chunk_start=1000, T=96, seed=47),
+        # a single query
+        "one_query": dict(chunk_start=333, T=1, seed=48),
+    }
+
+
+@pytest.mark.parametrize("name", list(_cases()))
+def test_prefill_local_dense_and_retrieval_p1(name):
+    print(f"[case] prefill {name}", flush=True)
+    w = wl.small_prefill(DEV, **_cases()[name])
+    L = w.layer
+    run = PrefillRun(w)
+    oi = prefill_oracle_inputs(w)
+    rows = [(t, h) for t in range(w.T) for h in range(L.n_q_heads)]
+
+    # local heads + retrieval heads with p = 1 (the paper's prefill rule) fill the whole output
+    run.out.fill_(9.0)
+    run.local_attn()
+    run.sparse_prefill(p=1.0)
+    torch.cuda.synchronize()
+    out = run.out.float().cpu().numpy().astype(np.float64)
+    lse = run.lse.cpu().numpy()
+    ref = orc.prefill_rows(rows=rows, p=1.0, **oi)
+    o_ref = np.zeros_like(out)
+    l_ref = np.zeros_like(lse)
+    for r in ref:
+        o_ref[r["t"], r["h"]] = r["out"]
+        l_ref[r["t"], r["h"]] = r["lse"]
+    check_out(out, o_ref, f"{name} local + retrieval(p=1)", tight="mfma")
+    assert np.allclose(lse, l_ref, atol=3e-3, rtol=0)
+
+    # dense comparison over all heads
+    dout = torch.zeros_like(run.out)
+    dlse = torch.zeros_like(run.lse)
+    run.dense_attn(dout, dlse)
+    torch.cuda.synchronize()
+    dref = orc.dense_rows(rows=rows, q_bits=oi["q_bits"], K_bits=oi["K_bits"], V_bits=oi["V_bits"],
+                          chunk_start=w.chunk_start, n_q_heads=L.n_q_heads, n_kv_heads=L.n_kv_heads)
+    o_ref = np.zeros_like(out)
+    for r in dref:
+        o_ref[r["t"], r["h"]] = r["out"]
+    check_out(dout.float().cpu().numpy().astype(np.float64), o_ref, f"{name} dense", tight="mfma")
+
+
+def test_prefill_two_sequences_and_interleaved_kv():
+    """B = 2 packed sequences with different chunk positions; K|V interleaved rows."""
+    print("[case] prefill two sequences / interleaved", flush=True)
+    d = wl.small_decode(DEV, seed=51, ctx=(900, 1300), sink=4, window=200, n_planted=0)
+    L = d.layer
+    n_q = 70
+    g = torch.Generator(device=DEV)
+    g.manual_seed(5)
+    q = torch.randn((2, n_q, L.n_q_heads, 128), generator=g, device=DEV).to(torch.bfloat16)
+    q_start = [900 - n_q, 1300 - n_q - 37]
+    desc = layer_desc_of(L)
+    out = torch.zeros((2, n_q, L.n_q_heads, 128), dtype=torch.bfloat16, device=DEV)
+    dout = torch.zeros_like(out)
+    ws = ws_alloc(rtp.rtp_local_attn_workspace_bytes(desc, 2, n_q, 1300))
+    kv = torch.cat([d.K, d.V], dim=2).contiguous()
+    T = d.T_tot
+    rtp.rtp_local_attn(desc, q, kv.data_ptr(), kv.data_ptr() + 256, 256, T * 256, i64(d.seq_start), i32(d.ctx_len),
+                       i32(q_start), 2, n_q, 1300, out, None, ws)
+    rtp.rtp_dense_attn(desc, q, d.K, d.V, 128, T * 128, i64(d.seq_start), i32(d.ctx_len), i32(q_start), 2, n_q, 1300,
+                       dout, None, ws)
+    torch.cuda.synchronize()
+    Kb, Vb, qb = wl.bf16_bits(d.K), wl.bf16_bits(d.V), wl.bf16_bits(q)
+    local_heads = [h for h in range(L.n_q_heads) if h not in L.ret_heads]
+    for b in range(2):
+        s0, n = d.seq_start[b], d.ctx_len[b]
+        common = dict(q_bits=qb[b], K_bits=Kb[:, s0:s0 + n], V_bits=Vb[:, s0:s0 + n], chunk_start=q_start[b],
+                      n_q_heads=L.n_q_heads, n_kv_heads=L.n_kv_heads)
+        rows = [(t, h) for t in range(n_q) for h in local_heads]
+        ref = orc.prefill_rows(rows=rows, kI_bits=None, ret_heads=L.ret_heads, sink=L.sink, window=L.window, p=1.0,
+                               **common)
+        got = out[b].float().cpu().numpy().astype(np.float64)
+        for r in ref:
+            check_out(got[r["t"], r["h"]], r["out"], f"local b{b} t{r['t']} h{r['h']}", tight="mfma")
+        for h in L.ret_heads:
+            assert np.all(got[:, h] == 0)                       # retrieval rows untouched by the local call
+        rows = [(t, h) for t in range(n_q) for h in range(L.n_q_heads)]
+        dref = orc.dense_rows(rows=rows, **common)
+        dgot = dout[b].float().cpu().numpy().astype(np.float64)
+        for r in dref:
+            check_out(dgot[r["t"], r["h"]], r["out"], f"dense b{b} t{r['t']} h{r['h']}", tight="mfma")
