@@ -185,12 +185,12 @@ def check_out(o_gpu: np.ndarray, o_ref: np.ndarray, what="", tight=True):
     """The stated bar is 2e-2 absolute + 1e-2 relative.  `tight` additionally holds the kernels to
     what their arithmetic should give: True = fp32 accumulation + one bf16 rounding of the output
     (1e-3 + 2^-8*|ref|, the decode kernels); "mfma" = probabilities also rounded to bf16 before the
-    PV product (3e-3 + 2^-7*|ref|, the prefill kernels)."""
+    PV product (6e-3 + 2^-7*|ref|, the prefill kernels)."""
     err = np.abs(o_gpu - o_ref)
     tol = OUT_ATOL + OUT_RTOL * np.abs(o_ref)
     assert (err <= tol).all(), f"{what}: max abs err {err.max()} (tolerance 2e-2 + 1e-2*|ref|)"
     if tight:
-        tol = (3e-3 + 2.0 ** -7 * np.abs(o_ref)) if tight == "mfma" else (1e-3 + 2.0 ** -8 * np.abs(o_ref))
+        tol = (6e-3 + 2.0 ** -7 * np.abs(o_ref)) if tight == "mfma" else (1e-3 + 2.0 ** -8 * np.abs(o_ref))
         assert (err <= tol).all(), f"{what}: max abs err {err.max()} exceeds the rounding budget"
     return float(err.max())
 

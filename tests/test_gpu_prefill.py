@@ -109,3 +109,96 @@ def test_prefill_two_sequences_and_interleaved_kv():
         dgot = dout[b].float().cpu().numpy().astype(np.float64)
         for r in dref:
             check_out(dgot[r["t"], r["h"]], r["out"], f"dense b{b} t{r['t']} h{r['h']}", tight="mfma")
+
+
+# ---------------------------------------------------------------------------------------------
+# per-query top-p in prefill (p < 1)
+# ---------------------------------------------------------------------------------------------
+FINE = 2.0 ** -17           # threshold resolution of the prefill selector (score units)
+BAND = 3e-5                 # fp32 rounding of (max - score) and of the MFMA index scores
+
+
+def _sparse_cases():
+    return {
+        "small_p90": (dict(), 0.9),
+        "small_p50": (dict(seed=61), 0.5),
+        "small_p999": (dict(seed=62), 0.999),
+        "first_chunk": (dict(chunk_start=0, T=150, seed=63), 0.9),
+        "proj": (dict(index_mode="proj", chunk_start=500, T=70, seed=64), 0.8),
+        "zipf_g8": (dict(n_q_heads=16, n_kv_heads=2, ret_heads=(0, 8), chunk_start=1800, T=96, seed=65, zipf=1.1), 0.9),
+        "p_to_one": (dict(chunk_start=300, T=40, seed=66), 0.9999999),
+    }
+
+
+@pytest.mark.parametrize("name", list(_sparse_cases()))
+def test_sparse_prefill_matches_oracle(name):
+    print(f"[case] sparse prefill {name}", flush=True)
+    kw, p = _sparse_cases()[name]
+    w = wl.small_prefill(DEV, p=p, **kw)
+    L = w.layer
+    run = PrefillRun(w)
+    oi = prefill_oracle_inputs(w)
+    run.out.fill_(5.0)
+    run.sparse_prefill()
+    torch.cuda.synchronize()
+    out = run.out.float().cpu().numpy().astype(np.float64)
+    tau, cnt, mass = run.tau.cpu().numpy(), run.count.cpu().numpy(), run.mass.cpu().numpy()
+    p32 = float(np.float32(p))
+    rows = [(t, h) for t in range(w.T) for h in L.ret_heads]
+    ref = orc.prefill_rows(rows=rows, p=p32, **oi)
+    sc = 1.0 / np.sqrt(128.0)
+    worst = 0.0
+    for r in ref:
+        t, h, m = r["t"], r["h"], r["m"]
+        j = L.ret_heads.index(h)
+        s = r["scores"]
+        wgt = np.exp(s - s.max())
+        Z = wgt.sum()
+        tg = float(tau[j, t])
+        # (a) the kept set reaches p, and the threshold is never above the exact one
+        keep = s > tg
+        amb = np.abs(s - tg) <= BAND
+        assert tg <= r["sel"]["tau"] + BAND, f"{name} t{t} h{h}: threshold {tg} above the exact {r['sel']['tau']}"
+        assert wgt[keep | amb].sum() / Z >= p32 - 1e-6, f"{name} t{t} h{h}: kept mass below p"
+        # (b) ... and not lower than one fine bin (plus the 1e-4 safety inflation of the target)
+        if np.isfinite(tg):
+            above = s > tg + FINE + BAND
+            assert wgt[above].sum() / Z < p32 + 1e-6, \
+                f"{name} t{t} h{h}: threshold {tg} is more than one fine bin below the exact one"
+        # (c) statistics
+        assert abs(int(cnt[j, t]) - int(keep.sum())) <= int(amb.sum()), f"{name} t{t} h{h}: count {cnt[j, t]} vs {keep.sum()}"
+        assert abs(mass[j, t] - wgt[keep].sum() / Z) <= 1e-5 + wgt[amb].sum() / Z
+        # (d) attention over exactly the set the library says it kept
+        kvh = h // (L.n_q_heads // L.n_kv_heads)
+        o, _ = orc.attend(oi["q_bits"][t, h], oi["K_bits"][kvh, :m + 1], oi["V_bits"][kvh, :m + 1], np.nonzero(keep)[0], sc)
+        worst = max(worst, check_out(out[t, h], o, f"{name} t{t} h{h} (same set)", tight=False if amb.any() else "mfma"))
+        # (e) end to end against the exact top-p set: the stated tolerance.  Tokens within 1e-5 of the
+        # exact threshold may legitimately differ; rows that have such a token are only held to (d).
+        near = np.abs(s - r["sel"]["tau"]) <= 1e-5 * max(1.0, abs(r["sel"]["tau"]))
+        if near.sum() <= 1:
+            assert np.array_equal(np.nonzero(keep)[0], np.sort(r["sel"]["idx"])), f"{name} t{t} h{h}: set differs"
+            check_out(out[t, h], r["out"], f"{name} t{t} h{h} (exact top-p)", tight=False)
+    for h in range(L.n_q_heads):
+        if h not in L.ret_heads:
+            assert np.all(out[:, h] == 5.0)
+    print(f"   worst abs err vs same-set oracle {worst:.2e}; kept tokens min/mean/max "
+          f"{cnt.min()}/{cnt.mean():.1f}/{cnt.max()}", flush=True)
+
+
+def test_sparse_prefill_p1_statistics_and_dense_equivalence():
+    """p = 1 with statistics requested runs the selecting kernel with nothing to select:
+    same output as the dense path, count = m + 1, mass = 1."""
+    print("[case] sparse prefill p=1 statistics", flush=True)
+    w = wl.small_prefill(DEV, seed=71, chunk_start=260, T=90)
+    run = PrefillRun(w)
+    L = w.layer
+    run.sparse_prefill(p=1.0)
+    torch.cuda.synchronize()
+    a = run.out.clone()
+    cnt = run.count.cpu().numpy()
+    assert np.array_equal(cnt, np.tile(w.chunk_start + np.arange(w.T) + 1, (L.n_ret, 1)))
+    assert np.all(run.mass.cpu().numpy() == 1.0)
+    dout = torch.zeros_like(run.out)
+    run.dense_attn(dout)
+    torch.cuda.synchronize()
+    assert torch.equal(a[:, L.ret_heads], dout[:, L.ret_heads])
