@@ -1,0 +1,183 @@
+"""Parity at the full sizes of the baseline configurations, in the launch configuration the benchmark
+times.  Decode rows are cheap for the oracle, so every retrieval row is checked; prefill checks a
+sample of (query, head) rows that includes the chunk edges (rows are independent, so sampling is sound).
+"""
+import numpy as np
+import pytest
+import torch
+
+from oracle import rtp_oracle as orc
+from paper_2605_16928_amd import rtp, workloads as wl
+from gpu_util import (DEV, DecodeRun, PrefillRun, check_scores, check_selection, check_selection_valid, check_out)
+
+pytestmark = pytest.mark.gpu
+SC = 1.0 / np.sqrt(128.0)
+
+
+def _decode_fullsize(w, n_local_samples=24, n_dense_samples=2, seed=0):
+    L = w.layer
+    G = L.n_q_heads // L.n_kv_heads
+    run = DecodeRun(w)
+    side = torch.cuda.Stream()
+    run.step_two_streams(side)
+    torch.cuda.synchronize()
+    s_gpu = run.scores.cpu().numpy()
+    sets, cnt = run.sel_sets()
+    out = run.out_f64()
+    kI, qI = wl.bf16_bits(w.kI), wl.bf16_bits(w.qI)
+    qb = wl.bf16_bits(w.q)
+    rng = np.random.default_rng(seed)
+    sizes = []
+
+    def kv_slice(kvh, t0, ids):
+        ids_t = torch.as_tensor(np.asarray(ids) + t0, device=DEV)
+        return wl.bf16_bits(w.K[kvh].index_select(0, ids_t)), wl.bf16_bits(w.V[kvh].index_select(0, ids_t))
+
+    for b in range(w.B):
+        t0, n = w.seq_start[b], w.ctx_len[b]
+        for j, h in enumerate(L.ret_heads):
+            r = b * L.n_ret + j
+            p = float(w.p_rows[r])
+            s_ref = orc.index_score(qI[b, j], kI[j, t0:t0 + n])
+            check_scores(s_gpu[r, :n], s_ref, qI[b, j], kI[j, t0:t0 + n], f"row {r}")
+            s64 = s_gpu[r, :n].astype(np.float64)
+            check_selection(sets[r], s64, orc.topp_select(s64, p), p, f"row {r} (same scores)")
+            check_selection_valid(sets[r], s_ref, p, float(np.abs(s64 - s_ref).max()), f"row {r} (end to end)")
+            Ks, Vs = kv_slice(h // G, t0, sets[r])
+            o, _ = orc.attend(qb[b, h], Ks, Vs, np.arange(len(sets[r])), SC)
+            check_out(out[b, h], o, f"sparse b{b} h{h}")
+            sizes.append(len(sets[r]))
+    local_heads = [h for h in range(L.n_q_heads) if h not in L.ret_heads]
+    for _ in range(n_local_samples):
+        b = int(rng.integers(w.B))
+        h = int(rng.choice(local_heads))
+        ids = orc.local_set(w.ctx_len[b] - 1, L.sink, L.window)
+        Ks, Vs = kv_slice(h // G, w.seq_start[b], ids)
+        o, _ = orc.attend(qb[b, h], Ks, Vs, np.arange(len(ids)), SC)
+        check_out(out[b, h], o, f"local b{b} h{h}")
+    dout = torch.zeros_like(run.out)
+    run.dense_attn(dout)
+    torch.cuda.synchronize()
+    dgot = dout.float().cpu().numpy().astype(np.float64)
+    for _ in range(n_dense_samples):
+        b = int(rng.integers(w.B))
+        h = int(rng.integers(L.n_q_heads))
+        t0, n = w.seq_start[b], w.ctx_len[b]
+        o, _ = orc.attend(qb[b, h], wl.bf16_bits(w.K[h // G, t0:t0 + n]), wl.bf16_bits(w.V[h // G, t0:t0 + n]),
+                          np.arange(n), SC)
+        check_out(dgot[b, h], o, f"dense b{b} h{h}")
+    return sizes
+
+
+@pytest.mark.parametrize("p", [0.8, 0.9, 0.95])
+def test_c2_full_size(p):
+    print(f"[case] c2 full size p={p}", flush=True)
+    sizes = _decode_fullsize(wl.c2(DEV, p=p))
+    print(f"   selected tokens per row: min {min(sizes)} mean {np.mean(sizes):.0f} max {max(sizes)}", flush=True)
+    assert len(sizes) == 32
+
+
+def test_c5_full_size():
+    print("[case] c5 full size (ragged batch of 32, 64 query heads)", flush=True)
+    w = wl.c5(DEV)
+    sizes = _decode_fullsize(w, n_local_samples=16, n_dense_samples=1)
+    print(f"   selected tokens per row: min {min(sizes)} mean {np.mean(sizes):.0f} max {max(sizes)}", flush=True)
+    assert max(sizes) >= 100 * max(min(sizes), 1)          # the recipe spans two orders of magnitude
+
+
+def test_c4_decode_full_size():
+    print("[case] decode at 1,048,576 tokens", flush=True)
+    sizes = _decode_fullsize(wl.c4_decode(DEV), n_local_samples=8, n_dense_samples=1)
+    print(f"   selected tokens per row: {sizes}", flush=True)
+
+
+def _prefill_fullsize(w, rows_local, rows_ret, rows_dense, what):
+    L = w.layer
+    G = L.n_q_heads // L.n_kv_heads
+    run = PrefillRun(w)
+    run.local_attn()
+    run.sparse_prefill()
+    torch.cuda.synchronize()
+    out = run.out.float().cpu().numpy().astype(np.float64)
+    tau, cnt = run.tau.cpu().numpy(), run.count.cpu().numpy()
+    qb, kI, qI = wl.bf16_bits(w.q), wl.bf16_bits(w.kI), wl.bf16_bits(w.qI)
+    p32 = float(np.float32(w.p))
+
+    def kv_rows(kvh, ids):
+        ids_t = torch.as_tensor(np.asarray(ids), device=DEV)
+        return wl.bf16_bits(w.K[kvh].index_select(0, ids_t)), wl.bf16_bits(w.V[kvh].index_select(0, ids_t))
+
+    for (t, h) in rows_local:
+        m = w.chunk_start + t
+        ids = orc.local_set(m, L.sink, L.window)
+        Ks, Vs = kv_rows(h // G, ids)
+        o, _ = orc.attend(qb[t, h], Ks, Vs, np.arange(len(ids)), SC)
+        check_out(out[t, h], o, f"{what} local t{t} h{h}", tight="mfma")
+    kept = []
+    for (t, h) in rows_ret:
+        m = w.chunk_start + t
+        j = L.ret_heads.index(h)
+        s = orc.index_score(qI[j, t], kI[j, :m + 1])
+        ref = orc.topp_select(s, p32)
+        tg = float(tau[j, t])
+        keep = s > tg
+        amb = np.abs(s - tg) <= 3e-5
+        wgt = np.exp(s - s.max())
+        Z = wgt.sum()
+        assert tg <= ref["tau"] + 3e-5 and wgt[keep | amb].sum() / Z >= p32 - 1e-6
+        assert wgt[s > tg + 2.0 ** -17 + 3e-5].sum() / Z < p32 + 1e-6
+        assert abs(int(cnt[j, t]) - int(keep.sum())) <= int(amb.sum())
+        ids = np.nonzero(keep)[0]
+        Ks, Vs = kv_rows(h // G, ids)
+        o, _ = orc.attend(qb[t, h], Ks, Vs, np.arange(len(ids)), SC)
+        check_out(out[t, h], o, f"{what} sparse t{t} h{h}", tight=False if amb.any() else "mfma")
+        near = np.abs(s - ref["tau"]) <= 1e-5 * max(1.0, abs(ref["tau"]))
+        if near.sum() <= 1:
+            assert np.array_equal(ids, np.sort(ref["idx"])), f"{what} t{t} h{h}: set differs from exact top-p"
+        kept.append(int(keep.sum()))
+    if rows_dense:
+        dout = torch.zeros_like(run.out)
+        run.dense_attn(dout)
+        torch.cuda.synchronize()
+        dgot = dout.float().cpu().numpy().astype(np.float64)
+        for (t, h) in rows_dense:
+            m = w.chunk_start + t
+            o, _ = orc.attend(qb[t, h], wl.bf16_bits(w.K[h // G, :m + 1]), wl.bf16_bits(w.V[h // G, :m + 1]),
+                              np.arange(m + 1), SC)
+            check_out(dgot[t, h], o, f"{what} dense t{t} h{h}", tight="mfma")
+    return kept
+
+
+def _sample_rows(w, n, heads, rng, edges=True):
+    ts = set(rng.integers(0, w.T, size=n).tolist())
+    if edges:
+        ts |= {0, 1, 63, 64, 127, 128, w.T - 1, w.T - 2, w.T // 2}
+    ts = sorted(t for t in ts if 0 <= t < w.T)
+    return [(t, int(heads[i % len(heads)])) for i, t in enumerate(ts)]
+
+
+def test_c3_chunks_sampled_rows():
+    """Configuration 3: first chunk (queries below one key tile, below the sink count) and last chunk."""
+    rng = np.random.default_rng(7)
+    for chunk in (0, 31):
+        print(f"[case] c3 chunk {chunk}", flush=True)
+        w = wl.c3_chunk(DEV, chunk=chunk)
+        L = w.layer
+        local_heads = [h for h in range(L.n_q_heads) if h not in L.ret_heads]
+        kept = _prefill_fullsize(w, _sample_rows(w, 96, local_heads, rng), _sample_rows(w, 120, L.ret_heads, rng),
+                                 _sample_rows(w, 6, list(range(L.n_q_heads)), rng, edges=False), f"c3 chunk {chunk}")
+        print(f"   kept tokens over {len(kept)} sampled retrieval rows: min {min(kept)} mean {np.mean(kept):.0f} "
+              f"max {max(kept)}", flush=True)
+
+
+def test_c4_last_chunk_sampled_rows():
+    """Configuration 4: the 8192-query chunk that sees the whole 1,048,576-token context."""
+    print("[case] c4 last chunk", flush=True)
+    rng = np.random.default_rng(8)
+    w = wl.c4_chunk(DEV, chunk=127)
+    L = w.layer
+    local_heads = [h for h in range(L.n_q_heads) if h not in L.ret_heads]
+    kept = _prefill_fullsize(w, _sample_rows(w, 40, local_heads, rng), _sample_rows(w, 40, L.ret_heads, rng),
+                             _sample_rows(w, 3, list(range(L.n_q_heads)), rng, edges=False), "c4 last chunk")
+    print(f"   kept tokens over {len(kept)} sampled retrieval rows: min {min(kept)} mean {np.mean(kept):.0f} "
+          f"max {max(kept)}", flush=True)
