@@ -36,8 +36,10 @@ def main() -> int:
     ap.add_argument("--ctx", type=int, default=131072)
     ap.add_argument("--batch", type=int, default=8)
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--no-graph", action="store_true", help="time eager launches instead of HIP graph replays")
+    ap.add_argument("--graph", action="store_true", help="time HIP graph replays instead of eager launches "
+                    "(eager launches on two streams are the faster configuration on this box)")
     ap.add_argument("--one-stream", action="store_true", help="keep the local heads on the main stream")
+    ap.add_argument("--no-prefill", action="store_true", help="skip the 1M-token prefill measurements")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build is single-GPU by design (no collectives, no sharding); run with --gpus 1",
@@ -90,7 +92,7 @@ def main() -> int:
     torch.cuda.synchronize()
     sel_counts = runs[0].sel_count.cpu().numpy().astype(np.int64)
     graphs = []
-    if not args.no_graph:
+    if True:
         side = torch.cuda.Stream()
         for r in runs:
             g = torch.cuda.CUDAGraph()
@@ -107,7 +109,7 @@ def main() -> int:
                 assert torch.equal(r.out, o), "graph replay differs from the eager step"
 
     def step(i):
-        if graphs:
+        if args.graph:
             graphs[i % len(graphs)].replay()
         else:
             run_step(runs[i % len(runs)])
@@ -134,6 +136,8 @@ def main() -> int:
     }
     dense_us = timed(lambda i: runs[i % len(runs)].dense_attn(runs[i % len(runs)].out), max(10, it // 10), 2)
     eager_us = timed(lambda i: run_step(runs[i % len(runs)]), it, wu)
+    graph_us = timed(lambda i: graphs[i % len(graphs)].replay(), it, wu)
+    launch_mode = "hip-graph replay" if args.graph else "eager"
 
     # ---- algorithmic bytes per step (design notes: per-unit figures x units) ----
     sel_total = int(sel_counts.sum())
@@ -189,6 +193,70 @@ def main() -> int:
         err = float(np.abs(got - ref["out"]).max())
         assert err < 2e-2, f"bench output differs from the oracle on the sample: {err}"
 
+    # ---- prefill at 1,048,576 tokens (configuration 4): chunks of 8192 queries at five depths ----
+    prefill = None
+    if not args.no_prefill:
+        from gpu_util import PrefillRun
+        del graphs, runs
+        torch.cuda.empty_cache()
+        MFMA_PEAK = 2.5e15
+        depth = {}
+        for chunk in (0, 31, 63, 95, 127):
+            w = wl.c4_chunk(dev, chunk=chunk)
+            pr = PrefillRun(w)
+            Lp = w.layer
+            n_loc = Lp.n_q_heads - Lp.n_ret
+            pairs_dense = sum(w.chunk_start + t + 1 for t in range(w.T))
+            pairs_local = sum(min(w.chunk_start + t + 1, Lp.sink + Lp.window) for t in range(w.T))
+
+            def ret_dense():
+                rtp.rtp_sparse_attn_prefill(pr.desc, w.qI, w.q, None, w.kI, w.N * 16, pr.Kp, pr.Vp, pr.rs, pr.hs,
+                                            w.chunk_start, w.T, 1.0, pr.out, None, None, None, None, pr.ws)
+
+            reps = 3 if chunk < 100 else 2
+            t_local = timed(lambda i: pr.local_attn(), reps, 1)
+            t_ret = timed(lambda i: ret_dense(), reps, 1)
+            t_topp = timed(lambda i: pr.sparse_prefill(), reps, 1)
+            t_dense = timed(lambda i: pr.dense_attn(), 1, 1 if chunk < 100 else 0)
+            depth[chunk] = {
+                "context": w.N, "local_ms": round(t_local / 1e3, 3), "retrieval_dense_ms": round(t_ret / 1e3, 3),
+                "retrieval_topp_ms": round(t_topp / 1e3, 3), "dense_all_heads_ms": round(t_dense / 1e3, 3),
+                "local_mfma_frac": round(n_loc * pairs_local * 512 / (t_local * 1e-6) / MFMA_PEAK, 4),
+                "retrieval_dense_mfma_frac": round(Lp.n_ret * pairs_dense * 512 / (t_ret * 1e-6) / MFMA_PEAK, 4),
+                "dense_mfma_frac": round(Lp.n_q_heads * pairs_dense * 512 / (t_dense * 1e-6) / MFMA_PEAK, 4),
+                "topp_kept_tokens_mean": round(float(pr.count.float().mean()), 1),
+            }
+            del pr, w
+            torch.cuda.empty_cache()
+        T8 = 8192
+        last = depth[127]
+        # whole-sequence time: trapezoid over the five sampled depths, 128 chunks in total
+        def integrate(key):
+            cs = sorted(depth)
+            tot = 0.0
+            for a_, b_ in zip(cs[:-1], cs[1:]):
+                tot += 0.5 * (sum(depth[a_][k] for k in key) + sum(depth[b_][k] for k in key)) * (b_ - a_)
+            return tot + sum(depth[cs[-1]][k] for k in key)          # + the last chunk itself
+        ms_paper = integrate(("local_ms", "retrieval_dense_ms"))
+        ms_topp = integrate(("local_ms", "retrieval_topp_ms"))
+        ms_dense = integrate(("dense_all_heads_ms",))
+        prefill = {
+            "workload": "c4: prefill of 1,048,576 tokens in 8192-query chunks, 32 query / 8 KV heads, 4 retrieval heads, "
+                        "local heads 4 sink + 4096 window; chunks 0/31/63/95/127 timed, others interpolated",
+            "last_chunk_tokens_per_s_paper_rule": round(T8 / ((last["local_ms"] + last["retrieval_dense_ms"]) * 1e-3), 1),
+            "last_chunk_tokens_per_s_topp_rule": round(T8 / ((last["local_ms"] + last["retrieval_topp_ms"]) * 1e-3), 1),
+            "last_chunk_tokens_per_s_dense": round(T8 / (last["dense_all_heads_ms"] * 1e-3), 1),
+            "last_chunk_speedup_vs_inhouse_dense_paper_rule":
+                round(last["dense_all_heads_ms"] / (last["local_ms"] + last["retrieval_dense_ms"]), 2),
+            "whole_sequence_tokens_per_s_paper_rule": round((1 << 20) / (ms_paper * 1e-3), 1),
+            "whole_sequence_tokens_per_s_topp_rule": round((1 << 20) / (ms_topp * 1e-3), 1),
+            "whole_sequence_tokens_per_s_dense": round((1 << 20) / (ms_dense * 1e-3), 1),
+            "whole_sequence_speedup_vs_inhouse_dense_paper_rule": round(ms_dense / ms_paper, 2),
+            "by_chunk": depth,
+            "paper_context": "paper reports 9.36x prefill speedup over FlashAttention-2 at 1M on NVIDIA H20 with "
+                             "retrieval heads dense (its prefill rule); relative only",
+        }
+
     line = {
         "metric": "decode_us_per_step_128k",
         "value": round(us_step, 2),
@@ -204,15 +272,17 @@ def main() -> int:
         "data": "synthetic",
         "config": {"workload": f"c2: decode step, batch {B} x context {N}, 32 query / 8 KV heads, head_dim 128, "
                                f"4 retrieval heads (index dim 16, top-p {args.p}), local heads 4 sink + 2048 window",
-                   "copies_cycled": args.copies, "launch": "hip-graph replay" if graphs else "eager",
+                   "copies_cycled": args.copies, "launch": launch_mode,
                    "streams": 1 if args.one_stream else 2},
         "roofline": roofline,
         "cpu_baseline": cpu,
+        "prefill_1m": prefill,
         "extra": {
             "decode_tokens_per_s": round(B / (us_step * 1e-6), 1),
             "step_hbm_GBps_algorithmic": round(step_bytes / (us_step * 1e-6) / 1e9, 1),
             "step_algorithmic_bytes": step_bytes,
             "eager_us_per_step": round(eager_us, 2),
+            "graph_replay_us_per_step": round(graph_us, 2),
             "call_us": {k: round(v, 2) for k, v in br.items()},
             "call_GBps": {"index_score": round(bytes_index / br["index_score"] / 1e3, 1),
                           "topp_select": round(bytes_topp / br["topp_select"] / 1e3, 1),
