@@ -23,6 +23,7 @@ constexpr int kPfQ = 128;          // queries per workgroup
 constexpr int kPfK = 64;           // keys per tile
 constexpr int kKsStride = 136;     // bf16 per K row in LDS   (128 + 8: rows start 4 banks apart)
 constexpr int kVtStride = 72;      // bf16 per V^T row in LDS (64 + 8)
+constexpr int kPfPart = kHeadDim + 4;   // floats per partial row: max, sum, 2 pad, unnormalised output[128]
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
@@ -45,6 +46,8 @@ struct PrefillArgs {
   float* lse;
   int32_t n_heads;
   uint8_t heads[128];           // query heads this launch computes
+  int32_t n_splits;             // dense mode: key range of every query tile cut into this many parts
+  float* part;                  // n_splits > 1: partial results [split, head slot, query, kPfPart]
   // sparse mode only (per-query top-p over the indexer scores):
   const uint16_t* qI;           // bf16 [n_ret, n_q, 16]
   const uint16_t* kI;           // bf16 [n_ret, >= pos0 + n_q, 16]
@@ -63,7 +66,8 @@ enum { kModeDense = 0, kModeLocal = 1, kModeSparse = 2 };
 constexpr int kSelBins = 128;
 constexpr float kSelScale = 131072.0f;
 constexpr int kSelQMax = (1 << 21) - 1;
-constexpr int kSmemDense = (kPfK * kKsStride + kHeadDim * kVtStride) * 2;
+constexpr int kTileHalfs = kPfK * kKsStride + kHeadDim * kVtStride;   // bf16 elements of one staged K + V^T tile
+constexpr int kSmemDense = kTileHalfs * 2 * 2;                        // two buffers
 constexpr int kSmemSparse = (kPfThreads / 64) * 32 * kSelBins * 8;
 
 __device__ __forceinline__ int sel_q(float M, float s) {
@@ -76,18 +80,19 @@ __device__ __forceinline__ uint32_t pack_bf16(float a, float b) {
 }
 
 template <int MODE>
-__global__ __launch_bounds__(kPfThreads) void flash_prefill_kernel(const PrefillArgs a) {
+__global__ __launch_bounds__(kPfThreads, 2) void flash_prefill_kernel(const PrefillArgs a) {
   constexpr bool LOCAL = MODE == kModeLocal;
   constexpr bool SPARSE = MODE == kModeSparse;
   __shared__ __attribute__((aligned(16))) unsigned char smem[SPARSE ? (kSmemSparse > kSmemDense ? kSmemSparse : kSmemDense)
                                                                     : kSmemDense];
   uint16_t* Ks = reinterpret_cast<uint16_t*>(smem);
-  uint16_t* Vt = Ks + kPfK * kKsStride;
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int g = lane >> 5, r = lane & 31;
   const int h = a.heads[blockIdx.x];
-  const int b = blockIdx.z;
+  const int n_splits = SPARSE || LOCAL ? 1 : a.n_splits;
+  const int b = blockIdx.z / n_splits;
+  const int split = blockIdx.z - b * n_splits;
   const int t0 = ((int)gridDim.y - 1 - (int)blockIdx.y) * kPfQ;
   const int kvh = h / (a.n_q_heads / a.n_kv_heads);
   const int pos0 = a.q_start ? a.q_start[b] : (int)a.q_start_host;
@@ -215,15 +220,153 @@ __global__ __launch_bounds__(kPfThreads) void flash_prefill_kernel(const Prefill
     for (int i = 0; i < 16; ++i) O[db][i] = 0.f;
   float mrow = ninf, lrow = 0.f;
   const float c = a.scale_log2;
+  const int m_wave_lo = pos0 + t0 + wave * 32;
+  const int m_wave_hi = pos0 + min(t0 + wave * 32 + 32, a.n_q) - 1;
 
-  for (int it = 0; it < n_tiles; ++it) {
-    const int kt = it < ks_end ? it : kt_w0 + (it - ks_end);
-    const int n0 = kt * kPfK;
+  // ---- tile movers -------------------------------------------------------------------------------
+  // K: thread handles chunks idx = i * 256 + tid -> (key idx / 16, 16-byte chunk idx % 16).
+  // V: thread handles keys wave * 16 + (lane / 16) * 4 + {0..3} at chunk lane % 16, so that it can
+  //    transpose a 4 x 8 block in registers and write 8-byte runs of V^T.
+  u32x4 kr[4], vr[4];
+  const int v_ck = lane & 15;
+  const int v_key0 = wave * 16 + (lane >> 4) * 4;
+  auto load_tile = [&](int n0) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int idx = i * kPfThreads + tid;
+      const int n = n0 + (idx >> 4);
+      kr[i] = (u32x4){0u, 0u, 0u, 0u};
+      if (n <= m_hi) kr[i] = *reinterpret_cast<const u32x4*>(Kg + (int64_t)n * a.row_stride + (idx & 15) * 8);
+    }
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int n = n0 + v_key0 + i;
+      vr[i] = (u32x4){0u, 0u, 0u, 0u};
+      if (n <= m_hi) vr[i] = *reinterpret_cast<const u32x4*>(Vg + (int64_t)n * a.row_stride + v_ck * 8);
+    }
+  };
+  // V^T row d holds the tile's 64 keys in the order the PV MFMAs consume them: inside every 32-key
+  // block, position = tt*16 + g*8 + hi*4 + j for key = tt*16 + hi*8 + g*4 + j, so the 8 keys a lane
+  // needs for one MFMA are one 16-byte read.  16-byte units are XOR-swizzled with bits of d so that
+  // the transposing 8-byte writes spread over the banks.
+  auto store_tile = [&](int buf) {
+    uint16_t* ks = Ks + buf * (kTileHalfs);
+    uint16_t* vt = ks + kPfK * kKsStride;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int idx = i * kPfThreads + tid;
+      *reinterpret_cast<u32x4*>(&ks[(idx >> 4) * kKsStride + (idx & 15) * 8]) = kr[i];
+    }
+    const int pos0v = (v_key0 & 32) + ((v_key0 >> 4) & 1) * 16 + ((v_key0 >> 2) & 1) * 8 + ((v_key0 >> 3) & 1) * 4;
+    const uint32_t w0[4] = {vr[0].x, vr[0].y, vr[0].z, vr[0].w};
+    const uint32_t w1[4] = {vr[1].x, vr[1].y, vr[1].z, vr[1].w};
+    const uint32_t w2[4] = {vr[2].x, vr[2].y, vr[2].z, vr[2].w};
+    const uint32_t w3[4] = {vr[3].x, vr[3].y, vr[3].z, vr[3].w};
+#pragma unroll
+    for (int aa = 0; aa < 4; ++aa) {
+#pragma unroll
+      for (int hl = 0; hl < 2; ++hl) {
+        const int d = v_ck * 8 + aa * 2 + hl;
+        const uint32_t sel = hl ? 0x07060302u : 0x05040100u;      // high / low halves of (second, first)
+        const u32x2 val = (u32x2){__builtin_amdgcn_perm(w1[aa], w0[aa], sel), __builtin_amdgcn_perm(w3[aa], w2[aa], sel)};
+        const int off = d * kVtStride + ((((pos0v >> 3) ^ ((d >> 4) & 7))) << 3) + (pos0v & 7);
+        *reinterpret_cast<u32x2*>(&vt[off]) = val;
+      }
+    }
+  };
 
-    // ---- sparse mode: which (key, query) pairs of this tile are in the active sets ----
-    uint32_t selmask[2] = {0xffffu, 0xffffu};       // bit i: accumulator element i of block kb is kept
-    if (SPARSE) {
-      const int n_rows = pos0 + a.n_q;
+  // ---- one key tile: S^T = K Q^T, online softmax, O^T += V^T P^T -----------------------------------
+  auto compute_tile = [&](int buf, int n0, const uint32_t (&selmask)[2]) {
+    const uint16_t* ks = Ks + buf * (kTileHalfs);
+    const uint16_t* vt = ks + kPfK * kKsStride;
+    f32x16 S[2];
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb) {
+#pragma unroll
+      for (int i = 0; i < 16; ++i) S[kb][i] = 0.f;
+#pragma unroll
+      for (int kk = 0; kk < 8; ++kk) {
+        const u32x4 ka = *reinterpret_cast<const u32x4*>(&ks[(kb * 32 + r) * kKsStride + kk * 16 + g * 8]);
+        S[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, ka),
+                                                        __builtin_bit_cast(bf16x8, qreg[kk]), S[kb], 0, 0, 0);
+      }
+    }
+    // interior tiles (every key visible to every query of the wave) skip the mask arithmetic
+    const bool masked = SPARSE || (n0 + kPfK - 1 > m_wave_lo) || (LOCAL && n0 <= m_wave_hi - a.window);
+    float mx = ninf;
+    if (masked) {
+#pragma unroll
+      for (int kb = 0; kb < 2; ++kb) {
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+          const int n = n0 + kb * 32 + (i >> 2) * 8 + g * 4 + (i & 3);
+          bool ok = qok && n <= m;
+          if (LOCAL) ok = ok && (n < a.sink || n > m - a.window);
+          if (SPARSE) ok = (selmask[kb] >> i) & 1u;
+          S[kb][i] = ok ? S[kb][i] : ninf;
+          mx = fmaxf(mx, S[kb][i]);
+        }
+      }
+    } else {
+#pragma unroll
+      for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) mx = fmaxf(mx, S[kb][i]);
+    }
+    mx = fmaxf(mx, __shfl_xor(mx, 32));
+    const float mnew = fmaxf(mrow, mx);
+    uint32_t P[2][8];
+    if (mnew == ninf) {
+#pragma unroll
+      for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+        for (int i = 0; i < 8; ++i) P[kb][i] = 0u;
+    } else {
+      const float mc = mnew * c;
+      float lsum = 0.f;
+#pragma unroll
+      for (int kb = 0; kb < 2; ++kb) {
+#pragma unroll
+        for (int i = 0; i < 16; i += 2) {
+          const float p0 = fast_exp2(fmaf(S[kb][i], c, -mc));
+          const float p1 = fast_exp2(fmaf(S[kb][i + 1], c, -mc));
+          lsum += p0 + p1;
+          P[kb][i >> 1] = pack_bf16(p0, p1);
+        }
+      }
+      const float corr = fast_exp2((mrow - mnew) * c);     // 1 where the maximum did not move
+      lrow = lrow * corr + lsum;
+      if (__ballot(mnew > mrow) != 0ull) {                   // rescale only when some query's maximum grew
+#pragma unroll
+        for (int db = 0; db < 4; ++db)
+#pragma unroll
+          for (int i = 0; i < 16; ++i) O[db][i] *= corr;
+      }
+      mrow = mnew;
+    }
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb) {
+#pragma unroll
+      for (int tt = 0; tt < 2; ++tt) {
+        const u32x4 pb = (u32x4){P[kb][4 * tt], P[kb][4 * tt + 1], P[kb][4 * tt + 2], P[kb][4 * tt + 3]};
+        const int pos8 = kb * 4 + tt * 2 + g;
+#pragma unroll
+        for (int db = 0; db < 4; ++db) {
+          const int d = db * 32 + r;
+          const u32x4 va = *reinterpret_cast<const u32x4*>(&vt[d * kVtStride + ((pos8 ^ ((d >> 4) & 7)) << 3)]);
+          O[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, va),
+                                                          __builtin_bit_cast(bf16x8, pb), O[db], 0, 0, 0);
+        }
+      }
+    }
+  };
+
+  if (SPARSE) {
+    // Selecting mode: a tile is staged only if some query of the workgroup keeps one of its keys.
+    const int n_rows = pos0 + a.n_q;
+    for (int kt = 0; kt <= kt_end; ++kt) {
+      const int n0 = kt * kPfK;
+      uint32_t selmask[2];
 #pragma unroll
       for (int kb = 0; kb < 2; ++kb) {
         const int nrow = n0 + kb * 32 + r;
@@ -247,118 +390,47 @@ __global__ __launch_bounds__(kPfThreads) void flash_prefill_kernel(const Prefill
       }
       const int wave_any = (__ballot((selmask[0] | selmask[1]) != 0u) != 0ull) ? 1 : 0;
       if (!__syncthreads_or(wave_any)) continue;     // nobody in the workgroup needs this key tile
+      load_tile(n0);
+      store_tile(0);
+      __syncthreads();
+      if (wave_any) compute_tile(0, n0, selmask);
     }
-
-    // ---- stage K (row-major) and V (transposed) in LDS ----
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const int idx = i * kPfThreads + tid;
-      const int key = idx >> 4, ck = idx & 15;
-      const int n = n0 + key;
-      u32x4 v = (u32x4){0u, 0u, 0u, 0u};
-      if (n <= m_hi) v = *reinterpret_cast<const u32x4*>(Kg + (int64_t)n * a.row_stride + ck * 8);
-      *reinterpret_cast<u32x4*>(&Ks[key * kKsStride + ck * 8]) = v;
+  } else {
+    // Software pipeline: the global loads of tile it+1 are in flight while tile it is computed from
+    // the other LDS buffer; one barrier per tile.
+    const uint32_t nomask[2] = {0xffffu, 0xffffu};
+    auto tile_n0 = [&](int it) { return (it < ks_end ? it : kt_w0 + (it - ks_end)) * kPfK; };
+    const int it_lo = (int)((int64_t)n_tiles * split / n_splits);
+    const int it_hi = (int)((int64_t)n_tiles * (split + 1) / n_splits);
+    if (it_lo < it_hi) {
+      load_tile(tile_n0(it_lo));
+      store_tile(it_lo & 1);
+      __syncthreads();
     }
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const int key = i * 16 + (tid & 15), ck = tid >> 4;
-      const int n = n0 + key;
-      u32x4 v = (u32x4){0u, 0u, 0u, 0u};
-      if (n <= m_hi) v = *reinterpret_cast<const u32x4*>(Vg + (int64_t)n * a.row_stride + ck * 8);
-      uint16_t* dst = &Vt[(ck * 8) * kVtStride + key];
-      dst[0 * kVtStride] = (uint16_t)(v.x & 0xffffu);
-      dst[1 * kVtStride] = (uint16_t)(v.x >> 16);
-      dst[2 * kVtStride] = (uint16_t)(v.y & 0xffffu);
-      dst[3 * kVtStride] = (uint16_t)(v.y >> 16);
-      dst[4 * kVtStride] = (uint16_t)(v.z & 0xffffu);
-      dst[5 * kVtStride] = (uint16_t)(v.z >> 16);
-      dst[6 * kVtStride] = (uint16_t)(v.w & 0xffffu);
-      dst[7 * kVtStride] = (uint16_t)(v.w >> 16);
+    for (int it = it_lo; it < it_hi; ++it) {
+      const bool has_next = it + 1 < it_hi;
+      if (has_next) load_tile(tile_n0(it + 1));
+      compute_tile(it & 1, tile_n0(it), nomask);
+      if (has_next) store_tile((it + 1) & 1);
+      __syncthreads();
     }
-    __syncthreads();
-
-    // ---- S^T = K Q^T : two 32-key blocks ----
-    f32x16 S[2];
-#pragma unroll
-    for (int kb = 0; kb < 2; ++kb) {
-#pragma unroll
-      for (int i = 0; i < 16; ++i) S[kb][i] = 0.f;
-#pragma unroll
-      for (int kk = 0; kk < 8; ++kk) {
-        const u32x4 ka = *reinterpret_cast<const u32x4*>(&Ks[(kb * 32 + r) * kKsStride + kk * 16 + g * 8]);
-        S[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, ka),
-                                                        __builtin_bit_cast(bf16x8, qreg[kk]), S[kb], 0, 0, 0);
-      }
-    }
-
-    // ---- mask, online softmax (per-lane state: this lane's query) ----
-    float mx = ninf;
-#pragma unroll
-    for (int kb = 0; kb < 2; ++kb) {
-#pragma unroll
-      for (int i = 0; i < 16; ++i) {
-        const int n = n0 + kb * 32 + (i >> 2) * 8 + g * 4 + (i & 3);
-        bool ok = qok && n <= m;
-        if (LOCAL) ok = ok && (n < a.sink || n > m - a.window);
-        if (SPARSE) ok = (selmask[kb] >> i) & 1u;
-        S[kb][i] = ok ? S[kb][i] : ninf;
-        mx = fmaxf(mx, S[kb][i]);
-      }
-    }
-    mx = fmaxf(mx, __shfl_xor(mx, 32));
-    const float mnew = fmaxf(mrow, mx);
-    uint32_t P[2][8];
-    if (mnew == ninf) {
-#pragma unroll
-      for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-        for (int i = 0; i < 8; ++i) P[kb][i] = 0u;
-    } else {
-      const float corr = fast_exp2((mrow - mnew) * c);
-      const float mc = mnew * c;
-      float lsum = 0.f;
-#pragma unroll
-      for (int kb = 0; kb < 2; ++kb) {
-#pragma unroll
-        for (int i = 0; i < 16; i += 2) {
-          const float p0 = fast_exp2(fmaf(S[kb][i], c, -mc));
-          const float p1 = fast_exp2(fmaf(S[kb][i + 1], c, -mc));
-          lsum += p0 + p1;
-          P[kb][i >> 1] = pack_bf16(p0, p1);
-        }
-      }
-      lrow = lrow * corr + lsum;
-      mrow = mnew;
-#pragma unroll
-      for (int db = 0; db < 4; ++db)
-#pragma unroll
-        for (int i = 0; i < 16; ++i) O[db][i] *= corr;
-    }
-
-    // ---- O^T += V^T P^T ----
-#pragma unroll
-    for (int kb = 0; kb < 2; ++kb) {
-#pragma unroll
-      for (int tt = 0; tt < 2; ++tt) {
-        const u32x4 pb = (u32x4){P[kb][4 * tt], P[kb][4 * tt + 1], P[kb][4 * tt + 2], P[kb][4 * tt + 3]};
-        const int kbase = kb * 32 + tt * 16 + g * 4;
-#pragma unroll
-        for (int db = 0; db < 4; ++db) {
-          const uint16_t* vrow = &Vt[(db * 32 + r) * kVtStride + kbase];
-          const u32x2 lo = *reinterpret_cast<const u32x2*>(vrow);
-          const u32x2 hi = *reinterpret_cast<const u32x2*>(vrow + 8);
-          const u32x4 va = (u32x4){lo.x, lo.y, hi.x, hi.y};
-          O[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, va),
-                                                          __builtin_bit_cast(bf16x8, pb), O[db], 0, 0, 0);
-        }
-      }
-    }
-    __syncthreads();
   }
 
   // ---- normalise and store ----
   const float ltot = lrow + __shfl_xor(lrow, 32);
   if (!qok) return;
+  if (n_splits > 1) {
+    // partial result of this key range: merged by prefill_combine_kernel
+    float* prow = a.part + (((int64_t)split * a.n_heads + blockIdx.x) * a.n_q + t) * kPfPart;
+    if (g == 0) { prow[0] = mrow; prow[1] = ltot; }
+#pragma unroll
+    for (int db = 0; db < 4; ++db)
+#pragma unroll
+      for (int i4 = 0; i4 < 4; ++i4)
+        *reinterpret_cast<float4*>(prow + 4 + db * 32 + i4 * 8 + g * 4) =
+            make_float4(O[db][i4 * 4], O[db][i4 * 4 + 1], O[db][i4 * 4 + 2], O[db][i4 * 4 + 3]);
+    return;
+  }
   const float inv = ltot > 0.f ? 1.f / ltot : 0.f;
   uint16_t* orow = a.out + qrow;
 #pragma unroll
@@ -406,12 +478,48 @@ __global__ __launch_bounds__(256) void index_project_kernel(const ProjectArgs a)
   a.out[((int64_t)j * a.n_q + t) * kIndexDim + i] = f64_to_bf16_rne(acc);
 }
 
+// Merges the key-range partials of one (query, head): thread = output dim, two queries per block.
+__global__ __launch_bounds__(256) void prefill_combine_kernel(const PrefillArgs a) {
+  const int t = blockIdx.x * 2 + (threadIdx.x >> 7), d = threadIdx.x & 127, hs = blockIdx.y;
+  if (t >= a.n_q) return;
+  const float ninf = -__builtin_huge_valf();
+  float M = ninf;
+  for (int s = 0; s < a.n_splits; ++s) M = fmaxf(M, a.part[(((int64_t)s * a.n_heads + hs) * a.n_q + t) * kPfPart]);
+  float L = 0.f, A = 0.f;
+  if (M != ninf) {
+    for (int s = 0; s < a.n_splits; ++s) {
+      const float* p = a.part + (((int64_t)s * a.n_heads + hs) * a.n_q + t) * kPfPart;
+      if (p[0] == ninf) continue;
+      const float cw = fast_exp2((p[0] - M) * a.scale_log2);
+      L += p[1] * cw;
+      A += p[4 + d] * cw;
+    }
+  }
+  const int h = a.heads[hs];
+  const int64_t o = (int64_t)t * a.n_q_heads + h;        // single sequence
+  a.out[o * kHeadDim + d] = f32_to_bf16_rne(L > 0.f ? A / L : 0.f);
+  if (a.lse && d == 0) a.lse[o] = L > 0.f ? M * a.scale + logf(L) : ninf;
+}
+
+// Number of key-range splits for a dense launch with few workgroups (long context, few heads).
+static int choose_splits(int n_heads, int32_t T, int64_t chunk_start) {
+  const int64_t wgs = (int64_t)n_heads * ((T + kPfQ - 1) / kPfQ);
+  const int64_t avg_tiles = (chunk_start + T / 2) / kPfK + 1;
+  int64_t s = 1024 / (wgs > 0 ? wgs : 1);
+  if (s > avg_tiles / 32) s = avg_tiles / 32;
+  if (s > 8) s = 8;
+  return s < 1 ? 1 : (int)s;
+}
+
 static int32_t launch_prefill(const char* who, bool local, PrefillArgs& a, int32_t B, hipStream_t s) {
   if (a.n_heads == 0) return RTP_OK;
-  dim3 grid((unsigned)a.n_heads, (unsigned)((a.n_q + kPfQ - 1) / kPfQ), (unsigned)B);
+  if (a.n_splits < 1) a.n_splits = 1;
+  dim3 grid((unsigned)a.n_heads, (unsigned)((a.n_q + kPfQ - 1) / kPfQ), (unsigned)(B * (local ? 1 : a.n_splits)));
   if (grid.y > 65535 || grid.z > 65535) return fail(RTP_ERR_INVALID_ARG, "%s: n_q / B too large for one launch", who);
   if (local) hipLaunchKernelGGL(flash_prefill_kernel<kModeLocal>, grid, dim3(kPfThreads), 0, s, a);
   else hipLaunchKernelGGL(flash_prefill_kernel<kModeDense>, grid, dim3(kPfThreads), 0, s, a);
+  if (!local && a.n_splits > 1)
+    hipLaunchKernelGGL(prefill_combine_kernel, dim3((unsigned)((a.n_q + 1) / 2), (unsigned)a.n_heads), dim3(256), 0, s, a);
   return check_launch(who);
 }
 
@@ -467,9 +575,11 @@ int32_t prefill_range_attn(const char* who, bool dense, const rtp_layer_desc* L,
 using namespace rtp;
 
 extern "C" size_t rtp_sparse_attn_prefill_workspace_bytes(const rtp_layer_desc* layer, int32_t T, int64_t chunk_start) {
-  (void)chunk_start;
   if (!layer || T <= 0 || layer->n_ret <= 0) return 256;
-  return align_up((size_t)layer->n_ret * T * kIndexDim * sizeof(uint16_t), 256);   // projected index queries
+  const size_t proj = align_up((size_t)layer->n_ret * T * kIndexDim * sizeof(uint16_t), 256);   // projected index queries
+  const int ns = choose_splits(layer->n_ret, T, chunk_start < 0 ? 0 : chunk_start);
+  const size_t part = ns > 1 ? align_up((size_t)ns * layer->n_ret * T * kPfPart * sizeof(float), 256) : 0;
+  return proj > part ? proj : part;
 }
 
 extern "C" int32_t rtp_sparse_attn_prefill(const rtp_layer_desc* layer, const void* q_pre, const void* q, const float* WQ,
@@ -520,7 +630,15 @@ extern "C" int32_t rtp_sparse_attn_prefill(const rtp_layer_desc* layer, const vo
   a.lse = lse;
   a.n_heads = layer->n_ret;
   for (int j = 0; j < layer->n_ret; ++j) a.heads[j] = (uint8_t)layer->ret_heads[j];
-  if (!sparse) return launch_prefill(who, false, a, 1, (hipStream_t)stream);   // the paper's dense prefill rule
+  if (!sparse) {                                     // the paper's dense prefill rule
+    a.n_splits = choose_splits(layer->n_ret, T, chunk_start);
+    if (a.n_splits > 1) {
+      const size_t need = rtp_sparse_attn_prefill_workspace_bytes(layer, T, chunk_start);
+      if (!ws || ((uintptr_t)ws & 255) || ws_bytes < need) a.n_splits = 1;   // no scratch: run unsplit
+      a.part = (float*)ws;
+    }
+    return launch_prefill(who, false, a, 1, (hipStream_t)stream);
+  }
 
   // index queries: given, or projected in fp64 into the workspace first
   const uint16_t* qI = (const uint16_t*)q_pre;

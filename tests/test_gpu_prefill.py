@@ -202,3 +202,31 @@ def test_sparse_prefill_p1_statistics_and_dense_equivalence():
     run.dense_attn(dout)
     torch.cuda.synchronize()
     assert torch.equal(a[:, L.ret_heads], dout[:, L.ret_heads])
+
+
+def test_retrieval_dense_split_keys_matches_unsplit():
+    """Few heads and a long context: the dense rule cuts every query tile's key range into parts and
+    merges them.  With a workspace the split path runs, without one the unsplit path: same result."""
+    print("[case] dense retrieval rule with key-range splits", flush=True)
+    w = wl.small_prefill(DEV, seed=81, chunk_start=6000, T=130, n_q_heads=4, n_kv_heads=2, ret_heads=(1,))
+    run = PrefillRun(w)
+    L = w.layer
+    need = rtp.rtp_sparse_attn_prefill_workspace_bytes(run.desc, w.T, w.chunk_start)
+    assert need > L.n_ret * w.T * 132 * 4            # room for at least two partials per row
+    a = torch.zeros_like(run.out)
+    b = torch.zeros_like(run.out)
+    la, lb = torch.zeros_like(run.lse), torch.zeros_like(run.lse)
+    args = (run.desc, w.qI, w.q, None, w.kI, w.N * 16, run.Kp, run.Vp, run.rs, run.hs, w.chunk_start, w.T, 1.0)
+    rtp.rtp_sparse_attn_prefill(*args, a, la, None, None, None, run.ws)
+    rtp.rtp_sparse_attn_prefill(*args, b, lb, None, None, None, None)
+    torch.cuda.synchronize()
+    oi = prefill_oracle_inputs(w)
+    rows = [(t, 1) for t in range(w.T)]
+    ref = orc.dense_rows(rows=rows, q_bits=oi["q_bits"], K_bits=oi["K_bits"], V_bits=oi["V_bits"],
+                         chunk_start=w.chunk_start, n_q_heads=L.n_q_heads, n_kv_heads=L.n_kv_heads)
+    ga = a.float().cpu().numpy().astype(np.float64)
+    gb = b.float().cpu().numpy().astype(np.float64)
+    for r in ref:
+        check_out(ga[r["t"], 1], r["out"], "split", tight="mfma")
+        check_out(gb[r["t"], 1], r["out"], "unsplit", tight="mfma")
+        assert abs(la[r["t"], 1].item() - r["lse"]) < 3e-3 and abs(lb[r["t"], 1].item() - r["lse"]) < 3e-3
