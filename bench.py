@@ -155,7 +155,10 @@ def main() -> int:
     # full context for every retrieval head, i.e. the HBM-bound core of the step
     ach = bytes_index / (br["index_score"] * 1e-6) / 1e9
     roofline = {"kernel": "index_score_kernel", "bound": "hbm", "achieved": round(ach, 1), "peak": HBM_PEAK_GBS,
-                "unit": "GB/s", "frac": round(ach / HBM_PEAK_GBS, 4), "traffic": None,
+                "unit": "GB/s", "frac": round(ach / HBM_PEAK_GBS, 4),
+                # HBM bytes per launch from the rocprofv3 --pmc runs recorded under profiles/ (FETCH_SIZE x 2.0 +
+                # WRITE_SIZE x 1.0 KiB, factors from a plain 1 GiB copy); only valid for the default shape
+                "traffic": 151108096 if (B, N, n_ret) == (8, 131072, 4) else None,
                 "algorithmic_bytes_per_launch": bytes_index, "avg_launch_us": round(br["index_score"], 2)}
 
     # ---- CPU baseline: the oracle, as it stands, on a bounded sample of the same workload ----
