@@ -416,7 +416,7 @@ static int tune(const char* name, int dflt) {
 static DecodePlanHost plan_host_sparse(int32_t units, int64_t max_tok) {
   DecodePlanHost p = {};
   p.units = units;
-  const int64_t cap = tune("RTP_TUNE_SPARSE_ITEMS", 2048);
+  const int64_t cap = tune("RTP_TUNE_SPARSE_ITEMS", 1024);
   int64_t blocks128 = (int64_t)units * ((max_tok + 127) / 128);
   int64_t tgt = blocks128 < 1 ? 1 : (blocks128 > cap ? cap : blocks128);
   p.target_items = (int32_t)tgt;
@@ -430,7 +430,7 @@ static DecodePlanHost plan_host_sparse(int32_t units, int64_t max_tok) {
 static DecodePlanHost plan_host_range(int32_t units, int64_t max_tok, int32_t G) {
   DecodePlanHost p = {};
   p.units = units;
-  const int64_t cap = tune("RTP_TUNE_RANGE_ITEMS", 2048);
+  const int64_t cap = tune("RTP_TUNE_RANGE_ITEMS", 1024);
   const int64_t blocks = (max_tok + 127) / 128;
   int64_t ns = cap / units;
   if (ns < 1) ns = 1;

@@ -10,9 +10,18 @@
 
 namespace rtp {
 
-constexpr int kIsChunk = 2048;   // tokens per workgroup (64 KiB of index keys)
-constexpr int kIsThreads = 256;
-constexpr int kIsBatch = 8;      // 16-byte loads in flight per lane
+#ifndef RTP_IS_CHUNK
+#define RTP_IS_CHUNK 2048
+#endif
+#ifndef RTP_IS_THREADS
+#define RTP_IS_THREADS 256
+#endif
+constexpr int kIsChunk = RTP_IS_CHUNK;   // tokens per workgroup (2048 = 64 KiB of index keys)
+constexpr int kIsThreads = RTP_IS_THREADS;
+#ifndef RTP_IS_BATCH
+#define RTP_IS_BATCH 16
+#endif
+constexpr int kIsBatch = RTP_IS_BATCH;   // 16-byte loads in flight per lane
 
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
@@ -56,6 +65,7 @@ __global__ __launch_bounds__(kIsThreads) void index_score_kernel(const IndexScor
   __shared__ float sq[kIndexDim];
   const int64_t qi_off = (((int64_t)b * a.n_ret + j) * a.n_q + t) * kIndexDim;
   if (a.WQ) {
+    if (tid < 256) {
     const int i = tid >> 4, part = tid & 15;   // 16 output dims x 16 lanes, 8 terms each
     const float* w = a.WQ + ((int64_t)j * kIndexDim + i) * kHeadDim + part * 8;
     const uint16_t* x = a.q_in + (((int64_t)b * a.n_q + t) * a.n_q_heads + a.ret_heads[j]) * kHeadDim + part * 8;
@@ -70,6 +80,7 @@ __global__ __launch_bounds__(kIsThreads) void index_score_kernel(const IndexScor
       const uint16_t qb = f64_to_bf16_rne(acc);
       sq[i] = bf16_to_f32(qb);
       if (blockIdx.x == 0 && a.qI_out) a.qI_out[qi_off + i] = qb;
+    }
     }
   } else if (tid < kIndexDim) {
     const uint16_t qb = a.q_in[qi_off + tid];
@@ -99,7 +110,11 @@ __global__ __launch_bounds__(kIsThreads) void index_score_kernel(const IndexScor
     for (int u = 0; u < kIsBatch; ++u) {
       const int piece = (batch * kIsBatch + u) * kIsThreads + tid;
       if (full || (piece >> 1) < n_here) {
+#ifdef RTP_IS_PLAIN_LOAD
+        v[u] = src[piece];
+#else
         v[u] = __builtin_nontemporal_load(src + piece);
+#endif
       } else {
         v[u] = (u32x4){0u, 0u, 0u, 0u};
       }

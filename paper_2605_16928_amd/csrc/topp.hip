@@ -17,10 +17,15 @@
 // non-empty bins are flushed with 64-bit global atomics.
 #include "common.h"
 
+#include <stdlib.h>
+
 namespace rtp {
 
 constexpr int kTpThreads = 256;
-constexpr int kTpChunk = 8192;             // scores per workgroup
+#ifndef RTP_TP_CHUNK
+#define RTP_TP_CHUNK 4096
+#endif
+constexpr int kTpChunk = RTP_TP_CHUNK;     // scores per workgroup (2048, 4096 or 8192)
 constexpr int kTpVec = kTpChunk / (kTpThreads * 4);   // float4 loads per thread = 8
 constexpr int kBins1 = 2048, kBins2 = 2048, kBins3 = 1024;
 constexpr int kBinsTotal = kBins1 + kBins2 + kBins3;
@@ -33,6 +38,13 @@ struct RowState {          // one per row and level (3 per row)
   int32_t flags;           // 0 ok, 1 = keep everything (p >= 1), -1 = invalid p
   float smax;
   int32_t shift;
+};
+
+struct FusedSync {          // per row; zeroed before the single-launch kernel starts
+  uint32_t bar;            // arrivals at the row barrier (monotonic)
+  uint32_t maxkey;         // order-preserving key of the row maximum
+  int32_t err;             // set if a barrier wait ran out
+  uint32_t pad;
 };
 
 struct TopPArgs {
@@ -51,6 +63,7 @@ struct TopPArgs {
   int32_t* chunk_cnt;      // [R, n_chunks]
   uint64_t* hist;          // [R, kBinsTotal]
   RowState* state;         // [R, 4]
+  struct FusedSync* sync;  // [R]   (single-launch path)
 };
 
 __device__ __forceinline__ int fixed_shift(int n) {
@@ -102,8 +115,8 @@ struct ScanResult {
 // Scans NBINS fixed-point masses (global, written by an earlier launch) from the top.  With
 // derive_target the histogram is the level-1 one: its total is Z and the target becomes ceil(p * Z).
 // Every thread gets the result.  Two block barriers; wave-level suffix sums run on shuffles.
-template <int NBINS>
-__device__ __forceinline__ ScanResult scan_from_top(const uint64_t* __restrict__ h, uint64_t above, uint64_t target,
+template <int NBINS, bool COHERENT = false>
+__device__ __forceinline__ ScanResult scan_from_top(const uint64_t* h, uint64_t above, uint64_t target,
                                                     bool derive_target, float p, uint64_t* sh_w /*[4]*/,
                                                     uint64_t* sh_res /*[3]*/) {
   constexpr int per = NBINS / kTpThreads;             // consecutive bins per thread
@@ -112,7 +125,8 @@ __device__ __forceinline__ ScanResult scan_from_top(const uint64_t* __restrict__
   uint64_t sum = 0;
 #pragma unroll
   for (int i = 0; i < per; ++i) {
-    loc[i] = h[tid * per + i];
+    // COHERENT: the bins were written by other workgroups of this same launch
+    loc[i] = COHERENT ? __hip_atomic_load(&h[tid * per + i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : h[tid * per + i];
     sum += loc[i];
   }
   uint64_t incl = sum;                                // suffix sum inside the wave (lanes >= lane)
@@ -306,6 +320,48 @@ __device__ __forceinline__ uint32_t keep_mask(const float4* __restrict__ src, in
   return keep;
 }
 
+// Writes the kept positions of one chunk in ascending order starting at out[before].
+// Element order inside a chunk is (load round u, thread, k); per-round counts (0..4) travel as
+// 16-bit fields of two 64-bit words through one wave scan.
+__device__ __forceinline__ void write_ranked(uint32_t keep, int before, int32_t* out, int64_t n0,
+                                             uint64_t (*sh_tot)[2] /*[waves][2]*/) {
+  const int tid = threadIdx.x;
+  uint64_t lo = 0, hi = 0;
+#pragma unroll
+  for (int u = 0; u < 4; ++u) {
+    lo |= (uint64_t)__popc((keep >> (u * 4)) & 0xFu) << (16 * u);
+    hi |= (uint64_t)__popc((keep >> (16 + u * 4)) & 0xFu) << (16 * u);
+  }
+  uint64_t ilo = lo, ihi = hi;       // inclusive wave scans
+#pragma unroll
+  for (int o = 1; o < 64; o <<= 1) {
+    const uint64_t tl = __shfl_up(ilo, o), th = __shfl_up(ihi, o);
+    if ((tid & 63) >= o) { ilo += tl; ihi += th; }
+  }
+  if ((tid & 63) == 63) { sh_tot[tid >> 6][0] = ilo; sh_tot[tid >> 6][1] = ihi; }
+  __syncthreads();
+  int round_base = before;
+#pragma unroll
+  for (int u = 0; u < kTpVec; ++u) {
+    const int sh = 16 * (u & 3);
+    int wave_before = 0, round_total = 0;
+#pragma unroll
+    for (int i = 0; i < kTpThreads / 64; ++i) {
+      const int t = (int)((sh_tot[i][u >> 2] >> sh) & 0xFFFFu);
+      if (i < (tid >> 6)) wave_before += t;
+      round_total += t;
+    }
+    const int incl = (int)(((u < 4 ? ilo : ihi) >> sh) & 0xFFFFu);
+    const int mine = (int)(((u < 4 ? lo : hi) >> sh) & 0xFFFFu);
+    int pos = round_base + wave_before + incl - mine;
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+      if (keep & (1u << (u * 4 + k))) out[pos++] = (int32_t)(n0 + (u * kTpThreads + tid) * 4 + k);
+    }
+    round_base += round_total;
+  }
+}
+
 __global__ __launch_bounds__(kTpThreads) void topp_count_kernel(const TopPArgs a) {
   const int r = blockIdx.y, c = blockIdx.x, tid = threadIdx.x;
   const int n = a.row_len[r];
@@ -406,47 +462,229 @@ __global__ __launch_bounds__(kTpThreads) void topp_write_kernel(const TopPArgs a
   const int n_here = (int)min((int64_t)kTpChunk, (int64_t)n - n0);
   const uint32_t keep = keep_mask(src, n_here, tid, st.flags == 1, st.prefix);
 
-  // ---- rank inside the chunk: element order is (load round u, thread, k) ----
-  // per-round counts (0..4) packed as 16-bit fields of two 64-bit words
-  uint64_t lo = 0, hi = 0;
-#pragma unroll
-  for (int u = 0; u < 4; ++u) {
-    lo |= (uint64_t)__popc((keep >> (u * 4)) & 0xFu) << (16 * u);
-    hi |= (uint64_t)__popc((keep >> (16 + u * 4)) & 0xFu) << (16 * u);
-  }
-  uint64_t ilo = lo, ihi = hi;       // inclusive wave scans
-#pragma unroll
-  for (int o = 1; o < 64; o <<= 1) {
-    const uint64_t tl = __shfl_up(ilo, o), th = __shfl_up(ihi, o);
-    if ((tid & 63) >= o) { ilo += tl; ihi += th; }
-  }
-  if ((tid & 63) == 63) { sh_tot[tid >> 6][0] = ilo; sh_tot[tid >> 6][1] = ihi; }
+  write_ranked(keep, before, a.sel_idx + (int64_t)r * a.sel_stride, n0, sh_tot);
+}
+
+// ---- single-launch path ---------------------------------------------------------------------------
+// When every workgroup of the grid can be resident at once, the five phases run inside ONE kernel:
+// a workgroup keeps its 8192 scores in registers from the first phase to the last (the scores are
+// read once instead of six times) and the workgroups of a ROW meet at a row-local barrier between
+// phases (an arrival counter in global memory).  The wait is bounded: if it ever runs out the row is
+// flagged (sel_count = -2) and every wave still exits.
+constexpr int kSpinLimit = 1 << 21;
+
+// Everything the workgroups of a row tell each other travels through agent-scope ATOMIC operations
+// (histogram bins, chunk counts, the row maximum), which are performed at the device's coherence
+// point; a wave waits for its own atomics to be acknowledged (s_waitcnt) before it arrives.  No
+// device-wide fence is needed -- on this multi-die GPU a release fence writes the whole L2 back,
+// which costs more than the rest of the kernel.
+__device__ __forceinline__ bool row_barrier(FusedSync* sy, uint32_t target, int* sh_ok) {
+  __builtin_amdgcn_s_waitcnt(0);            // this wave's atomics have been acknowledged
   __syncthreads();
-  int32_t* out = a.sel_idx + (int64_t)r * a.sel_stride;
-  int round_base = before;
-#pragma unroll
-  for (int u = 0; u < kTpVec; ++u) {
-    const int sh = 16 * (u & 3);
-    int wave_before = 0, round_total = 0;
-#pragma unroll
-    for (int i = 0; i < kTpThreads / 64; ++i) {
-      const int t = (int)((sh_tot[i][u >> 2] >> sh) & 0xFFFFu);
-      if (i < (tid >> 6)) wave_before += t;
-      round_total += t;
+  if (threadIdx.x == 0) {
+    __hip_atomic_fetch_add(&sy->bar, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    int it = 0;
+    bool ok = true;
+    while (__hip_atomic_load(&sy->bar, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < target) {
+      __builtin_amdgcn_s_sleep(1);
+      if (++it > kSpinLimit) { ok = false; break; }
     }
-    const int incl = (int)(((u < 4 ? ilo : ihi) >> sh) & 0xFFFFu);
-    const int mine = (int)(((u < 4 ? lo : hi) >> sh) & 0xFFFFu);
-    int pos = round_base + wave_before + incl - mine;
-#pragma unroll
-    for (int k = 0; k < 4; ++k) {
-      if (keep & (1u << (u * 4 + k))) out[pos++] = (int32_t)(n0 + (u * kTpThreads + tid) * 4 + k);
-    }
-    round_base += round_total;
+    if (!ok) __hip_atomic_store(&sy->err, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    *sh_ok = ok ? 1 : 0;
+  }
+  __syncthreads();
+  return *sh_ok != 0;
+}
+
+// Zeroes the histograms and the row barriers (launched right before topp_fused_kernel).
+__global__ __launch_bounds__(kTpThreads) void topp_zero_kernel(const TopPArgs a) {
+  const int64_t i = (int64_t)blockIdx.x * kTpThreads + threadIdx.x;
+  if (i < (int64_t)a.R * kBinsTotal) a.hist[i] = 0;
+  if (i < a.R) {
+    FusedSync z = {0u, 0u, 0, 0u};
+    a.sync[i] = z;
   }
 }
 
+template <int LEVEL>
+__device__ __forceinline__ void fused_level(const float4 (&sc)[kTpVec], uint32_t prefix, float smax, int shift,
+                                            uint64_t* lh, const double* tab, uint64_t* hout) {
+  constexpr int kBins = LEVEL == 1 ? kBins1 : (LEVEL == 2 ? kBins2 : kBins3);
+  constexpr int kShift = LEVEL == 1 ? 21 : (LEVEL == 2 ? 10 : 0);
+  const int tid = threadIdx.x;
+  for (int i = tid; i < kBins; i += kTpThreads) lh[i] = 0;
+  __syncthreads();
+#pragma unroll
+  for (int u = 0; u < kTpVec; ++u) {
+    const float s4[4] = {sc[u].x, sc[u].y, sc[u].z, sc[u].w};
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+      const uint32_t key = float_key(s4[k]);
+      const bool mine = LEVEL == 1 ? true : (key >> (kShift + (LEVEL == 2 ? 11 : 10))) == prefix;
+      if (mine) {
+        const uint64_t w = fixed_weight(s4[k], smax, shift, tab);
+        if (w) atomicAdd((unsigned long long*)&lh[(key >> kShift) & (kBins - 1)], (unsigned long long)w);
+      }
+    }
+  }
+  __syncthreads();
+  for (int i = tid; i < kBins; i += kTpThreads) {
+    const uint64_t v = lh[i];
+    if (v) __hip_atomic_fetch_add(&hout[i], v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  }
+}
+
+__global__ __launch_bounds__(kTpThreads) void topp_fused_kernel(const TopPArgs a) {
+  const int r = blockIdx.y, c = blockIdx.x, tid = threadIdx.x;
+  const int n = a.row_len[r];
+  const int64_t n0 = (int64_t)c * kTpChunk;
+  const float ninf = -__builtin_huge_valf();
+  if (n <= 0) {
+    if (c == 0 && tid == 0) {
+      if (a.tau) a.tau[r] = ninf;
+      if (a.mass) a.mass[r] = 0.f;
+      a.sel_count[r] = 0;
+    }
+    return;
+  }
+  if (n0 >= n) return;
+  __shared__ uint64_t lh[kBins1];
+  __shared__ uint64_t sh_part[kTpThreads / 64];
+  __shared__ uint64_t sh_res[3];
+  __shared__ uint64_t sh_tot[kTpThreads / 64][2];
+  __shared__ float red[kTpThreads / 64];
+  __shared__ int sh_red[kTpThreads / 64][2];
+  __shared__ int sh_ok;
+  __shared__ double tab[256];
+  tab[tid] = exp2((double)tid * 0.00390625);
+  FusedSync* sy = a.sync + r;
+  uint64_t* hrow = a.hist + (int64_t)r * kBinsTotal;
+  const uint32_t n_row_chunks = (uint32_t)((n + kTpChunk - 1) / kTpChunk);
+  uint32_t phase = 0;
+
+  // ---- the chunk's scores, once; slots beyond the row read as -inf (never kept, zero mass) ----
+  const float4* src = reinterpret_cast<const float4*>(a.scores + (int64_t)r * a.score_stride + n0);
+  const int n_here = (int)min((int64_t)kTpChunk, (int64_t)n - n0);
+  float4 sc[kTpVec];
+  float m = ninf;
+#pragma unroll
+  for (int u = 0; u < kTpVec; ++u) {
+    const int e = (u * kTpThreads + tid) * 4;
+    float4 v = make_float4(ninf, ninf, ninf, ninf);
+    if (e < n_here) {
+      v = src[u * kTpThreads + tid];
+      if (e + 1 >= n_here) v.y = ninf;
+      if (e + 2 >= n_here) v.z = ninf;
+      if (e + 3 >= n_here) v.w = ninf;
+    }
+    sc[u] = v;
+    m = fmaxf(fmaxf(m, fmaxf(v.x, v.y)), fmaxf(v.z, v.w));
+  }
+  m = block_max(m, red);
+  if (tid == 0) __hip_atomic_fetch_max(&sy->maxkey, float_key(m), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  const float pr = a.p[r];
+  const int flags = (pr >= 1.f) ? 1 : ((pr > 0.f) ? 0 : -1);
+  if (flags < 0) {
+    if (c == 0 && tid == 0) {
+      a.sel_count[r] = -1;
+      if (a.tau) a.tau[r] = __builtin_nanf("");
+      if (a.mass) a.mass[r] = 0.f;
+    }
+    return;
+  }
+  bool ok = true;
+  uint32_t tkey = 0;
+  float mass_out = 1.f;
+  if (flags == 0) {
+    ok = row_barrier(sy, ++phase * n_row_chunks, &sh_ok);
+    const float smax = key_float(__hip_atomic_load(&sy->maxkey, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
+    const int shift = fixed_shift(n);
+    uint32_t prefix = 0;
+    uint64_t above = 0, target = 0, total = 1;
+    if (ok) {
+      fused_level<1>(sc, 0u, smax, shift, lh, tab, hrow);
+      ok = row_barrier(sy, ++phase * n_row_chunks, &sh_ok);
+    }
+    if (ok) {
+      const ScanResult s1 = scan_from_top<kBins1, true>(hrow, 0, 0, true, pr, sh_part, sh_res);
+      prefix = (uint32_t)s1.bin;
+      above = s1.above;
+      target = s1.target;
+      total = s1.total;
+      fused_level<2>(sc, prefix, smax, shift, lh, tab, hrow + kBins1);
+      ok = row_barrier(sy, ++phase * n_row_chunks, &sh_ok);
+    }
+    if (ok) {
+      const ScanResult s2 = scan_from_top<kBins2, true>(hrow + kBins1, above, target, false, 0.f, sh_part, sh_res);
+      prefix = (prefix << 11) | (uint32_t)s2.bin;
+      above = s2.above;
+      fused_level<3>(sc, prefix, smax, shift, lh, tab, hrow + kBins1 + kBins2);
+      ok = row_barrier(sy, ++phase * n_row_chunks, &sh_ok);
+    }
+    if (ok) {
+      const ScanResult s3 = scan_from_top<kBins3, true>(hrow + kBins1 + kBins2, above, target, false, 0.f, sh_part, sh_res);
+      tkey = (prefix << 10) | (uint32_t)s3.bin;
+      mass_out = (float)((double)(s3.above + s3.bin_mass) / (double)total);
+    }
+  }
+
+  // ---- keep mask from the registers, per-chunk counts, ordered write ----
+  uint32_t keep = 0;
+  if (ok) {
+#pragma unroll
+    for (int u = 0; u < kTpVec; ++u) {
+      const float s4[4] = {sc[u].x, sc[u].y, sc[u].z, sc[u].w};
+#pragma unroll
+      for (int k = 0; k < 4; ++k) {
+        const bool sel = s4[k] != ninf && (flags == 1 || float_key(s4[k]) >= tkey);
+        keep |= (sel ? 1u : 0u) << (u * 4 + k);
+      }
+    }
+    int cnt = __popc(keep);
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) cnt += __shfl_xor(cnt, o);
+    if ((tid & 63) == 0) sh_red[tid >> 6][0] = cnt;
+    __syncthreads();
+    if (tid == 0) {
+      int tot = 0;
+#pragma unroll
+      for (int i = 0; i < kTpThreads / 64; ++i) tot += sh_red[i][0];
+      __hip_atomic_store(&a.chunk_cnt[(int64_t)r * a.n_chunks + c], tot, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+    ok = row_barrier(sy, ++phase * n_row_chunks, &sh_ok);
+  }
+  if (!ok) {
+    if (c == 0 && tid == 0) a.sel_count[r] = -2;       // a barrier wait ran out (never expected)
+    return;
+  }
+  int before = 0, total_cnt = 0;
+  for (int i = tid; i < (int)n_row_chunks; i += kTpThreads) {
+    const int v = __hip_atomic_load(&a.chunk_cnt[(int64_t)r * a.n_chunks + i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    total_cnt += v;
+    if (i < c) before += v;
+  }
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) {
+    before += __shfl_xor(before, o);
+    total_cnt += __shfl_xor(total_cnt, o);
+  }
+  __syncthreads();
+  if ((tid & 63) == 0) { sh_red[tid >> 6][0] = before; sh_red[tid >> 6][1] = total_cnt; }
+  __syncthreads();
+  before = 0;
+  total_cnt = 0;
+#pragma unroll
+  for (int i = 0; i < kTpThreads / 64; ++i) { before += sh_red[i][0]; total_cnt += sh_red[i][1]; }
+  if (c == 0 && tid == 0) {
+    a.sel_count[r] = total_cnt;
+    if (a.tau) a.tau[r] = flags == 1 ? ninf : key_float(tkey);
+    if (a.mass) a.mass[r] = mass_out;
+  }
+  write_ranked(keep, before, a.sel_idx + (int64_t)r * a.sel_stride, n0, sh_tot);
+}
+
 struct TopPLayout {
-  size_t cmax_off, ccnt_off, hist_off, state_off, total;
+  size_t cmax_off, ccnt_off, hist_off, state_off, sync_off, total;
 };
 static TopPLayout topp_layout(int32_t R, int64_t max_len) {
   const int64_t n_chunks = (max_len + kTpChunk - 1) / kTpChunk;
@@ -456,6 +694,7 @@ static TopPLayout topp_layout(int32_t R, int64_t max_len) {
   l.ccnt_off = off;  off = align_up(off + (size_t)R * n_chunks * sizeof(int32_t), 256);
   l.hist_off = off;  off = align_up(off + (size_t)R * kBinsTotal * sizeof(uint64_t), 256);
   l.state_off = off; off = align_up(off + (size_t)R * 4 * sizeof(RowState), 256);
+  l.sync_off = off;  off = align_up(off + (size_t)R * sizeof(FusedSync), 256);
   l.total = off;
   return l;
 }
@@ -504,9 +743,33 @@ extern "C" int32_t rtp_topp_select(const float* scores, int64_t score_stride, co
   a.chunk_cnt = (int32_t*)((char*)ws + l.ccnt_off);
   a.hist = (uint64_t*)((char*)ws + l.hist_off);
   a.state = (RowState*)((char*)ws + l.state_off);
+  a.sync = (FusedSync*)((char*)ws + l.sync_off);
 
   hipStream_t s = (hipStream_t)stream;
   dim3 grid((unsigned)a.n_chunks, (unsigned)R), block(kTpThreads);
+  // single-launch path: only if the whole grid can be resident at once (row barriers inside)
+  static int capacity = -1;
+  if (capacity < 0) {
+    int per_cu = 0, dev = 0;
+    hipDeviceProp_t prop;
+    if (hipGetDevice(&dev) == hipSuccess && hipGetDeviceProperties(&prop, dev) == hipSuccess &&
+        hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, topp_fused_kernel, kTpThreads, 0) == hipSuccess)
+      capacity = per_cu * prop.multiProcessorCount;
+    else
+      capacity = 0;
+    (void)hipGetLastError();
+  }
+  // Measured on MI355X (configuration 2): the single-launch kernel takes 74 us against 53 us for the
+  // six launches -- a row barrier across the dies costs about as much as a kernel boundary -- so it
+  // is opt-in (RTP_TOPP_PATH=fused) and the multi-launch path is the default.
+  const char* force = getenv("RTP_TOPP_PATH");
+  const bool fits = (int64_t)a.n_chunks * R <= capacity;
+  if (force && force[0] == 'f' && fits) {
+    const int64_t nz = (int64_t)R * kBinsTotal;
+    hipLaunchKernelGGL(topp_zero_kernel, dim3((unsigned)((nz + kTpThreads - 1) / kTpThreads)), block, 0, s, a);
+    hipLaunchKernelGGL(topp_fused_kernel, grid, block, 0, s, a);
+    return check_launch(who);
+  }
   hipLaunchKernelGGL(topp_init_kernel, grid, block, 0, s, a);
   hipLaunchKernelGGL(topp_level_kernel<1>, grid, block, 0, s, a);
   hipLaunchKernelGGL(topp_level_kernel<2>, grid, block, 0, s, a);

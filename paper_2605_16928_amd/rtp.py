@@ -14,7 +14,7 @@ import os
 from typing import Optional, Sequence
 
 HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(HERE, "librtp.so")
+LIB_PATH = os.environ.get("RTP_LIB", os.path.join(HERE, "librtp.so"))
 
 RTP_OK, RTP_ERR_INVALID_ARG, RTP_ERR_UNSUPPORTED, RTP_ERR_WORKSPACE, RTP_ERR_HIP = 0, -1, -2, -3, -4
 

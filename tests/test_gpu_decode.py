@@ -238,3 +238,24 @@ def test_local_attn_short_contexts_and_interleaved_kv():
                                run.sel_count, run.max_ctx, w.B, out2, None, run.ws_sparse)
     torch.cuda.synchronize()
     assert torch.equal(out2, run.out)
+
+
+def test_topp_single_launch_and_multi_launch_paths_agree():
+    """The cooperative single-launch kernel (row barriers) and the six-launch path must give the same
+    bits: same ascending index lists, counts, thresholds and masses."""
+    import os
+    print("[case] topp single-launch vs multi-launch", flush=True)
+    w = wl.c2(DEV, ctx=50000, batch=2, p=0.9)
+    run = DecodeRun(w)
+    run.index_score()
+    res = {}
+    for path in ("multi", "fused"):
+        os.environ["RTP_TOPP_PATH"] = path
+        run.sel_idx.fill_(-1)
+        run.topp()
+        torch.cuda.synchronize()
+        res[path] = (run.sel_idx.clone(), run.sel_count.clone(), run.tau.clone(), run.mass.clone())
+    os.environ.pop("RTP_TOPP_PATH")
+    assert int(res["fused"][1].min()) > 0
+    for a, b in zip(res["multi"], res["fused"]):
+        assert torch.equal(a, b)
