@@ -95,24 +95,33 @@ const char* rtp_version(void);
  * qI_out (optional, bf16 [B, n_ret, n_q, 16]) receives the index queries used.
  *
  * max_ctx: host upper bound of ctx_len[] (sizes the grid).  score_stride >= max_ctx, multiple of 4;
- * `scores` 16-byte aligned.  No workspace.
+ * `scores` 16-byte aligned.
+ *
+ * topp_ws (optional): the workspace of the rtp_topp_select call that will consume these scores, sized
+ * by rtp_topp_workspace_bytes(B * n_ret * n_q, max_ctx) and INITIALISED (rtp_topp_workspace_init once
+ * after allocation; rtp_topp_select with level1_ready = 1 leaves it initialised again).  When given,
+ * the score pass also accumulates the first level of the selector's mass histogram while the scores
+ * are in registers, and the following rtp_topp_select(..., level1_ready = 1, same workspace, row_len =
+ * ctx_len of each row, max_len = max_ctx) skips its first two launches.
  */
 int32_t rtp_index_score(const rtp_layer_desc* layer, const void* q_in, const float* WQ,
                         const void* kI, int64_t kI_head_stride,
                         const int64_t* seq_start, const int32_t* ctx_len, const int32_t* q_start,
                         int32_t B, int32_t n_q, int64_t max_ctx,
-                        float* scores, int64_t score_stride, void* qI_out, void* stream);
+                        float* scores, int64_t score_stride, void* qI_out,
+                        void* topp_ws, size_t topp_ws_bytes, void* stream);
 
 /* ---------------------------------------------------------------------------------------------
- * (2) Dynamic top-p selection -- Sec. 3.2 (S = Top-P(s, p)) and Sec. 3.4 (sort-free thresholding:
- * "the score threshold at which the cumulative attention mass reaches p").
+ * (2) Dynamic top-p selection -- Sec. 3.2 (S = Top-P(s, p)) and Sec. 3.4 (the threshold is found
+ * without sorting, as the score where the descending cumulative softmax mass first reaches p).
  *
  * For each of R independent rows: w_n = exp(s_n - max_n s_n), Z = sum w_n; the selected set is
  * { n : s_n >= tau } where tau is the largest score whose descending cumulative mass reaches p * Z.
  * This is the smallest such set up to ties AT tau, all of which are kept.  The search is a three-level
  * radix histogram over the order-preserving 32-bit key of the fp32 score (exact: no sort, no sampling);
  * masses are accumulated as 64-bit fixed point of fp64 exponentials, so the result does not depend on
- * summation order.
+ * summation order.  Scores of magnitude >= 64 lose mass resolution gradually (the fixed-point reference
+ * of a score is the upper edge of its coarse bin, and those bins are 16 or more wide).
  *
  *   scores    fp32 [R, score_stride] (16-byte aligned, score_stride multiple of 4); row r uses
  *             entries [0, row_len[r]); -inf entries are never selected.
@@ -122,12 +131,18 @@ int32_t rtp_index_score(const rtp_layer_desc* layer, const void* q_in, const flo
  *   sel_idx   out, int32 [R, sel_stride], sel_stride >= max_len; the selected positions in
  *             ascending order (the result is deterministic: same inputs, same bits).
  *   sel_count out, int32 [R].   tau, mass: optional outputs fp32 [R] (threshold score; selected mass / Z).
+ *   level1_ready  0: the call is self-contained and the workspace contents do not matter.
+ *             1: rtp_index_score has accumulated the first histogram level into this (initialised)
+ *             workspace; the call starts at level 2 and leaves the workspace initialised for the next step.
  */
 size_t rtp_topp_workspace_bytes(int32_t R, int64_t max_len);
+/* Zero-fills a top-p workspace (needed once before it is first handed to rtp_index_score). */
+int32_t rtp_topp_workspace_init(void* ws, size_t ws_bytes, void* stream);
 int32_t rtp_topp_select(const float* scores, int64_t score_stride, const int32_t* row_len,
                         const float* p, int32_t R, int64_t max_len,
                         int32_t* sel_idx, int64_t sel_stride, int32_t* sel_count,
-                        float* tau, float* mass, void* ws, size_t ws_bytes, void* stream);
+                        float* tau, float* mass, int32_t level1_ready,
+                        void* ws, size_t ws_bytes, void* stream);
 
 /* ---------------------------------------------------------------------------------------------
  * (3) Exact softmax attention over the selected tokens, decode, retrieval heads only --

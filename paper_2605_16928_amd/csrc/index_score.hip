@@ -6,7 +6,11 @@
 // query, lanes 2i and 2i+1 exchange their partial sums through DPP, and even/odd lanes write the
 // scores of two consecutive load rounds, which keeps the fp32 stores full-line as well.
 // Algorithmic traffic: 32 B read + 4 B written per (token, retrieval head).
-#include "common.h"
+//
+// Optionally the pass also accumulates the first level of the top-p mass histogram of every row
+// (topp_common.h) while the scores are still in registers: the exponentials run in the shadow of the
+// HBM stream and the selector then starts at its second level.
+#include "topp_common.h"
 
 namespace rtp {
 
@@ -38,6 +42,7 @@ struct IndexScoreArgs {
   float* scores;
   int64_t score_stride;
   uint16_t* qI_out;
+  uint64_t* hist;          // level-1 histograms [rows, kBinsTotal] or NULL
   int32_t ret_heads[64];
 };
 
@@ -53,6 +58,7 @@ __device__ __forceinline__ float dot8(const u32x4 v, const float (&q)[8]) {
   return acc;
 }
 
+template <bool HIST>
 __global__ __launch_bounds__(kIsThreads) void index_score_kernel(const IndexScoreArgs a) {
   const int bj = blockIdx.z;
   const int b = bj / a.n_ret, j = bj - b * a.n_ret, t = blockIdx.y;
@@ -60,6 +66,14 @@ __global__ __launch_bounds__(kIsThreads) void index_score_kernel(const IndexScor
   const int64_t n0 = (int64_t)blockIdx.x * kIsChunk;
   if (n0 >= n_ctx) return;
   const int tid = threadIdx.x;
+
+  __shared__ uint64_t lh[HIST ? kBins1 : 1];
+  __shared__ double tab[HIST ? 256 : 1];
+  if (HIST) {
+    for (int i = tid; i < kBins1; i += kIsThreads) lh[i] = 0;
+    fill_exp_table(tab);
+  }
+  const int shift = fixed_shift(n_ctx);
 
   // ---- the index query of this row: 16 floats in LDS (bf16 values) ----
   __shared__ float sq[kIndexDim];
@@ -126,8 +140,15 @@ __global__ __launch_bounds__(kIsThreads) void index_score_kernel(const IndexScor
       const int tok = (((batch * kIsBatch + u + half) * kIsThreads) + tid) >> 1;
       float val = (half ? d1 : d0) * a.index_scale;
       if (tok >= lim_here) val = ninf;
-      if (tok < n_here) dst[tok] = val;
+      if (tok < n_here) {
+        dst[tok] = val;
+        if (HIST) level1_add(lh, val, shift, tab);
+      }
     }
+  }
+  if (HIST) {
+    __syncthreads();
+    flush_hist(lh, a.hist + ((int64_t)bj * a.n_q + t) * kBinsTotal, kBins1, kIsThreads);
   }
 }
 
@@ -139,7 +160,8 @@ extern "C" int32_t rtp_index_score(const rtp_layer_desc* layer, const void* q_in
                                    const void* kI, int64_t kI_head_stride,
                                    const int64_t* seq_start, const int32_t* ctx_len, const int32_t* q_start,
                                    int32_t B, int32_t n_q, int64_t max_ctx,
-                                   float* scores, int64_t score_stride, void* qI_out, void* stream) {
+                                   float* scores, int64_t score_stride, void* qI_out,
+                                   void* topp_ws, size_t topp_ws_bytes, void* stream) {
   const char* who = "rtp_index_score";
   int32_t rc = check_layer(layer, who);
   if (rc != RTP_OK) return rc;
@@ -154,10 +176,21 @@ extern "C" int32_t rtp_index_score(const rtp_layer_desc* layer, const void* q_in
     return fail(RTP_ERR_INVALID_ARG, "%s: score_stride must be >= max_ctx and a multiple of 4", who);
   if (((uintptr_t)scores & 15) || ((uintptr_t)kI & 15) || (kI_head_stride & 7) || kI_head_stride < 0)
     return fail(RTP_ERR_INVALID_ARG, "%s: scores/kI must be 16-byte aligned, kI_head_stride a multiple of 8", who);
+  uint64_t* hist = nullptr;
+  if (topp_ws) {
+    const int64_t rows = (int64_t)B * layer->n_ret * n_q;
+    if (rows > 65535) return fail(RTP_ERR_INVALID_ARG, "%s: more than 65535 score rows", who);
+    const TopPLayout l = topp_layout((int32_t)rows, max_ctx);
+    if (((uintptr_t)topp_ws & 255) || topp_ws_bytes < l.total)
+      return fail(RTP_ERR_WORKSPACE, "%s: top-p workspace of %zu bytes (256-byte aligned) required, got %zu", who,
+                  l.total, topp_ws_bytes);
+    hist = (uint64_t*)((char*)topp_ws + l.hist_off);
+  }
   clear_error();
   if (layer->n_ret == 0) return RTP_OK;
 
   IndexScoreArgs a;
+  a.hist = hist;
   a.q_in = (const uint16_t*)q_in;
   a.WQ = WQ;
   a.kI = (const uint16_t*)kI;
@@ -175,6 +208,7 @@ extern "C" int32_t rtp_index_score(const rtp_layer_desc* layer, const void* q_in
   for (int j = 0; j < 64; ++j) a.ret_heads[j] = j < layer->n_ret ? layer->ret_heads[j] : 0;
 
   dim3 grid((unsigned)((max_ctx + kIsChunk - 1) / kIsChunk), (unsigned)n_q, (unsigned)(B * layer->n_ret));
-  hipLaunchKernelGGL(index_score_kernel, grid, dim3(kIsThreads), 0, (hipStream_t)stream, a);
+  if (hist) hipLaunchKernelGGL(index_score_kernel<true>, grid, dim3(kIsThreads), 0, (hipStream_t)stream, a);
+  else hipLaunchKernelGGL(index_score_kernel<false>, grid, dim3(kIsThreads), 0, (hipStream_t)stream, a);
   return check_launch(who);
 }

@@ -1,0 +1,78 @@
+// Pieces of the top-p threshold search shared by the selector (topp.hip) and the score pass
+// (index_score.hip), which can accumulate the first histogram level while it produces the scores.
+//
+// The search works on the order-preserving 32-bit key of an fp32 score, in three radix levels of
+// 11 + 11 + 10 bits.  A level histograms softmax MASS per bin.  Masses are 64-bit integers:
+//   w = floor-rounded( exp(s - ref) * 2^shift ),  ref = the upper edge of the element's LEVEL-1 bin,
+// so that no row maximum is needed before the first pass (every bin has its own reference, exp <= 1)
+// and sums do not depend on the order in which atomics land.  The scan of level 1 rescales the bins to
+// a common reference in fp64; levels 2 and 3 live inside one level-1 bin and stay pure integer.
+#pragma once
+
+#include "common.h"
+
+namespace rtp {
+
+constexpr int kBins1 = 2048, kBins2 = 2048, kBins3 = 1024;
+constexpr int kBinsTotal = kBins1 + kBins2 + kBins3;
+
+// weights are <= 1 and a row has n of them: n * 2^shift must stay below 2^63
+__device__ __forceinline__ int fixed_shift(int n) {
+  const int lg = 32 - __clz(max(n, 2) - 1);      // ceil(log2 n)
+  return min(52, 62 - lg);
+}
+
+// Upper edge (as a finite float) of level-1 bin `bin` = the reference of every score in that bin.
+__device__ __forceinline__ float bin_ref(int bin) {
+  const float f = key_float(((uint32_t)bin << 21) | 0x1fffffu);
+  const uint32_t u = __float_as_uint(f);
+  if ((u & 0x7f800000u) == 0x7f800000u) return __uint_as_float((u & 0x80000000u) | 0x7f7fffffu);   // inf/nan bins
+  return f;
+}
+
+// 2^(j/256), j < 256: the table behind fixed_weight (256 threads fill it, then a barrier).
+__device__ __forceinline__ void fill_exp_table(double* tab) {
+  if (threadIdx.x < 256) tab[threadIdx.x] = exp2((double)threadIdx.x * 0.00390625);
+}
+
+// exp(s - ref) * 2^shift as an integer, s <= ref.  exp in fp64 as 2^n * T[j] * P(t):
+// y = x * log2(e) = n + j/256 + f, P a degree-4 polynomial in t = f * ln 2 < 2.8e-3 (~1e-15 relative).
+__device__ __forceinline__ uint64_t fixed_weight(float s, float ref, int shift, const double* __restrict__ tab) {
+  const double x = (double)s - (double)ref;          // exact
+  if (!(x >= -60.0)) return 0;                        // below 2^-86: under the fixed-point resolution
+  const double y = fmin(x, 0.0) * 1.4426950408889634;
+  const double n = floor(y);
+  const double f = y - n;                             // [0, 1)
+  const int j = min((int)(f * 256.0), 255);
+  const double t = (f - (double)j * 0.00390625) * 0.6931471805599453;
+  double pl = fma(t, 1.0 / 24.0, 1.0 / 6.0);
+  pl = fma(t, pl, 0.5);
+  pl = fma(t, pl, 1.0);
+  pl = fma(t, pl, 1.0);
+  return (uint64_t)__double2ull_rn(ldexp(tab[j] * pl, shift + (int)n));
+}
+
+// Adds one score to a level-1 LDS histogram (2048 x u64).  -inf scores carry no mass.
+__device__ __forceinline__ void level1_add(uint64_t* lh, float s, int shift, const double* tab) {
+  if (s == -__builtin_huge_valf()) return;
+  const int bin = (int)(float_key(s) >> 21);
+  const uint64_t w = fixed_weight(s, bin_ref(bin), shift, tab);
+  if (w) atomicAdd((unsigned long long*)&lh[bin], (unsigned long long)w);
+}
+
+// Adds the non-empty bins of an LDS histogram to a global one.
+__device__ __forceinline__ void flush_hist(const uint64_t* lh, uint64_t* gh, int nbins, int nthreads) {
+  for (int i = threadIdx.x; i < nbins; i += nthreads) {
+    const uint64_t v = lh[i];
+    if (v) atomicAdd((unsigned long long*)&gh[i], (unsigned long long)v);
+  }
+}
+
+// Workspace of one rtp_topp_select call (R rows of at most max_len scores).  rtp_index_score uses
+// the same layout when it is asked to accumulate level 1.
+struct TopPLayout {
+  size_t ccnt_off, hist_off, state_off, total;
+};
+TopPLayout topp_layout(int32_t R, int64_t max_len);
+
+}  // namespace rtp

@@ -21,7 +21,7 @@ RTP_OK, RTP_ERR_INVALID_ARG, RTP_ERR_UNSUPPORTED, RTP_ERR_WORKSPACE, RTP_ERR_HIP
 EXPORTS = [
     "rtp_last_error", "rtp_version",
     "rtp_index_score",
-    "rtp_topp_workspace_bytes", "rtp_topp_select",
+    "rtp_topp_workspace_bytes", "rtp_topp_workspace_init", "rtp_topp_select",
     "rtp_sparse_attn_decode_workspace_bytes", "rtp_sparse_attn_decode",
     "rtp_sparse_attn_prefill_workspace_bytes", "rtp_sparse_attn_prefill",
     "rtp_local_attn_workspace_bytes", "rtp_local_attn",
@@ -73,11 +73,13 @@ def lib() -> C.CDLL:
     L.rtp_version.restype = C.c_char_p
     L.rtp_version.argtypes = []
     L.rtp_index_score.restype = i32
-    L.rtp_index_score.argtypes = [dp, vp, vp, vp, i64, vp, vp, vp, i32, i32, i64, vp, i64, vp, vp]
+    L.rtp_index_score.argtypes = [dp, vp, vp, vp, i64, vp, vp, vp, i32, i32, i64, vp, i64, vp, vp, sz, vp]
     L.rtp_topp_workspace_bytes.restype = sz
     L.rtp_topp_workspace_bytes.argtypes = [i32, i64]
     L.rtp_topp_select.restype = i32
-    L.rtp_topp_select.argtypes = [vp, i64, vp, vp, i32, i64, vp, i64, vp, vp, vp, vp, sz, vp]
+    L.rtp_topp_select.argtypes = [vp, i64, vp, vp, i32, i64, vp, i64, vp, vp, vp, i32, vp, sz, vp]
+    L.rtp_topp_workspace_init.restype = i32
+    L.rtp_topp_workspace_init.argtypes = [vp, sz, vp]
     L.rtp_sparse_attn_decode_workspace_bytes.restype = sz
     L.rtp_sparse_attn_decode_workspace_bytes.argtypes = [dp, i32, i64]
     L.rtp_sparse_attn_decode.restype = i32
@@ -131,21 +133,25 @@ def rtp_last_error() -> str:
 
 
 def rtp_index_score(layer, q_in, WQ, kI, kI_head_stride, seq_start, ctx_len, q_start, B, n_q, max_ctx,
-                    scores, score_stride, qI_out=None, stream=None):
+                    scores, score_stride, qI_out=None, topp_ws=None, stream=None):
     _check(lib().rtp_index_score(C.byref(layer), _ptr(q_in), _ptr(WQ), _ptr(kI), kI_head_stride, _ptr(seq_start),
                                  _ptr(ctx_len), _ptr(q_start), B, n_q, max_ctx, _ptr(scores), score_stride,
-                                 _ptr(qI_out), _stream(stream)))
+                                 _ptr(qI_out), _ptr(topp_ws), _nbytes(topp_ws), _stream(stream)))
 
 
 def rtp_topp_workspace_bytes(R, max_len) -> int:
     return lib().rtp_topp_workspace_bytes(R, max_len)
 
 
+def rtp_topp_workspace_init(ws, stream=None):
+    _check(lib().rtp_topp_workspace_init(_ptr(ws), _nbytes(ws), _stream(stream)))
+
+
 def rtp_topp_select(scores, score_stride, row_len, p, R, max_len, sel_idx, sel_stride, sel_count,
-                    tau, mass, ws, stream=None):
+                    tau, mass, ws, level1_ready=0, stream=None):
     _check(lib().rtp_topp_select(_ptr(scores), score_stride, _ptr(row_len), _ptr(p), R, max_len, _ptr(sel_idx),
-                                 sel_stride, _ptr(sel_count), _ptr(tau), _ptr(mass), _ptr(ws), _nbytes(ws),
-                                 _stream(stream)))
+                                 sel_stride, _ptr(sel_count), _ptr(tau), _ptr(mass), level1_ready, _ptr(ws),
+                                 _nbytes(ws), _stream(stream)))
 
 
 def rtp_sparse_attn_decode_workspace_bytes(layer, B, max_sel) -> int:

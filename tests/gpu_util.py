@@ -35,8 +35,11 @@ def i64(x):
 class DecodeRun:
     """Device buffers for one decode workload and the C-ABI calls on them."""
 
-    def __init__(self, w: wl.DecodeWorkload):
+    def __init__(self, w: wl.DecodeWorkload, fuse_level1: bool = True):
+        """fuse_level1: the score pass accumulates the selector's first histogram level (the
+        configuration the benchmark times); False runs the two calls independently."""
         self.w = w
+        self.fuse_level1 = fuse_level1
         L = w.layer
         self.desc = layer_desc_of(L)
         self.B, self.n_ret = w.B, L.n_ret
@@ -54,6 +57,8 @@ class DecodeRun:
         self.out = torch.zeros((self.B, L.n_q_heads, 128), dtype=torch.bfloat16, device=DEV)
         self.lse = torch.zeros((self.B, L.n_q_heads), dtype=torch.float32, device=DEV)
         self.ws_topp = ws_alloc(rtp.rtp_topp_workspace_bytes(max(self.R, 1), self.max_ctx))
+        rtp.rtp_topp_workspace_init(self.ws_topp)
+        self._level1_pending = False
         self.ws_sparse = ws_alloc(rtp.rtp_sparse_attn_decode_workspace_bytes(self.desc, self.B, self.max_ctx))
         self.ws_local = ws_alloc(rtp.rtp_local_attn_workspace_bytes(self.desc, self.B, 1, self.max_ctx))
         self.ws_dense = ws_alloc(rtp.rtp_dense_attn_workspace_bytes(self.desc, self.B, 1, self.max_ctx))
@@ -63,14 +68,27 @@ class DecodeRun:
     def index_score(self):
         w = self.w
         q_in = w.q_pre if w.WQ is not None else w.qI
+        fuse = self.fuse_level1 and not self._level1_pending and self.R > 0
         rtp.rtp_index_score(self.desc, q_in, w.WQ, w.kI, self.T_tot * 16, self.seq_start, self.ctx_len, None,
-                            self.B, 1, self.max_ctx, self.scores, self.stride, self.qI_out)
+                            self.B, 1, self.max_ctx, self.scores, self.stride, self.qI_out,
+                            self.ws_topp if fuse else None)
+        self._level1_pending = self._level1_pending or fuse
+
+    def index_score_fused_timing(self, scratch):
+        """The fused score pass on its own, for timing: level 1 goes to a scratch workspace."""
+        w = self.w
+        q_in = w.q_pre if w.WQ is not None else w.qI
+        rtp.rtp_index_score(self.desc, q_in, w.WQ, w.kI, self.T_tot * 16, self.seq_start, self.ctx_len, None,
+                            self.B, 1, self.max_ctx, self.scores, self.stride, self.qI_out, scratch)
 
     def topp(self, scores=None, p_rows=None):
         s = self.scores if scores is None else scores
         p = self.w.p_rows if p_rows is None else p_rows
+        ready = 1 if (self._level1_pending and scores is None) else 0
         rtp.rtp_topp_select(s, self.stride, self.row_len, p, self.R, self.max_ctx, self.sel_idx, self.stride,
-                            self.sel_count, self.tau, self.mass, self.ws_topp)
+                            self.sel_count, self.tau, self.mass, self.ws_topp, level1_ready=ready)
+        if ready:
+            self._level1_pending = False
 
     def sparse_attn(self, sel_idx=None, sel_count=None, max_sel=None):
         w = self.w
@@ -102,12 +120,14 @@ class DecodeRun:
         indexer / top-p chain and write disjoint output rows."""
         main = torch.cuda.current_stream()
         fork, join = torch.cuda.Event(), torch.cuda.Event()
+        # the score pass saturates HBM on its own; the local heads start once it is done and overlap
+        # the top-p launches, which leave HBM idle
+        self.index_score()
         fork.record(main)
         side.wait_event(fork)
         with torch.cuda.stream(side):
             self.local_attn()
             join.record(side)
-        self.index_score()
         self.topp()
         self.sparse_attn()
         main.wait_event(join)

@@ -73,6 +73,11 @@ def test_index_score_argument_checks():
         if k == "max_ctx" and v > 64:
             bad["score_stride"] = v + 3
         _expect(rtp.RTP_ERR_INVALID_ARG, rtp.rtp_index_score, L, **bad)
+    # a top-p workspace handed to the score pass must be large enough
+    lib = rtp.lib()
+    rc = lib.rtp_index_score(C.byref(L), C.c_void_p(A), None, C.c_void_p(A), 16 * 64, C.c_void_p(A), C.c_void_p(A), None,
+                             1, 1, 64, C.c_void_p(A), 64, None, C.c_void_p(A), 256, None)
+    assert rc == rtp.RTP_ERR_WORKSPACE
 
 
 def test_topp_argument_and_workspace_checks():
@@ -83,9 +88,9 @@ def test_topp_argument_and_workspace_checks():
     vp = C.c_void_p
 
     def call(scores=A, stride=1000, row_len=A, p=A, R=4, max_len=1000, sel=A, sel_stride=1000, cnt=A, ws=A,
-             ws_bytes=need):
+             ws_bytes=need, ready=0):
         return lib.rtp_topp_select(vp(scores), stride, vp(row_len), vp(p), R, max_len, vp(sel), sel_stride, vp(cnt),
-                                   None, None, vp(ws), ws_bytes, None)
+                                   None, None, ready, vp(ws), ws_bytes, None)
 
     assert call(scores=None) == rtp.RTP_ERR_INVALID_ARG
     assert call(R=0) == rtp.RTP_ERR_INVALID_ARG
@@ -93,10 +98,14 @@ def test_topp_argument_and_workspace_checks():
     assert call(stride=1002) == rtp.RTP_ERR_INVALID_ARG
     assert call(sel_stride=999) == rtp.RTP_ERR_INVALID_ARG
     assert call(max_len=(1 << 24) + 4, stride=(1 << 24) + 4, sel_stride=(1 << 24) + 4) == rtp.RTP_ERR_INVALID_ARG
+    assert call(ready=2) == rtp.RTP_ERR_INVALID_ARG
     assert call(ws=None) == rtp.RTP_ERR_WORKSPACE
     assert call(ws=A + 8) == rtp.RTP_ERR_WORKSPACE
     assert call(ws_bytes=need - 1) == rtp.RTP_ERR_WORKSPACE
     assert b"workspace" in lib.rtp_last_error()
+    assert lib.rtp_topp_workspace_init(None, 1024, None) == rtp.RTP_ERR_WORKSPACE
+    assert lib.rtp_topp_workspace_init(vp(A + 8), 1024, None) == rtp.RTP_ERR_WORKSPACE
+    assert lib.rtp_topp_workspace_init(vp(A), 1023, None) == rtp.RTP_ERR_WORKSPACE
 
 
 def test_attention_argument_and_workspace_checks():
