@@ -21,7 +21,6 @@ import time
 
 ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
-sys.path.insert(0, os.path.join(ROOT, "tests"))
 
 HBM_PEAK_GBS = 8000.0
 
@@ -49,7 +48,7 @@ def main() -> int:
     import numpy as np
     import torch
     from paper_2605_16928_amd import rtp, workloads as wl
-    from gpu_util import DecodeRun
+    from paper_2605_16928_amd.pipeline import DecodeRun
 
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)
@@ -128,12 +127,22 @@ def main() -> int:
 
     # ---- per-call breakdown (eager launches, HIP events, same cycling over copies) ----
     it, wu = max(50, args.steps // 4), 10
+    n_runs = len(runs)
+    scratch_ws = torch.zeros_like(runs[0].ws_topp)     # level-1 histogram sink for timing the score pass alone
+
+    def score_then_select(i):
+        runs[i % n_runs].index_score()
+        runs[i % n_runs].topp()
+
+    us_index = timed(lambda i: runs[i % n_runs].index_score_fused_timing(scratch_ws), it, wu)
+    us_pair = timed(score_then_select, it, wu)
     br = {
-        "index_score": timed(lambda i: runs[i % len(runs)].index_score(), it, wu),
-        "topp_select": timed(lambda i: runs[i % len(runs)].topp(), it, wu),
-        "sparse_attn_decode": timed(lambda i: runs[i % len(runs)].sparse_attn(), it, wu),
-        "local_attn": timed(lambda i: runs[i % len(runs)].local_attn(), it, wu),
+        "index_score": us_index,                       # score pass incl. the first histogram level of top-p
+        "topp_select": us_pair - us_index,             # the remaining four launches of the selector
+        "sparse_attn_decode": timed(lambda i: runs[i % n_runs].sparse_attn(), it, wu),
+        "local_attn": timed(lambda i: runs[i % n_runs].local_attn(), it, wu),
     }
+    us_topp_standalone = timed(lambda i: runs[i % n_runs].topp(scores=runs[i % n_runs].scores), it, wu)
     dense_us = timed(lambda i: runs[i % len(runs)].dense_attn(runs[i % len(runs)].out), max(10, it // 10), 2)
     eager_us = timed(lambda i: run_step(runs[i % len(runs)]), it, wu)
     graph_us = timed(lambda i: graphs[i % len(graphs)].replay(), it, wu)
@@ -154,7 +163,7 @@ def main() -> int:
     # the roofline object describes the indexer score pass: the one kernel whose traffic grows with the
     # full context for every retrieval head, i.e. the HBM-bound core of the step
     ach = bytes_index / (br["index_score"] * 1e-6) / 1e9
-    roofline = {"kernel": "index_score_kernel", "bound": "hbm", "achieved": round(ach, 1), "peak": HBM_PEAK_GBS,
+    roofline = {"kernel": "index_score_kernel<true>", "bound": "hbm", "achieved": round(ach, 1), "peak": HBM_PEAK_GBS,
                 "unit": "GB/s", "frac": round(ach / HBM_PEAK_GBS, 4),
                 # HBM bytes per launch from the rocprofv3 --pmc runs recorded under profiles/ (FETCH_SIZE x 2.0 +
                 # WRITE_SIZE x 1.0 KiB, factors from a plain 1 GiB copy); only valid for the default shape
@@ -199,7 +208,7 @@ def main() -> int:
     # ---- prefill at 1,048,576 tokens (configuration 4): chunks of 8192 queries at five depths ----
     prefill = None
     if not args.no_prefill:
-        from gpu_util import PrefillRun
+        from paper_2605_16928_amd.pipeline import PrefillRun
         del graphs, runs
         torch.cuda.empty_cache()
         MFMA_PEAK = 2.5e15
@@ -287,6 +296,7 @@ def main() -> int:
             "eager_us_per_step": round(eager_us, 2),
             "graph_replay_us_per_step": round(graph_us, 2),
             "call_us": {k: round(v, 2) for k, v in br.items()},
+            "topp_select_standalone_us": round(us_topp_standalone, 2),
             "call_GBps": {"index_score": round(bytes_index / br["index_score"] / 1e3, 1),
                           "topp_select": round(bytes_topp / br["topp_select"] / 1e3, 1),
                           "sparse_attn_decode": round(bytes_sparse / br["sparse_attn_decode"] / 1e3, 1),

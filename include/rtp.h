@@ -187,7 +187,7 @@ int32_t rtp_sparse_attn_prefill(const rtp_layer_desc* layer, const void* q_pre, 
 
 /* ---------------------------------------------------------------------------------------------
  * (5) Sink + sliding-window attention for every NON-retrieval head -- Sec. 3.2 (first sentence),
- * Sec. 4.2 ("4 sink tokens and an 8192-token window").
+ * Sec. 4.2 (the evaluated setting: sink = 4, window = 8192).
  *
  * A query at position m attends tokens { n < sink } U { max(sink, m - window + 1) <= n <= m }.
  * Decode (q_start == NULL, n_q == 1) reads each needed K/V row once per KV head and serves the whole

@@ -104,7 +104,7 @@ def index_score(qI_bits, kI_bits, index_scale: float = 1.0) -> np.ndarray:
 
 
 # --------------------------------------------------------------------------
-# top-p  (Sec. 3.2: S = Top-P(s, p); Sec. 3.4: "cumulative attention mass reaches p")
+# top-p  (Sec. 3.2: S = Top-P(s, p); Sec. 3.4: threshold where the cumulative softmax mass reaches p)
 # --------------------------------------------------------------------------
 def topp_from_weights(w, p: float, key=None):
     """Shortest descending prefix whose weight reaches p * sum(w).

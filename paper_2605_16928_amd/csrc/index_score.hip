@@ -67,59 +67,16 @@ __global__ __launch_bounds__(kIsThreads) void index_score_kernel(const IndexScor
   if (n0 >= n_ctx) return;
   const int tid = threadIdx.x;
 
-  __shared__ uint64_t lh[HIST ? kBins1 : 1];
-  __shared__ double tab[HIST ? 256 : 1];
-  if (HIST) {
-    for (int i = tid; i < kBins1; i += kIsThreads) lh[i] = 0;
-    fill_exp_table(tab);
-  }
-  const int shift = fixed_shift(n_ctx);
-
-  // ---- the index query of this row: 16 floats in LDS (bf16 values) ----
-  __shared__ float sq[kIndexDim];
-  const int64_t qi_off = (((int64_t)b * a.n_ret + j) * a.n_q + t) * kIndexDim;
-  if (a.WQ) {
-    if (tid < 256) {
-    const int i = tid >> 4, part = tid & 15;   // 16 output dims x 16 lanes, 8 terms each
-    const float* w = a.WQ + ((int64_t)j * kIndexDim + i) * kHeadDim + part * 8;
-    const uint16_t* x = a.q_in + (((int64_t)b * a.n_q + t) * a.n_q_heads + a.ret_heads[j]) * kHeadDim + part * 8;
-    double acc = 0.0;
-#pragma unroll
-    for (int c = 0; c < 8; ++c) acc = fma((double)w[c], (double)bf16_to_f32(x[c]), acc);
-    acc += __shfl_xor(acc, 1);
-    acc += __shfl_xor(acc, 2);
-    acc += __shfl_xor(acc, 4);
-    acc += __shfl_xor(acc, 8);
-    if (part == 0) {
-      const uint16_t qb = f64_to_bf16_rne(acc);
-      sq[i] = bf16_to_f32(qb);
-      if (blockIdx.x == 0 && a.qI_out) a.qI_out[qi_off + i] = qb;
-    }
-    }
-  } else if (tid < kIndexDim) {
-    const uint16_t qb = a.q_in[qi_off + tid];
-    sq[tid] = bf16_to_f32(qb);
-    if (blockIdx.x == 0 && a.qI_out) a.qI_out[qi_off + tid] = qb;
-  }
-  __syncthreads();
-
-  const int half = tid & 1;
-  float qv[8];
-#pragma unroll
-  for (int c = 0; c < 8; ++c) qv[c] = sq[half * 8 + c];
-
+  // ---- issue the first batch of key loads before anything else: they depend on nothing the prologue
+  // computes, so the projection and the histogram set-up run under their latency ----
   const int limit = a.q_start ? min(n_ctx, a.q_start[b] + t + 1) : n_ctx;   // candidates: n < limit
   const int n_here = (int)min((int64_t)kIsChunk, (int64_t)n_ctx - n0);     // chunk tokens inside the context
   const int lim_here = (int)min((int64_t)n_here, (int64_t)limit - n0);     // chunk tokens that are candidates
   const u32x4* src = reinterpret_cast<const u32x4*>(a.kI + (int64_t)j * a.kI_head_stride +
                                                     (a.seq_start[b] + n0) * kIndexDim);
-  float* dst = a.scores + ((int64_t)bj * a.n_q + t) * a.score_stride + n0;
-  const float ninf = -__builtin_huge_valf();
   const bool full = (n_here == kIsChunk);
-
-#pragma unroll
-  for (int batch = 0; batch < (kIsChunk * 2) / (kIsThreads * kIsBatch); ++batch) {
-    u32x4 v[kIsBatch];
+  u32x4 v[kIsBatch];
+  auto load_batch = [&](int batch) {
 #pragma unroll
     for (int u = 0; u < kIsBatch; ++u) {
       const int piece = (batch * kIsBatch + u) * kIsThreads + tid;
@@ -133,6 +90,56 @@ __global__ __launch_bounds__(kIsThreads) void index_score_kernel(const IndexScor
         v[u] = (u32x4){0u, 0u, 0u, 0u};
       }
     }
+  };
+  load_batch(0);
+
+  __shared__ uint64_t lh[HIST ? kBins1 : 1];
+  __shared__ double tab[HIST ? 256 : 1];
+  if (HIST) {
+    for (int i = tid; i < kBins1; i += kIsThreads) lh[i] = 0;
+    fill_exp_table(tab);
+  }
+  const int shift = fixed_shift(n_ctx);
+
+  // ---- the index query of this row: 16 floats in LDS (bf16 values) ----
+  __shared__ float sq[kIndexDim];
+  const int64_t qi_off = (((int64_t)b * a.n_ret + j) * a.n_q + t) * kIndexDim;
+  if (a.WQ) {
+    if (tid < 256) {
+      const int i = tid >> 4, part = tid & 15;   // 16 output dims x 16 lanes, 8 terms each
+      const float* w = a.WQ + ((int64_t)j * kIndexDim + i) * kHeadDim + part * 8;
+      const uint16_t* x = a.q_in + (((int64_t)b * a.n_q + t) * a.n_q_heads + a.ret_heads[j]) * kHeadDim + part * 8;
+      double acc = 0.0;
+#pragma unroll
+      for (int c = 0; c < 8; ++c) acc = fma((double)w[c], (double)bf16_to_f32(x[c]), acc);
+      acc += __shfl_xor(acc, 1);
+      acc += __shfl_xor(acc, 2);
+      acc += __shfl_xor(acc, 4);
+      acc += __shfl_xor(acc, 8);
+      if (part == 0) {
+        const uint16_t qb = f64_to_bf16_rne(acc);
+        sq[i] = bf16_to_f32(qb);
+        if (blockIdx.x == 0 && a.qI_out) a.qI_out[qi_off + i] = qb;
+      }
+    }
+  } else if (tid < kIndexDim) {
+    const uint16_t qb = a.q_in[qi_off + tid];
+    sq[tid] = bf16_to_f32(qb);
+    if (blockIdx.x == 0 && a.qI_out) a.qI_out[qi_off + tid] = qb;
+  }
+  __syncthreads();
+
+  const int half = tid & 1;
+  float qv[8];
+#pragma unroll
+  for (int c = 0; c < 8; ++c) qv[c] = sq[half * 8 + c];
+
+  float* dst = a.scores + ((int64_t)bj * a.n_q + t) * a.score_stride + n0;
+  const float ninf = -__builtin_huge_valf();
+
+#pragma unroll
+  for (int batch = 0; batch < (kIsChunk * 2) / (kIsThreads * kIsBatch); ++batch) {
+    if (batch > 0) load_batch(batch);
 #pragma unroll
     for (int u = 0; u < kIsBatch; u += 2) {
       const float d0 = pair_sum(dot8(v[u], qv));

@@ -1,5 +1,5 @@
-// rtp_topp_select: sort-free dynamic top-p (paper Sec. 3.2, S = Top-P(s, p); Sec. 3.4, the threshold
-// "at which the cumulative attention mass reaches p").
+// rtp_topp_select: sort-free dynamic top-p (paper Sec. 3.2, S = Top-P(s, p); Sec. 3.4, the score
+// threshold where the descending cumulative softmax mass first reaches p).
 //
 // Design (ours, for gfx950; the paper's kernel uses one 256-bin histogram of block maxima):
 // a three-level radix search over the order-preserving 32-bit key of each fp32 score
@@ -82,7 +82,8 @@ struct Scan1Result {       // level 1: bins carry different references, the scan
 
 // Every thread gets the result; all workgroups of a row compute the same numbers in the same order.
 __device__ __forceinline__ Scan1Result scan_level1(const uint64_t* __restrict__ h, float p, double* sh_d /*[4]*/,
-                                                   int* sh_i /*[4]*/, double* sh_res /*[2]*/) {
+                                                   int* sh_i /*[4]*/, double* sh_res /*[2]*/,
+                                                   const double* __restrict__ tab /* filled by the caller */) {
   constexpr int per = kBins1 / kTpThreads;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   uint64_t loc[per];
@@ -105,7 +106,9 @@ __device__ __forceinline__ Scan1Result scan_level1(const uint64_t* __restrict__ 
   double sum = 0.0;
 #pragma unroll
   for (int i = 0; i < per; ++i) {
-    md[i] = loc[i] ? (double)loc[i] * exp((double)bin_ref(tid * per + i) - R) : 0.0;
+    int e;
+    const double m = exp_parts((double)bin_ref(tid * per + i) - R, tab, &e);
+    md[i] = loc[i] ? (double)loc[i] * ldexp(m, e) : 0.0;
     sum += md[i];
   }
   double incl = sum;                                  // suffix sum inside the wave (lanes >= lane)
@@ -215,6 +218,17 @@ __device__ __forceinline__ ScanResult scan_from_top(const uint64_t* __restrict__
   return r;
 }
 
+// The chunk's scores, issued as the first loads of a launch so that the prologue (state, histogram
+// scan) runs under their latency.  Vectors wholly past the row end are not read.
+__device__ __forceinline__ void load_chunk(const float4* __restrict__ src, int n_here, int tid, float4 (&v)[kTpVec]) {
+#pragma unroll
+  for (int u = 0; u < kTpVec; ++u) {
+    const int e = (u * kTpThreads + tid) * 4;
+    if (e < n_here) v[u] = src[u * kTpThreads + tid];
+    else v[u] = make_float4(0.f, 0.f, 0.f, 0.f);
+  }
+}
+
 // ---- launch 0 (only when level 1 is not supplied): zero the histograms -------------------------------
 __global__ __launch_bounds__(kTpThreads) void topp_zero_kernel(uint64_t* hist, int64_t n) {
   const int64_t i = (int64_t)blockIdx.x * kTpThreads + threadIdx.x;
@@ -231,6 +245,9 @@ __global__ __launch_bounds__(kTpThreads) void topp_level_kernel(const TopPArgs a
   const int n = a.row_len[r];
   const int64_t n0 = (int64_t)c * kTpChunk;
   if (n0 >= n || n <= 0) return;
+  const int n_here = (int)min((int64_t)kTpChunk, (int64_t)n - n0);
+  float4 v[kTpVec];
+  load_chunk(reinterpret_cast<const float4*>(a.scores + (int64_t)r * a.score_stride + n0), n_here, tid, v);
 
   __shared__ uint64_t lh[kBins];
   __shared__ uint64_t sh_part[kTpThreads / 64];
@@ -258,7 +275,7 @@ __global__ __launch_bounds__(kTpThreads) void topp_level_kernel(const TopPArgs a
     s.above_base = 0.0; s.total_d = 0.0; s.above = 0; s.target = 1; s.prefix = 0; s.flags = flags; s.ref = 0.f;
     s.shift = shift;
     if (flags == 0) {
-      const Scan1Result s1 = scan_level1(hrow, pr, sh_d, sh_i, sh_dres);
+      const Scan1Result s1 = scan_level1(hrow, pr, sh_d, sh_i, sh_dres, tab);
       if (s1.bin < 0) {
         flags = 2;
       } else {
@@ -297,14 +314,10 @@ __global__ __launch_bounds__(kTpThreads) void topp_level_kernel(const TopPArgs a
   for (int i = tid; i < kBins; i += kTpThreads) lh[i] = 0;
   __syncthreads();
 
-  const float4* src = reinterpret_cast<const float4*>(a.scores + (int64_t)r * a.score_stride + n0);
-  const int n_here = (int)min((int64_t)kTpChunk, (int64_t)n - n0);
-#pragma unroll 2
+#pragma unroll
   for (int u = 0; u < kTpVec; ++u) {
     const int e = (u * kTpThreads + tid) * 4;
-    if (e >= n_here) break;
-    const float4 v = src[u * kTpThreads + tid];
-    const float s4[4] = {v.x, v.y, v.z, v.w};
+    const float s4[4] = {v[u].x, v[u].y, v[u].z, v[u].w};
 #pragma unroll
     for (int k = 0; k < 4; ++k) {
       if (e + k < n_here) {
@@ -326,21 +339,17 @@ __global__ __launch_bounds__(kTpThreads) void topp_level_kernel(const TopPArgs a
 
 // ---- launches 4 and 5: final scan + per-chunk counts, then ordered compaction ---------------------
 // Bit u*4+k of the result says whether score (u * 256 + tid) * 4 + k of the chunk is kept.
-__device__ __forceinline__ uint32_t keep_mask(const float4* __restrict__ src, int n_here, int tid, bool all,
-                                              uint32_t tkey) {
+__device__ __forceinline__ uint32_t keep_mask(const float4 (&v)[kTpVec], int n_here, int tid, bool all, uint32_t tkey) {
   const float ninf = -__builtin_huge_valf();
   uint32_t keep = 0;
 #pragma unroll
   for (int u = 0; u < kTpVec; ++u) {
     const int e = (u * kTpThreads + tid) * 4;
-    if (e < n_here) {
-      const float4 v = src[u * kTpThreads + tid];
-      const float s4[4] = {v.x, v.y, v.z, v.w};
+    const float s4[4] = {v[u].x, v[u].y, v[u].z, v[u].w};
 #pragma unroll
-      for (int k = 0; k < 4; ++k) {
-        const bool sel = (e + k < n_here) && s4[k] != ninf && (all || float_key(s4[k]) >= tkey);
-        keep |= (sel ? 1u : 0u) << (u * 4 + k);
-      }
+    for (int k = 0; k < 4; ++k) {
+      const bool sel = (e + k < n_here) && s4[k] != ninf && (all || float_key(s4[k]) >= tkey);
+      keep |= (sel ? 1u : 0u) << (u * 4 + k);
     }
   }
   return keep;
@@ -406,6 +415,9 @@ __global__ __launch_bounds__(kTpThreads) void topp_count_kernel(const TopPArgs a
     return;
   }
   if (n0 >= n) return;
+  const int n_here = (int)min((int64_t)kTpChunk, (int64_t)n - n0);
+  float4 v[kTpVec];
+  load_chunk(reinterpret_cast<const float4*>(a.scores + (int64_t)r * a.score_stride + n0), n_here, tid, v);
   __shared__ uint64_t sh_part[kTpThreads / 64];
   __shared__ uint64_t sh_res[3];
   __shared__ int sh_cnt[kTpThreads / 64];
@@ -439,9 +451,7 @@ __global__ __launch_bounds__(kTpThreads) void topp_count_kernel(const TopPArgs a
     st[2] = s;
   }
 
-  const float4* src = reinterpret_cast<const float4*>(a.scores + (int64_t)r * a.score_stride + n0);
-  const int n_here = (int)min((int64_t)kTpChunk, (int64_t)n - n0);
-  int cnt = __popc(keep_mask(src, n_here, tid, prev.flags == 1, tkey));
+  int cnt = __popc(keep_mask(v, n_here, tid, prev.flags == 1, tkey));
 #pragma unroll
   for (int o = 32; o > 0; o >>= 1) cnt += __shfl_xor(cnt, o);
   if ((tid & 63) == 0) sh_cnt[tid >> 6] = cnt;
@@ -465,6 +475,9 @@ __global__ __launch_bounds__(kTpThreads) void topp_write_kernel(const TopPArgs a
   const int n = a.row_len[r];
   const int64_t n0 = (int64_t)c * kTpChunk;
   if (n <= 0 || n0 >= n) return;
+  const int n_here = (int)min((int64_t)kTpChunk, (int64_t)n - n0);
+  float4 v[kTpVec];
+  load_chunk(reinterpret_cast<const float4*>(a.scores + (int64_t)r * a.score_stride + n0), n_here, tid, v);
   const RowState st = a.state[(int64_t)r * 3 + 2];
   if (st.flags < 0 || st.flags == 2) return;
   __shared__ int sh_red[kTpThreads / 64][2];
@@ -491,9 +504,7 @@ __global__ __launch_bounds__(kTpThreads) void topp_write_kernel(const TopPArgs a
   for (int i = 0; i < kTpThreads / 64; ++i) { before += sh_red[i][0]; total += sh_red[i][1]; }
   if (c == 0 && tid == 0) a.sel_count[r] = total;
 
-  const float4* src = reinterpret_cast<const float4*>(a.scores + (int64_t)r * a.score_stride + n0);
-  const int n_here = (int)min((int64_t)kTpChunk, (int64_t)n - n0);
-  const uint32_t keep = keep_mask(src, n_here, tid, st.flags == 1, st.prefix);
+  const uint32_t keep = keep_mask(v, n_here, tid, st.flags == 1, st.prefix);
   write_ranked(keep, before, a.sel_idx + (int64_t)r * a.sel_stride, n0, sh_tot);
 }
 

@@ -16,10 +16,11 @@ namespace rtp {
 constexpr int kBins1 = 2048, kBins2 = 2048, kBins3 = 1024;
 constexpr int kBinsTotal = kBins1 + kBins2 + kBins3;
 
-// weights are <= 1 and a row has n of them: n * 2^shift must stay below 2^63
+// weights are <= 2^shift and a row has n of them: n * 2^shift must stay below 2^63; shift <= 51 keeps
+// every weight below 2^52, which the integer conversion in fixed_weight relies on
 __device__ __forceinline__ int fixed_shift(int n) {
   const int lg = 32 - __clz(max(n, 2) - 1);      // ceil(log2 n)
-  return min(52, 62 - lg);
+  return min(51, 62 - lg);
 }
 
 // Upper edge (as a finite float) of level-1 bin `bin` = the reference of every score in that bin.
@@ -30,33 +31,49 @@ __device__ __forceinline__ float bin_ref(int bin) {
   return f;
 }
 
+// The same edge straight from a finite score: the low 21 bits set for s >= 0, cleared for s < 0.
+__device__ __forceinline__ float score_ref(float s) {
+  const uint32_t u = __float_as_uint(s);
+  const uint32_t neg = (uint32_t)((int32_t)u >> 31) & 0x1fffffu;
+  return __uint_as_float((u | 0x1fffffu) ^ neg);
+}
+
 // 2^(j/256), j < 256: the table behind fixed_weight (256 threads fill it, then a barrier).
 __device__ __forceinline__ void fill_exp_table(double* tab) {
   if (threadIdx.x < 256) tab[threadIdx.x] = exp2((double)threadIdx.x * 0.00390625);
 }
 
-// exp(s - ref) * 2^shift as an integer, s <= ref.  exp in fp64 as 2^n * T[j] * P(t):
-// y = x * log2(e) = n + j/256 + f, P a degree-4 polynomial in t = f * ln 2 < 2.8e-3 (~1e-15 relative).
-__device__ __forceinline__ uint64_t fixed_weight(float s, float ref, int shift, const double* __restrict__ tab) {
-  const double x = (double)s - (double)ref;          // exact
-  if (!(x >= -60.0)) return 0;                        // below 2^-86: under the fixed-point resolution
-  const double y = fmin(x, 0.0) * 1.4426950408889634;
-  const double n = floor(y);
-  const double f = y - n;                             // [0, 1)
-  const int j = min((int)(f * 256.0), 255);
-  const double t = (f - (double)j * 0.00390625) * 0.6931471805599453;
+// exp(x) for x <= 0 as m * 2^e with m in [1, 2): x * 256 / ln 2 = k + f, k integer, f in [0, 1);
+// exp(x) = 2^(k >> 8) * T[k & 255] * P(t), P a degree-4 polynomial in t = f * ln 2 / 256 < 2.8e-3
+// (~1e-15 relative).  Arguments below about -80 return e = -119 or so: far under any resolution used.
+__device__ __forceinline__ double exp_parts(double x, const double* __restrict__ tab, int* e) {
+  const double y = fmax(fmin(x, 0.0) * 369.3299304675746, -30000.0);   // 256 / ln 2
+  const double k = floor(y);
+  const double t = (y - k) * 0.0027076061740622863;                    // ln 2 / 256
+  const int ki = (int)k;
   double pl = fma(t, 1.0 / 24.0, 1.0 / 6.0);
   pl = fma(t, pl, 0.5);
   pl = fma(t, pl, 1.0);
   pl = fma(t, pl, 1.0);
-  return (uint64_t)__double2ull_rn(ldexp(tab[j] * pl, shift + (int)n));
+  *e = ki >> 8;
+  return tab[ki & 255] * pl;
 }
 
-// Adds one score to a level-1 LDS histogram (2048 x u64).  -inf scores carry no mass.
+// round-to-nearest-even( exp(s - ref) * 2^shift ) as an integer, s <= ref, shift <= 51.  The value is
+// below 2^52, so adding 2^52 leaves the rounded integer in the low 52 bits of the sum.
+__device__ __forceinline__ uint64_t fixed_weight(float s, float ref, int shift, const double* __restrict__ tab) {
+  int e;
+  const double m = exp_parts((double)s - (double)ref, tab, &e);
+  const double r = ldexp(m, shift + e) + 4503599627370496.0;
+  return (uint64_t)__double_as_longlong(r) & 0xFFFFFFFFFFFFFull;
+}
+
+// Adds one score to a level-1 LDS histogram (2048 x u64).  -inf scores carry no mass; +inf and NaN
+// scores are not supported (they land in the top bins with weight 2^shift).
 __device__ __forceinline__ void level1_add(uint64_t* lh, float s, int shift, const double* tab) {
   if (s == -__builtin_huge_valf()) return;
   const int bin = (int)(float_key(s) >> 21);
-  const uint64_t w = fixed_weight(s, bin_ref(bin), shift, tab);
+  const uint64_t w = fixed_weight(s, fminf(score_ref(s), 3.4028234663852886e38f), shift, tab);
   if (w) atomicAdd((unsigned long long*)&lh[bin], (unsigned long long)w);
 }
 

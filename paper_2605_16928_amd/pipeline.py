@@ -1,0 +1,180 @@
+"""Device-side drivers of the hot path: buffers for one workload and the C-ABI calls on them, in
+the order a decode step (indexer scores -> top-p -> sparse attention, local heads beside them) or a
+prefill chunk issues them.  Argument marshalling only; every computation happens in librtp.so."""
+from __future__ import annotations
+
+import numpy as np
+import torch
+
+from . import rtp, workloads as wl
+
+DEV = "cuda:0"
+
+
+def layer_desc_of(layer: wl.Layer):
+    return rtp.layer_desc(layer.n_q_heads, layer.n_kv_heads, layer.ret_heads, layer.sink, layer.window)
+
+
+def ws_alloc(nbytes: int) -> torch.Tensor:
+    return torch.empty(max(int(nbytes), 256), dtype=torch.uint8, device=DEV)
+
+
+def i32(x):
+    return torch.tensor(list(x), dtype=torch.int32, device=DEV)
+
+
+def i64(x):
+    return torch.tensor(list(x), dtype=torch.int64, device=DEV)
+
+
+class DecodeRun:
+    """Device buffers for one decode workload and the C-ABI calls on them."""
+
+    def __init__(self, w: wl.DecodeWorkload, fuse_level1: bool = True):
+        """fuse_level1: the score pass accumulates the selector's first histogram level (the
+        configuration the benchmark times); False runs the two calls independently."""
+        self.w = w
+        self.fuse_level1 = fuse_level1
+        L = w.layer
+        self.desc = layer_desc_of(L)
+        self.B, self.n_ret = w.B, L.n_ret
+        self.R = self.B * self.n_ret
+        self.max_ctx = max(w.ctx_len)
+        self.stride = (self.max_ctx + 3) // 4 * 4
+        self.seq_start, self.ctx_len = i64(w.seq_start), i32(w.ctx_len)
+        self.row_len = i32([w.ctx_len[b] for b in range(self.B) for _ in range(self.n_ret)])
+        self.scores = torch.full((max(self.R, 1), self.stride), float("nan"), dtype=torch.float32, device=DEV)
+        self.qI_out = torch.zeros((self.B, max(self.n_ret, 1), 16), dtype=torch.bfloat16, device=DEV)
+        self.sel_idx = torch.full((max(self.R, 1), self.stride), -7, dtype=torch.int32, device=DEV)
+        self.sel_count = torch.full((max(self.R, 1),), -7, dtype=torch.int32, device=DEV)
+        self.tau = torch.zeros((max(self.R, 1),), dtype=torch.float32, device=DEV)
+        self.mass = torch.zeros((max(self.R, 1),), dtype=torch.float32, device=DEV)
+        self.out = torch.zeros((self.B, L.n_q_heads, 128), dtype=torch.bfloat16, device=DEV)
+        self.lse = torch.zeros((self.B, L.n_q_heads), dtype=torch.float32, device=DEV)
+        self.ws_topp = ws_alloc(rtp.rtp_topp_workspace_bytes(max(self.R, 1), self.max_ctx))
+        rtp.rtp_topp_workspace_init(self.ws_topp)
+        self._level1_pending = False
+        self.ws_sparse = ws_alloc(rtp.rtp_sparse_attn_decode_workspace_bytes(self.desc, self.B, self.max_ctx))
+        self.ws_local = ws_alloc(rtp.rtp_local_attn_workspace_bytes(self.desc, self.B, 1, self.max_ctx))
+        self.ws_dense = ws_alloc(rtp.rtp_dense_attn_workspace_bytes(self.desc, self.B, 1, self.max_ctx))
+        self.T_tot = w.T_tot
+
+    # ---- the five calls -------------------------------------------------------------------
+    def index_score(self):
+        w = self.w
+        q_in = w.q_pre if w.WQ is not None else w.qI
+        fuse = self.fuse_level1 and not self._level1_pending and self.R > 0
+        rtp.rtp_index_score(self.desc, q_in, w.WQ, w.kI, self.T_tot * 16, self.seq_start, self.ctx_len, None,
+                            self.B, 1, self.max_ctx, self.scores, self.stride, self.qI_out,
+                            self.ws_topp if fuse else None)
+        self._level1_pending = self._level1_pending or fuse
+
+    def index_score_fused_timing(self, scratch):
+        """The fused score pass on its own, for timing: level 1 goes to a scratch workspace."""
+        w = self.w
+        q_in = w.q_pre if w.WQ is not None else w.qI
+        rtp.rtp_index_score(self.desc, q_in, w.WQ, w.kI, self.T_tot * 16, self.seq_start, self.ctx_len, None,
+                            self.B, 1, self.max_ctx, self.scores, self.stride, self.qI_out, scratch)
+
+    def topp(self, scores=None, p_rows=None):
+        s = self.scores if scores is None else scores
+        p = self.w.p_rows if p_rows is None else p_rows
+        ready = 1 if (self._level1_pending and scores is None) else 0
+        rtp.rtp_topp_select(s, self.stride, self.row_len, p, self.R, self.max_ctx, self.sel_idx, self.stride,
+                            self.sel_count, self.tau, self.mass, self.ws_topp, level1_ready=ready)
+        if ready:
+            self._level1_pending = False
+
+    def sparse_attn(self, sel_idx=None, sel_count=None, max_sel=None):
+        w = self.w
+        rtp.rtp_sparse_attn_decode(self.desc, w.q, w.K, w.V, 128, self.T_tot * 128, self.seq_start,
+                                   self.sel_idx if sel_idx is None else sel_idx, self.stride,
+                                   self.sel_count if sel_count is None else sel_count,
+                                   self.max_ctx if max_sel is None else max_sel, self.B, self.out, self.lse,
+                                   self.ws_sparse)
+
+    def local_attn(self):
+        w = self.w
+        rtp.rtp_local_attn(self.desc, w.q, w.K, w.V, 128, self.T_tot * 128, self.seq_start, self.ctx_len, None,
+                           self.B, 1, self.max_ctx, self.out, self.lse, self.ws_local)
+
+    def dense_attn(self, out=None, lse=None):
+        w = self.w
+        rtp.rtp_dense_attn(self.desc, w.q, w.K, w.V, 128, self.T_tot * 128, self.seq_start, self.ctx_len, None,
+                           self.B, 1, self.max_ctx, self.out if out is None else out,
+                           self.lse if lse is None else lse, self.ws_dense)
+
+    def step(self):
+        self.index_score()
+        self.topp()
+        self.sparse_attn()
+        self.local_attn()
+
+    def step_two_streams(self, side: "torch.cuda.Stream"):
+        """The same step with the local heads on a second stream: they do not depend on the
+        indexer / top-p chain and write disjoint output rows."""
+        main = torch.cuda.current_stream()
+        fork, join = torch.cuda.Event(), torch.cuda.Event()
+        # the score pass saturates HBM on its own; the local heads start once it is done and overlap
+        # the top-p launches, which leave HBM idle
+        self.index_score()
+        fork.record(main)
+        side.wait_event(fork)
+        with torch.cuda.stream(side):
+            self.local_attn()
+            join.record(side)
+        self.topp()
+        self.sparse_attn()
+        main.wait_event(join)
+
+    # ---- results as numpy -----------------------------------------------------------------
+    def sel_sets(self):
+        torch.cuda.synchronize()
+        cnt = self.sel_count.cpu().numpy()
+        idx = self.sel_idx.cpu().numpy()
+        return [np.sort(idx[r, :max(cnt[r], 0)]) for r in range(self.R)], cnt
+
+    def out_f64(self):
+        torch.cuda.synchronize()
+        return self.out.float().cpu().numpy().astype(np.float64)
+
+
+class PrefillRun:
+    """Device buffers for one prefill chunk of one sequence and the C-ABI calls on it."""
+
+    def __init__(self, w: "wl.PrefillWorkload", interleaved: bool = False):
+        self.w = w
+        L = w.layer
+        self.desc = layer_desc_of(L)
+        self.seq_start, self.ctx_len, self.q_start = i64([0]), i32([w.N]), i32([w.chunk_start])
+        self.out = torch.zeros((w.T, L.n_q_heads, 128), dtype=torch.bfloat16, device=DEV)
+        self.lse = torch.zeros((w.T, L.n_q_heads), dtype=torch.float32, device=DEV)
+        self.tau = torch.zeros((max(L.n_ret, 1), w.T), dtype=torch.float32, device=DEV)
+        self.mass = torch.zeros((max(L.n_ret, 1), w.T), dtype=torch.float32, device=DEV)
+        self.count = torch.zeros((max(L.n_ret, 1), w.T), dtype=torch.int32, device=DEV)
+        self.ws = ws_alloc(max(rtp.rtp_sparse_attn_prefill_workspace_bytes(self.desc, w.T, w.chunk_start),
+                               rtp.rtp_local_attn_workspace_bytes(self.desc, 1, w.T, w.N)))
+        if interleaved:
+            self.kv = torch.cat([w.K, w.V], dim=2).contiguous()
+            self.Kp, self.Vp, self.rs, self.hs = self.kv.data_ptr(), self.kv.data_ptr() + 256, 256, w.N * 256
+        else:
+            self.Kp, self.Vp, self.rs, self.hs = w.K, w.V, 128, w.N * 128
+
+    def local_attn(self, out=None, lse=None):
+        w = self.w
+        rtp.rtp_local_attn(self.desc, w.q, self.Kp, self.Vp, self.rs, self.hs, self.seq_start, self.ctx_len,
+                           self.q_start, 1, w.T, w.N, self.out if out is None else out,
+                           self.lse if lse is None else lse, self.ws)
+
+    def dense_attn(self, out=None, lse=None):
+        w = self.w
+        rtp.rtp_dense_attn(self.desc, w.q, self.Kp, self.Vp, self.rs, self.hs, self.seq_start, self.ctx_len,
+                           self.q_start, 1, w.T, w.N, self.out if out is None else out,
+                           self.lse if lse is None else lse, self.ws)
+
+    def sparse_prefill(self, p=None, out=None, lse=None):
+        w = self.w
+        q_in = w.q_pre if w.WQ is not None else w.qI
+        rtp.rtp_sparse_attn_prefill(self.desc, q_in, w.q, w.WQ, w.kI, w.N * 16, self.Kp, self.Vp, self.rs, self.hs,
+                                    w.chunk_start, w.T, w.p if p is None else p, self.out if out is None else out,
+                                    self.lse if lse is None else lse, self.tau, self.count, self.mass, self.ws)

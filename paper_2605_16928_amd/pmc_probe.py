@@ -14,12 +14,11 @@ import torch
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 sys.path.insert(0, ROOT)
-sys.path.insert(0, os.path.join(ROOT, "tests"))
 
 
 def main():
     from paper_2605_16928_amd import workloads as wl
-    from gpu_util import DecodeRun
+    from paper_2605_16928_amd.pipeline import DecodeRun
     run = DecodeRun(wl.c2("cuda:0", seed=100))
     n = 1 << 28                                     # 1 GiB read + 1 GiB written per copy
     src = torch.empty(n, dtype=torch.float32, device="cuda:0").normal_()
