@@ -311,26 +311,79 @@ __global__ __launch_bounds__(kTpThreads) void topp_level_kernel(const TopPArgs a
   }
   if (flags != 0) return;          // keep-all, invalid or empty rows need no histogram
 
+  // Levels 2 and 3 weigh only the members of the prefix bin (a few percent of the chunk at level 2,
+  // a handful at level 3).  At level 2, weighing them where they sit would run the fp64 arithmetic in
+  // nearly every wave instruction slot for one or two active lanes, so the members are first packed
+  // into an LDS list (order is irrelevant: integer masses) and then weighed densely.  At level 3 almost
+  // every slot is empty and skipped as it is; packing costs more than it saves there.
+  __shared__ float sh_list[LEVEL == 2 ? kTpChunk : 1];
+  __shared__ int sh_n;
+  static_assert(kTpVec * 4 <= 32, "member mask is one 32-bit word");
   for (int i = tid; i < kBins; i += kTpThreads) lh[i] = 0;
+  if (tid == 0) sh_n = 0;
   __syncthreads();
 
+  if (LEVEL == 1) {
 #pragma unroll
-  for (int u = 0; u < kTpVec; ++u) {
-    const int e = (u * kTpThreads + tid) * 4;
-    const float s4[4] = {v[u].x, v[u].y, v[u].z, v[u].w};
+    for (int u = 0; u < kTpVec; ++u) {
+      const int e = (u * kTpThreads + tid) * 4;
+      const float s4[4] = {v[u].x, v[u].y, v[u].z, v[u].w};
 #pragma unroll
-    for (int k = 0; k < 4; ++k) {
-      if (e + k < n_here) {
-        if (LEVEL == 1) {
-          level1_add(lh, s4[k], shift, tab);
-        } else {
-          const uint32_t key = float_key(s4[k]);
-          if ((key >> (kShift + (LEVEL == 2 ? 11 : 10))) == prefix && s4[k] != -__builtin_huge_valf()) {
-            const uint64_t w = fixed_weight(s4[k], ref, shift, tab);
-            if (w) atomicAdd((unsigned long long*)&lh[(key >> kShift) & (kBins - 1)], (unsigned long long)w);
-          }
+      for (int k = 0; k < 4; ++k)
+        if (e + k < n_here) level1_add(lh, s4[k], shift, tab);
+    }
+  } else if (LEVEL == 3) {
+#pragma unroll
+    for (int u = 0; u < kTpVec; ++u) {
+      const int e = (u * kTpThreads + tid) * 4;
+      const float s4[4] = {v[u].x, v[u].y, v[u].z, v[u].w};
+#pragma unroll
+      for (int k = 0; k < 4; ++k) {
+        const uint32_t key = float_key(s4[k]);
+        if (e + k < n_here && (key >> 10) == prefix && s4[k] != -__builtin_huge_valf()) {
+          const uint64_t w = fixed_weight(s4[k], ref, shift, tab);
+          if (w) atomicAdd((unsigned long long*)&lh[key & (kBins - 1)], (unsigned long long)w);
         }
       }
+    }
+  } else {
+    constexpr int kAbove = kShift + 11;                          // key bits of the prefix start here
+    uint32_t member = 0;
+#pragma unroll
+    for (int u = 0; u < kTpVec; ++u) {
+      const int e = (u * kTpThreads + tid) * 4;
+      const float s4[4] = {v[u].x, v[u].y, v[u].z, v[u].w};
+#pragma unroll
+      for (int k = 0; k < 4; ++k) {
+        const bool in = (e + k < n_here) && (float_key(s4[k]) >> kAbove) == prefix && s4[k] != -__builtin_huge_valf();
+        member |= (in ? 1u : 0u) << (u * 4 + k);
+      }
+    }
+    const int lane = tid & 63;
+    const int cnt = __popc(member);
+    int incl = cnt;
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+      const int t = __shfl_up(incl, o);
+      if (lane >= o) incl += t;
+    }
+    int base = 0;
+    if (lane == 63 && incl > 0) base = atomicAdd(&sh_n, incl);
+    base = __shfl(base, 63);
+    int pos = base + incl - cnt;
+#pragma unroll
+    for (int u = 0; u < kTpVec; ++u) {
+      const float s4[4] = {v[u].x, v[u].y, v[u].z, v[u].w};
+#pragma unroll
+      for (int k = 0; k < 4; ++k)
+        if (member & (1u << (u * 4 + k))) sh_list[pos++] = s4[k];
+    }
+    __syncthreads();
+    const int total = sh_n;
+    for (int i = tid; i < total; i += kTpThreads) {
+      const float sv = sh_list[i];
+      const uint64_t w = fixed_weight(sv, ref, shift, tab);
+      if (w) atomicAdd((unsigned long long*)&lh[(float_key(sv) >> kShift) & (kBins - 1)], (unsigned long long)w);
     }
   }
   __syncthreads();

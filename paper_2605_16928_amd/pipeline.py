@@ -30,11 +30,20 @@ def i64(x):
 class DecodeRun:
     """Device buffers for one decode workload and the C-ABI calls on them."""
 
-    def __init__(self, w: wl.DecodeWorkload, fuse_level1: bool = True):
+    def __init__(self, w: wl.DecodeWorkload, fuse_level1: bool = True, interleaved: bool = False):
         """fuse_level1: the score pass accumulates the selector's first histogram level (the
-        configuration the benchmark times); False runs the two calls independently."""
+        configuration the benchmark times); False runs the two calls independently.
+        interleaved: keep the K and V rows of a token next to each other ([Hkv, T, 2, 128], one
+        512-byte piece per gathered token) instead of in two tensors; the workload's own K and V
+        are released."""
         self.w = w
         self.fuse_level1 = fuse_level1
+        if interleaved:
+            self.kv = torch.stack([w.K, w.V], dim=2).contiguous()
+            T = w.K.shape[1]
+            self.Kp, self.Vp, self.kv_rs, self.kv_hs = self.kv.data_ptr(), self.kv.data_ptr() + 256, 256, T * 256
+        else:
+            self.Kp, self.Vp, self.kv_rs, self.kv_hs = w.K, w.V, 128, w.K.shape[1] * 128
         L = w.layer
         self.desc = layer_desc_of(L)
         self.B, self.n_ret = w.B, L.n_ret
@@ -87,7 +96,7 @@ class DecodeRun:
 
     def sparse_attn(self, sel_idx=None, sel_count=None, max_sel=None):
         w = self.w
-        rtp.rtp_sparse_attn_decode(self.desc, w.q, w.K, w.V, 128, self.T_tot * 128, self.seq_start,
+        rtp.rtp_sparse_attn_decode(self.desc, w.q, self.Kp, self.Vp, self.kv_rs, self.kv_hs, self.seq_start,
                                    self.sel_idx if sel_idx is None else sel_idx, self.stride,
                                    self.sel_count if sel_count is None else sel_count,
                                    self.max_ctx if max_sel is None else max_sel, self.B, self.out, self.lse,
@@ -95,12 +104,12 @@ class DecodeRun:
 
     def local_attn(self):
         w = self.w
-        rtp.rtp_local_attn(self.desc, w.q, w.K, w.V, 128, self.T_tot * 128, self.seq_start, self.ctx_len, None,
+        rtp.rtp_local_attn(self.desc, w.q, self.Kp, self.Vp, self.kv_rs, self.kv_hs, self.seq_start, self.ctx_len, None,
                            self.B, 1, self.max_ctx, self.out, self.lse, self.ws_local)
 
     def dense_attn(self, out=None, lse=None):
         w = self.w
-        rtp.rtp_dense_attn(self.desc, w.q, w.K, w.V, 128, self.T_tot * 128, self.seq_start, self.ctx_len, None,
+        rtp.rtp_dense_attn(self.desc, w.q, self.Kp, self.Vp, self.kv_rs, self.kv_hs, self.seq_start, self.ctx_len, None,
                            self.B, 1, self.max_ctx, self.out if out is None else out,
                            self.lse if lse is None else lse, self.ws_dense)
 
