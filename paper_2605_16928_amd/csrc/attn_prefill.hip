@@ -16,6 +16,8 @@
 // are adjacent in the grid so that they meet in L2; late (long) query tiles are scheduled first.
 #include "common.h"
 
+#include <type_traits>
+
 namespace rtp {
 
 constexpr int kPfThreads = 256;
@@ -457,6 +459,457 @@ __global__ __launch_bounds__(kPfThreads, 2) void flash_prefill_kernel(const Pref
   }
 }
 
+// ---- the wide kernel: dense and local modes ---------------------------------------------------------
+// Same data flow as above with TWO 32-query column blocks per wave (64 consecutive queries per wave,
+// 256 per workgroup).  Every A operand read from LDS (a K row block, a V^T row block) feeds two MFMAs,
+// which halves the LDS operand traffic per flop -- the 32-query version spends its time waiting on
+// the LDS read port (about 240 of its 256 bytes per clock at a third of the MFMA peak) -- and halves
+// the global->LDS tile traffic per flop as well.  The price is registers (2 x 64 output accumulators,
+// 64 for the two Q operand sets): one wave per SIMD, the accumulators in AGPRs.
+//
+// With a single wave per SIMD nothing hides latency by itself, so the loop is software-pipelined over
+// 32-key blocks: while the softmax of block i runs on the vector ALU, the matrix pipe executes the PV
+// MFMAs of block i-1; the two are independent instruction streams inside one basic block and are
+// interleaved with scheduling-group hints.  For that the accumulators must never be touched by the
+// vector ALU inside the loop (the register allocator would otherwise shuttle all 128 of them between
+// the two register files), so there is no running maximum: every query takes a FIXED reference
+// maximum from the scores of the first key tile and the probabilities are exp2(s - ref), which fp32 and
+// bf16 represent over +-126 binades.  After the pass the row sums tell whether a reference was off by
+// more than that leaves room for (sum outside [2^-60, 2^100], or not finite); the workgroup then
+// repeats its keys with the classical running-maximum recurrence (exact_pass).  Real score rows
+// have their maximum at the first tokens; the repeat exists for correctness, not for speed.
+// K/V tiles rotate through three LDS buffers (the PV of a tile's last block reads its V^T while the
+// next tile is current), one workgroup barrier per 64-key tile.
+constexpr int kPwQ = 256;
+constexpr int kPwStages = 3;
+// One staged tile: 64 K rows then 64 V rows, 256 bytes each, no padding -- the tiles are written by
+// direct global->LDS loads (16 bytes per lane, a wave's 64 lanes fill 1 KiB contiguously), so bank
+// spreading comes from the order of the 16-byte chunks inside a row instead: K row n keeps chunk c at
+// position c ^ (n % 16) (the MFMA operand read takes one chunk of 16 consecutive rows), V row n keeps
+// 32-byte unit u at position u ^ (n % 8) (the transposing operand read takes 32 bytes of 8 rows).
+constexpr int kPwTileBytes = 2 * kPfK * kHeadDim * 2;
+constexpr int kSmemWide = kPwTileBytes * kPwStages;
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+typedef short s16x8 __attribute__((ext_vector_type(8)));
+
+template <int MODE>
+__global__ __launch_bounds__(kPfThreads, 1) void flash_prefill_wide_kernel(const PrefillArgs a) {
+  constexpr bool LOCAL = MODE == kModeLocal;
+  __shared__ __attribute__((aligned(16))) unsigned char smem[kSmemWide];
+  unsigned char* const Ls = smem;       // stage s: K rows at Ls + s * kPwTileBytes, V rows 16 KiB further
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int g = lane >> 5, r = lane & 31;
+  const int h = a.heads[blockIdx.x];
+  const int n_splits = LOCAL ? 1 : a.n_splits;
+  const int b = blockIdx.z / n_splits;
+  const int split = blockIdx.z - b * n_splits;
+  const int t0 = ((int)gridDim.y - 1 - (int)blockIdx.y) * kPwQ;
+  const int kvh = h / (a.n_q_heads / a.n_kv_heads);
+  const int pos0 = a.q_start ? a.q_start[b] : (int)a.q_start_host;
+  const int64_t tok0 = a.seq_start ? a.seq_start[b] : 0;
+  const float ninf = -__builtin_huge_valf();
+
+  // ---- this lane's two queries (column r of each of the wave's two blocks) ----
+  int tq[2], mq[2];
+  bool qok[2];
+  int64_t qrow[2];
+  u32x4 qreg[2][8];
+#pragma unroll
+  for (int qb = 0; qb < 2; ++qb) {
+    tq[qb] = t0 + wave * 64 + qb * 32 + r;
+    qok[qb] = tq[qb] < a.n_q;
+    mq[qb] = pos0 + tq[qb];
+    qrow[qb] = (((int64_t)b * a.n_q + tq[qb]) * a.n_q_heads + h) * kHeadDim;
+#pragma unroll
+    for (int kk = 0; kk < 8; ++kk)
+      qreg[qb][kk] = qok[qb] ? *reinterpret_cast<const u32x4*>(a.q + qrow[qb] + kk * 16 + g * 8) : (u32x4){0u, 0u, 0u, 0u};
+  }
+
+  // ---- key tiles this workgroup needs ----
+  const int m_lo = pos0 + t0;
+  const int m_hi = pos0 + min(t0 + kPwQ, a.n_q) - 1;
+  const int kt_end = m_hi / kPfK;                       // inclusive
+  int kt_w0 = 0, ks_end = 0;
+  if (LOCAL) {
+    const int lo = max(a.sink, m_lo - a.window + 1);
+    kt_w0 = lo / kPfK;
+    ks_end = min((a.sink + kPfK - 1) / kPfK, kt_w0);    // sink tiles not already inside the band
+  }
+  const int n_tiles = ks_end + (kt_end - kt_w0 + 1);
+  const uint16_t* Kg = a.K + (int64_t)kvh * a.head_stride + tok0 * a.row_stride;
+  const uint16_t* Vg = a.V + (int64_t)kvh * a.head_stride + tok0 * a.row_stride;
+
+  f32x16 O[2][4];
+  float mrow[2], lrow[2];
+  const float c = a.scale_log2;
+  const int q_last = pos0 + a.n_q - 1;
+  const int m_w_lo = pos0 + t0 + wave * 64;             // the wave's first query position
+  const int m_w_hi = min(m_w_lo + 63, q_last);          // and its last (< m_w_lo: the wave has no queries)
+
+  // ---- tile movers: direct global->LDS loads, no staging registers (rows past the last needed key
+  // repeat that key: they are masked for every query, and real data keeps 0 * V finite) ----
+  // Load j (0..3: K, 4..7: V) of a wave covers rows 16 * (j % 4) + 4 * wave + lane / 16 of the tile,
+  // lane % 16 is the 16-byte position inside the row; the lane fetches the chunk that belongs there.
+  const int uwave = __builtin_amdgcn_readfirstlane(wave);
+  const uint32_t lds_base = (uint32_t)(size_t)(__attribute__((address_space(3))) unsigned char*)Ls;
+  const int ld_row = 4 * wave + (lane >> 4);
+  const int ld_pos = lane & 15;
+  const int ld_ck = ld_pos ^ (ld_row & 15);                                          // K chunk of this lane
+  const int ld_cv = ((((ld_pos >> 1) ^ (ld_row & 7)) << 1) | (ld_pos & 1));          // V chunk of this lane
+  auto load_piece = [&](int n0, int slot, int j) __attribute__((always_inline)) {
+    const int jj = j & 3;
+    const int n = min(n0 + 16 * jj + ld_row, m_hi);
+    const uint16_t* src = (j < 4 ? Kg + ld_ck * 8 : Vg + ld_cv * 8) + (int64_t)n * a.row_stride;
+    const uint32_t dst = lds_base + slot * kPwTileBytes + (j < 4 ? 0 : kPwTileBytes / 2) + (jj * 4 + uwave) * 1024;
+    // Written as assembly on purpose: through the compiler's own intrinsic every later LDS read waits
+    // for ALL outstanding direct loads (it cannot tell the buffers apart), which serialises the
+    // pipeline; completion is awaited explicitly (loads_landed) before the barrier that publishes a tile.
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(dst), "v"(src) : "memory", "m0");
+  };
+  auto load_tile = [&](int n0, int slot) __attribute__((always_inline)) {
+#pragma unroll
+    for (int j = 0; j < 8; ++j) load_piece(n0, slot, j);
+  };
+  auto loads_landed = [&]() __attribute__((always_inline)) { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); };
+  // operand read addresses (bytes inside a staged tile)
+  const int rd_k = r * 256, rd_kx = (g ^ (r & 15)) << 4;                              // K: + kb * 8192, chunk (2 kk) ^ ...
+  const int rd_j = lane & 15, rd_G = (lane >> 4) & 1;
+  const int rd_v = kPwTileBytes / 2 + (4 * g + (rd_j >> 2)) * 256 + 8 * (rd_j & 3);   // V: + (kb * 32 + 16 tt + 8 h) * 256
+  const int rd_vx = (rd_G ^ (4 * g + (rd_j >> 2))) << 5;                              //    unit (2 db) ^ ...
+  auto read_k = [&](const unsigned char* tile, int kb, int kk) __attribute__((always_inline)) {
+    return *reinterpret_cast<const u32x4*>(tile + kb * 8192 + rd_k + ((kk << 5) ^ rd_kx));
+  };
+  // the 8 keys x 1 dim a lane needs of V^T for MFMA (tt, db): two transposing reads of 4 keys each
+  auto read_v = [&](const unsigned char* tile, int kb, int tt, int db) __attribute__((always_inline)) {
+    const unsigned char* p0 = tile + rd_v + (kb * 32 + 16 * tt) * 256 + ((db << 6) ^ rd_vx);
+    const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)(p0));
+    const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 __attribute__((address_space(3)))*)(p0 + 8 * 256));
+    return __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+  };
+
+  // ---- MFMA streams ----
+  // scores of key block kb of the staged tile, for both query blocks
+  auto mfma_S = [&](const unsigned char* tile, int kb, f32x16 (&S)[2]) __attribute__((always_inline)) {
+#pragma unroll
+    for (int qb = 0; qb < 2; ++qb)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) S[qb][i] = 0.f;
+#pragma unroll
+    for (int kk = 0; kk < 8; ++kk) {
+      const bf16x8 ka = __builtin_bit_cast(bf16x8, read_k(tile, kb, kk));
+      S[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka, __builtin_bit_cast(bf16x8, qreg[0][kk]), S[0], 0, 0, 0);
+      S[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka, __builtin_bit_cast(bf16x8, qreg[1][kk]), S[1], 0, 0, 0);
+    }
+  };
+  // The same MFMAs with their K operands read three steps ahead and a slice of other work (issuing
+  // the loads of a later tile) between every pair; scheduling fences keep the order.
+  auto scores_beside = [&](const unsigned char* tile, int kb, f32x16 (&S)[2], auto&& work) __attribute__((always_inline)) {
+    u32x4 ka[8];
+    ka[0] = read_k(tile, kb, 0);
+    ka[1] = read_k(tile, kb, 1);
+    ka[2] = read_k(tile, kb, 2);
+#pragma unroll
+    for (int qb = 0; qb < 2; ++qb)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) S[qb][i] = 0.f;
+#pragma unroll
+    for (int kk = 0; kk < 8; ++kk) {
+      if (kk + 3 < 8) ka[kk + 3] = read_k(tile, kb, kk + 3);
+      S[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, ka[kk]), __builtin_bit_cast(bf16x8, qreg[0][kk]), S[0], 0, 0, 0);
+      work(kk);
+      __builtin_amdgcn_sched_barrier(0);
+      S[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, ka[kk]), __builtin_bit_cast(bf16x8, qreg[1][kk]), S[1], 0, 0, 0);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+  };
+  // O^T += V^T P^T for key block kb of the staged tile
+  auto mfma_PV = [&](const unsigned char* tile, int kb, const uint32_t (&P)[2][8]) __attribute__((always_inline)) {
+#pragma unroll
+    for (int tt = 0; tt < 2; ++tt) {
+      const bf16x8 pb0 = __builtin_bit_cast(bf16x8, (u32x4){P[0][4 * tt], P[0][4 * tt + 1], P[0][4 * tt + 2], P[0][4 * tt + 3]});
+      const bf16x8 pb1 = __builtin_bit_cast(bf16x8, (u32x4){P[1][4 * tt], P[1][4 * tt + 1], P[1][4 * tt + 2], P[1][4 * tt + 3]});
+#pragma unroll
+      for (int db = 0; db < 4; ++db) {
+        const bf16x8 va = __builtin_bit_cast(bf16x8, read_v(tile, kb, tt, db));
+        O[0][db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va, pb0, O[0][db], 0, 0, 0);
+        O[1][db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va, pb1, O[1][db], 0, 0, 0);
+      }
+    }
+  };
+  // per-element visibility without control flow: key nb0 + off, off = (i / 4) * 8 + g * 4 + i % 4, is
+  // visible iff off <= hi and (LOCAL) off > lo or off < sk, three per-lane bounds
+  auto mask_block = [&](f32x16 (&S)[2], int nb0) __attribute__((always_inline)) {
+#pragma unroll
+    for (int qb = 0; qb < 2; ++qb) {
+      const int base = nb0 + g * 4;
+      const int hi = qok[qb] ? mq[qb] - base : -1;
+      const int lo = mq[qb] - a.window - base;
+      const int sk = a.sink - base;
+#pragma unroll
+      for (int i = 0; i < 16; ++i) {
+        const int off = (i >> 2) * 8 + (i & 3);
+        bool ok = off <= hi;
+        if (LOCAL) ok = ok & ((off > lo) | (off < sk));
+        S[qb][i] = ok ? S[qb][i] : ninf;
+      }
+    }
+  };
+  // probabilities against the fixed reference; masked scores are -inf and give exactly 0
+  auto softmax_fixed = [&](const f32x16 (&S)[2], uint32_t (&P)[2][8]) __attribute__((always_inline)) {
+#pragma unroll
+    for (int qb = 0; qb < 2; ++qb) {
+      const float mc = mrow[qb] * c;
+      float lsum = 0.f;
+#pragma unroll
+      for (int i = 0; i < 16; i += 2) {
+        const float p0 = fast_exp2(fmaf(S[qb][i], c, -mc));
+        const float p1 = fast_exp2(fmaf(S[qb][i + 1], c, -mc));
+        lsum += p0 + p1;
+        P[qb][i >> 1] = pack_bf16(p0, p1);
+      }
+      lrow[qb] += lsum;
+    }
+  };
+  // The steady-state step: the 16 PV MFMAs of the previous block and the softmax of the current block
+  // as ONE hand-interleaved instruction sequence -- per MFMA (32 cycles of the matrix pipe) one pair of
+  // probabilities (2 fma, 2 exp, 1 convert, 2 adds on the vector ALU); scheduling fences keep the
+  // compiler from regrouping it, V^T operands are read two MFMA pairs ahead.
+  auto pv_beside_softmax = [&](const unsigned char* tile, int kb, const uint32_t (&Pin)[2][8], const f32x16 (&S)[2],
+                               uint32_t (&Pout)[2][8]) __attribute__((always_inline)) {
+    const float mc0 = mrow[0] * c, mc1 = mrow[1] * c;
+    float l0 = 0.f, l1 = 0.f;
+    s16x8 va[8];
+    auto read_va = [&](int k) __attribute__((always_inline)) { va[k] = read_v(tile, kb, k >> 2, k & 3); };   // k = tt * 4 + db
+    read_va(0);
+    read_va(1);
+#pragma unroll
+    for (int k = 0; k < 8; ++k) {
+      const int tt = k >> 2, db = k & 3;
+      const bf16x8 pb0 = __builtin_bit_cast(bf16x8, (u32x4){Pin[0][4 * tt], Pin[0][4 * tt + 1], Pin[0][4 * tt + 2], Pin[0][4 * tt + 3]});
+      const bf16x8 pb1 = __builtin_bit_cast(bf16x8, (u32x4){Pin[1][4 * tt], Pin[1][4 * tt + 1], Pin[1][4 * tt + 2], Pin[1][4 * tt + 3]});
+      if (k + 2 < 8) read_va(k + 2);
+      O[0][db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, va[k]), pb0, O[0][db], 0, 0, 0);
+      {
+        const float p0 = fast_exp2(fmaf(S[0][2 * k], c, -mc0));
+        const float p1 = fast_exp2(fmaf(S[0][2 * k + 1], c, -mc0));
+        l0 += p0 + p1;
+        Pout[0][k] = pack_bf16(p0, p1);
+      }
+      __builtin_amdgcn_sched_barrier(0);
+      O[1][db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, va[k]), pb1, O[1][db], 0, 0, 0);
+      {
+        const float p0 = fast_exp2(fmaf(S[1][2 * k], c, -mc1));
+        const float p1 = fast_exp2(fmaf(S[1][2 * k + 1], c, -mc1));
+        l1 += p0 + p1;
+        Pout[1][k] = pack_bf16(p0, p1);
+      }
+      __builtin_amdgcn_sched_barrier(0);
+    }
+    lrow[0] += l0;
+    lrow[1] += l1;
+  };
+  // does the 32-key block starting at nb0 need per-element masks for some query of this wave?
+  auto needs_mask = [&](int nb0) __attribute__((always_inline)) {
+    bool e = false;
+#pragma unroll
+    for (int qb = 0; qb < 2; ++qb) {
+      const int m_b_lo = m_w_lo + qb * 32;
+      const int m_b_hi = min(m_b_lo + 31, q_last);
+      e = e || (m_b_hi < m_b_lo) || (nb0 + 31 > m_b_lo) || (LOCAL && !(nb0 > m_b_hi - a.window || nb0 + 31 < a.sink));
+    }
+    return e;
+  };
+  // can some query of this wave see a key of the block at all?
+  auto is_active = [&](int nb0) __attribute__((always_inline)) {
+    if (m_w_hi < m_w_lo || nb0 > m_w_hi) return false;
+    if (LOCAL && nb0 >= a.sink && nb0 + 31 <= m_w_lo - a.window) return false;
+    return true;
+  };
+
+  auto tile_n0 = [&](int it) __attribute__((always_inline)) { return (it < ks_end ? it : kt_w0 + (it - ks_end)) * kPfK; };
+  const int it_lo = (int)((int64_t)n_tiles * split / n_splits);
+  const int it_hi = (int)((int64_t)n_tiles * (split + 1) / n_splits);
+  auto slot_of = [&](int it) __attribute__((always_inline)) { return (it - it_lo) % kPwStages; };
+  auto tile_at = [&](int it) __attribute__((always_inline)) { return Ls + slot_of(it) * kPwTileBytes; };
+  auto block_n0 = [&](int it, int hf) __attribute__((always_inline)) { return tile_n0(it) + hf * 32; };
+
+  bool redo = false;
+  if (it_lo < it_hi) {
+    f32x16 S[2];
+    uint32_t P0[2][8], P1[2][8];
+#pragma unroll
+    for (int qb = 0; qb < 2; ++qb) {
+      lrow[qb] = 0.f;
+#pragma unroll
+      for (int db = 0; db < 4; ++db)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) O[qb][db][i] = 0.f;
+    }
+    load_tile(tile_n0(it_lo), 0);
+    load_tile(tile_n0(min(it_lo + 1, it_hi - 1)), 1);
+    loads_landed();
+    __syncthreads();
+    // reference maxima: the largest score of the first tile, masks ignored (always finite)
+#pragma unroll
+    for (int qb = 0; qb < 2; ++qb) mrow[qb] = ninf;
+#pragma unroll
+    for (int kb = 1; kb >= 0; --kb) {
+      mfma_S(Ls, kb, S);
+#pragma unroll
+      for (int qb = 0; qb < 2; ++qb) {
+        float mx = S[qb][0];
+#pragma unroll
+        for (int i = 1; i < 16; ++i) mx = fmaxf(mx, S[qb][i]);
+        mrow[qb] = fmaxf(mrow[qb], fmaxf(mx, __shfl_xor(mx, 32)));
+      }
+    }                                                    // S now holds block (it_lo, 0)
+
+    // Invariant at the start of half hf of tile it: S holds the scores of that block if it is active
+    // for this wave; if `pend`, the probabilities of the last active block wait in P1 (hf = 0, V in
+    // the previous tile's buffer) or P0 (hf = 1); tiles it and it + 1 are in LDS.  The loads of tile
+    // it + 2 go out during half 1 (their buffer held tile it - 1, last read in half 0) and every wave
+    // waits for its own before the barrier that ends half 0 of tile it + 1.
+    bool pend = false;
+    auto half = [&](int it, auto hf_tag) __attribute__((always_inline)) {
+      constexpr int hf = decltype(hf_tag)::value;
+      const int nb0 = block_n0(it, hf);
+      const unsigned char* t_pend = hf == 0 ? tile_at(it - 1) : tile_at(it);
+      const uint32_t (&Pin)[2][8] = hf == 0 ? P1 : P0;
+      uint32_t (&Pout)[2][8] = hf == 0 ? P0 : P1;
+      if (!is_active(nb0)) {
+        if (pend) mfma_PV(t_pend, 1 - hf, Pin);
+        pend = false;
+      } else if (pend && !needs_mask(nb0)) {
+        // steady state: PV of the previous block beside the softmax of this one
+        pv_beside_softmax(t_pend, 1 - hf, Pin, S, Pout);
+      } else {
+        if (pend) mfma_PV(t_pend, 1 - hf, Pin);
+        mask_block(S, nb0);
+        softmax_fixed(S, Pout);
+        pend = true;
+      }
+      if (hf == 0) {
+        if (is_active(nb0 + 32)) scores_beside(tile_at(it), 1, S, [&](int) __attribute__((always_inline)) {});
+        loads_landed();
+        __syncthreads();
+      } else {
+        // past the last tile the same loads re-fetch it into a buffer nobody reads: no branches
+        const int n2 = tile_n0(min(it + 2, it_hi - 1));
+        const int s2 = slot_of(it + 2);
+        if (it + 1 < it_hi && is_active(tile_n0(it + 1))) {
+          scores_beside(tile_at(it + 1), 0, S, [&](int kk) __attribute__((always_inline)) { load_piece(n2, s2, kk); });
+        } else {
+          load_tile(n2, s2);
+        }
+      }
+    };
+    for (int it = it_lo; it < it_hi; ++it) {
+      half(it, std::integral_constant<int, 0>{});
+      half(it, std::integral_constant<int, 1>{});
+    }
+    if (pend) mfma_PV(tile_at(it_hi - 1), 1, P1);        // drain: PV of the last block
+    loads_landed();
+
+    // was every reference within reach?  (rows that saw no key at all have sum 0 and are fine)
+    bool bad = false;
+#pragma unroll
+    for (int qb = 0; qb < 2; ++qb) {
+      const float ltot = lrow[qb] + __shfl_xor(lrow[qb], 32);
+      bad = bad || (qok[qb] && ltot != 0.f && !(ltot > 0x1p-60f && ltot < 0x1p100f));
+    }
+    redo = __syncthreads_or(bad ? 1 : 0) != 0;
+  }
+
+  if (redo) {
+    // ---- exact pass: running maximum, accumulators rescaled in place; no pipelining (rare) ----
+    f32x16 S[2];
+    uint32_t P[2][8];
+#pragma unroll
+    for (int qb = 0; qb < 2; ++qb) {
+      mrow[qb] = ninf;
+      lrow[qb] = 0.f;
+#pragma unroll
+      for (int db = 0; db < 4; ++db)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) O[qb][db][i] = 0.f;
+    }
+    for (int it = it_lo; it < it_hi; ++it) {
+      __syncthreads();
+      load_tile(tile_n0(it), 0);
+      loads_landed();
+      __syncthreads();
+      for (int kb = 0; kb < 2; ++kb) {
+        const int nb0 = tile_n0(it) + kb * 32;
+        if (!is_active(nb0)) continue;
+        if (kb == 0) mfma_S(Ls, 0, S); else mfma_S(Ls, 1, S);
+        mask_block(S, nb0);
+#pragma unroll
+        for (int qb = 0; qb < 2; ++qb) {
+          float mx = S[qb][0];
+#pragma unroll
+          for (int i = 1; i < 16; ++i) mx = fmaxf(mx, S[qb][i]);
+          mx = fmaxf(mx, __shfl_xor(mx, 32));
+          const float mnew = fmaxf(mrow[qb], mx);
+          const float msafe = mnew == ninf ? 0.f : mnew;
+          const float mc = msafe * c;
+          float lsum = 0.f;
+#pragma unroll
+          for (int i = 0; i < 16; i += 2) {
+            const float p0 = fast_exp2(fmaf(S[qb][i], c, -mc));
+            const float p1 = fast_exp2(fmaf(S[qb][i + 1], c, -mc));
+            lsum += p0 + p1;
+            P[qb][i >> 1] = pack_bf16(p0, p1);
+          }
+          const float corr = fast_exp2((mrow[qb] - msafe) * c);
+          lrow[qb] = lrow[qb] * corr + lsum;
+#pragma unroll
+          for (int db = 0; db < 4; ++db)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) O[qb][db][i] *= corr;
+          mrow[qb] = mnew;
+        }
+        if (kb == 0) mfma_PV(Ls, 0, P); else mfma_PV(Ls, 1, P);
+      }
+    }
+  }
+
+  // ---- normalise and store ----
+#pragma unroll
+  for (int qb = 0; qb < 2; ++qb) {
+    const float ltot = (it_lo < it_hi) ? lrow[qb] + __shfl_xor(lrow[qb], 32) : 0.f;
+    if (!qok[qb]) continue;
+    const float mfin = (it_lo < it_hi && ltot > 0.f) ? mrow[qb] : ninf;
+    if (n_splits > 1) {
+      float* prow = a.part + (((int64_t)split * a.n_heads + blockIdx.x) * a.n_q + tq[qb]) * kPfPart;
+      if (g == 0) { prow[0] = mfin; prow[1] = ltot; }
+#pragma unroll
+      for (int db = 0; db < 4; ++db)
+#pragma unroll
+        for (int i4 = 0; i4 < 4; ++i4)
+          *reinterpret_cast<float4*>(prow + 4 + db * 32 + i4 * 8 + g * 4) =
+              ltot > 0.f ? make_float4(O[qb][db][i4 * 4], O[qb][db][i4 * 4 + 1], O[qb][db][i4 * 4 + 2], O[qb][db][i4 * 4 + 3])
+                         : make_float4(0.f, 0.f, 0.f, 0.f);
+      continue;
+    }
+    const float inv = ltot > 0.f ? 1.f / ltot : 0.f;
+    uint16_t* orow = a.out + qrow[qb];
+#pragma unroll
+    for (int db = 0; db < 4; ++db) {
+#pragma unroll
+      for (int i4 = 0; i4 < 4; ++i4) {
+        const u32x2 w = ltot > 0.f ? (u32x2){pack_bf16(O[qb][db][i4 * 4] * inv, O[qb][db][i4 * 4 + 1] * inv),
+                                             pack_bf16(O[qb][db][i4 * 4 + 2] * inv, O[qb][db][i4 * 4 + 3] * inv)}
+                                   : (u32x2){0u, 0u};
+        *reinterpret_cast<u32x2*>(orow + db * 32 + i4 * 8 + g * 4) = w;
+      }
+    }
+    if (a.lse && g == 0) {
+      a.lse[((int64_t)b * a.n_q + tq[qb]) * a.n_q_heads + h] = ltot > 0.f ? mfin * a.scale + logf(ltot) : ninf;
+    }
+  }
+}
+
 // qI[j, t, :] = bf16( W[j] . x[t, ret_heads[j], :] ), the 128-term sums in fp64, one rounding
 // (Sec. 3.2, indexer equation, query side).  16 queries per workgroup: thread = (query, output dim).
 struct ProjectArgs {
@@ -503,7 +956,7 @@ __global__ __launch_bounds__(256) void prefill_combine_kernel(const PrefillArgs 
 
 // Number of key-range splits for a dense launch with few workgroups (long context, few heads).
 static int choose_splits(int n_heads, int32_t T, int64_t chunk_start) {
-  const int64_t wgs = (int64_t)n_heads * ((T + kPfQ - 1) / kPfQ);
+  const int64_t wgs = (int64_t)n_heads * ((T + kPwQ - 1) / kPwQ);
   const int64_t avg_tiles = (chunk_start + T / 2) / kPfK + 1;
   int64_t s = 1024 / (wgs > 0 ? wgs : 1);
   if (s > avg_tiles / 32) s = avg_tiles / 32;
@@ -514,10 +967,13 @@ static int choose_splits(int n_heads, int32_t T, int64_t chunk_start) {
 static int32_t launch_prefill(const char* who, bool local, PrefillArgs& a, int32_t B, hipStream_t s) {
   if (a.n_heads == 0) return RTP_OK;
   if (a.n_splits < 1) a.n_splits = 1;
-  dim3 grid((unsigned)a.n_heads, (unsigned)((a.n_q + kPfQ - 1) / kPfQ), (unsigned)(B * (local ? 1 : a.n_splits)));
+  // dense launches take the 64-queries-per-wave kernel; the local band (a few dozen key tiles per query
+  // tile, many of them masked) stays on the 32-queries-per-wave kernel, whose masked tiles cost less
+  const int qt = local ? kPfQ : kPwQ;
+  dim3 grid((unsigned)a.n_heads, (unsigned)((a.n_q + qt - 1) / qt), (unsigned)(B * (local ? 1 : a.n_splits)));
   if (grid.y > 65535 || grid.z > 65535) return fail(RTP_ERR_INVALID_ARG, "%s: n_q / B too large for one launch", who);
   if (local) hipLaunchKernelGGL(flash_prefill_kernel<kModeLocal>, grid, dim3(kPfThreads), 0, s, a);
-  else hipLaunchKernelGGL(flash_prefill_kernel<kModeDense>, grid, dim3(kPfThreads), 0, s, a);
+  else hipLaunchKernelGGL(flash_prefill_wide_kernel<kModeDense>, grid, dim3(kPfThreads), 0, s, a);
   if (!local && a.n_splits > 1)
     hipLaunchKernelGGL(prefill_combine_kernel, dim3((unsigned)((a.n_q + 1) / 2), (unsigned)a.n_heads), dim3(256), 0, s, a);
   return check_launch(who);
@@ -545,7 +1001,7 @@ int32_t prefill_range_attn(const char* who, bool dense, const rtp_layer_desc* L,
   if (rc != RTP_OK) return rc;
   if (!seq_start || !ctx_len || !q_start) return fail(RTP_ERR_INVALID_ARG, "%s: NULL seq_start/ctx_len/q_start", who);
   if (B <= 0 || n_q <= 0 || max_ctx <= 0) return fail(RTP_ERR_INVALID_ARG, "%s: B, n_q and max_ctx must be positive", who);
-  if (max_ctx > 0x7fffffffLL - kPfQ) return fail(RTP_ERR_INVALID_ARG, "%s: max_ctx too large", who);
+  if (max_ctx > 0x7fffffffLL - kPwQ) return fail(RTP_ERR_INVALID_ARG, "%s: max_ctx too large", who);
   clear_error();
   PrefillArgs a = {};
   a.q = (const uint16_t*)q;
@@ -595,7 +1051,7 @@ extern "C" int32_t rtp_sparse_attn_prefill(const rtp_layer_desc* layer, const vo
   rc = check_prefill_common(who, q, K, V, kv_row_stride, kv_head_stride, out);
   if (rc != RTP_OK) return rc;
   if (T <= 0 || chunk_start < 0) return fail(RTP_ERR_INVALID_ARG, "%s: T must be positive and chunk_start >= 0", who);
-  if (chunk_start + T > 0x7fffffffLL - kPfQ) return fail(RTP_ERR_INVALID_ARG, "%s: context too long", who);
+  if (chunk_start + T > 0x7fffffffLL - kPwQ) return fail(RTP_ERR_INVALID_ARG, "%s: context too long", who);
   if (!(p > 0.f)) return fail(RTP_ERR_INVALID_ARG, "%s: p must be > 0", who);
   const bool sparse = p < 1.f || tau || count || mass;
   if (sparse) {

@@ -187,7 +187,8 @@ def test_sparse_prefill_matches_oracle(name):
 
 def test_sparse_prefill_p1_statistics_and_dense_equivalence():
     """p = 1 with statistics requested runs the selecting kernel with nothing to select:
-    same output as the dense path, count = m + 1, mass = 1."""
+    the dense path's output up to rounding (the two kernels block the keys differently),
+    count = m + 1, mass = 1."""
     print("[case] sparse prefill p=1 statistics", flush=True)
     w = wl.small_prefill(DEV, seed=71, chunk_start=260, T=90)
     run = PrefillRun(w)
@@ -201,7 +202,9 @@ def test_sparse_prefill_p1_statistics_and_dense_equivalence():
     dout = torch.zeros_like(run.out)
     run.dense_attn(dout)
     torch.cuda.synchronize()
-    assert torch.equal(a[:, L.ret_heads], dout[:, L.ret_heads])
+    ga = a[:, L.ret_heads].float().cpu().numpy().astype(np.float64)
+    gd = dout[:, L.ret_heads].float().cpu().numpy().astype(np.float64)
+    assert (np.abs(ga - gd) <= 2e-3 + 2.0 ** -7 * np.abs(gd)).all(), np.abs(ga - gd).max()
 
 
 def test_retrieval_dense_split_keys_matches_unsplit():
