@@ -811,12 +811,15 @@ __global__ __launch_bounds__(kPfThreads, 1) void flash_prefill_wide_kernel(const
     if (pend) mfma_PV(tile_at(it_hi - 1), 1, P1);        // drain: PV of the last block
     loads_landed();
 
-    // was every reference within reach?  (rows that saw no key at all have sum 0 and are fine)
+    // was every reference within reach?  A query that can see a key of this key range (always, with
+    // the whole band of a local launch; from the range's first key on, in a dense one) must have a sum
+    // in the comfortable middle of the fp32 range; everything else (0, tiny, huge, inf, NaN) repeats.
     bool bad = false;
 #pragma unroll
     for (int qb = 0; qb < 2; ++qb) {
       const float ltot = lrow[qb] + __shfl_xor(lrow[qb], 32);
-      bad = bad || (qok[qb] && ltot != 0.f && !(ltot > 0x1p-60f && ltot < 0x1p100f));
+      const bool sees_key = qok[qb] && (LOCAL || tile_n0(it_lo) <= mq[qb]);
+      bad = bad || (sees_key && !(ltot > 0x1p-60f && ltot < 0x1p100f));
     }
     redo = __syncthreads_or(bad ? 1 : 0) != 0;
   }

@@ -111,6 +111,48 @@ def test_prefill_two_sequences_and_interleaved_kv():
             check_out(dgot[r["t"], r["h"]], r["out"], f"dense b{b} t{r['t']} h{r['h']}", tight="mfma")
 
 
+def _dense_vs_oracle(w, what):
+    L = w.layer
+    run = PrefillRun(w)
+    oi = prefill_oracle_inputs(w)
+    rows = [(t, h) for t in range(w.T) for h in range(L.n_q_heads)]
+    dout = torch.zeros_like(run.out)
+    dlse = torch.zeros_like(run.lse)
+    run.dense_attn(dout, dlse)
+    torch.cuda.synchronize()
+    dref = orc.dense_rows(rows=rows, q_bits=oi["q_bits"], K_bits=oi["K_bits"], V_bits=oi["V_bits"],
+                          chunk_start=w.chunk_start, n_q_heads=L.n_q_heads, n_kv_heads=L.n_kv_heads)
+    got = dout.float().cpu().numpy().astype(np.float64)
+    o_ref = np.zeros_like(got)
+    for r in dref:
+        o_ref[r["t"], r["h"]] = r["out"]
+    assert np.isfinite(got).all(), what
+    check_out(got, o_ref, what, tight="mfma")
+
+
+def test_dense_prefill_scores_far_above_the_first_tile():
+    """The dense kernel takes every query's reference maximum from the first key tile.  Here the late
+    keys score ~90 (natural units) above it: exp overflows against that reference and the workgroup
+    has to notice and repeat its keys with the running-maximum recurrence."""
+    print("[case] dense prefill, reference outrun upwards", flush=True)
+    w = wl.small_prefill(DEV, seed=91, chunk_start=600, T=150)
+    w.q[:] = 2.0
+    w.K[:, 300:, :] = 4.0                     # q.k * scale = 128 * 8 / sqrt(128) ~ 90.5 for keys >= 300
+    _dense_vs_oracle(w, "reference outrun upwards")
+
+
+def test_dense_prefill_reference_above_every_visible_score():
+    """First chunk: keys 32..63 score ~90 above the rest but the first 32 queries cannot see them, so
+    their reference (taken over the whole first tile, masks ignored) is far above everything they
+    attend to; their probabilities underflow and the repeat pass has to produce them."""
+    print("[case] dense prefill, reference outrun downwards", flush=True)
+    w = wl.small_prefill(DEV, seed=92, chunk_start=0, T=100)
+    w.q[:] = 2.0
+    w.K[:, :, :] = (torch.randn_like(w.K.float()) * 0.05).to(w.K.dtype)
+    w.K[:, 32:64, :] = 4.0
+    _dense_vs_oracle(w, "reference outrun downwards")
+
+
 # ---------------------------------------------------------------------------------------------
 # per-query top-p in prefill (p < 1)
 # ---------------------------------------------------------------------------------------------
