@@ -167,7 +167,7 @@ def main() -> int:
                 "unit": "GB/s", "frac": round(ach / HBM_PEAK_GBS, 4),
                 # HBM bytes per launch from the rocprofv3 --pmc runs recorded under profiles/ (FETCH_SIZE x 2.0 +
                 # WRITE_SIZE x 1.0 KiB, factors from a plain 1 GiB copy); only valid for the default shape
-                "traffic": 151108096 if (B, N, n_ret) == (8, 131072, 4) else None,
+                "traffic": 152147866 if (B, N, n_ret) == (8, 131072, 4) else None,
                 "algorithmic_bytes_per_launch": bytes_index, "avg_launch_us": round(br["index_score"], 2)}
 
     # ---- CPU baseline: the oracle, as it stands, on a bounded sample of the same workload ----
