@@ -43,6 +43,7 @@ struct AttnDecodeArgs {
   int32_t n_q_heads, n_kv_heads, n_ret, sink, window;
   int32_t units;           // B * n_ret (sparse) or B * n_kv_heads
   int32_t target_items;    // sparse: host hint, aim for this many work items
+  int32_t min_split_blocks;  // sparse: shortest split, in blocks of 128 tokens
   int32_t split_tokens;    // local / dense: tokens per work item, fixed by the host
   int32_t n_splits;        // local / dense: work items per unit
   float scale_log2;        // softmax scale * log2(e)
@@ -99,8 +100,9 @@ __device__ __forceinline__ void build_plan(const AttnDecodeArgs& a, int* sh_pref
   }
   int total128;
   block_excl_scan(mine, sh_w, &total128);
+  // at least kMinSplitBlocks * 128 tokens per item: shorter items spend their time in the prologue and the merge
   int st = (total128 + a.target_items - 1) / max(a.target_items, 1);
-  st = max(st, 1) * 128;
+  st = max(st, a.min_split_blocks) * 128;
   int items = 0;
 #pragma unroll
   for (int i = 0; i < kAdMaxUnits / kAdThreads; ++i) {
@@ -527,6 +529,7 @@ int32_t decode_range_attn(const char* who, bool dense, const rtp_layer_desc* L, 
   fill_common(a, L, ht, q, K, V, row_stride, head_stride, seq_start, ctx_len, out, lse, ws);
   a.units = p.units;
   a.target_items = 0;
+  a.min_split_blocks = 1;
   a.split_tokens = p.split_tokens;
   a.n_splits = p.n_splits;
   return dense ? launch_decode<kSrcDense>(a, G, p.grid, s, who) : launch_decode<kSrcLocal>(a, G, p.grid, s, who);
@@ -577,6 +580,7 @@ extern "C" int32_t rtp_sparse_attn_decode(const rtp_layer_desc* layer, const voi
   a.sel_count = sel_count;
   a.units = p.units;
   a.target_items = p.target_items;
+  a.min_split_blocks = tune("RTP_TUNE_SPARSE_MIN_BLOCKS", 5);
   a.split_tokens = 0;
   a.n_splits = 0;
   return launch_decode<kSrcSparse>(a, 1, p.grid, (hipStream_t)stream, who);

@@ -58,6 +58,7 @@ struct PrefillArgs {
   float* tau;                   // optional [n_ret, n_q]
   int32_t* count;
   float* mass;
+  float* sel_thr;               // [n_ret, n_q]: a candidate is kept iff its raw index product is >= this
 };
 
 enum { kModeDense = 0, kModeLocal = 1, kModeSparse = 2 };
@@ -70,10 +71,14 @@ constexpr float kSelScale = 131072.0f;
 constexpr int kSelQMax = (1 << 21) - 1;
 constexpr int kTileHalfs = kPfK * kKsStride + kHeadDim * kVtStride;   // bf16 elements of one staged K + V^T tile
 constexpr int kSmemDense = kTileHalfs * 2 * 2;                        // two buffers
-constexpr int kSmemSparse = (kPfThreads / 64) * 32 * kSelBins * 8;
+constexpr int kSelListCap = 24;      // entries per lane; a tile adds at most 16, so lists are emptied above 8
+#ifndef RTP_SEL_RING
+#define RTP_SEL_RING 8
+#endif
+constexpr int kSelRing = RTP_SEL_RING;          // index-key tiles in flight per wave during the threshold search
 
-__device__ __forceinline__ int sel_q(float M, float s) {
-  return (int)fminf((M - s) * kSelScale, (float)kSelQMax);
+__device__ __forceinline__ int sel_q_of_t(float tt) {       // tt = M - s >= 0
+  return (int)fminf(tt * kSelScale, (float)kSelQMax);
 }
 
 __device__ __forceinline__ uint32_t pack_bf16(float a, float b) {
@@ -82,11 +87,10 @@ __device__ __forceinline__ uint32_t pack_bf16(float a, float b) {
 }
 
 template <int MODE>
-__global__ __launch_bounds__(kPfThreads, 2) void flash_prefill_kernel(const PrefillArgs a) {
+__global__ __launch_bounds__(kPfThreads, MODE == kModeSparse ? 1 : 2) void flash_prefill_kernel(const PrefillArgs a) {
   constexpr bool LOCAL = MODE == kModeLocal;
   constexpr bool SPARSE = MODE == kModeSparse;
-  __shared__ __attribute__((aligned(16))) unsigned char smem[SPARSE ? (kSmemSparse > kSmemDense ? kSmemSparse : kSmemDense)
-                                                                    : kSmemDense];
+  __shared__ __attribute__((aligned(16))) unsigned char smem[kSmemDense];
   uint16_t* Ks = reinterpret_cast<uint16_t*>(smem);
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -127,93 +131,28 @@ __global__ __launch_bounds__(kPfThreads, 2) void flash_prefill_kernel(const Pref
   const uint16_t* Kg = a.K + (int64_t)kvh * a.head_stride + tok0 * a.row_stride;
   const uint16_t* Vg = a.V + (int64_t)kvh * a.head_stride + tok0 * a.row_stride;
 
-  // ---- sparse mode: per-query top-p threshold over the indexer scores (three sweeps over kI) ----
-  // Every wave works alone on its 32 queries.  The index-score tile is ONE MFMA (K = 16) in the same
-  // transposed layout as the attention scores, so a lane sees 16 keys of its own query.
+  // ---- sparse mode: the per-query threshold was found by prefill_select_kernel ----
+  // The index-score tile is ONE MFMA (K = 16) in the same transposed layout as the attention scores,
+  // so a lane sees 16 keys of its own query; a key is kept iff its raw product reaches the threshold.
   u32x4 qIreg = (u32x4){0u, 0u, 0u, 0u};
   const uint16_t* kIg = nullptr;
-  float selM = ninf;          // row maximum of the index scores
-  int selQ = 0x7fffffff;      // keep a candidate iff sel_q(selM, s) <= selQ; the default keeps everything
-  float sel_mass = 1.f;
+  float selThr = ninf;                           // -inf keeps every candidate (p >= 1)
   int sel_cnt = 0;
+  const bool wave_partial = t0 + wave * 32 + 32 > a.n_q;
+  const int n_rows = pos0 + a.n_q;               // index-key rows that exist
   if (SPARSE) {
     const int j = blockIdx.x;
     kIg = a.kI + (int64_t)j * a.kI_head_stride;
     if (qok) qIreg = *reinterpret_cast<const u32x4*>(a.qI + ((int64_t)j * a.n_q + t) * kIndexDim + g * 8);
-    const int n_rows = pos0 + a.n_q;                          // index-key rows that exist
-    const int m_wave_hi = pos0 + min(t0 + wave * 32 + 32, a.n_q) - 1;
-    double* hist = reinterpret_cast<double*>(smem) + (wave * 32 + r) * kSelBins;   // this query's bins
-    const bool keep_all = !(a.p < 1.f);
-    double Z = 0.0, above = 0.0;
-    int prefix = 0;            // digits of the threshold found so far
-    // Control flow around the barriers is uniform: every thread runs all four sweeps (or none when
-    // p >= 1); per-lane state only decides what a lane accumulates.
-    for (int phase = 0; phase < 4 && !keep_all; ++phase) {
-      if (phase > 0) {
-        for (int i = g; i < kSelBins; i += 2) hist[i] = 0.0;
-        __syncthreads();
-      }
-      const int shift = 7 * (3 - phase);                      // phase 1: 14, phase 2: 7, phase 3: 0
-      float mx = ninf;
-      for (int nb = 0; nb <= m_wave_hi; nb += 32) {
-        const int nrow = nb + r;
-        u32x4 ka = (u32x4){0u, 0u, 0u, 0u};
-        if (nrow < n_rows) ka = *reinterpret_cast<const u32x4*>(kIg + (int64_t)nrow * kIndexDim + g * 8);
-        f32x16 SI;
-#pragma unroll
-        for (int i = 0; i < 16; ++i) SI[i] = 0.f;
-        SI = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, ka), __builtin_bit_cast(bf16x8, qIreg),
-                                                     SI, 0, 0, 0);
-#pragma unroll
-        for (int i = 0; i < 16; ++i) {
-          const int n = nb + (i >> 2) * 8 + g * 4 + (i & 3);
-          const bool ok = qok && n <= m;
-          const float sv = SI[i] * a.index_scale;
-          if (phase == 0) {
-            mx = fmaxf(mx, ok ? sv : ninf);
-          } else if (ok) {
-            const int qv = sel_q(selM, sv);
-            if (phase == 1 || (qv >> (shift + 7)) == prefix) {
-              const float wgt = fast_exp2((sv - selM) * 1.4426950408889634f);
-              atomicAdd(&hist[(qv >> shift) & (kSelBins - 1)], (double)wgt);
-            }
-          }
-        }
-      }
-      if (phase == 0) {
-        selM = fmaxf(mx, __shfl_xor(mx, 32));
-      } else {
-        __syncthreads();
-        // scan this query's bins from the top of the score range (bin 0) down; both lanes of the
-        // pair run the same scan on the same numbers
-        if (phase == 1) {
-          Z = 0.0;
-          for (int i = 0; i < kSelBins; ++i) Z += hist[i];
-        }
-        const double target = (double)a.p * Z;
-        double cum = above, hsel = 0.0;
-        int bsel = kSelBins - 1;
-        bool found = false;
-        for (int i = 0; i < kSelBins; ++i) {
-          const double hv = hist[i];
-          if (!found) {
-            if (cum + hv >= target) { bsel = i; hsel = hv; found = true; }
-            else cum += hv;
-          }
-        }
-        prefix = (prefix << 7) | bsel;
-        above = cum;
-        if (phase == 3) {
-          // a threshold inside the open-ended last coarse bin keeps every candidate
-          const bool lump = (prefix >> 14) == kSelBins - 1;
-          selQ = lump ? 0x7fffffff : prefix;
-          sel_mass = (lump || !(Z > 0.0)) ? 1.f : (float)((cum + hsel) / Z);
-        }
-        __syncthreads();
-      }
-    }
-    __syncthreads();             // the histogram memory becomes the K/V tile buffers
+    if (a.p < 1.f && qok) selThr = a.sel_thr[(int64_t)j * a.n_q + t];
   }
+  auto load_ki = [&](int n0, u32x4 (&k2)[2]) {
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb) {
+      const int nrow = min(n0 + kb * 32 + r, n_rows - 1);         // rows past the chunk are causally masked anyway
+      k2[kb] = *reinterpret_cast<const u32x4*>(kIg + (int64_t)nrow * kIndexDim + g * 8);
+    }
+  };
 
   f32x16 O[4];
 #pragma unroll
@@ -278,7 +217,7 @@ __global__ __launch_bounds__(kPfThreads, 2) void flash_prefill_kernel(const Pref
   };
 
   // ---- one key tile: S^T = K Q^T, online softmax, O^T += V^T P^T -----------------------------------
-  auto compute_tile = [&](int buf, int n0, const uint32_t (&selmask)[2]) {
+  auto compute_tile = [&](int buf, int n0, const u32x4 (&ki2)[2]) {
     const uint16_t* ks = Ks + buf * (kTileHalfs);
     const uint16_t* vt = ks + kPfK * kKsStride;
     f32x16 S[2];
@@ -294,9 +233,37 @@ __global__ __launch_bounds__(kPfThreads, 2) void flash_prefill_kernel(const Pref
       }
     }
     // interior tiles (every key visible to every query of the wave) skip the mask arithmetic
-    const bool masked = SPARSE || (n0 + kPfK - 1 > m_wave_lo) || (LOCAL && n0 <= m_wave_hi - a.window);
+    const bool edge = (n0 + kPfK - 1 > m_wave_lo) || (LOCAL && n0 <= m_wave_hi - a.window) || (SPARSE && wave_partial);
     float mx = ninf;
-    if (masked) {
+    if (SPARSE) {
+      // selecting mode: one index-score MFMA per 32 keys, one comparison per pair
+#pragma unroll
+      for (int kb = 0; kb < 2; ++kb) {
+        f32x16 SI;
+#pragma unroll
+        for (int i = 0; i < 16; ++i) SI[i] = 0.f;
+        SI = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, ki2[kb]), __builtin_bit_cast(bf16x8, qIreg),
+                                                     SI, 0, 0, 0);
+        if (!edge) {
+#pragma unroll
+          for (int i = 0; i < 16; ++i) {
+            const bool keep = SI[i] >= selThr;
+            sel_cnt += keep ? 1 : 0;
+            S[kb][i] = keep ? S[kb][i] : ninf;
+            mx = fmaxf(mx, S[kb][i]);
+          }
+        } else {
+#pragma unroll
+          for (int i = 0; i < 16; ++i) {
+            const int n = n0 + kb * 32 + (i >> 2) * 8 + g * 4 + (i & 3);
+            const bool keep = SI[i] >= selThr && qok && n <= m;
+            sel_cnt += keep ? 1 : 0;
+            S[kb][i] = keep ? S[kb][i] : ninf;
+            mx = fmaxf(mx, S[kb][i]);
+          }
+        }
+      }
+    } else if (edge) {
 #pragma unroll
       for (int kb = 0; kb < 2; ++kb) {
 #pragma unroll
@@ -304,7 +271,6 @@ __global__ __launch_bounds__(kPfThreads, 2) void flash_prefill_kernel(const Pref
           const int n = n0 + kb * 32 + (i >> 2) * 8 + g * 4 + (i & 3);
           bool ok = qok && n <= m;
           if (LOCAL) ok = ok && (n < a.sink || n > m - a.window);
-          if (SPARSE) ok = (selmask[kb] >> i) & 1u;
           S[kb][i] = ok ? S[kb][i] : ninf;
           mx = fmaxf(mx, S[kb][i]);
         }
@@ -363,56 +329,34 @@ __global__ __launch_bounds__(kPfThreads, 2) void flash_prefill_kernel(const Pref
     }
   };
 
-  if (SPARSE) {
-    // Selecting mode: a tile is staged only if some query of the workgroup keeps one of its keys.
-    const int n_rows = pos0 + a.n_q;
-    for (int kt = 0; kt <= kt_end; ++kt) {
-      const int n0 = kt * kPfK;
-      uint32_t selmask[2];
-#pragma unroll
-      for (int kb = 0; kb < 2; ++kb) {
-        const int nrow = n0 + kb * 32 + r;
-        u32x4 ka = (u32x4){0u, 0u, 0u, 0u};
-        if (nrow < n_rows) ka = *reinterpret_cast<const u32x4*>(kIg + (int64_t)nrow * kIndexDim + g * 8);
-        f32x16 SI;
-#pragma unroll
-        for (int i = 0; i < 16; ++i) SI[i] = 0.f;
-        SI = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, ka), __builtin_bit_cast(bf16x8, qIreg),
-                                                     SI, 0, 0, 0);
-        uint32_t mk = 0;
-#pragma unroll
-        for (int i = 0; i < 16; ++i) {
-          const int n = n0 + kb * 32 + (i >> 2) * 8 + g * 4 + (i & 3);
-          bool keep = qok && n <= m;
-          if (selQ != 0x7fffffff) keep = keep && sel_q(selM, SI[i] * a.index_scale) <= selQ;
-          mk |= (keep ? 1u : 0u) << i;
-        }
-        selmask[kb] = mk;
-        sel_cnt += __popc(mk);
-      }
-      const int wave_any = (__ballot((selmask[0] | selmask[1]) != 0u) != 0ull) ? 1 : 0;
-      if (!__syncthreads_or(wave_any)) continue;     // nobody in the workgroup needs this key tile
-      load_tile(n0);
-      store_tile(0);
-      __syncthreads();
-      if (wave_any) compute_tile(0, n0, selmask);
-    }
-  } else {
+  {
     // Software pipeline: the global loads of tile it+1 are in flight while tile it is computed from
-    // the other LDS buffer; one barrier per tile.
-    const uint32_t nomask[2] = {0xffffu, 0xffffu};
+    // the other LDS buffer; one barrier per tile.  Selecting mode: the index keys of a tile are fetched
+    // two tiles ahead (every tile is staged: at the set sizes top-p produces, a 128-query x 64-key
+    // tile without a single kept pair practically does not occur).
     auto tile_n0 = [&](int it) { return (it < ks_end ? it : kt_w0 + (it - ks_end)) * kPfK; };
     const int it_lo = (int)((int64_t)n_tiles * split / n_splits);
     const int it_hi = (int)((int64_t)n_tiles * (split + 1) / n_splits);
+    u32x4 kiA[2] = {(u32x4){0u, 0u, 0u, 0u}, (u32x4){0u, 0u, 0u, 0u}}, kiB[2] = {(u32x4){0u, 0u, 0u, 0u}, (u32x4){0u, 0u, 0u, 0u}};
     if (it_lo < it_hi) {
       load_tile(tile_n0(it_lo));
+      if (SPARSE) {
+        load_ki(tile_n0(it_lo), kiA);
+        load_ki(tile_n0(it_lo + 1), kiB);
+      }
       store_tile(it_lo & 1);
       __syncthreads();
     }
     for (int it = it_lo; it < it_hi; ++it) {
       const bool has_next = it + 1 < it_hi;
       if (has_next) load_tile(tile_n0(it + 1));
-      compute_tile(it & 1, tile_n0(it), nomask);
+      if (SPARSE) {
+        // kiA carries the tiles it_lo, it_lo + 2, ..., kiB the ones between; refill the consumed one
+        if ((it - it_lo) & 1) { compute_tile(it & 1, tile_n0(it), kiB); load_ki(tile_n0(it + 2), kiB); }
+        else                  { compute_tile(it & 1, tile_n0(it), kiA); load_ki(tile_n0(it + 2), kiA); }
+      } else {
+        compute_tile(it & 1, tile_n0(it), kiA);
+      }
       if (has_next) store_tile((it + 1) & 1);
       __syncthreads();
     }
@@ -452,11 +396,298 @@ __global__ __launch_bounds__(kPfThreads, 2) void flash_prefill_kernel(const Pref
     if (g == 0) {
       const int64_t o = (int64_t)blockIdx.x * a.n_q + t;
       if (a.count) a.count[o] = cnt;
-      if (a.mass) a.mass[o] = sel_mass;
-      // kept: scores s with floor((M - s) * 2^17) <= selQ, i.e. s > M - (selQ + 1) / 2^17
-      if (a.tau) a.tau[o] = selQ != 0x7fffffff ? selM - (float)(selQ + 1) * (1.0f / kSelScale) : ninf;
+      if (!(a.p < 1.f)) {                      // keep-all: the threshold search did not run
+        if (a.mass) a.mass[o] = 1.f;
+        if (a.tau) a.tau[o] = ninf;
+      }
     }
   }
+}
+
+// ---- per-query top-p threshold search (selecting mode of rtp_sparse_attn_prefill) ---------------------
+// Sec. 3.2, S = Top-P(s(m, .), p), applied to every prefill query over its causal candidates n <= m.
+//
+// A wave works alone on 32 queries of one retrieval head and sweeps the index keys 0..m four times:
+// sweep 0 finds the row maximum M; sweeps 1-3 histogram the softmax mass over the integer
+// q = floor(min((M - s) * 2^17, 2^21 - 1)) one base-128 digit at a time (all candidates in sweep 1, only
+// the members of the digit prefix found so far in sweeps 2 and 3) and scan the histogram from the top of
+// the score range for the bin where the cumulative mass reaches p * Z.  The index-score tile of 32 keys
+// x 32 queries is ONE MFMA (K = 16) in the transposed layout, so a lane holds 16 keys of its own query.
+//
+// What makes the sweeps cheap:
+//  - index keys are fetched kSelRing tiles ahead into registers (the wave is alone on its SIMD, so
+//    nothing else hides the latency);
+//  - interior tiles (every key a candidate of every query of the wave) carry no mask arithmetic;
+//  - the histogram of a wave is laid out [bin][query]: the 32 queries of a wave sit in 32 different
+//    LDS bank pairs whatever their bins, so an fp64 LDS atomic of the wave sees only the two-way
+//    conflict between the two lanes of one query;
+//  - q is a monotone function of the raw MFMA product x (s = x * index_scale), so "q lies in the digit
+//    prefix" is an interval of x.  Its two end points are found once per query and sweep by bisection
+//    over the float bit patterns, evaluating the very expression that defines q -- the comparisons of
+//    sweeps 2, 3 and of the attention kernel are then exact restatements of that definition, two
+//    (one) compare per pair, and only members do any further arithmetic.
+// No workgroup barrier: every wave owns its slice of LDS.
+#pragma clang fp contract(off)
+__device__ __forceinline__ float sel_t(float M, float x, float index_scale) { return M - x * index_scale; }
+#pragma clang fp contract(on)
+
+// Smallest float x (as a raw product) with sel_t(M, x) < bound; -inf if every finite x qualifies.
+// sel_t is non-increasing in x, so the predicate flips once from false to true.
+__device__ __forceinline__ float sel_first_below(float M, float index_scale, float bound) {
+  if (bound == __builtin_huge_valf()) return -__builtin_huge_valf();
+  uint32_t lo = float_key(-__builtin_huge_valf()), hi = float_key(__builtin_huge_valf());
+  while (lo < hi) {
+    const uint32_t mid = lo + ((hi - lo) >> 1);
+    if (sel_t(M, key_float(mid), index_scale) < bound) hi = mid; else lo = mid + 1;
+  }
+  return key_float(lo);
+}
+
+__global__ __launch_bounds__(kPfThreads, 1) void prefill_select_kernel(const PrefillArgs a) {
+  __shared__ double hist_all[kPfThreads / 64][kSelBins][32];       // 128 KB
+  __shared__ float list_all[kPfThreads / 64][kSelListCap][64];     // per-lane member lists of sweeps 2 and 3
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int g = lane >> 5, r = lane & 31;
+  // Workgroups go round-robin over the chip's 8 dies, each with its own L2.  The 1-D grid is decoded so
+  // that a die works on ONE head (8 / n_heads dies per head): all its waves then stream the same index
+  // keys and meet in that L2.
+  int j, qtile;
+  const int n_qtiles = (a.n_q + kPfQ - 1) / kPfQ;
+  if (a.n_heads <= 8 && 8 % a.n_heads == 0) {
+    const int per_head = 8 / a.n_heads;                            // dies per head
+    const int die = blockIdx.x & 7, k = blockIdx.x >> 3;
+    j = die / per_head;
+    qtile = k * per_head + die % per_head;
+  } else {
+    j = blockIdx.x % a.n_heads;
+    qtile = blockIdx.x / a.n_heads;
+  }
+  if (qtile >= n_qtiles) return;
+  const int t0 = (n_qtiles - 1 - qtile) * kPfQ;                    // long rows first
+  if (t0 + wave * 32 >= a.n_q) return;                             // no query in this wave
+  const int pos0 = (int)a.q_start_host;
+  const int t = t0 + wave * 32 + r;
+  const bool qok = t < a.n_q;
+  const int m = pos0 + t;
+  const float ninf = -__builtin_huge_valf(), pinf = __builtin_huge_valf();
+  const float cs = a.index_scale;
+  const uint16_t* kIg = a.kI + (int64_t)j * a.kI_head_stride;
+  u32x4 qIreg = (u32x4){0u, 0u, 0u, 0u};
+  if (qok) qIreg = *reinterpret_cast<const u32x4*>(a.qI + ((int64_t)j * a.n_q + t) * kIndexDim + g * 8);
+  const int n_rows = pos0 + a.n_q;                                 // index-key rows that exist
+  const int m_wave_lo = pos0 + t0 + wave * 32;
+  const int m_wave_hi = pos0 + min(t0 + wave * 32 + 32, a.n_q) - 1;
+  const bool wave_partial = t0 + wave * 32 + 32 > a.n_q;
+  const int n_tiles = m_wave_hi / 32 + 1;
+  const int n_interior = wave_partial ? 0 : (m_wave_lo + 1) / 32;  // tiles with nb + 31 <= m_wave_lo
+  double (*hist)[32] = hist_all[wave];
+  float (*lst)[64] = list_all[wave];
+  int lcnt = 0;                     // entries in this lane's member list
+
+  auto load_k = [&](int tile) {
+    const int nrow = min(tile * 32 + r, n_rows - 1);               // rows past the chunk are causally masked anyway
+    return *reinterpret_cast<const u32x4*>(kIg + (int64_t)nrow * kIndexDim + g * 8);
+  };
+  auto zero_hist = [&]() {
+    double* h = &hist[0][0];
+    for (int i = lane; i < kSelBins * 32; i += 64) h[i] = 0.0;
+  };
+  // One candidate's mass into bin `bin` of this lane's query.
+  auto add_mass = [&](int bin, float tt) {
+    const float wgt = fast_exp2(tt * -1.4426950408889634f);        // exp(s - M)
+    atomicAdd(&hist[bin][r], (double)wgt);
+  };
+
+  float selM = ninf;
+  float x_lo = ninf, x_top = pinf;  // sweeps 2, 3: members of the prefix have x_lo <= x <= x_top
+  int shift = 0;
+  float mxs[4] = {ninf, ninf, ninf, ninf};
+
+  // One sweep over the index keys; PH is std::integral_constant<int, phase>, EDGE says whether the tiles
+  // [tile_begin, tile_end) need the causal mask.
+  // Weighs the listed members of every lane: lane-private lists, so the only cross-lane step is the
+  // loop bound.
+  auto drain_list = [&]() {
+    for (int k = 0; __ballot(k < lcnt) != 0ull; ++k) {
+      if (k < lcnt) {
+        const float tt = sel_t(selM, lst[k][lane], cs);
+        add_mass((sel_q_of_t(tt) >> shift) & (kSelBins - 1), tt);
+      }
+    }
+    lcnt = 0;
+  };
+
+  // What one tile contributes in phase PH: SI = its 32 x 32 index products, nb = its first key.
+  auto tile_work = [&](auto PH, auto EDGE, const f32x16& SI, int nb, float& mxacc) {
+    constexpr int phase = decltype(PH)::value;
+    constexpr bool edge = decltype(EDGE)::value;
+    if (phase == 0) {
+      // scaling by a positive constant is monotone, so the maximum is taken on the raw products
+      float v[16];
+#pragma unroll
+      for (int i = 0; i < 16; ++i) {
+        const int n = nb + (i >> 2) * 8 + g * 4 + (i & 3);
+        v[i] = (!edge || (qok && n <= m)) ? SI[i] : ninf;
+      }
+#pragma unroll
+      for (int st = 8; st > 0; st >>= 1)
+#pragma unroll
+        for (int i = 0; i < st; ++i) v[i] = fmaxf(v[i], v[i + st]);
+      mxacc = fmaxf(mxacc, v[0]);
+    } else if (phase == 1) {
+#pragma unroll
+      for (int i = 0; i < 16; ++i) {
+        const int n = nb + (i >> 2) * 8 + g * 4 + (i & 3);
+        if (!edge || (qok && n <= m)) {
+          const float tt = sel_t(selM, SI[i], cs);
+          // first digit of q: floor(min(tt * 2^17, 2^21 - 1)) >> 14 == floor(min(tt * 8, (2^21 - 1) / 2^14))
+          const int bin = (int)fminf(tt * 8.0f, 127.99993896484375f);
+          add_mass(bin, tt);
+        }
+      }
+    } else {
+      // Members of the digit prefix (about one pair in a hundred in sweep 2, one in ten thousand in
+      // sweep 3) are only noted here -- their raw product goes to the lane's list -- and weighed later
+      // with all lanes busy (drain_list); weighing them where they turn up would run the exponential
+      // and the atomic for one or two active lanes at a time.
+      // Membership x_lo <= x <= x_top is one median and one comparison on the vector ALU (going through
+      // scalar condition registers costs a vector-to-scalar hand-off per pair).  Appending is branch-free:
+      // every pair writes its product at the list's end, members advance the end.  Sweep 3 first counts the
+      // tile's members and skips the appends when the whole wave has none (nearly always).
+      auto member = [&](int i) {
+        const int n = nb + (i >> 2) * 8 + g * 4 + (i & 3);
+        const bool in = __builtin_amdgcn_fmed3f(SI[i], x_lo, x_top) == SI[i];
+        return edge ? (in && qok && n <= m) : in;
+      };
+      bool go = true;
+      if (phase == 3) {
+        int c = 0;
+#pragma unroll
+        for (int i = 0; i < 16; ++i) c += member(i) ? 1 : 0;
+        go = __ballot(c != 0) != 0ull;
+      }
+      if (go) {
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+          lst[lcnt][lane] = SI[i];
+          lcnt += member(i) ? 1 : 0;
+        }
+        if (__ballot(lcnt > kSelListCap - 16) != 0ull) drain_list();
+      }
+    }
+  };
+
+  // One sweep over the tiles [tile_begin, tile_end) in rounds of 2 * kSelRing: two groups of index-key
+  // registers alternate, each refilled (for two groups ahead) as soon as its MFMAs have read it, so a
+  // load has a whole group's arithmetic to land in; the kSelRing MFMAs of a group are issued together and
+  // their latency hides behind one another.  No tail test: the interior range is a whole number of
+  // rounds, and in the edge range a tile past the last one holds only keys n > m, which the causal mask drops.
+  auto sweep = [&](auto PH, auto EDGE, int tile_begin, int tile_end) {
+    if (tile_begin >= tile_end) return;
+    u32x4 ringA[kSelRing], ringB[kSelRing];
+#pragma unroll
+    for (int u = 0; u < kSelRing; ++u) {
+      ringA[u] = load_k(tile_begin + u);
+      ringB[u] = load_k(tile_begin + kSelRing + u);
+    }
+    auto group = [&](u32x4 (&ring)[kSelRing], int first) {
+#pragma unroll
+      for (int hb = 0; hb < kSelRing; hb += 4) {                   // four MFMAs in flight at a time
+        f32x16 SI[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+#pragma unroll
+          for (int i = 0; i < 16; ++i) SI[u][i] = 0.f;
+          SI[u] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, ring[hb + u]),
+                                                          __builtin_bit_cast(bf16x8, qIreg), SI[u], 0, 0, 0);
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) ring[hb + u] = load_k(first + 2 * kSelRing + hb + u);
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+          __builtin_amdgcn_sched_barrier(0);       // one tile at a time: hoisting four tiles' operands runs out of registers
+          tile_work(PH, EDGE, SI[u], (first + hb + u) * 32, mxs[u]);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+      }
+    };
+#pragma unroll 1
+    for (int base = tile_begin; base < tile_end; base += 2 * kSelRing) {
+      group(ringA, base);
+      group(ringB, base + kSelRing);
+    }
+  };
+  const int n_plain = n_interior / (2 * kSelRing) * (2 * kSelRing);   // whole rounds of interior tiles run without masks
+  auto sweep_all = [&](auto PH) {
+    sweep(PH, std::false_type{}, 0, n_plain);
+    sweep(PH, std::true_type{}, n_plain, n_tiles);
+    if (decltype(PH)::value >= 2) drain_list();
+  };
+
+  double Z = 0.0, above = 0.0;
+  int prefix = 0;                 // digits of the threshold found so far
+  float sel_mass = 1.f;
+  float cut = pinf;               // keep a candidate iff M - s < cut
+
+  zero_hist();
+#pragma unroll 1
+  for (int phase = 0; phase < 4; ++phase) {
+    shift = 7 * (3 - phase);                                       // phase 1: 14, phase 2: 7, phase 3: 0
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");         // zeroed bins before this sweep's atomics
+    if (phase == 0) sweep_all(std::integral_constant<int, 0>{});
+    else if (phase == 1) sweep_all(std::integral_constant<int, 1>{});
+    else if (phase == 2) sweep_all(std::integral_constant<int, 2>{});
+    else sweep_all(std::integral_constant<int, 3>{});
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");         // the wave's atomics before the scan's loads
+    if (phase == 0) {
+      float mx = fmaxf(fmaxf(mxs[0], mxs[1]), fmaxf(mxs[2], mxs[3]));
+      mx = fmaxf(mx, __shfl_xor(mx, 32));
+      selM = mx * cs;
+      continue;
+    }
+    // ---- scan this query's bins from the top of the score range (bin 0) down; both lanes of the
+    // pair run the same scan on the same numbers ----
+    if (phase == 1) {
+      Z = 0.0;
+      for (int i = 0; i < kSelBins; ++i) Z += hist[i][r];
+    }
+    const double target = (double)a.p * Z;
+    double cum = above, hsel = 0.0;
+    int bsel = kSelBins - 1;
+    bool found = false;
+    for (int i = 0; i < kSelBins; ++i) {
+      const double hv = hist[i][r];
+      if (!found) {
+        if (cum + hv >= target) { bsel = i; hsel = hv; found = true; }
+        else cum += hv;
+      }
+    }
+    prefix = (prefix << 7) | bsel;
+    above = cum;
+    if (phase < 3) {
+      // members of the prefix: prefix << shift <= q < (prefix + 1) << shift; for the non-negative
+      // tt = M - s of a candidate that is qlo / 2^17 <= tt < qhi / 2^17 (the last bin is open-ended),
+      // and in terms of the raw product x: first x with tt < hi bound <= x < first x with tt < lo bound
+      const int qlo = prefix << shift, qhi = (prefix + 1) << shift;
+      const float lo_t = (float)qlo * (1.0f / kSelScale);
+      const float hi_t = qhi > kSelQMax ? pinf : (float)qhi * (1.0f / kSelScale);
+      x_lo = sel_first_below(selM, cs, hi_t);
+      // the largest x that is still a member: the float just below the first x with tt < lo bound
+      x_top = key_float(float_key(sel_first_below(selM, cs, lo_t)) - 1u);
+      zero_hist();
+    } else {
+      // a threshold inside the open-ended last coarse bin keeps every candidate
+      const bool lump = (prefix >> 14) == kSelBins - 1;
+      cut = lump ? pinf : (float)(prefix + 1) * (1.0f / kSelScale);
+      sel_mass = (lump || !(Z > 0.0)) ? 1.f : (float)((cum + hsel) / Z);
+    }
+  }
+  if (!qok || g != 0) return;
+  const int64_t o = (int64_t)j * a.n_q + t;
+  a.sel_thr[o] = sel_first_below(selM, cs, cut);
+  if (a.mass) a.mass[o] = sel_mass;
+  // kept: candidates with floor((M - s) * 2^17) <= the threshold's digit string, i.e. s > M - cut
+  if (a.tau) a.tau[o] = cut != pinf ? selM - cut : ninf;
 }
 
 // ---- the wide kernel: dense and local modes ---------------------------------------------------------
@@ -1035,10 +1266,13 @@ using namespace rtp;
 
 extern "C" size_t rtp_sparse_attn_prefill_workspace_bytes(const rtp_layer_desc* layer, int32_t T, int64_t chunk_start) {
   if (!layer || T <= 0 || layer->n_ret <= 0) return 256;
-  const size_t proj = align_up((size_t)layer->n_ret * T * kIndexDim * sizeof(uint16_t), 256);   // projected index queries
+  // selecting mode: projected index queries, then one threshold per (retrieval head, query)
+  const size_t proj = align_up((size_t)layer->n_ret * T * kIndexDim * sizeof(uint16_t), 256);
+  const size_t state = align_up((size_t)layer->n_ret * T * sizeof(float), 256);
+  // dense rule: key-range partials
   const int ns = choose_splits(layer->n_ret, T, chunk_start < 0 ? 0 : chunk_start);
   const size_t part = ns > 1 ? align_up((size_t)ns * layer->n_ret * T * kPfPart * sizeof(float), 256) : 0;
-  return proj > part ? proj : part;
+  return proj + state > part ? proj + state : part;
 }
 
 extern "C" int32_t rtp_sparse_attn_prefill(const rtp_layer_desc* layer, const void* q_pre, const void* q, const float* WQ,
@@ -1061,7 +1295,7 @@ extern "C" int32_t rtp_sparse_attn_prefill(const rtp_layer_desc* layer, const vo
     if (!q_pre || !kI) return fail(RTP_ERR_INVALID_ARG, "%s: NULL index tensors", who);
     if (((uintptr_t)q_pre & 15) || ((uintptr_t)kI & 15) || (kI_head_stride & 7) || kI_head_stride < 0)
       return fail(RTP_ERR_INVALID_ARG, "%s: index tensors must be 16-byte aligned, kI_head_stride a multiple of 8", who);
-    if (layer->n_ret > 0 && WQ) {
+    if (layer->n_ret > 0 && (WQ || p < 1.f)) {
       const size_t need = rtp_sparse_attn_prefill_workspace_bytes(layer, T, chunk_start);
       if (!ws || ((uintptr_t)ws & 255) || ws_bytes < need)
         return fail(RTP_ERR_WORKSPACE, "%s: workspace of %zu bytes (256-byte aligned) required, got %zu", who, need, ws_bytes);
@@ -1122,8 +1356,19 @@ extern "C" int32_t rtp_sparse_attn_prefill(const rtp_layer_desc* layer, const vo
   a.tau = tau;
   a.count = count;
   a.mass = mass;
+  a.sel_thr = ws ? (float*)((char*)ws + align_up((size_t)layer->n_ret * T * kIndexDim * sizeof(uint16_t), 256)) : nullptr;
   dim3 grid((unsigned)a.n_heads, (unsigned)((T + kPfQ - 1) / kPfQ), 1);
   if (grid.y > 65535) return fail(RTP_ERR_INVALID_ARG, "%s: T too large for one launch", who);
+  if (p < 1.f) {
+    // 1-D grid, padded so that every die gets whole (head, query tile) columns (see the kernel's decoding)
+    const unsigned n_qtiles = grid.y;
+    unsigned wgs = (unsigned)a.n_heads * n_qtiles;
+    if (a.n_heads <= 8 && 8 % a.n_heads == 0) {
+      const unsigned per_head = 8u / (unsigned)a.n_heads;
+      wgs = 8u * ((n_qtiles + per_head - 1) / per_head);
+    }
+    hipLaunchKernelGGL(prefill_select_kernel, dim3(wgs), dim3(kPfThreads), 0, (hipStream_t)stream, a);
+  }
   hipLaunchKernelGGL(flash_prefill_kernel<kModeSparse>, grid, dim3(kPfThreads), 0, (hipStream_t)stream, a);
   return check_launch(who);
 }
