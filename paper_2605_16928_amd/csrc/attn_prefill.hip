@@ -87,16 +87,16 @@ __device__ __forceinline__ uint32_t pack_bf16(float a, float b) {
 }
 
 template <int MODE>
-__global__ __launch_bounds__(kPfThreads, MODE == kModeSparse ? 1 : 2) void flash_prefill_kernel(const PrefillArgs a) {
+__global__ __launch_bounds__(kPfThreads, 2) void flash_prefill_kernel(const PrefillArgs a) {
   constexpr bool LOCAL = MODE == kModeLocal;
-  constexpr bool SPARSE = MODE == kModeSparse;
+  static_assert(MODE == kModeDense || MODE == kModeLocal, "the selecting mode lives in the wide kernel");
   __shared__ __attribute__((aligned(16))) unsigned char smem[kSmemDense];
   uint16_t* Ks = reinterpret_cast<uint16_t*>(smem);
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int g = lane >> 5, r = lane & 31;
   const int h = a.heads[blockIdx.x];
-  const int n_splits = SPARSE || LOCAL ? 1 : a.n_splits;
+  const int n_splits = LOCAL ? 1 : a.n_splits;
   const int b = blockIdx.z / n_splits;
   const int split = blockIdx.z - b * n_splits;
   const int t0 = ((int)gridDim.y - 1 - (int)blockIdx.y) * kPfQ;
@@ -130,29 +130,6 @@ __global__ __launch_bounds__(kPfThreads, MODE == kModeSparse ? 1 : 2) void flash
 
   const uint16_t* Kg = a.K + (int64_t)kvh * a.head_stride + tok0 * a.row_stride;
   const uint16_t* Vg = a.V + (int64_t)kvh * a.head_stride + tok0 * a.row_stride;
-
-  // ---- sparse mode: the per-query threshold was found by prefill_select_kernel ----
-  // The index-score tile is ONE MFMA (K = 16) in the same transposed layout as the attention scores,
-  // so a lane sees 16 keys of its own query; a key is kept iff its raw product reaches the threshold.
-  u32x4 qIreg = (u32x4){0u, 0u, 0u, 0u};
-  const uint16_t* kIg = nullptr;
-  float selThr = ninf;                           // -inf keeps every candidate (p >= 1)
-  int sel_cnt = 0;
-  const bool wave_partial = t0 + wave * 32 + 32 > a.n_q;
-  const int n_rows = pos0 + a.n_q;               // index-key rows that exist
-  if (SPARSE) {
-    const int j = blockIdx.x;
-    kIg = a.kI + (int64_t)j * a.kI_head_stride;
-    if (qok) qIreg = *reinterpret_cast<const u32x4*>(a.qI + ((int64_t)j * a.n_q + t) * kIndexDim + g * 8);
-    if (a.p < 1.f && qok) selThr = a.sel_thr[(int64_t)j * a.n_q + t];
-  }
-  auto load_ki = [&](int n0, u32x4 (&k2)[2]) {
-#pragma unroll
-    for (int kb = 0; kb < 2; ++kb) {
-      const int nrow = min(n0 + kb * 32 + r, n_rows - 1);         // rows past the chunk are causally masked anyway
-      k2[kb] = *reinterpret_cast<const u32x4*>(kIg + (int64_t)nrow * kIndexDim + g * 8);
-    }
-  };
 
   f32x16 O[4];
 #pragma unroll
@@ -217,7 +194,7 @@ __global__ __launch_bounds__(kPfThreads, MODE == kModeSparse ? 1 : 2) void flash
   };
 
   // ---- one key tile: S^T = K Q^T, online softmax, O^T += V^T P^T -----------------------------------
-  auto compute_tile = [&](int buf, int n0, const u32x4 (&ki2)[2]) {
+  auto compute_tile = [&](int buf, int n0) {
     const uint16_t* ks = Ks + buf * (kTileHalfs);
     const uint16_t* vt = ks + kPfK * kKsStride;
     f32x16 S[2];
@@ -233,37 +210,9 @@ __global__ __launch_bounds__(kPfThreads, MODE == kModeSparse ? 1 : 2) void flash
       }
     }
     // interior tiles (every key visible to every query of the wave) skip the mask arithmetic
-    const bool edge = (n0 + kPfK - 1 > m_wave_lo) || (LOCAL && n0 <= m_wave_hi - a.window) || (SPARSE && wave_partial);
+    const bool edge = (n0 + kPfK - 1 > m_wave_lo) || (LOCAL && n0 <= m_wave_hi - a.window);
     float mx = ninf;
-    if (SPARSE) {
-      // selecting mode: one index-score MFMA per 32 keys, one comparison per pair
-#pragma unroll
-      for (int kb = 0; kb < 2; ++kb) {
-        f32x16 SI;
-#pragma unroll
-        for (int i = 0; i < 16; ++i) SI[i] = 0.f;
-        SI = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, ki2[kb]), __builtin_bit_cast(bf16x8, qIreg),
-                                                     SI, 0, 0, 0);
-        if (!edge) {
-#pragma unroll
-          for (int i = 0; i < 16; ++i) {
-            const bool keep = SI[i] >= selThr;
-            sel_cnt += keep ? 1 : 0;
-            S[kb][i] = keep ? S[kb][i] : ninf;
-            mx = fmaxf(mx, S[kb][i]);
-          }
-        } else {
-#pragma unroll
-          for (int i = 0; i < 16; ++i) {
-            const int n = n0 + kb * 32 + (i >> 2) * 8 + g * 4 + (i & 3);
-            const bool keep = SI[i] >= selThr && qok && n <= m;
-            sel_cnt += keep ? 1 : 0;
-            S[kb][i] = keep ? S[kb][i] : ninf;
-            mx = fmaxf(mx, S[kb][i]);
-          }
-        }
-      }
-    } else if (edge) {
+    if (edge) {
 #pragma unroll
       for (int kb = 0; kb < 2; ++kb) {
 #pragma unroll
@@ -331,32 +280,19 @@ __global__ __launch_bounds__(kPfThreads, MODE == kModeSparse ? 1 : 2) void flash
 
   {
     // Software pipeline: the global loads of tile it+1 are in flight while tile it is computed from
-    // the other LDS buffer; one barrier per tile.  Selecting mode: the index keys of a tile are fetched
-    // two tiles ahead (every tile is staged: at the set sizes top-p produces, a 128-query x 64-key
-    // tile without a single kept pair practically does not occur).
+    // the other LDS buffer; one barrier per tile.
     auto tile_n0 = [&](int it) { return (it < ks_end ? it : kt_w0 + (it - ks_end)) * kPfK; };
     const int it_lo = (int)((int64_t)n_tiles * split / n_splits);
     const int it_hi = (int)((int64_t)n_tiles * (split + 1) / n_splits);
-    u32x4 kiA[2] = {(u32x4){0u, 0u, 0u, 0u}, (u32x4){0u, 0u, 0u, 0u}}, kiB[2] = {(u32x4){0u, 0u, 0u, 0u}, (u32x4){0u, 0u, 0u, 0u}};
     if (it_lo < it_hi) {
       load_tile(tile_n0(it_lo));
-      if (SPARSE) {
-        load_ki(tile_n0(it_lo), kiA);
-        load_ki(tile_n0(it_lo + 1), kiB);
-      }
       store_tile(it_lo & 1);
       __syncthreads();
     }
     for (int it = it_lo; it < it_hi; ++it) {
       const bool has_next = it + 1 < it_hi;
       if (has_next) load_tile(tile_n0(it + 1));
-      if (SPARSE) {
-        // kiA carries the tiles it_lo, it_lo + 2, ..., kiB the ones between; refill the consumed one
-        if ((it - it_lo) & 1) { compute_tile(it & 1, tile_n0(it), kiB); load_ki(tile_n0(it + 2), kiB); }
-        else                  { compute_tile(it & 1, tile_n0(it), kiA); load_ki(tile_n0(it + 2), kiA); }
-      } else {
-        compute_tile(it & 1, tile_n0(it), kiA);
-      }
+      compute_tile(it & 1, tile_n0(it));
       if (has_next) store_tile((it + 1) & 1);
       __syncthreads();
     }
@@ -390,17 +326,6 @@ __global__ __launch_bounds__(kPfThreads, MODE == kModeSparse ? 1 : 2) void flash
   }
   if (a.lse && g == 0) {
     a.lse[((int64_t)b * a.n_q + t) * a.n_q_heads + h] = ltot > 0.f ? mrow * a.scale + logf(ltot) : ninf;
-  }
-  if (SPARSE) {
-    const int cnt = sel_cnt + __shfl_xor(sel_cnt, 32);
-    if (g == 0) {
-      const int64_t o = (int64_t)blockIdx.x * a.n_q + t;
-      if (a.count) a.count[o] = cnt;
-      if (!(a.p < 1.f)) {                      // keep-all: the threshold search did not run
-        if (a.mass) a.mass[o] = 1.f;
-        if (a.tau) a.tau[o] = ninf;
-      }
-    }
   }
 }
 
@@ -726,6 +651,7 @@ typedef short s16x8 __attribute__((ext_vector_type(8)));
 template <int MODE>
 __global__ __launch_bounds__(kPfThreads, 1) void flash_prefill_wide_kernel(const PrefillArgs a) {
   constexpr bool LOCAL = MODE == kModeLocal;
+  constexpr bool SPARSE = MODE == kModeSparse;
   __shared__ __attribute__((aligned(16))) unsigned char smem[kSmemWide];
   unsigned char* const Ls = smem;       // stage s: K rows at Ls + s * kPwTileBytes, V rows 16 KiB further
 
@@ -777,6 +703,48 @@ __global__ __launch_bounds__(kPfThreads, 1) void flash_prefill_wide_kernel(const
   const int q_last = pos0 + a.n_q - 1;
   const int m_w_lo = pos0 + t0 + wave * 64;             // the wave's first query position
   const int m_w_hi = min(m_w_lo + 63, q_last);          // and its last (< m_w_lo: the wave has no queries)
+
+  // ---- selecting mode: a key is kept by a query iff the raw index product reaches the query's
+  // threshold (found by prefill_select_kernel; -inf keeps every candidate).  The index-score block of
+  // 32 keys x 32 queries is one MFMA (K = 16) in the layout of the attention scores. ----
+  u32x4 qIreg[2] = {(u32x4){0u, 0u, 0u, 0u}, (u32x4){0u, 0u, 0u, 0u}};
+  float selThr[2] = {ninf, ninf};
+  int sel_cnt[2] = {0, 0};
+  const uint16_t* kIg = nullptr;
+  const int n_rows = pos0 + a.n_q;                      // index-key rows that exist
+  if (SPARSE) {
+    const int j = blockIdx.x;
+    kIg = a.kI + (int64_t)j * a.kI_head_stride;
+#pragma unroll
+    for (int qb = 0; qb < 2; ++qb) {
+      if (qok[qb]) {
+        qIreg[qb] = *reinterpret_cast<const u32x4*>(a.qI + ((int64_t)j * a.n_q + tq[qb]) * kIndexDim + g * 8);
+        if (a.p < 1.f) selThr[qb] = a.sel_thr[(int64_t)j * a.n_q + tq[qb]];
+      }
+    }
+  }
+  // index keys of the 32-key block at nb0 (rows past the chunk repeat the last one: causally masked anyway)
+  auto load_ki = [&](int nb0) __attribute__((always_inline)) {
+    const int nrow = min(nb0 + r, n_rows - 1);
+    return *reinterpret_cast<const u32x4*>(kIg + (int64_t)nrow * kIndexDim + g * 8);
+  };
+  // drops the keys a query does not keep from its scores and counts the kept ones; run AFTER mask_block
+  // (causality shows as -inf there)
+  auto select_block = [&](f32x16 (&S)[2], const u32x4 ki) __attribute__((always_inline)) {
+#pragma unroll
+    for (int qb = 0; qb < 2; ++qb) {
+      f32x16 SI;
+#pragma unroll
+      for (int i = 0; i < 16; ++i) SI[i] = 0.f;
+      SI = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, ki), __builtin_bit_cast(bf16x8, qIreg[qb]), SI, 0, 0, 0);
+#pragma unroll
+      for (int i = 0; i < 16; ++i) {
+        const bool keep = SI[i] >= selThr[qb] && S[qb][i] != ninf;
+        sel_cnt[qb] += keep ? 1 : 0;
+        S[qb][i] = keep ? S[qb][i] : ninf;
+      }
+    }
+  };
 
   // ---- tile movers: direct global->LDS loads, no staging registers (rows past the last needed key
   // repeat that key: they are masked for every query, and real data keeps 0 * V finite) ----
@@ -940,6 +908,55 @@ __global__ __launch_bounds__(kPfThreads, 1) void flash_prefill_wide_kernel(const
     lrow[0] += l0;
     lrow[1] += l1;
   };
+  // The steady-state step of the selecting mode: the same interleaving, with the block's two index-score
+  // MFMAs in front and every probability gated by its query's keep test (one compare, one select, one
+  // add for the count per pair on the vector ALU).
+  auto pv_beside_softmax_sel = [&](const unsigned char* tile, int kb, const uint32_t (&Pin)[2][8], const f32x16 (&S)[2],
+                                   uint32_t (&Pout)[2][8], const u32x4 ki) __attribute__((always_inline)) {
+    f32x16 SI0, SI1;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) { SI0[i] = 0.f; SI1[i] = 0.f; }
+    SI0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, ki), __builtin_bit_cast(bf16x8, qIreg[0]), SI0, 0, 0, 0);
+    SI1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, ki), __builtin_bit_cast(bf16x8, qIreg[1]), SI1, 0, 0, 0);
+    const float mc0 = mrow[0] * c, mc1 = mrow[1] * c;
+    float l0 = 0.f, l1 = 0.f;
+    int c0 = 0, c1 = 0;
+    s16x8 va[8];
+    auto read_va = [&](int k) __attribute__((always_inline)) { va[k] = read_v(tile, kb, k >> 2, k & 3); };   // k = tt * 4 + db
+    read_va(0);
+    read_va(1);
+#pragma unroll
+    for (int k = 0; k < 8; ++k) {
+      const int tt = k >> 2, db = k & 3;
+      const bf16x8 pb0 = __builtin_bit_cast(bf16x8, (u32x4){Pin[0][4 * tt], Pin[0][4 * tt + 1], Pin[0][4 * tt + 2], Pin[0][4 * tt + 3]});
+      const bf16x8 pb1 = __builtin_bit_cast(bf16x8, (u32x4){Pin[1][4 * tt], Pin[1][4 * tt + 1], Pin[1][4 * tt + 2], Pin[1][4 * tt + 3]});
+      if (k + 2 < 8) read_va(k + 2);
+      O[0][db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, va[k]), pb0, O[0][db], 0, 0, 0);
+      {
+        const bool k0 = SI0[2 * k] >= selThr[0], k1 = SI0[2 * k + 1] >= selThr[0];
+        const float p0 = k0 ? fast_exp2(fmaf(S[0][2 * k], c, -mc0)) : 0.f;
+        const float p1 = k1 ? fast_exp2(fmaf(S[0][2 * k + 1], c, -mc0)) : 0.f;
+        c0 += (k0 ? 1 : 0) + (k1 ? 1 : 0);
+        l0 += p0 + p1;
+        Pout[0][k] = pack_bf16(p0, p1);
+      }
+      __builtin_amdgcn_sched_barrier(0);
+      O[1][db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, va[k]), pb1, O[1][db], 0, 0, 0);
+      {
+        const bool k0 = SI1[2 * k] >= selThr[1], k1 = SI1[2 * k + 1] >= selThr[1];
+        const float p0 = k0 ? fast_exp2(fmaf(S[1][2 * k], c, -mc1)) : 0.f;
+        const float p1 = k1 ? fast_exp2(fmaf(S[1][2 * k + 1], c, -mc1)) : 0.f;
+        c1 += (k0 ? 1 : 0) + (k1 ? 1 : 0);
+        l1 += p0 + p1;
+        Pout[1][k] = pack_bf16(p0, p1);
+      }
+      __builtin_amdgcn_sched_barrier(0);
+    }
+    lrow[0] += l0;
+    lrow[1] += l1;
+    sel_cnt[0] += c0;
+    sel_cnt[1] += c1;
+  };
   // does the 32-key block starting at nb0 need per-element masks for some query of this wave?
   auto needs_mask = [&](int nb0) __attribute__((always_inline)) {
     bool e = false;
@@ -1002,6 +1019,11 @@ __global__ __launch_bounds__(kPfThreads, 1) void flash_prefill_wide_kernel(const
     // it + 2 go out during half 1 (their buffer held tile it - 1, last read in half 0) and every wave
     // waits for its own before the barrier that ends half 0 of tile it + 1.
     bool pend = false;
+    u32x4 ki0 = (u32x4){0u, 0u, 0u, 0u}, ki1 = ki0;       // index keys of the current tile's two blocks
+    if (SPARSE) {
+      ki0 = load_ki(tile_n0(it_lo));
+      ki1 = load_ki(tile_n0(it_lo) + 32);
+    }
     auto half = [&](int it, auto hf_tag) __attribute__((always_inline)) {
       constexpr int hf = decltype(hf_tag)::value;
       const int nb0 = block_n0(it, hf);
@@ -1013,12 +1035,18 @@ __global__ __launch_bounds__(kPfThreads, 1) void flash_prefill_wide_kernel(const
         pend = false;
       } else if (pend && !needs_mask(nb0)) {
         // steady state: PV of the previous block beside the softmax of this one
-        pv_beside_softmax(t_pend, 1 - hf, Pin, S, Pout);
+        if (SPARSE) pv_beside_softmax_sel(t_pend, 1 - hf, Pin, S, Pout, hf == 0 ? ki0 : ki1);
+        else pv_beside_softmax(t_pend, 1 - hf, Pin, S, Pout);
       } else {
         if (pend) mfma_PV(t_pend, 1 - hf, Pin);
         mask_block(S, nb0);
+        if (SPARSE) select_block(S, hf == 0 ? ki0 : ki1);
         softmax_fixed(S, Pout);
         pend = true;
+      }
+      if (SPARSE && hf == 1) {                             // the next tile's index keys: a tile's time to arrive
+        ki0 = load_ki(tile_n0(min(it + 1, it_hi - 1)));
+        ki1 = load_ki(tile_n0(min(it + 1, it_hi - 1)) + 32);
       }
       if (hf == 0) {
         if (is_active(nb0 + 32)) scores_beside(tile_at(it), 1, S, [&](int) __attribute__((always_inline)) {});
@@ -1049,7 +1077,9 @@ __global__ __launch_bounds__(kPfThreads, 1) void flash_prefill_wide_kernel(const
 #pragma unroll
     for (int qb = 0; qb < 2; ++qb) {
       const float ltot = lrow[qb] + __shfl_xor(lrow[qb], 32);
-      const bool sees_key = qok[qb] && (LOCAL || tile_n0(it_lo) <= mq[qb]);
+      // selecting mode: a query that kept no key of this range legitimately sums to zero
+      const bool sees_key = SPARSE ? (sel_cnt[qb] + __shfl_xor(sel_cnt[qb], 32) > 0)
+                                   : (qok[qb] && (LOCAL || tile_n0(it_lo) <= mq[qb]));
       bad = bad || (sees_key && !(ltot > 0x1p-60f && ltot < 0x1p100f));
     }
     redo = __syncthreads_or(bad ? 1 : 0) != 0;
@@ -1063,6 +1093,7 @@ __global__ __launch_bounds__(kPfThreads, 1) void flash_prefill_wide_kernel(const
     for (int qb = 0; qb < 2; ++qb) {
       mrow[qb] = ninf;
       lrow[qb] = 0.f;
+      sel_cnt[qb] = 0;
 #pragma unroll
       for (int db = 0; db < 4; ++db)
 #pragma unroll
@@ -1078,6 +1109,7 @@ __global__ __launch_bounds__(kPfThreads, 1) void flash_prefill_wide_kernel(const
         if (!is_active(nb0)) continue;
         if (kb == 0) mfma_S(Ls, 0, S); else mfma_S(Ls, 1, S);
         mask_block(S, nb0);
+        if (SPARSE) select_block(S, load_ki(nb0));
 #pragma unroll
         for (int qb = 0; qb < 2; ++qb) {
           float mx = S[qb][0];
@@ -1114,9 +1146,15 @@ __global__ __launch_bounds__(kPfThreads, 1) void flash_prefill_wide_kernel(const
     const float ltot = (it_lo < it_hi) ? lrow[qb] + __shfl_xor(lrow[qb], 32) : 0.f;
     if (!qok[qb]) continue;
     const float mfin = (it_lo < it_hi && ltot > 0.f) ? mrow[qb] : ninf;
+    const int kept = sel_cnt[qb] + __shfl_xor(sel_cnt[qb], 32);
+    if (SPARSE && g == 0 && split == 0 && !(a.p < 1.f)) {   // keep-all: the threshold search did not run
+      const int64_t o = (int64_t)blockIdx.x * a.n_q + tq[qb];
+      if (a.mass) a.mass[o] = 1.f;
+      if (a.tau) a.tau[o] = ninf;
+    }
     if (n_splits > 1) {
       float* prow = a.part + (((int64_t)split * a.n_heads + blockIdx.x) * a.n_q + tq[qb]) * kPfPart;
-      if (g == 0) { prow[0] = mfin; prow[1] = ltot; }
+      if (g == 0) { prow[0] = mfin; prow[1] = ltot; prow[2] = __int_as_float(kept); }
 #pragma unroll
       for (int db = 0; db < 4; ++db)
 #pragma unroll
@@ -1141,6 +1179,7 @@ __global__ __launch_bounds__(kPfThreads, 1) void flash_prefill_wide_kernel(const
     if (a.lse && g == 0) {
       a.lse[((int64_t)b * a.n_q + tq[qb]) * a.n_q_heads + h] = ltot > 0.f ? mfin * a.scale + logf(ltot) : ninf;
     }
+    if (SPARSE && a.count && g == 0) a.count[(int64_t)blockIdx.x * a.n_q + tq[qb]] = kept;
   }
 }
 
@@ -1172,6 +1211,11 @@ __global__ __launch_bounds__(256) void prefill_combine_kernel(const PrefillArgs 
   const float ninf = -__builtin_huge_valf();
   float M = ninf;
   for (int s = 0; s < a.n_splits; ++s) M = fmaxf(M, a.part[(((int64_t)s * a.n_heads + hs) * a.n_q + t) * kPfPart]);
+  if (a.count && d == 0) {                                 // selecting mode: kept keys over all key ranges
+    int kept = 0;
+    for (int s = 0; s < a.n_splits; ++s) kept += __float_as_int(a.part[(((int64_t)s * a.n_heads + hs) * a.n_q + t) * kPfPart + 2]);
+    a.count[(int64_t)hs * a.n_q + t] = kept;
+  }
   float L = 0.f, A = 0.f;
   if (M != ninf) {
     for (int s = 0; s < a.n_splits; ++s) {
@@ -1269,10 +1313,10 @@ extern "C" size_t rtp_sparse_attn_prefill_workspace_bytes(const rtp_layer_desc* 
   // selecting mode: projected index queries, then one threshold per (retrieval head, query)
   const size_t proj = align_up((size_t)layer->n_ret * T * kIndexDim * sizeof(uint16_t), 256);
   const size_t state = align_up((size_t)layer->n_ret * T * sizeof(float), 256);
-  // dense rule: key-range partials
+  // both rules: key-range partials
   const int ns = choose_splits(layer->n_ret, T, chunk_start < 0 ? 0 : chunk_start);
   const size_t part = ns > 1 ? align_up((size_t)ns * layer->n_ret * T * kPfPart * sizeof(float), 256) : 0;
-  return proj + state > part ? proj + state : part;
+  return proj + state + part;
 }
 
 extern "C" int32_t rtp_sparse_attn_prefill(const rtp_layer_desc* layer, const void* q_pre, const void* q, const float* WQ,
@@ -1295,7 +1339,7 @@ extern "C" int32_t rtp_sparse_attn_prefill(const rtp_layer_desc* layer, const vo
     if (!q_pre || !kI) return fail(RTP_ERR_INVALID_ARG, "%s: NULL index tensors", who);
     if (((uintptr_t)q_pre & 15) || ((uintptr_t)kI & 15) || (kI_head_stride & 7) || kI_head_stride < 0)
       return fail(RTP_ERR_INVALID_ARG, "%s: index tensors must be 16-byte aligned, kI_head_stride a multiple of 8", who);
-    if (layer->n_ret > 0 && (WQ || p < 1.f)) {
+    if (layer->n_ret > 0) {
       const size_t need = rtp_sparse_attn_prefill_workspace_bytes(layer, T, chunk_start);
       if (!ws || ((uintptr_t)ws & 255) || ws_bytes < need)
         return fail(RTP_ERR_WORKSPACE, "%s: workspace of %zu bytes (256-byte aligned) required, got %zu", who, need, ws_bytes);
@@ -1356,12 +1400,15 @@ extern "C" int32_t rtp_sparse_attn_prefill(const rtp_layer_desc* layer, const vo
   a.tau = tau;
   a.count = count;
   a.mass = mass;
-  a.sel_thr = ws ? (float*)((char*)ws + align_up((size_t)layer->n_ret * T * kIndexDim * sizeof(uint16_t), 256)) : nullptr;
-  dim3 grid((unsigned)a.n_heads, (unsigned)((T + kPfQ - 1) / kPfQ), 1);
-  if (grid.y > 65535) return fail(RTP_ERR_INVALID_ARG, "%s: T too large for one launch", who);
+  const size_t proj_bytes = align_up((size_t)layer->n_ret * T * kIndexDim * sizeof(uint16_t), 256);
+  const size_t state_bytes = align_up((size_t)layer->n_ret * T * sizeof(float), 256);
+  a.sel_thr = (float*)((char*)ws + proj_bytes);
+  a.part = (float*)((char*)ws + proj_bytes + state_bytes);
+  a.n_splits = choose_splits(layer->n_ret, T, chunk_start);
+  const unsigned n_qtiles = (unsigned)((T + kPfQ - 1) / kPfQ);
+  if (n_qtiles > 65535) return fail(RTP_ERR_INVALID_ARG, "%s: T too large for one launch", who);
   if (p < 1.f) {
     // 1-D grid, padded so that every die gets whole (head, query tile) columns (see the kernel's decoding)
-    const unsigned n_qtiles = grid.y;
     unsigned wgs = (unsigned)a.n_heads * n_qtiles;
     if (a.n_heads <= 8 && 8 % a.n_heads == 0) {
       const unsigned per_head = 8u / (unsigned)a.n_heads;
@@ -1369,6 +1416,10 @@ extern "C" int32_t rtp_sparse_attn_prefill(const rtp_layer_desc* layer, const vo
     }
     hipLaunchKernelGGL(prefill_select_kernel, dim3(wgs), dim3(kPfThreads), 0, (hipStream_t)stream, a);
   }
-  hipLaunchKernelGGL(flash_prefill_kernel<kModeSparse>, grid, dim3(kPfThreads), 0, (hipStream_t)stream, a);
+  dim3 grid((unsigned)a.n_heads, (unsigned)((T + kPwQ - 1) / kPwQ), (unsigned)a.n_splits);
+  hipLaunchKernelGGL(flash_prefill_wide_kernel<kModeSparse>, grid, dim3(kPfThreads), 0, (hipStream_t)stream, a);
+  if (a.n_splits > 1)
+    hipLaunchKernelGGL(prefill_combine_kernel, dim3((unsigned)((T + 1) / 2), (unsigned)a.n_heads), dim3(256), 0,
+                       (hipStream_t)stream, a);
   return check_launch(who);
 }
