@@ -34,6 +34,13 @@ Readings taken where the paper is silent:
   * decode candidates are all ctx_len cached tokens; prefill candidates are
     the causal ones, n <= m.
 
+Widened rows (each pinned the same way, see the end of this file):
+    build_index_keys   kI = bf16( W^K_h k^pre_{n,kv(h)} ), the key side of the indexer equation
+    topk_select        the static top-k rule the paper ablates against (Sec. 4.1 "Baselines")
+    block_topp_select  the block-wise histogram selector of Sec. 3.4, with the readings stated there
+    attention_mass     true attention probability captured by a token set        Sec. 4.2, sparsity table
+    sparsity_stats     compute / memory sparsity, active tokens                  Sec. 3.2 (last paragraph), Sec. 4.2
+
 Parity status: every function below is pinned by tests/test_oracle_pins.py
 (brute-force dense attention, hand-worked exact-binary top-p cases, closed
 forms, invariants).  Agreement with the paper's real-model statistics
@@ -48,6 +55,7 @@ __all__ = [
     "bf16_to_f64", "f64_to_bf16_bits", "index_project", "index_score",
     "topp_from_weights", "topp_select", "attend", "local_set", "kv_head_of",
     "decode_layer", "prefill_rows", "dense_rows",
+    "build_index_keys", "topk_select", "block_topp_select", "attention_mass", "sparsity_stats",
 ]
 
 
@@ -279,3 +287,139 @@ def dense_rows(*, rows, q_bits, K_bits, V_bits, chunk_start, n_q_heads, n_kv_hea
         o, l = attend(q_bits[t, h], K_bits[kvh, :m + 1], V_bits[kvh, :m + 1], np.arange(m + 1), sc)
         res.append(dict(t=t, h=h, m=m, out=o, lse=l))
     return res
+
+
+# --------------------------------------------------------------------------
+# index keys  (Sec. 3.2, indexer equation, key side)
+# --------------------------------------------------------------------------
+def build_index_keys(WK, k_pre_bits, ret_heads, n_q_heads: int, n_kv_heads: int) -> np.ndarray:
+    """kI[j, n, :] = bf16( W^K_{h_j} k^pre_{n, kv(h_j)} ) for every retrieval query head h_j.
+
+    WK float32 [n_ret, r, d]; k_pre_bits bf16 [T, Hkv, d] (keys BEFORE the rotary
+    embedding).  The projection is indexed by the QUERY head, the key row it is
+    applied to belongs to the KV head that query head reads.  -> uint16 [n_ret, T, r].
+    """
+    out = []
+    for j, h in enumerate(ret_heads):
+        kvh = kv_head_of(int(h), n_q_heads, n_kv_heads)
+        out.append(index_project(WK[j], k_pre_bits[:, kvh]))
+    return np.stack(out)
+
+
+# --------------------------------------------------------------------------
+# static top-k  (Sec. 4.1 "Baselines": the fixed-budget comparison, k = 4096 there)
+# --------------------------------------------------------------------------
+def topk_select(scores, k: int) -> dict:
+    """The k highest-scoring candidates (all of them if there are fewer); ties go to the lower index.
+
+    Returns dict(idx in rank order, count, tau = score of the last selected token,
+    mass = selected softmax mass of the scores).
+    """
+    s = np.asarray(scores, dtype=np.float64)
+    n = s.shape[0]
+    if n == 0:
+        raise ValueError("top-k needs at least one candidate")
+    if k < 1:
+        raise ValueError("k must be at least 1")
+    order = np.lexsort((np.arange(n), -s))
+    kk = min(int(k), n)
+    sel = order[:kk]
+    w = np.exp(s - np.max(s))
+    return dict(idx=sel, count=kk, tau=float(s[sel[-1]]), mass=float(np.sum(w[sel]) / np.sum(w)))
+
+
+# --------------------------------------------------------------------------
+# block-wise top-p  (Sec. 3.4 "Sort-free top-p via histogram")
+# --------------------------------------------------------------------------
+def block_topp_select(scores, p: float, block: int = 64, n_bins: int = 256,
+                      bin_lo: float = -32.0, bin_width: float = 0.25) -> dict:
+    """Block-level top-p in the order the section gives its steps.
+
+    1. cut the candidates into blocks of `block` consecutive tokens; block b is
+       reduced to its log-sum-exp pair  m_b = max s,  l_b = sum exp(s - m_b);
+    2. every block deposits its mass  l_b * exp(m_b)  into the histogram bin its
+       maximum m_b falls into;
+    3. the histogram is scanned from the highest bin down; the threshold bin is
+       the first one at which the cumulative mass reaches p * (total mass);
+    4. the mask keeps every block whose bin is at or above the threshold bin.
+
+    Readings (the section names neither the bin mapping nor the common scale of
+    the deposits): bins are uniform in score, bin(m) = floor((m - bin_lo) /
+    bin_width) clamped to [0, n_bins - 1]; masses are compared on one common
+    scale (here exp(. - max score), any common scale decides alike); p >= 1
+    keeps every block; whole blocks are kept, so the kept mass overshoots p by
+    up to the mass of the threshold bin.
+
+    Returns dict(block_mask bool [N_b], bins int [N_b], threshold_bin, idx =
+    token ids of the kept blocks ascending, count, mass = kept mass / total,
+    m_b, l_b).
+    """
+    s = np.asarray(scores, dtype=np.float64)
+    n = s.shape[0]
+    if n == 0:
+        raise ValueError("needs at least one candidate")
+    if not (p > 0.0):
+        raise ValueError("p must be positive")
+    nb = (n + block - 1) // block
+    m_b = np.empty(nb)
+    l_b = np.empty(nb)
+    for b in range(nb):
+        sb = s[b * block:(b + 1) * block]
+        m_b[b] = np.max(sb)
+        l_b[b] = np.sum(np.exp(sb - m_b[b]))
+    bins = np.clip(np.floor((m_b - bin_lo) / bin_width), 0, n_bins - 1).astype(np.int64)
+    ref = np.max(m_b)
+    mass_b = l_b * np.exp(m_b - ref)
+    hist = np.zeros(n_bins)
+    for b in range(nb):
+        hist[bins[b]] += mass_b[b]
+    total = float(np.sum(mass_b))
+    if p >= 1.0:
+        thr = 0
+    else:
+        cum = 0.0
+        thr = 0
+        for k in range(n_bins - 1, -1, -1):
+            cum += hist[k]
+            if cum >= p * total:
+                thr = k
+                break
+    mask = bins >= thr
+    idx = np.concatenate([np.arange(b * block, min((b + 1) * block, n)) for b in range(nb) if mask[b]])
+    return dict(block_mask=mask, bins=bins, threshold_bin=int(thr), idx=idx.astype(np.int64), count=int(idx.shape[0]),
+                mass=float(np.sum(mass_b[mask]) / total), m_b=m_b, l_b=l_b)
+
+
+# --------------------------------------------------------------------------
+# sparsity statistics  (Sec. 3.2 last paragraph; Sec. 4.2 "Sparsity Analysis" and its table)
+# --------------------------------------------------------------------------
+def attention_mass(q_bits, K_bits, token_ids, softmax_scale: float) -> float:
+    """Probability the FULL softmax attention of q over all rows of K puts on the set `token_ids`."""
+    q = bf16_to_f64(q_bits)
+    logits = float(softmax_scale) * (bf16_to_f64(K_bits) @ q)
+    a = np.exp(logits - np.max(logits))
+    return float(np.sum(a[np.asarray(token_ids, dtype=np.int64)]) / np.sum(a))
+
+
+def sparsity_stats(attended, n_ctx: int, n_q_heads: int, n_kv_heads: int, ret_heads) -> dict:
+    """Sparsity of one decode step of one sequence.
+
+    attended: list over query heads of the token-id sets they attend to.
+    compute sparsity = 1 - (mean over query heads of the attended count) / n_ctx;
+    memory sparsity  = 1 - (mean over KV heads of the size of the UNION of the
+    sets of the query heads mapped to that KV head) / n_ctx;
+    active tokens    = mean attended count over the retrieval heads.
+    """
+    sizes = [len(set(int(x) for x in a)) for a in attended]
+    compute = 1.0 - float(np.mean(sizes)) / n_ctx
+    unions = []
+    for g in range(n_kv_heads):
+        u = set()
+        for h in range(n_q_heads):
+            if kv_head_of(h, n_q_heads, n_kv_heads) == g:
+                u |= set(int(x) for x in attended[h])
+        unions.append(len(u))
+    memory = 1.0 - float(np.mean(unions)) / n_ctx
+    ret = list(ret_heads)
+    active = float(np.mean([sizes[h] for h in ret])) if ret else 0.0
+    return dict(compute_sparsity=compute, memory_sparsity=memory, active_tokens=active, union_sizes=unions)

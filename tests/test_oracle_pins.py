@@ -408,3 +408,187 @@ def test_prefill_rows_causal_and_dense_limit():
             s = [sum(x * y for x, y in zip(orc.bf16_to_f64(qI[0, a["t"]]).tolist(), kn))
                  for kn in orc.bf16_to_f64(kI[0, :m + 1]).tolist()]
             assert sorted(brute_topp(s, 0.5)) == sorted(a["sel"]["idx"].tolist())
+
+
+# =====================================================================================================
+# widened rows: index-key build, static top-k, block-wise histogram selector, sparsity statistics
+# =====================================================================================================
+def test_build_index_keys_routes_kv_heads_and_is_exact():
+    """Key side of the indexer equation (Sec. 3.2): the projection belongs to the QUERY head, the key row
+    to the KV head that query head reads.  One-hot projections must copy key columns bit for bit, and a
+    dense projection must agree with exact rational arithmetic."""
+    rng = np.random.default_rng(5)
+    T, Hq, Hkv, d, r = 9, 8, 2, 128, 16
+    ret = [1, 6]                                         # KV heads 0 and 1
+    k_pre = rand_bf16(rng, (T, Hkv, d))
+    cols = rng.integers(0, d, size=(2, r))
+    W = np.zeros((2, r, d), dtype=np.float32)
+    for j in range(2):
+        W[j, np.arange(r), cols[j]] = 1.0
+    kI = orc.build_index_keys(W, k_pre, ret, Hq, Hkv)
+    assert kI.shape == (2, T, r) and kI.dtype == np.uint16
+    for j, kvh in enumerate((0, 1)):
+        assert np.array_equal(kI[j], k_pre[:, kvh][:, cols[j]])
+    # dense projection, one output against Fractions
+    W = (rng.standard_normal((2, r, d)) / 8).astype(np.float32)
+    kI = orc.build_index_keys(W, k_pre, ret, Hq, Hkv)
+    j, n, i = 1, 4, 7
+    exact = sum(Fraction(float(W[j, i, c])) * bf16_fraction(int(k_pre[n, 1, c])) for c in range(d))
+    got = bf16_fraction(int(kI[j, n, i]))
+    ulp = Fraction(2) ** (math.floor(math.log2(abs(float(exact)))) - 7)
+    assert abs(got - exact) <= ulp / 2
+
+
+def test_topk_hand_cases_with_ties():
+    """Static top-k (Sec. 4.1 'Baselines'): the k best scores, ties to the lower index, never more than exist."""
+    s = np.array([3.0, 1.0, 2.0, 5.0, 0.0, 4.0, 4.0, -1.0])
+    want = {1: [3], 2: [3, 5], 3: [3, 5, 6], 4: [3, 5, 6, 0], 8: [3, 5, 6, 0, 2, 1, 4, 7], 100: [3, 5, 6, 0, 2, 1, 4, 7]}
+    for k, ids in want.items():
+        r = orc.topk_select(s, k)
+        assert list(r["idx"]) == ids and r["count"] == len(ids)
+        assert r["tau"] == s[ids[-1]]
+    # masses on exactly representable weights: scores ln(8,4,2,1,1) -> top-2 holds 12/16
+    r = orc.topk_select(np.log(np.array([8.0, 4.0, 2.0, 1.0, 1.0])), 2)
+    assert list(r["idx"]) == [0, 1] and abs(r["mass"] - 0.75) < 1e-12
+    with pytest.raises(ValueError):
+        orc.topk_select(s, 0)
+    with pytest.raises(ValueError):
+        orc.topk_select(np.zeros(0), 3)
+
+
+@pytest.mark.parametrize("seed", range(5))
+def test_topk_invariants_and_relation_to_topp(seed):
+    rng = np.random.default_rng(seed)
+    n = int(rng.integers(50, 400))
+    s = rng.standard_normal(n) * 2.0                      # continuous: no ties
+    prev = set()
+    for k in (1, 2, 7, n // 3, n - 1, n, n + 5):
+        r = orc.topk_select(s, k)
+        sel = set(r["idx"].tolist())
+        assert len(sel) == min(k, n) == r["count"]
+        rest = np.setdiff1d(np.arange(n), r["idx"])
+        if rest.size:
+            assert s[r["idx"]].min() > s[rest].max()      # nothing left out beats anything kept
+        assert prev <= sel                                # monotone in k
+        prev = sel
+        # the same set by a library partition (independent of the oracle's sort)
+        part = set(np.argpartition(-s, min(k, n) - 1)[:min(k, n)].tolist())
+        assert part == sel
+    # a top-k with the budget top-p arrived at is the top-p set
+    tp = orc.topp_select(s, 0.9)
+    tk = orc.topk_select(s, tp["count"])
+    assert set(tk["idx"].tolist()) == set(tp["idx"].tolist())
+    assert abs(tk["mass"] - tp["mass"]) < 1e-12 and tk["tau"] == tp["tau"]
+
+
+def _read_block_cases():
+    cases = []
+    with open(os.path.join(GOLD, "block_topp_hand_cases.txt")) as f:
+        for line in f:
+            line = line.split("#")[0].strip()
+            if not line:
+                continue
+            w, p, thr, blocks = [x.strip() for x in line.split(";")]
+            cases.append(([float(x) for x in w.split()], float(p), int(thr), [int(x) for x in blocks.split()]))
+    return cases
+
+
+@pytest.mark.parametrize("w,p,thr,blocks", _read_block_cases())
+def test_block_topp_hand_worked_cases(w, p, thr, blocks):
+    """Sec. 3.4 selector on hand-worked inputs (tests/golden/block_topp_hand_cases.txt)."""
+    ln2 = math.log(2.0)
+    r = orc.block_topp_select(np.log(np.array(w)), p, block=2, n_bins=8, bin_lo=-0.5 * ln2, bin_width=ln2)
+    assert r["threshold_bin"] == thr
+    assert list(np.nonzero(r["block_mask"])[0]) == blocks
+    want_idx = [n for b in blocks for n in (2 * b, 2 * b + 1) if n < len(w)]
+    assert list(r["idx"]) == want_idx and r["count"] == len(want_idx)
+    tot = sum(w)
+    assert abs(r["mass"] - sum(w[n] for n in want_idx) / tot) < 1e-12
+
+
+def test_block_topp_bins_clamp_and_block_pairs():
+    # block maxima outside the binned range fall into the first / last bin
+    s = np.array([-100.0, -101.0, 0.1, 0.0, 50.0, 49.0])
+    r = orc.block_topp_select(s, 0.5, block=2, n_bins=16, bin_lo=-4.0, bin_width=0.5)
+    assert list(r["bins"]) == [0, 8, 15]
+    # the log-sum-exp pair of a block, against math.fsum
+    assert abs(r["m_b"][1] - 0.1) < 1e-15
+    assert abs(r["l_b"][1] - math.fsum([1.0, math.exp(-0.1)])) < 1e-15
+
+
+@pytest.mark.parametrize("seed", range(6))
+def test_block_topp_invariants(seed):
+    """The selector's defining properties: the kept mass reaches p, dropping the threshold bin's blocks
+    falls short of p, the mask is upward closed in the block maximum, and with one-token blocks and fine
+    bins it contains the exact top-p set plus only tokens within one bin of the threshold."""
+    rng = np.random.default_rng(100 + seed)
+    n = int(rng.integers(300, 2000))
+    s = rng.standard_normal(n) * 1.5
+    s[rng.integers(0, n, size=5)] += 6.0
+    for p in (0.3, 0.8, 0.95):
+        r = orc.block_topp_select(s, p, block=64)
+        w = np.exp(s - s.max())
+        Z = w.sum()
+        assert r["mass"] >= p - 1e-12 and abs(w[r["idx"]].sum() / Z - r["mass"]) < 1e-12
+        blk = np.arange(n) // 64
+        below = r["bins"] > r["threshold_bin"]                        # strictly above the threshold bin
+        assert w[np.isin(blk, np.nonzero(below)[0])].sum() / Z < p
+        kept_max = r["m_b"][r["block_mask"]].min()
+        if (~r["block_mask"]).any():
+            assert r["m_b"][~r["block_mask"]].max() < kept_max + 0.25  # only a bin's width of overlap
+            assert r["bins"][~r["block_mask"]].max() < r["bins"][r["block_mask"]].min()
+        # one token per block, fine bins: the exact set is inside, the surplus hugs the threshold
+        width = 1e-3
+        r1 = orc.block_topp_select(s, p, block=1, n_bins=1 << 15, bin_lo=-16.0, bin_width=width)
+        exact = orc.topp_select(s, p)
+        extra = set(r1["idx"].tolist()) - set(exact["idx"].tolist())
+        assert set(exact["idx"].tolist()) <= set(r1["idx"].tolist())
+        assert all(exact["tau"] - width <= s[i] <= exact["tau"] for i in extra)
+    assert orc.block_topp_select(s, 1.0)["count"] == n
+    with pytest.raises(ValueError):
+        orc.block_topp_select(s, 0.0)
+
+
+def test_attention_mass_closed_forms_and_lse_identity():
+    """True attention mass of a token set (Sec. 4.2, sparsity table): uniform logits give |S| / N, a
+    two-level logit pattern gives its closed form, and for any set it equals exp(lse_S - lse_all) with
+    the log-sum-exps of `attend` (an independently pinned function)."""
+    rng = np.random.default_rng(3)
+    N, d = 37, 128
+    q = rand_bf16(rng, (d,))
+    K0 = np.zeros((N, d), dtype=np.uint16)
+    ids = np.array([1, 5, 6, 30])
+    assert abs(orc.attention_mass(q, K0, ids, 0.125) - 4 / 37) < 1e-15
+    # q = e_0, K[n, 0] = 2 for the set, 0 elsewhere: mass = k e^{2c} / (k e^{2c} + (N - k))
+    q1 = np.zeros(d, dtype=np.uint16); q1[0] = 0x3F80
+    K1 = np.zeros((N, d), dtype=np.uint16); K1[ids, 0] = 0x4000
+    c = 0.3
+    want = 4 * math.exp(2 * c) / (4 * math.exp(2 * c) + (N - 4))
+    assert abs(orc.attention_mass(q1, K1, ids, c) - want) < 1e-14
+    K = rand_bf16(rng, (N, d)); V = rand_bf16(rng, (N, d))
+    _, lse_s = orc.attend(q, K, V, ids, 0.09)
+    _, lse_a = orc.attend(q, K, V, np.arange(N), 0.09)
+    assert abs(orc.attention_mass(q, K, ids, 0.09) - math.exp(lse_s - lse_a)) < 1e-13
+    assert abs(orc.attention_mass(q, K, np.arange(N), 0.09) - 1.0) < 1e-15
+
+
+def test_sparsity_stats_hand_case_and_limits():
+    """Compute sparsity over query heads, memory sparsity over the per-KV-head unions (Sec. 3.2, last paragraph)."""
+    att = [[0, 1, 2], [2, 3], [5], [5, 6, 7, 8]]                     # Hq = 4, Hkv = 2, N = 10
+    r = orc.sparsity_stats(att, 10, 4, 2, ret_heads=[0, 3])
+    assert abs(r["compute_sparsity"] - 0.75) < 1e-15                 # 1 - mean(3, 2, 1, 4) / 10
+    assert r["union_sizes"] == [4, 4] and abs(r["memory_sparsity"] - 0.6) < 1e-15
+    assert abs(r["active_tokens"] - 3.5) < 1e-15
+    full = [list(range(10))] * 4
+    r = orc.sparsity_stats(full, 10, 4, 2, ret_heads=[1])
+    assert r["compute_sparsity"] == 0.0 and r["memory_sparsity"] == 0.0 and r["active_tokens"] == 10
+    # disjoint sets of k tokens: the union of a group of G heads holds G k tokens
+    att = [list(range(h * 3, h * 3 + 3)) for h in range(8)]
+    r = orc.sparsity_stats(att, 48, 8, 2, ret_heads=[])
+    assert abs(r["compute_sparsity"] - (1 - 3 / 48)) < 1e-15 and abs(r["memory_sparsity"] - (1 - 12 / 48)) < 1e-15
+    # the union is never smaller than the mean: memory sparsity <= compute sparsity
+    rng = np.random.default_rng(0)
+    for _ in range(20):
+        att = [rng.choice(64, size=int(rng.integers(1, 40)), replace=False).tolist() for _ in range(8)]
+        r = orc.sparsity_stats(att, 64, 8, 4, ret_heads=[0, 2])
+        assert r["memory_sparsity"] <= r["compute_sparsity"] + 1e-15
