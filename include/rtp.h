@@ -212,6 +212,90 @@ int32_t rtp_dense_attn(const rtp_layer_desc* layer, const void* q,
                        int32_t B, int32_t n_q, int64_t max_ctx, void* out, float* lse,
                        void* ws, size_t ws_bytes, void* stream);
 
+/* =============================================================================================
+ * Entry points beside the five above: the index-key build, the two other selectors the paper
+ * discusses, and its sparsity figures.
+ * ============================================================================================= */
+
+/* ---------------------------------------------------------------------------------------------
+ * Indexer projections -- Sec. 3.2, indexer equation: kI = bf16(W^K_h k^pre), qI = bf16(W^Q_h q^pre).
+ *
+ * For the j-th retrieval query head h_j and token t < T:
+ *   xI_out[j * out_head_stride + (out_t0 + t) * 16 + i] = bf16_rne( sum_c W[j, i, c] * x_pre[t, xh(j), c] ),  i < 16,
+ * the 128-term sum in fp64, rounded once.  W: fp32 [n_ret, 16, 128].  side = RTP_SIDE_KEY: x_pre is the
+ * PRE-rotary key tensor bf16 [T, n_kv_heads, 128] and xh(j) = kv(h_j) -- the call that appends T tokens to
+ * the index-key cache at token offset out_t0 (out_head_stride = the cache's kI_head_stride).
+ * side = RTP_SIDE_QUERY: x_pre is the pre-rotary query tensor bf16 [T, n_q_heads, 128] and xh(j) = h_j.
+ * x_pre 16-byte aligned, xI_out 8-byte aligned, out_head_stride a multiple of 4.  No workspace.
+ */
+#define RTP_SIDE_QUERY 0
+#define RTP_SIDE_KEY   1
+int32_t rtp_index_project(const rtp_layer_desc* layer, const float* W, const void* x_pre, int32_t side,
+                          int32_t T, void* xI_out, int64_t out_head_stride, int64_t out_t0, void* stream);
+
+/* ---------------------------------------------------------------------------------------------
+ * Static top-k selection -- the fixed-budget rule the paper compares its dynamic top-p against
+ * (Sec. 2.3, top-k / top-p table; Sec. 4.1 "Baselines", k = 4096).
+ *
+ * Row r keeps its k[r] highest scores (k: device int32 [R]); all scores tied with the k-th are kept, so
+ * sel_count can exceed k[r] by the ties; a budget that covers every finite score keeps them all;
+ * k[r] <= 0 marks the row invalid (sel_count = -1).  Same radix search, tensors, ordering (ascending
+ * positions, deterministic) and workspace (rtp_topp_workspace_bytes) as rtp_topp_select, with counts in
+ * place of masses.  tau (optional): the k-th best score.
+ */
+int32_t rtp_topk_select(const float* scores, int64_t score_stride, const int32_t* row_len,
+                        const int32_t* k, int32_t R, int64_t max_len,
+                        int32_t* sel_idx, int64_t sel_stride, int32_t* sel_count, float* tau,
+                        void* ws, size_t ws_bytes, void* stream);
+
+/* ---------------------------------------------------------------------------------------------
+ * Block-wise top-p selection -- Sec. 3.4, "Sort-free top-p via histogram" (block size 64 in the
+ * paper's configuration table).
+ *
+ * Row r is cut into blocks of `block` (= 64) consecutive scores.  Block b has the log-sum-exp pair
+ * m_b = max s, l_b = sum exp(s - m_b) and deposits the mass l_b * exp(m_b) into bin
+ * clamp(floor((m_b - bin_lo) / bin_width), 0, 255) of a 256-bin histogram.  The histogram is scanned from
+ * the highest bin down; the threshold bin is the first at which the cumulative mass reaches p[r] times the
+ * total; every block whose bin is at or above it is kept WHOLE -- the kept mass overshoots p by up to the
+ * mass of the threshold bin (the price of the one-pass, sort-free search; rtp_topp_select is the
+ * token-exact selector).  The paper gives neither the bin mapping nor the scale of the deposits; uniform
+ * bins over a caller-chosen range and exact integer deposits are this library's reading.  Scores above
+ * bin_lo + 256 * bin_width count with the mass of that upper edge: choose a range that covers the scores.
+ * p >= 1 keeps every block; p <= 0 or NaN: sel_count = -1.
+ *
+ *   sel_idx / sel_count  the tokens of the kept blocks, ascending (what rtp_sparse_attn_decode reads).
+ *   threshold_bin (optional int32 [R]), mass (optional fp32 [R]: kept mass / total),
+ *   block_mask (optional uint8 [R, mask_stride], 1 = kept, mask_stride >= ceil(max_len / 64)).
+ */
+size_t rtp_block_topp_workspace_bytes(int32_t R, int64_t max_len);
+int32_t rtp_block_topp_select(const float* scores, int64_t score_stride, const int32_t* row_len,
+                              const float* p, int32_t R, int64_t max_len,
+                              int32_t block, float bin_lo, float bin_width,
+                              int32_t* sel_idx, int64_t sel_stride, int32_t* sel_count,
+                              int32_t* threshold_bin, float* mass, uint8_t* block_mask, int64_t mask_stride,
+                              void* ws, size_t ws_bytes, void* stream);
+
+/* ---------------------------------------------------------------------------------------------
+ * Sparsity figures of one decode step -- Sec. 3.2 (last paragraph: compute vs memory sparsity under
+ * GQA), Sec. 4.2 ("Sparsity Analysis" and its table).
+ *
+ * stats[b] = { compute sparsity, memory sparsity, active tokens, attention mass } (fp32 [B, 4]):
+ *   compute sparsity = 1 - (mean over query heads of attended tokens) / ctx_len[b], a local head attending
+ *                      its sink + window set, a retrieval head its selected list;
+ *   memory sparsity  = 1 - (mean over KV heads of the size of the union of its query heads' sets) / ctx_len[b];
+ *   active tokens    = mean sel_count over the retrieval heads;
+ *   attention mass   = mean over the retrieval heads of exp(lse_selected - lse_full): the probability the
+ *                      full softmax attention puts on the selected set.  lse_selected / lse_full are the
+ *                      lse outputs (fp32 [B, n_q_heads], n_q = 1) of rtp_sparse_attn_decode and
+ *                      rtp_dense_attn; pass both or neither (NaN then).
+ * sel_idx rows must be ascending (every selector of this library writes them so).
+ * union_size (optional int32 [B, n_kv_heads]): the union sizes themselves.
+ */
+int32_t rtp_sparsity_stats(const rtp_layer_desc* layer, const int32_t* ctx_len,
+                           const int32_t* sel_idx, int64_t sel_stride, const int32_t* sel_count,
+                           const float* lse_selected, const float* lse_full, int32_t B,
+                           float* stats, int32_t* union_size, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -51,6 +51,8 @@ struct TopPArgs {
   int32_t R;
   int32_t n_chunks;        // grid.x
   int32_t rezero;          // write launch leaves the histograms zeroed (level1_ready protocol)
+  const int32_t* kcount;   // NULL: top-p by softmax mass; else static top-k, every score weighs 1 and
+                           // the target is kcount[r] (rtp_topk_select)
   int32_t* sel_idx;
   int64_t sel_stride;
   int32_t* sel_count;
@@ -165,6 +167,7 @@ struct ScanResult {
   int bin;             // highest bin b with  above + sum_{i >= b} h[i] >= target
   uint64_t above;      // mass strictly above bin b (including the incoming `above`)
   uint64_t bin_mass;   // h[b]
+  uint64_t total;      // above + sum of all bins
 };
 
 // Levels 2 and 3: integer masses with one reference.  Two block barriers; wave suffix sums by shuffle.
@@ -189,10 +192,12 @@ __device__ __forceinline__ ScanResult scan_from_top(const uint64_t* __restrict__
   if (lane == 0) sh_w[wave] = incl;
   if (tid == 0) { sh_res[0] = 0; sh_res[1] = above; sh_res[2] = loc[0]; }
   __syncthreads();
-  uint64_t after = 0;
+  uint64_t after = 0, total = above;
 #pragma unroll
-  for (int w = 0; w < kTpThreads / 64; ++w)
+  for (int w = 0; w < kTpThreads / 64; ++w) {
     if (w > wave) after += sh_w[w];
+    total += sh_w[w];
+  }
   incl += after;                                      // bins of threads >= tid
   const uint64_t excl = incl - sum;                   // bins of threads > tid
   if (above + excl < target && above + incl >= target) {
@@ -214,6 +219,7 @@ __device__ __forceinline__ ScanResult scan_from_top(const uint64_t* __restrict__
   r.bin = (int)sh_res[0];
   r.above = sh_res[1];
   r.bin_mass = sh_res[2];
+  r.total = total;
   __syncthreads();                                    // sh_w / sh_res may be reused by the caller
   return r;
 }
@@ -265,16 +271,36 @@ __global__ __launch_bounds__(kTpThreads) void topp_level_kernel(const TopPArgs a
   uint32_t prefix = 0;
   float ref = 0.f;
   int flags = 0;
+  const bool by_count = a.kcount != nullptr;
   if (LEVEL == 1) {
-    const float pr = a.p[r];
-    flags = (pr >= 1.f) ? 1 : ((pr > 0.f) ? 0 : -1);
+    if (by_count) {
+      flags = a.kcount[r] > 0 ? 0 : -1;
+    } else {
+      const float pr = a.p[r];
+      flags = (pr >= 1.f) ? 1 : ((pr > 0.f) ? 0 : -1);
+    }
   } else if (LEVEL == 2) {
-    const float pr = a.p[r];
-    flags = (pr >= 1.f) ? 1 : ((pr > 0.f) ? 0 : -1);
+    const float pr = by_count ? 0.5f : a.p[r];
+    flags = by_count ? (a.kcount[r] > 0 ? 0 : -1) : ((pr >= 1.f) ? 1 : ((pr > 0.f) ? 0 : -1));
     RowState s;
     s.above_base = 0.0; s.total_d = 0.0; s.above = 0; s.target = 1; s.prefix = 0; s.flags = flags; s.ref = 0.f;
     s.shift = shift;
-    if (flags == 0) {
+    if (flags == 0 && by_count) {
+      // static top-k: level 1 holds plain counts; the k-th best score lies in the bin where the count
+      // from the top reaches k.  A budget that covers every finite score keeps them all.
+      const uint64_t k = (uint64_t)a.kcount[r];
+      const ScanResult s1 = scan_from_top<kBins1>(hrow, 0, k, sh_part, sh_res);
+      if (s1.total == 0) {
+        flags = 2;
+      } else if (k >= s1.total) {
+        flags = 1;
+      } else {
+        prefix = (uint32_t)s1.bin;
+        s.target = k - s1.above;              // still to find inside the bin
+        s.prefix = prefix;
+      }
+      s.flags = flags;
+    } else if (flags == 0) {
       const Scan1Result s1 = scan_level1(hrow, pr, sh_d, sh_i, sh_dres, tab);
       if (s1.bin < 0) {
         flags = 2;
@@ -329,8 +355,11 @@ __global__ __launch_bounds__(kTpThreads) void topp_level_kernel(const TopPArgs a
       const int e = (u * kTpThreads + tid) * 4;
       const float s4[4] = {v[u].x, v[u].y, v[u].z, v[u].w};
 #pragma unroll
-      for (int k = 0; k < 4; ++k)
-        if (e + k < n_here) level1_add(lh, s4[k], shift, tab);
+      for (int k = 0; k < 4; ++k) {
+        if (e + k >= n_here) continue;
+        if (!by_count) level1_add(lh, s4[k], shift, tab);
+        else if (s4[k] != -__builtin_huge_valf()) atomicAdd((unsigned long long*)&lh[float_key(s4[k]) >> 21], 1ull);
+      }
     }
   } else if (LEVEL == 3) {
 #pragma unroll
@@ -341,7 +370,7 @@ __global__ __launch_bounds__(kTpThreads) void topp_level_kernel(const TopPArgs a
       for (int k = 0; k < 4; ++k) {
         const uint32_t key = float_key(s4[k]);
         if (e + k < n_here && (key >> 10) == prefix && s4[k] != -__builtin_huge_valf()) {
-          const uint64_t w = fixed_weight(s4[k], ref, shift, tab);
+          const uint64_t w = by_count ? 1ull : fixed_weight(s4[k], ref, shift, tab);
           if (w) atomicAdd((unsigned long long*)&lh[key & (kBins - 1)], (unsigned long long)w);
         }
       }
@@ -382,7 +411,7 @@ __global__ __launch_bounds__(kTpThreads) void topp_level_kernel(const TopPArgs a
     const int total = sh_n;
     for (int i = tid; i < total; i += kTpThreads) {
       const float sv = sh_list[i];
-      const uint64_t w = fixed_weight(sv, ref, shift, tab);
+      const uint64_t w = by_count ? 1ull : fixed_weight(sv, ref, shift, tab);
       if (w) atomicAdd((unsigned long long*)&lh[(float_key(sv) >> kShift) & (kBins - 1)], (unsigned long long)w);
     }
   }
@@ -492,7 +521,7 @@ __global__ __launch_bounds__(kTpThreads) void topp_count_kernel(const TopPArgs a
     tkey = (prev.prefix << 10) | (uint32_t)sr.bin;
     if (c == 0 && tid == 0) {
       if (a.tau) a.tau[r] = key_float(tkey);
-      if (a.mass) a.mass[r] = (float)((prev.above_base + (double)(sr.above + sr.bin_mass)) / prev.total_d);
+      if (a.mass) a.mass[r] = a.kcount ? __builtin_nanf("") : (float)((prev.above_base + (double)(sr.above + sr.bin_mass)) / prev.total_d);
     }
   } else if (c == 0 && tid == 0) {
     if (a.tau) a.tau[r] = ninf;
@@ -581,13 +610,13 @@ extern "C" int32_t rtp_topp_workspace_init(void* ws, size_t ws_bytes, void* stre
   return check_launch(who);
 }
 
-extern "C" int32_t rtp_topp_select(const float* scores, int64_t score_stride, const int32_t* row_len,
-                                   const float* p, int32_t R, int64_t max_len,
-                                   int32_t* sel_idx, int64_t sel_stride, int32_t* sel_count,
-                                   float* tau, float* mass, int32_t level1_ready,
-                                   void* ws, size_t ws_bytes, void* stream) {
-  const char* who = "rtp_topp_select";
-  if (!scores || !row_len || !p || !sel_idx || !sel_count)
+// Shared body of rtp_topp_select (p != NULL) and rtp_topk_select (kcount != NULL).
+static int32_t run_select(const char* who, const float* scores, int64_t score_stride, const int32_t* row_len,
+                          const float* p, const int32_t* kcount, int32_t R, int64_t max_len,
+                          int32_t* sel_idx, int64_t sel_stride, int32_t* sel_count,
+                          float* tau, float* mass, int32_t level1_ready,
+                          void* ws, size_t ws_bytes, void* stream) {
+  if (!scores || !row_len || (!p && !kcount) || !sel_idx || !sel_count)
     return fail(RTP_ERR_INVALID_ARG, "%s: NULL tensor pointer", who);
   if (R <= 0 || R > 65535) return fail(RTP_ERR_INVALID_ARG, "%s: R must be in [1, 65535]", who);
   if (max_len <= 0 || max_len > RTP_MAX_ROW_LEN)
@@ -607,6 +636,7 @@ extern "C" int32_t rtp_topp_select(const float* scores, int64_t score_stride, co
   a.score_stride = score_stride;
   a.row_len = row_len;
   a.p = p;
+  a.kcount = kcount;
   a.R = R;
   a.n_chunks = (int32_t)((max_len + kTpChunk - 1) / kTpChunk);
   a.rezero = level1_ready;
@@ -631,4 +661,23 @@ extern "C" int32_t rtp_topp_select(const float* scores, int64_t score_stride, co
   hipLaunchKernelGGL(topp_count_kernel, grid, block, 0, s, a);
   hipLaunchKernelGGL(topp_write_kernel, grid, block, 0, s, a);
   return check_launch(who);
+}
+
+extern "C" int32_t rtp_topp_select(const float* scores, int64_t score_stride, const int32_t* row_len,
+                                   const float* p, int32_t R, int64_t max_len,
+                                   int32_t* sel_idx, int64_t sel_stride, int32_t* sel_count,
+                                   float* tau, float* mass, int32_t level1_ready,
+                                   void* ws, size_t ws_bytes, void* stream) {
+  if (!p) return fail(RTP_ERR_INVALID_ARG, "rtp_topp_select: NULL tensor pointer");
+  return run_select("rtp_topp_select", scores, score_stride, row_len, p, nullptr, R, max_len, sel_idx, sel_stride,
+                    sel_count, tau, mass, level1_ready, ws, ws_bytes, stream);
+}
+
+extern "C" int32_t rtp_topk_select(const float* scores, int64_t score_stride, const int32_t* row_len,
+                                   const int32_t* k, int32_t R, int64_t max_len,
+                                   int32_t* sel_idx, int64_t sel_stride, int32_t* sel_count, float* tau,
+                                   void* ws, size_t ws_bytes, void* stream) {
+  if (!k) return fail(RTP_ERR_INVALID_ARG, "rtp_topk_select: NULL tensor pointer");
+  return run_select("rtp_topk_select", scores, score_stride, row_len, nullptr, k, R, max_len, sel_idx, sel_stride,
+                    sel_count, tau, nullptr, 0, ws, ws_bytes, stream);
 }

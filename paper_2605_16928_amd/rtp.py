@@ -26,7 +26,10 @@ EXPORTS = [
     "rtp_sparse_attn_prefill_workspace_bytes", "rtp_sparse_attn_prefill",
     "rtp_local_attn_workspace_bytes", "rtp_local_attn",
     "rtp_dense_attn_workspace_bytes", "rtp_dense_attn",
+    "rtp_index_project", "rtp_topk_select",
+    "rtp_block_topp_workspace_bytes", "rtp_block_topp_select", "rtp_sparsity_stats",
 ]
+RTP_SIDE_QUERY, RTP_SIDE_KEY = 0, 1
 
 
 class RtpError(RuntimeError):
@@ -94,6 +97,17 @@ def lib() -> C.CDLL:
         getattr(L, name + "_workspace_bytes").argtypes = [dp, i32, i32, i64]
         getattr(L, name).restype = i32
         getattr(L, name).argtypes = [dp, vp, vp, vp, i64, i64, vp, vp, vp, i32, i32, i64, vp, vp, vp, sz, vp]
+    L.rtp_index_project.restype = i32
+    L.rtp_index_project.argtypes = [dp, vp, vp, i32, i32, vp, i64, i64, vp]
+    L.rtp_topk_select.restype = i32
+    L.rtp_topk_select.argtypes = [vp, i64, vp, vp, i32, i64, vp, i64, vp, vp, vp, sz, vp]
+    L.rtp_block_topp_workspace_bytes.restype = sz
+    L.rtp_block_topp_workspace_bytes.argtypes = [i32, i64]
+    L.rtp_block_topp_select.restype = i32
+    L.rtp_block_topp_select.argtypes = [vp, i64, vp, vp, i32, i64, i32, C.c_float, C.c_float, vp, i64, vp, vp, vp,
+                                        vp, i64, vp, sz, vp]
+    L.rtp_sparsity_stats.restype = i32
+    L.rtp_sparsity_stats.argtypes = [dp, vp, vp, i64, vp, vp, vp, i32, vp, vp, vp]
     _lib = L
     return L
 
@@ -197,3 +211,33 @@ def rtp_dense_attn(layer, q, K, V, kv_row_stride, kv_head_stride, seq_start, ctx
     _check(lib().rtp_dense_attn(C.byref(layer), _ptr(q), _ptr(K), _ptr(V), kv_row_stride, kv_head_stride,
                                 _ptr(seq_start), _ptr(ctx_len), _ptr(q_start), B, n_q, max_ctx, _ptr(out), _ptr(lse),
                                 _ptr(ws), _nbytes(ws), _stream(stream)))
+
+
+def rtp_index_project(layer, W, x_pre, side, T, xI_out, out_head_stride, out_t0=0, stream=None):
+    _check(lib().rtp_index_project(C.byref(layer), _ptr(W), _ptr(x_pre), side, T, _ptr(xI_out), out_head_stride,
+                                   out_t0, _stream(stream)))
+
+
+def rtp_topk_select(scores, score_stride, row_len, k, R, max_len, sel_idx, sel_stride, sel_count, tau, ws,
+                    stream=None):
+    _check(lib().rtp_topk_select(_ptr(scores), score_stride, _ptr(row_len), _ptr(k), R, max_len, _ptr(sel_idx),
+                                 sel_stride, _ptr(sel_count), _ptr(tau), _ptr(ws), _nbytes(ws), _stream(stream)))
+
+
+def rtp_block_topp_workspace_bytes(R, max_len) -> int:
+    return lib().rtp_block_topp_workspace_bytes(R, max_len)
+
+
+def rtp_block_topp_select(scores, score_stride, row_len, p, R, max_len, block, bin_lo, bin_width, sel_idx,
+                          sel_stride, sel_count, threshold_bin, mass, block_mask, mask_stride, ws, stream=None):
+    _check(lib().rtp_block_topp_select(_ptr(scores), score_stride, _ptr(row_len), _ptr(p), R, max_len, block,
+                                       bin_lo, bin_width, _ptr(sel_idx), sel_stride, _ptr(sel_count),
+                                       _ptr(threshold_bin), _ptr(mass), _ptr(block_mask), mask_stride,
+                                       _ptr(ws), _nbytes(ws), _stream(stream)))
+
+
+def rtp_sparsity_stats(layer, ctx_len, sel_idx, sel_stride, sel_count, lse_selected, lse_full, B, stats,
+                       union_size=None, stream=None):
+    _check(lib().rtp_sparsity_stats(C.byref(layer), _ptr(ctx_len), _ptr(sel_idx), sel_stride, _ptr(sel_count),
+                                    _ptr(lse_selected), _ptr(lse_full), B, _ptr(stats), _ptr(union_size),
+                                    _stream(stream)))

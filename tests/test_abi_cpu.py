@@ -146,6 +146,50 @@ def test_attention_argument_and_workspace_checks():
         assert rng(wsb=0) == rtp.RTP_ERR_WORKSPACE
 
 
+def test_widened_entry_points_argument_checks():
+    lib = rtp.lib()
+    L = _layer()
+    vp = C.c_void_p
+    # index-key build
+    proj = lambda W=A, x=A, side=rtp.RTP_SIDE_KEY, T=8, out=A, hs=16 * 64, t0=0: lib.rtp_index_project(
+        C.byref(L), vp(W), vp(x), side, T, vp(out), hs, t0, None)
+    assert proj(W=None) == rtp.RTP_ERR_INVALID_ARG
+    assert proj(side=2) == rtp.RTP_ERR_INVALID_ARG
+    assert proj(T=0) == rtp.RTP_ERR_INVALID_ARG
+    assert proj(x=A + 8) == rtp.RTP_ERR_INVALID_ARG
+    assert proj(hs=6) == rtp.RTP_ERR_INVALID_ARG
+    assert proj(t0=-1) == rtp.RTP_ERR_INVALID_ARG
+    # static top-k shares the top-p workspace rule
+    need = rtp.rtp_topp_workspace_bytes(4, 1000)
+    topk = lambda scores=A, k=A, ws=A, wsb=need, R=4: lib.rtp_topk_select(
+        vp(scores), 1000, vp(A), vp(k), R, 1000, vp(A), 1000, vp(A), None, vp(ws), wsb, None)
+    assert topk(k=None) == rtp.RTP_ERR_INVALID_ARG
+    assert topk(scores=None) == rtp.RTP_ERR_INVALID_ARG
+    assert topk(R=0) == rtp.RTP_ERR_INVALID_ARG
+    assert topk(wsb=need - 1) == rtp.RTP_ERR_WORKSPACE
+    # block-wise selector
+    needb = rtp.rtp_block_topp_workspace_bytes(4, 1000)
+    assert needb > 0 and needb % 256 == 0 and rtp.rtp_block_topp_workspace_bytes(4, 100000) > needb
+    blk = lambda scores=A, block=64, lo=-32.0, width=0.25, mask=None, mstride=0, ws=A, wsb=needb: lib.rtp_block_topp_select(
+        vp(scores), 1000, vp(A), vp(A), 4, 1000, block, lo, width, vp(A), 1000, vp(A), None, None, vp(mask), mstride,
+        vp(ws), wsb, None)
+    assert blk(scores=None) == rtp.RTP_ERR_INVALID_ARG
+    assert blk(block=32) == rtp.RTP_ERR_UNSUPPORTED
+    assert blk(width=0.0) == rtp.RTP_ERR_INVALID_ARG
+    assert blk(width=float("nan")) == rtp.RTP_ERR_INVALID_ARG
+    assert blk(mask=A, mstride=3) == rtp.RTP_ERR_INVALID_ARG
+    assert blk(ws=None) == rtp.RTP_ERR_WORKSPACE
+    assert blk(wsb=needb - 1) == rtp.RTP_ERR_WORKSPACE
+    # sparsity figures
+    st = lambda ctx=A, sel=A, cnt=A, ls=None, lf=None, B=2, out=A: lib.rtp_sparsity_stats(
+        C.byref(L), vp(ctx), vp(sel), 1000, vp(cnt), vp(ls), vp(lf), B, vp(out), None, None)
+    assert st(ctx=None) == rtp.RTP_ERR_INVALID_ARG
+    assert st(sel=None) == rtp.RTP_ERR_INVALID_ARG
+    assert st(ls=A) == rtp.RTP_ERR_INVALID_ARG             # one log-sum-exp array without the other
+    assert st(B=0) == rtp.RTP_ERR_INVALID_ARG
+    assert st(out=None) == rtp.RTP_ERR_INVALID_ARG
+
+
 def test_missing_library_is_an_error_not_a_fallback(monkeypatch):
     monkeypatch.setattr(rtp, "_lib", None)
     monkeypatch.setattr(rtp, "LIB_PATH", "/nonexistent/librtp.so")

@@ -1,0 +1,235 @@
+"""GPU parity tests of the entry points beside the five core ones: index-key build, static top-k,
+block-wise histogram top-p and the sparsity figures -- each through the C-ABI against the CPU oracle
+on the same seeded inputs.  Integer and index results are compared bit for bit."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import rtp_oracle as orc
+from paper_2605_16928_amd import rtp, workloads as wl
+from gpu_util import DEV, DecodeRun, oracle_inputs, i32, ws_alloc, layer_desc_of
+
+pytestmark = pytest.mark.gpu
+
+
+def _bits(t):
+    return wl.bf16_bits(t)
+
+
+# ---------------------------------------------------------------------------------------------------
+# index-key build (Sec. 3.2, indexer equation)
+# ---------------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("T,Hq,Hkv,ret", [(1, 8, 2, [0, 4]), (197, 8, 2, [1, 2, 6]), (4096 + 33, 32, 8, [0, 8, 16, 24]),
+                                          (70, 64, 8, list(range(0, 64, 8)))])
+def test_index_project_key_and_query_side_bit_exact(T, Hq, Hkv, ret):
+    print(f"[case] index_project T={T} Hq={Hq} Hkv={Hkv}", flush=True)
+    g = torch.Generator(device="cpu").manual_seed(1000 + T)
+    n_ret = len(ret)
+    W = (torch.randn((n_ret, 16, 128), generator=g) / 128 ** 0.5).float()
+    k_pre = torch.randn((T, Hkv, 128), generator=g).to(torch.bfloat16)
+    q_pre = torch.randn((T, Hq, 128), generator=g).to(torch.bfloat16)
+    desc = rtp.layer_desc(Hq, Hkv, ret, 4, 64)
+    t0, cap = 5, T + 9                                    # append at token offset 5 of a larger cache
+    kI = torch.full((n_ret, cap, 16), 7.0, dtype=torch.bfloat16, device=DEV)
+    rtp.rtp_index_project(desc, W.to(DEV), k_pre.to(DEV), rtp.RTP_SIDE_KEY, T, kI, cap * 16, t0)
+    qI = torch.zeros((n_ret, T, 16), dtype=torch.bfloat16, device=DEV)
+    rtp.rtp_index_project(desc, W.to(DEV), q_pre.to(DEV), rtp.RTP_SIDE_QUERY, T, qI, T * 16, 0)
+    torch.cuda.synchronize()
+    want_k = orc.build_index_keys(W.numpy(), _bits(k_pre), ret, Hq, Hkv)
+    got_k = _bits(kI)
+    assert np.array_equal(got_k[:, t0:t0 + T], want_k)
+    seven = _bits(torch.tensor([7.0], dtype=torch.bfloat16))[0]
+    assert np.all(got_k[:, :t0] == seven) and np.all(got_k[:, t0 + T:] == seven)      # nothing else touched
+    want_q = np.stack([orc.index_project(W.numpy()[j], _bits(q_pre)[:, h]) for j, h in enumerate(ret)])
+    assert np.array_equal(_bits(qI), want_q)
+
+
+# ---------------------------------------------------------------------------------------------------
+# static top-k (Sec. 4.1 baseline)
+# ---------------------------------------------------------------------------------------------------
+def _score_rows(rng):
+    rows = [rng.standard_normal(5000) * 2, rng.standard_normal(9001), np.full(300, -3.0),
+            np.concatenate([[30.0], rng.standard_normal(3000)]), rng.standard_normal(1), rng.standard_normal(8193) * 0.01,
+            np.round(rng.standard_normal(6000) * 4) / 4]                         # heavy ties
+    s = rng.standard_normal(8191) * 2
+    s[100:200] = -np.inf
+    rows.append(s)
+    return [r.astype(np.float32) for r in rows]
+
+
+def test_topk_select_matches_oracle_with_ties_and_edge_budgets():
+    print("[case] topk_select", flush=True)
+    rng = np.random.default_rng(7)
+    rows = _score_rows(rng)
+    ks_per_row = [[1, 17, 4096, 4999, 5000, 6000], [1, 4096, 9001], [1, 10, 300, 301], [1, 2, 3001], [1, 5], [4096], [1, 100, 3000],
+                  [1, 8000, 8091, 8092]]
+    cases = [(r, k) for r, ks in enumerate(ks_per_row) for k in ks] + [(0, 0), (1, -3)]
+    R = len(cases)
+    n_max = max(len(s) for s in rows)
+    stride = (n_max + 3) // 4 * 4
+    sc = torch.full((R, stride), float("nan"), dtype=torch.float32)
+    for i, (r, k) in enumerate(cases):
+        sc[i, :len(rows[r])] = torch.from_numpy(rows[r])
+    sc = sc.to(DEV)
+    row_len = i32([len(rows[r]) for r, _ in cases])
+    kk = i32([k for _, k in cases])
+    sel = torch.full((R, stride), -1, dtype=torch.int32, device=DEV)
+    cnt = torch.full((R,), -9, dtype=torch.int32, device=DEV)
+    tau = torch.zeros(R, device=DEV)
+    ws = torch.empty(rtp.rtp_topp_workspace_bytes(R, n_max), dtype=torch.uint8, device=DEV)
+    for rep in range(2):                                  # twice: the workspace is reused dirty
+        rtp.rtp_topk_select(sc, stride, row_len, kk, R, n_max, sel, stride, cnt, tau, ws)
+        torch.cuda.synchronize()
+        c, idx, t = cnt.cpu().numpy(), sel.cpu().numpy(), tau.cpu().numpy()
+        for i, (r, k) in enumerate(cases):
+            if k <= 0:
+                assert c[i] == -1
+                continue
+            s64 = rows[r].astype(np.float64)
+            finite = np.isfinite(s64)
+            got = idx[i, :c[i]]
+            assert np.all(np.diff(got) > 0), "positions must ascend"
+            if k >= finite.sum():
+                assert np.array_equal(got, np.nonzero(finite)[0])
+                continue
+            ref = orc.topk_select(np.where(finite, s64, -1e30), k)
+            want = np.nonzero(finite & (s64 >= ref["tau"]))[0]      # every tie with the k-th score is kept
+            assert np.array_equal(got, want), f"case {i}: {len(got)} vs {len(want)}"
+            assert c[i] >= k and set(ref["idx"].tolist()) <= set(got.tolist())
+            assert t[i] == np.float32(ref["tau"])
+
+
+# ---------------------------------------------------------------------------------------------------
+# block-wise histogram top-p (Sec. 3.4)
+# ---------------------------------------------------------------------------------------------------
+def test_block_topp_select_matches_oracle():
+    print("[case] block_topp_select", flush=True)
+    rng = np.random.default_rng(11)
+    rows, ps = [], []
+
+    def add(s, p):
+        rows.append(np.asarray(s, dtype=np.float32))
+        ps.append(p)
+
+    base = rng.standard_normal(10000) * 1.5
+    base[rng.integers(0, 10000, size=12)] += 7.0
+    for p in (0.3, 0.8, 0.9, 0.95, 0.999, 1.0, 0.0):
+        add(base, p)
+    add(rng.standard_normal(64) * 2, 0.9)                                # exactly one block
+    add(rng.standard_normal(65) * 2, 0.9)                                # a one-token ragged block
+    add(rng.standard_normal(4096 + 63), 0.5)                             # chunk boundary + ragged tail
+    add(rng.standard_normal(3 * 4096), 0.97)
+    add(np.full(1000, 0.1), 0.5)                                         # every block in one bin
+    add(np.clip(rng.standard_normal(777) * 8, -31.0, 31.0), 0.9)         # maxima over many bins, inside the binned range
+    add([2.0], 0.7)
+    planted = rng.standard_normal(131072).astype(np.float32)
+    planted[rng.integers(0, 131072, size=64)] += 9.9
+    add(planted, 0.9)                                                    # the benchmark's score law
+    R = len(rows)
+    n_max = max(len(s) for s in rows)
+    stride = (n_max + 3) // 4 * 4
+    sc = torch.full((R, stride), float("nan"), dtype=torch.float32)
+    for r, s in enumerate(rows):
+        sc[r, :len(s)] = torch.from_numpy(s)
+    sc = sc.to(DEV)
+    row_len = i32([len(s) for s in rows])
+    p = torch.tensor(ps, dtype=torch.float32, device=DEV)
+    sel = torch.full((R, stride), -1, dtype=torch.int32, device=DEV)
+    cnt = torch.full((R,), -9, dtype=torch.int32, device=DEV)
+    thr = torch.full((R,), -9, dtype=torch.int32, device=DEV)
+    mass = torch.zeros(R, device=DEV)
+    nbk = (n_max + 63) // 64
+    mask = torch.full((R, nbk), 9, dtype=torch.uint8, device=DEV)
+    ws = torch.empty(rtp.rtp_block_topp_workspace_bytes(R, n_max), dtype=torch.uint8, device=DEV)
+    lo, width = -32.0, 0.25
+    for rep in range(2):
+        rtp.rtp_block_topp_select(sc, stride, row_len, p, R, n_max, 64, lo, width, sel, stride, cnt, thr, mass, mask, nbk, ws)
+        torch.cuda.synchronize()
+        c, idx, tb, ms, mk = cnt.cpu().numpy(), sel.cpu().numpy(), thr.cpu().numpy(), mass.cpu().numpy(), mask.cpu().numpy()
+        for r, s in enumerate(rows):
+            pr = ps[r]
+            if not (pr > 0):
+                assert c[r] == -1
+                continue
+            ref = orc.block_topp_select(s.astype(np.float64), float(np.float32(pr)), block=64, n_bins=256, bin_lo=lo, bin_width=width)
+            assert c[r] == ref["count"], f"row {r}: {c[r]} vs {ref['count']}"
+            assert np.array_equal(idx[r, :c[r]], ref["idx"]), f"row {r}"
+            nb = len(ref["block_mask"])
+            assert np.array_equal(mk[r, :nb].astype(bool), ref["block_mask"])
+            if pr < 1:
+                assert tb[r] == ref["threshold_bin"]
+            assert abs(ms[r] - ref["mass"]) < 1e-6
+
+
+def test_block_selector_feeds_sparse_attention():
+    """Selection by blocks, then exact attention over the kept tokens: the output must match the oracle's
+    attention over the oracle's block selection."""
+    print("[case] block selector -> sparse attention", flush=True)
+    w = wl.small_decode(DEV, seed=31, ctx=(700, 1531, 64, 2048))
+    run = DecodeRun(w, fuse_level1=False)
+    L = w.layer
+    run.index_score()
+    thr = torch.zeros(run.R, dtype=torch.int32, device=DEV)
+    ws = ws_alloc(rtp.rtp_block_topp_workspace_bytes(run.R, run.max_ctx))
+    rtp.rtp_block_topp_select(run.scores, run.stride, run.row_len, w.p_rows, run.R, run.max_ctx, 64, -32.0, 0.25,
+                              run.sel_idx, run.stride, run.sel_count, thr, run.mass, None, 0, ws)
+    run.sparse_attn()
+    out = run.out_f64()
+    sets, cnt = run.sel_sets()
+    sc = run.scores.cpu().numpy().astype(np.float64)
+    oi = oracle_inputs(w)
+    sm = 1.0 / np.sqrt(128.0)
+    for r in range(run.R):
+        b, j = divmod(r, L.n_ret)
+        n, t0 = w.ctx_len[b], w.seq_start[b]
+        # staged: the oracle selects from the GPU's own fp32 scores
+        ref = orc.block_topp_select(sc[r, :n], float(w.p_rows[r].item()))
+        assert np.array_equal(sets[r], ref["idx"])
+        h = L.ret_heads[j]
+        kvh = orc.kv_head_of(h, L.n_q_heads, L.n_kv_heads)
+        o, _ = orc.attend(oi["q_bits"][b, h], oi["K_bits"][kvh, t0:t0 + n], oi["V_bits"][kvh, t0:t0 + n], ref["idx"], sm)
+        err = np.abs(out[b, h] - o)
+        assert (err <= 2e-2 + 1e-2 * np.abs(o)).all() and (err <= 1e-3 + 2.0 ** -8 * np.abs(o)).all()
+
+
+# ---------------------------------------------------------------------------------------------------
+# sparsity figures (Sec. 3.2 last paragraph, Sec. 4.2 table)
+# ---------------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("ret_heads", [(0, 1, 5), (0, 4), (2,), (0, 1, 2, 3)])
+def test_sparsity_stats_match_oracle(ret_heads):
+    print(f"[case] sparsity_stats ret={ret_heads}", flush=True)
+    w = wl.small_decode(DEV, seed=41, ctx=(700, 1531, 64, 2048), ret_heads=ret_heads)
+    run = DecodeRun(w)
+    L = w.layer
+    run.step()
+    lse_sel = run.lse.clone()
+    dense_out, lse_full = torch.zeros_like(run.out), torch.zeros_like(run.lse)
+    run.dense_attn(dense_out, lse_full)
+    stats = torch.zeros((w.B, 4), dtype=torch.float32, device=DEV)
+    unions = torch.zeros((w.B, L.n_kv_heads), dtype=torch.int32, device=DEV)
+    rtp.rtp_sparsity_stats(run.desc, run.ctx_len, run.sel_idx, run.stride, run.sel_count, lse_sel, lse_full, w.B, stats, unions)
+    nolse = torch.zeros((w.B, 4), dtype=torch.float32, device=DEV)
+    rtp.rtp_sparsity_stats(run.desc, run.ctx_len, run.sel_idx, run.stride, run.sel_count, None, None, w.B, nolse, None)
+    sets, cnt = run.sel_sets()
+    st, un, nl = stats.cpu().numpy(), unions.cpu().numpy(), nolse.cpu().numpy()
+    oi = oracle_inputs(w)
+    sm = 1.0 / np.sqrt(128.0)
+    for b in range(w.B):
+        n, t0 = w.ctx_len[b], w.seq_start[b]
+        attended, masses = [], []
+        for h in range(L.n_q_heads):
+            if h in L.ret_heads:
+                s = sets[b * L.n_ret + L.ret_heads.index(h)]
+                attended.append(s)
+                kvh = orc.kv_head_of(h, L.n_q_heads, L.n_kv_heads)
+                masses.append(orc.attention_mass(oi["q_bits"][b, h], oi["K_bits"][kvh, t0:t0 + n], s, sm))
+            else:
+                attended.append(orc.local_set(n - 1, L.sink, L.window))
+        ref = orc.sparsity_stats(attended, n, L.n_q_heads, L.n_kv_heads, L.ret_heads)
+        assert list(un[b]) == ref["union_sizes"]                                  # integers: exact
+        assert abs(st[b, 0] - ref["compute_sparsity"]) < 1e-6
+        assert abs(st[b, 1] - ref["memory_sparsity"]) < 1e-6
+        assert abs(st[b, 2] - ref["active_tokens"]) < 1e-3
+        # the mass comes from two fp32 log-sum-exps of bf16-rounded logits: 1e-3 is their rounding budget
+        assert abs(st[b, 3] - float(np.mean(masses))) < 2e-3
+        assert np.array_equal(nl[b, :3], st[b, :3]) and np.isnan(nl[b, 3])
