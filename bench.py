@@ -148,6 +148,37 @@ def main() -> int:
     graph_us = timed(lambda i: graphs[i % len(graphs)].replay(), it, wu)
     launch_mode = "hip-graph replay" if args.graph else "eager"
 
+    # ---- the three selectors side by side on the same scores (paper Sec. 2.3 table: fixed top-k trades
+    # recall for sparsity; Sec. 3.4: the block-wise histogram selector) ----
+    selectors = {}
+    lse_full = [torch.zeros_like(r.lse) for r in runs]
+    scratch_out = torch.zeros_like(runs[0].out)
+    for r, lf in zip(runs, lse_full):
+        r.index_score_fused_timing(scratch_ws)            # plain scores in r.scores, nothing pending in the workspace
+        r.dense_attn(scratch_out, lf)
+    for name, sel_fn in (("top_p_%g" % args.p, lambda r: r.topp(scores=r.scores)),
+                         ("top_k_4096", lambda r: r.topk(4096)),
+                         ("block64_top_p_%g" % args.p, lambda r: r.block_topp())):
+        us_sel = timed(lambda i: sel_fn(runs[i % n_runs]), it, wu)
+        us_att = timed(lambda i: runs[i % n_runs].sparse_attn(), it, wu)
+        st = torch.stack([r.sparsity_stats(lf).clone() for r, lf in zip(runs, lse_full)]).mean(dim=(0, 1)).cpu().numpy()
+        selectors[name] = {"select_us": round(us_sel, 2), "sparse_attn_us": round(us_att, 2),
+                           "tokens_per_row_mean": round(float(st[2]), 1), "attention_mass": round(float(st[3]), 4),
+                           "compute_sparsity": round(float(st[0]), 4), "memory_sparsity": round(float(st[1]), 4)}
+    for r in runs:                                        # back to the benchmark's own selection
+        r.step()
+
+    # ---- index-key build: appending a prefill chunk / one decode token per sequence to the index cache ----
+    ib = {}
+    for T_app in (8192, B):
+        kpre = torch.randn((T_app, L.n_kv_heads, 128), device=dev).to(torch.bfloat16)
+        Wk = (torch.randn((n_ret, 16, 128), device=dev) / 128 ** 0.5).float()
+        dst = torch.zeros((n_ret, T_app, 16), dtype=torch.bfloat16, device=dev)
+        us_ib = timed(lambda i: rtp.rtp_index_project(runs[0].desc, Wk, kpre, rtp.RTP_SIDE_KEY, T_app, dst, T_app * 16, 0),
+                      it, wu)
+        ib["append_%d_tokens_us" % T_app] = round(us_ib, 2)
+    ib["append_8192_GBps"] = round(8192 * n_ret * (256 + 32) / ib["append_8192_tokens_us"] / 1e3, 1)
+
     # ---- algorithmic bytes per step (design notes: per-unit figures x units) ----
     sel_total = int(sel_counts.sum())
     bytes_index = B * n_ret * N * (32 + 4)
@@ -187,7 +218,7 @@ def main() -> int:
         while True:
             ref = orc.decode_layer(**oi)
             reps += 1
-            if time.perf_counter() - c0 > 10.0 or reps >= 20:
+            if time.perf_counter() - c0 > 10.0:
                 break
         c1 = time.perf_counter()
         cpu_us_step = (c1 - c0) / reps / nseq * B * 1e6
@@ -302,6 +333,8 @@ def main() -> int:
                           "sparse_attn_decode": round(bytes_sparse / br["sparse_attn_decode"] / 1e3, 1),
                           "local_attn": round(bytes_local / br["local_attn"] / 1e3, 1)},
             "slowest_call": dom,
+            "selectors": selectors,
+            "index_key_build": ib,
             "selected_tokens_per_row_mean": round(float(sel_counts.mean()), 1),
             "dense_attn_us": round(dense_us, 2),
             "dense_attn_GBps": round(bytes_dense / dense_us / 1e3, 1),

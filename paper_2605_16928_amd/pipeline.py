@@ -94,6 +94,31 @@ class DecodeRun:
         if ready:
             self._level1_pending = False
 
+    def topk(self, k: int):
+        """Static top-k over the scores of the last index_score call (the fixed-budget rule)."""
+        if not hasattr(self, "_k_rows") or self._k_val != k:
+            self._k_rows, self._k_val = i32([k] * max(self.R, 1)), k
+        rtp.rtp_topk_select(self.scores, self.stride, self.row_len, self._k_rows, self.R, self.max_ctx, self.sel_idx,
+                            self.stride, self.sel_count, self.tau, self.ws_topp)
+
+    def block_topp(self, bin_lo: float = -32.0, bin_width: float = 0.25):
+        """Block-wise histogram top-p (blocks of 64) over the scores of the last index_score call."""
+        if not hasattr(self, "ws_block"):
+            self.ws_block = ws_alloc(rtp.rtp_block_topp_workspace_bytes(max(self.R, 1), self.max_ctx))
+            self.thr_bin = torch.zeros((max(self.R, 1),), dtype=torch.int32, device=DEV)
+        rtp.rtp_block_topp_select(self.scores, self.stride, self.row_len, self.w.p_rows, self.R, self.max_ctx, 64,
+                                  bin_lo, bin_width, self.sel_idx, self.stride, self.sel_count, self.thr_bin,
+                                  self.mass, None, 0, self.ws_block)
+
+    def sparsity_stats(self, lse_full=None):
+        """[B, 4] compute sparsity, memory sparsity, active tokens, attention mass of the current selection
+        (the mass needs the log-sum-exps of the last sparse call in self.lse and of a dense call in lse_full)."""
+        if not hasattr(self, "stats"):
+            self.stats = torch.zeros((self.B, 4), dtype=torch.float32, device=DEV)
+        rtp.rtp_sparsity_stats(self.desc, self.ctx_len, self.sel_idx, self.stride, self.sel_count,
+                               self.lse if lse_full is not None else None, lse_full, self.B, self.stats)
+        return self.stats
+
     def sparse_attn(self, sel_idx=None, sel_count=None, max_sel=None):
         w = self.w
         rtp.rtp_sparse_attn_decode(self.desc, w.q, self.Kp, self.Vp, self.kv_rs, self.kv_hs, self.seq_start,
