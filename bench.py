@@ -236,12 +236,50 @@ def main() -> int:
         err = float(np.abs(got - ref["out"]).max())
         assert err < 2e-2, f"bench output differs from the oracle on the sample: {err}"
 
+    # ---- one decode step at 1,048,576 tokens (the 1M layer of configuration 4, batch 1) ----
+    decode_1m = None
+    if not args.no_prefill:
+        del graphs, runs
+        graphs, runs = [], []
+        torch.cuda.empty_cache()
+        r1 = [DecodeRun(wl.c4_decode(dev, seed=300 + i)) for i in range(2)]
+        for r in r1:
+            r.step()
+        torch.cuda.synchronize()
+        N1 = 1 << 20
+        sel1 = int(r1[0].sel_count.sum().item())
+        side1 = torch.cuda.Stream()
+        scratch1 = torch.zeros_like(r1[0].ws_topp)
+
+        def pair1(i):
+            r1[i % 2].index_score()
+            r1[i % 2].topp()
+
+        u_idx = timed(lambda i: r1[i % 2].index_score_fused_timing(scratch1), it, wu)
+        u_pair = timed(pair1, it, wu)
+        u_sp = timed(lambda i: r1[i % 2].sparse_attn(), it, wu)
+        u_lo = timed(lambda i: r1[i % 2].local_attn(), it, wu)
+        u_step = timed(lambda i: r1[i % 2].step_two_streams(side1), it, wu)
+        u_dense = timed(lambda i: r1[i % 2].dense_attn(r1[i % 2].out), 10, 2)
+        b_idx = n_ret * N1 * 36
+        decode_1m = {
+            "workload": "c4 layer, one decode step: batch 1 x context 1,048,576, 4 retrieval heads (top-p 0.9), local heads 4 sink + 4096 window",
+            "us_per_step": round(u_step, 2),
+            "call_us": {"index_score": round(u_idx, 2), "topp_select": round(u_pair - u_idx, 2),
+                        "sparse_attn_decode": round(u_sp, 2), "local_attn": round(u_lo, 2)},
+            "index_score_GBps": round(b_idx / u_idx / 1e3, 1), "index_score_frac_of_hbm_peak": round(b_idx / u_idx / 1e3 / HBM_PEAK_GBS, 4),
+            "selected_tokens_per_row_mean": round(sel1 / n_ret, 1),
+            "sparse_attn_GBps": round(sel1 * 516 / u_sp / 1e3, 1),
+            "dense_attn_us": round(u_dense, 2), "dense_attn_GBps": round(L.n_kv_heads * N1 * 512 / u_dense / 1e3, 1),
+            "speedup_vs_inhouse_dense": round(u_dense / u_step, 2),
+        }
+        del r1, scratch1
+        torch.cuda.empty_cache()
+
     # ---- prefill at 1,048,576 tokens (configuration 4): chunks of 8192 queries at five depths ----
     prefill = None
     if not args.no_prefill:
         from paper_2605_16928_amd.pipeline import PrefillRun
-        del graphs, runs
-        torch.cuda.empty_cache()
         MFMA_PEAK = 2.5e15
         depth = {}
         for chunk in (0, 31, 63, 95, 127):
@@ -320,6 +358,7 @@ def main() -> int:
         "roofline": roofline,
         "cpu_baseline": cpu,
         "prefill_1m": prefill,
+        "decode_1m": decode_1m,
         "extra": {
             "decode_tokens_per_s": round(B / (us_step * 1e-6), 1),
             "step_hbm_GBps_algorithmic": round(step_bytes / (us_step * 1e-6) / 1e9, 1),

@@ -177,6 +177,29 @@ def test_sparse_prefill_matches_oracle(name):
     print(f"[case] sparse prefill {name}", flush=True)
     kw, p = _sparse_cases()[name]
     w = wl.small_prefill(DEV, p=p, **kw)
+    _check_sparse_prefill(w, name, p)
+
+
+def test_sparse_prefill_key_ranges_without_a_kept_key():
+    """Long context, few heads: the launch cuts every query tile's key range in two, and with a small p the
+    few kept tokens of a query leave whole ranges empty -- a legitimate zero partial, not a failed reference."""
+    print("[case] sparse prefill, empty key ranges", flush=True)
+    w = wl.small_prefill(DEV, p=0.3, chunk_start=6000, T=64, seed=67)
+    cnt = _check_sparse_prefill(w, "empty_ranges", 0.3)
+    assert cnt.min() < 64                     # some query keeps less than one tile's worth of keys
+
+
+def test_sparse_prefill_reference_outrun_repeats_exactly():
+    """The selecting mode on inputs whose late keys score ~90 above the first tile: the fixed reference
+    overflows and the workgroup repeats its keys with the running maximum, keep test included."""
+    print("[case] sparse prefill, reference outrun upwards", flush=True)
+    w = wl.small_prefill(DEV, p=0.9, chunk_start=600, T=150, seed=93)
+    w.q[:] = 2.0
+    w.K[:, 300:, :] = 4.0
+    _check_sparse_prefill(w, "sparse_outrun", 0.9)
+
+
+def _check_sparse_prefill(w, name, p):
     L = w.layer
     run = PrefillRun(w)
     oi = prefill_oracle_inputs(w)
@@ -225,6 +248,7 @@ def test_sparse_prefill_matches_oracle(name):
             assert np.all(out[:, h] == 5.0)
     print(f"   worst abs err vs same-set oracle {worst:.2e}; kept tokens min/mean/max "
           f"{cnt.min()}/{cnt.mean():.1f}/{cnt.max()}", flush=True)
+    return cnt
 
 
 def test_sparse_prefill_p1_statistics_and_dense_equivalence():
