@@ -2,8 +2,11 @@
 // equation), rtp_local_attn in decode mode (sink + window rule, Sec. 3.2 / Sec. 4.2) and the dense
 // comparison rtp_dense_attn in decode mode.
 //
-// All three are the same HBM-bound kernel with a different token source: an index list (sparse), or
-// the ranges [0, sink) U [ctx - window, ctx) (local) / [0, ctx) (dense).  One K or V row is 256 bytes
+// All three stream K/V rows with a different token source: an index list (sparse), or the ranges
+// [0, sink) U [ctx - window, ctx) (local) / [0, ctx) (dense).  Two kernels share the work-item plan, the
+// partial format and the merge launch: the vector-ALU kernel described next (one query head per row:
+// the selected-token source, and range sources without GQA), and attn_decode_gqa_kernel further down
+// (a GQA group per row: the scores go to the matrix cores).  One K or V row is 256 bytes
 // = 16 lanes x 16 bytes, so a 64-lane wave loads four rows per instruction; the 16 lanes of a DPP row
 // own one token, multiply their 8 dims with the query and reduce with four DPP adds.  Each 16-lane
 // group keeps its own online-softmax state (max, sum, 8 output dims per lane) in registers for all
@@ -339,6 +342,186 @@ __global__ __launch_bounds__(kAdThreads) void attn_decode_kernel(const AttnDecod
   }
 }
 
+// ---- GQA groups on the matrix cores ---------------------------------------------------------------
+// With G >= 2 query heads per KV row the kernel above spends its time on the vector ALU (every head
+// repeats the 128-term dot product and its DPP reduction per row).  Here the scores of 16 tokens x G
+// heads are four v_mfma_f32_16x16x32_bf16 (A = the K rows in the MFMA operand layout: lane = token +
+// 16 * quarter, loaded straight from global memory, 64 contiguous bytes per row and instruction; B = the
+// G queries in 16 columns, zero beyond G).  The softmax runs in the MFMA result layout (lane = head +
+// 16 * row group, four tokens per lane), where a head's running maximum is uniform over its four lanes
+// after two cross-row exchanges.  The PV product stays on the vector ALU in the row-streaming layout
+// of the kernel above (16 lanes per token, 8 dims per lane): token 4 * grp + j of a tile is loaded by
+// lane group grp in round j, so the probability it needs sits in ITS OWN 16-lane row at lane = head,
+// register j, and one DPP row_share brings it to all 16 lanes.  Work items, partials and the merge
+// launch are those of the kernel above.
+typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
+typedef float f32x4_t __attribute__((ext_vector_type(4)));
+
+template <int H>
+__device__ __forceinline__ float row_share(float x) {      // every lane reads lane H of its own 16-lane row
+  return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), 0x150 + H, 0xf, 0xf, false));
+}
+
+template <int G, int SRC>
+__global__ __launch_bounds__(kAdThreads) void attn_decode_gqa_kernel(const AttnDecodeArgs a) {
+  static_assert(SRC != kSrcSparse && G >= 2 && G <= 16, "range sources, GQA groups");
+  constexpr int kTile = 16;                 // tokens per MFMA tile
+  constexpr int kTilesInFlight = 2;         // 8 x 16-byte loads per lane and tile in flight (1, 3 and 4 measured slower)
+  __shared__ float sh_m[kAdThreads / 64][G], sh_l[kAdThreads / 64][G];
+  __shared__ float sh_acc[kAdThreads / 64][G][kHeadDim];
+
+  const int ST = a.split_tokens;
+  const int n_items = a.units * a.n_splits;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int grp = lane >> 4, piece = lane & 15;
+  const float ninf = -__builtin_huge_valf();
+
+  for (int item = blockIdx.x; item < n_items; item += gridDim.x) {
+    const int unit = item / a.n_splits, split = item - unit * a.n_splits;
+    const int b = unit / a.n_kv_heads, kvh = unit - b * a.n_kv_heads, h0 = kvh * G;
+    const int n_tok = unit_tokens<SRC>(a, unit);
+    const int t_begin = split * ST, t_end = min(n_tok, t_begin + ST);
+    if (t_begin >= n_tok) continue;
+    int s0 = 0, w0 = 0;
+    if (SRC == kSrcLocal) {
+      const int n = a.ctx_len[b];
+      s0 = max(min(a.sink, n), 0);
+      w0 = max(a.sink, n - a.window);
+    }
+    auto pos_of = [&](int i) { return SRC == kSrcLocal ? (i < s0 ? i : w0 + (i - s0)) : i; };
+    const uint16_t* Kb = a.K + (int64_t)kvh * a.head_stride + a.seq_start[b] * a.row_stride;
+    const uint16_t* Vb = a.V + (int64_t)kvh * a.head_stride + a.seq_start[b] * a.row_stride;
+
+    // B operand: column piece = head (zero beyond G), k slice grp * 8 .. + 7 of each 32-dim step
+    u32x4 qB[4];
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk) {
+      qB[kk] = (u32x4){0u, 0u, 0u, 0u};
+      if (piece < G) qB[kk] = *reinterpret_cast<const u32x4*>(a.q + ((int64_t)b * a.n_q_heads + h0 + piece) * kHeadDim + kk * 32 + grp * 8);
+    }
+    float m_run = ninf, l_run = 0.f;         // head `piece`: maximum uniform over its four lanes, sum per lane
+    float acc[G][8];
+#pragma unroll
+    for (int hh = 0; hh < G; ++hh)
+#pragma unroll
+      for (int c = 0; c < 8; ++c) acc[hh][c] = 0.f;
+
+    // the wave's tiles: base, base + 4 * 16, ...; kTilesInFlight of them per round
+    const int wave_first = t_begin + wave * kTile;
+    for (int base = wave_first; base < t_end; base += (kAdThreads / 64) * kTile * kTilesInFlight) {
+      u32x4 kr[kTilesInFlight][4], vr[kTilesInFlight][4];
+#pragma unroll
+      for (int tl = 0; tl < kTilesInFlight; ++tl) {
+        const int tb = base + tl * (kAdThreads / 64) * kTile;
+        // K: lane (token piece, quarter grp) of the tile; rows past the end repeat the last valid one (masked below)
+        const int ik = min(tb + piece, t_end - 1);
+        const uint16_t* krow = Kb + (int64_t)pos_of(ik) * a.row_stride + grp * 8;
+#pragma unroll
+        for (int kk = 0; kk < 4; ++kk) kr[tl][kk] = *reinterpret_cast<const u32x4*>(krow + kk * 32);
+        // V: round j, lane group grp -> token 4 * grp + j, 8 dims per lane
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          const int iv = min(tb + 4 * grp + j, t_end - 1);
+          vr[tl][j] = *reinterpret_cast<const u32x4*>(Vb + (int64_t)pos_of(iv) * a.row_stride + piece * 8);
+        }
+      }
+#pragma unroll
+      for (int tl = 0; tl < kTilesInFlight; ++tl) {
+        const int tb = base + tl * (kAdThreads / 64) * kTile;
+        if (tb >= t_end) continue;                                   // wave-uniform
+        f32x4_t S = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int kk = 0; kk < 4; ++kk)
+          S = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, kr[tl][kk]),
+                                                      __builtin_bit_cast(bf16x8_t, qB[kk]), S, 0, 0, 0);
+        // lane (head piece, row group grp) holds tokens tb + 4 * grp + i, i < 4
+        float sc[4];
+        float mx = ninf;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          sc[i] = (tb + 4 * grp + i < t_end) ? S[i] * a.scale_log2 : ninf;
+          mx = fmaxf(mx, sc[i]);
+        }
+        mx = fmaxf(mx, __shfl_xor(mx, 16));
+        mx = fmaxf(mx, __shfl_xor(mx, 32));
+        const float m_new = fmaxf(m_run, mx);                       // finite: the tile has a valid token
+        const float corr = fast_exp2(m_run - m_new);                // 0 on the first tile (m_run = -inf)
+        float pw[4];
+        float ls = 0.f;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          pw[i] = fast_exp2(sc[i] - m_new);                         // exp2(-inf) = 0 for masked tokens
+          ls += pw[i];
+        }
+        l_run = l_run * corr + ls;
+        m_run = m_new;
+        // rescale the accumulators: head hh's factor sits in lane hh of every row
+        if (__ballot(corr != 1.f) != 0ull) {
+#pragma unroll
+          for (int hh = 0; hh < G; ++hh) {
+            const float ch = __shfl(corr, hh);
+#pragma unroll
+            for (int c = 0; c < 8; ++c) acc[hh][c] *= ch;
+          }
+        }
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          float vf[8];
+          unpack8(vr[tl][j], vf);
+          // probability of token 4 * grp + j for head hh: register j of lane hh of this lane's own row
+          float ph[G];
+          ph[0] = row_share<0>(pw[j]);
+          if (G > 1) ph[1] = row_share<1>(pw[j]);
+          if (G > 2) { ph[2] = row_share<2>(pw[j]); ph[3] = row_share<3>(pw[j]); }
+          if (G > 4) { ph[4] = row_share<4>(pw[j]); ph[5] = row_share<5>(pw[j]); ph[6] = row_share<6>(pw[j]); ph[7] = row_share<7>(pw[j]); }
+#pragma unroll
+          for (int hh = 0; hh < G; ++hh)
+#pragma unroll
+            for (int c = 0; c < 8; ++c) acc[hh][c] = fmaf(ph[hh], vf[c], acc[hh][c]);
+        }
+      }
+    }
+
+    // ---- the wave's result: sums over its four lane groups (they share the head maxima), then LDS ----
+    l_run += __shfl_xor(l_run, 16);
+    l_run += __shfl_xor(l_run, 32);
+#pragma unroll
+    for (int hh = 0; hh < G; ++hh)
+#pragma unroll
+      for (int c = 0; c < 8; ++c) {
+        acc[hh][c] += __shfl_xor(acc[hh][c], 16);
+        acc[hh][c] += __shfl_xor(acc[hh][c], 32);
+      }
+    __syncthreads();   // previous item's readers are done with the LDS buffers
+    if (lane < G) { sh_m[wave][lane] = m_run; sh_l[wave][lane] = l_run; }
+    if (lane < 16) {
+#pragma unroll
+      for (int hh = 0; hh < G; ++hh)
+#pragma unroll
+        for (int c = 0; c < 8; ++c) sh_acc[wave][hh][piece * 8 + c] = acc[hh][c];
+    }
+    __syncthreads();
+    float* pout = a.part + (int64_t)item * G * kPartStride;
+    for (int e = tid; e < G * kHeadDim; e += kAdThreads) {
+      const int hh = e >> 7, d = e & 127;
+      float M = sh_m[0][hh];
+#pragma unroll
+      for (int w = 1; w < kAdThreads / 64; ++w) M = fmaxf(M, sh_m[w][hh]);
+      float L = 0.f, A = 0.f;
+      if (M != ninf) {
+#pragma unroll
+        for (int w = 0; w < kAdThreads / 64; ++w) {
+          const float cw = fast_exp2(sh_m[w][hh] - M);
+          L += sh_l[w][hh] * cw;
+          A += sh_acc[w][hh][d] * cw;
+        }
+      }
+      pout[hh * kPartStride + 4 + d] = A;
+      if (d == 0) { pout[hh * kPartStride] = M; pout[hh * kPartStride + 1] = L; }
+    }
+  }
+}
+
 // Merges the partials of one (unit, head) per workgroup: 8 slices of 32 lanes, each lane owns 4 of the
 // 128 output dims and walks the unit's work items slice, slice + 8, ...; LDS merges the 8 slices.
 template <int G, int SRC>
@@ -449,22 +632,23 @@ static DecodePlanHost plan_host_range(int32_t units, int64_t max_tok, int32_t G)
 template <int SRC>
 static int32_t launch_decode(const AttnDecodeArgs& a, int G, int grid, hipStream_t s, const char* who) {
   const int cgrid = a.units * G;
-#define RTP_LAUNCH(GG, UU)                                                                          \
-  hipLaunchKernelGGL((attn_decode_kernel<GG, SRC, UU>), dim3(grid), dim3(kAdThreads), 0, s, a);     \
+  // one head per K/V row (always so for the selected-token source): the vector-ALU kernel;
+  // a GQA group per row: scores on the matrix cores
+#define RTP_LAUNCH_GQA(GG)                                                                                   \
+  hipLaunchKernelGGL((attn_decode_gqa_kernel<GG, SRC == kSrcSparse ? kSrcDense : SRC>), dim3(grid), dim3(kAdThreads), 0, s, a); \
   hipLaunchKernelGGL((attn_decode_combine_kernel<GG, SRC>), dim3(cgrid), dim3(kAdThreads), 0, s, a);
-  if (SRC == kSrcSparse) {
-    RTP_LAUNCH(1, 8)
+  if (SRC == kSrcSparse || G == 1) {
+    hipLaunchKernelGGL((attn_decode_kernel<1, SRC, 8>), dim3(grid), dim3(kAdThreads), 0, s, a);
+    hipLaunchKernelGGL((attn_decode_combine_kernel<1, SRC>), dim3(cgrid), dim3(kAdThreads), 0, s, a);
   } else {
-    const int u4 = tune("RTP_TUNE_G4_U", 8);
     switch (G) {
-      case 1: RTP_LAUNCH(1, 8) break;
-      case 2: RTP_LAUNCH(2, 8) break;
-      case 4: if (u4 == 4) { RTP_LAUNCH(4, 4) } else { RTP_LAUNCH(4, 8) } break;
-      case 8: RTP_LAUNCH(8, 4) break;
+      case 2: RTP_LAUNCH_GQA(2) break;
+      case 4: RTP_LAUNCH_GQA(4) break;
+      case 8: RTP_LAUNCH_GQA(8) break;
       default: return fail(RTP_ERR_UNSUPPORTED, "%s: group size %d", who, G);
     }
   }
-#undef RTP_LAUNCH
+#undef RTP_LAUNCH_GQA
   return check_launch(who);
 }
 
