@@ -8,8 +8,14 @@
 // descending cumulative mass crosses p * Z.  After three levels the threshold key is exact.
 // Masses are integers (see topp_common.h), so the result does not depend on atomic ordering.
 //
-// Launches: [zero] -> level 1 -> level 2 -> level 3 -> count -> write.  The first two disappear when
-// the score pass has already accumulated level 1 (level1_ready).  There is no "last block" hand-off:
+// Launches: [zero] -> level 1 -> level 2 -> level 3 -> write.  The first two disappear when
+// the score pass has already accumulated level 1 (level1_ready).  Level 3 also leaves, per chunk, the
+// number of scores strictly above the 22-bit prefix (certainly kept) and appends the few scores that
+// share the prefix to a short per-row list; the write launch finds the exact threshold from the
+// level-3 histogram and takes the kept list members' positions into its chunk offsets, so no separate
+// counting pass over the scores is needed.  (A row whose list overflows -- thousands of scores equal
+// in their top 22 key bits -- is still written correctly: its workgroups count their predecessors'
+// kept scores themselves.)  There is no "last block" hand-off:
 // each level's histogram is scanned redundantly in the prologue of every workgroup of the NEXT
 // launch, so kernel boundaries provide all the ordering.  A row is cut into chunks of kTpChunk
 // scores, one workgroup each; histograms live in LDS and only non-empty bins are flushed with 64-bit
@@ -32,16 +38,18 @@ constexpr int kTpThreads = 256;
 constexpr int kTpChunk = RTP_TP_CHUNK;     // scores per workgroup (2048, 4096 or 8192)
 constexpr int kTpVec = kTpChunk / (kTpThreads * 4);   // float4 loads per thread
 
-struct RowState {          // one per row and launch (levels 2, 3 and count leave one each)
+struct RowState {          // one per row and launch (levels 2 and 3 leave one each)
   double above_base;       // mass strictly above the level-1 threshold bin, in that bin's integer units
   double total_d;          // Z in the same units
   uint64_t above;          // integer mass above the current prefix range INSIDE the level-1 bin
   uint64_t target;         // integer mass to reach inside the level-1 bin
-  uint32_t prefix;         // key bits resolved so far (right-aligned); after count: the threshold key
+  uint32_t prefix;         // key bits resolved so far (right-aligned)
   int32_t flags;           // 0 ok, 1 = keep everything (p >= 1), -1 = invalid p, 2 = no finite score
   float ref;               // reference score of the level-1 threshold bin
   int32_t shift;
 };
+
+constexpr int kBucketCap = 1024;
 
 struct TopPArgs {
   const float* scores;
@@ -58,9 +66,11 @@ struct TopPArgs {
   int32_t* sel_count;
   float* tau;
   float* mass;
-  int32_t* chunk_cnt;      // [R, n_chunks]
+  int32_t* chunk_cnt;      // [R, n_chunks]: scores of the chunk strictly above the level-2 prefix (or all finite ones)
   uint64_t* hist;          // [R, kBinsTotal]
   RowState* state;         // [R, 3]
+  int32_t* bucket_n;       // [R]: scores that share the level-2 prefix (may exceed kBucketCap)
+  uint2* bucket;           // [R, kBucketCap]: (key, position) of the first kBucketCap of them
 };
 
 TopPLayout topp_layout(int32_t R, int64_t max_len) {
@@ -70,6 +80,8 @@ TopPLayout topp_layout(int32_t R, int64_t max_len) {
   l.hist_off = off;  off = align_up(off + (size_t)R * kBinsTotal * sizeof(uint64_t), 256);
   l.ccnt_off = off;  off = align_up(off + (size_t)R * n_chunks * sizeof(int32_t), 256);
   l.state_off = off; off = align_up(off + (size_t)R * 3 * sizeof(RowState), 256);
+  l.bn_off = off;    off = align_up(off + (size_t)R * sizeof(int32_t), 256);
+  l.bucket_off = off; off = align_up(off + (size_t)R * kBucketCap * sizeof(uint2), 256);
   l.total = off;
   return l;
 }
@@ -241,6 +253,21 @@ __global__ __launch_bounds__(kTpThreads) void topp_zero_kernel(uint64_t* hist, i
   if (i < n) hist[i] = 0;
 }
 
+// Sum of `cnt` over the workgroup, stored by thread 0 (two barriers).
+__device__ __forceinline__ void block_count_to(int cnt, int32_t* dst, int* sh_i /*[waves]*/) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) cnt += __shfl_xor(cnt, o);
+  __syncthreads();
+  if ((threadIdx.x & 63) == 0) sh_i[threadIdx.x >> 6] = cnt;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    int tot = 0;
+#pragma unroll
+    for (int i = 0; i < kTpThreads / 64; ++i) tot += sh_i[i];
+    *dst = tot;
+  }
+}
+
 // ---- launches 1-3: one histogram level each ----------------------------------------------------
 template <int LEVEL>
 __global__ __launch_bounds__(kTpThreads) void topp_level_kernel(const TopPArgs a) {
@@ -265,6 +292,13 @@ __global__ __launch_bounds__(kTpThreads) void topp_level_kernel(const TopPArgs a
   fill_exp_table(tab);
   uint64_t* hrow = a.hist + (int64_t)r * kBinsTotal;
   RowState* st = a.state + (int64_t)r * 3;
+  if (LEVEL == 2) {
+    // level 3's histogram and the row's short list are written by the NEXT launch and were last read by
+    // the write launch of the previous call: this is the safe place to clear them
+    const int active = (n + kTpChunk - 1) / kTpChunk;
+    for (int i = c * kTpThreads + tid; i < kBins3; i += active * kTpThreads) hrow[kBins1 + kBins2 + i] = 0;
+    if (c == 0 && tid == 0) a.bucket_n[r] = 0;
+  }
 
   // ---- prologue: what the previous launch left for this row ----
   const int shift = fixed_shift(n);
@@ -335,6 +369,18 @@ __global__ __launch_bounds__(kTpThreads) void topp_level_kernel(const TopPArgs a
       st[1].shift = st[0].shift;
     }
   }
+  if (LEVEL == 3 && flags == 1) {
+    // keep-everything rows: the write launch needs the number of finite scores per chunk
+    int cnt = 0;
+#pragma unroll
+    for (int u = 0; u < kTpVec; ++u) {
+      const int e = (u * kTpThreads + tid) * 4;
+      const float s4[4] = {v[u].x, v[u].y, v[u].z, v[u].w};
+#pragma unroll
+      for (int k = 0; k < 4; ++k) cnt += (e + k < n_here && s4[k] != -__builtin_huge_valf()) ? 1 : 0;
+    }
+    block_count_to(cnt, a.chunk_cnt + (int64_t)r * a.n_chunks + c, sh_i);
+  }
   if (flags != 0) return;          // keep-all, invalid or empty rows need no histogram
 
   // Levels 2 and 3 weigh only the members of the prefix bin (a few percent of the chunk at level 2,
@@ -362,6 +408,9 @@ __global__ __launch_bounds__(kTpThreads) void topp_level_kernel(const TopPArgs a
       }
     }
   } else if (LEVEL == 3) {
+    // scores strictly above the prefix are certainly kept: count them; the few that share the prefix go
+    // into the level-3 histogram and onto the row's short list (key, position)
+    int cnt_above = 0;
 #pragma unroll
     for (int u = 0; u < kTpVec; ++u) {
       const int e = (u * kTpThreads + tid) * 4;
@@ -369,12 +418,17 @@ __global__ __launch_bounds__(kTpThreads) void topp_level_kernel(const TopPArgs a
 #pragma unroll
       for (int k = 0; k < 4; ++k) {
         const uint32_t key = float_key(s4[k]);
-        if (e + k < n_here && (key >> 10) == prefix && s4[k] != -__builtin_huge_valf()) {
+        const bool ok = e + k < n_here && s4[k] != -__builtin_huge_valf();
+        cnt_above += (ok && (key >> 10) > prefix) ? 1 : 0;
+        if (ok && (key >> 10) == prefix) {
           const uint64_t w = by_count ? 1ull : fixed_weight(s4[k], ref, shift, tab);
           if (w) atomicAdd((unsigned long long*)&lh[key & (kBins - 1)], (unsigned long long)w);
+          const int slot = atomicAdd(&a.bucket_n[r], 1);
+          if (slot < kBucketCap) a.bucket[(int64_t)r * kBucketCap + slot] = make_uint2(key, (uint32_t)(n0 + e + k));
         }
       }
     }
+    block_count_to(cnt_above, a.chunk_cnt + (int64_t)r * a.n_chunks + c, sh_i);
   } else {
     constexpr int kAbove = kShift + 11;                          // key bits of the prefix start here
     uint32_t member = 0;
@@ -479,20 +533,25 @@ __device__ __forceinline__ void write_ranked(uint32_t keep, int before, int32_t*
   }
 }
 
-__global__ __launch_bounds__(kTpThreads) void topp_count_kernel(const TopPArgs a) {
+// ---- launch 4: exact threshold, chunk offsets, ordered compaction -----------------------------------
+// Every workgroup of a row repeats the final scan (level-3 histogram -> threshold key) and derives its
+// chunk's offset: the certainly-kept counts of the chunks before it (level-3 launch) plus the kept
+// members of the row's short list that lie before it.  Positions inside a chunk come from block-wide
+// prefix sums, so the row's kept positions are ascending.
+__global__ __launch_bounds__(kTpThreads) void topp_write_kernel(const TopPArgs a) {
   const int r = blockIdx.y, c = blockIdx.x, tid = threadIdx.x;
+  if (a.rezero) {                  // levels 1 and 2 were last read by the level-2 / level-3 launches
+    uint64_t* h = a.hist + (int64_t)r * kBinsTotal;
+    for (int i = c * kTpThreads + tid; i < kBins1 + kBins2; i += a.n_chunks * kTpThreads) h[i] = 0;
+  }
   const int n = a.row_len[r];
   const int64_t n0 = (int64_t)c * kTpChunk;
-  RowState* st = a.state + (int64_t)r * 3;
   const float ninf = -__builtin_huge_valf();
   if (n <= 0) {
     if (c == 0 && tid == 0) {
       if (a.tau) a.tau[r] = ninf;
       if (a.mass) a.mass[r] = 0.f;
       a.sel_count[r] = 0;
-      RowState s = {};
-      s.flags = 2;
-      st[2] = s;
     }
     return;
   }
@@ -502,21 +561,22 @@ __global__ __launch_bounds__(kTpThreads) void topp_count_kernel(const TopPArgs a
   load_chunk(reinterpret_cast<const float4*>(a.scores + (int64_t)r * a.score_stride + n0), n_here, tid, v);
   __shared__ uint64_t sh_part[kTpThreads / 64];
   __shared__ uint64_t sh_res[3];
-  __shared__ int sh_cnt[kTpThreads / 64];
+  __shared__ int sh_red[kTpThreads / 64][2];
+  __shared__ uint64_t sh_tot[kTpThreads / 64][2];
   const uint64_t* hrow = a.hist + (int64_t)r * kBinsTotal;
   // level 2 always leaves st[0]; level 3 leaves st[1] (a copy of st[0] for rows that carry no search)
-  const RowState prev = st[1];
+  const RowState prev = a.state[(int64_t)r * 3 + 1];
 
-  uint32_t tkey = 0;      // keep keys >= tkey
   if (prev.flags < 0 || prev.flags == 2) {
     if (c == 0 && tid == 0) {
       a.sel_count[r] = prev.flags < 0 ? -1 : 0;
       if (a.tau) a.tau[r] = prev.flags < 0 ? __builtin_nanf("") : ninf;
       if (a.mass) a.mass[r] = 0.f;
-      st[2] = prev;
     }
     return;
-  } else if (prev.flags == 0) {
+  }
+  uint32_t tkey = 0;      // keep keys >= tkey
+  if (prev.flags == 0) {
     const ScanResult sr = scan_from_top<kBins3>(hrow + kBins1 + kBins2, prev.above, prev.target, sh_part, sh_res);
     tkey = (prev.prefix << 10) | (uint32_t)sr.bin;
     if (c == 0 && tid == 0) {
@@ -527,51 +587,35 @@ __global__ __launch_bounds__(kTpThreads) void topp_count_kernel(const TopPArgs a
     if (a.tau) a.tau[r] = ninf;
     if (a.mass) a.mass[r] = 1.f;
   }
-  if (c == 0 && tid == 0) {
-    RowState s = prev;
-    s.prefix = tkey;
-    st[2] = s;
-  }
 
-  int cnt = __popc(keep_mask(v, n_here, tid, prev.flags == 1, tkey));
-#pragma unroll
-  for (int o = 32; o > 0; o >>= 1) cnt += __shfl_xor(cnt, o);
-  if ((tid & 63) == 0) sh_cnt[tid >> 6] = cnt;
-  __syncthreads();
-  if (tid == 0) {
-    int tot = 0;
-#pragma unroll
-    for (int i = 0; i < kTpThreads / 64; ++i) tot += sh_cnt[i];
-    a.chunk_cnt[(int64_t)r * a.n_chunks + c] = tot;
-  }
-}
-
-// Writes the kept positions of the row in ascending order: chunk bases come from the per-chunk
-// counts of the previous launch, positions inside a chunk from block-wide prefix sums.
-__global__ __launch_bounds__(kTpThreads) void topp_write_kernel(const TopPArgs a) {
-  const int r = blockIdx.y, c = blockIdx.x, tid = threadIdx.x;
-  if (a.rezero) {                  // every reader of the histograms ran in an earlier launch
-    uint64_t* h = a.hist + (int64_t)r * kBinsTotal;
-    for (int i = c * kTpThreads + tid; i < kBinsTotal; i += a.n_chunks * kTpThreads) h[i] = 0;
-  }
-  const int n = a.row_len[r];
-  const int64_t n0 = (int64_t)c * kTpChunk;
-  if (n <= 0 || n0 >= n) return;
-  const int n_here = (int)min((int64_t)kTpChunk, (int64_t)n - n0);
-  float4 v[kTpVec];
-  load_chunk(reinterpret_cast<const float4*>(a.scores + (int64_t)r * a.score_stride + n0), n_here, tid, v);
-  const RowState st = a.state[(int64_t)r * 3 + 2];
-  if (st.flags < 0 || st.flags == 2) return;
-  __shared__ int sh_red[kTpThreads / 64][2];
-  __shared__ uint64_t sh_tot[kTpThreads / 64][2];
-
-  // ---- base of this chunk = kept count of the chunks before it; chunk 0 also publishes the total ----
+  // ---- offset of this chunk = kept scores of the chunks before it; chunk 0 also publishes the total ----
   const int n_row_chunks = (n + kTpChunk - 1) / kTpChunk;
+  const int listed = prev.flags == 0 ? a.bucket_n[r] : 0;
   int before = 0, total = 0;
-  for (int i = tid; i < n_row_chunks; i += kTpThreads) {
-    const int v = a.chunk_cnt[(int64_t)r * a.n_chunks + i];
-    total += v;
-    if (i < c) before += v;
+  if (listed <= kBucketCap) {
+    for (int i = tid; i < n_row_chunks; i += kTpThreads) {
+      const int cv = a.chunk_cnt[(int64_t)r * a.n_chunks + i];
+      total += cv;
+      if (i < c) before += cv;
+    }
+    for (int i = tid; i < listed; i += kTpThreads) {
+      const uint2 e = a.bucket[(int64_t)r * kBucketCap + i];
+      if (e.x >= tkey) {
+        total += 1;
+        if ((int64_t)e.y < n0) before += 1;
+      }
+    }
+  } else {
+    // more scores share the 22-bit prefix than the list holds: count the kept scores before this chunk
+    // (and, for chunk 0, of the whole row) straight from the scores
+    const float* row = a.scores + (int64_t)r * a.score_stride;
+    const int64_t upto = c == 0 ? n : n0;
+    for (int64_t i = tid; i < upto; i += kTpThreads) {
+      const float sv = row[i];
+      const int k1 = (sv != ninf && float_key(sv) >= tkey) ? 1 : 0;
+      total += k1;
+      if (i < n0) before += k1;
+    }
   }
 #pragma unroll
   for (int o = 32; o > 0; o >>= 1) {
@@ -586,7 +630,7 @@ __global__ __launch_bounds__(kTpThreads) void topp_write_kernel(const TopPArgs a
   for (int i = 0; i < kTpThreads / 64; ++i) { before += sh_red[i][0]; total += sh_red[i][1]; }
   if (c == 0 && tid == 0) a.sel_count[r] = total;
 
-  const uint32_t keep = keep_mask(v, n_here, tid, st.flags == 1, st.prefix);
+  const uint32_t keep = keep_mask(v, n_here, tid, prev.flags == 1, tkey);
   write_ranked(keep, before, a.sel_idx + (int64_t)r * a.sel_stride, n0, sh_tot);
 }
 
@@ -648,6 +692,8 @@ static int32_t run_select(const char* who, const float* scores, int64_t score_st
   a.chunk_cnt = (int32_t*)((char*)ws + l.ccnt_off);
   a.hist = (uint64_t*)((char*)ws + l.hist_off);
   a.state = (RowState*)((char*)ws + l.state_off);
+  a.bucket_n = (int32_t*)((char*)ws + l.bn_off);
+  a.bucket = (uint2*)((char*)ws + l.bucket_off);
 
   hipStream_t s = (hipStream_t)stream;
   dim3 grid((unsigned)a.n_chunks, (unsigned)R), block(kTpThreads);
@@ -658,7 +704,6 @@ static int32_t run_select(const char* who, const float* scores, int64_t score_st
   }
   hipLaunchKernelGGL(topp_level_kernel<2>, grid, block, 0, s, a);
   hipLaunchKernelGGL(topp_level_kernel<3>, grid, block, 0, s, a);
-  hipLaunchKernelGGL(topp_count_kernel, grid, block, 0, s, a);
   hipLaunchKernelGGL(topp_write_kernel, grid, block, 0, s, a);
   return check_launch(who);
 }

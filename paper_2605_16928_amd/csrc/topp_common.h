@@ -88,7 +88,7 @@ __device__ __forceinline__ void flush_hist(const uint64_t* lh, uint64_t* gh, int
 // Workspace of one rtp_topp_select call (R rows of at most max_len scores).  rtp_index_score uses
 // the same layout when it is asked to accumulate level 1.
 struct TopPLayout {
-  size_t ccnt_off, hist_off, state_off, total;
+  size_t ccnt_off, hist_off, state_off, bn_off, bucket_off, total;
 };
 TopPLayout topp_layout(int32_t R, int64_t max_len);
 
