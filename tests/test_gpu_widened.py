@@ -99,6 +99,28 @@ def test_topk_select_matches_oracle_with_ties_and_edge_budgets():
             assert t[i] == np.float32(ref["tau"])
 
 
+def test_topk_and_block_selectors_at_benchmark_size():
+    """Configuration 2's score rows (131072 tokens, 64 planted), the budgets the benchmark compares:
+    k = 4096 and the block-64 selector at p = 0.9, every row against the oracle."""
+    print("[case] selectors at 131072", flush=True)
+    w = wl.c2(DEV, seed=77, batch=2)
+    run = DecodeRun(w, fuse_level1=False)
+    run.index_score()
+    sc = run.scores.cpu().numpy().astype(np.float64)
+    run.topk(4096)
+    sets, cnt = run.sel_sets()
+    for r in range(run.R):
+        ref = orc.topk_select(sc[r, :131072], 4096)
+        want = np.nonzero(sc[r, :131072] >= ref["tau"])[0]
+        assert np.array_equal(sets[r], want) and cnt[r] >= 4096
+    run.block_topp()
+    sets, cnt = run.sel_sets()
+    thr = run.thr_bin.cpu().numpy()
+    for r in range(run.R):
+        ref = orc.block_topp_select(sc[r, :131072], float(w.p_rows[r].item()))
+        assert np.array_equal(sets[r], ref["idx"]) and thr[r] == ref["threshold_bin"]
+
+
 # ---------------------------------------------------------------------------------------------------
 # block-wise histogram top-p (Sec. 3.4)
 # ---------------------------------------------------------------------------------------------------
