@@ -134,14 +134,23 @@ def main() -> int:
         runs[i % n_runs].index_score()
         runs[i % n_runs].topp()
 
+    def score_then_select_attend(i):
+        runs[i % n_runs].index_score()
+        runs[i % n_runs].select_attend()
+
     us_index = timed(lambda i: runs[i % n_runs].index_score_fused_timing(scratch_ws), it, wu)
     us_pair = timed(score_then_select, it, wu)
+    us_chain = timed(score_then_select_attend, it, wu)
     br = {
         "index_score": us_index,                       # score pass incl. the first histogram level of top-p
-        "topp_select": us_pair - us_index,             # the remaining four launches of the selector
-        "sparse_attn_decode": timed(lambda i: runs[i % n_runs].sparse_attn(), it, wu),
+        "select_attend_decode": us_chain - us_index,   # what the step runs: selection + retrieval-head attention, one call
         "local_attn": timed(lambda i: runs[i % n_runs].local_attn(), it, wu),
     }
+    br_separate = {                                    # the same work as two calls
+        "topp_select": us_pair - us_index,             # the remaining three launches of the selector
+        "sparse_attn_decode": timed(lambda i: runs[i % n_runs].sparse_attn(), it, wu),
+    }
+    us_step_separate = timed(lambda i: runs[i % n_runs].step_two_streams(side2, fused=False), it, wu)
     us_topp_standalone = timed(lambda i: runs[i % n_runs].topp(scores=runs[i % n_runs].scores), it, wu)
     dense_us = timed(lambda i: runs[i % len(runs)].dense_attn(runs[i % len(runs)].out), max(10, it // 10), 2)
     eager_us = timed(lambda i: run_step(runs[i % len(runs)]), it, wu)
@@ -189,8 +198,6 @@ def main() -> int:
     step_bytes = bytes_index + bytes_topp + bytes_sparse + bytes_local
 
     dom = max(br, key=br.get)
-    dom_bytes = {"index_score": bytes_index, "topp_select": bytes_topp, "sparse_attn_decode": bytes_sparse,
-                 "local_attn": bytes_local}[dom]
     # the roofline object describes the indexer score pass: the one kernel whose traffic grows with the
     # full context for every retrieval head, i.e. the HBM-bound core of the step
     ach = bytes_index / (br["index_score"] * 1e-6) / 1e9
@@ -255,8 +262,13 @@ def main() -> int:
             r1[i % 2].index_score()
             r1[i % 2].topp()
 
+        def chain1(i):
+            r1[i % 2].index_score()
+            r1[i % 2].select_attend()
+
         u_idx = timed(lambda i: r1[i % 2].index_score_fused_timing(scratch1), it, wu)
         u_pair = timed(pair1, it, wu)
+        u_chain = timed(chain1, it, wu)
         u_sp = timed(lambda i: r1[i % 2].sparse_attn(), it, wu)
         u_lo = timed(lambda i: r1[i % 2].local_attn(), it, wu)
         u_step = timed(lambda i: r1[i % 2].step_two_streams(side1), it, wu)
@@ -265,8 +277,10 @@ def main() -> int:
         decode_1m = {
             "workload": "c4 layer, one decode step: batch 1 x context 1,048,576, 4 retrieval heads (top-p 0.9), local heads 4 sink + 4096 window",
             "us_per_step": round(u_step, 2),
-            "call_us": {"index_score": round(u_idx, 2), "topp_select": round(u_pair - u_idx, 2),
-                        "sparse_attn_decode": round(u_sp, 2), "local_attn": round(u_lo, 2)},
+            "call_us": {"index_score": round(u_idx, 2), "select_attend_decode": round(u_chain - u_idx, 2),
+                        "local_attn": round(u_lo, 2)},
+            "separate_calls_us": {"topp_select": round(u_pair - u_idx, 2), "sparse_attn_decode": round(u_sp, 2),
+                                  "step": round(timed(lambda i: r1[i % 2].step_two_streams(side1, fused=False), it, wu), 2)},
             "index_score_GBps": round(b_idx / u_idx / 1e3, 1), "index_score_frac_of_hbm_peak": round(b_idx / u_idx / 1e3 / HBM_PEAK_GBS, 4),
             "selected_tokens_per_row_mean": round(sel1 / n_ret, 1),
             "sparse_attn_GBps": round(sel1 * 516 / u_sp / 1e3, 1),
@@ -366,11 +380,14 @@ def main() -> int:
             "eager_us_per_step": round(eager_us, 2),
             "graph_replay_us_per_step": round(graph_us, 2),
             "call_us": {k: round(v, 2) for k, v in br.items()},
-            "topp_select_standalone_us": round(us_topp_standalone, 2),
             "call_GBps": {"index_score": round(bytes_index / br["index_score"] / 1e3, 1),
-                          "topp_select": round(bytes_topp / br["topp_select"] / 1e3, 1),
-                          "sparse_attn_decode": round(bytes_sparse / br["sparse_attn_decode"] / 1e3, 1),
+                          "select_attend_decode": round((bytes_topp + bytes_sparse) / br["select_attend_decode"] / 1e3, 1),
                           "local_attn": round(bytes_local / br["local_attn"] / 1e3, 1)},
+            "separate_calls": {"us_per_step": round(us_step_separate, 2),
+                               "call_us": {k: round(v, 2) for k, v in br_separate.items()},
+                               "call_GBps": {"topp_select": round(bytes_topp / br_separate["topp_select"] / 1e3, 1),
+                                             "sparse_attn_decode": round(bytes_sparse / br_separate["sparse_attn_decode"] / 1e3, 1)},
+                               "topp_select_standalone_us": round(us_topp_standalone, 2)},
             "slowest_call": dom,
             "selectors": selectors,
             "index_key_build": ib,

@@ -296,6 +296,35 @@ int32_t rtp_sparsity_stats(const rtp_layer_desc* layer, const int32_t* ctx_len,
                            const float* lse_selected, const float* lse_full, int32_t B,
                            float* stats, int32_t* union_size, void* stream);
 
+/* ---------------------------------------------------------------------------------------------
+ * (2) + (3) in one call for a decode step -- Sec. 3.2 (S = Top-P(s, p), then exact softmax attention
+ * over S).  Sec. 3.4 saves a launch per step by fusing neighbouring stages (there: scoring and selection);
+ * the pair fused here is the last selection launch and the attention.
+ *
+ * The results are those of rtp_topp_select followed by rtp_sparse_attn_decode on the same tensors
+ * (sel_idx, sel_count, tau, mass bit-identical; out and lse equal up to the order of the fp32 partial
+ * sums), with one launch and one pass over the index list less: the launch that writes the ordered
+ * positions of a 4096-score chunk keeps them in LDS, gathers their K/V rows and leaves a partial softmax
+ * state per (row, chunk); a merge launch finishes each row.
+ *
+ * Rows are the retrieval heads of the batch: row r = b * n_ret + j scores the cached tokens of sequence b
+ * for head ret_heads[j] (the layout rtp_index_score writes with n_q = 1), R = B * n_ret rows.
+ *   scores, score_stride, row_len, p, sel_idx, sel_stride, sel_count, tau, mass, level1_ready, topp_ws:
+ *             as in rtp_topp_select with R = B * n_ret and max_len = max_ctx.
+ *   q, K, V, kv_row_stride, kv_head_stride, seq_start, out, lse: as in rtp_sparse_attn_decode.
+ *   attn_ws   rtp_select_attend_decode_workspace_bytes(layer, B, max_ctx) bytes, 256-byte aligned.
+ * Rows that select nothing (invalid p, no finite score, row_len <= 0) write zeros and lse = -inf.
+ */
+size_t rtp_select_attend_decode_workspace_bytes(const rtp_layer_desc* layer, int32_t B, int64_t max_ctx);
+int32_t rtp_select_attend_decode(const rtp_layer_desc* layer, const float* scores, int64_t score_stride,
+                                 const int32_t* row_len, const float* p, int32_t B, int64_t max_ctx,
+                                 const void* q, const void* K, const void* V, int64_t kv_row_stride,
+                                 int64_t kv_head_stride, const int64_t* seq_start,
+                                 int32_t* sel_idx, int64_t sel_stride, int32_t* sel_count,
+                                 float* tau, float* mass, int32_t level1_ready, void* out, float* lse,
+                                 void* topp_ws, size_t topp_ws_bytes, void* attn_ws, size_t attn_ws_bytes,
+                                 void* stream);
+
 #ifdef __cplusplus
 }
 #endif

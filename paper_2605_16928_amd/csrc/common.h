@@ -90,4 +90,52 @@ __device__ __forceinline__ float pair_sum(float x) {
 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
+// ---- wave-wide inclusive prefix sums on the DPP data path ------------------------------------------
+// Four shifts inside the 16-lane rows, then lane 15 of rows 0 and 2 into rows 1 and 3 (row_bcast:15) and
+// lane 31 into the upper half (row_bcast:31): six dependent vector-ALU steps, where a shuffle-based scan
+// makes six round trips through the LDS crossbar.  A lane without a source (and a row the mask leaves
+// out) receives 0.
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ int dpp_or_zero(int x) { return __builtin_amdgcn_update_dpp(0, x, CTRL, ROW_MASK, 0xf, false); }
+
+#define RTP_WAVE_SCAN_STEPS(STEP) \
+  STEP(0x111, 0xf) STEP(0x112, 0xf) STEP(0x114, 0xf) STEP(0x118, 0xf) STEP(0x142, 0xa) STEP(0x143, 0xc)
+
+__device__ __forceinline__ int wave_incl_scan(int x) {
+#define RTP_STEP(CTRL, MASK) x += dpp_or_zero<CTRL, MASK>(x);
+  RTP_WAVE_SCAN_STEPS(RTP_STEP)
+#undef RTP_STEP
+  return x;
+}
+__device__ __forceinline__ uint64_t wave_incl_scan(uint64_t x) {
+#define RTP_STEP(CTRL, MASK)                                                                   \
+  x += ((uint64_t)(uint32_t)dpp_or_zero<CTRL, MASK>((int)(uint32_t)(x >> 32)) << 32) |        \
+       (uint64_t)(uint32_t)dpp_or_zero<CTRL, MASK>((int)(uint32_t)x);
+  RTP_WAVE_SCAN_STEPS(RTP_STEP)
+#undef RTP_STEP
+  return x;
+}
+__device__ __forceinline__ double wave_incl_scan(double x) {
+#define RTP_STEP(CTRL, MASK)                                                                   \
+  {                                                                                            \
+    const uint64_t b = (uint64_t)__double_as_longlong(x);                                      \
+    const uint64_t t = ((uint64_t)(uint32_t)dpp_or_zero<CTRL, MASK>((int)(uint32_t)(b >> 32)) << 32) | \
+                       (uint64_t)(uint32_t)dpp_or_zero<CTRL, MASK>((int)(uint32_t)b);          \
+    x += __longlong_as_double((long long)t);                                                   \
+  }
+  RTP_WAVE_SCAN_STEPS(RTP_STEP)
+#undef RTP_STEP
+  return x;
+}
+// The value of lane 63 in every lane (a scalar register): the wave total after an inclusive scan.
+__device__ __forceinline__ int wave_last(int x) { return __builtin_amdgcn_readlane(x, 63); }
+// Wave-wide sum / maximum of non-negative-or-(-1) ints, in every lane.
+__device__ __forceinline__ int wave_sum(int x) { return wave_last(wave_incl_scan(x)); }
+__device__ __forceinline__ int wave_max_ge_m1(int x) {      // x >= -1 in every lane
+#define RTP_STEP(CTRL, MASK) x = max(x, __builtin_amdgcn_update_dpp(-1, x, CTRL, MASK, 0xf, false));
+  RTP_WAVE_SCAN_STEPS(RTP_STEP)
+#undef RTP_STEP
+  return wave_last(x);
+}
+
 }  // namespace rtp

@@ -20,8 +20,8 @@ namespace rtp {
 // tokens per workgroup: 2048 (64 KiB of index keys) for the plain pass; the pass that also builds the
 // histogram takes 4096 so that half as many workgroups zero, scan and flush a 2048-bin LDS histogram
 // (measured on batch 8 x 131072: 27.5 us against 28.4 us with 2048; the plain pass prefers 2048)
-constexpr int kIsChunkPlain = 2048, kIsChunkHist = 4096;
 constexpr int kIsThreads = RTP_IS_THREADS;
+constexpr int kIsChunkPlain = 8 * kIsThreads, kIsChunkHist = 16 * kIsThreads;
 #ifndef RTP_IS_BATCH
 #define RTP_IS_BATCH 16
 #endif

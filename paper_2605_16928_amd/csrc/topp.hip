@@ -95,20 +95,22 @@ struct Scan1Result {       // level 1: bins carry different references, the scan
 };
 
 // Every thread gets the result; all workgroups of a row compute the same numbers in the same order.
+// Threads own `per` consecutive bins in order FROM THE TOP of the score range (thread 0 the highest bins),
+// so "the mass above" is an ordinary inclusive prefix sum over lanes and waves.
 __device__ __forceinline__ Scan1Result scan_level1(const uint64_t* __restrict__ h, float p, double* sh_d /*[4]*/,
-                                                   int* sh_i /*[4]*/, double* sh_res /*[2]*/,
+                                                   int* sh_i /*[4]*/, double* sh_res /*[3]*/,
                                                    const double* __restrict__ tab /* filled by the caller */) {
   constexpr int per = kBins1 / kTpThreads;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int first = (kTpThreads - 1 - tid) * per;     // this thread's lowest bin
   uint64_t loc[per];
   int top = -1;
 #pragma unroll
   for (int i = 0; i < per; ++i) {
-    loc[i] = h[tid * per + i];
-    if (loc[i]) top = tid * per + i;
+    loc[i] = h[first + i];
+    if (loc[i]) top = first + i;
   }
-#pragma unroll
-  for (int o = 32; o > 0; o >>= 1) top = max(top, __shfl_xor(top, o));
+  top = wave_max_ge_m1(top);
   if (lane == 0) sh_i[wave] = top;
   __syncthreads();
   top = max(max(sh_i[0], sh_i[1]), max(sh_i[2], sh_i[3]));
@@ -120,27 +122,32 @@ __device__ __forceinline__ Scan1Result scan_level1(const uint64_t* __restrict__ 
   double sum = 0.0;
 #pragma unroll
   for (int i = 0; i < per; ++i) {
-    int e;
-    const double m = exp_parts((double)bin_ref(tid * per + i) - R, tab, &e);
-    md[i] = loc[i] ? (double)loc[i] * ldexp(m, e) : 0.0;
+    md[i] = 0.0;
+    if (loc[i]) {
+      int e;
+      const double m = exp_parts((double)bin_ref(first + i) - R, tab, &e);
+      md[i] = (double)loc[i] * ldexp(m, e);
+    }
     sum += md[i];
   }
-  double incl = sum;                                  // suffix sum inside the wave (lanes >= lane)
+  double incl = wave_incl_scan(sum);                  // this thread's bins and every higher bin of the wave
+  if (lane == 63) sh_d[wave] = incl;
+  // defaults (nobody crosses): the top bin, nothing above it -- left by the thread that owns that bin
+  if (top >= first && top < first + per) {
+    uint64_t lt = loc[0];
 #pragma unroll
-  for (int o = 1; o < 64; o <<= 1) {
-    const double t = __shfl_down(incl, o);
-    if (lane + o < 64) incl += t;
+    for (int i = 1; i < per; ++i) if (top - first == i) lt = loc[i];
+    sh_res[0] = (double)top; sh_res[1] = 0.0; sh_res[2] = __longlong_as_double((long long)lt);
   }
-  if (lane == 0) sh_d[wave] = incl;
-  if (tid == 0) { sh_res[0] = (double)top; sh_res[1] = 0.0; }
   __syncthreads();
-  double total = 0.0, after = 0.0;
-  for (int w = kTpThreads / 64 - 1; w >= 0; --w) {    // fixed order: identical in every workgroup
-    if (w > wave) after += sh_d[w];
+  double total = 0.0, before = 0.0;
+#pragma unroll
+  for (int w = 0; w < kTpThreads / 64; ++w) {         // fixed order: identical in every workgroup
+    if (w < wave) before += sh_d[w];
     total += sh_d[w];
   }
   const double target = (double)p * total;
-  incl += after;
+  incl += before;
   const double excl = incl - sum;
   // the crossing thread: the mass above its bins is below the target, the mass including them reaches it.
   // (if rounding left the target unreachable nobody matches and the defaults -- top bin -- stand, which
@@ -152,15 +159,23 @@ __device__ __forceinline__ Scan1Result scan_level1(const uint64_t* __restrict__ 
     for (int i = per - 1; i > 0; --i) {
       if (b == i && !(loc[i] && run + md[i] >= target)) { run += md[i]; b = i - 1; }
     }
-    sh_res[0] = (double)(tid * per + b);
+    uint64_t lb = loc[0];
+#pragma unroll
+    for (int i = 1; i < per; ++i) if (b == i) lb = loc[i];
+    sh_res[0] = (double)(first + b);
     sh_res[1] = run;
+    sh_res[2] = __longlong_as_double((long long)lb);
   }
   __syncthreads();
   const int b1 = (int)sh_res[0];
   const double above_true = sh_res[1];
+  const uint64_t hb = (uint64_t)__double_as_longlong(sh_res[2]);
   const float ref1 = bin_ref(b1);
-  const double scale = fmin(exp(R - (double)ref1), 1e250);
-  const uint64_t hb = h[b1];
+  // exp(R - ref1) >= 1 as the reciprocal of the table-based exponential of the negative argument (which
+  // may underflow to 0 here: the reciprocal is then capped)
+  int es;
+  const double ms = exp_parts((double)ref1 - R, tab, &es, -300000.0);
+  const double scale = fmin(1.0 / ldexp(ms, es), 1e250);
   double t2 = ceil((target - above_true) * scale);
   if (!(t2 >= 1.0)) t2 = 1.0;
   uint64_t tgt = (uint64_t)__double2ull_rn(fmin(t2, 1.8e19));
@@ -182,36 +197,33 @@ struct ScanResult {
   uint64_t total;      // above + sum of all bins
 };
 
-// Levels 2 and 3: integer masses with one reference.  Two block barriers; wave suffix sums by shuffle.
+// Levels 2 and 3: integer masses with one reference.  Same thread order as above (thread 0 owns the
+// highest bins); two block barriers.
 template <int NBINS>
 __device__ __forceinline__ ScanResult scan_from_top(const uint64_t* __restrict__ h, uint64_t above, uint64_t target,
                                                     uint64_t* sh_w /*[4]*/, uint64_t* sh_res /*[3]*/) {
   constexpr int per = NBINS / kTpThreads;             // consecutive bins per thread
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int first = (kTpThreads - 1 - tid) * per;     // this thread's lowest bin
   uint64_t loc[per];
   uint64_t sum = 0;
 #pragma unroll
   for (int i = 0; i < per; ++i) {
-    loc[i] = h[tid * per + i];
+    loc[i] = h[first + i];
     sum += loc[i];
   }
-  uint64_t incl = sum;                                // suffix sum inside the wave (lanes >= lane)
-#pragma unroll
-  for (int o = 1; o < 64; o <<= 1) {
-    const uint64_t t = __shfl_down(incl, o);
-    if (lane + o < 64) incl += t;
-  }
-  if (lane == 0) sh_w[wave] = incl;
-  if (tid == 0) { sh_res[0] = 0; sh_res[1] = above; sh_res[2] = loc[0]; }
+  uint64_t incl = wave_incl_scan(sum);                // this thread's bins and every higher bin of the wave
+  if (lane == 63) sh_w[wave] = incl;
+  if (first == 0) { sh_res[0] = 0; sh_res[1] = above; sh_res[2] = loc[0]; }   // defaults: bin 0
   __syncthreads();
-  uint64_t after = 0, total = above;
+  uint64_t before = 0, total = above;
 #pragma unroll
   for (int w = 0; w < kTpThreads / 64; ++w) {
-    if (w > wave) after += sh_w[w];
+    if (w < wave) before += sh_w[w];
     total += sh_w[w];
   }
-  incl += after;                                      // bins of threads >= tid
-  const uint64_t excl = incl - sum;                   // bins of threads > tid
+  incl += before;                                     // bins of threads <= tid
+  const uint64_t excl = incl - sum;                   // bins of threads < tid: everything above this thread's
   if (above + excl < target && above + incl >= target) {
     uint64_t run = above + excl;
     int b = per - 1;
@@ -222,7 +234,7 @@ __device__ __forceinline__ ScanResult scan_from_top(const uint64_t* __restrict__
     uint64_t lb = loc[0];
 #pragma unroll
     for (int i = 1; i < per; ++i) if (b == i) lb = loc[i];
-    sh_res[0] = (uint64_t)(tid * per + b);
+    sh_res[0] = (uint64_t)(first + b);
     sh_res[1] = run;
     sh_res[2] = lb;
   }
@@ -255,8 +267,7 @@ __global__ __launch_bounds__(kTpThreads) void topp_zero_kernel(uint64_t* hist, i
 
 // Sum of `cnt` over the workgroup, stored by thread 0 (two barriers).
 __device__ __forceinline__ void block_count_to(int cnt, int32_t* dst, int* sh_i /*[waves]*/) {
-#pragma unroll
-  for (int o = 32; o > 0; o >>= 1) cnt += __shfl_xor(cnt, o);
+  cnt = wave_sum(cnt);
   __syncthreads();
   if ((threadIdx.x & 63) == 0) sh_i[threadIdx.x >> 6] = cnt;
   __syncthreads();
@@ -286,7 +297,7 @@ __global__ __launch_bounds__(kTpThreads) void topp_level_kernel(const TopPArgs a
   __shared__ uint64_t sh_part[kTpThreads / 64];
   __shared__ uint64_t sh_res[3];
   __shared__ double sh_d[kTpThreads / 64];
-  __shared__ double sh_dres[2];
+  __shared__ double sh_dres[3];
   __shared__ int sh_i[kTpThreads / 64];
   __shared__ double tab[256];
   fill_exp_table(tab);
@@ -444,15 +455,10 @@ __global__ __launch_bounds__(kTpThreads) void topp_level_kernel(const TopPArgs a
     }
     const int lane = tid & 63;
     const int cnt = __popc(member);
-    int incl = cnt;
-#pragma unroll
-    for (int o = 1; o < 64; o <<= 1) {
-      const int t = __shfl_up(incl, o);
-      if (lane >= o) incl += t;
-    }
+    const int incl = wave_incl_scan(cnt);
     int base = 0;
     if (lane == 63 && incl > 0) base = atomicAdd(&sh_n, incl);
-    base = __shfl(base, 63);
+    base = wave_last(base);
     int pos = base + incl - cnt;
 #pragma unroll
     for (int u = 0; u < kTpVec; ++u) {
@@ -494,8 +500,9 @@ __device__ __forceinline__ uint32_t keep_mask(const float4 (&v)[kTpVec], int n_h
 // Writes the kept positions of one chunk in ascending order starting at out[before].
 // Element order inside a chunk is (load round u, thread, k); per-round counts (0..4) travel as
 // 16-bit fields of two 64-bit words through one wave scan.
-__device__ __forceinline__ void write_ranked(uint32_t keep, int before, int32_t* out, int64_t n0,
-                                             uint64_t (*sh_tot)[2] /*[waves][2]*/) {
+// `local` (optional, LDS) receives the same positions starting at local[0].  Returns the chunk's kept count.
+__device__ __forceinline__ int write_ranked(uint32_t keep, int before, int32_t* out, int64_t n0,
+                                            uint64_t (*sh_tot)[2] /*[waves][2]*/, int32_t* local = nullptr) {
   const int tid = threadIdx.x;
   uint64_t lo = 0, hi = 0;
 #pragma unroll
@@ -503,12 +510,7 @@ __device__ __forceinline__ void write_ranked(uint32_t keep, int before, int32_t*
     lo |= (uint64_t)__popc((keep >> (u * 4)) & 0xFu) << (16 * u);
     hi |= (uint64_t)__popc((keep >> (16 + u * 4)) & 0xFu) << (16 * u);
   }
-  uint64_t ilo = lo, ihi = hi;       // inclusive wave scans
-#pragma unroll
-  for (int o = 1; o < 64; o <<= 1) {
-    const uint64_t tl = __shfl_up(ilo, o), th = __shfl_up(ihi, o);
-    if ((tid & 63) >= o) { ilo += tl; ihi += th; }
-  }
+  const uint64_t ilo = wave_incl_scan(lo), ihi = wave_incl_scan(hi);
   if ((tid & 63) == 63) { sh_tot[tid >> 6][0] = ilo; sh_tot[tid >> 6][1] = ihi; }
   __syncthreads();
   int round_base = before;
@@ -527,10 +529,16 @@ __device__ __forceinline__ void write_ranked(uint32_t keep, int before, int32_t*
     int pos = round_base + wave_before + incl - mine;
 #pragma unroll
     for (int k = 0; k < 4; ++k) {
-      if (keep & (1u << (u * 4 + k))) out[pos++] = (int32_t)(n0 + (u * kTpThreads + tid) * 4 + k);
+      if (keep & (1u << (u * 4 + k))) {
+        const int32_t where = (int32_t)(n0 + (u * kTpThreads + tid) * 4 + k);
+        out[pos] = where;
+        if (local) local[pos - before] = where;
+        ++pos;
+      }
     }
     round_base += round_total;
   }
+  return round_base - before;
 }
 
 // ---- launch 4: exact threshold, chunk offsets, ordered compaction -----------------------------------
@@ -538,8 +546,38 @@ __device__ __forceinline__ void write_ranked(uint32_t keep, int before, int32_t*
 // chunk's offset: the certainly-kept counts of the chunks before it (level-3 launch) plus the kept
 // members of the row's short list that lie before it.  Positions inside a chunk come from block-wide
 // prefix sums, so the row's kept positions are ascending.
-__global__ __launch_bounds__(kTpThreads) void topp_write_kernel(const TopPArgs a) {
+//
+// ATTEND: the same launch goes on to the sparse-attention step of Sec. 3.2 for its chunk -- the kept
+// positions stay in LDS, their K/V rows are gathered and a partial softmax state (m, l, acc[128]) is left
+// per (row, chunk) for select_attend_combine_kernel.  One launch and one pass over the index list less than
+// selecting and attending separately; rows are the retrieval heads of a decode batch, r = b * n_ret + j.
+struct GatherArgs {
+  const uint16_t* q;
+  const uint16_t* K;
+  const uint16_t* V;
+  int64_t row_stride, head_stride;
+  const int64_t* seq_start;
+  int32_t n_q_heads, n_kv_heads, n_ret;
+  float scale_log2;        // softmax scale * log2(e)
+  float* part;             // [R, n_chunks, kSaPart]
+  uint16_t* out;
+  float* lse;
+  int32_t ret_heads[64];
+};
+constexpr int kSaPart = kHeadDim + 4;      // m, l, 2 pad, acc[128]  (floats)
+constexpr int kSaInFlight = 8;             // K/V rows in flight per 16-lane group (two register sets taking turns,
+                                           // or more rows, measured no faster: the gather is bandwidth-bound)
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+__device__ __forceinline__ void unpack_bf16x8(const u32x4 v, float (&f)[8]) {
+  f[0] = bf16_lo(v.x); f[1] = bf16_hi(v.x); f[2] = bf16_lo(v.y); f[3] = bf16_hi(v.y);
+  f[4] = bf16_lo(v.z); f[5] = bf16_hi(v.z); f[6] = bf16_lo(v.w); f[7] = bf16_hi(v.w);
+}
+
+template <bool ATTEND>
+__global__ __launch_bounds__(kTpThreads) void topp_write_kernel(const TopPArgs a, const GatherArgs ga) {
   const int r = blockIdx.y, c = blockIdx.x, tid = threadIdx.x;
+  __shared__ int32_t sh_list[ATTEND ? kTpChunk : 1];
   if (a.rezero) {                  // levels 1 and 2 were last read by the level-2 / level-3 launches
     uint64_t* h = a.hist + (int64_t)r * kBinsTotal;
     for (int i = c * kTpThreads + tid; i < kBins1 + kBins2; i += a.n_chunks * kTpThreads) h[i] = 0;
@@ -567,14 +605,16 @@ __global__ __launch_bounds__(kTpThreads) void topp_write_kernel(const TopPArgs a
   // level 2 always leaves st[0]; level 3 leaves st[1] (a copy of st[0] for rows that carry no search)
   const RowState prev = a.state[(int64_t)r * 3 + 1];
 
-  if (prev.flags < 0 || prev.flags == 2) {
+  int kept_here = 0;
+  const bool empty_row = prev.flags < 0 || prev.flags == 2;      // the same in every workgroup of the row
+  if (empty_row) {
     if (c == 0 && tid == 0) {
       a.sel_count[r] = prev.flags < 0 ? -1 : 0;
       if (a.tau) a.tau[r] = prev.flags < 0 ? __builtin_nanf("") : ninf;
       if (a.mass) a.mass[r] = 0.f;
     }
-    return;
-  }
+    if (!ATTEND) return;
+  } else {
   uint32_t tkey = 0;      // keep keys >= tkey
   if (prev.flags == 0) {
     const ScanResult sr = scan_from_top<kBins3>(hrow + kBins1 + kBins2, prev.above, prev.target, sh_part, sh_res);
@@ -617,11 +657,8 @@ __global__ __launch_bounds__(kTpThreads) void topp_write_kernel(const TopPArgs a
       if (i < n0) before += k1;
     }
   }
-#pragma unroll
-  for (int o = 32; o > 0; o >>= 1) {
-    before += __shfl_xor(before, o);
-    total += __shfl_xor(total, o);
-  }
+  before = wave_sum(before);
+  total = wave_sum(total);
   if ((tid & 63) == 0) { sh_red[tid >> 6][0] = before; sh_red[tid >> 6][1] = total; }
   __syncthreads();
   before = 0;
@@ -631,7 +668,176 @@ __global__ __launch_bounds__(kTpThreads) void topp_write_kernel(const TopPArgs a
   if (c == 0 && tid == 0) a.sel_count[r] = total;
 
   const uint32_t keep = keep_mask(v, n_here, tid, prev.flags == 1, tkey);
-  write_ranked(keep, before, a.sel_idx + (int64_t)r * a.sel_stride, n0, sh_tot);
+  kept_here = write_ranked(keep, before, a.sel_idx + (int64_t)r * a.sel_stride, n0, sh_tot, ATTEND ? sh_list : nullptr);
+  }
+  if (!ATTEND) return;
+
+  // ---- attention over this chunk's kept positions: 16 groups of 16 lanes, one K/V row (256 bytes) per
+  // group and load, kSaInFlight rows per group in flight; a lane owns 8 of the 128 dims ----
+  __shared__ float sh_m[kTpThreads / 64], sh_l[kTpThreads / 64];
+  __shared__ float sh_acc[kTpThreads / 64][kHeadDim];
+  __syncthreads();                           // the list is complete
+  const int lane = tid & 63, wave = tid >> 6;
+  const int grp = wave * 4 + (lane >> 4), piece = lane & 15;
+  const int b = r / ga.n_ret;
+  const int h = ga.ret_heads[r - b * ga.n_ret];
+  const int kvh = h / (ga.n_q_heads / ga.n_kv_heads);
+  const uint16_t* Kb = ga.K + (int64_t)kvh * ga.head_stride + ga.seq_start[b] * ga.row_stride + piece * 8;
+  const uint16_t* Vb = ga.V + (int64_t)kvh * ga.head_stride + ga.seq_start[b] * ga.row_stride + piece * 8;
+  float qv[8];
+  unpack_bf16x8(*reinterpret_cast<const u32x4*>(ga.q + ((int64_t)b * ga.n_q_heads + h) * kHeadDim + piece * 8), qv);
+#pragma unroll
+  for (int d = 0; d < 8; ++d) qv[d] *= ga.scale_log2;
+  float m = ninf, l = 0.f, acc[8];
+#pragma unroll
+  for (int d = 0; d < 8; ++d) acc[d] = 0.f;
+  for (int base = 0; base < kept_here; base += 16 * kSaInFlight) {
+    u32x4 kr[kSaInFlight], vr[kSaInFlight];
+    bool ok[kSaInFlight];
+#pragma unroll
+    for (int u = 0; u < kSaInFlight; ++u) {
+      const int i = base + u * 16 + grp;
+      ok[u] = i < kept_here;
+      if (ok[u]) {
+        const int64_t pos = sh_list[i];
+        kr[u] = *reinterpret_cast<const u32x4*>(Kb + pos * ga.row_stride);
+        vr[u] = *reinterpret_cast<const u32x4*>(Vb + pos * ga.row_stride);
+      } else {
+        kr[u] = (u32x4){0u, 0u, 0u, 0u};
+        vr[u] = (u32x4){0u, 0u, 0u, 0u};
+      }
+    }
+    float sc[kSaInFlight];
+    float mx = ninf;
+#pragma unroll
+    for (int u = 0; u < kSaInFlight; ++u) {
+      float kf[8];
+      unpack_bf16x8(kr[u], kf);
+      float d = kf[0] * qv[0];
+#pragma unroll
+      for (int e = 1; e < 8; ++e) d = fmaf(kf[e], qv[e], d);
+      d = row16_sum(d);
+      sc[u] = ok[u] ? d : ninf;
+      mx = fmaxf(mx, sc[u]);
+    }
+    const float mn = fmaxf(m, mx);
+    if (mn != ninf) {
+      const float corr = fast_exp2(m - mn);
+      l *= corr;
+#pragma unroll
+      for (int d = 0; d < 8; ++d) acc[d] *= corr;
+      m = mn;
+    }
+#pragma unroll
+    for (int u = 0; u < kSaInFlight; ++u) {
+      float vf[8];
+      unpack_bf16x8(vr[u], vf);
+      const float pw = (sc[u] == ninf) ? 0.f : fast_exp2(sc[u] - m);
+      l += pw;
+#pragma unroll
+      for (int d = 0; d < 8; ++d) acc[d] = fmaf(pw, vf[d], acc[d]);
+    }
+  }
+  // the four groups of a wave in registers, the four waves through LDS
+#pragma unroll
+  for (int o = 16; o <= 32; o <<= 1) {
+    const float mo = __shfl_xor(m, o), lo = __shfl_xor(l, o);
+    float ao[8];
+#pragma unroll
+    for (int d = 0; d < 8; ++d) ao[d] = __shfl_xor(acc[d], o);
+    const float M = fmaxf(m, mo);
+    if (M != ninf) {
+      const float ca = fast_exp2(m - M), cb = fast_exp2(mo - M);
+      l = l * ca + lo * cb;
+#pragma unroll
+      for (int d = 0; d < 8; ++d) acc[d] = acc[d] * ca + ao[d] * cb;
+      m = M;
+    }
+  }
+  if (lane < 16) {
+    if (piece == 0) { sh_m[wave] = m; sh_l[wave] = l; }
+#pragma unroll
+    for (int d = 0; d < 8; ++d) sh_acc[wave][piece * 8 + d] = acc[d];
+  }
+  __syncthreads();
+  if (tid < kHeadDim) {
+    float M = sh_m[0];
+#pragma unroll
+    for (int w = 1; w < kTpThreads / 64; ++w) M = fmaxf(M, sh_m[w]);
+    float L = 0.f, A = 0.f;
+    if (M != ninf) {
+#pragma unroll
+      for (int w = 0; w < kTpThreads / 64; ++w) {
+        const float cw = fast_exp2(sh_m[w] - M);
+        L += sh_l[w] * cw;
+        A += sh_acc[w][tid] * cw;
+      }
+    }
+    float* pout = ga.part + ((int64_t)r * a.n_chunks + c) * kSaPart;
+    pout[4 + tid] = A;
+    if (tid == 0) { pout[0] = M; pout[1] = L; }
+  }
+}
+
+// Merges the (row, chunk) partials of one row: 8 slices of 32 lanes walk the chunks slice, slice + 8, ...
+// (each lane owns 4 of the 128 output dims); LDS merges the slices.  Rows without a kept token give zeros.
+__global__ __launch_bounds__(kTpThreads) void select_attend_combine_kernel(const TopPArgs a, const GatherArgs ga) {
+  __shared__ float sh_m[8], sh_l[8];
+  __shared__ float sh_acc[8][kHeadDim];
+  const int r = blockIdx.x, tid = threadIdx.x;
+  const float ninf = -__builtin_huge_valf();
+  const int n = a.row_len[r];
+  const int n_row_chunks = n > 0 ? (n + kTpChunk - 1) / kTpChunk : 0;
+  const int d4 = tid & 31, slice = tid >> 5;
+  float M = ninf, L = 0.f;
+  float4 A = make_float4(0.f, 0.f, 0.f, 0.f);
+  // four partials in flight per slice: a long row has hundreds of chunks and each load is a round trip
+  for (int i0 = slice; i0 < n_row_chunks; i0 += 8 * 4) {
+    float pm[4], pl[4];
+    float4 pv[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const int i = i0 + u * 8;
+      pm[u] = ninf; pl[u] = 0.f; pv[u] = make_float4(0.f, 0.f, 0.f, 0.f);
+      if (i < n_row_chunks) {
+        const float* p = ga.part + ((int64_t)r * a.n_chunks + i) * kSaPart;
+        pm[u] = p[0]; pl[u] = p[1];
+        pv[u] = *reinterpret_cast<const float4*>(p + 4 + d4 * 4);
+      }
+    }
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const float Mn = fmaxf(M, pm[u]);
+      if (Mn != ninf) {
+        const float c0 = fast_exp2(M - Mn), c1 = fast_exp2(pm[u] - Mn);
+        L = L * c0 + pl[u] * c1;
+        A.x = A.x * c0 + pv[u].x * c1; A.y = A.y * c0 + pv[u].y * c1;
+        A.z = A.z * c0 + pv[u].z * c1; A.w = A.w * c0 + pv[u].w * c1;
+        M = Mn;
+      }
+    }
+  }
+  if (d4 == 0) { sh_m[slice] = M; sh_l[slice] = L; }
+  *reinterpret_cast<float4*>(&sh_acc[slice][d4 * 4]) = A;
+  __syncthreads();
+  if (tid < kHeadDim) {
+    float Mt = sh_m[0];
+#pragma unroll
+    for (int s = 1; s < 8; ++s) Mt = fmaxf(Mt, sh_m[s]);
+    float Lt = 0.f, At = 0.f;
+    if (Mt != ninf) {
+#pragma unroll
+      for (int s = 0; s < 8; ++s) {
+        const float cw = fast_exp2(sh_m[s] - Mt);
+        Lt += sh_l[s] * cw;
+        At += sh_acc[s][tid] * cw;
+      }
+    }
+    const int b = r / ga.n_ret;
+    const int64_t o = (int64_t)b * ga.n_q_heads + ga.ret_heads[r - b * ga.n_ret];
+    ga.out[o * kHeadDim + tid] = f32_to_bf16_rne(Lt > 0.f ? At / Lt : 0.f);
+    if (ga.lse && tid == 0) ga.lse[o] = Lt > 0.f ? (Mt + log2f(Lt)) * 0.6931471805599453f : ninf;
+  }
 }
 
 }  // namespace rtp
@@ -659,7 +865,7 @@ static int32_t run_select(const char* who, const float* scores, int64_t score_st
                           const float* p, const int32_t* kcount, int32_t R, int64_t max_len,
                           int32_t* sel_idx, int64_t sel_stride, int32_t* sel_count,
                           float* tau, float* mass, int32_t level1_ready,
-                          void* ws, size_t ws_bytes, void* stream) {
+                          void* ws, size_t ws_bytes, void* stream, const GatherArgs* attend = nullptr) {
   if (!scores || !row_len || (!p && !kcount) || !sel_idx || !sel_count)
     return fail(RTP_ERR_INVALID_ARG, "%s: NULL tensor pointer", who);
   if (R <= 0 || R > 65535) return fail(RTP_ERR_INVALID_ARG, "%s: R must be in [1, 65535]", who);
@@ -704,7 +910,12 @@ static int32_t run_select(const char* who, const float* scores, int64_t score_st
   }
   hipLaunchKernelGGL(topp_level_kernel<2>, grid, block, 0, s, a);
   hipLaunchKernelGGL(topp_level_kernel<3>, grid, block, 0, s, a);
-  hipLaunchKernelGGL(topp_write_kernel, grid, block, 0, s, a);
+  if (attend) {
+    hipLaunchKernelGGL(topp_write_kernel<true>, grid, block, 0, s, a, *attend);
+    hipLaunchKernelGGL(select_attend_combine_kernel, dim3((unsigned)R), block, 0, s, a, *attend);
+  } else {
+    hipLaunchKernelGGL(topp_write_kernel<false>, grid, block, 0, s, a, GatherArgs{});
+  }
   return check_launch(who);
 }
 
@@ -725,4 +936,54 @@ extern "C" int32_t rtp_topk_select(const float* scores, int64_t score_stride, co
   if (!k) return fail(RTP_ERR_INVALID_ARG, "rtp_topk_select: NULL tensor pointer");
   return run_select("rtp_topk_select", scores, score_stride, row_len, nullptr, k, R, max_len, sel_idx, sel_stride,
                     sel_count, tau, nullptr, 0, ws, ws_bytes, stream);
+}
+
+extern "C" size_t rtp_select_attend_decode_workspace_bytes(const rtp_layer_desc* layer, int32_t B, int64_t max_ctx) {
+  if (!layer || B <= 0 || max_ctx <= 0 || layer->n_ret <= 0) return 256;
+  const int64_t n_chunks = (max_ctx + kTpChunk - 1) / kTpChunk;
+  return align_up((size_t)B * layer->n_ret * n_chunks * kSaPart * sizeof(float), 256);
+}
+
+extern "C" int32_t rtp_select_attend_decode(const rtp_layer_desc* layer, const float* scores, int64_t score_stride,
+                                            const int32_t* row_len, const float* p, int32_t B, int64_t max_ctx,
+                                            const void* q, const void* K, const void* V, int64_t kv_row_stride,
+                                            int64_t kv_head_stride, const int64_t* seq_start,
+                                            int32_t* sel_idx, int64_t sel_stride, int32_t* sel_count,
+                                            float* tau, float* mass, int32_t level1_ready, void* out, float* lse,
+                                            void* topp_ws, size_t topp_ws_bytes, void* attn_ws, size_t attn_ws_bytes,
+                                            void* stream) {
+  const char* who = "rtp_select_attend_decode";
+  HeadTable ht;
+  int32_t rc = fill_head_table(layer, &ht, who);
+  if (rc != RTP_OK) return rc;
+  if (!p || !q || !K || !V || !out || !seq_start) return fail(RTP_ERR_INVALID_ARG, "%s: NULL tensor pointer", who);
+  if (kv_row_stride < kHeadDim || (kv_row_stride & 7) || (kv_head_stride & 7) || kv_head_stride < 0)
+    return fail(RTP_ERR_INVALID_ARG, "%s: kv_row_stride must be >= 128, strides multiples of 8", who);
+  if (((uintptr_t)q & 15) || ((uintptr_t)K & 15) || ((uintptr_t)V & 15) || ((uintptr_t)out & 15))
+    return fail(RTP_ERR_INVALID_ARG, "%s: q, K, V and out must be 16-byte aligned", who);
+  if (B <= 0) return fail(RTP_ERR_INVALID_ARG, "%s: B must be positive", who);
+  if (layer->n_ret == 0) { clear_error(); return RTP_OK; }
+  const int64_t R = (int64_t)B * layer->n_ret;
+  if (R > 65535) return fail(RTP_ERR_INVALID_ARG, "%s: B * n_ret is limited to 65535", who);
+  const size_t need = rtp_select_attend_decode_workspace_bytes(layer, B, max_ctx);
+  if (!attn_ws || ((uintptr_t)attn_ws & 255) || attn_ws_bytes < need)
+    return fail(RTP_ERR_WORKSPACE, "%s: attention workspace of %zu bytes (256-byte aligned) required, got %zu", who, need,
+                attn_ws_bytes);
+  GatherArgs ga;
+  ga.q = (const uint16_t*)q;
+  ga.K = (const uint16_t*)K;
+  ga.V = (const uint16_t*)V;
+  ga.row_stride = kv_row_stride;
+  ga.head_stride = kv_head_stride;
+  ga.seq_start = seq_start;
+  ga.n_q_heads = layer->n_q_heads;
+  ga.n_kv_heads = layer->n_kv_heads;
+  ga.n_ret = layer->n_ret;
+  ga.scale_log2 = softmax_scale_of(layer) * 1.4426950408889634f;
+  ga.part = (float*)attn_ws;
+  ga.out = (uint16_t*)out;
+  ga.lse = lse;
+  for (int j = 0; j < 64; ++j) ga.ret_heads[j] = ht.ret_heads[j];
+  return run_select(who, scores, score_stride, row_len, p, nullptr, (int32_t)R, max_ctx, sel_idx, sel_stride, sel_count,
+                    tau, mass, level1_ready, topp_ws, topp_ws_bytes, stream, &ga);
 }

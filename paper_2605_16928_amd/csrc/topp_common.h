@@ -46,8 +46,8 @@ __device__ __forceinline__ void fill_exp_table(double* tab) {
 // exp(x) for x <= 0 as m * 2^e with m in [1, 2): x * 256 / ln 2 = k + f, k integer, f in [0, 1);
 // exp(x) = 2^(k >> 8) * T[k & 255] * P(t), P a degree-4 polynomial in t = f * ln 2 / 256 < 2.8e-3
 // (~1e-15 relative).  Arguments below about -80 return e = -119 or so: far under any resolution used.
-__device__ __forceinline__ double exp_parts(double x, const double* __restrict__ tab, int* e) {
-  const double y = fmax(fmin(x, 0.0) * 369.3299304675746, -30000.0);   // 256 / ln 2
+__device__ __forceinline__ double exp_parts(double x, const double* __restrict__ tab, int* e, double y_min = -30000.0) {
+  const double y = fmax(fmin(x, 0.0) * 369.3299304675746, y_min);      // 256 / ln 2
   const double k = floor(y);
   const double t = (y - k) * 0.0027076061740622863;                    // ln 2 / 256
   const int ki = (int)k;

@@ -64,6 +64,7 @@ class DecodeRun:
         rtp.rtp_topp_workspace_init(self.ws_topp)
         self._level1_pending = False
         self.ws_sparse = ws_alloc(rtp.rtp_sparse_attn_decode_workspace_bytes(self.desc, self.B, self.max_ctx))
+        self.ws_fused = ws_alloc(rtp.rtp_select_attend_decode_workspace_bytes(self.desc, self.B, self.max_ctx))
         self.ws_local = ws_alloc(rtp.rtp_local_attn_workspace_bytes(self.desc, self.B, 1, self.max_ctx))
         self.ws_dense = ws_alloc(rtp.rtp_dense_attn_workspace_bytes(self.desc, self.B, 1, self.max_ctx))
         self.T_tot = w.T_tot
@@ -127,6 +128,18 @@ class DecodeRun:
                                    self.max_ctx if max_sel is None else max_sel, self.B, self.out, self.lse,
                                    self.ws_sparse)
 
+    def select_attend(self):
+        """Top-p selection and the retrieval heads' attention as one call (same outputs as topp() followed
+        by sparse_attn())."""
+        w = self.w
+        ready = 1 if self._level1_pending else 0
+        rtp.rtp_select_attend_decode(self.desc, self.scores, self.stride, self.row_len, w.p_rows, self.B, self.max_ctx,
+                                     w.q, self.Kp, self.Vp, self.kv_rs, self.kv_hs, self.seq_start,
+                                     self.sel_idx, self.stride, self.sel_count, self.tau, self.mass,
+                                     self.out, self.lse, self.ws_topp, self.ws_fused, level1_ready=ready)
+        if ready:
+            self._level1_pending = False
+
     def local_attn(self):
         w = self.w
         rtp.rtp_local_attn(self.desc, w.q, self.Kp, self.Vp, self.kv_rs, self.kv_hs, self.seq_start, self.ctx_len, None,
@@ -138,13 +151,20 @@ class DecodeRun:
                            self.B, 1, self.max_ctx, self.out if out is None else out,
                            self.lse if lse is None else lse, self.ws_dense)
 
-    def step(self):
+    def select_then_attend(self, fused: bool):
+        if fused:
+            self.select_attend()
+        else:
+            self.topp()
+            self.sparse_attn()
+
+    def step(self, fused: bool = True):
+        """One decode step; fused: selection and retrieval-head attention as one call."""
         self.index_score()
-        self.topp()
-        self.sparse_attn()
+        self.select_then_attend(fused)
         self.local_attn()
 
-    def step_two_streams(self, side: "torch.cuda.Stream"):
+    def step_two_streams(self, side: "torch.cuda.Stream", fused: bool = True):
         """The same step with the local heads on a second stream: they do not depend on the
         indexer / top-p chain and write disjoint output rows."""
         main = torch.cuda.current_stream()
@@ -157,8 +177,7 @@ class DecodeRun:
         with torch.cuda.stream(side):
             self.local_attn()
             join.record(side)
-        self.topp()
-        self.sparse_attn()
+        self.select_then_attend(fused)
         main.wait_event(join)
 
     # ---- results as numpy -----------------------------------------------------------------

@@ -28,6 +28,7 @@ EXPORTS = [
     "rtp_dense_attn_workspace_bytes", "rtp_dense_attn",
     "rtp_index_project", "rtp_topk_select",
     "rtp_block_topp_workspace_bytes", "rtp_block_topp_select", "rtp_sparsity_stats",
+    "rtp_select_attend_decode_workspace_bytes", "rtp_select_attend_decode",
 ]
 RTP_SIDE_QUERY, RTP_SIDE_KEY = 0, 1
 
@@ -106,6 +107,11 @@ def lib() -> C.CDLL:
     L.rtp_block_topp_select.restype = i32
     L.rtp_block_topp_select.argtypes = [vp, i64, vp, vp, i32, i64, i32, C.c_float, C.c_float, vp, i64, vp, vp, vp,
                                         vp, i64, vp, sz, vp]
+    L.rtp_select_attend_decode_workspace_bytes.restype = sz
+    L.rtp_select_attend_decode_workspace_bytes.argtypes = [dp, i32, i64]
+    L.rtp_select_attend_decode.restype = i32
+    L.rtp_select_attend_decode.argtypes = [dp, vp, i64, vp, vp, i32, i64, vp, vp, vp, i64, i64, vp, vp, i64, vp, vp, vp,
+                                           i32, vp, vp, vp, sz, vp, sz, vp]
     L.rtp_sparsity_stats.restype = i32
     L.rtp_sparsity_stats.argtypes = [dp, vp, vp, i64, vp, vp, vp, i32, vp, vp, vp]
     _lib = L
@@ -177,6 +183,20 @@ def rtp_sparse_attn_decode(layer, q, K, V, kv_row_stride, kv_head_stride, seq_st
     _check(lib().rtp_sparse_attn_decode(C.byref(layer), _ptr(q), _ptr(K), _ptr(V), kv_row_stride, kv_head_stride,
                                         _ptr(seq_start), _ptr(sel_idx), sel_stride, _ptr(sel_count), max_sel, B,
                                         _ptr(out), _ptr(lse), _ptr(ws), _nbytes(ws), _stream(stream)))
+
+
+def rtp_select_attend_decode_workspace_bytes(layer, B, max_ctx) -> int:
+    return lib().rtp_select_attend_decode_workspace_bytes(C.byref(layer), B, max_ctx)
+
+
+def rtp_select_attend_decode(layer, scores, score_stride, row_len, p, B, max_ctx, q, K, V, kv_row_stride,
+                             kv_head_stride, seq_start, sel_idx, sel_stride, sel_count, tau, mass, out, lse,
+                             topp_ws, attn_ws, level1_ready=0, stream=None):
+    _check(lib().rtp_select_attend_decode(C.byref(layer), _ptr(scores), score_stride, _ptr(row_len), _ptr(p), B,
+                                          max_ctx, _ptr(q), _ptr(K), _ptr(V), kv_row_stride, kv_head_stride,
+                                          _ptr(seq_start), _ptr(sel_idx), sel_stride, _ptr(sel_count), _ptr(tau),
+                                          _ptr(mass), level1_ready, _ptr(out), _ptr(lse), _ptr(topp_ws),
+                                          _nbytes(topp_ws), _ptr(attn_ws), _nbytes(attn_ws), _stream(stream)))
 
 
 def rtp_sparse_attn_prefill_workspace_bytes(layer, T, chunk_start) -> int:

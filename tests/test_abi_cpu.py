@@ -188,6 +188,23 @@ def test_widened_entry_points_argument_checks():
     assert st(ls=A) == rtp.RTP_ERR_INVALID_ARG             # one log-sum-exp array without the other
     assert st(B=0) == rtp.RTP_ERR_INVALID_ARG
     assert st(out=None) == rtp.RTP_ERR_INVALID_ARG
+    # selection + attention in one call: both workspaces and both argument groups are checked
+    needt = rtp.rtp_topp_workspace_bytes(2 * 2, 1000)
+    needa = rtp.rtp_select_attend_decode_workspace_bytes(L, 2, 1000)
+    assert needa > 0 and needa % 256 == 0
+    assert rtp.rtp_select_attend_decode_workspace_bytes(L, 2, 100000) > needa
+    fa = lambda scores=A, p=A, q=A, rs=128, B=2, tws=A, twsb=needt, aws=A, awsb=needa: lib.rtp_select_attend_decode(
+        C.byref(L), vp(scores), 1000, vp(A), vp(p), B, 1000, vp(q), vp(A), vp(A), rs, 128 * 1000, vp(A),
+        vp(A), 1000, vp(A), None, None, 0, vp(A), None, vp(tws), twsb, vp(aws), awsb, None)
+    assert fa(scores=None) == rtp.RTP_ERR_INVALID_ARG
+    assert fa(p=None) == rtp.RTP_ERR_INVALID_ARG
+    assert fa(q=None) == rtp.RTP_ERR_INVALID_ARG
+    assert fa(q=A + 8) == rtp.RTP_ERR_INVALID_ARG
+    assert fa(rs=100) == rtp.RTP_ERR_INVALID_ARG
+    assert fa(B=0) == rtp.RTP_ERR_INVALID_ARG
+    assert fa(aws=None) == rtp.RTP_ERR_WORKSPACE
+    assert fa(awsb=needa - 1) == rtp.RTP_ERR_WORKSPACE
+    assert fa(twsb=needt - 1) == rtp.RTP_ERR_WORKSPACE
 
 
 def test_missing_library_is_an_error_not_a_fallback(monkeypatch):

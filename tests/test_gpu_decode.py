@@ -258,3 +258,96 @@ def test_level1_in_score_pass_gives_the_same_selection():
         assert int(res[True][2].min()) > 0
         for a, b in zip(res[False], res[True]):
             assert torch.equal(a, b, ) if a.dtype != torch.float32 else torch.equal(a.nan_to_num(), b.nan_to_num())
+
+
+def _attend_reference(w, oi, sets):
+    """The oracle's attention of every retrieval row over the given sets: {(b, h): (out, lse)}."""
+    L = w.layer
+    sc = 1.0 / np.sqrt(128.0)
+    ref = {}
+    for b in range(w.B):
+        t0, n = w.seq_start[b], w.ctx_len[b]
+        for j, h in enumerate(L.ret_heads):
+            kvh = h // (L.n_q_heads // L.n_kv_heads)
+            if len(sets[b * L.n_ret + j]) == 0:
+                continue
+            ref[(b, h)] = orc.attend(oi["q_bits"][b, h], oi["K_bits"][kvh, t0:t0 + n], oi["V_bits"][kvh, t0:t0 + n],
+                                     sets[b * L.n_ret + j], sc)
+    return ref
+
+
+@pytest.mark.parametrize("name", ["small", "small_proj", "g1", "g2", "c2_small", "c5_small"])
+@pytest.mark.parametrize("fuse", [False, True])
+def test_select_attend_in_one_call_matches_oracle_and_the_two_calls(name, fuse):
+    """rtp_select_attend_decode: the selection must be the oracle's top-p set of the same scores, the
+    output the oracle's attention over that set, and every selection output bit-identical to
+    rtp_topp_select's; twice in a row, the workspaces reused as the call left them."""
+    print(f"[case] select+attend {name} level1-in-score-pass={fuse}", flush=True)
+    w = _cases()[name]()
+    L = w.layer
+    oi = oracle_inputs(w)
+    two = DecodeRun(w, fuse_level1=fuse)
+    two.index_score()
+    two.topp()
+    two.sparse_attn()
+    torch.cuda.synchronize()
+    run = DecodeRun(w, fuse_level1=fuse)
+    for rep in range(2):
+        run.sel_idx.fill_(-1)
+        run.sel_count.fill_(-9)
+        run.out.zero_()
+        run.lse.zero_()
+        run.index_score()
+        run.select_attend()
+        sets, cnt = run.sel_sets()
+        assert torch.equal(run.sel_count, two.sel_count)
+        for r in range(run.R):
+            assert torch.equal(run.sel_idx[r, :cnt[r]], two.sel_idx[r, :cnt[r]])
+        assert torch.equal(run.tau, two.tau) and torch.equal(run.mass, two.mass)
+        s_gpu = run.scores.cpu().numpy()
+        for r in range(run.R):
+            n = w.ctx_len[r // L.n_ret]
+            s64 = s_gpu[r, :n].astype(np.float64)
+            p = float(w.p_rows[r])
+            check_selection(sets[r], s64, orc.topp_select(s64, p), p, f"{name} row {r}")
+        out, lse = run.out_f64(), run.lse.cpu().numpy()
+        ref = _attend_reference(w, oi, sets)
+        for (b, h), (o, l) in ref.items():
+            check_out(out[b, h], o, f"{name} b{b} h{h}")
+            assert abs(lse[b, h] - l) < 2e-3
+        ret = list(L.ret_heads)
+        assert (run.out[:, ret].float() - two.out[:, ret].float()).abs().max().item() <= 2e-2
+
+
+def test_select_attend_degenerate_rows():
+    """Rows that keep everything (p = 1), invalid rows (p = 0), a row without a finite score and contexts
+    shorter than one chunk, next to ordinary rows of the same batch."""
+    print("[case] select+attend degenerate rows", flush=True)
+    w = wl.small_decode(DEV, seed=21, ctx=(700, 5000, 9, 4097))
+    L = w.layer
+    oi = oracle_inputs(w)
+    p = w.p_rows.clone()
+    p[0] = 1.0                       # sequence 0, first retrieval head: keep everything
+    p[1] = 0.0                       # invalid
+    p[5] = float("nan")              # invalid
+    w.p_rows = p
+    run = DecodeRun(w, fuse_level1=False)
+    dead = 3                         # sequence 1, first retrieval head: no finite score
+    for rep in range(2):
+        run.out.fill_(7.0)
+        run.lse.fill_(7.0)
+        run.index_score()
+        run.scores[dead, :] = float("-inf")
+        run.select_attend()
+        sets, cnt = run.sel_sets()
+        assert cnt[0] == w.ctx_len[0] and cnt[1] == -1 and cnt[5] == -1 and cnt[dead] == 0
+        out, lse = run.out_f64(), run.lse.cpu().numpy()
+        sets = [s if c > 0 else np.zeros(0, dtype=np.int64) for s, c in zip(sets, cnt)]
+        ref = _attend_reference(w, oi, sets)
+        for r in range(run.R):
+            b, h = r // L.n_ret, L.ret_heads[r % L.n_ret]
+            if cnt[r] <= 0:
+                assert np.all(out[b, h] == 0.0) and lse[b, h] == -np.inf
+            else:
+                check_out(out[b, h], ref[(b, h)][0], f"row {r}")
+                assert abs(lse[b, h] - ref[(b, h)][1]) < 2e-3

@@ -66,6 +66,15 @@ def _decode_fullsize(w, n_local_samples=24, n_dense_samples=2, seed=0):
         o, _ = orc.attend(qb[b, h], wl.bf16_bits(w.K[h // G, t0:t0 + n]), wl.bf16_bits(w.V[h // G, t0:t0 + n]),
                           np.arange(n), SC)
         check_out(dgot[b, h], o, f"dense b{b} h{h}")
+
+    # selection and attention as two calls: the same sets bit for bit, the same outputs up to summation order
+    sel1, cnt1, tau1, out1 = run.sel_idx.clone(), run.sel_count.clone(), run.tau.clone(), run.out.clone()
+    run.step_two_streams(side, fused=False)
+    torch.cuda.synchronize()
+    assert torch.equal(cnt1, run.sel_count) and torch.equal(tau1, run.tau)
+    for r in range(run.R):
+        assert torch.equal(sel1[r, :cnt[r]], run.sel_idx[r, :cnt[r]])
+    assert (out1.float() - run.out.float()).abs().max().item() <= 2e-2
     return sizes
 
 
