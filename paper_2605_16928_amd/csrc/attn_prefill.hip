@@ -368,24 +368,16 @@ __device__ __forceinline__ float sel_first_below(float M, float index_scale, flo
   return key_float(lo);
 }
 
-// WAVES waves (32 queries each) per workgroup: the waves never meet, so the workgroup size only sets the
-// grain at which the launch spreads over the compute units (32 KB of histogram + 6 KB of lists a wave).
-template <int WAVES>
-__global__ __launch_bounds__(WAVES * 64, 1) void prefill_select_kernel(const PrefillArgs a) {
-  constexpr int kSelQ = WAVES * 32;                                // queries per workgroup
-  // Rows past kSelBins are never touched: they size the workgroup's LDS beyond half a compute unit's, so
-  // that the dispatcher places one workgroup per compute unit and small launches spread over the chip
-  // instead of stacking on a part of it.
-  constexpr int kPadBins = WAVES >= 4 ? 0 : WAVES == 2 ? 16 : 176;
-  __shared__ double hist_all[WAVES][kSelBins + kPadBins][32];
-  __shared__ float list_all[WAVES][kSelListCap][64];               // per-lane member lists of sweeps 2 and 3
+__global__ __launch_bounds__(kPfThreads, 1) void prefill_select_kernel(const PrefillArgs a) {
+  __shared__ double hist_all[kPfThreads / 64][kSelBins][32];       // 128 KB
+  __shared__ float list_all[kPfThreads / 64][kSelListCap][64];     // per-lane member lists of sweeps 2 and 3
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int g = lane >> 5, r = lane & 31;
   // Workgroups go round-robin over the chip's 8 dies, each with its own L2.  The 1-D grid is decoded so
   // that a die works on ONE head (8 / n_heads dies per head): all its waves then stream the same index
   // keys and meet in that L2.
   int j, qtile;
-  const int n_qtiles = (a.n_q + kSelQ - 1) / kSelQ;
+  const int n_qtiles = (a.n_q + kPfQ - 1) / kPfQ;
   if (a.n_heads <= 8 && 8 % a.n_heads == 0) {
     const int per_head = 8 / a.n_heads;                            // dies per head
     const int die = blockIdx.x & 7, k = blockIdx.x >> 3;
@@ -396,7 +388,7 @@ __global__ __launch_bounds__(WAVES * 64, 1) void prefill_select_kernel(const Pre
     qtile = blockIdx.x / a.n_heads;
   }
   if (qtile >= n_qtiles) return;
-  const int t0 = (n_qtiles - 1 - qtile) * kSelQ;                   // long rows first
+  const int t0 = (n_qtiles - 1 - qtile) * kPfQ;                    // long rows first
   if (t0 + wave * 32 >= a.n_q) return;                             // no query in this wave
   const int pos0 = (int)a.q_start_host;
   const int t = t0 + wave * 32 + r;
@@ -413,7 +405,7 @@ __global__ __launch_bounds__(WAVES * 64, 1) void prefill_select_kernel(const Pre
   const bool wave_partial = t0 + wave * 32 + 32 > a.n_q;
   const int n_tiles = m_wave_hi / 32 + 1;
   const int n_interior = wave_partial ? 0 : (m_wave_lo + 1) / 32;  // tiles with nb + 31 <= m_wave_lo
-  double (*hist)[32] = hist_all[wave];                             // [kSelBins (+ padding)][32]
+  double (*hist)[32] = hist_all[wave];
   float (*lst)[64] = list_all[wave];
   int lcnt = 0;                     // entries in this lane's member list
 
@@ -1241,12 +1233,6 @@ __global__ __launch_bounds__(256) void prefill_combine_kernel(const PrefillArgs 
 }
 
 // Number of key-range splits for a dense launch with few workgroups (long context, few heads).
-// measurement override of a launch heuristic (environment variable; 0 or unset = the heuristic)
-static int tune(const char* name, int dflt) {
-  const char* e = getenv(name);
-  return e ? atoi(e) : dflt;
-}
-
 static int choose_splits(int n_heads, int32_t T, int64_t chunk_start) {
   const int64_t wgs = (int64_t)n_heads * ((T + kPwQ - 1) / kPwQ);
   const int64_t avg_tiles = (chunk_start + T / 2) / kPfK + 1;
@@ -1419,21 +1405,16 @@ extern "C" int32_t rtp_sparse_attn_prefill(const rtp_layer_desc* layer, const vo
   a.sel_thr = (float*)((char*)ws + proj_bytes);
   a.part = (float*)((char*)ws + proj_bytes + state_bytes);
   a.n_splits = choose_splits(layer->n_ret, T, chunk_start);
-  if ((T + kPwQ - 1) / kPwQ > 65535) return fail(RTP_ERR_INVALID_ARG, "%s: T too large for one launch", who);
+  const unsigned n_qtiles = (unsigned)((T + kPfQ - 1) / kPfQ);
+  if (n_qtiles > 65535) return fail(RTP_ERR_INVALID_ARG, "%s: T too large for one launch", who);
   if (p < 1.f) {
-    // Workgroups of four waves when that already gives every SIMD of the chip a wave, else single waves.
-    static const int force_waves = tune("RTP_TUNE_SELECT_WAVES", 0);
-    const int waves = force_waves ? force_waves : ((int64_t)a.n_heads * ((T + 127) / 128) >= 256 ? 4 : 1);
-    const unsigned n_qtiles = (unsigned)((T + waves * 32 - 1) / (waves * 32));
     // 1-D grid, padded so that every die gets whole (head, query tile) columns (see the kernel's decoding)
     unsigned wgs = (unsigned)a.n_heads * n_qtiles;
     if (a.n_heads <= 8 && 8 % a.n_heads == 0) {
       const unsigned per_head = 8u / (unsigned)a.n_heads;
       wgs = 8u * ((n_qtiles + per_head - 1) / per_head);
     }
-    if (waves == 4) hipLaunchKernelGGL(prefill_select_kernel<4>, dim3(wgs), dim3(256), 0, (hipStream_t)stream, a);
-    else if (waves == 2) hipLaunchKernelGGL(prefill_select_kernel<2>, dim3(wgs), dim3(128), 0, (hipStream_t)stream, a);
-    else hipLaunchKernelGGL(prefill_select_kernel<1>, dim3(wgs), dim3(64), 0, (hipStream_t)stream, a);
+    hipLaunchKernelGGL(prefill_select_kernel, dim3(wgs), dim3(kPfThreads), 0, (hipStream_t)stream, a);
   }
   dim3 grid((unsigned)a.n_heads, (unsigned)((T + kPwQ - 1) / kPwQ), (unsigned)a.n_splits);
   hipLaunchKernelGGL(flash_prefill_wide_kernel<kModeSparse>, grid, dim3(kPfThreads), 0, (hipStream_t)stream, a);

@@ -33,7 +33,8 @@ def decode():
     for _ in range(3):
         dst.copy_(src)
     for _ in range(5):
-        run.step()
+        run.step()                                  # selection + retrieval-head attention as one call
+        run.step(fused=False)                       # ... and as two calls
         run.dense_attn(run.out)
     torch.cuda.synchronize()
     print("copy bytes per launch:", n * 4, "read and", n * 4, "written")
