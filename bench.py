@@ -292,12 +292,11 @@ def main() -> int:
 
     # ---- prefill at 1,048,576 tokens (configuration 4): chunks of 8192 queries at five depths ----
     prefill = None
+    prefill_128k = None
     if not args.no_prefill:
         from paper_2605_16928_amd.pipeline import PrefillRun
         MFMA_PEAK = 2.5e15
-        depth = {}
-        for chunk in (0, 31, 63, 95, 127):
-            w = wl.c4_chunk(dev, chunk=chunk)
+        def chunk_times(w, reps, dense_warm):
             pr = PrefillRun(w)
             Lp = w.layer
             n_loc = Lp.n_q_heads - Lp.n_ret
@@ -308,12 +307,11 @@ def main() -> int:
                 rtp.rtp_sparse_attn_prefill(pr.desc, w.qI, w.q, None, w.kI, w.N * 16, pr.Kp, pr.Vp, pr.rs, pr.hs,
                                             w.chunk_start, w.T, 1.0, pr.out, None, None, None, None, pr.ws)
 
-            reps = 3 if chunk < 100 else 2
             t_local = timed(lambda i: pr.local_attn(), reps, 1)
             t_ret = timed(lambda i: ret_dense(), reps, 1)
             t_topp = timed(lambda i: pr.sparse_prefill(), reps, 1)
-            t_dense = timed(lambda i: pr.dense_attn(), 1, 1 if chunk < 100 else 0)
-            depth[chunk] = {
+            t_dense = timed(lambda i: pr.dense_attn(), 1, dense_warm)
+            res = {
                 "context": w.N, "local_ms": round(t_local / 1e3, 3), "retrieval_dense_ms": round(t_ret / 1e3, 3),
                 "retrieval_topp_ms": round(t_topp / 1e3, 3), "dense_all_heads_ms": round(t_dense / 1e3, 3),
                 "local_mfma_frac": round(n_loc * pairs_local * 512 / (t_local * 1e-6) / MFMA_PEAK, 4),
@@ -321,8 +319,28 @@ def main() -> int:
                 "dense_mfma_frac": round(Lp.n_q_heads * pairs_dense * 512 / (t_dense * 1e-6) / MFMA_PEAK, 4),
                 "topp_kept_tokens_mean": round(float(pr.count.float().mean()), 1),
             }
-            del pr, w
+            del pr
             torch.cuda.empty_cache()
+            return res
+
+        depth = {}
+        for chunk in (0, 31, 63, 95, 127):
+            depth[chunk] = chunk_times(wl.c4_chunk(dev, chunk=chunk), 3 if chunk < 100 else 2, 1 if chunk < 100 else 0)
+        # configuration 3: the 131072-token sequence in 4096-query chunks, first / middle / last chunk
+        depth3 = {chunk: chunk_times(wl.c3_chunk(dev, chunk=chunk), 5, 1) for chunk in (0, 15, 31)}
+        last3 = depth3[31]
+        prefill_128k = {
+            "workload": "c3: prefill of 131072 tokens in 4096-query chunks, 32 query / 8 KV heads, 4 retrieval heads (top-p 0.9), "
+                        "local heads 4 sink + 2048 window; chunks 0/15/31 timed",
+            "last_chunk_tokens_per_s_paper_rule": round(4096 / ((last3["local_ms"] + last3["retrieval_dense_ms"]) * 1e-3), 1),
+            "last_chunk_tokens_per_s_topp_rule": round(4096 / ((last3["local_ms"] + last3["retrieval_topp_ms"]) * 1e-3), 1),
+            "last_chunk_tokens_per_s_dense": round(4096 / (last3["dense_all_heads_ms"] * 1e-3), 1),
+            "last_chunk_speedup_vs_inhouse_dense_paper_rule":
+                round(last3["dense_all_heads_ms"] / (last3["local_ms"] + last3["retrieval_dense_ms"]), 2),
+            "last_chunk_speedup_vs_inhouse_dense_topp_rule":
+                round(last3["dense_all_heads_ms"] / (last3["local_ms"] + last3["retrieval_topp_ms"]), 2),
+            "by_chunk": depth3,
+        }
         T8 = 8192
         last = depth[127]
         # whole-sequence time: trapezoid over the five sampled depths, 128 chunks in total
@@ -372,6 +390,7 @@ def main() -> int:
         "roofline": roofline,
         "cpu_baseline": cpu,
         "prefill_1m": prefill,
+        "prefill_128k": prefill_128k,
         "decode_1m": decode_1m,
         "extra": {
             "decode_tokens_per_s": round(B / (us_step * 1e-6), 1),

@@ -368,16 +368,24 @@ __device__ __forceinline__ float sel_first_below(float M, float index_scale, flo
   return key_float(lo);
 }
 
+//
+// KS (1, 2 or 4) waves share one group of 32 queries and split its key range between them: a launch with
+// few queries (a 4096-query chunk of 4 heads is 512 groups for 1024 SIMDs) then still fills the chip.  Each
+// wave keeps its own histogram; the scans add the KS histograms of a group in a fixed order, and the waves
+// of a workgroup meet at a barrier before and after every scan.
+template <int KS>
 __global__ __launch_bounds__(kPfThreads, 1) void prefill_select_kernel(const PrefillArgs a) {
+  constexpr int kSelQ = 32 * (kPfThreads / 64) / KS;               // queries per workgroup
   __shared__ double hist_all[kPfThreads / 64][kSelBins][32];       // 128 KB
   __shared__ float list_all[kPfThreads / 64][kSelListCap][64];     // per-lane member lists of sweeps 2 and 3
+  __shared__ float max_all[kPfThreads / 64][32];                   // sweep 0: the waves' row maxima
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int g = lane >> 5, r = lane & 31;
   // Workgroups go round-robin over the chip's 8 dies, each with its own L2.  The 1-D grid is decoded so
   // that a die works on ONE head (8 / n_heads dies per head): all its waves then stream the same index
   // keys and meet in that L2.
   int j, qtile;
-  const int n_qtiles = (a.n_q + kPfQ - 1) / kPfQ;
+  const int n_qtiles = (a.n_q + kSelQ - 1) / kSelQ;
   if (a.n_heads <= 8 && 8 % a.n_heads == 0) {
     const int per_head = 8 / a.n_heads;                            // dies per head
     const int die = blockIdx.x & 7, k = blockIdx.x >> 3;
@@ -388,10 +396,13 @@ __global__ __launch_bounds__(kPfThreads, 1) void prefill_select_kernel(const Pre
     qtile = blockIdx.x / a.n_heads;
   }
   if (qtile >= n_qtiles) return;
-  const int t0 = (n_qtiles - 1 - qtile) * kPfQ;                    // long rows first
-  if (t0 + wave * 32 >= a.n_q) return;                             // no query in this wave
+  const int t0 = (n_qtiles - 1 - qtile) * kSelQ;                   // long rows first
+  const int qgroup = wave / KS, part = wave - qgroup * KS;         // this wave's queries and its share of their keys
+  const int tw = t0 + qgroup * 32;                                 // first query of the group
+  const bool idle = tw >= a.n_q;                                   // no query in this group
+  if (KS == 1 && idle) return;                                     // (with KS > 1 the wave still goes to the barriers)
   const int pos0 = (int)a.q_start_host;
-  const int t = t0 + wave * 32 + r;
+  const int t = tw + r;
   const bool qok = t < a.n_q;
   const int m = pos0 + t;
   const float ninf = -__builtin_huge_valf(), pinf = __builtin_huge_valf();
@@ -400,11 +411,11 @@ __global__ __launch_bounds__(kPfThreads, 1) void prefill_select_kernel(const Pre
   u32x4 qIreg = (u32x4){0u, 0u, 0u, 0u};
   if (qok) qIreg = *reinterpret_cast<const u32x4*>(a.qI + ((int64_t)j * a.n_q + t) * kIndexDim + g * 8);
   const int n_rows = pos0 + a.n_q;                                 // index-key rows that exist
-  const int m_wave_lo = pos0 + t0 + wave * 32;
-  const int m_wave_hi = pos0 + min(t0 + wave * 32 + 32, a.n_q) - 1;
-  const bool wave_partial = t0 + wave * 32 + 32 > a.n_q;
-  const int n_tiles = m_wave_hi / 32 + 1;
-  const int n_interior = wave_partial ? 0 : (m_wave_lo + 1) / 32;  // tiles with nb + 31 <= m_wave_lo
+  const int m_wave_lo = pos0 + tw;
+  const int m_wave_hi = pos0 + min(tw + 32, a.n_q) - 1;
+  const bool wave_partial = tw + 32 > a.n_q;
+  const int n_tiles = idle ? 0 : m_wave_hi / 32 + 1;
+  const int n_interior = (wave_partial || idle) ? 0 : (m_wave_lo + 1) / 32;  // tiles with nb + 31 <= m_wave_lo
   double (*hist)[32] = hist_all[wave];
   float (*lst)[64] = list_all[wave];
   int lcnt = 0;                     // entries in this lane's member list
@@ -543,10 +554,20 @@ __global__ __launch_bounds__(kPfThreads, 1) void prefill_select_kernel(const Pre
     }
   };
   const int n_plain = n_interior / (2 * kSelRing) * (2 * kSelRing);   // whole rounds of interior tiles run without masks
+  // this wave's share: an equal run of the mask-free rounds; the last wave of the group also takes the edge
+  const int rounds = n_plain / (2 * kSelRing);
+  const int plain_lo = (rounds * part / KS) * (2 * kSelRing), plain_hi = (rounds * (part + 1) / KS) * (2 * kSelRing);
   auto sweep_all = [&](auto PH) {
-    sweep(PH, std::false_type{}, 0, n_plain);
-    sweep(PH, std::true_type{}, n_plain, n_tiles);
+    sweep(PH, std::false_type{}, plain_lo, plain_hi);
+    if (part == KS - 1) sweep(PH, std::true_type{}, n_plain, n_tiles);
     if (decltype(PH)::value >= 2) drain_list();
+  };
+  // bin i of this lane's query, summed over the group's waves (fixed order)
+  auto hist_sum = [&](int i) {
+    double v = hist_all[qgroup * KS][i][r];
+#pragma unroll
+    for (int k = 1; k < KS; ++k) v += hist_all[qgroup * KS + k][i][r];
+    return v;
   };
 
   double Z = 0.0, above = 0.0;
@@ -567,21 +588,28 @@ __global__ __launch_bounds__(kPfThreads, 1) void prefill_select_kernel(const Pre
     if (phase == 0) {
       float mx = fmaxf(fmaxf(mxs[0], mxs[1]), fmaxf(mxs[2], mxs[3]));
       mx = fmaxf(mx, __shfl_xor(mx, 32));
+      if (KS > 1) {
+        if (g == 0) max_all[wave][r] = mx;
+        __syncthreads();
+#pragma unroll
+        for (int k = 0; k < KS; ++k) mx = fmaxf(mx, max_all[qgroup * KS + k][r]);
+      }
       selM = mx * cs;
       continue;
     }
+    if (KS > 1) __syncthreads();                                   // every wave of the group has added its masses
     // ---- scan this query's bins from the top of the score range (bin 0) down; both lanes of the
     // pair run the same scan on the same numbers ----
     if (phase == 1) {
       Z = 0.0;
-      for (int i = 0; i < kSelBins; ++i) Z += hist[i][r];
+      for (int i = 0; i < kSelBins; ++i) Z += hist_sum(i);
     }
     const double target = (double)a.p * Z;
     double cum = above, hsel = 0.0;
     int bsel = kSelBins - 1;
     bool found = false;
     for (int i = 0; i < kSelBins; ++i) {
-      const double hv = hist[i][r];
+      const double hv = hist_sum(i);
       if (!found) {
         if (cum + hv >= target) { bsel = i; hsel = hv; found = true; }
         else cum += hv;
@@ -599,6 +627,7 @@ __global__ __launch_bounds__(kPfThreads, 1) void prefill_select_kernel(const Pre
       x_lo = sel_first_below(selM, cs, hi_t);
       // the largest x that is still a member: the float just below the first x with tt < lo bound
       x_top = key_float(float_key(sel_first_below(selM, cs, lo_t)) - 1u);
+      if (KS > 1) __syncthreads();                                 // every wave of the group has read the histograms
       zero_hist();
     } else {
       // a threshold inside the open-ended last coarse bin keeps every candidate
@@ -607,7 +636,7 @@ __global__ __launch_bounds__(kPfThreads, 1) void prefill_select_kernel(const Pre
       sel_mass = (lump || !(Z > 0.0)) ? 1.f : (float)((cum + hsel) / Z);
     }
   }
-  if (!qok || g != 0) return;
+  if (!qok || g != 0 || part != 0) return;
   const int64_t o = (int64_t)j * a.n_q + t;
   a.sel_thr[o] = sel_first_below(selM, cs, cut);
   if (a.mass) a.mass[o] = sel_mass;
@@ -1233,6 +1262,12 @@ __global__ __launch_bounds__(256) void prefill_combine_kernel(const PrefillArgs 
 }
 
 // Number of key-range splits for a dense launch with few workgroups (long context, few heads).
+// measurement override of a launch heuristic (environment variable; 0 or unset = the heuristic)
+static int tune(const char* name, int dflt) {
+  const char* e = getenv(name);
+  return e ? atoi(e) : dflt;
+}
+
 static int choose_splits(int n_heads, int32_t T, int64_t chunk_start) {
   const int64_t wgs = (int64_t)n_heads * ((T + kPwQ - 1) / kPwQ);
   const int64_t avg_tiles = (chunk_start + T / 2) / kPfK + 1;
@@ -1405,16 +1440,22 @@ extern "C" int32_t rtp_sparse_attn_prefill(const rtp_layer_desc* layer, const vo
   a.sel_thr = (float*)((char*)ws + proj_bytes);
   a.part = (float*)((char*)ws + proj_bytes + state_bytes);
   a.n_splits = choose_splits(layer->n_ret, T, chunk_start);
-  const unsigned n_qtiles = (unsigned)((T + kPfQ - 1) / kPfQ);
-  if (n_qtiles > 65535) return fail(RTP_ERR_INVALID_ARG, "%s: T too large for one launch", who);
+  if ((T + kPfQ - 1) / kPfQ > 65535) return fail(RTP_ERR_INVALID_ARG, "%s: T too large for one launch", who);
   if (p < 1.f) {
+    // waves per 32-query group: as many as it takes to give each of the chip's 1024 SIMDs a wave
+    static const int force_ks = tune("RTP_TUNE_SELECT_KEY_SPLIT", 0);
+    const int64_t groups = (int64_t)a.n_heads * ((T + 31) / 32);
+    const int ks = force_ks ? force_ks : (groups > 512 ? 1 : groups > 256 ? 2 : 4);
+    const unsigned n_qtiles = (unsigned)((T + 128 / ks - 1) / (128 / ks));
     // 1-D grid, padded so that every die gets whole (head, query tile) columns (see the kernel's decoding)
     unsigned wgs = (unsigned)a.n_heads * n_qtiles;
     if (a.n_heads <= 8 && 8 % a.n_heads == 0) {
       const unsigned per_head = 8u / (unsigned)a.n_heads;
       wgs = 8u * ((n_qtiles + per_head - 1) / per_head);
     }
-    hipLaunchKernelGGL(prefill_select_kernel, dim3(wgs), dim3(kPfThreads), 0, (hipStream_t)stream, a);
+    if (ks == 1) hipLaunchKernelGGL(prefill_select_kernel<1>, dim3(wgs), dim3(kPfThreads), 0, (hipStream_t)stream, a);
+    else if (ks == 2) hipLaunchKernelGGL(prefill_select_kernel<2>, dim3(wgs), dim3(kPfThreads), 0, (hipStream_t)stream, a);
+    else hipLaunchKernelGGL(prefill_select_kernel<4>, dim3(wgs), dim3(kPfThreads), 0, (hipStream_t)stream, a);
   }
   dim3 grid((unsigned)a.n_heads, (unsigned)((T + kPwQ - 1) / kPwQ), (unsigned)a.n_splits);
   hipLaunchKernelGGL(flash_prefill_wide_kernel<kModeSparse>, grid, dim3(kPfThreads), 0, (hipStream_t)stream, a);
