@@ -51,6 +51,12 @@ struct RowState {          // one per row and launch (levels 2 and 3 leave one e
 
 constexpr int kBucketCap = 1024;
 
+#ifdef RTP_DBG_CLOCKS
+#define RTP_CLK(KID, K) if (threadIdx.x == 0) reinterpret_cast<uint64_t*>(a.sel_idx + (int64_t)blockIdx.y * a.sel_stride + 65536)[((KID) * 64 + blockIdx.x) * 8 + (K)] = wall_clock64();
+#else
+#define RTP_CLK(KID, K)
+#endif
+
 struct TopPArgs {
   const float* scores;
   int64_t score_stride;
@@ -97,17 +103,25 @@ struct Scan1Result {       // level 1: bins carry different references, the scan
 // Every thread gets the result; all workgroups of a row compute the same numbers in the same order.
 // Threads own `per` consecutive bins in order FROM THE TOP of the score range (thread 0 the highest bins),
 // so "the mass above" is an ordinary inclusive prefix sum over lanes and waves.
-__device__ __forceinline__ Scan1Result scan_level1(const uint64_t* __restrict__ h, float p, double* sh_d /*[4]*/,
+// The bins arrive in registers (load_bins): a kernel issues those loads first thing, so that they are in
+// flight while it finds out what else it needs.
+template <int NBINS>
+__device__ __forceinline__ void load_bins(const uint64_t* __restrict__ h, uint64_t (&loc)[NBINS / kTpThreads]) {
+  const int first = (kTpThreads - 1 - (int)threadIdx.x) * (NBINS / kTpThreads);
+#pragma unroll
+  for (int i = 0; i < NBINS / kTpThreads; ++i) loc[i] = h[first + i];
+}
+
+__device__ __forceinline__ Scan1Result scan_level1(const uint64_t (&loc)[kBins1 / kTpThreads], float p, double* sh_d /*[4]*/,
                                                    int* sh_i /*[4]*/, double* sh_res /*[3]*/,
-                                                   const double* __restrict__ tab /* filled by the caller */) {
+                                                   const double* __restrict__ tab /* filled by the caller */,
+                                                   uint64_t* dbg = nullptr) {
   constexpr int per = kBins1 / kTpThreads;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int first = (kTpThreads - 1 - tid) * per;     // this thread's lowest bin
-  uint64_t loc[per];
   int top = -1;
 #pragma unroll
   for (int i = 0; i < per; ++i) {
-    loc[i] = h[first + i];
     if (loc[i]) top = first + i;
   }
   top = wave_max_ge_m1(top);
@@ -117,6 +131,7 @@ __device__ __forceinline__ Scan1Result scan_level1(const uint64_t* __restrict__ 
   Scan1Result res;
   res.bin = -1; res.above_base = 0.0; res.total_d = 0.0; res.target = 1; res.ref = 0.f;
   if (top < 0) { __syncthreads(); return res; }       // uniform: every thread sees the same `top`
+  if (dbg && threadIdx.x == 0) dbg[5] = wall_clock64();
   const double R = (double)bin_ref(top);
   double md[per];
   double sum = 0.0;
@@ -130,6 +145,7 @@ __device__ __forceinline__ Scan1Result scan_level1(const uint64_t* __restrict__ 
     }
     sum += md[i];
   }
+  if (dbg && threadIdx.x == 0) dbg[6] = wall_clock64();
   double incl = wave_incl_scan(sum);                  // this thread's bins and every higher bin of the wave
   if (lane == 63) sh_d[wave] = incl;
   // defaults (nobody crosses): the top bin, nothing above it -- left by the thread that owns that bin
@@ -167,6 +183,7 @@ __device__ __forceinline__ Scan1Result scan_level1(const uint64_t* __restrict__ 
     sh_res[2] = __longlong_as_double((long long)lb);
   }
   __syncthreads();
+  if (dbg && threadIdx.x == 0) dbg[7] = wall_clock64();
   const int b1 = (int)sh_res[0];
   const double above_true = sh_res[1];
   const uint64_t hb = (uint64_t)__double_as_longlong(sh_res[2]);
@@ -200,18 +217,14 @@ struct ScanResult {
 // Levels 2 and 3: integer masses with one reference.  Same thread order as above (thread 0 owns the
 // highest bins); two block barriers.
 template <int NBINS>
-__device__ __forceinline__ ScanResult scan_from_top(const uint64_t* __restrict__ h, uint64_t above, uint64_t target,
+__device__ __forceinline__ ScanResult scan_from_top(const uint64_t (&loc)[NBINS / kTpThreads], uint64_t above, uint64_t target,
                                                     uint64_t* sh_w /*[4]*/, uint64_t* sh_res /*[3]*/) {
   constexpr int per = NBINS / kTpThreads;             // consecutive bins per thread
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int first = (kTpThreads - 1 - tid) * per;     // this thread's lowest bin
-  uint64_t loc[per];
   uint64_t sum = 0;
 #pragma unroll
-  for (int i = 0; i < per; ++i) {
-    loc[i] = h[first + i];
-    sum += loc[i];
-  }
+  for (int i = 0; i < per; ++i) sum += loc[i];
   uint64_t incl = wave_incl_scan(sum);                // this thread's bins and every higher bin of the wave
   if (lane == 63) sh_w[wave] = incl;
   if (first == 0) { sh_res[0] = 0; sh_res[1] = above; sh_res[2] = loc[0]; }   // defaults: bin 0
@@ -286,6 +299,11 @@ __global__ __launch_bounds__(kTpThreads) void topp_level_kernel(const TopPArgs a
   constexpr int kShift = LEVEL == 1 ? 21 : (LEVEL == 2 ? 10 : 0);     // key bits below this level's field
   constexpr int kOff = LEVEL == 1 ? 0 : (LEVEL == 2 ? kBins1 : kBins1 + kBins2);
   const int r = blockIdx.y, c = blockIdx.x, tid = threadIdx.x;
+  // what the previous launch left for this row: in flight before anything else (levels 2 and 3 scan the
+  // histogram of the level before in their prologue)
+  static_assert(kBins1 == kBins2, "one register array serves the scans of levels 2 and 3");
+  uint64_t prev_bins[kBins1 / kTpThreads];
+  if (LEVEL >= 2) load_bins<kBins1>(a.hist + (int64_t)r * kBinsTotal + (LEVEL == 3 ? kBins1 : 0), prev_bins);
   const int n = a.row_len[r];
   const int64_t n0 = (int64_t)c * kTpChunk;
   if (n0 >= n || n <= 0) return;
@@ -300,16 +318,19 @@ __global__ __launch_bounds__(kTpThreads) void topp_level_kernel(const TopPArgs a
   __shared__ double sh_dres[3];
   __shared__ int sh_i[kTpThreads / 64];
   __shared__ double tab[256];
+  RTP_CLK(LEVEL - 2, 0)
   fill_exp_table(tab);
   uint64_t* hrow = a.hist + (int64_t)r * kBinsTotal;
   RowState* st = a.state + (int64_t)r * 3;
-  if (LEVEL == 2) {
-    // level 3's histogram and the row's short list are written by the NEXT launch and were last read by
-    // the write launch of the previous call: this is the safe place to clear them
+  // Level 3's histogram and the row's short list are written by the NEXT launch and were last read by the
+  // write launch of the previous call: the level-2 launch clears them -- as the last thing it does, because a
+  // workgroup barrier waits for the stores issued before it, and the prologue below is a chain of barriers.
+  auto clear_level3 = [&]() {
+    if (LEVEL != 2) return;
     const int active = (n + kTpChunk - 1) / kTpChunk;
     for (int i = c * kTpThreads + tid; i < kBins3; i += active * kTpThreads) hrow[kBins1 + kBins2 + i] = 0;
     if (c == 0 && tid == 0) a.bucket_n[r] = 0;
-  }
+  };
 
   // ---- prologue: what the previous launch left for this row ----
   const int shift = fixed_shift(n);
@@ -334,7 +355,7 @@ __global__ __launch_bounds__(kTpThreads) void topp_level_kernel(const TopPArgs a
       // static top-k: level 1 holds plain counts; the k-th best score lies in the bin where the count
       // from the top reaches k.  A budget that covers every finite score keeps them all.
       const uint64_t k = (uint64_t)a.kcount[r];
-      const ScanResult s1 = scan_from_top<kBins1>(hrow, 0, k, sh_part, sh_res);
+      const ScanResult s1 = scan_from_top<kBins1>(prev_bins, 0, k, sh_part, sh_res);
       if (s1.total == 0) {
         flags = 2;
       } else if (k >= s1.total) {
@@ -346,7 +367,12 @@ __global__ __launch_bounds__(kTpThreads) void topp_level_kernel(const TopPArgs a
       }
       s.flags = flags;
     } else if (flags == 0) {
-      const Scan1Result s1 = scan_level1(hrow, pr, sh_d, sh_i, sh_dres, tab);
+#ifdef RTP_DBG_CLOCKS
+      const Scan1Result s1 = scan_level1(prev_bins, pr, sh_d, sh_i, sh_dres, tab,
+                                         reinterpret_cast<uint64_t*>(a.sel_idx + (int64_t)blockIdx.y * a.sel_stride + 65536) + blockIdx.x * 8);
+#else
+      const Scan1Result s1 = scan_level1(prev_bins, pr, sh_d, sh_i, sh_dres, tab);
+#endif
       if (s1.bin < 0) {
         flags = 2;
       } else {
@@ -365,7 +391,7 @@ __global__ __launch_bounds__(kTpThreads) void topp_level_kernel(const TopPArgs a
     ref = st[0].ref;
     uint64_t above3 = 0;
     if (flags == 0) {
-      const ScanResult sr = scan_from_top<kBins2>(hrow + kBins1, 0, st[0].target, sh_part, sh_res);
+      const ScanResult sr = scan_from_top<kBins2>(prev_bins, 0, st[0].target, sh_part, sh_res);
       prefix = (st[0].prefix << 11) | (uint32_t)sr.bin;
       above3 = sr.above;
     }
@@ -392,7 +418,11 @@ __global__ __launch_bounds__(kTpThreads) void topp_level_kernel(const TopPArgs a
     }
     block_count_to(cnt, a.chunk_cnt + (int64_t)r * a.n_chunks + c, sh_i);
   }
-  if (flags != 0) return;          // keep-all, invalid or empty rows need no histogram
+  if (flags != 0) {                // keep-all, invalid or empty rows need no histogram
+    clear_level3();
+    return;
+  }
+  RTP_CLK(LEVEL - 2, 1)
 
   // Levels 2 and 3 weigh only the members of the prefix bin (a few percent of the chunk at level 2,
   // a handful at level 3).  At level 2, weighing them where they sit would run the fp64 arithmetic in
@@ -468,6 +498,7 @@ __global__ __launch_bounds__(kTpThreads) void topp_level_kernel(const TopPArgs a
         if (member & (1u << (u * 4 + k))) sh_list[pos++] = s4[k];
     }
     __syncthreads();
+    RTP_CLK(LEVEL - 2, 2)
     const int total = sh_n;
     for (int i = tid; i < total; i += kTpThreads) {
       const float sv = sh_list[i];
@@ -476,7 +507,10 @@ __global__ __launch_bounds__(kTpThreads) void topp_level_kernel(const TopPArgs a
     }
   }
   __syncthreads();
+  RTP_CLK(LEVEL - 2, 3)
   flush_hist(lh, hrow + kOff, kBins, kTpThreads);
+  clear_level3();
+  RTP_CLK(LEVEL - 2, 4)
 }
 
 // ---- launches 4 and 5: final scan + per-chunk counts, then ordered compaction ---------------------
@@ -531,7 +565,7 @@ __device__ __forceinline__ int write_ranked(uint32_t keep, int before, int32_t* 
     for (int k = 0; k < 4; ++k) {
       if (keep & (1u << (u * 4 + k))) {
         const int32_t where = (int32_t)(n0 + (u * kTpThreads + tid) * 4 + k);
-        out[pos] = where;
+        if (out) out[pos] = where;
         if (local) local[pos - before] = where;
         ++pos;
       }
@@ -578,22 +612,44 @@ template <bool ATTEND>
 __global__ __launch_bounds__(kTpThreads) void topp_write_kernel(const TopPArgs a, const GatherArgs ga) {
   const int r = blockIdx.y, c = blockIdx.x, tid = threadIdx.x;
   __shared__ int32_t sh_list[ATTEND ? kTpChunk : 1];
-  if (a.rezero) {                  // levels 1 and 2 were last read by the level-2 / level-3 launches
+  RTP_CLK(2, 0)
+  // Levels 1 and 2 were last read by the level-2 / level-3 launches; every workgroup of the grid clears its
+  // share on its way out (not on its way in: the barriers below would wait for the stores).
+  // The same goes for the row's scalar results (chunk 0 stores them at the end).
+  float res_tau = 0.f, res_mass = 0.f;
+  int res_count = 0;
+  bool have_res = false;
+  auto rezero = [&]() {
+    if (have_res && c == 0 && tid == 0) {
+      a.sel_count[r] = res_count;
+      if (a.tau) a.tau[r] = res_tau;
+      if (a.mass) a.mass[r] = res_mass;
+    }
+    if (!a.rezero) return;
     uint64_t* h = a.hist + (int64_t)r * kBinsTotal;
     for (int i = c * kTpThreads + tid; i < kBins1 + kBins2; i += a.n_chunks * kTpThreads) h[i] = 0;
-  }
+  };
+  // what the level-3 launch left for this row, in flight before anything else: its histogram, the per-chunk
+  // counts (one per thread covers 256 chunks = 1M scores) and the row's short list
+  uint64_t l3_bins[kBins3 / kTpThreads];
+  load_bins<kBins3>(a.hist + (int64_t)r * kBinsTotal + kBins1 + kBins2, l3_bins);
+  const int cc_mine = tid < a.n_chunks ? a.chunk_cnt[(int64_t)r * a.n_chunks + tid] : 0;
+  const int listed_raw = a.bucket_n[r];
+  uint2 be[kBucketCap / kTpThreads];
+#pragma unroll
+  for (int k = 0; k < kBucketCap / kTpThreads; ++k) be[k] = a.bucket[(int64_t)r * kBucketCap + k * kTpThreads + tid];
   const int n = a.row_len[r];
   const int64_t n0 = (int64_t)c * kTpChunk;
   const float ninf = -__builtin_huge_valf();
   if (n <= 0) {
-    if (c == 0 && tid == 0) {
-      if (a.tau) a.tau[r] = ninf;
-      if (a.mass) a.mass[r] = 0.f;
-      a.sel_count[r] = 0;
-    }
+    have_res = true; res_tau = ninf; res_mass = 0.f; res_count = 0;
+    rezero();
     return;
   }
-  if (n0 >= n) return;
+  if (n0 >= n) {
+    rezero();
+    return;
+  }
   const int n_here = (int)min((int64_t)kTpChunk, (int64_t)n - n0);
   float4 v[kTpVec];
   load_chunk(reinterpret_cast<const float4*>(a.scores + (int64_t)r * a.score_stride + n0), n_here, tid, v);
@@ -605,44 +661,50 @@ __global__ __launch_bounds__(kTpThreads) void topp_write_kernel(const TopPArgs a
   // level 2 always leaves st[0]; level 3 leaves st[1] (a copy of st[0] for rows that carry no search)
   const RowState prev = a.state[(int64_t)r * 3 + 1];
 
-  int kept_here = 0;
+  int kept_here = 0, kept_base = 0;
   const bool empty_row = prev.flags < 0 || prev.flags == 2;      // the same in every workgroup of the row
   if (empty_row) {
-    if (c == 0 && tid == 0) {
-      a.sel_count[r] = prev.flags < 0 ? -1 : 0;
-      if (a.tau) a.tau[r] = prev.flags < 0 ? __builtin_nanf("") : ninf;
-      if (a.mass) a.mass[r] = 0.f;
+    have_res = true;
+    res_count = prev.flags < 0 ? -1 : 0;
+    res_tau = prev.flags < 0 ? __builtin_nanf("") : ninf;
+    res_mass = 0.f;
+    if (!ATTEND) {
+      rezero();
+      return;
     }
-    if (!ATTEND) return;
   } else {
   uint32_t tkey = 0;      // keep keys >= tkey
   if (prev.flags == 0) {
-    const ScanResult sr = scan_from_top<kBins3>(hrow + kBins1 + kBins2, prev.above, prev.target, sh_part, sh_res);
+    const ScanResult sr = scan_from_top<kBins3>(l3_bins, prev.above, prev.target, sh_part, sh_res);
     tkey = (prev.prefix << 10) | (uint32_t)sr.bin;
-    if (c == 0 && tid == 0) {
-      if (a.tau) a.tau[r] = key_float(tkey);
-      if (a.mass) a.mass[r] = a.kcount ? __builtin_nanf("") : (float)((prev.above_base + (double)(sr.above + sr.bin_mass)) / prev.total_d);
-    }
-  } else if (c == 0 && tid == 0) {
-    if (a.tau) a.tau[r] = ninf;
-    if (a.mass) a.mass[r] = 1.f;
+    res_tau = key_float(tkey);
+    res_mass = a.kcount ? __builtin_nanf("") : (float)((prev.above_base + (double)(sr.above + sr.bin_mass)) / prev.total_d);
+  } else {
+    res_tau = ninf;
+    res_mass = 1.f;
   }
+  have_res = true;
 
+  RTP_CLK(2, 1)
   // ---- offset of this chunk = kept scores of the chunks before it; chunk 0 also publishes the total ----
   const int n_row_chunks = (n + kTpChunk - 1) / kTpChunk;
-  const int listed = prev.flags == 0 ? a.bucket_n[r] : 0;
+  const int listed = prev.flags == 0 ? listed_raw : 0;
   int before = 0, total = 0;
   if (listed <= kBucketCap) {
-    for (int i = tid; i < n_row_chunks; i += kTpThreads) {
+    if (tid < n_row_chunks) {
+      total += cc_mine;
+      if (tid < c) before += cc_mine;
+    }
+    for (int i = tid + kTpThreads; i < n_row_chunks; i += kTpThreads) {      // rows beyond 256 chunks
       const int cv = a.chunk_cnt[(int64_t)r * a.n_chunks + i];
       total += cv;
       if (i < c) before += cv;
     }
-    for (int i = tid; i < listed; i += kTpThreads) {
-      const uint2 e = a.bucket[(int64_t)r * kBucketCap + i];
-      if (e.x >= tkey) {
+#pragma unroll
+    for (int k = 0; k < kBucketCap / kTpThreads; ++k) {
+      if (k * kTpThreads + tid < listed && be[k].x >= tkey) {
         total += 1;
-        if ((int64_t)e.y < n0) before += 1;
+        if ((int64_t)be[k].y < n0) before += 1;
       }
     }
   } else {
@@ -665,18 +727,27 @@ __global__ __launch_bounds__(kTpThreads) void topp_write_kernel(const TopPArgs a
   total = 0;
 #pragma unroll
   for (int i = 0; i < kTpThreads / 64; ++i) { before += sh_red[i][0]; total += sh_red[i][1]; }
-  if (c == 0 && tid == 0) a.sel_count[r] = total;
+  res_count = total;
 
+  RTP_CLK(2, 2)
   const uint32_t keep = keep_mask(v, n_here, tid, prev.flags == 1, tkey);
-  kept_here = write_ranked(keep, before, a.sel_idx + (int64_t)r * a.sel_stride, n0, sh_tot, ATTEND ? sh_list : nullptr);
+  // ATTEND: the positions go to LDS only for now and to memory after the gather (same reason as above: the
+  // gather starts behind a barrier, and every wait for a K/V row would also wait for stores in flight)
+  kept_here = write_ranked(keep, before, ATTEND ? nullptr : a.sel_idx + (int64_t)r * a.sel_stride, n0, sh_tot,
+                           ATTEND ? sh_list : nullptr);
+  kept_base = before;
   }
-  if (!ATTEND) return;
+  if (!ATTEND) {
+    rezero();
+    return;
+  }
 
   // ---- attention over this chunk's kept positions: 16 groups of 16 lanes, one K/V row (256 bytes) per
   // group and load, kSaInFlight rows per group in flight; a lane owns 8 of the 128 dims ----
   __shared__ float sh_m[kTpThreads / 64], sh_l[kTpThreads / 64];
   __shared__ float sh_acc[kTpThreads / 64][kHeadDim];
   __syncthreads();                           // the list is complete
+  RTP_CLK(2, 3)
   const int lane = tid & 63, wave = tid >> 6;
   const int grp = wave * 4 + (lane >> 4), piece = lane & 15;
   const int b = r / ga.n_ret;
@@ -738,6 +809,7 @@ __global__ __launch_bounds__(kTpThreads) void topp_write_kernel(const TopPArgs a
       for (int d = 0; d < 8; ++d) acc[d] = fmaf(pw, vf[d], acc[d]);
     }
   }
+  RTP_CLK(2, 4)
   // the four groups of a wave in registers, the four waves through LDS
 #pragma unroll
   for (int o = 16; o <= 32; o <<= 1) {
@@ -777,6 +849,12 @@ __global__ __launch_bounds__(kTpThreads) void topp_write_kernel(const TopPArgs a
     pout[4 + tid] = A;
     if (tid == 0) { pout[0] = M; pout[1] = L; }
   }
+  {   // the chunk's positions, in one coalesced piece (after the last barrier)
+    int32_t* dst = a.sel_idx + (int64_t)r * a.sel_stride + kept_base;
+    for (int i = tid; i < kept_here; i += kTpThreads) dst[i] = sh_list[i];
+  }
+  rezero();
+  RTP_CLK(2, 5)
 }
 
 // Merges the (row, chunk) partials of one row: 8 slices of 32 lanes walk the chunks slice, slice + 8, ...
