@@ -304,7 +304,7 @@ int32_t rtp_sparsity_stats(const rtp_layer_desc* layer, const int32_t* ctx_len,
  * The results are those of rtp_topp_select followed by rtp_sparse_attn_decode on the same tensors
  * (sel_idx, sel_count, tau, mass bit-identical; out and lse equal up to the order of the fp32 partial
  * sums), with one launch and one pass over the index list less: the launch that writes the ordered
- * positions of a 4096-score chunk keeps them in LDS, gathers their K/V rows and leaves a partial softmax
+ * positions of a chunk of the row (8192 scores) keeps them in LDS, gathers their K/V rows and leaves a partial softmax
  * state per (row, chunk); a merge launch finishes each row.
  *
  * Rows are the retrieval heads of the batch: row r = b * n_ret + j scores the cached tokens of sequence b

@@ -31,11 +31,20 @@
 
 namespace rtp {
 
-constexpr int kTpThreads = 256;
-#ifndef RTP_TP_CHUNK
-#define RTP_TP_CHUNK 4096
+// Workgroup shape, measured on batch 8 x 131072 and batch 1 x 1048576 (whole decode step, us):
+//   256 threads x 4096 scores 108.8 / 118.9 | 512 x 8192 107.3 / 110.3 | 1024 x 16384 113.6 / 109.5 |
+//   256 x 8192 111.8 / 113.9 | 512 x 4096 111.6 / 120.7 | 512 x 16384 111.4 / 109.5.
+// Every workgroup repeats the scan of the previous level, and the workgroups resident on a compute unit
+// run their phases in step and share its vector ALUs: fewer, larger workgroups repeat less (and start
+// sooner: a launch of 1024 workgroups takes 2.5 us to get them all going), smaller ones balance better.
+#ifndef RTP_TP_THREADS
+#define RTP_TP_THREADS 512
 #endif
-constexpr int kTpChunk = RTP_TP_CHUNK;     // scores per workgroup (2048, 4096 or 8192)
+constexpr int kTpThreads = RTP_TP_THREADS;
+#ifndef RTP_TP_CHUNK
+#define RTP_TP_CHUNK 8192
+#endif
+constexpr int kTpChunk = RTP_TP_CHUNK;     // scores per workgroup
 constexpr int kTpVec = kTpChunk / (kTpThreads * 4);   // float4 loads per thread
 
 struct RowState {          // one per row and launch (levels 2 and 3 leave one each)
@@ -127,7 +136,9 @@ __device__ __forceinline__ Scan1Result scan_level1(const uint64_t (&loc)[kBins1 
   top = wave_max_ge_m1(top);
   if (lane == 0) sh_i[wave] = top;
   __syncthreads();
-  top = max(max(sh_i[0], sh_i[1]), max(sh_i[2], sh_i[3]));
+  top = sh_i[0];
+#pragma unroll
+  for (int w = 1; w < kTpThreads / 64; ++w) top = max(top, sh_i[w]);
   Scan1Result res;
   res.bin = -1; res.above_base = 0.0; res.total_d = 0.0; res.target = 1; res.ref = 0.f;
   if (top < 0) { __syncthreads(); return res; }       // uniform: every thread sees the same `top`
@@ -630,7 +641,7 @@ __global__ __launch_bounds__(kTpThreads) void topp_write_kernel(const TopPArgs a
     for (int i = c * kTpThreads + tid; i < kBins1 + kBins2; i += a.n_chunks * kTpThreads) h[i] = 0;
   };
   // what the level-3 launch left for this row, in flight before anything else: its histogram, the per-chunk
-  // counts (one per thread covers 256 chunks = 1M scores) and the row's short list
+  // counts (one per thread: that covers rows of kTpThreads chunks) and the row's short list
   uint64_t l3_bins[kBins3 / kTpThreads];
   load_bins<kBins3>(a.hist + (int64_t)r * kBinsTotal + kBins1 + kBins2, l3_bins);
   const int cc_mine = tid < a.n_chunks ? a.chunk_cnt[(int64_t)r * a.n_chunks + tid] : 0;
@@ -695,7 +706,7 @@ __global__ __launch_bounds__(kTpThreads) void topp_write_kernel(const TopPArgs a
       total += cc_mine;
       if (tid < c) before += cc_mine;
     }
-    for (int i = tid + kTpThreads; i < n_row_chunks; i += kTpThreads) {      // rows beyond 256 chunks
+    for (int i = tid + kTpThreads; i < n_row_chunks; i += kTpThreads) {      // longer rows
       const int cv = a.chunk_cnt[(int64_t)r * a.n_chunks + i];
       total += cv;
       if (i < c) before += cv;
@@ -742,7 +753,7 @@ __global__ __launch_bounds__(kTpThreads) void topp_write_kernel(const TopPArgs a
     return;
   }
 
-  // ---- attention over this chunk's kept positions: 16 groups of 16 lanes, one K/V row (256 bytes) per
+  // ---- attention over this chunk's kept positions: groups of 16 lanes, one K/V row (256 bytes) per
   // group and load, kSaInFlight rows per group in flight; a lane owns 8 of the 128 dims ----
   __shared__ float sh_m[kTpThreads / 64], sh_l[kTpThreads / 64];
   __shared__ float sh_acc[kTpThreads / 64][kHeadDim];
@@ -762,12 +773,13 @@ __global__ __launch_bounds__(kTpThreads) void topp_write_kernel(const TopPArgs a
   float m = ninf, l = 0.f, acc[8];
 #pragma unroll
   for (int d = 0; d < 8; ++d) acc[d] = 0.f;
-  for (int base = 0; base < kept_here; base += 16 * kSaInFlight) {
+  constexpr int kGroups = kTpThreads / 16;   // 16-lane groups of the workgroup, one K/V row each per load
+  for (int base = 0; base < kept_here; base += kGroups * kSaInFlight) {
     u32x4 kr[kSaInFlight], vr[kSaInFlight];
     bool ok[kSaInFlight];
 #pragma unroll
     for (int u = 0; u < kSaInFlight; ++u) {
-      const int i = base + u * 16 + grp;
+      const int i = base + u * kGroups + grp;
       ok[u] = i < kept_here;
       if (ok[u]) {
         const int64_t pos = sh_list[i];
@@ -859,7 +871,7 @@ __global__ __launch_bounds__(kTpThreads) void topp_write_kernel(const TopPArgs a
 
 // Merges the (row, chunk) partials of one row: 8 slices of 32 lanes walk the chunks slice, slice + 8, ...
 // (each lane owns 4 of the 128 output dims); LDS merges the slices.  Rows without a kept token give zeros.
-__global__ __launch_bounds__(kTpThreads) void select_attend_combine_kernel(const TopPArgs a, const GatherArgs ga) {
+__global__ __launch_bounds__(256) void select_attend_combine_kernel(const TopPArgs a, const GatherArgs ga) {
   __shared__ float sh_m[8], sh_l[8];
   __shared__ float sh_acc[8][kHeadDim];
   const int r = blockIdx.x, tid = threadIdx.x;
@@ -990,7 +1002,7 @@ static int32_t run_select(const char* who, const float* scores, int64_t score_st
   hipLaunchKernelGGL(topp_level_kernel<3>, grid, block, 0, s, a);
   if (attend) {
     hipLaunchKernelGGL(topp_write_kernel<true>, grid, block, 0, s, a, *attend);
-    hipLaunchKernelGGL(select_attend_combine_kernel, dim3((unsigned)R), block, 0, s, a, *attend);
+    hipLaunchKernelGGL(select_attend_combine_kernel, dim3((unsigned)R), dim3(256), 0, s, a, *attend);
   } else {
     hipLaunchKernelGGL(topp_write_kernel<false>, grid, block, 0, s, a, GatherArgs{});
   }

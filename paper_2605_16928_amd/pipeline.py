@@ -63,6 +63,7 @@ class DecodeRun:
         self.ws_topp = ws_alloc(rtp.rtp_topp_workspace_bytes(max(self.R, 1), self.max_ctx))
         rtp.rtp_topp_workspace_init(self.ws_topp)
         self._level1_pending = False
+        self._fork, self._join = (torch.cuda.Event(), torch.cuda.Event()) if torch.cuda.is_available() else (None, None)
         self.ws_sparse = ws_alloc(rtp.rtp_sparse_attn_decode_workspace_bytes(self.desc, self.B, self.max_ctx))
         self.ws_fused = ws_alloc(rtp.rtp_select_attend_decode_workspace_bytes(self.desc, self.B, self.max_ctx))
         self.ws_local = ws_alloc(rtp.rtp_local_attn_workspace_bytes(self.desc, self.B, 1, self.max_ctx))
@@ -140,10 +141,10 @@ class DecodeRun:
         if ready:
             self._level1_pending = False
 
-    def local_attn(self):
+    def local_attn(self, stream=None):
         w = self.w
         rtp.rtp_local_attn(self.desc, w.q, self.Kp, self.Vp, self.kv_rs, self.kv_hs, self.seq_start, self.ctx_len, None,
-                           self.B, 1, self.max_ctx, self.out, self.lse, self.ws_local)
+                           self.B, 1, self.max_ctx, self.out, self.lse, self.ws_local, stream=stream)
 
     def dense_attn(self, out=None, lse=None):
         w = self.w
@@ -168,15 +169,16 @@ class DecodeRun:
         """The same step with the local heads on a second stream: they do not depend on the
         indexer / top-p chain and write disjoint output rows."""
         main = torch.cuda.current_stream()
-        fork, join = torch.cuda.Event(), torch.cuda.Event()
+        # (the two events are made once and the side stream is passed to the call rather than made current:
+        # the host has about as much to do per step as the GPU, so its share is kept small)
+        fork, join = self._fork, self._join
         # the score pass saturates HBM on its own; the local heads start once it is done and overlap
         # the top-p launches, which leave HBM idle
         self.index_score()
         fork.record(main)
         side.wait_event(fork)
-        with torch.cuda.stream(side):
-            self.local_attn()
-            join.record(side)
+        self.local_attn(stream=side)
+        join.record(side)
         self.select_then_attend(fused)
         main.wait_event(join)
 
