@@ -60,12 +60,6 @@ struct RowState {          // one per row and launch (levels 2 and 3 leave one e
 
 constexpr int kBucketCap = 1024;
 
-#ifdef RTP_DBG_CLOCKS
-#define RTP_CLK(KID, K) if (threadIdx.x == 0) reinterpret_cast<uint64_t*>(a.sel_idx + (int64_t)blockIdx.y * a.sel_stride + 65536)[((KID) * 64 + blockIdx.x) * 8 + (K)] = wall_clock64();
-#else
-#define RTP_CLK(KID, K)
-#endif
-
 struct TopPArgs {
   const float* scores;
   int64_t score_stride;
@@ -123,8 +117,7 @@ __device__ __forceinline__ void load_bins(const uint64_t* __restrict__ h, uint64
 
 __device__ __forceinline__ Scan1Result scan_level1(const uint64_t (&loc)[kBins1 / kTpThreads], float p, double* sh_d /*[4]*/,
                                                    int* sh_i /*[4]*/, double* sh_res /*[3]*/,
-                                                   const double* __restrict__ tab /* filled by the caller */,
-                                                   uint64_t* dbg = nullptr) {
+                                                   const double* __restrict__ tab /* filled by the caller */) {
   constexpr int per = kBins1 / kTpThreads;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int first = (kTpThreads - 1 - tid) * per;     // this thread's lowest bin
@@ -142,7 +135,6 @@ __device__ __forceinline__ Scan1Result scan_level1(const uint64_t (&loc)[kBins1 
   Scan1Result res;
   res.bin = -1; res.above_base = 0.0; res.total_d = 0.0; res.target = 1; res.ref = 0.f;
   if (top < 0) { __syncthreads(); return res; }       // uniform: every thread sees the same `top`
-  if (dbg && threadIdx.x == 0) dbg[5] = wall_clock64();
   const double R = (double)bin_ref(top);
   double md[per];
   double sum = 0.0;
@@ -156,7 +148,6 @@ __device__ __forceinline__ Scan1Result scan_level1(const uint64_t (&loc)[kBins1 
     }
     sum += md[i];
   }
-  if (dbg && threadIdx.x == 0) dbg[6] = wall_clock64();
   double incl = wave_incl_scan(sum);                  // this thread's bins and every higher bin of the wave
   if (lane == 63) sh_d[wave] = incl;
   // defaults (nobody crosses): the top bin, nothing above it -- left by the thread that owns that bin
@@ -194,7 +185,6 @@ __device__ __forceinline__ Scan1Result scan_level1(const uint64_t (&loc)[kBins1 
     sh_res[2] = __longlong_as_double((long long)lb);
   }
   __syncthreads();
-  if (dbg && threadIdx.x == 0) dbg[7] = wall_clock64();
   const int b1 = (int)sh_res[0];
   const double above_true = sh_res[1];
   const uint64_t hb = (uint64_t)__double_as_longlong(sh_res[2]);
@@ -329,7 +319,6 @@ __global__ __launch_bounds__(kTpThreads) void topp_level_kernel(const TopPArgs a
   __shared__ double sh_dres[3];
   __shared__ int sh_i[kTpThreads / 64];
   __shared__ double tab[256];
-  RTP_CLK(LEVEL - 2, 0)
   fill_exp_table(tab);
   uint64_t* hrow = a.hist + (int64_t)r * kBinsTotal;
   RowState* st = a.state + (int64_t)r * 3;
@@ -378,12 +367,7 @@ __global__ __launch_bounds__(kTpThreads) void topp_level_kernel(const TopPArgs a
       }
       s.flags = flags;
     } else if (flags == 0) {
-#ifdef RTP_DBG_CLOCKS
-      const Scan1Result s1 = scan_level1(prev_bins, pr, sh_d, sh_i, sh_dres, tab,
-                                         reinterpret_cast<uint64_t*>(a.sel_idx + (int64_t)blockIdx.y * a.sel_stride + 65536) + blockIdx.x * 8);
-#else
       const Scan1Result s1 = scan_level1(prev_bins, pr, sh_d, sh_i, sh_dres, tab);
-#endif
       if (s1.bin < 0) {
         flags = 2;
       } else {
@@ -433,7 +417,6 @@ __global__ __launch_bounds__(kTpThreads) void topp_level_kernel(const TopPArgs a
     clear_level3();
     return;
   }
-  RTP_CLK(LEVEL - 2, 1)
 
   // Levels 2 and 3 weigh only the members of the prefix bin (a few percent of the chunk at level 2,
   // a handful at level 3).  At level 2, weighing them where they sit would run the fp64 arithmetic in
@@ -509,7 +492,6 @@ __global__ __launch_bounds__(kTpThreads) void topp_level_kernel(const TopPArgs a
         if (member & (1u << (u * 4 + k))) sh_list[pos++] = s4[k];
     }
     __syncthreads();
-    RTP_CLK(LEVEL - 2, 2)
     const int total = sh_n;
     for (int i = tid; i < total; i += kTpThreads) {
       const float sv = sh_list[i];
@@ -518,10 +500,8 @@ __global__ __launch_bounds__(kTpThreads) void topp_level_kernel(const TopPArgs a
     }
   }
   __syncthreads();
-  RTP_CLK(LEVEL - 2, 3)
   flush_hist(lh, hrow + kOff, kBins, kTpThreads);
   clear_level3();
-  RTP_CLK(LEVEL - 2, 4)
 }
 
 // ---- launches 4 and 5: final scan + per-chunk counts, then ordered compaction ---------------------
@@ -623,7 +603,6 @@ template <bool ATTEND>
 __global__ __launch_bounds__(kTpThreads) void topp_write_kernel(const TopPArgs a, const GatherArgs ga) {
   const int r = blockIdx.y, c = blockIdx.x, tid = threadIdx.x;
   __shared__ int32_t sh_list[ATTEND ? kTpChunk : 1];
-  RTP_CLK(2, 0)
   // Levels 1 and 2 were last read by the level-2 / level-3 launches; every workgroup of the grid clears its
   // share on its way out (not on its way in: the barriers below would wait for the stores).
   // The same goes for the row's scalar results (chunk 0 stores them at the end).
@@ -696,7 +675,6 @@ __global__ __launch_bounds__(kTpThreads) void topp_write_kernel(const TopPArgs a
   }
   have_res = true;
 
-  RTP_CLK(2, 1)
   // ---- offset of this chunk = kept scores of the chunks before it; chunk 0 also publishes the total ----
   const int n_row_chunks = (n + kTpChunk - 1) / kTpChunk;
   const int listed = prev.flags == 0 ? listed_raw : 0;
@@ -740,7 +718,6 @@ __global__ __launch_bounds__(kTpThreads) void topp_write_kernel(const TopPArgs a
   for (int i = 0; i < kTpThreads / 64; ++i) { before += sh_red[i][0]; total += sh_red[i][1]; }
   res_count = total;
 
-  RTP_CLK(2, 2)
   const uint32_t keep = keep_mask(v, n_here, tid, prev.flags == 1, tkey);
   // ATTEND: the positions go to LDS only for now and to memory after the gather (same reason as above: the
   // gather starts behind a barrier, and every wait for a K/V row would also wait for stores in flight)
@@ -758,7 +735,6 @@ __global__ __launch_bounds__(kTpThreads) void topp_write_kernel(const TopPArgs a
   __shared__ float sh_m[kTpThreads / 64], sh_l[kTpThreads / 64];
   __shared__ float sh_acc[kTpThreads / 64][kHeadDim];
   __syncthreads();                           // the list is complete
-  RTP_CLK(2, 3)
   const int lane = tid & 63, wave = tid >> 6;
   const int grp = wave * 4 + (lane >> 4), piece = lane & 15;
   const int b = r / ga.n_ret;
@@ -821,7 +797,6 @@ __global__ __launch_bounds__(kTpThreads) void topp_write_kernel(const TopPArgs a
       for (int d = 0; d < 8; ++d) acc[d] = fmaf(pw, vf[d], acc[d]);
     }
   }
-  RTP_CLK(2, 4)
   // the four groups of a wave in registers, the four waves through LDS
 #pragma unroll
   for (int o = 16; o <= 32; o <<= 1) {
@@ -866,7 +841,6 @@ __global__ __launch_bounds__(kTpThreads) void topp_write_kernel(const TopPArgs a
     for (int i = tid; i < kept_here; i += kTpThreads) dst[i] = sh_list[i];
   }
   rezero();
-  RTP_CLK(2, 5)
 }
 
 // Merges the (row, chunk) partials of one row: 8 slices of 32 lanes walk the chunks slice, slice + 8, ...
