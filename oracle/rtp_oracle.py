@@ -40,6 +40,10 @@ Widened rows (each pinned the same way, see the end of this file):
     block_topp_select  the block-wise histogram selector of Sec. 3.4, with the readings stated there
     attention_mass     true attention probability captured by a token set        Sec. 4.2, sparsity table
     sparsity_stats     compute / memory sparsity, active tokens                  Sec. 3.2 (last paragraph), Sec. 4.2
+    ring_kv_heads, ring_slot, ring_append, ring_fill, ring_local_attend
+                       the KV cache of a KV head whose query heads are all local keeps only the sink
+                       tokens and the last `window` tokens (Sec. 2.1: the full cache is retained for
+                       retrieval heads only; Sec. 3.2 last paragraph: memory is counted per KV head)
 
 Parity status: every function below is pinned by tests/test_oracle_pins.py
 (brute-force dense attention, hand-worked exact-binary top-p cases, closed
@@ -56,6 +60,7 @@ __all__ = [
     "topp_from_weights", "topp_select", "attend", "local_set", "kv_head_of",
     "decode_layer", "prefill_rows", "dense_rows",
     "build_index_keys", "topk_select", "block_topp_select", "attention_mass", "sparsity_stats",
+    "ring_kv_heads", "ring_slot", "ring_append", "ring_fill", "ring_local_attend",
 ]
 
 
@@ -423,3 +428,46 @@ def sparsity_stats(attended, n_ctx: int, n_q_heads: int, n_kv_heads: int, ret_he
     ret = list(ret_heads)
     active = float(np.mean([sizes[h] for h in ret])) if ret else 0.0
     return dict(compute_sparsity=compute, memory_sparsity=memory, active_tokens=active, union_sizes=unions)
+
+
+# ---- bounded cache of the all-local KV heads --------------------------------------------------------
+# Sec. 2.1 keeps the full KV cache for retrieval heads only; the other heads may drop remote tokens.
+# Under GQA the cache is per KV head (Sec. 3.2, last paragraph), so a KV head can drop them only when
+# every query head mapped to it is local.  Such a head then needs `sink + window` rows per sequence.
+# Reading (the paper does not give a layout): row i < sink holds token i; token t >= sink lives in row
+# sink + (t - sink) mod window, overwriting the token that left the window when t arrived.
+
+def ring_kv_heads(n_q_heads: int, n_kv_heads: int, ret_heads) -> list:
+    """KV heads none of whose query heads is a retrieval head, ascending."""
+    ret = set(int(h) for h in ret_heads)
+    g = n_q_heads // n_kv_heads
+    return [kv for kv in range(n_kv_heads) if not any(h in ret for h in range(kv * g, (kv + 1) * g))]
+
+
+def ring_slot(t: int, sink: int, window: int) -> int:
+    """Row of the bounded cache that token position t occupies."""
+    return int(t) if t < sink else sink + (int(t) - sink) % window
+
+
+def ring_append(ring_K_bits, ring_V_bits, k_row_bits, v_row_bits, t: int, sink: int, window: int) -> None:
+    """Stores token t's K and V rows (uint16 [d]) into the bounded cache (uint16 [sink + window, d]), in place."""
+    s = ring_slot(t, sink, window)
+    ring_K_bits[s] = k_row_bits
+    ring_V_bits[s] = v_row_bits
+
+
+def ring_fill(K_bits, V_bits, n: int, sink: int, window: int):
+    """The bounded cache after tokens 0..n-1 of one KV head (rows of K_bits, V_bits) have been appended
+    in order, written out token by token.  Returns (ring_K, ring_V, rows): rows = how many rows hold a token."""
+    d = K_bits.shape[1]
+    rk = np.zeros((sink + window, d), dtype=np.uint16)
+    rv = np.zeros((sink + window, d), dtype=np.uint16)
+    for t in range(int(n)):
+        ring_append(rk, rv, K_bits[t], V_bits[t], t, sink, window)
+    return rk, rv, min(int(n), sink + window)
+
+
+def ring_local_attend(q_bits, ring_K_bits, ring_V_bits, rows: int, softmax_scale: float):
+    """A local head's attention at decode time read from the bounded cache: softmax attention over its
+    first `rows` rows (a softmax over a set does not depend on the order of its members)."""
+    return attend(q_bits, ring_K_bits, ring_V_bits, np.arange(int(rows)), softmax_scale)

@@ -592,3 +592,50 @@ def test_sparsity_stats_hand_case_and_limits():
         att = [rng.choice(64, size=int(rng.integers(1, 40)), replace=False).tolist() for _ in range(8)]
         r = orc.sparsity_stats(att, 64, 8, 4, ret_heads=[0, 2])
         assert r["memory_sparsity"] <= r["compute_sparsity"] + 1e-15
+
+
+# ---------------------------------------------------------------- bounded cache of all-local KV heads
+def test_ring_kv_heads_hand_cases():
+    """Sec. 2.1 / Sec. 3.2 last paragraph: a KV head may drop remote tokens only if all its query heads are local."""
+    assert orc.ring_kv_heads(32, 8, [0, 8, 16, 24]) == [1, 3, 5, 7]     # the benchmark layer: G = 4
+    assert orc.ring_kv_heads(8, 2, [0, 5]) == []                        # both groups hold a retrieval head
+    assert orc.ring_kv_heads(8, 8, [1, 3]) == [0, 2, 4, 5, 6, 7]        # G = 1
+    assert orc.ring_kv_heads(8, 2, []) == [0, 1]
+
+
+def test_ring_slots_keep_exactly_the_local_set():
+    """Brute force, independent of ring_fill: replay the appends into a dict slot -> token and compare the
+    resident tokens with the sink + window set of the newest position, for contexts below the sink count,
+    below sink + window, equal to it and far above (several wraps)."""
+    for sink, window in ((4, 16), (0, 5), (3, 1), (4, 96)):
+        resident = {}
+        for t in range(0, 3 * (sink + window) + 7):
+            s = orc.ring_slot(t, sink, window)
+            assert 0 <= s < sink + window
+            assert (s == t) if t < sink else (sink <= s)
+            resident[s] = t
+            want = set(int(x) for x in orc.local_set(t, sink, window))    # the set a local head at position t sees
+            assert set(resident.values()) == want, (sink, window, t)
+            # valid rows are a prefix of the buffer
+            assert sorted(resident) == list(range(min(t + 1, sink + window)))
+
+
+def test_ring_fill_and_attention_match_the_full_cache():
+    """The bounded cache holds the same (K, V) rows as the full cache restricted to the local set, so a local
+    head's attention read from it equals its attention read from the full cache (same terms, other order)."""
+    rng = np.random.default_rng(5)
+    d, sink, window = 8, 4, 12
+    for n in (1, 3, 4, 5, 16, 17, 40, 100):
+        K = rng.integers(0x3c00, 0x4100, size=(n, d)).astype(np.uint16)    # bf16 patterns of moderate values
+        V = rng.integers(0xbc00, 0xc100, size=(n, d)).astype(np.uint16)
+        q = rng.integers(0x3c00, 0x4100, size=d).astype(np.uint16)
+        rk, rv, rows = orc.ring_fill(K, V, n, sink, window)
+        assert rows == min(n, sink + window)
+        ids = orc.local_set(n - 1, sink, window)
+        # row contents: token t sits where ring_slot says, bit for bit
+        for t in ids:
+            s = orc.ring_slot(int(t), sink, window)
+            assert np.array_equal(rk[s], K[t]) and np.array_equal(rv[s], V[t])
+        o_ring, lse_ring = orc.ring_local_attend(q, rk, rv, rows, 0.35)
+        o_full, lse_full = orc.attend(q, K, V, ids, 0.35)
+        assert np.allclose(o_ring, o_full, rtol=1e-13, atol=1e-13) and abs(lse_ring - lse_full) < 1e-12
