@@ -188,6 +188,30 @@ def main() -> int:
         ib["append_%d_tokens_us" % T_app] = round(us_ib, 2)
     ib["append_8192_GBps"] = round(8192 * n_ret * (256 + 32) / ib["append_8192_tokens_us"] / 1e3, 1)
 
+    # ---- bounded cache of the KV heads whose query heads are all local (paper Sec. 2.1: the full cache is
+    # kept for retrieval heads only): what it saves and what reading from it costs ----
+    r0 = runs[0]
+    r0.make_ring()
+    cap = L.sink + L.window
+    k_new = torch.randn((B, L.n_kv_heads, 128), device=dev).to(torch.bfloat16)
+    pos_new = torch.full((B,), N - 1, dtype=torch.int32, device=dev)
+    ref_out = r0.out.clone()
+    r0.local_attn_ring()
+    torch.cuda.synchronize()
+    loc_heads = [h for h in range(L.n_q_heads) if h not in L.ret_heads]
+    ring_err = float((r0.out[:, loc_heads].float() - ref_out[:, loc_heads].float()).abs().max())
+    assert ring_err <= 2e-2, f"local attention from the bounded cache differs: {ring_err}"
+    bounded = {
+        "kv_heads_bounded": len(r0.ring_heads), "kv_heads": L.n_kv_heads, "rows_per_sequence": cap,
+        "kv_bytes_per_sequence_full": L.n_kv_heads * N * 512,
+        "kv_bytes_per_sequence_with_bounded_heads": (L.n_kv_heads - len(r0.ring_heads)) * N * 512 + len(r0.ring_heads) * cap * 512,
+        "local_attn_from_bounded_cache_us": round(timed(lambda i: r0.local_attn_ring(), it, wu), 2),
+        "local_attn_from_full_cache_us": round(timed(lambda i: r0.local_attn(), it, wu), 2),
+        "append_one_token_per_sequence_us": round(timed(lambda i: r0.ring_append(k_new, k_new, pos_new), it, wu), 2),
+        "max_abs_diff_vs_full_cache": ring_err,
+    }
+    r0.step()
+
     # ---- algorithmic bytes per step (design notes: per-unit figures x units) ----
     sel_total = int(sel_counts.sum())
     bytes_index = B * n_ret * N * (32 + 4)
@@ -413,6 +437,7 @@ def main() -> int:
             "slowest_call": dom,
             "selectors": selectors,
             "index_key_build": ib,
+            "bounded_cache": bounded,
             "selected_tokens_per_row_mean": round(float(sel_counts.mean()), 1),
             "dense_attn_us": round(dense_us, 2),
             "dense_attn_GBps": round(bytes_dense / dense_us / 1e3, 1),

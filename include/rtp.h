@@ -325,6 +325,48 @@ int32_t rtp_select_attend_decode(const rtp_layer_desc* layer, const float* score
                                  void* topp_ws, size_t topp_ws_bytes, void* attn_ws, size_t attn_ws_bytes,
                                  void* stream);
 
+/* ---------------------------------------------------------------------------------------------
+ * Bounded KV cache of the all-local KV heads, decode -- Sec. 2.1 (the full KV cache is kept for
+ * retrieval heads only, the other heads drop remote tokens) and Sec. 3.2, last paragraph (memory is
+ * counted per KV head: under GQA a KV head can drop them when EVERY query head mapped to it is local).
+ *
+ * Such a KV head keeps cap = sink + window rows per sequence.  Layout (this library's; the paper gives
+ * none): row i < sink holds token i; token t >= sink lives in row sink + (t - sink) mod window.  Row s of
+ * bounded head i (the i-th all-local KV head in ascending order) of sequence b is at
+ * ring_K + i * ring_head_stride + (ring_seq_start[b] + s) * ring_row_stride (bf16, 16-byte aligned,
+ * ring_row_stride >= 128 and a multiple of 8; ring_seq_start: device int64 [B]); ring_V likewise.
+ *
+ *   rtp_kv_ring_heads   host helper: the all-local KV heads (kv_heads: host int32 [n_kv_heads] or NULL);
+ *                       returns their number, -1 on a bad descriptor.
+ *   rtp_kv_ring_append  stores the new token of every sequence: k_new, v_new bf16 [B, n_kv_heads, 128]
+ *                       (post-rotary), pos device int32 [B] = its position (pos < 0: sequence skipped).
+ *   rtp_kv_ring_fill    hand-over after prefill: copies from the full cache (layout of rtp_local_attn)
+ *                       the rows that are inside the bounded cache after ctx_len[b] tokens.
+ *   rtp_local_attn_ring rtp_local_attn for n_q = 1 with the bounded cache as the source of the all-local
+ *                       KV heads: they attend the first min(ctx_len, cap) rows as they lie (a softmax over a
+ *                       set does not depend on the order of its members).  Local heads that share their KV
+ *                       head with a retrieval head still read K, V (the full cache, whose rows for the
+ *                       bounded heads are never touched and need not be backed by memory).
+ *                       Workspace: rtp_local_attn_ring_workspace_bytes(layer, B, max_ctx).
+ */
+int32_t rtp_kv_ring_heads(const rtp_layer_desc* layer, int32_t* kv_heads);
+int32_t rtp_kv_ring_append(const rtp_layer_desc* layer, const void* k_new, const void* v_new,
+                           const int32_t* pos, int32_t B, void* ring_K, void* ring_V,
+                           int64_t ring_row_stride, int64_t ring_head_stride,
+                           const int64_t* ring_seq_start, void* stream);
+int32_t rtp_kv_ring_fill(const rtp_layer_desc* layer, const void* K, const void* V, int64_t kv_row_stride,
+                         int64_t kv_head_stride, const int64_t* seq_start, const int32_t* ctx_len, int32_t B,
+                         void* ring_K, void* ring_V, int64_t ring_row_stride, int64_t ring_head_stride,
+                         const int64_t* ring_seq_start, void* stream);
+size_t rtp_local_attn_ring_workspace_bytes(const rtp_layer_desc* layer, int32_t B, int64_t max_ctx);
+int32_t rtp_local_attn_ring(const rtp_layer_desc* layer, const void* q,
+                            const void* K, const void* V, int64_t kv_row_stride, int64_t kv_head_stride,
+                            const int64_t* seq_start,
+                            const void* ring_K, const void* ring_V, int64_t ring_row_stride,
+                            int64_t ring_head_stride, const int64_t* ring_seq_start,
+                            const int32_t* ctx_len, int32_t B, int64_t max_ctx, void* out, float* lse,
+                            void* ws, size_t ws_bytes, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

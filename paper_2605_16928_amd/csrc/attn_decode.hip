@@ -55,6 +55,13 @@ struct AttnDecodeArgs {
   float* lse;
   int32_t ret_heads[64];
   uint8_t is_ret[128];
+  // local source only: bounded (sink + window rows) cache of the KV heads whose query heads are all local;
+  // NULL = every head reads the full cache.  ring_of_kv[kv] = its index among the bounded heads, or -1.
+  const uint16_t* ringK;
+  const uint16_t* ringV;
+  int64_t ring_row_stride, ring_head_stride;
+  const int64_t* ring_seq_start;
+  int8_t ring_of_kv[128];
 };
 
 template <int SRC>
@@ -205,6 +212,15 @@ __global__ __launch_bounds__(kAdThreads) void attn_decode_kernel(const AttnDecod
     const int32_t* idx = (SRC == kSrcSparse) ? a.sel_idx + (int64_t)unit * a.sel_stride : nullptr;
     const uint16_t* Kb = a.K + (int64_t)kvh * a.head_stride + a.seq_start[b] * a.row_stride + piece * 8;
     const uint16_t* Vb = a.V + (int64_t)kvh * a.head_stride + a.seq_start[b] * a.row_stride + piece * 8;
+    int64_t row_stride = a.row_stride;
+    if (SRC == kSrcLocal && a.ringK && a.ring_of_kv[kvh] >= 0) {
+      // bounded cache: its first n_tok rows are exactly this unit's tokens, in some order
+      const int64_t off = (int64_t)a.ring_of_kv[kvh] * a.ring_head_stride + a.ring_seq_start[b] * a.ring_row_stride + piece * 8;
+      Kb = a.ringK + off;
+      Vb = a.ringV + off;
+      row_stride = a.ring_row_stride;
+      s0 = n_tok;                         // logical token i is row i
+    }
 
     float qv[G][8];
 #pragma unroll
@@ -243,8 +259,8 @@ __global__ __launch_bounds__(kAdThreads) void attn_decode_kernel(const AttnDecod
         else if (SRC == kSrcLocal) pos = i < s0 ? i : w0 + (i - s0);
         else pos = i;
         if (ok[u]) {
-          kr[u] = *reinterpret_cast<const u32x4*>(Kb + (int64_t)pos * a.row_stride);
-          vr[u] = *reinterpret_cast<const u32x4*>(Vb + (int64_t)pos * a.row_stride);
+          kr[u] = *reinterpret_cast<const u32x4*>(Kb + (int64_t)pos * row_stride);
+          vr[u] = *reinterpret_cast<const u32x4*>(Vb + (int64_t)pos * row_stride);
         } else {
           kr[u] = (u32x4){0u, 0u, 0u, 0u};
           vr[u] = (u32x4){0u, 0u, 0u, 0u};
@@ -388,9 +404,18 @@ __global__ __launch_bounds__(kAdThreads) void attn_decode_gqa_kernel(const AttnD
       s0 = max(min(a.sink, n), 0);
       w0 = max(a.sink, n - a.window);
     }
-    auto pos_of = [&](int i) { return SRC == kSrcLocal ? (i < s0 ? i : w0 + (i - s0)) : i; };
     const uint16_t* Kb = a.K + (int64_t)kvh * a.head_stride + a.seq_start[b] * a.row_stride;
     const uint16_t* Vb = a.V + (int64_t)kvh * a.head_stride + a.seq_start[b] * a.row_stride;
+    int64_t row_stride = a.row_stride;
+    if (SRC == kSrcLocal && a.ringK && a.ring_of_kv[kvh] >= 0) {
+      // bounded cache: its first n_tok rows are exactly this unit's tokens, in some order
+      const int64_t off = (int64_t)a.ring_of_kv[kvh] * a.ring_head_stride + a.ring_seq_start[b] * a.ring_row_stride;
+      Kb = a.ringK + off;
+      Vb = a.ringV + off;
+      row_stride = a.ring_row_stride;
+      s0 = n_tok;                         // logical token i is row i
+    }
+    auto pos_of = [&](int i) { return SRC == kSrcLocal ? (i < s0 ? i : w0 + (i - s0)) : i; };
 
     // B operand: column piece = head (zero beyond G), k slice grp * 8 .. + 7 of each 32-dim step
     u32x4 qB[4];
@@ -415,14 +440,14 @@ __global__ __launch_bounds__(kAdThreads) void attn_decode_gqa_kernel(const AttnD
         const int tb = base + tl * (kAdThreads / 64) * kTile;
         // K: lane (token piece, quarter grp) of the tile; rows past the end repeat the last valid one (masked below)
         const int ik = min(tb + piece, t_end - 1);
-        const uint16_t* krow = Kb + (int64_t)pos_of(ik) * a.row_stride + grp * 8;
+        const uint16_t* krow = Kb + (int64_t)pos_of(ik) * row_stride + grp * 8;
 #pragma unroll
         for (int kk = 0; kk < 4; ++kk) kr[tl][kk] = *reinterpret_cast<const u32x4*>(krow + kk * 32);
         // V: round j, lane group grp -> token 4 * grp + j, 8 dims per lane
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
           const int iv = min(tb + 4 * grp + j, t_end - 1);
-          vr[tl][j] = *reinterpret_cast<const u32x4*>(Vb + (int64_t)pos_of(iv) * a.row_stride + piece * 8);
+          vr[tl][j] = *reinterpret_cast<const u32x4*>(Vb + (int64_t)pos_of(iv) * row_stride + piece * 8);
         }
       }
 #pragma unroll
@@ -690,13 +715,25 @@ static void fill_common(AttnDecodeArgs& a, const rtp_layer_desc* L, const HeadTa
   a.lse = lse;
   for (int j = 0; j < 64; ++j) a.ret_heads[j] = ht.ret_heads[j];
   for (int h = 0; h < 128; ++h) a.is_ret[h] = ht.is_ret[h];
+  a.ringK = a.ringV = nullptr;
+  a.ring_row_stride = a.ring_head_stride = 0;
+  a.ring_seq_start = nullptr;
+  for (int h = 0; h < 128; ++h) a.ring_of_kv[h] = -1;
 }
 
 // Decode-mode local / dense attention (called from attn_api.hip).
-int32_t decode_range_attn(const char* who, bool dense, const rtp_layer_desc* L, const void* q, const void* K,
-                          const void* V, int64_t row_stride, int64_t head_stride, const int64_t* seq_start,
-                          const int32_t* ctx_len, int32_t B, int64_t max_ctx, void* out, float* lse, void* ws,
-                          size_t ws_bytes, hipStream_t s) {
+struct RingSource {       // bounded cache of the all-local KV heads (see kv_ring.hip)
+  const void* K;
+  const void* V;
+  int64_t row_stride, head_stride;
+  const int64_t* seq_start;
+};
+int ring_heads_of(const rtp_layer_desc* L, int32_t* heads, int8_t* ring_of_kv);
+
+static int32_t decode_range_attn_from(const char* who, bool dense, const rtp_layer_desc* L, const void* q, const void* K,
+                                      const void* V, int64_t row_stride, int64_t head_stride, const int64_t* seq_start,
+                                      const int32_t* ctx_len, int32_t B, int64_t max_ctx, void* out, float* lse, void* ws,
+                                      size_t ws_bytes, hipStream_t s, const RingSource* ring) {
   HeadTable ht;
   int32_t rc = fill_head_table(L, &ht, who);
   if (rc != RTP_OK) return rc;
@@ -720,7 +757,23 @@ int32_t decode_range_attn(const char* who, bool dense, const rtp_layer_desc* L, 
   a.min_split_blocks = 1;
   a.split_tokens = p.split_tokens;
   a.n_splits = p.n_splits;
+  if (ring) {
+    a.ringK = (const uint16_t*)ring->K;
+    a.ringV = (const uint16_t*)ring->V;
+    a.ring_row_stride = ring->row_stride;
+    a.ring_head_stride = ring->head_stride;
+    a.ring_seq_start = ring->seq_start;
+    ring_heads_of(L, nullptr, a.ring_of_kv);
+  }
   return dense ? launch_decode<kSrcDense>(a, G, p.grid, s, who) : launch_decode<kSrcLocal>(a, G, p.grid, s, who);
+}
+
+int32_t decode_range_attn(const char* who, bool dense, const rtp_layer_desc* L, const void* q, const void* K,
+                          const void* V, int64_t row_stride, int64_t head_stride, const int64_t* seq_start,
+                          const int32_t* ctx_len, int32_t B, int64_t max_ctx, void* out, float* lse, void* ws,
+                          size_t ws_bytes, hipStream_t s) {
+  return decode_range_attn_from(who, dense, L, q, K, V, row_stride, head_stride, seq_start, ctx_len, B, max_ctx, out, lse,
+                                ws, ws_bytes, s, nullptr);
 }
 
 size_t decode_range_ws(bool dense, const rtp_layer_desc* L, int32_t B, int64_t max_ctx) {
@@ -772,4 +825,30 @@ extern "C" int32_t rtp_sparse_attn_decode(const rtp_layer_desc* layer, const voi
   a.split_tokens = 0;
   a.n_splits = 0;
   return launch_decode<kSrcSparse>(a, 1, p.grid, (hipStream_t)stream, who);
+}
+
+extern "C" size_t rtp_local_attn_ring_workspace_bytes(const rtp_layer_desc* layer, int32_t B, int64_t max_ctx) {
+  const size_t w = decode_range_ws(false, layer, B, max_ctx);
+  return w ? w : 256;
+}
+
+extern "C" int32_t rtp_local_attn_ring(const rtp_layer_desc* layer, const void* q,
+                                       const void* K, const void* V, int64_t kv_row_stride, int64_t kv_head_stride,
+                                       const int64_t* seq_start,
+                                       const void* ring_K, const void* ring_V, int64_t ring_row_stride,
+                                       int64_t ring_head_stride, const int64_t* ring_seq_start,
+                                       const int32_t* ctx_len, int32_t B, int64_t max_ctx, void* out, float* lse,
+                                       void* ws, size_t ws_bytes, void* stream) {
+  const char* who = "rtp_local_attn_ring";
+  int32_t rc = check_layer(layer, who);
+  if (rc != RTP_OK) return rc;
+  if (!ring_K || !ring_V || !ring_seq_start) return fail(RTP_ERR_INVALID_ARG, "%s: NULL ring pointer", who);
+  if (((uintptr_t)ring_K & 15) || ((uintptr_t)ring_V & 15))
+    return fail(RTP_ERR_INVALID_ARG, "%s: ring_K and ring_V must be 16-byte aligned", who);
+  if (ring_row_stride < kHeadDim || (ring_row_stride & 7) || (ring_head_stride & 7) || ring_head_stride < 0)
+    return fail(RTP_ERR_INVALID_ARG, "%s: ring_row_stride must be >= 128, ring strides multiples of 8", who);
+  if (layer->window <= 0) return fail(RTP_ERR_INVALID_ARG, "%s: a bounded cache needs window > 0", who);
+  const RingSource ring = {ring_K, ring_V, ring_row_stride, ring_head_stride, ring_seq_start};
+  return decode_range_attn_from(who, false, layer, q, K, V, kv_row_stride, kv_head_stride, seq_start, ctx_len, B, max_ctx,
+                                out, lse, ws, ws_bytes, (hipStream_t)stream, &ring);
 }

@@ -146,6 +146,29 @@ class DecodeRun:
         rtp.rtp_local_attn(self.desc, w.q, self.Kp, self.Vp, self.kv_rs, self.kv_hs, self.seq_start, self.ctx_len, None,
                            self.B, 1, self.max_ctx, self.out, self.lse, self.ws_local, stream=stream)
 
+    def make_ring(self):
+        """Bounded (sink + window rows) cache of the all-local KV heads, filled from the full cache."""
+        L = self.w.layer
+        self.ring_heads = rtp.rtp_kv_ring_heads(self.desc)
+        cap = L.sink + L.window
+        n = max(len(self.ring_heads), 1)
+        self.ring_K = torch.zeros((n, self.B * cap, 128), dtype=torch.bfloat16, device=DEV)
+        self.ring_V = torch.zeros_like(self.ring_K)
+        self.ring_start = i64([b * cap for b in range(self.B)])
+        self.ring_hs = self.B * cap * 128
+        rtp.rtp_kv_ring_fill(self.desc, self.Kp, self.Vp, self.kv_rs, self.kv_hs, self.seq_start, self.ctx_len, self.B,
+                             self.ring_K, self.ring_V, 128, self.ring_hs, self.ring_start)
+
+    def ring_append(self, k_new, v_new, pos):
+        rtp.rtp_kv_ring_append(self.desc, k_new, v_new, pos, self.B, self.ring_K, self.ring_V, 128, self.ring_hs,
+                               self.ring_start)
+
+    def local_attn_ring(self, stream=None):
+        """local_attn with the bounded cache as the source of the all-local KV heads."""
+        rtp.rtp_local_attn_ring(self.desc, self.w.q, self.Kp, self.Vp, self.kv_rs, self.kv_hs, self.seq_start,
+                                self.ring_K, self.ring_V, 128, self.ring_hs, self.ring_start, self.ctx_len, self.B,
+                                self.max_ctx, self.out, self.lse, self.ws_local, stream=stream)
+
     def dense_attn(self, out=None, lse=None):
         w = self.w
         rtp.rtp_dense_attn(self.desc, w.q, self.Kp, self.Vp, self.kv_rs, self.kv_hs, self.seq_start, self.ctx_len, None,

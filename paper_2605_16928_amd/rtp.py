@@ -29,6 +29,8 @@ EXPORTS = [
     "rtp_index_project", "rtp_topk_select",
     "rtp_block_topp_workspace_bytes", "rtp_block_topp_select", "rtp_sparsity_stats",
     "rtp_select_attend_decode_workspace_bytes", "rtp_select_attend_decode",
+    "rtp_kv_ring_heads", "rtp_kv_ring_append", "rtp_kv_ring_fill",
+    "rtp_local_attn_ring_workspace_bytes", "rtp_local_attn_ring",
 ]
 RTP_SIDE_QUERY, RTP_SIDE_KEY = 0, 1
 
@@ -112,6 +114,16 @@ def lib() -> C.CDLL:
     L.rtp_select_attend_decode.restype = i32
     L.rtp_select_attend_decode.argtypes = [dp, vp, i64, vp, vp, i32, i64, vp, vp, vp, i64, i64, vp, vp, i64, vp, vp, vp,
                                            i32, vp, vp, vp, sz, vp, sz, vp]
+    L.rtp_kv_ring_heads.restype = i32
+    L.rtp_kv_ring_heads.argtypes = [dp, vp]
+    L.rtp_kv_ring_append.restype = i32
+    L.rtp_kv_ring_append.argtypes = [dp, vp, vp, vp, i32, vp, vp, i64, i64, vp, vp]
+    L.rtp_kv_ring_fill.restype = i32
+    L.rtp_kv_ring_fill.argtypes = [dp, vp, vp, i64, i64, vp, vp, i32, vp, vp, i64, i64, vp, vp]
+    L.rtp_local_attn_ring_workspace_bytes.restype = sz
+    L.rtp_local_attn_ring_workspace_bytes.argtypes = [dp, i32, i64]
+    L.rtp_local_attn_ring.restype = i32
+    L.rtp_local_attn_ring.argtypes = [dp, vp, vp, vp, i64, i64, vp, vp, vp, i64, i64, vp, vp, i32, i64, vp, vp, vp, sz, vp]
     L.rtp_sparsity_stats.restype = i32
     L.rtp_sparsity_stats.argtypes = [dp, vp, vp, i64, vp, vp, vp, i32, vp, vp, vp]
     _lib = L
@@ -197,6 +209,40 @@ def rtp_select_attend_decode(layer, scores, score_stride, row_len, p, B, max_ctx
                                           _ptr(seq_start), _ptr(sel_idx), sel_stride, _ptr(sel_count), _ptr(tau),
                                           _ptr(mass), level1_ready, _ptr(out), _ptr(lse), _ptr(topp_ws),
                                           _nbytes(topp_ws), _ptr(attn_ws), _nbytes(attn_ws), _stream(stream)))
+
+
+def rtp_kv_ring_heads(layer) -> list:
+    """The KV heads whose query heads are all local (they may live in the bounded cache), ascending."""
+    buf = (C.c_int32 * max(1, layer.n_kv_heads))()
+    n = lib().rtp_kv_ring_heads(C.byref(layer), buf)
+    if n < 0:
+        raise RtpError(RTP_ERR_INVALID_ARG, lib().rtp_last_error().decode())
+    return [int(buf[i]) for i in range(n)]
+
+
+def rtp_kv_ring_append(layer, k_new, v_new, pos, B, ring_K, ring_V, ring_row_stride, ring_head_stride, ring_seq_start,
+                       stream=None):
+    _check(lib().rtp_kv_ring_append(C.byref(layer), _ptr(k_new), _ptr(v_new), _ptr(pos), B, _ptr(ring_K), _ptr(ring_V),
+                                    ring_row_stride, ring_head_stride, _ptr(ring_seq_start), _stream(stream)))
+
+
+def rtp_kv_ring_fill(layer, K, V, kv_row_stride, kv_head_stride, seq_start, ctx_len, B, ring_K, ring_V,
+                     ring_row_stride, ring_head_stride, ring_seq_start, stream=None):
+    _check(lib().rtp_kv_ring_fill(C.byref(layer), _ptr(K), _ptr(V), kv_row_stride, kv_head_stride, _ptr(seq_start),
+                                  _ptr(ctx_len), B, _ptr(ring_K), _ptr(ring_V), ring_row_stride, ring_head_stride,
+                                  _ptr(ring_seq_start), _stream(stream)))
+
+
+def rtp_local_attn_ring_workspace_bytes(layer, B, max_ctx) -> int:
+    return lib().rtp_local_attn_ring_workspace_bytes(C.byref(layer), B, max_ctx)
+
+
+def rtp_local_attn_ring(layer, q, K, V, kv_row_stride, kv_head_stride, seq_start, ring_K, ring_V, ring_row_stride,
+                        ring_head_stride, ring_seq_start, ctx_len, B, max_ctx, out, lse, ws, stream=None):
+    _check(lib().rtp_local_attn_ring(C.byref(layer), _ptr(q), _ptr(K), _ptr(V), kv_row_stride, kv_head_stride,
+                                     _ptr(seq_start), _ptr(ring_K), _ptr(ring_V), ring_row_stride, ring_head_stride,
+                                     _ptr(ring_seq_start), _ptr(ctx_len), B, max_ctx, _ptr(out), _ptr(lse), _ptr(ws),
+                                     _nbytes(ws), _stream(stream)))
 
 
 def rtp_sparse_attn_prefill_workspace_bytes(layer, T, chunk_start) -> int:

@@ -207,6 +207,44 @@ def test_widened_entry_points_argument_checks():
     assert fa(twsb=needt - 1) == rtp.RTP_ERR_WORKSPACE
 
 
+def test_bounded_cache_entry_points_host_side():
+    lib = rtp.lib()
+    vp = C.c_void_p
+    # which KV heads may live in the bounded cache: computed on the host
+    assert rtp.rtp_kv_ring_heads(rtp.layer_desc(n_q_heads=32, n_kv_heads=8, ret_heads=[0, 8, 16, 24], sink=4, window=64)) == [1, 3, 5, 7]
+    assert rtp.rtp_kv_ring_heads(_layer()) == []                     # both KV heads serve a retrieval head
+    assert rtp.rtp_kv_ring_heads(_layer(ret_heads=[])) == [0, 1]
+    L = rtp.layer_desc(n_q_heads=8, n_kv_heads=4, ret_heads=[0, 5], sink=4, window=64)
+    assert rtp.rtp_kv_ring_heads(L) == [1, 3]
+    app = lambda k=A, pos=A, B=2, rk=A, rs=128, hs=128 * 200, rss=A, layer=L: lib.rtp_kv_ring_append(
+        C.byref(layer), vp(k), vp(A), vp(pos), B, vp(rk), vp(A), rs, hs, vp(rss), None)
+    assert app(k=None) == rtp.RTP_ERR_INVALID_ARG
+    assert app(pos=None) == rtp.RTP_ERR_INVALID_ARG
+    assert app(B=0) == rtp.RTP_ERR_INVALID_ARG
+    assert app(rk=None) == rtp.RTP_ERR_INVALID_ARG
+    assert app(rk=A + 4) == rtp.RTP_ERR_INVALID_ARG
+    assert app(rs=100) == rtp.RTP_ERR_INVALID_ARG
+    assert app(rss=None) == rtp.RTP_ERR_INVALID_ARG
+    assert app(layer=rtp.layer_desc(n_q_heads=8, n_kv_heads=4, ret_heads=[0, 5], sink=4, window=0)) == rtp.RTP_ERR_INVALID_ARG
+    fill = lambda K=A, krs=128, ctx=A, B=2, rk=A: lib.rtp_kv_ring_fill(
+        C.byref(L), vp(K), vp(A), krs, 128 * 1000, vp(A), vp(ctx), B, vp(rk), vp(A), 128, 128 * 200, vp(A), None)
+    assert fill(K=None) == rtp.RTP_ERR_INVALID_ARG
+    assert fill(krs=64) == rtp.RTP_ERR_INVALID_ARG
+    assert fill(ctx=None) == rtp.RTP_ERR_INVALID_ARG
+    assert fill(B=0) == rtp.RTP_ERR_INVALID_ARG
+    assert fill(rk=None) == rtp.RTP_ERR_INVALID_ARG
+    need = rtp.rtp_local_attn_ring_workspace_bytes(L, 2, 1000)
+    assert need == rtp.rtp_local_attn_workspace_bytes(L, 2, 1, 1000)
+    att = lambda q=A, rk=A, rrs=128, ws=A, wsb=need: lib.rtp_local_attn_ring(
+        C.byref(L), vp(q), vp(A), vp(A), 128, 128 * 1000, vp(A), vp(rk), vp(A), rrs, 128 * 200, vp(A), vp(A), 2, 1000,
+        vp(A), None, vp(ws), wsb, None)
+    assert att(q=None) == rtp.RTP_ERR_INVALID_ARG
+    assert att(rk=None) == rtp.RTP_ERR_INVALID_ARG
+    assert att(rrs=120) == rtp.RTP_ERR_INVALID_ARG
+    assert att(ws=None) == rtp.RTP_ERR_WORKSPACE
+    assert att(wsb=need - 1) == rtp.RTP_ERR_WORKSPACE
+
+
 def test_missing_library_is_an_error_not_a_fallback(monkeypatch):
     monkeypatch.setattr(rtp, "_lib", None)
     monkeypatch.setattr(rtp, "LIB_PATH", "/nonexistent/librtp.so")

@@ -7,7 +7,7 @@ import torch
 
 from oracle import rtp_oracle as orc
 from paper_2605_16928_amd import rtp, workloads as wl
-from gpu_util import DEV, DecodeRun, oracle_inputs, i32, ws_alloc, layer_desc_of
+from gpu_util import DEV, DecodeRun, oracle_inputs, i32, i64, ws_alloc, layer_desc_of
 
 pytestmark = pytest.mark.gpu
 
@@ -255,3 +255,78 @@ def test_sparsity_stats_match_oracle(ret_heads):
         # the mass comes from two fp32 log-sum-exps of bf16-rounded logits: 1e-3 is their rounding budget
         assert abs(st[b, 3] - float(np.mean(masses))) < 2e-3
         assert np.array_equal(nl[b, :3], st[b, :3]) and np.isnan(nl[b, 3])
+
+
+# ---------------------------------------------------------------------------------------------------
+# bounded (sink + window) cache of the all-local KV heads (Sec. 2.1; Sec. 3.2 last paragraph)
+# ---------------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("heads", [dict(n_q_heads=8, n_kv_heads=4, ret_heads=(0, 5)),      # G = 2, bounded heads 1 and 3
+                                   dict(n_q_heads=8, n_kv_heads=2, ret_heads=(1,)),        # G = 4, bounded head 1
+                                   dict(n_q_heads=4, n_kv_heads=4, ret_heads=(1, 3)),      # G = 1, bounded heads 0 and 2
+                                   dict(n_q_heads=16, n_kv_heads=2, ret_heads=(9,))])      # G = 8, bounded head 0
+def test_bounded_cache_fill_append_and_local_attention(heads):
+    """The bounded cache filled after "prefill" and extended token by token holds the oracle's rows bit for
+    bit; local attention read from it matches the oracle's local attention over the full cache -- with the
+    full cache's rows of the bounded heads overwritten, to show they are never read."""
+    print(f"[case] bounded cache {heads}", flush=True)
+    sink, window = 4, 96
+    cap = sink + window
+    w = wl.small_decode(DEV, seed=51, ctx=(700, 1531, 64, 2048, 3, 100, 101), sink=sink, window=window, **heads)
+    L = w.layer
+    run = DecodeRun(w)
+    ring_heads = rtp.rtp_kv_ring_heads(run.desc)
+    assert ring_heads == orc.ring_kv_heads(L.n_q_heads, L.n_kv_heads, L.ret_heads) and len(ring_heads) > 0
+    n_ring, B = len(ring_heads), w.B
+    ring_K = torch.zeros((n_ring, B * cap + 5, 128), dtype=torch.bfloat16, device=DEV)
+    ring_V = torch.zeros_like(ring_K)
+    ring_start = i64([b * cap + 5 for b in range(B)])                  # (an offset: the start array is honoured)
+    hs = ring_K.shape[1] * 128
+    # "prefill" leaves all but the last two tokens; the last two arrive one decode step at a time
+    rtp.rtp_kv_ring_fill(run.desc, w.K, w.V, 128, w.K.shape[1] * 128, run.seq_start, i32([n - 2 for n in w.ctx_len]), B,
+                         ring_K, ring_V, 128, hs, ring_start)
+    for back in (2, 1):
+        pos = [n - back for n in w.ctx_len]
+        rows = torch.as_tensor([w.seq_start[b] + pos[b] for b in range(B)], device=DEV)
+        k_new = w.K[:, rows].transpose(0, 1).contiguous()             # [B, n_kv_heads, 128]
+        v_new = w.V[:, rows].transpose(0, 1).contiguous()
+        rtp.rtp_kv_ring_append(run.desc, k_new, v_new, i32(pos), B, ring_K, ring_V, 128, hs, ring_start)
+    torch.cuda.synchronize()
+    Kb, Vb = wl.bf16_bits(w.K), wl.bf16_bits(w.V)
+    rKb, rVb = wl.bf16_bits(ring_K), wl.bf16_bits(ring_V)
+    for b in range(B):
+        t0, n = w.seq_start[b], w.ctx_len[b]
+        for i, kv in enumerate(ring_heads):
+            ok, ov, rows_ = orc.ring_fill(Kb[kv, t0:t0 + n], Vb[kv, t0:t0 + n], n, sink, window)
+            r0 = b * cap + 5
+            assert np.array_equal(rKb[i, r0:r0 + rows_], ok[:rows_]) and np.array_equal(rVb[i, r0:r0 + rows_], ov[:rows_])
+
+    # local attention: reference results first (full cache), then from the bounded cache with the full
+    # cache's copies of the bounded heads destroyed
+    run.local_attn()
+    torch.cuda.synchronize()
+    out_full, lse_full = run.out.clone(), run.lse.clone()
+    ref = orc.decode_layer(**oracle_inputs(w))
+    Kp, Vp = w.K.clone(), w.V.clone()
+    Kp[ring_heads] = float("nan")
+    Vp[ring_heads] = float("nan")
+    out = torch.full_like(run.out, 5.0)
+    lse = torch.full_like(run.lse, 5.0)
+    ws = ws_alloc(rtp.rtp_local_attn_ring_workspace_bytes(run.desc, B, run.max_ctx))
+    for rep in range(2):
+        rtp.rtp_local_attn_ring(run.desc, w.q, Kp, Vp, 128, w.K.shape[1] * 128, run.seq_start, ring_K, ring_V, 128, hs,
+                                ring_start, run.ctx_len, B, run.max_ctx, out, lse, ws)
+    torch.cuda.synchronize()
+    got, got_lse = out.float().cpu().numpy().astype(np.float64), lse.cpu().numpy()
+    loc = [h for h in range(L.n_q_heads) if h not in L.ret_heads]
+    G = L.n_q_heads // L.n_kv_heads
+    assert any(h // G in ring_heads for h in loc)
+    for b in range(B):
+        for h in loc:
+            err = np.abs(got[b, h] - ref["out"][b, h])
+            assert (err <= 1e-3 + 2.0 ** -8 * np.abs(ref["out"][b, h])).all(), f"b{b} h{h}: {err.max()}"
+            assert abs(got_lse[b, h] - ref["lse"][b, h]) < 2e-3
+    # retrieval heads' rows are left alone, and the two sources agree up to summation order
+    ret = list(L.ret_heads)
+    assert torch.all(out[:, ret] == 5.0)
+    assert (out[:, loc].float() - out_full[:, loc].float()).abs().max().item() <= 2e-2
+    assert (lse[:, loc] - lse_full[:, loc]).abs().max().item() <= 1e-4
