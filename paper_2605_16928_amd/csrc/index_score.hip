@@ -21,7 +21,10 @@ namespace rtp {
 // histogram takes 4096 so that half as many workgroups zero, scan and flush a 2048-bin LDS histogram
 // (measured on batch 8 x 131072: 27.5 us against 28.4 us with 2048; the plain pass prefers 2048)
 constexpr int kIsThreads = RTP_IS_THREADS;
-constexpr int kIsChunkPlain = 8 * kIsThreads, kIsChunkHist = 16 * kIsThreads;
+#ifndef RTP_IS_HIST_MULT
+#define RTP_IS_HIST_MULT 16
+#endif
+constexpr int kIsChunkPlain = 8 * kIsThreads, kIsChunkHist = RTP_IS_HIST_MULT * kIsThreads;
 #ifndef RTP_IS_BATCH
 #define RTP_IS_BATCH 16
 #endif

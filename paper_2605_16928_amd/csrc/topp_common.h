@@ -10,6 +10,7 @@
 #pragma once
 
 #include "common.h"
+#include "exp2_table.h"
 
 namespace rtp {
 
@@ -38,9 +39,11 @@ __device__ __forceinline__ float score_ref(float s) {
   return __uint_as_float((u | 0x1fffffu) ^ neg);
 }
 
-// 2^(j/256), j < 256: the table behind fixed_weight (256 threads fill it, then a barrier).
+// 2^(j/256), j < 256: the table behind fixed_weight, copied into LDS (256 threads, then a barrier).  The
+// values are constants (exp2_table.h): computing them costs every workgroup a double-precision exp2 per thread
+// at the very start, when all workgroups of a launch do the same thing at once.
 __device__ __forceinline__ void fill_exp_table(double* tab) {
-  if (threadIdx.x < 256) tab[threadIdx.x] = exp2((double)threadIdx.x * 0.00390625);
+  if (threadIdx.x < 256) tab[threadIdx.x] = kExp2Frac256[threadIdx.x];
 }
 
 // exp(x) for x <= 0 as m * 2^e with m in [1, 2): x * 256 / ln 2 = k + f, k integer, f in [0, 1);
@@ -63,7 +66,8 @@ __device__ __forceinline__ double exp_parts(double x, const double* __restrict__
 // below 2^52, so adding 2^52 leaves the rounded integer in the low 52 bits of the sum.
 __device__ __forceinline__ uint64_t fixed_weight(float s, float ref, int shift, const double* __restrict__ tab) {
   int e;
-  const double m = exp_parts((double)s - (double)ref, tab, &e);
+  // s lies in the bin whose upper edge ref is: same binade, so the fp32 difference is exact
+  const double m = exp_parts((double)(s - ref), tab, &e);
   const double r = ldexp(m, shift + e) + 4503599627370496.0;
   return (uint64_t)__double_as_longlong(r) & 0xFFFFFFFFFFFFFull;
 }
