@@ -84,8 +84,9 @@ def main() -> int:
         if args.one_stream:
             r.step()
         else:
-            r.step_two_streams(side2)
+            r.step_fastest(side2)
 
+    carried = runs[0].carries_local_heads      # local heads travel inside the selector's launches: one stream
     for r in runs:
         run_step(r)
     torch.cuda.synchronize()
@@ -151,6 +152,8 @@ def main() -> int:
         "sparse_attn_decode": timed(lambda i: runs[i % n_runs].sparse_attn(), it, wu),
     }
     us_step_separate = timed(lambda i: runs[i % n_runs].step_two_streams(side2, fused=False), it, wu)
+    us_step_two_streams = timed(lambda i: runs[i % n_runs].step_two_streams(side2), it, wu)
+    us_attention_call = timed(lambda i: (runs[i % n_runs].index_score(), runs[i % n_runs].decode_attention()), it, wu) - us_index
     us_topp_standalone = timed(lambda i: runs[i % n_runs].topp(scores=runs[i % n_runs].scores), it, wu)
     dense_us = timed(lambda i: runs[i % len(runs)].dense_attn(runs[i % len(runs)].out), max(10, it // 10), 2)
     eager_us = timed(lambda i: run_step(runs[i % len(runs)]), it, wu)
@@ -260,7 +263,8 @@ def main() -> int:
         u_chain = timed(chain1, it, wu)
         u_sp = timed(lambda i: r1[i % 2].sparse_attn(), it, wu)
         u_lo = timed(lambda i: r1[i % 2].local_attn(), it, wu)
-        u_step = timed(lambda i: r1[i % 2].step_two_streams(side1), it, wu)
+        u_step = timed(lambda i: r1[i % 2].step_fastest(side1), it, wu)
+        u_step2 = timed(lambda i: r1[i % 2].step_two_streams(side1), it, wu)
         u_dense = timed(lambda i: r1[i % 2].dense_attn(r1[i % 2].out), 10, 2)
         b_idx = n_ret * N1 * 36
         decode_1m = {
@@ -268,6 +272,7 @@ def main() -> int:
             "us_per_step": round(u_step, 2),
             "call_us": {"index_score": round(u_idx, 2), "select_attend_decode": round(u_chain - u_idx, 2),
                         "local_attn": round(u_lo, 2)},
+            "two_streams_us_per_step": round(u_step2, 2),
             "separate_calls_us": {"topp_select": round(u_pair - u_idx, 2), "sparse_attn_decode": round(u_sp, 2),
                                   "step": round(timed(lambda i: r1[i % 2].step_two_streams(side1, fused=False), it, wu), 2)},
             "index_score_GBps": round(b_idx / u_idx / 1e3, 1), "index_score_frac_of_hbm_peak": round(b_idx / u_idx / 1e3 / HBM_PEAK_GBS, 4),
@@ -413,7 +418,9 @@ def main() -> int:
         "config": {"workload": f"c2: decode step, batch {B} x context {N}, 32 query / 8 KV heads, head_dim 128, "
                                f"4 retrieval heads (index dim 16, top-p {args.p}), local heads 4 sink + 2048 window",
                    "copies_cycled": args.copies, "launch": launch_mode,
-                   "streams": 1 if args.one_stream else 2},
+                   "calls_per_step": "index_score + decode_attention" if (carried and not args.one_stream) else
+                                     "index_score + select_attend_decode + local_attn",
+                   "streams": 1 if (args.one_stream or carried) else 2},
         "roofline": roofline,
         "cpu_baseline": cpu,
         "prefill_1m": prefill,
@@ -429,6 +436,9 @@ def main() -> int:
             "call_GBps": {"index_score": round(bytes_index / br["index_score"] / 1e3, 1),
                           "select_attend_decode": round((bytes_topp + bytes_sparse) / br["select_attend_decode"] / 1e3, 1),
                           "local_attn": round(bytes_local / br["local_attn"] / 1e3, 1)},
+            "decode_attention_call_us": round(us_attention_call, 2),      # selection + retrieval + local heads, one call
+            "two_streams": {"us_per_step": round(us_step_two_streams, 2),
+                            "what": "index_score, select_attend_decode on the main stream, local_attn on a second stream"},
             "separate_calls": {"us_per_step": round(us_step_separate, 2),
                                "call_us": {k: round(v, 2) for k, v in br_separate.items()},
                                "call_GBps": {"topp_select": round(bytes_topp / br_separate["topp_select"] / 1e3, 1),

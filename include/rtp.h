@@ -326,6 +326,29 @@ int32_t rtp_select_attend_decode(const rtp_layer_desc* layer, const float* score
                                  void* stream);
 
 /* ---------------------------------------------------------------------------------------------
+ * (2) + (3) + (4) in one call for a decode step: everything after the score pass -- Sec. 3.2 (Top-P
+ * selection, attention of the retrieval heads over the selected tokens, sink + window attention of the
+ * other heads).
+ *
+ * The results are those of rtp_select_attend_decode followed by rtp_local_attn (n_q = 1) on the same
+ * tensors.  With 2 or 4 query heads per KV head the local heads' work items are carried by the selector's
+ * second launch, which is latency-bound and leaves HBM idle: one stream, no fork and join, four launches
+ * after the score pass.  Other group sizes run the two parts one after the other.
+ *
+ *   ctx_len   device int32 [B]: cached tokens per sequence (row_len[b * n_ret + j] must equal ctx_len[b]).
+ *   local_ws  rtp_local_attn_workspace_bytes(layer, B, 1, max_ctx) bytes, 256-byte aligned.
+ *   every other argument as in rtp_select_attend_decode.
+ */
+int32_t rtp_decode_attention(const rtp_layer_desc* layer, const float* scores, int64_t score_stride,
+                             const int32_t* row_len, const float* p, const int32_t* ctx_len, int32_t B,
+                             int64_t max_ctx, const void* q, const void* K, const void* V,
+                             int64_t kv_row_stride, int64_t kv_head_stride, const int64_t* seq_start,
+                             int32_t* sel_idx, int64_t sel_stride, int32_t* sel_count,
+                             float* tau, float* mass, int32_t level1_ready, void* out, float* lse,
+                             void* topp_ws, size_t topp_ws_bytes, void* attn_ws, size_t attn_ws_bytes,
+                             void* local_ws, size_t local_ws_bytes, void* stream);
+
+/* ---------------------------------------------------------------------------------------------
  * Bounded KV cache of the all-local KV heads, decode -- Sec. 2.1 (the full KV cache is kept for
  * retrieval heads only, the other heads drop remote tokens) and Sec. 3.2, last paragraph (memory is
  * counted per KV head: under GQA a KV head can drop them when EVERY query head mapped to it is local).

@@ -457,18 +457,16 @@ static void fill_common(AttnDecodeArgs& a, const rtp_layer_desc* L, const HeadTa
 }
 
 // Decode-mode local / dense attention (called from attn_api.hip).
-struct RingSource {       // bounded cache of the all-local KV heads (see kv_ring.hip)
-  const void* K;
-  const void* V;
-  int64_t row_stride, head_stride;
-  const int64_t* seq_start;
-};
 int ring_heads_of(const rtp_layer_desc* L, int32_t* heads, int8_t* ring_of_kv);
 
-static int32_t decode_range_attn_from(const char* who, bool dense, const rtp_layer_desc* L, const void* q, const void* K,
-                                      const void* V, int64_t row_stride, int64_t head_stride, const int64_t* seq_start,
-                                      const int32_t* ctx_len, int32_t B, int64_t max_ctx, void* out, float* lse, void* ws,
-                                      size_t ws_bytes, hipStream_t s, const RingSource* ring) {
+// Checks the arguments of a range-source decode call and fills the kernels' argument block and grid.
+// *launch = false: nothing to compute (no local head).  Also used by the selector's launch that carries the
+// local heads' work items (topp.hip).
+int32_t decode_range_prepare(const char* who, bool dense, const rtp_layer_desc* L, const void* q, const void* K,
+                             const void* V, int64_t row_stride, int64_t head_stride, const int64_t* seq_start,
+                             const int32_t* ctx_len, int32_t B, int64_t max_ctx, void* out, float* lse, void* ws,
+                             size_t ws_bytes, const RingSource* ring, AttnDecodeArgs* args, int* grid, bool* launch) {
+  *launch = false;
   HeadTable ht;
   int32_t rc = fill_head_table(L, &ht, who);
   if (rc != RTP_OK) return rc;
@@ -485,7 +483,7 @@ static int32_t decode_range_attn_from(const char* who, bool dense, const rtp_lay
     return fail(RTP_ERR_WORKSPACE, "%s: workspace of %zu bytes (256-byte aligned) required, got %zu", who, p.ws_bytes, ws_bytes);
   clear_error();
   if (!dense && L->n_ret == L->n_q_heads) return RTP_OK;   // no local head
-  AttnDecodeArgs a;
+  AttnDecodeArgs& a = *args;
   fill_common(a, L, ht, q, K, V, row_stride, head_stride, seq_start, ctx_len, out, lse, ws);
   a.units = p.units;
   a.target_items = 0;
@@ -500,7 +498,23 @@ static int32_t decode_range_attn_from(const char* who, bool dense, const rtp_lay
     a.ring_seq_start = ring->seq_start;
     ring_heads_of(L, nullptr, a.ring_of_kv);
   }
-  return dense ? launch_decode<kSrcDense>(a, G, p.grid, s, who) : launch_decode<kSrcLocal>(a, G, p.grid, s, who);
+  *grid = p.grid;
+  *launch = true;
+  return RTP_OK;
+}
+
+static int32_t decode_range_attn_from(const char* who, bool dense, const rtp_layer_desc* L, const void* q, const void* K,
+                                      const void* V, int64_t row_stride, int64_t head_stride, const int64_t* seq_start,
+                                      const int32_t* ctx_len, int32_t B, int64_t max_ctx, void* out, float* lse, void* ws,
+                                      size_t ws_bytes, hipStream_t s, const RingSource* ring) {
+  AttnDecodeArgs a;
+  int grid = 0;
+  bool launch = false;
+  const int32_t rc = decode_range_prepare(who, dense, L, q, K, V, row_stride, head_stride, seq_start, ctx_len, B, max_ctx,
+                                          out, lse, ws, ws_bytes, ring, &a, &grid, &launch);
+  if (rc != RTP_OK || !launch) return rc;
+  const int G = L->n_q_heads / L->n_kv_heads;
+  return dense ? launch_decode<kSrcDense>(a, G, grid, s, who) : launch_decode<kSrcLocal>(a, G, grid, s, who);
 }
 
 int32_t decode_range_attn(const char* who, bool dense, const rtp_layer_desc* L, const void* q, const void* K,

@@ -73,7 +73,8 @@ __device__ __forceinline__ float row_share(float x) {      // every lane reads l
 // The work items first_item, first_item + item_step, ... of a workgroup of THREADS threads, TILES tiles per wave
 // in flight (alone in its launch the kernel runs 256 threads and 2 tiles: 1, 3 and 4 measured slower).
 template <int G, int SRC, int THREADS, int TILES>
-__device__ __forceinline__ void gqa_decode_items(const AttnDecodeArgs& a, const int first_item, const int item_step) {
+__device__ __forceinline__ void gqa_decode_items(const AttnDecodeArgs& a, const int first_item, const int item_step,
+                                                 const int item_end = -1) {
   static_assert(SRC != kSrcSparse && G >= 2 && G <= 16, "range sources, GQA groups");
   constexpr int kTile = 16;                 // tokens per MFMA tile
   constexpr int kTilesInFlight = TILES;     // 8 x 16-byte loads per lane and tile in flight
@@ -82,7 +83,7 @@ __device__ __forceinline__ void gqa_decode_items(const AttnDecodeArgs& a, const 
   __shared__ float sh_acc[kAdThreads / 64][G][kHeadDim];
 
   const int ST = a.split_tokens;
-  const int n_items = a.units * a.n_splits;
+  const int n_items = item_end >= 0 ? item_end : a.units * a.n_splits;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int grp = lane >> 4, piece = lane & 15;
   const float ninf = -__builtin_huge_valf();
@@ -287,5 +288,23 @@ __device__ __forceinline__ void merge_partials_to_out(const AttnDecodeArgs& a, i
     if (a.lse && tid == 0) a.lse[o] = Lt > 0.f ? (Mt + log2f(Lt)) * 0.6931471805599453f : ninf;
   }
 }
+
+struct RingSource {       // bounded cache of the all-local KV heads (see kv_ring.hip)
+  const void* K;
+  const void* V;
+  int64_t row_stride, head_stride;
+  const int64_t* seq_start;
+};
+
+// attn_decode.hip: argument checks + plan of a range-source (local / dense) decode call, without the launch
+int32_t decode_range_prepare(const char* who, bool dense, const rtp_layer_desc* L, const void* q, const void* K,
+                             const void* V, int64_t row_stride, int64_t head_stride, const int64_t* seq_start,
+                             const int32_t* ctx_len, int32_t B, int64_t max_ctx, void* out, float* lse, void* ws,
+                             size_t ws_bytes, const RingSource* ring, AttnDecodeArgs* args, int* grid, bool* launch);
+int32_t decode_range_attn(const char* who, bool dense, const rtp_layer_desc* L, const void* q, const void* K,
+                          const void* V, int64_t row_stride, int64_t head_stride, const int64_t* seq_start,
+                          const int32_t* ctx_len, int32_t B, int64_t max_ctx, void* out, float* lse, void* ws,
+                          size_t ws_bytes, hipStream_t s);
+size_t decode_range_ws(bool dense, const rtp_layer_desc* L, int32_t B, int64_t max_ctx);
 
 }  // namespace rtp

@@ -26,6 +26,7 @@
 // against 53 us for the separate launches on batch 8 x 131072: a barrier across the chip's dies costs
 // about as much as a kernel boundary.  It is not kept.)
 #include "topp_common.h"
+#include "attn_decode_shared.h"
 
 #include <stdlib.h>
 
@@ -295,11 +296,11 @@ __device__ __forceinline__ void block_count_to(int cnt, int32_t* dst, int* sh_i 
 
 // ---- launches 1-3: one histogram level each ----------------------------------------------------
 template <int LEVEL>
-__global__ __launch_bounds__(kTpThreads) void topp_level_kernel(const TopPArgs a) {
+__device__ __forceinline__ void level_body(const TopPArgs& a, const int c, const int r) {
   constexpr int kBins = LEVEL == 1 ? kBins1 : (LEVEL == 2 ? kBins2 : kBins3);
   constexpr int kShift = LEVEL == 1 ? 21 : (LEVEL == 2 ? 10 : 0);     // key bits below this level's field
   constexpr int kOff = LEVEL == 1 ? 0 : (LEVEL == 2 ? kBins1 : kBins1 + kBins2);
-  const int r = blockIdx.y, c = blockIdx.x, tid = threadIdx.x;
+  const int tid = threadIdx.x;
   // what the previous launch left for this row: in flight before anything else (levels 2 and 3 scan the
   // histogram of the level before in their prologue)
   static_assert(kBins1 == kBins2, "one register array serves the scans of levels 2 and 3");
@@ -502,6 +503,30 @@ __global__ __launch_bounds__(kTpThreads) void topp_level_kernel(const TopPArgs a
   __syncthreads();
   flush_hist(lh, hrow + kOff, kBins, kTpThreads);
   clear_level3();
+}
+
+template <int LEVEL>
+__global__ __launch_bounds__(kTpThreads) void topp_level_kernel(const TopPArgs a) {
+  level_body<LEVEL>(a, blockIdx.x, blockIdx.y);
+}
+
+// A level-2 or level-3 launch with local heads of the same decode step on board (rtp_decode_attention): the
+// first n_ride workgroups run the work items item_lo .. item_hi-1 of the local-attention plan
+// (attn_decode_shared.h), the others are the level's own workgroups.  The selector's middle launches are
+// latency-bound and leave HBM idle, which is where the local heads' K/V rows get streamed; as riders they need
+// no second stream (a fork and a join per step cost more than the overlap they buy).  Two workgroups per
+// compute unit, i.e. at most 128 vector registers: one tile per wave in flight.
+template <int LEVEL, int G>
+__global__ __launch_bounds__(kTpThreads, 4) void topp_level_ride_kernel(const TopPArgs a, const AttnDecodeArgs la,
+                                                                        const int n_ride, const int item_lo,
+                                                                        const int item_hi) {
+  const int bid = blockIdx.x;
+  if (bid < n_ride) {
+    gqa_decode_items<G, kSrcLocal, kTpThreads, 1>(la, item_lo + bid, n_ride, item_hi);
+    return;
+  }
+  const int r = (bid - n_ride) / a.n_chunks;
+  level_body<LEVEL>(a, (bid - n_ride) - r * a.n_chunks, r);
 }
 
 // ---- launches 4 and 5: final scan + per-chunk counts, then ordered compaction ---------------------
@@ -845,7 +870,20 @@ __global__ __launch_bounds__(kTpThreads) void topp_write_kernel(const TopPArgs a
 
 // Merges the (row, chunk) partials of one row: 8 slices of 32 lanes walk the chunks slice, slice + 8, ...
 // (each lane owns 4 of the 128 output dims); LDS merges the slices.  Rows without a kept token give zeros.
-__global__ __launch_bounds__(256) void select_attend_combine_kernel(const TopPArgs a, const GatherArgs ga) {
+// Workgroups past the R rows (rtp_decode_attention only) merge the local heads' partials, one (unit, head) each.
+template <int RIDE_G>
+__global__ __launch_bounds__(256) void select_attend_combine_kernel(const TopPArgs a, const GatherArgs ga,
+                                                                    const AttnDecodeArgs la) {
+  if (RIDE_G > 0 && (int)blockIdx.x >= a.R) {
+    const int blk = (int)blockIdx.x - a.R;
+    const int unit = blk / RIDE_G, hh = blk - unit * RIDE_G;
+    const int b = unit / la.n_kv_heads, h = (unit - b * la.n_kv_heads) * RIDE_G + hh;
+    if (la.is_ret[h]) return;
+    const int i0 = unit * la.n_splits;
+    const int i1 = i0 + (unit_tokens<kSrcLocal>(la, unit) + la.split_tokens - 1) / la.split_tokens;
+    merge_partials_to_out(la, RIDE_G, hh, b, h, i0, i1);
+    return;
+  }
   __shared__ float sh_m[8], sh_l[8];
   __shared__ float sh_acc[8][kHeadDim];
   const int r = blockIdx.x, tid = threadIdx.x;
@@ -929,7 +967,8 @@ static int32_t run_select(const char* who, const float* scores, int64_t score_st
                           const float* p, const int32_t* kcount, int32_t R, int64_t max_len,
                           int32_t* sel_idx, int64_t sel_stride, int32_t* sel_count,
                           float* tau, float* mass, int32_t level1_ready,
-                          void* ws, size_t ws_bytes, void* stream, const GatherArgs* attend = nullptr) {
+                          void* ws, size_t ws_bytes, void* stream, const GatherArgs* attend = nullptr,
+                          const AttnDecodeArgs* ride = nullptr, int ride_G = 0) {
   if (!scores || !row_len || (!p && !kcount) || !sel_idx || !sel_count)
     return fail(RTP_ERR_INVALID_ARG, "%s: NULL tensor pointer", who);
   if (R <= 0 || R > 65535) return fail(RTP_ERR_INVALID_ARG, "%s: R must be in [1, 65535]", who);
@@ -972,11 +1011,29 @@ static int32_t run_select(const char* who, const float* scores, int64_t score_st
     hipLaunchKernelGGL(topp_zero_kernel, dim3((unsigned)((nz + kTpThreads - 1) / kTpThreads)), block, 0, s, a.hist, nz);
     hipLaunchKernelGGL(topp_level_kernel<1>, grid, block, 0, s, a);
   }
-  hipLaunchKernelGGL(topp_level_kernel<2>, grid, block, 0, s, a);
-  hipLaunchKernelGGL(topp_level_kernel<3>, grid, block, 0, s, a);
+  if (ride) {
+    // the local heads' work items travel in the level-2 launch (the longer of the two middle launches; giving
+    // level 3 a share was measured slower: a carried item costs its chain of load rounds whichever launch it is
+    // in); at most one carried workgroup per compute unit
+    const int n_items = ride->units * ride->n_splits;
+    const int n_ride = n_items < 256 ? n_items : 256;
+    const dim3 grid2((unsigned)(n_ride + a.n_chunks * R));
+    if (ride_G == 2) hipLaunchKernelGGL((topp_level_ride_kernel<2, 2>), grid2, block, 0, s, a, *ride, n_ride, 0, n_items);
+    else hipLaunchKernelGGL((topp_level_ride_kernel<2, 4>), grid2, block, 0, s, a, *ride, n_ride, 0, n_items);
+    hipLaunchKernelGGL(topp_level_kernel<3>, grid, block, 0, s, a);
+  } else {
+    hipLaunchKernelGGL(topp_level_kernel<2>, grid, block, 0, s, a);
+    hipLaunchKernelGGL(topp_level_kernel<3>, grid, block, 0, s, a);
+  }
   if (attend) {
     hipLaunchKernelGGL(topp_write_kernel<true>, grid, block, 0, s, a, *attend);
-    hipLaunchKernelGGL(select_attend_combine_kernel, dim3((unsigned)R), dim3(256), 0, s, a, *attend);
+    if (ride) {
+      const dim3 cgrid((unsigned)(R + ride->units * ride_G));
+      if (ride_G == 2) hipLaunchKernelGGL(select_attend_combine_kernel<2>, cgrid, dim3(256), 0, s, a, *attend, *ride);
+      else hipLaunchKernelGGL(select_attend_combine_kernel<4>, cgrid, dim3(256), 0, s, a, *attend, *ride);
+    } else {
+      hipLaunchKernelGGL(select_attend_combine_kernel<0>, dim3((unsigned)R), dim3(256), 0, s, a, *attend, AttnDecodeArgs{});
+    }
   } else {
     hipLaunchKernelGGL(topp_write_kernel<false>, grid, block, 0, s, a, GatherArgs{});
   }
@@ -1008,15 +1065,11 @@ extern "C" size_t rtp_select_attend_decode_workspace_bytes(const rtp_layer_desc*
   return align_up((size_t)B * layer->n_ret * n_chunks * kSaPart * sizeof(float), 256);
 }
 
-extern "C" int32_t rtp_select_attend_decode(const rtp_layer_desc* layer, const float* scores, int64_t score_stride,
-                                            const int32_t* row_len, const float* p, int32_t B, int64_t max_ctx,
-                                            const void* q, const void* K, const void* V, int64_t kv_row_stride,
-                                            int64_t kv_head_stride, const int64_t* seq_start,
-                                            int32_t* sel_idx, int64_t sel_stride, int32_t* sel_count,
-                                            float* tau, float* mass, int32_t level1_ready, void* out, float* lse,
-                                            void* topp_ws, size_t topp_ws_bytes, void* attn_ws, size_t attn_ws_bytes,
-                                            void* stream) {
-  const char* who = "rtp_select_attend_decode";
+// Argument checks of the selection + attention call and its gather arguments (shared by the two entry points).
+static int32_t prepare_select_attend(const char* who, const rtp_layer_desc* layer, const float* p, int32_t B, int64_t max_ctx,
+                                     const void* q, const void* K, const void* V, int64_t kv_row_stride,
+                                     int64_t kv_head_stride, const int64_t* seq_start, void* out, float* lse,
+                                     void* attn_ws, size_t attn_ws_bytes, GatherArgs* ga, int64_t* R) {
   HeadTable ht;
   int32_t rc = fill_head_table(layer, &ht, who);
   if (rc != RTP_OK) return rc;
@@ -1026,28 +1079,85 @@ extern "C" int32_t rtp_select_attend_decode(const rtp_layer_desc* layer, const f
   if (((uintptr_t)q & 15) || ((uintptr_t)K & 15) || ((uintptr_t)V & 15) || ((uintptr_t)out & 15))
     return fail(RTP_ERR_INVALID_ARG, "%s: q, K, V and out must be 16-byte aligned", who);
   if (B <= 0) return fail(RTP_ERR_INVALID_ARG, "%s: B must be positive", who);
-  if (layer->n_ret == 0) { clear_error(); return RTP_OK; }
-  const int64_t R = (int64_t)B * layer->n_ret;
-  if (R > 65535) return fail(RTP_ERR_INVALID_ARG, "%s: B * n_ret is limited to 65535", who);
+  *R = (int64_t)B * layer->n_ret;
+  if (*R > 65535) return fail(RTP_ERR_INVALID_ARG, "%s: B * n_ret is limited to 65535", who);
+  if (layer->n_ret == 0) return RTP_OK;
   const size_t need = rtp_select_attend_decode_workspace_bytes(layer, B, max_ctx);
   if (!attn_ws || ((uintptr_t)attn_ws & 255) || attn_ws_bytes < need)
     return fail(RTP_ERR_WORKSPACE, "%s: attention workspace of %zu bytes (256-byte aligned) required, got %zu", who, need,
                 attn_ws_bytes);
+  ga->q = (const uint16_t*)q;
+  ga->K = (const uint16_t*)K;
+  ga->V = (const uint16_t*)V;
+  ga->row_stride = kv_row_stride;
+  ga->head_stride = kv_head_stride;
+  ga->seq_start = seq_start;
+  ga->n_q_heads = layer->n_q_heads;
+  ga->n_kv_heads = layer->n_kv_heads;
+  ga->n_ret = layer->n_ret;
+  ga->scale_log2 = softmax_scale_of(layer) * 1.4426950408889634f;
+  ga->part = (float*)attn_ws;
+  ga->out = (uint16_t*)out;
+  ga->lse = lse;
+  for (int j = 0; j < 64; ++j) ga->ret_heads[j] = ht.ret_heads[j];
+  return RTP_OK;
+}
+
+extern "C" int32_t rtp_select_attend_decode(const rtp_layer_desc* layer, const float* scores, int64_t score_stride,
+                                            const int32_t* row_len, const float* p, int32_t B, int64_t max_ctx,
+                                            const void* q, const void* K, const void* V, int64_t kv_row_stride,
+                                            int64_t kv_head_stride, const int64_t* seq_start,
+                                            int32_t* sel_idx, int64_t sel_stride, int32_t* sel_count,
+                                            float* tau, float* mass, int32_t level1_ready, void* out, float* lse,
+                                            void* topp_ws, size_t topp_ws_bytes, void* attn_ws, size_t attn_ws_bytes,
+                                            void* stream) {
+  const char* who = "rtp_select_attend_decode";
   GatherArgs ga;
-  ga.q = (const uint16_t*)q;
-  ga.K = (const uint16_t*)K;
-  ga.V = (const uint16_t*)V;
-  ga.row_stride = kv_row_stride;
-  ga.head_stride = kv_head_stride;
-  ga.seq_start = seq_start;
-  ga.n_q_heads = layer->n_q_heads;
-  ga.n_kv_heads = layer->n_kv_heads;
-  ga.n_ret = layer->n_ret;
-  ga.scale_log2 = softmax_scale_of(layer) * 1.4426950408889634f;
-  ga.part = (float*)attn_ws;
-  ga.out = (uint16_t*)out;
-  ga.lse = lse;
-  for (int j = 0; j < 64; ++j) ga.ret_heads[j] = ht.ret_heads[j];
+  int64_t R = 0;
+  const int32_t rc = prepare_select_attend(who, layer, p, B, max_ctx, q, K, V, kv_row_stride, kv_head_stride, seq_start, out,
+                                           lse, attn_ws, attn_ws_bytes, &ga, &R);
+  if (rc != RTP_OK) return rc;
+  if (layer->n_ret == 0) { clear_error(); return RTP_OK; }
   return run_select(who, scores, score_stride, row_len, p, nullptr, (int32_t)R, max_ctx, sel_idx, sel_stride, sel_count,
                     tau, mass, level1_ready, topp_ws, topp_ws_bytes, stream, &ga);
+}
+
+extern "C" int32_t rtp_decode_attention(const rtp_layer_desc* layer, const float* scores, int64_t score_stride,
+                                        const int32_t* row_len, const float* p, const int32_t* ctx_len, int32_t B,
+                                        int64_t max_ctx, const void* q, const void* K, const void* V,
+                                        int64_t kv_row_stride, int64_t kv_head_stride, const int64_t* seq_start,
+                                        int32_t* sel_idx, int64_t sel_stride, int32_t* sel_count,
+                                        float* tau, float* mass, int32_t level1_ready, void* out, float* lse,
+                                        void* topp_ws, size_t topp_ws_bytes, void* attn_ws, size_t attn_ws_bytes,
+                                        void* local_ws, size_t local_ws_bytes, void* stream) {
+  const char* who = "rtp_decode_attention";
+  GatherArgs ga;
+  int64_t R = 0;
+  int32_t rc = prepare_select_attend(who, layer, p, B, max_ctx, q, K, V, kv_row_stride, kv_head_stride, seq_start, out, lse,
+                                     attn_ws, attn_ws_bytes, &ga, &R);
+  if (rc != RTP_OK) return rc;
+  AttnDecodeArgs la;
+  int lgrid = 0;
+  bool have_local = false;
+  rc = decode_range_prepare(who, false, layer, q, K, V, kv_row_stride, kv_head_stride, seq_start, ctx_len, B, max_ctx, out,
+                            lse, local_ws, local_ws_bytes, nullptr, &la, &lgrid, &have_local);
+  if (rc != RTP_OK) return rc;
+  const int G = layer->n_q_heads / layer->n_kv_heads;
+  hipStream_t s = (hipStream_t)stream;
+  if (layer->n_ret == 0) {               // nothing to select: the local heads are the whole layer
+    return have_local ? decode_range_attn(who, false, layer, q, K, V, kv_row_stride, kv_head_stride, seq_start, ctx_len, B,
+                                          max_ctx, out, lse, local_ws, local_ws_bytes, s)
+                      : RTP_OK;
+  }
+  const bool ride = have_local && (G == 2 || G == 4);
+  if (!ride) {
+    // group sizes the carried form does not cover: the two parts one after the other
+    rc = run_select(who, scores, score_stride, row_len, p, nullptr, (int32_t)R, max_ctx, sel_idx, sel_stride, sel_count, tau,
+                    mass, level1_ready, topp_ws, topp_ws_bytes, stream, &ga);
+    if (rc != RTP_OK || !have_local) return rc;
+    return decode_range_attn(who, false, layer, q, K, V, kv_row_stride, kv_head_stride, seq_start, ctx_len, B, max_ctx, out,
+                             lse, local_ws, local_ws_bytes, s);
+  }
+  return run_select(who, scores, score_stride, row_len, p, nullptr, (int32_t)R, max_ctx, sel_idx, sel_stride, sel_count, tau,
+                    mass, level1_ready, topp_ws, topp_ws_bytes, stream, &ga, &la, G);
 }

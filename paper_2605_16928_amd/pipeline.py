@@ -141,6 +141,38 @@ class DecodeRun:
         if ready:
             self._level1_pending = False
 
+    def decode_attention(self):
+        """Everything of the step after the score pass as one call: selection, retrieval-head attention and the
+        local heads (their work items travel inside the selector's launches)."""
+        w = self.w
+        ready = 1 if self._level1_pending else 0
+        rtp.rtp_decode_attention(self.desc, self.scores, self.stride, self.row_len, w.p_rows, self.ctx_len, self.B,
+                                 self.max_ctx, w.q, self.Kp, self.Vp, self.kv_rs, self.kv_hs, self.seq_start,
+                                 self.sel_idx, self.stride, self.sel_count, self.tau, self.mass, self.out, self.lse,
+                                 self.ws_topp, self.ws_fused, self.ws_local, level1_ready=ready)
+        if ready:
+            self._level1_pending = False
+
+    def step_one_stream(self):
+        """One decode step as two calls on one stream: the score pass, then rtp_decode_attention."""
+        self.index_score()
+        self.decode_attention()
+
+    @property
+    def carries_local_heads(self) -> bool:
+        """Whether rtp_decode_attention carries the local heads inside the selector's launches for this layer
+        (2 or 4 query heads per KV head, at least one retrieval and one local head)."""
+        L = self.w.layer
+        return L.n_q_heads // L.n_kv_heads in (2, 4) and 0 < L.n_ret < L.n_q_heads
+
+    def step_fastest(self, side: "torch.cuda.Stream"):
+        """The step in the form the benchmark times: one stream where the local heads can be carried, else the
+        local heads on a second stream."""
+        if self.carries_local_heads:
+            self.step_one_stream()
+        else:
+            self.step_two_streams(side)
+
     def local_attn(self, stream=None):
         w = self.w
         rtp.rtp_local_attn(self.desc, w.q, self.Kp, self.Vp, self.kv_rs, self.kv_hs, self.seq_start, self.ctx_len, None,

@@ -29,6 +29,7 @@ EXPORTS = [
     "rtp_index_project", "rtp_topk_select",
     "rtp_block_topp_workspace_bytes", "rtp_block_topp_select", "rtp_sparsity_stats",
     "rtp_select_attend_decode_workspace_bytes", "rtp_select_attend_decode",
+    "rtp_decode_attention",
     "rtp_kv_ring_heads", "rtp_kv_ring_append", "rtp_kv_ring_fill",
     "rtp_local_attn_ring_workspace_bytes", "rtp_local_attn_ring",
 ]
@@ -114,6 +115,9 @@ def lib() -> C.CDLL:
     L.rtp_select_attend_decode.restype = i32
     L.rtp_select_attend_decode.argtypes = [dp, vp, i64, vp, vp, i32, i64, vp, vp, vp, i64, i64, vp, vp, i64, vp, vp, vp,
                                            i32, vp, vp, vp, sz, vp, sz, vp]
+    L.rtp_decode_attention.restype = i32
+    L.rtp_decode_attention.argtypes = [dp, vp, i64, vp, vp, vp, i32, i64, vp, vp, vp, i64, i64, vp, vp, i64, vp, vp, vp,
+                                       i32, vp, vp, vp, sz, vp, sz, vp, sz, vp]
     L.rtp_kv_ring_heads.restype = i32
     L.rtp_kv_ring_heads.argtypes = [dp, vp]
     L.rtp_kv_ring_append.restype = i32
@@ -209,6 +213,16 @@ def rtp_select_attend_decode(layer, scores, score_stride, row_len, p, B, max_ctx
                                           _ptr(seq_start), _ptr(sel_idx), sel_stride, _ptr(sel_count), _ptr(tau),
                                           _ptr(mass), level1_ready, _ptr(out), _ptr(lse), _ptr(topp_ws),
                                           _nbytes(topp_ws), _ptr(attn_ws), _nbytes(attn_ws), _stream(stream)))
+
+
+def rtp_decode_attention(layer, scores, score_stride, row_len, p, ctx_len, B, max_ctx, q, K, V, kv_row_stride,
+                         kv_head_stride, seq_start, sel_idx, sel_stride, sel_count, tau, mass, out, lse,
+                         topp_ws, attn_ws, local_ws, level1_ready=0, stream=None):
+    _check(lib().rtp_decode_attention(C.byref(layer), _ptr(scores), score_stride, _ptr(row_len), _ptr(p), _ptr(ctx_len),
+                                      B, max_ctx, _ptr(q), _ptr(K), _ptr(V), kv_row_stride, kv_head_stride,
+                                      _ptr(seq_start), _ptr(sel_idx), sel_stride, _ptr(sel_count), _ptr(tau), _ptr(mass),
+                                      level1_ready, _ptr(out), _ptr(lse), _ptr(topp_ws), _nbytes(topp_ws), _ptr(attn_ws),
+                                      _nbytes(attn_ws), _ptr(local_ws), _nbytes(local_ws), _stream(stream)))
 
 
 def rtp_kv_ring_heads(layer) -> list:

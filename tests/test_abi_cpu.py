@@ -205,6 +205,18 @@ def test_widened_entry_points_argument_checks():
     assert fa(aws=None) == rtp.RTP_ERR_WORKSPACE
     assert fa(awsb=needa - 1) == rtp.RTP_ERR_WORKSPACE
     assert fa(twsb=needt - 1) == rtp.RTP_ERR_WORKSPACE
+    # ... and with the local heads in the same call
+    needl = rtp.rtp_local_attn_workspace_bytes(L, 2, 1, 1000)
+    da = lambda scores=A, ctx=A, q=A, aws=A, awsb=needa, lws=A, lwsb=needl, twsb=needt: lib.rtp_decode_attention(
+        C.byref(L), vp(scores), 1000, vp(A), vp(A), vp(ctx), 2, 1000, vp(q), vp(A), vp(A), 128, 128 * 1000, vp(A),
+        vp(A), 1000, vp(A), None, None, 0, vp(A), None, vp(A), twsb, vp(aws), awsb, vp(lws), lwsb, None)
+    assert da(scores=None) == rtp.RTP_ERR_INVALID_ARG
+    assert da(ctx=None) == rtp.RTP_ERR_INVALID_ARG
+    assert da(q=A + 2) == rtp.RTP_ERR_INVALID_ARG
+    assert da(aws=None) == rtp.RTP_ERR_WORKSPACE
+    assert da(lws=None) == rtp.RTP_ERR_WORKSPACE
+    assert da(lwsb=needl - 1) == rtp.RTP_ERR_WORKSPACE
+    assert da(twsb=needt - 1) == rtp.RTP_ERR_WORKSPACE
 
 
 def test_bounded_cache_entry_points_host_side():

@@ -338,7 +338,10 @@ def test_select_attend_degenerate_rows():
         run.lse.fill_(7.0)
         run.index_score()
         run.scores[dead, :] = float("-inf")
-        run.select_attend()
+        if rep == 0:
+            run.select_attend()
+        else:
+            run.decode_attention()             # the same with the local heads on board
         sets, cnt = run.sel_sets()
         assert cnt[0] == w.ctx_len[0] and cnt[1] == -1 and cnt[5] == -1 and cnt[dead] == 0
         out, lse = run.out_f64(), run.lse.cpu().numpy()
@@ -351,3 +354,42 @@ def test_select_attend_degenerate_rows():
             else:
                 check_out(out[b, h], ref[(b, h)][0], f"row {r}")
                 assert abs(lse[b, h] - ref[(b, h)][1]) < 2e-3
+
+
+@pytest.mark.parametrize("name", ["small", "g1", "g2", "c2_small", "c5_small"])
+def test_decode_attention_in_one_call_matches_oracle(name):
+    """rtp_decode_attention: everything after the score pass -- the layer's output (retrieval and local rows)
+    against the oracle end to end, the selection bit-identical to rtp_topp_select's, twice in a row.  The cases
+    cover the carried form (G = 2, 4) and the fall-back (G = 1, 8)."""
+    print(f"[case] decode attention in one call {name}", flush=True)
+    w = _cases()[name]()
+    L = w.layer
+    oi = oracle_inputs(w)
+    ref = orc.decode_layer(**oi)
+    two = DecodeRun(w)
+    two.index_score()
+    two.topp()
+    torch.cuda.synchronize()
+    run = DecodeRun(w)
+    for rep in range(2):
+        run.sel_idx.fill_(-1)
+        run.sel_count.fill_(-9)
+        run.out.fill_(3.0)
+        run.lse.fill_(3.0)
+        run.step_one_stream()
+        sets, cnt = run.sel_sets()
+        assert torch.equal(run.sel_count, two.sel_count) and torch.equal(run.tau, two.tau)
+        for r in range(run.R):
+            assert torch.equal(run.sel_idx[r, :cnt[r]], two.sel_idx[r, :cnt[r]])
+        out, lse = run.out_f64(), run.lse.cpu().numpy()
+        # retrieval rows: the oracle's attention over the GPU's sets; local rows: the oracle's layer
+        att = _attend_reference(w, oi, sets)
+        for b in range(w.B):
+            for h in range(L.n_q_heads):
+                if h in L.ret_heads:
+                    o, l = att[(b, h)]
+                else:
+                    o, l = ref["out"][b, h], ref["lse"][b, h]
+                check_out(out[b, h], o, f"{name} b{b} h{h}")
+                assert abs(lse[b, h] - l) < 2e-3
+        check_out(out, ref["out"], f"{name} layer")

@@ -19,7 +19,7 @@ def _decode_fullsize(w, n_local_samples=24, n_dense_samples=2, seed=0):
     G = L.n_q_heads // L.n_kv_heads
     run = DecodeRun(w)
     side = torch.cuda.Stream()
-    run.step_two_streams(side)
+    run.step_fastest(side)
     torch.cuda.synchronize()
     s_gpu = run.scores.cpu().numpy()
     sets, cnt = run.sel_sets()
