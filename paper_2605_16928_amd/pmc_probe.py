@@ -33,8 +33,9 @@ def decode():
     for _ in range(3):
         dst.copy_(src)
     for _ in range(5):
-        run.step()                                  # selection + retrieval-head attention as one call
-        run.step(fused=False)                       # ... and as two calls
+        run.step_one_stream()                       # score pass + rtp_decode_attention (local heads carried)
+        run.step()                                  # selection + retrieval-head attention as one call, local heads apart
+        run.step(fused=False)                       # ... and selection and attention as two calls
         run.dense_attn(run.out)
     torch.cuda.synchronize()
     print("copy bytes per launch:", n * 4, "read and", n * 4, "written")
