@@ -45,7 +45,9 @@ struct IndexScoreArgs {
   float* scores;
   int64_t score_stride;
   uint16_t* qI_out;
-  uint64_t* hist;          // level-1 histograms [rows, kBinsTotal] or NULL
+  uint64_t* hist;          // level-1 histograms of the selector's workspace or NULL
+  int64_t hist_stride;     // words per row; n_sub copies of level 1 per row (topp_common.h)
+  int32_t n_sub;
   int32_t ret_heads[64];
 };
 
@@ -160,7 +162,8 @@ __global__ __launch_bounds__(kIsThreads) void index_score_kernel(const IndexScor
   }
   if (HIST) {
     __syncthreads();
-    flush_hist(lh, a.hist + ((int64_t)bj * a.n_q + t) * kBinsTotal, kBins1, kIsThreads);
+    flush_hist(lh, a.hist + ((int64_t)bj * a.n_q + t) * a.hist_stride + level1_copy_offset((int)(blockIdx.x % a.n_sub)), kBins1,
+               kIsThreads);
   }
 }
 
@@ -189,6 +192,8 @@ extern "C" int32_t rtp_index_score(const rtp_layer_desc* layer, const void* q_in
   if (((uintptr_t)scores & 15) || ((uintptr_t)kI & 15) || (kI_head_stride & 7) || kI_head_stride < 0)
     return fail(RTP_ERR_INVALID_ARG, "%s: scores/kI must be 16-byte aligned, kI_head_stride a multiple of 8", who);
   uint64_t* hist = nullptr;
+  int64_t hist_stride = 0;
+  int32_t n_sub = 1;
   if (topp_ws) {
     const int64_t rows = (int64_t)B * layer->n_ret * n_q;
     if (rows > 65535) return fail(RTP_ERR_INVALID_ARG, "%s: more than 65535 score rows", who);
@@ -197,12 +202,16 @@ extern "C" int32_t rtp_index_score(const rtp_layer_desc* layer, const void* q_in
       return fail(RTP_ERR_WORKSPACE, "%s: top-p workspace of %zu bytes (256-byte aligned) required, got %zu", who,
                   l.total, topp_ws_bytes);
     hist = (uint64_t*)((char*)topp_ws + l.hist_off);
+    hist_stride = l.hist_stride;
+    n_sub = l.n_sub;
   }
   clear_error();
   if (layer->n_ret == 0) return RTP_OK;
 
   IndexScoreArgs a;
   a.hist = hist;
+  a.hist_stride = hist_stride;
+  a.n_sub = n_sub;
   a.q_in = (const uint16_t*)q_in;
   a.WQ = WQ;
   a.kI = (const uint16_t*)kI;

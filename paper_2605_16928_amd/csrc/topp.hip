@@ -77,7 +77,9 @@ struct TopPArgs {
   float* tau;
   float* mass;
   int32_t* chunk_cnt;      // [R, n_chunks]: scores of the chunk strictly above the level-2 prefix (or all finite ones)
-  uint64_t* hist;          // [R, kBinsTotal]
+  uint64_t* hist;          // [R, hist_stride]
+  int64_t hist_stride;
+  int32_t n_sub;           // copies of level 1 per row (topp_common.h)
   RowState* state;         // [R, 3]
   int32_t* bucket_n;       // [R]: scores that share the level-2 prefix (may exceed kBucketCap)
   uint2* bucket;           // [R, kBucketCap]: (key, position) of the first kBucketCap of them
@@ -87,7 +89,9 @@ TopPLayout topp_layout(int32_t R, int64_t max_len) {
   const int64_t n_chunks = (max_len + kTpChunk - 1) / kTpChunk;
   TopPLayout l;
   size_t off = 0;
-  l.hist_off = off;  off = align_up(off + (size_t)R * kBinsTotal * sizeof(uint64_t), 256);
+  l.n_sub = R >= 16 ? 1 : (R >= 8 ? 2 : (R >= 4 ? 4 : 8));
+  l.hist_stride = kBinsTotal + (int64_t)(l.n_sub - 1) * kBins1;
+  l.hist_off = off;  off = align_up(off + (size_t)R * l.hist_stride * sizeof(uint64_t), 256);
   l.ccnt_off = off;  off = align_up(off + (size_t)R * n_chunks * sizeof(int32_t), 256);
   l.state_off = off; off = align_up(off + (size_t)R * 3 * sizeof(RowState), 256);
   l.bn_off = off;    off = align_up(off + (size_t)R * sizeof(int32_t), 256);
@@ -305,7 +309,15 @@ __device__ __forceinline__ void level_body(const TopPArgs& a, const int c, const
   // histogram of the level before in their prologue)
   static_assert(kBins1 == kBins2, "one register array serves the scans of levels 2 and 3");
   uint64_t prev_bins[kBins1 / kTpThreads];
-  if (LEVEL >= 2) load_bins<kBins1>(a.hist + (int64_t)r * kBinsTotal + (LEVEL == 3 ? kBins1 : 0), prev_bins);
+  if (LEVEL >= 2) load_bins<kBins1>(a.hist + (int64_t)r * a.hist_stride + (LEVEL == 3 ? kBins1 : 0), prev_bins);
+  if (LEVEL == 2) {      // level 1 may be spread over several copies
+    for (int sub = 1; sub < a.n_sub; ++sub) {
+      uint64_t more[kBins1 / kTpThreads];
+      load_bins<kBins1>(a.hist + (int64_t)r * a.hist_stride + level1_copy_offset(sub), more);
+#pragma unroll
+      for (int i = 0; i < kBins1 / kTpThreads; ++i) prev_bins[i] += more[i];
+    }
+  }
   const int n = a.row_len[r];
   const int64_t n0 = (int64_t)c * kTpChunk;
   if (n0 >= n || n <= 0) return;
@@ -321,7 +333,7 @@ __device__ __forceinline__ void level_body(const TopPArgs& a, const int c, const
   __shared__ int sh_i[kTpThreads / 64];
   __shared__ double tab[256];
   fill_exp_table(tab);
-  uint64_t* hrow = a.hist + (int64_t)r * kBinsTotal;
+  uint64_t* hrow = a.hist + (int64_t)r * a.hist_stride;
   RowState* st = a.state + (int64_t)r * 3;
   // Level 3's histogram and the row's short list are written by the NEXT launch and were last read by the
   // write launch of the previous call: the level-2 launch clears them -- as the last thing it does, because a
@@ -501,7 +513,7 @@ __device__ __forceinline__ void level_body(const TopPArgs& a, const int c, const
     }
   }
   __syncthreads();
-  flush_hist(lh, hrow + kOff, kBins, kTpThreads);
+  flush_hist(lh, hrow + (LEVEL == 1 ? level1_copy_offset(c % a.n_sub) : kOff), kBins, kTpThreads);
   clear_level3();
 }
 
@@ -641,13 +653,14 @@ __global__ __launch_bounds__(kTpThreads) void topp_write_kernel(const TopPArgs a
       if (a.mass) a.mass[r] = res_mass;
     }
     if (!a.rezero) return;
-    uint64_t* h = a.hist + (int64_t)r * kBinsTotal;
+    uint64_t* h = a.hist + (int64_t)r * a.hist_stride;
     for (int i = c * kTpThreads + tid; i < kBins1 + kBins2; i += a.n_chunks * kTpThreads) h[i] = 0;
+    for (int i = kBinsTotal + c * kTpThreads + tid; i < a.hist_stride; i += a.n_chunks * kTpThreads) h[i] = 0;
   };
   // what the level-3 launch left for this row, in flight before anything else: its histogram, the per-chunk
   // counts (one per thread: that covers rows of kTpThreads chunks) and the row's short list
   uint64_t l3_bins[kBins3 / kTpThreads];
-  load_bins<kBins3>(a.hist + (int64_t)r * kBinsTotal + kBins1 + kBins2, l3_bins);
+  load_bins<kBins3>(a.hist + (int64_t)r * a.hist_stride + kBins1 + kBins2, l3_bins);
   const int cc_mine = tid < a.n_chunks ? a.chunk_cnt[(int64_t)r * a.n_chunks + tid] : 0;
   const int listed_raw = a.bucket_n[r];
   uint2 be[kBucketCap / kTpThreads];
@@ -672,7 +685,7 @@ __global__ __launch_bounds__(kTpThreads) void topp_write_kernel(const TopPArgs a
   __shared__ uint64_t sh_res[3];
   __shared__ int sh_red[kTpThreads / 64][2];
   __shared__ uint64_t sh_tot[kTpThreads / 64][2];
-  const uint64_t* hrow = a.hist + (int64_t)r * kBinsTotal;
+  const uint64_t* hrow = a.hist + (int64_t)r * a.hist_stride;
   // level 2 always leaves st[0]; level 3 leaves st[1] (a copy of st[0] for rows that carry no search)
   const RowState prev = a.state[(int64_t)r * 3 + 1];
 
@@ -1000,6 +1013,8 @@ static int32_t run_select(const char* who, const float* scores, int64_t score_st
   a.mass = mass;
   a.chunk_cnt = (int32_t*)((char*)ws + l.ccnt_off);
   a.hist = (uint64_t*)((char*)ws + l.hist_off);
+  a.hist_stride = l.hist_stride;
+  a.n_sub = l.n_sub;
   a.state = (RowState*)((char*)ws + l.state_off);
   a.bucket_n = (int32_t*)((char*)ws + l.bn_off);
   a.bucket = (uint2*)((char*)ws + l.bucket_off);
@@ -1007,7 +1022,7 @@ static int32_t run_select(const char* who, const float* scores, int64_t score_st
   hipStream_t s = (hipStream_t)stream;
   dim3 grid((unsigned)a.n_chunks, (unsigned)R), block(kTpThreads);
   if (!level1_ready) {
-    const int64_t nz = (int64_t)R * kBinsTotal;
+    const int64_t nz = (int64_t)R * l.hist_stride;
     hipLaunchKernelGGL(topp_zero_kernel, dim3((unsigned)((nz + kTpThreads - 1) / kTpThreads)), block, 0, s, a.hist, nz);
     hipLaunchKernelGGL(topp_level_kernel<1>, grid, block, 0, s, a);
   }

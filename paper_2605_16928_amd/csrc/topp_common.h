@@ -93,7 +93,15 @@ __device__ __forceinline__ void flush_hist(const uint64_t* lh, uint64_t* gh, int
 // the same layout when it is asked to accumulate level 1.
 struct TopPLayout {
   size_t ccnt_off, hist_off, state_off, bn_off, bucket_off, total;
+  // A row's histograms: level 1 (copy 0), level 2, level 3, then n_sub - 1 more copies of level 1.  With few
+  // rows every workgroup of a long row would add its level-1 bins to the same hundred addresses (256
+  // workgroups per row at 1M tokens), and those atomics queue up at the end of the score pass; the workgroups
+  // of a row therefore spread over n_sub copies, which the level-2 prologue adds up.
+  int32_t n_sub;
+  int64_t hist_stride;     // 64-bit words per row
 };
+// where copy `sub` of a row's level-1 histogram starts, in words from the row's start
+__host__ __device__ inline int64_t level1_copy_offset(int sub) { return sub == 0 ? 0 : kBinsTotal + (int64_t)(sub - 1) * kBins1; }
 TopPLayout topp_layout(int32_t R, int64_t max_len);
 
 }  // namespace rtp
