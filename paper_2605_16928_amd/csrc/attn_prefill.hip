@@ -435,6 +435,8 @@ __global__ __launch_bounds__(kPfThreads, 1) void prefill_select_kernel(const Pre
   };
 
   float selM = ninf;
+  float selM8 = ninf;               // 8 * selM and 8 * index_scale for sweep 1
+  const float cs8 = cs * 8.0f;
   float x_lo = ninf, x_top = pinf;  // sweeps 2, 3: members of the prefix have x_lo <= x <= x_top
   int shift = 0;
   float mxs[4] = {ninf, ninf, ninf, ninf};
@@ -475,10 +477,13 @@ __global__ __launch_bounds__(kPfThreads, 1) void prefill_select_kernel(const Pre
       for (int i = 0; i < 16; ++i) {
         const int n = nb + (i >> 2) * 8 + g * 4 + (i & 3);
         if (!edge || (qok && n <= m)) {
-          const float tt = sel_t(selM, SI[i], cs);
+          // 8 * (M - x * scale) straight from 8 M and 8 * scale: scaling by a power of two commutes with both
+          // roundings, so this IS 8 * sel_t(M, x, scale), one multiplication less per pair
+          const float tt8 = sel_t(selM8, SI[i], cs8);
           // first digit of q: floor(min(tt * 2^17, 2^21 - 1)) >> 14 == floor(min(tt * 8, (2^21 - 1) / 2^14))
-          const int bin = (int)fminf(tt * 8.0f, 127.99993896484375f);
-          add_mass(bin, tt);
+          const int bin = (int)fminf(tt8, 127.99993896484375f);
+          // exp(s - M) = exp2(tt * -log2(e)); the constant carries the 1/8, again exactly
+          atomicAdd(&hist[bin][r], (double)fast_exp2(tt8 * -0.18033688011112042f));
         }
       }
     } else {
@@ -580,6 +585,7 @@ __global__ __launch_bounds__(kPfThreads, 1) void prefill_select_kernel(const Pre
   for (int phase = 0; phase < 4; ++phase) {
     shift = 7 * (3 - phase);                                       // phase 1: 14, phase 2: 7, phase 3: 0
     __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");         // zeroed bins before this sweep's atomics
+    selM8 = selM * 8.0f;                                           // (used by sweep 1; exact unless it overflows)
     if (phase == 0) sweep_all(std::integral_constant<int, 0>{});
     else if (phase == 1) sweep_all(std::integral_constant<int, 1>{});
     else if (phase == 2) sweep_all(std::integral_constant<int, 2>{});
