@@ -44,6 +44,10 @@ Widened rows (each pinned the same way, see the end of this file):
                        the KV cache of a KV head whose query heads are all local keeps only the sink
                        tokens and the last `window` tokens (Sec. 2.1: the full cache is retained for
                        retrieval heads only; Sec. 3.2 last paragraph: memory is counted per KV head)
+    paged_rows, paged_attend
+                       the same sparse-attention equation with the full cache of the retrieval heads held in
+                       fixed-size pages (a storage layout, not in the paper: token t of a sequence lives in row
+                       page_table[t // page_size] * page_size + t % page_size of a pool shared by all sequences)
 
 Parity status: every function below is pinned by tests/test_oracle_pins.py
 (brute-force dense attention, hand-worked exact-binary top-p cases, closed
@@ -61,6 +65,7 @@ __all__ = [
     "decode_layer", "prefill_rows", "dense_rows",
     "build_index_keys", "topk_select", "block_topp_select", "attention_mass", "sparsity_stats",
     "ring_kv_heads", "ring_slot", "ring_append", "ring_fill", "ring_local_attend",
+    "paged_rows", "paged_attend",
 ]
 
 
@@ -471,3 +476,18 @@ def ring_local_attend(q_bits, ring_K_bits, ring_V_bits, rows: int, softmax_scale
     """A local head's attention at decode time read from the bounded cache: softmax attention over its
     first `rows` rows (a softmax over a set does not depend on the order of its members)."""
     return attend(q_bits, ring_K_bits, ring_V_bits, np.arange(int(rows)), softmax_scale)
+
+
+# ---- paged cache ------------------------------------------------------------------------------------
+def paged_rows(page_table, page_size: int, token_ids) -> np.ndarray:
+    """Pool rows of the given token positions of ONE sequence: page_table[i] is the pool page that holds
+    tokens i * page_size .. (i + 1) * page_size - 1."""
+    t = np.asarray(token_ids, dtype=np.int64)
+    pt = np.asarray(page_table, dtype=np.int64)
+    return pt[t // int(page_size)] * int(page_size) + t % int(page_size)
+
+
+def paged_attend(q_bits, K_pool_bits, V_pool_bits, page_table, page_size: int, token_ids, softmax_scale: float):
+    """The sparse-attention equation over the set `token_ids` of a sequence whose K/V rows live in a paged
+    pool (uint16 [pool_rows, d], one KV head)."""
+    return attend(q_bits, K_pool_bits, V_pool_bits, paged_rows(page_table, page_size, token_ids), softmax_scale)

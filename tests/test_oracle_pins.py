@@ -639,3 +639,34 @@ def test_ring_fill_and_attention_match_the_full_cache():
         o_ring, lse_ring = orc.ring_local_attend(q, rk, rv, rows, 0.35)
         o_full, lse_full = orc.attend(q, K, V, ids, 0.35)
         assert np.allclose(o_ring, o_full, rtol=1e-13, atol=1e-13) and abs(lse_ring - lse_full) < 1e-12
+
+
+# ---------------------------------------------------------------- paged cache
+def test_paged_rows_by_construction_and_attention_is_layout_independent():
+    """A pool is filled by explicit loops from a contiguous cache through a shuffled page table; the rows the
+    oracle looks up must hold exactly the tokens asked for, and attention through the page table must equal
+    attention on the contiguous cache bit for bit (same terms in the same order)."""
+    rng = np.random.default_rng(9)
+    d = 8
+    for page_size, n in ((16, 100), (64, 64), (32, 1), (16, 257)):
+        n_pages = -(-n // page_size)
+        pool_pages = n_pages + 5
+        table = rng.permutation(pool_pages)[:n_pages]
+        K = rng.integers(0x3c00, 0x4100, size=(n, d)).astype(np.uint16)
+        V = rng.integers(0xbc00, 0xc100, size=(n, d)).astype(np.uint16)
+        Kp = np.zeros((pool_pages * page_size, d), dtype=np.uint16)
+        Vp = np.zeros_like(Kp)
+        for t in range(n):                                   # explicit placement, no oracle code
+            page, off = divmod(t, page_size)
+            Kp[int(table[page]) * page_size + off] = K[t]
+            Vp[int(table[page]) * page_size + off] = V[t]
+        ids = np.sort(rng.choice(n, size=max(1, n // 3), replace=False))
+        rows = orc.paged_rows(table, page_size, ids)
+        assert len(set(rows.tolist())) == len(ids)
+        assert np.array_equal(Kp[rows], K[ids]) and np.array_equal(Vp[rows], V[ids])
+        q = rng.integers(0x3c00, 0x4100, size=d).astype(np.uint16)
+        o_p, l_p = orc.paged_attend(q, Kp, Vp, table, page_size, ids, 0.35)
+        o_c, l_c = orc.attend(q, K, V, ids, 0.35)
+        assert np.array_equal(o_p, o_c) and l_p == l_c
+    # hand case: page size 4, table [2, 0]: token 5 -> page 0 of the pool ... row 0 * 4 + 1
+    assert orc.paged_rows([2, 0], 4, [0, 3, 4, 5]).tolist() == [8, 11, 0, 1]
