@@ -215,6 +215,36 @@ def main() -> int:
     }
     r0.step()
 
+    # ---- the retrieval heads' cache in pages of 64 tokens, pages shuffled over a pool: the gather through the
+    # page table against the gather from contiguous sequences (same selection) ----
+    page = 64
+    w0 = r0.w
+    pages_per_seq = (N + page - 1) // page
+    perm = torch.randperm(B * pages_per_seq, generator=torch.Generator().manual_seed(5))
+    table = perm.view(B, pages_per_seq).to(torch.int32)
+    tok = torch.arange(N)
+    K_pool, V_pool = torch.empty_like(w0.K), torch.empty_like(w0.V)
+    for b in range(B):
+        rows = (table[b, tok // page].long() * page + tok % page).to(dev)
+        K_pool[:, rows] = w0.K[:, w0.seq_start[b]:w0.seq_start[b] + N]
+        V_pool[:, rows] = w0.V[:, w0.seq_start[b]:w0.seq_start[b] + N]
+    table_d = table.to(dev)
+    ref_out = r0.out.clone()
+    out_p = torch.zeros_like(r0.out)
+
+    def paged_call():
+        rtp.rtp_sparse_attn_decode_paged(r0.desc, w0.q, K_pool, V_pool, 128, K_pool.shape[1] * 128, table_d, pages_per_seq,
+                                         page, r0.sel_idx, r0.stride, r0.sel_count, r0.max_ctx, B, out_p, None, r0.ws_sparse)
+
+    r0.sparse_attn()
+    paged_call()
+    torch.cuda.synchronize()
+    assert torch.equal(out_p[:, list(L.ret_heads)], r0.out[:, list(L.ret_heads)]), "paged gather differs from the contiguous one"
+    paged = {"page_tokens": page, "sparse_attn_decode_paged_us": round(timed(lambda i: paged_call(), it, wu), 2),
+             "sparse_attn_decode_us": round(timed(lambda i: r0.sparse_attn(), it, wu), 2)}
+    del K_pool, V_pool
+    r0.out.copy_(ref_out)
+
     # ---- algorithmic bytes per step (design notes: per-unit figures x units) ----
     sel_total = int(sel_counts.sum())
     bytes_index = B * n_ret * N * (32 + 4)
@@ -448,6 +478,7 @@ def main() -> int:
             "selectors": selectors,
             "index_key_build": ib,
             "bounded_cache": bounded,
+            "paged_cache": paged,
             "selected_tokens_per_row_mean": round(float(sel_counts.mean()), 1),
             "dense_attn_us": round(dense_us, 2),
             "dense_attn_GBps": round(bytes_dense / dense_us / 1e3, 1),

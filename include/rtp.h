@@ -297,6 +297,26 @@ int32_t rtp_sparsity_stats(const rtp_layer_desc* layer, const int32_t* ctx_len,
                            float* stats, int32_t* union_size, void* stream);
 
 /* ---------------------------------------------------------------------------------------------
+ * (3) with the retrieval heads' cache held in pages (a storage layout; the arithmetic is the
+ * sparse-attention equation of Sec. 3.2 unchanged).
+ *
+ * K and V are pools of rows shared by all sequences: token position t of sequence b lives in pool row
+ * page_table[b * pt_stride + t / page_size] * page_size + t % page_size, element (kvh, row, c) at
+ * base[kvh * kv_head_stride + row * kv_row_stride + c].  page_table: device int32; page_size: a power
+ * of two >= 16; pt_stride >= ceil(max_sel / page_size).  Everything else as in rtp_sparse_attn_decode
+ * (same workspace size, same plan, bit-identical results for the same rows).  The bounded cache of the
+ * all-local KV heads (rtp_kv_ring_*) needs no paging; local heads that share their KV head with a
+ * retrieval head are not covered by this entry point.
+ */
+int32_t rtp_sparse_attn_decode_paged(const rtp_layer_desc* layer, const void* q,
+                                     const void* K, const void* V, int64_t kv_row_stride,
+                                     int64_t kv_head_stride, const int32_t* page_table, int64_t pt_stride,
+                                     int32_t page_size,
+                                     const int32_t* sel_idx, int64_t sel_stride, const int32_t* sel_count,
+                                     int64_t max_sel, int32_t B, void* out, float* lse,
+                                     void* ws, size_t ws_bytes, void* stream);
+
+/* ---------------------------------------------------------------------------------------------
  * (2) + (3) in one call for a decode step -- Sec. 3.2 (S = Top-P(s, p), then exact softmax attention
  * over S).  Sec. 3.4 saves a launch per step by fusing neighbouring stages (there: scoring and selection);
  * the pair fused here is the last selection launch and the attention.

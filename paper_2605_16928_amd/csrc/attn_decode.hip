@@ -105,8 +105,13 @@ __device__ __forceinline__ void merge_state(float& m, float& l, float (&acc)[8],
   m = M;
 }
 
-template <int G, int SRC, int U>
+// PAGED (selected-token source only): token position p of sequence b lives in row
+// page_table[b][p >> page_shift] * page_size + p % page_size of a pool shared by all sequences.  The lookup is
+// one more dependent load in front of the K/V rows, so the index list runs TWO rounds ahead and the page
+// lookups one round ahead: both stay in the shadow of the row loads.
+template <int G, int SRC, int U, bool PAGED = false>
 __global__ __launch_bounds__(kAdThreads) void attn_decode_kernel(const AttnDecodeArgs a) {
+  static_assert(!PAGED || SRC == kSrcSparse, "paging is implemented for the selected-token source");
   __shared__ int sh_prefix[kAdMaxUnits + 1];
   __shared__ int sh_w[kAdThreads / 64];
   __shared__ float sh_m[kAdThreads / 64][G], sh_l[kAdThreads / 64][G];
@@ -156,9 +161,13 @@ __global__ __launch_bounds__(kAdThreads) void attn_decode_kernel(const AttnDecod
       w0 = max(a.sink, n - a.window);
     }
     const int32_t* idx = (SRC == kSrcSparse) ? a.sel_idx + (int64_t)unit * a.sel_stride : nullptr;
-    const uint16_t* Kb = a.K + (int64_t)kvh * a.head_stride + a.seq_start[b] * a.row_stride + piece * 8;
-    const uint16_t* Vb = a.V + (int64_t)kvh * a.head_stride + a.seq_start[b] * a.row_stride + piece * 8;
+    const int64_t seq0 = PAGED ? 0 : a.seq_start[b];      // PAGED: rows are pool rows, no per-sequence offset
+    const uint16_t* Kb = a.K + (int64_t)kvh * a.head_stride + seq0 * a.row_stride + piece * 8;
+    const uint16_t* Vb = a.V + (int64_t)kvh * a.head_stride + seq0 * a.row_stride + piece * 8;
     int64_t row_stride = a.row_stride;
+    const int32_t* pt = PAGED ? a.page_table + (int64_t)b * a.pt_stride : nullptr;
+    const int page_mask = (1 << a.page_shift) - 1;
+    auto pool_row = [&](int p) { return (pt[p >> a.page_shift] << a.page_shift) | (p & page_mask); };
     if (SRC == kSrcLocal && a.ringK && a.ring_of_kv[kvh] >= 0) {
       // bounded cache: its first n_tok rows are exactly this unit's tokens, in some order
       const int64_t off = (int64_t)a.ring_of_kv[kvh] * a.ring_head_stride + a.ring_seq_start[b] * a.ring_row_stride + piece * 8;
@@ -185,12 +194,17 @@ __global__ __launch_bounds__(kAdThreads) void attn_decode_kernel(const AttnDecod
       for (int c = 0; c < 8; ++c) acc[hh][c] = 0.f;
     }
 
-    int nxt[U];
+    int nxt[U];                 // rows of the coming round (positions, or pool rows when PAGED)
+    int ahead[PAGED ? U : 1];   // PAGED: positions of the round after it
     if (SRC == kSrcSparse) {
 #pragma unroll
       for (int u = 0; u < U; ++u) {
         const int i = t_begin + u * 16 + grp;
         nxt[u] = i < t_end ? idx[i] : 0;
+        if (PAGED) {
+          ahead[u] = i + 16 * U < t_end ? idx[i + 16 * U] : 0;
+          nxt[u] = i < t_end ? pool_row(nxt[u]) : 0;
+        }
       }
     }
     for (int base = t_begin; base < t_end; base += 16 * U) {
@@ -216,7 +230,12 @@ __global__ __launch_bounds__(kAdThreads) void attn_decode_kernel(const AttnDecod
 #pragma unroll
         for (int u = 0; u < U; ++u) {
           const int i = base + 16 * U + u * 16 + grp;
-          nxt[u] = i < t_end ? idx[i] : 0;
+          if (PAGED) {
+            nxt[u] = i < t_end ? pool_row(ahead[u]) : 0;               // its positions arrived a round ago
+            ahead[u] = i + 16 * U < t_end ? idx[i + 16 * U] : 0;
+          } else {
+            nxt[u] = i < t_end ? idx[i] : 0;
+          }
         }
       }
       float s[G][U];
@@ -402,7 +421,8 @@ static int32_t launch_decode(const AttnDecodeArgs& a, int G, int grid, hipStream
   hipLaunchKernelGGL((attn_decode_gqa_kernel<GG, SRC == kSrcSparse ? kSrcDense : SRC>), dim3(grid), dim3(kAdThreads), 0, s, a); \
   hipLaunchKernelGGL((attn_decode_combine_kernel<GG, SRC>), dim3(cgrid), dim3(kAdThreads), 0, s, a);
   if (SRC == kSrcSparse || G == 1) {
-    hipLaunchKernelGGL((attn_decode_kernel<1, SRC, 8>), dim3(grid), dim3(kAdThreads), 0, s, a);
+    if (SRC == kSrcSparse && a.page_table) hipLaunchKernelGGL((attn_decode_kernel<1, kSrcSparse, 8, true>), dim3(grid), dim3(kAdThreads), 0, s, a);
+    else hipLaunchKernelGGL((attn_decode_kernel<1, SRC, 8>), dim3(grid), dim3(kAdThreads), 0, s, a);
     hipLaunchKernelGGL((attn_decode_combine_kernel<1, SRC>), dim3(cgrid), dim3(kAdThreads), 0, s, a);
   } else {
     switch (G) {
@@ -454,6 +474,9 @@ static void fill_common(AttnDecodeArgs& a, const rtp_layer_desc* L, const HeadTa
   a.ring_row_stride = a.ring_head_stride = 0;
   a.ring_seq_start = nullptr;
   for (int h = 0; h < 128; ++h) a.ring_of_kv[h] = -1;
+  a.page_table = nullptr;
+  a.pt_stride = 0;
+  a.page_shift = 0;
 }
 
 // Decode-mode local / dense attention (called from attn_api.hip).
@@ -541,19 +564,28 @@ extern "C" size_t rtp_sparse_attn_decode_workspace_bytes(const rtp_layer_desc* l
   return plan_host_sparse(B * layer->n_ret, max_sel).ws_bytes;
 }
 
-extern "C" int32_t rtp_sparse_attn_decode(const rtp_layer_desc* layer, const void* q,
-                                          const void* K, const void* V, int64_t kv_row_stride, int64_t kv_head_stride,
-                                          const int64_t* seq_start,
-                                          const int32_t* sel_idx, int64_t sel_stride, const int32_t* sel_count,
-                                          int64_t max_sel, int32_t B, void* out, float* lse,
-                                          void* ws, size_t ws_bytes, void* stream) {
-  const char* who = "rtp_sparse_attn_decode";
+static int32_t sparse_attn_decode_impl(const char* who, const rtp_layer_desc* layer, const void* q,
+                                       const void* K, const void* V, int64_t kv_row_stride, int64_t kv_head_stride,
+                                       const int64_t* seq_start, const int32_t* page_table, int64_t pt_stride,
+                                       int32_t page_size,
+                                       const int32_t* sel_idx, int64_t sel_stride, const int32_t* sel_count,
+                                       int64_t max_sel, int32_t B, void* out, float* lse,
+                                       void* ws, size_t ws_bytes, void* stream) {
   HeadTable ht;
   int32_t rc = fill_head_table(layer, &ht, who);
   if (rc != RTP_OK) return rc;
   rc = check_kv(who, q, K, V, kv_row_stride, kv_head_stride, out);
   if (rc != RTP_OK) return rc;
-  if (!seq_start || !sel_idx || !sel_count) return fail(RTP_ERR_INVALID_ARG, "%s: NULL seq_start/sel_idx/sel_count", who);
+  if ((!seq_start && !page_table) || !sel_idx || !sel_count)
+    return fail(RTP_ERR_INVALID_ARG, "%s: NULL seq_start/page_table/sel_idx/sel_count", who);
+  int page_shift = 0;
+  if (page_table) {
+    if (page_size < 16 || (page_size & (page_size - 1)) || page_size > (1 << 20))
+      return fail(RTP_ERR_INVALID_ARG, "%s: page_size must be a power of two in [16, 2^20]", who);
+    while ((1 << page_shift) < page_size) ++page_shift;
+    if (pt_stride < (max_sel + page_size - 1) / page_size)
+      return fail(RTP_ERR_INVALID_ARG, "%s: pt_stride must cover max_sel tokens", who);
+  }
   if (B <= 0 || max_sel <= 0) return fail(RTP_ERR_INVALID_ARG, "%s: B and max_sel must be positive", who);
   if (sel_stride < max_sel) return fail(RTP_ERR_INVALID_ARG, "%s: sel_stride must be >= max_sel", who);
   const int64_t units = (int64_t)B * layer->n_ret;
@@ -573,7 +605,34 @@ extern "C" int32_t rtp_sparse_attn_decode(const rtp_layer_desc* layer, const voi
   a.min_split_blocks = tune("RTP_TUNE_SPARSE_MIN_BLOCKS", 5);
   a.split_tokens = 0;
   a.n_splits = 0;
+  a.page_table = page_table;
+  a.pt_stride = pt_stride;
+  a.page_shift = page_shift;
   return launch_decode<kSrcSparse>(a, 1, p.grid, (hipStream_t)stream, who);
+}
+
+extern "C" int32_t rtp_sparse_attn_decode(const rtp_layer_desc* layer, const void* q,
+                                          const void* K, const void* V, int64_t kv_row_stride, int64_t kv_head_stride,
+                                          const int64_t* seq_start,
+                                          const int32_t* sel_idx, int64_t sel_stride, const int32_t* sel_count,
+                                          int64_t max_sel, int32_t B, void* out, float* lse,
+                                          void* ws, size_t ws_bytes, void* stream) {
+  if (!seq_start) return fail(RTP_ERR_INVALID_ARG, "rtp_sparse_attn_decode: NULL seq_start/sel_idx/sel_count");
+  return sparse_attn_decode_impl("rtp_sparse_attn_decode", layer, q, K, V, kv_row_stride, kv_head_stride, seq_start,
+                                 nullptr, 0, 0, sel_idx, sel_stride, sel_count, max_sel, B, out, lse, ws, ws_bytes, stream);
+}
+
+extern "C" int32_t rtp_sparse_attn_decode_paged(const rtp_layer_desc* layer, const void* q,
+                                                const void* K, const void* V, int64_t kv_row_stride,
+                                                int64_t kv_head_stride, const int32_t* page_table, int64_t pt_stride,
+                                                int32_t page_size,
+                                                const int32_t* sel_idx, int64_t sel_stride, const int32_t* sel_count,
+                                                int64_t max_sel, int32_t B, void* out, float* lse,
+                                                void* ws, size_t ws_bytes, void* stream) {
+  if (!page_table) return fail(RTP_ERR_INVALID_ARG, "rtp_sparse_attn_decode_paged: NULL page_table");
+  return sparse_attn_decode_impl("rtp_sparse_attn_decode_paged", layer, q, K, V, kv_row_stride, kv_head_stride, nullptr,
+                                 page_table, pt_stride, page_size, sel_idx, sel_stride, sel_count, max_sel, B, out, lse, ws,
+                                 ws_bytes, stream);
 }
 
 extern "C" size_t rtp_local_attn_ring_workspace_bytes(const rtp_layer_desc* layer, int32_t B, int64_t max_ctx) {

@@ -44,6 +44,10 @@ struct AttnDecodeArgs {
   int64_t ring_row_stride, ring_head_stride;
   const int64_t* ring_seq_start;
   int8_t ring_of_kv[128];
+  // selected-token source only: paged cache (NULL = contiguous sequences at seq_start)
+  const int32_t* page_table;   // [B, pt_stride] pool pages
+  int64_t pt_stride;
+  int32_t page_shift;          // log2(page size in tokens)
 };
 
 template <int SRC>

@@ -29,7 +29,7 @@ EXPORTS = [
     "rtp_index_project", "rtp_topk_select",
     "rtp_block_topp_workspace_bytes", "rtp_block_topp_select", "rtp_sparsity_stats",
     "rtp_select_attend_decode_workspace_bytes", "rtp_select_attend_decode",
-    "rtp_decode_attention",
+    "rtp_decode_attention", "rtp_sparse_attn_decode_paged",
     "rtp_kv_ring_heads", "rtp_kv_ring_append", "rtp_kv_ring_fill",
     "rtp_local_attn_ring_workspace_bytes", "rtp_local_attn_ring",
 ]
@@ -115,6 +115,8 @@ def lib() -> C.CDLL:
     L.rtp_select_attend_decode.restype = i32
     L.rtp_select_attend_decode.argtypes = [dp, vp, i64, vp, vp, i32, i64, vp, vp, vp, i64, i64, vp, vp, i64, vp, vp, vp,
                                            i32, vp, vp, vp, sz, vp, sz, vp]
+    L.rtp_sparse_attn_decode_paged.restype = i32
+    L.rtp_sparse_attn_decode_paged.argtypes = [dp, vp, vp, vp, i64, i64, vp, i64, i32, vp, i64, vp, i64, i32, vp, vp, vp, sz, vp]
     L.rtp_decode_attention.restype = i32
     L.rtp_decode_attention.argtypes = [dp, vp, i64, vp, vp, vp, i32, i64, vp, vp, vp, i64, i64, vp, vp, i64, vp, vp, vp,
                                        i32, vp, vp, vp, sz, vp, sz, vp, sz, vp]
@@ -213,6 +215,14 @@ def rtp_select_attend_decode(layer, scores, score_stride, row_len, p, B, max_ctx
                                           _ptr(seq_start), _ptr(sel_idx), sel_stride, _ptr(sel_count), _ptr(tau),
                                           _ptr(mass), level1_ready, _ptr(out), _ptr(lse), _ptr(topp_ws),
                                           _nbytes(topp_ws), _ptr(attn_ws), _nbytes(attn_ws), _stream(stream)))
+
+
+def rtp_sparse_attn_decode_paged(layer, q, K, V, kv_row_stride, kv_head_stride, page_table, pt_stride, page_size,
+                                 sel_idx, sel_stride, sel_count, max_sel, B, out, lse, ws, stream=None):
+    _check(lib().rtp_sparse_attn_decode_paged(C.byref(layer), _ptr(q), _ptr(K), _ptr(V), kv_row_stride, kv_head_stride,
+                                              _ptr(page_table), pt_stride, page_size, _ptr(sel_idx), sel_stride,
+                                              _ptr(sel_count), max_sel, B, _ptr(out), _ptr(lse), _ptr(ws), _nbytes(ws),
+                                              _stream(stream)))
 
 
 def rtp_decode_attention(layer, scores, score_stride, row_len, p, ctx_len, B, max_ctx, q, K, V, kv_row_stride,

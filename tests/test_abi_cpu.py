@@ -257,6 +257,24 @@ def test_bounded_cache_entry_points_host_side():
     assert att(wsb=need - 1) == rtp.RTP_ERR_WORKSPACE
 
 
+def test_paged_sparse_attention_argument_checks():
+    lib = rtp.lib()
+    L = _layer()
+    vp = C.c_void_p
+    need = rtp.rtp_sparse_attn_decode_workspace_bytes(L, 2, 1000)
+    pg = lambda pt=A, pts=16, ps=64, K=A, sel=A, ws=A, wsb=need: lib.rtp_sparse_attn_decode_paged(
+        C.byref(L), vp(A), vp(K), vp(A), 128, 128 * 4096, vp(pt), pts, ps, vp(sel), 1000, vp(A), 1000, 2, vp(A), None,
+        vp(ws), wsb, None)
+    assert pg(pt=None) == rtp.RTP_ERR_INVALID_ARG
+    assert pg(ps=48) == rtp.RTP_ERR_INVALID_ARG              # not a power of two
+    assert pg(ps=8) == rtp.RTP_ERR_INVALID_ARG               # below 16
+    assert pg(pts=15) == rtp.RTP_ERR_INVALID_ARG             # 15 pages of 64 do not cover 1000 tokens
+    assert pg(K=None) == rtp.RTP_ERR_INVALID_ARG
+    assert pg(sel=None) == rtp.RTP_ERR_INVALID_ARG
+    assert pg(ws=None) == rtp.RTP_ERR_WORKSPACE
+    assert pg(wsb=need - 1) == rtp.RTP_ERR_WORKSPACE
+
+
 def test_missing_library_is_an_error_not_a_fallback(monkeypatch):
     monkeypatch.setattr(rtp, "_lib", None)
     monkeypatch.setattr(rtp, "LIB_PATH", "/nonexistent/librtp.so")

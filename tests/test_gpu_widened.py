@@ -330,3 +330,64 @@ def test_bounded_cache_fill_append_and_local_attention(heads):
     assert torch.all(out[:, ret] == 5.0)
     assert (out[:, loc].float() - out_full[:, loc].float()).abs().max().item() <= 2e-2
     assert (lse[:, loc] - lse_full[:, loc]).abs().max().item() <= 1e-4
+
+
+# ---------------------------------------------------------------------------------------------------
+# retrieval heads' cache in pages
+# ---------------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("page_size", [16, 64, 256])
+def test_paged_sparse_attention_matches_contiguous_and_oracle(page_size):
+    """The cache scattered into a shuffled page pool: the paged call must reproduce the contiguous call bit for
+    bit (same rows, same order of arithmetic) and match the oracle's paged attention."""
+    print(f"[case] paged sparse attention, page size {page_size}", flush=True)
+    w = wl.small_decode(DEV, seed=61, ctx=(700, 1531, 64, 2048, 5000))
+    L = w.layer
+    run = DecodeRun(w)
+    run.index_score()
+    run.topp()
+    run.sparse_attn()
+    torch.cuda.synchronize()
+    out_ref, lse_ref = run.out.clone(), run.lse.clone()
+    # page tables: every sequence draws its pages from one shuffled pool
+    g = torch.Generator().manual_seed(7)
+    n_pages = [-(-n // page_size) for n in w.ctx_len]
+    pool_pages = sum(n_pages) + 9
+    perm = torch.randperm(pool_pages, generator=g)
+    pt_stride = max(n_pages) + 2
+    table = torch.full((w.B, pt_stride), -1, dtype=torch.int32)
+    at = 0
+    for b in range(w.B):
+        table[b, :n_pages[b]] = perm[at:at + n_pages[b]].to(torch.int32)
+        at += n_pages[b]
+    K_pool = torch.full((L.n_kv_heads, pool_pages * page_size, 128), float("nan"), dtype=torch.bfloat16, device=DEV)
+    V_pool = torch.full_like(K_pool, float("nan"))
+    for b in range(w.B):
+        t0, n = w.seq_start[b], w.ctx_len[b]
+        t = torch.arange(n)
+        rows = (table[b, t // page_size].long() * page_size + t % page_size).to(DEV)
+        K_pool[:, rows] = w.K[:, t0:t0 + n]
+        V_pool[:, rows] = w.V[:, t0:t0 + n]
+    table_d = table.to(DEV)
+    out = torch.full_like(run.out, 2.0)
+    lse = torch.full_like(run.lse, 2.0)
+    for rep in range(2):
+        rtp.rtp_sparse_attn_decode_paged(run.desc, w.q, K_pool, V_pool, 128, K_pool.shape[1] * 128, table_d, pt_stride,
+                                         page_size, run.sel_idx, run.stride, run.sel_count, run.max_ctx, w.B, out, lse,
+                                         run.ws_sparse)
+    torch.cuda.synchronize()
+    ret = list(L.ret_heads)
+    assert torch.equal(out[:, ret], out_ref[:, ret]) and torch.equal(lse[:, ret], lse_ref[:, ret])
+    loc = [h for h in range(L.n_q_heads) if h not in ret]
+    assert torch.all(out[:, loc] == 2.0)                          # rows of the other heads are left alone
+    # the oracle through the page table
+    sets, cnt = run.sel_sets()
+    qb, Kb, Vb = wl.bf16_bits(w.q), wl.bf16_bits(K_pool.nan_to_num(0.0)), wl.bf16_bits(V_pool.nan_to_num(0.0))
+    got = out.float().cpu().numpy().astype(np.float64)
+    G = L.n_q_heads // L.n_kv_heads
+    for b in range(w.B):
+        for j, h in enumerate(ret):
+            o, l = orc.paged_attend(qb[b, h], Kb[h // G], Vb[h // G], table[b].numpy(), page_size, sets[b * L.n_ret + j],
+                                    1.0 / np.sqrt(128.0))
+            err = np.abs(got[b, h] - o)
+            assert (err <= 1e-3 + 2.0 ** -8 * np.abs(o)).all()
+            assert abs(float(lse[b, h]) - l) < 2e-3
