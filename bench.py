@@ -262,7 +262,7 @@ def main() -> int:
                 "unit": "GB/s", "frac": round(ach / HBM_PEAK_GBS, 4),
                 # HBM bytes per launch from the rocprofv3 --pmc runs recorded under profiles/ (FETCH_SIZE x 2.0 +
                 # WRITE_SIZE x 1.0 KiB, factors from a plain 1 GiB copy); only valid for the default shape
-                "traffic": 152147866 if (B, N, n_ret) == (8, 131072, 4) else None,
+                "traffic": 152158105 if (B, N, n_ret) == (8, 131072, 4) else None,
                 "algorithmic_bytes_per_launch": bytes_index, "avg_launch_us": round(br["index_score"], 2)}
 
     # ---- one decode step at 1,048,576 tokens (the 1M layer of configuration 4, batch 1) ----
