@@ -370,11 +370,6 @@ struct DecodePlanHost {
   size_t ws_bytes;
 };
 
-static int tune(const char* name, int dflt) {
-  const char* e = getenv(name);
-  return e ? atoi(e) : dflt;
-}
-
 // Sparse: the set sizes are only known on the device, so the host gives a target item count and a
 // persistent grid; the device derives the split length from the actual counts.
 static DecodePlanHost plan_host_sparse(int32_t units, int64_t max_tok) {

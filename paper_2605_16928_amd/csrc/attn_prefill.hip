@@ -1268,12 +1268,6 @@ __global__ __launch_bounds__(256) void prefill_combine_kernel(const PrefillArgs 
 }
 
 // Number of key-range splits for a dense launch with few workgroups (long context, few heads).
-// measurement override of a launch heuristic (environment variable; 0 or unset = the heuristic)
-static int tune(const char* name, int dflt) {
-  const char* e = getenv(name);
-  return e ? atoi(e) : dflt;
-}
-
 static int choose_splits(int n_heads, int32_t T, int64_t chunk_start) {
   const int64_t wgs = (int64_t)n_heads * ((T + kPwQ - 1) / kPwQ);
   const int64_t avg_tiles = (chunk_start + T / 2) / kPfK + 1;

@@ -88,11 +88,7 @@ __global__ __launch_bounds__(kIsThreads) void index_score_kernel(const IndexScor
     for (int u = 0; u < kIsBatch; ++u) {
       const int piece = (batch * kIsBatch + u) * kIsThreads + tid;
       if (full || (piece >> 1) < n_here) {
-#ifdef RTP_IS_PLAIN_LOAD
-        v[u] = src[piece];
-#else
         v[u] = __builtin_nontemporal_load(src + piece);
-#endif
       } else {
         v[u] = (u32x4){0u, 0u, 0u, 0u};
       }
