@@ -393,3 +393,29 @@ def test_decode_attention_in_one_call_matches_oracle(name):
                 check_out(out[b, h], o, f"{name} b{b} h{h}")
                 assert abs(lse[b, h] - l) < 2e-3
         check_out(out, ref["out"], f"{name} layer")
+
+
+def test_decode_step_replays_from_a_hip_graph():
+    """The step (score pass + rtp_decode_attention) captured once and replayed: every replay, with eager steps
+    of another copy and synchronisations in between, must reproduce the eager result bit for bit (the library
+    records kernel launches only: no memset nodes, no allocation, no host synchronisation)."""
+    print("[case] decode step in a HIP graph", flush=True)
+    w = wl.c2(DEV, ctx=20000, batch=3, p=0.9)
+    run, other = DecodeRun(w), DecodeRun(wl.c2(DEV, seed=5, ctx=9000, batch=2, p=0.8))
+    run.step_one_stream()
+    torch.cuda.synchronize()
+    want = (run.out.clone(), run.lse.clone(), run.sel_idx.clone(), run.sel_count.clone(), run.tau.clone())
+    side = torch.cuda.Stream()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g, stream=side):
+        run.step_one_stream()
+    for rep in range(3):
+        run.out.zero_()
+        run.sel_count.zero_()
+        other.step_one_stream()                      # eager work of the same library between the replays
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        got = (run.out, run.lse, run.sel_idx, run.sel_count, run.tau)
+        for a, b in zip(want, got):
+            assert torch.equal(a, b), f"replay {rep} differs from the eager step"
