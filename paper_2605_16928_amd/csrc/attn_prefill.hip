@@ -650,20 +650,25 @@ __global__ __launch_bounds__(kPfThreads, 1) void prefill_select_kernel(const Pre
   if (a.tau) a.tau[o] = cut != pinf ? selM - cut : ninf;
 }
 
-// ---- the wide kernel: dense and local modes ---------------------------------------------------------
-// Same data flow as above with TWO 32-query column blocks per wave (64 consecutive queries per wave,
-// 256 per workgroup).  Every A operand read from LDS (a K row block, a V^T row block) feeds two MFMAs,
-// which halves the LDS operand traffic per flop -- the 32-query version spends its time waiting on
-// the LDS read port (about 240 of its 256 bytes per clock at a third of the MFMA peak) -- and halves
-// the global->LDS tile traffic per flop as well.  The price is registers (2 x 64 output accumulators,
-// 64 for the two Q operand sets): one wave per SIMD, the accumulators in AGPRs.
+// ---- the wide kernel: dense and selecting modes ------------------------------------------------------
+// Same data flow as above for a workgroup of 256 queries whose waves share every staged K/V tile, in
+// one of two shapes (QB = 32-query column blocks per wave):
+//   QB = 1 (default): eight waves of 32 queries, two per SIMD, at most 256 registers each;
+//   QB = 2: four waves of 64 queries, one per SIMD.  Every A operand read from LDS (a K row block, a
+//           V^T row block) feeds two MFMAs, which halves the LDS operand traffic per flop; the price is
+//           registers (2 x 64 output accumulators, 64 for the two Q operand sets).
+// Measured on the chip: a lone wave on a SIMD issues an independent 32x32x16 MFMA every 38 cycles and
+// a vector instruction every ~6, two waves reach the pipes' 32 and 4; in this kernel's own address
+// patterns eight waves read K rows from LDS at ~250 bytes per clock and V^T (the transposing read) at
+// ~96, four waves at ~160 and ~63 -- enough for either shape, so the second instruction stream wins:
+// QB = 1 is 3 to 16 % faster than QB = 2 at every depth of the 131072- and 1048576-token configurations.
 //
-// With a single wave per SIMD nothing hides latency by itself, so the loop is software-pipelined over
+// Nothing hides latency by itself at one or two waves per SIMD, so the loop is software-pipelined over
 // 32-key blocks: while the softmax of block i runs on the vector ALU, the matrix pipe executes the PV
 // MFMAs of block i-1; the two are independent instruction streams inside one basic block and are
 // interleaved with scheduling-group hints.  For that the accumulators must never be touched by the
-// vector ALU inside the loop (the register allocator would otherwise shuttle all 128 of them between
-// the two register files), so there is no running maximum: every query takes a FIXED reference
+// vector ALU inside the loop (the register allocator would otherwise shuttle them between the two
+// register files), so there is no running maximum: every query takes a FIXED reference
 // maximum from the scores of the first key tile and the probabilities are exp2(s - ref), which fp32 and
 // bf16 represent over +-126 binades.  After the pass the row sums tell whether a reference was off by
 // more than that leaves room for (sum outside [2^-60, 2^100], or not finite); the workgroup then
@@ -683,8 +688,17 @@ constexpr int kSmemWide = kPwTileBytes * kPwStages;
 typedef short s16x4 __attribute__((ext_vector_type(4)));
 typedef short s16x8 __attribute__((ext_vector_type(8)));
 
-template <int MODE>
-__global__ __launch_bounds__(kPfThreads, 1) void flash_prefill_wide_kernel(const PrefillArgs a) {
+// QB of the launch (RTP_TUNE_PREFILL_QUERY_BLOCKS=2 selects the four-wave shape, for measurements)
+static int wide_query_blocks() {
+  static const int v = tune("RTP_TUNE_PREFILL_QUERY_BLOCKS", 1) == 2 ? 2 : 1;
+  return v;
+}
+
+template <int MODE, int QB>
+__global__ __launch_bounds__(64 * (8 / QB), QB == 1 ? 2 : 1) void flash_prefill_wide_kernel(const PrefillArgs a) {
+  constexpr int NW = 8 / QB;                 // waves per workgroup; each owns QB blocks of 32 queries
+  constexpr int RG = 4 * NW;                 // tile rows one load instruction of the whole workgroup covers
+  constexpr int GH = 64 / RG;                // such loads per wave for the K rows of a tile (and as many for V)
   constexpr bool LOCAL = MODE == kModeLocal;
   constexpr bool SPARSE = MODE == kModeSparse;
   __shared__ __attribute__((aligned(16))) unsigned char smem[kSmemWide];
@@ -703,13 +717,13 @@ __global__ __launch_bounds__(kPfThreads, 1) void flash_prefill_wide_kernel(const
   const float ninf = -__builtin_huge_valf();
 
   // ---- this lane's two queries (column r of each of the wave's two blocks) ----
-  int tq[2], mq[2];
-  bool qok[2];
-  int64_t qrow[2];
-  u32x4 qreg[2][8];
+  int tq[QB], mq[QB];
+  bool qok[QB];
+  int64_t qrow[QB];
+  u32x4 qreg[QB][8];
 #pragma unroll
-  for (int qb = 0; qb < 2; ++qb) {
-    tq[qb] = t0 + wave * 64 + qb * 32 + r;
+  for (int qb = 0; qb < QB; ++qb) {
+    tq[qb] = t0 + wave * (32 * QB) + qb * 32 + r;
     qok[qb] = tq[qb] < a.n_q;
     mq[qb] = pos0 + tq[qb];
     qrow[qb] = (((int64_t)b * a.n_q + tq[qb]) * a.n_q_heads + h) * kHeadDim;
@@ -732,26 +746,32 @@ __global__ __launch_bounds__(kPfThreads, 1) void flash_prefill_wide_kernel(const
   const uint16_t* Kg = a.K + (int64_t)kvh * a.head_stride + tok0 * a.row_stride;
   const uint16_t* Vg = a.V + (int64_t)kvh * a.head_stride + tok0 * a.row_stride;
 
-  f32x16 O[2][4];
-  float mrow[2], lrow[2];
+  f32x16 O[QB][4];
+  float mrow[QB], lrow[QB];
   const float c = a.scale_log2;
   const int q_last = pos0 + a.n_q - 1;
-  const int m_w_lo = pos0 + t0 + wave * 64;             // the wave's first query position
-  const int m_w_hi = min(m_w_lo + 63, q_last);          // and its last (< m_w_lo: the wave has no queries)
+  const int m_w_lo = pos0 + t0 + wave * (32 * QB);             // the wave's first query position
+  const int m_w_hi = min(m_w_lo + 32 * QB - 1, q_last);          // and its last (< m_w_lo: the wave has no queries)
 
   // ---- selecting mode: a key is kept by a query iff the raw index product reaches the query's
   // threshold (found by prefill_select_kernel; -inf keeps every candidate).  The index-score block of
   // 32 keys x 32 queries is one MFMA (K = 16) in the layout of the attention scores. ----
-  u32x4 qIreg[2] = {(u32x4){0u, 0u, 0u, 0u}, (u32x4){0u, 0u, 0u, 0u}};
-  float selThr[2] = {ninf, ninf};
-  int sel_cnt[2] = {0, 0};
+  u32x4 qIreg[QB];
+  float selThr[QB];
+  int sel_cnt[QB];
+#pragma unroll
+  for (int qb = 0; qb < QB; ++qb) {
+    qIreg[qb] = (u32x4){0u, 0u, 0u, 0u};
+    selThr[qb] = ninf;
+    sel_cnt[qb] = 0;
+  }
   const uint16_t* kIg = nullptr;
   const int n_rows = pos0 + a.n_q;                      // index-key rows that exist
   if (SPARSE) {
     const int j = blockIdx.x;
     kIg = a.kI + (int64_t)j * a.kI_head_stride;
 #pragma unroll
-    for (int qb = 0; qb < 2; ++qb) {
+    for (int qb = 0; qb < QB; ++qb) {
       if (qok[qb]) {
         qIreg[qb] = *reinterpret_cast<const u32x4*>(a.qI + ((int64_t)j * a.n_q + tq[qb]) * kIndexDim + g * 8);
         if (a.p < 1.f) selThr[qb] = a.sel_thr[(int64_t)j * a.n_q + tq[qb]];
@@ -765,9 +785,9 @@ __global__ __launch_bounds__(kPfThreads, 1) void flash_prefill_wide_kernel(const
   };
   // drops the keys a query does not keep from its scores and counts the kept ones; run AFTER mask_block
   // (causality shows as -inf there)
-  auto select_block = [&](f32x16 (&S)[2], const u32x4 ki) __attribute__((always_inline)) {
+  auto select_block = [&](f32x16 (&S)[QB], const u32x4 ki) __attribute__((always_inline)) {
 #pragma unroll
-    for (int qb = 0; qb < 2; ++qb) {
+    for (int qb = 0; qb < QB; ++qb) {
       f32x16 SI;
 #pragma unroll
       for (int i = 0; i < 16; ++i) SI[i] = 0.f;
@@ -783,8 +803,8 @@ __global__ __launch_bounds__(kPfThreads, 1) void flash_prefill_wide_kernel(const
 
   // ---- tile movers: direct global->LDS loads, no staging registers (rows past the last needed key
   // repeat that key: they are masked for every query, and real data keeps 0 * V finite) ----
-  // Load j (0..3: K, 4..7: V) of a wave covers rows 16 * (j % 4) + 4 * wave + lane / 16 of the tile,
-  // lane % 16 is the 16-byte position inside the row; the lane fetches the chunk that belongs there.
+  // Load j (0..GH-1: K, GH..2GH-1: V) of a wave covers rows RG * (j % GH) + 4 * wave + lane / 16 of the
+  // tile, lane % 16 is the 16-byte position inside the row; the lane fetches the chunk that belongs there.
   const int uwave = __builtin_amdgcn_readfirstlane(wave);
   const uint32_t lds_base = (uint32_t)(size_t)(__attribute__((address_space(3))) unsigned char*)Ls;
   const int ld_row = 4 * wave + (lane >> 4);
@@ -792,10 +812,10 @@ __global__ __launch_bounds__(kPfThreads, 1) void flash_prefill_wide_kernel(const
   const int ld_ck = ld_pos ^ (ld_row & 15);                                          // K chunk of this lane
   const int ld_cv = ((((ld_pos >> 1) ^ (ld_row & 7)) << 1) | (ld_pos & 1));          // V chunk of this lane
   auto load_piece = [&](int n0, int slot, int j) __attribute__((always_inline)) {
-    const int jj = j & 3;
-    const int n = min(n0 + 16 * jj + ld_row, m_hi);
-    const uint16_t* src = (j < 4 ? Kg + ld_ck * 8 : Vg + ld_cv * 8) + (int64_t)n * a.row_stride;
-    const uint32_t dst = lds_base + slot * kPwTileBytes + (j < 4 ? 0 : kPwTileBytes / 2) + (jj * 4 + uwave) * 1024;
+    const int jj = j % GH;
+    const int n = min(n0 + RG * jj + ld_row, m_hi);
+    const uint16_t* src = (j < GH ? Kg + ld_ck * 8 : Vg + ld_cv * 8) + (int64_t)n * a.row_stride;
+    const uint32_t dst = lds_base + slot * kPwTileBytes + (j < GH ? 0 : kPwTileBytes / 2) + (jj * NW + uwave) * 1024;
     // Written as assembly on purpose: through the compiler's own intrinsic every later LDS read waits
     // for ALL outstanding direct loads (it cannot tell the buffers apart), which serialises the
     // pipeline; completion is awaited explicitly (loads_landed) before the barrier that publishes a tile.
@@ -803,7 +823,7 @@ __global__ __launch_bounds__(kPfThreads, 1) void flash_prefill_wide_kernel(const
   };
   auto load_tile = [&](int n0, int slot) __attribute__((always_inline)) {
 #pragma unroll
-    for (int j = 0; j < 8; ++j) load_piece(n0, slot, j);
+    for (int j = 0; j < 2 * GH; ++j) load_piece(n0, slot, j);
   };
   auto loads_landed = [&]() __attribute__((always_inline)) { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); };
   // operand read addresses (bytes inside a staged tile)
@@ -824,58 +844,61 @@ __global__ __launch_bounds__(kPfThreads, 1) void flash_prefill_wide_kernel(const
 
   // ---- MFMA streams ----
   // scores of key block kb of the staged tile, for both query blocks
-  auto mfma_S = [&](const unsigned char* tile, int kb, f32x16 (&S)[2]) __attribute__((always_inline)) {
+  auto mfma_S = [&](const unsigned char* tile, int kb, f32x16 (&S)[QB]) __attribute__((always_inline)) {
 #pragma unroll
-    for (int qb = 0; qb < 2; ++qb)
+    for (int qb = 0; qb < QB; ++qb)
 #pragma unroll
       for (int i = 0; i < 16; ++i) S[qb][i] = 0.f;
 #pragma unroll
     for (int kk = 0; kk < 8; ++kk) {
       const bf16x8 ka = __builtin_bit_cast(bf16x8, read_k(tile, kb, kk));
-      S[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka, __builtin_bit_cast(bf16x8, qreg[0][kk]), S[0], 0, 0, 0);
-      S[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka, __builtin_bit_cast(bf16x8, qreg[1][kk]), S[1], 0, 0, 0);
+#pragma unroll
+      for (int qb = 0; qb < QB; ++qb)
+        S[qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka, __builtin_bit_cast(bf16x8, qreg[qb][kk]), S[qb], 0, 0, 0);
     }
   };
   // The same MFMAs with their K operands read three steps ahead and a slice of other work (issuing
   // the loads of a later tile) between every pair; scheduling fences keep the order.
-  auto scores_beside = [&](const unsigned char* tile, int kb, f32x16 (&S)[2], auto&& work) __attribute__((always_inline)) {
+  auto scores_beside = [&](const unsigned char* tile, int kb, f32x16 (&S)[QB], auto&& work) __attribute__((always_inline)) {
     u32x4 ka[8];
     ka[0] = read_k(tile, kb, 0);
     ka[1] = read_k(tile, kb, 1);
     ka[2] = read_k(tile, kb, 2);
 #pragma unroll
-    for (int qb = 0; qb < 2; ++qb)
+    for (int qb = 0; qb < QB; ++qb)
 #pragma unroll
       for (int i = 0; i < 16; ++i) S[qb][i] = 0.f;
 #pragma unroll
     for (int kk = 0; kk < 8; ++kk) {
       if (kk + 3 < 8) ka[kk + 3] = read_k(tile, kb, kk + 3);
-      S[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, ka[kk]), __builtin_bit_cast(bf16x8, qreg[0][kk]), S[0], 0, 0, 0);
-      work(kk);
-      __builtin_amdgcn_sched_barrier(0);
-      S[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, ka[kk]), __builtin_bit_cast(bf16x8, qreg[1][kk]), S[1], 0, 0, 0);
-      __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+      for (int qb = 0; qb < QB; ++qb) {
+        S[qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, ka[kk]), __builtin_bit_cast(bf16x8, qreg[qb][kk]), S[qb], 0, 0, 0);
+        if (qb == 0) work(kk);
+        __builtin_amdgcn_sched_barrier(0);
+      }
     }
   };
   // O^T += V^T P^T for key block kb of the staged tile
-  auto mfma_PV = [&](const unsigned char* tile, int kb, const uint32_t (&P)[2][8]) __attribute__((always_inline)) {
+  auto mfma_PV = [&](const unsigned char* tile, int kb, const uint32_t (&P)[QB][8]) __attribute__((always_inline)) {
 #pragma unroll
     for (int tt = 0; tt < 2; ++tt) {
-      const bf16x8 pb0 = __builtin_bit_cast(bf16x8, (u32x4){P[0][4 * tt], P[0][4 * tt + 1], P[0][4 * tt + 2], P[0][4 * tt + 3]});
-      const bf16x8 pb1 = __builtin_bit_cast(bf16x8, (u32x4){P[1][4 * tt], P[1][4 * tt + 1], P[1][4 * tt + 2], P[1][4 * tt + 3]});
 #pragma unroll
       for (int db = 0; db < 4; ++db) {
         const bf16x8 va = __builtin_bit_cast(bf16x8, read_v(tile, kb, tt, db));
-        O[0][db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va, pb0, O[0][db], 0, 0, 0);
-        O[1][db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va, pb1, O[1][db], 0, 0, 0);
+#pragma unroll
+        for (int qb = 0; qb < QB; ++qb) {
+          const bf16x8 pb = __builtin_bit_cast(bf16x8, (u32x4){P[qb][4 * tt], P[qb][4 * tt + 1], P[qb][4 * tt + 2], P[qb][4 * tt + 3]});
+          O[qb][db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va, pb, O[qb][db], 0, 0, 0);
+        }
       }
     }
   };
   // per-element visibility without control flow: key nb0 + off, off = (i / 4) * 8 + g * 4 + i % 4, is
   // visible iff off <= hi and (LOCAL) off > lo or off < sk, three per-lane bounds
-  auto mask_block = [&](f32x16 (&S)[2], int nb0) __attribute__((always_inline)) {
+  auto mask_block = [&](f32x16 (&S)[QB], int nb0) __attribute__((always_inline)) {
 #pragma unroll
-    for (int qb = 0; qb < 2; ++qb) {
+    for (int qb = 0; qb < QB; ++qb) {
       const int base = nb0 + g * 4;
       const int hi = qok[qb] ? mq[qb] - base : -1;
       const int lo = mq[qb] - a.window - base;
@@ -890,9 +913,9 @@ __global__ __launch_bounds__(kPfThreads, 1) void flash_prefill_wide_kernel(const
     }
   };
   // probabilities against the fixed reference; masked scores are -inf and give exactly 0
-  auto softmax_fixed = [&](const f32x16 (&S)[2], uint32_t (&P)[2][8]) __attribute__((always_inline)) {
+  auto softmax_fixed = [&](const f32x16 (&S)[QB], uint32_t (&P)[QB][8]) __attribute__((always_inline)) {
 #pragma unroll
-    for (int qb = 0; qb < 2; ++qb) {
+    for (int qb = 0; qb < QB; ++qb) {
       const float mc = mrow[qb] * c;
       float lsum = 0.f;
 #pragma unroll
@@ -905,57 +928,40 @@ __global__ __launch_bounds__(kPfThreads, 1) void flash_prefill_wide_kernel(const
       lrow[qb] += lsum;
     }
   };
-  // The steady-state step: the 16 PV MFMAs of the previous block and the softmax of the current block
-  // as ONE hand-interleaved instruction sequence -- per MFMA (32 cycles of the matrix pipe) one pair of
-  // probabilities (2 fma, 2 exp, 1 convert, 2 adds on the vector ALU); scheduling fences keep the
-  // compiler from regrouping it, V^T operands are read two MFMA pairs ahead.
-  auto pv_beside_softmax = [&](const unsigned char* tile, int kb, const uint32_t (&Pin)[2][8], const f32x16 (&S)[2],
-                               uint32_t (&Pout)[2][8]) __attribute__((always_inline)) {
-    const float mc0 = mrow[0] * c, mc1 = mrow[1] * c;
-    float l0 = 0.f, l1 = 0.f;
-    s16x8 va[8];
-    auto read_va = [&](int k) __attribute__((always_inline)) { va[k] = read_v(tile, kb, k >> 2, k & 3); };   // k = tt * 4 + db
-    read_va(0);
-    read_va(1);
-#pragma unroll
-    for (int k = 0; k < 8; ++k) {
-      const int tt = k >> 2, db = k & 3;
-      const bf16x8 pb0 = __builtin_bit_cast(bf16x8, (u32x4){Pin[0][4 * tt], Pin[0][4 * tt + 1], Pin[0][4 * tt + 2], Pin[0][4 * tt + 3]});
-      const bf16x8 pb1 = __builtin_bit_cast(bf16x8, (u32x4){Pin[1][4 * tt], Pin[1][4 * tt + 1], Pin[1][4 * tt + 2], Pin[1][4 * tt + 3]});
-      if (k + 2 < 8) read_va(k + 2);
-      O[0][db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, va[k]), pb0, O[0][db], 0, 0, 0);
-      {
-        const float p0 = fast_exp2(fmaf(S[0][2 * k], c, -mc0));
-        const float p1 = fast_exp2(fmaf(S[0][2 * k + 1], c, -mc0));
-        l0 += p0 + p1;
-        Pout[0][k] = pack_bf16(p0, p1);
-      }
-      __builtin_amdgcn_sched_barrier(0);
-      O[1][db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, va[k]), pb1, O[1][db], 0, 0, 0);
-      {
-        const float p0 = fast_exp2(fmaf(S[1][2 * k], c, -mc1));
-        const float p1 = fast_exp2(fmaf(S[1][2 * k + 1], c, -mc1));
-        l1 += p0 + p1;
-        Pout[1][k] = pack_bf16(p0, p1);
-      }
-      __builtin_amdgcn_sched_barrier(0);
-    }
-    lrow[0] += l0;
-    lrow[1] += l1;
+  // l += both halves of a packed pair of probabilities, i.e. the values as rounded to bf16 (what the PV
+  // product multiplies): one instruction, and of a kind the compiler leaves where it is written (plain
+  // additions get collected behind the last MFMA of the sequence, where nothing hides them)
+  // (the compiler's own dot product intrinsic gets collected the same way).  The result of a dot
+  // instruction must not be read by another kind of vector instruction for three wait states, and
+  // the compiler does not look into assembly text: row_sum_settled() goes between the last
+  // row_sum_add and the first use.
+  auto row_sum_settled = [&](float& l) __attribute__((always_inline)) { asm volatile("s_nop 3" : "+v"(l)); };
+  auto row_sum_add = [&](float& l, uint32_t pk) __attribute__((always_inline)) {
+    asm volatile("v_dot2c_f32_bf16 %0, %1, %2" : "+v"(l) : "v"(pk), "v"(0x3f803f80u));
   };
-  // The steady-state step of the selecting mode: the same interleaving, with the block's two index-score
-  // MFMAs in front and every probability gated by its query's keep test (one compare, one select, one
-  // add for the count per pair on the vector ALU).
-  auto pv_beside_softmax_sel = [&](const unsigned char* tile, int kb, const uint32_t (&Pin)[2][8], const f32x16 (&S)[2],
-                                   uint32_t (&Pout)[2][8], const u32x4 ki) __attribute__((always_inline)) {
-    f32x16 SI0, SI1;
+  // The steady-state step: the PV MFMAs of the previous block and the softmax of the current block as
+  // ONE hand-interleaved instruction sequence -- per MFMA (32 cycles of the matrix pipe) one pair of
+  // probabilities (2 fma, 2 exp, 1 convert, 1 packed dot product on the vector ALU); scheduling fences
+  // keep the compiler from regrouping it, V^T operands are read two steps ahead.  SEL (the selecting
+  // mode): the block's index-score MFMAs in front and every probability gated by its query's keep test
+  // (one compare, one select, one add for the count per probability).
+  auto pv_beside_softmax = [&](auto sel_tag, const unsigned char* tile, int kb, const uint32_t (&Pin)[QB][8], const f32x16 (&S)[QB],
+                               uint32_t (&Pout)[QB][8], const u32x4 ki) __attribute__((always_inline)) {
+    constexpr bool SEL = decltype(sel_tag)::value;
+    f32x16 SI[QB];
+    float mc[QB], l[QB];
+    int cnt[QB];
 #pragma unroll
-    for (int i = 0; i < 16; ++i) { SI0[i] = 0.f; SI1[i] = 0.f; }
-    SI0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, ki), __builtin_bit_cast(bf16x8, qIreg[0]), SI0, 0, 0, 0);
-    SI1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, ki), __builtin_bit_cast(bf16x8, qIreg[1]), SI1, 0, 0, 0);
-    const float mc0 = mrow[0] * c, mc1 = mrow[1] * c;
-    float l0 = 0.f, l1 = 0.f;
-    int c0 = 0, c1 = 0;
+    for (int qb = 0; qb < QB; ++qb) {
+      mc[qb] = mrow[qb] * c;
+      l[qb] = 0.f;
+      cnt[qb] = 0;
+      if (SEL) {
+#pragma unroll
+        for (int i = 0; i < 16; ++i) SI[qb][i] = 0.f;
+        SI[qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, ki), __builtin_bit_cast(bf16x8, qIreg[qb]), SI[qb], 0, 0, 0);
+      }
+    }
     s16x8 va[8];
     auto read_va = [&](int k) __attribute__((always_inline)) { va[k] = read_v(tile, kb, k >> 2, k & 3); };   // k = tt * 4 + db
     read_va(0);
@@ -963,40 +969,38 @@ __global__ __launch_bounds__(kPfThreads, 1) void flash_prefill_wide_kernel(const
 #pragma unroll
     for (int k = 0; k < 8; ++k) {
       const int tt = k >> 2, db = k & 3;
-      const bf16x8 pb0 = __builtin_bit_cast(bf16x8, (u32x4){Pin[0][4 * tt], Pin[0][4 * tt + 1], Pin[0][4 * tt + 2], Pin[0][4 * tt + 3]});
-      const bf16x8 pb1 = __builtin_bit_cast(bf16x8, (u32x4){Pin[1][4 * tt], Pin[1][4 * tt + 1], Pin[1][4 * tt + 2], Pin[1][4 * tt + 3]});
       if (k + 2 < 8) read_va(k + 2);
-      O[0][db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, va[k]), pb0, O[0][db], 0, 0, 0);
-      {
-        const bool k0 = SI0[2 * k] >= selThr[0], k1 = SI0[2 * k + 1] >= selThr[0];
-        const float p0 = k0 ? fast_exp2(fmaf(S[0][2 * k], c, -mc0)) : 0.f;
-        const float p1 = k1 ? fast_exp2(fmaf(S[0][2 * k + 1], c, -mc0)) : 0.f;
-        c0 += (k0 ? 1 : 0) + (k1 ? 1 : 0);
-        l0 += p0 + p1;
-        Pout[0][k] = pack_bf16(p0, p1);
+#pragma unroll
+      for (int qb = 0; qb < QB; ++qb) {
+        const bf16x8 pb = __builtin_bit_cast(bf16x8, (u32x4){Pin[qb][4 * tt], Pin[qb][4 * tt + 1], Pin[qb][4 * tt + 2], Pin[qb][4 * tt + 3]});
+        O[qb][db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, va[k]), pb, O[qb][db], 0, 0, 0);
+        {
+          float p0 = fast_exp2(fmaf(S[qb][2 * k], c, -mc[qb]));
+          float p1 = fast_exp2(fmaf(S[qb][2 * k + 1], c, -mc[qb]));
+          if (SEL) {
+            const bool k0 = SI[qb][2 * k] >= selThr[qb], k1 = SI[qb][2 * k + 1] >= selThr[qb];
+            p0 = k0 ? p0 : 0.f;
+            p1 = k1 ? p1 : 0.f;
+            cnt[qb] += (k0 ? 1 : 0) + (k1 ? 1 : 0);
+          }
+          Pout[qb][k] = pack_bf16(p0, p1);
+          row_sum_add(l[qb], Pout[qb][k]);
+        }
+        __builtin_amdgcn_sched_barrier(0);
       }
-      __builtin_amdgcn_sched_barrier(0);
-      O[1][db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, va[k]), pb1, O[1][db], 0, 0, 0);
-      {
-        const bool k0 = SI1[2 * k] >= selThr[1], k1 = SI1[2 * k + 1] >= selThr[1];
-        const float p0 = k0 ? fast_exp2(fmaf(S[1][2 * k], c, -mc1)) : 0.f;
-        const float p1 = k1 ? fast_exp2(fmaf(S[1][2 * k + 1], c, -mc1)) : 0.f;
-        c1 += (k0 ? 1 : 0) + (k1 ? 1 : 0);
-        l1 += p0 + p1;
-        Pout[1][k] = pack_bf16(p0, p1);
-      }
-      __builtin_amdgcn_sched_barrier(0);
     }
-    lrow[0] += l0;
-    lrow[1] += l1;
-    sel_cnt[0] += c0;
-    sel_cnt[1] += c1;
+#pragma unroll
+    for (int qb = 0; qb < QB; ++qb) {
+      row_sum_settled(l[qb]);
+      lrow[qb] += l[qb];
+      if (SEL) sel_cnt[qb] += cnt[qb];
+    }
   };
   // does the 32-key block starting at nb0 need per-element masks for some query of this wave?
   auto needs_mask = [&](int nb0) __attribute__((always_inline)) {
     bool e = false;
 #pragma unroll
-    for (int qb = 0; qb < 2; ++qb) {
+    for (int qb = 0; qb < QB; ++qb) {
       const int m_b_lo = m_w_lo + qb * 32;
       const int m_b_hi = min(m_b_lo + 31, q_last);
       e = e || (m_b_hi < m_b_lo) || (nb0 + 31 > m_b_lo) || (LOCAL && !(nb0 > m_b_hi - a.window || nb0 + 31 < a.sink));
@@ -1019,10 +1023,10 @@ __global__ __launch_bounds__(kPfThreads, 1) void flash_prefill_wide_kernel(const
 
   bool redo = false;
   if (it_lo < it_hi) {
-    f32x16 S[2];
-    uint32_t P0[2][8], P1[2][8];
+    f32x16 S[QB];
+    uint32_t P0[QB][8], P1[QB][8];
 #pragma unroll
-    for (int qb = 0; qb < 2; ++qb) {
+    for (int qb = 0; qb < QB; ++qb) {
       lrow[qb] = 0.f;
 #pragma unroll
       for (int db = 0; db < 4; ++db)
@@ -1035,12 +1039,12 @@ __global__ __launch_bounds__(kPfThreads, 1) void flash_prefill_wide_kernel(const
     __syncthreads();
     // reference maxima: the largest score of the first tile, masks ignored (always finite)
 #pragma unroll
-    for (int qb = 0; qb < 2; ++qb) mrow[qb] = ninf;
+    for (int qb = 0; qb < QB; ++qb) mrow[qb] = ninf;
 #pragma unroll
     for (int kb = 1; kb >= 0; --kb) {
       mfma_S(Ls, kb, S);
 #pragma unroll
-      for (int qb = 0; qb < 2; ++qb) {
+      for (int qb = 0; qb < QB; ++qb) {
         float mx = S[qb][0];
 #pragma unroll
         for (int i = 1; i < 16; ++i) mx = fmaxf(mx, S[qb][i]);
@@ -1063,15 +1067,14 @@ __global__ __launch_bounds__(kPfThreads, 1) void flash_prefill_wide_kernel(const
       constexpr int hf = decltype(hf_tag)::value;
       const int nb0 = block_n0(it, hf);
       const unsigned char* t_pend = hf == 0 ? tile_at(it - 1) : tile_at(it);
-      const uint32_t (&Pin)[2][8] = hf == 0 ? P1 : P0;
-      uint32_t (&Pout)[2][8] = hf == 0 ? P0 : P1;
+      const uint32_t (&Pin)[QB][8] = hf == 0 ? P1 : P0;
+      uint32_t (&Pout)[QB][8] = hf == 0 ? P0 : P1;
       if (!is_active(nb0)) {
         if (pend) mfma_PV(t_pend, 1 - hf, Pin);
         pend = false;
       } else if (pend && !needs_mask(nb0)) {
         // steady state: PV of the previous block beside the softmax of this one
-        if (SPARSE) pv_beside_softmax_sel(t_pend, 1 - hf, Pin, S, Pout, hf == 0 ? ki0 : ki1);
-        else pv_beside_softmax(t_pend, 1 - hf, Pin, S, Pout);
+        pv_beside_softmax(std::integral_constant<bool, SPARSE>{}, t_pend, 1 - hf, Pin, S, Pout, hf == 0 ? ki0 : ki1);
       } else {
         if (pend) mfma_PV(t_pend, 1 - hf, Pin);
         mask_block(S, nb0);
@@ -1092,7 +1095,7 @@ __global__ __launch_bounds__(kPfThreads, 1) void flash_prefill_wide_kernel(const
         const int n2 = tile_n0(min(it + 2, it_hi - 1));
         const int s2 = slot_of(it + 2);
         if (it + 1 < it_hi && is_active(tile_n0(it + 1))) {
-          scores_beside(tile_at(it + 1), 0, S, [&](int kk) __attribute__((always_inline)) { load_piece(n2, s2, kk); });
+          scores_beside(tile_at(it + 1), 0, S, [&](int kk) __attribute__((always_inline)) { if (kk < 2 * GH) load_piece(n2, s2, kk); });
         } else {
           load_tile(n2, s2);
         }
@@ -1110,7 +1113,7 @@ __global__ __launch_bounds__(kPfThreads, 1) void flash_prefill_wide_kernel(const
     // in the comfortable middle of the fp32 range; everything else (0, tiny, huge, inf, NaN) repeats.
     bool bad = false;
 #pragma unroll
-    for (int qb = 0; qb < 2; ++qb) {
+    for (int qb = 0; qb < QB; ++qb) {
       const float ltot = lrow[qb] + __shfl_xor(lrow[qb], 32);
       // selecting mode: a query that kept no key of this range legitimately sums to zero
       const bool sees_key = SPARSE ? (sel_cnt[qb] + __shfl_xor(sel_cnt[qb], 32) > 0)
@@ -1122,10 +1125,10 @@ __global__ __launch_bounds__(kPfThreads, 1) void flash_prefill_wide_kernel(const
 
   if (redo) {
     // ---- exact pass: running maximum, accumulators rescaled in place; no pipelining (rare) ----
-    f32x16 S[2];
-    uint32_t P[2][8];
+    f32x16 S[QB];
+    uint32_t P[QB][8];
 #pragma unroll
-    for (int qb = 0; qb < 2; ++qb) {
+    for (int qb = 0; qb < QB; ++qb) {
       mrow[qb] = ninf;
       lrow[qb] = 0.f;
       sel_cnt[qb] = 0;
@@ -1146,7 +1149,7 @@ __global__ __launch_bounds__(kPfThreads, 1) void flash_prefill_wide_kernel(const
         mask_block(S, nb0);
         if (SPARSE) select_block(S, load_ki(nb0));
 #pragma unroll
-        for (int qb = 0; qb < 2; ++qb) {
+        for (int qb = 0; qb < QB; ++qb) {
           float mx = S[qb][0];
 #pragma unroll
           for (int i = 1; i < 16; ++i) mx = fmaxf(mx, S[qb][i]);
@@ -1177,7 +1180,7 @@ __global__ __launch_bounds__(kPfThreads, 1) void flash_prefill_wide_kernel(const
 
   // ---- normalise and store ----
 #pragma unroll
-  for (int qb = 0; qb < 2; ++qb) {
+  for (int qb = 0; qb < QB; ++qb) {
     const float ltot = (it_lo < it_hi) ? lrow[qb] + __shfl_xor(lrow[qb], 32) : 0.f;
     if (!qok[qb]) continue;
     const float mfin = (it_lo < it_hi && ltot > 0.f) ? mrow[qb] : ninf;
@@ -1280,13 +1283,17 @@ static int choose_splits(int n_heads, int32_t T, int64_t chunk_start) {
 static int32_t launch_prefill(const char* who, bool local, PrefillArgs& a, int32_t B, hipStream_t s) {
   if (a.n_heads == 0) return RTP_OK;
   if (a.n_splits < 1) a.n_splits = 1;
-  // dense launches take the 64-queries-per-wave kernel; the local band (a few dozen key tiles per query
-  // tile, many of them masked) stays on the 32-queries-per-wave kernel, whose masked tiles cost less
+  // dense launches take the wide kernel; the local band (a few dozen key tiles per query tile, many of
+  // them masked) stays on the 128-query kernel, whose masked tiles cost less (the wide kernel takes
+  // twice as long for the band: its masked blocks leave the pipelined path)
   const int qt = local ? kPfQ : kPwQ;
   dim3 grid((unsigned)a.n_heads, (unsigned)((a.n_q + qt - 1) / qt), (unsigned)(B * (local ? 1 : a.n_splits)));
   if (grid.y > 65535 || grid.z > 65535) return fail(RTP_ERR_INVALID_ARG, "%s: n_q / B too large for one launch", who);
   if (local) hipLaunchKernelGGL(flash_prefill_kernel<kModeLocal>, grid, dim3(kPfThreads), 0, s, a);
-  else hipLaunchKernelGGL(flash_prefill_wide_kernel<kModeDense>, grid, dim3(kPfThreads), 0, s, a);
+  else {
+    if (wide_query_blocks() == 1) hipLaunchKernelGGL((flash_prefill_wide_kernel<kModeDense, 1>), grid, dim3(512), 0, s, a);
+    else hipLaunchKernelGGL((flash_prefill_wide_kernel<kModeDense, 2>), grid, dim3(256), 0, s, a);
+  }
   if (!local && a.n_splits > 1)
     hipLaunchKernelGGL(prefill_combine_kernel, dim3((unsigned)((a.n_q + 1) / 2), (unsigned)a.n_heads), dim3(256), 0, s, a);
   return check_launch(who);
@@ -1458,7 +1465,8 @@ extern "C" int32_t rtp_sparse_attn_prefill(const rtp_layer_desc* layer, const vo
     else hipLaunchKernelGGL(prefill_select_kernel<4>, dim3(wgs), dim3(kPfThreads), 0, (hipStream_t)stream, a);
   }
   dim3 grid((unsigned)a.n_heads, (unsigned)((T + kPwQ - 1) / kPwQ), (unsigned)a.n_splits);
-  hipLaunchKernelGGL(flash_prefill_wide_kernel<kModeSparse>, grid, dim3(kPfThreads), 0, (hipStream_t)stream, a);
+  if (wide_query_blocks() == 1) hipLaunchKernelGGL((flash_prefill_wide_kernel<kModeSparse, 1>), grid, dim3(512), 0, (hipStream_t)stream, a);
+  else hipLaunchKernelGGL((flash_prefill_wide_kernel<kModeSparse, 2>), grid, dim3(256), 0, (hipStream_t)stream, a);
   if (a.n_splits > 1)
     hipLaunchKernelGGL(prefill_combine_kernel, dim3((unsigned)((T + 1) / 2), (unsigned)a.n_heads), dim3(256), 0,
                        (hipStream_t)stream, a);

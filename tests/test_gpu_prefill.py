@@ -299,3 +299,24 @@ def test_retrieval_dense_split_keys_matches_unsplit():
         check_out(ga[r["t"], 1], r["out"], "split", tight="mfma")
         check_out(gb[r["t"], 1], r["out"], "unsplit", tight="mfma")
         assert abs(la[r["t"], 1].item() - r["lse"]) < 3e-3 and abs(lb[r["t"], 1].item() - r["lse"]) < 3e-3
+
+
+def test_four_wave_shape_of_the_wide_kernel():
+    """The wide prefill kernel's other shape (four waves of 64 queries; the library picks its shape once per
+    process, from RTP_TUNE_PREFILL_QUERY_BLOCKS) against the oracle: a fresh interpreter runs a dense, a
+    selecting and an outrun-reference case of this file with the variable set."""
+    import os
+    import subprocess
+    import sys
+    here = os.path.dirname(os.path.abspath(__file__))
+    code = ("import sys; sys.path.insert(0, %r); sys.path.insert(0, %r)\n"
+            "import test_gpu_prefill as t\n"
+            "t.test_prefill_local_dense_and_retrieval_p1('small')\n"
+            "t.test_prefill_local_dense_and_retrieval_p1('g8')\n"
+            "t.test_sparse_prefill_matches_oracle(list(t._sparse_cases())[0])\n"
+            "t.test_sparse_prefill_reference_outrun_repeats_exactly()\n"
+            "t.test_retrieval_dense_split_keys_matches_unsplit()\n"
+            "print('four-wave shape ok')\n") % (here, os.path.dirname(here))
+    env = dict(os.environ, RTP_TUNE_PREFILL_QUERY_BLOCKS="2")
+    r = subprocess.run([sys.executable, "-c", code], env=env, capture_output=True, text=True, timeout=110)
+    assert r.returncode == 0 and "four-wave shape ok" in r.stdout, r.stdout[-2000:] + r.stderr[-2000:]
