@@ -22,7 +22,7 @@
  *  - bf16 tensors are raw 16-bit patterns.  head_dim must be 128 and index_dim 16.
  *  - K and V caches: bf16, element (kvh, token, c) at  base[kvh * kv_head_stride + token * kv_row_stride + c],
  *    strides in ELEMENTS, kv_row_stride >= 128 and a multiple of 8 (256 with V = K + 128 gives
- *    interleaved K|V rows).  Sequences are packed along the token axis: sequence b owns tokens
+ *    interleaved K|V rows; the prefill calls also require kv_row_stride <= 2^24).  Sequences are packed along the token axis: sequence b owns tokens
  *    seq_start[b] .. seq_start[b] + ctx_len[b] - 1  (seq_start int64, ctx_len int32, both device).
  *  - Index-key cache kI = bf16(W^K_h k^pre): element (j, token, i) at kI[j * kI_head_stride + token * 16 + i],
  *    one stream per RETRIEVAL QUERY head j (j-th entry of ret_heads).

@@ -821,6 +821,23 @@ __global__ __launch_bounds__(64 * (8 / QB), QB == 1 ? 2 : 1) void flash_prefill_
     // pipeline; completion is awaited explicitly (loads_landed) before the barrier that publishes a tile.
     asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(dst), "v"(src) : "memory", "m0");
   };
+  // The same for a tile that lies wholly inside the key range (every tile but the last): the tile's first
+  // K and V rows as scalar base addresses, the lane's place inside the tile as a 32-bit offset computed
+  // once -- no vector arithmetic per load (the general form costs seven vector instructions per piece,
+  // two of them quarter-rate multiplies, a tenth of the kernel's issue slots).
+  uint32_t off_k[GH], off_v[GH];
+#pragma unroll
+  for (int jj = 0; jj < GH; ++jj) {
+    off_k[jj] = (uint32_t)(((int64_t)(RG * jj + ld_row) * a.row_stride + ld_ck * 8) * 2);
+    off_v[jj] = (uint32_t)(((int64_t)(RG * jj + ld_row) * a.row_stride + ld_cv * 8) * 2);
+  }
+  auto load_piece_full = [&](int n0, int slot, int j) __attribute__((always_inline)) {
+    const int jj = j % GH;
+    const unsigned char* base = reinterpret_cast<const unsigned char*>((j < GH ? Kg : Vg) + (int64_t)n0 * a.row_stride);
+    const uint32_t dst = lds_base + slot * kPwTileBytes + (j < GH ? 0 : kPwTileBytes / 2) + (jj * NW + uwave) * 1024;
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(dst), "v"(j < GH ? off_k[jj] : off_v[jj]), "s"(base)
+                 : "memory", "m0");
+  };
   auto load_tile = [&](int n0, int slot) __attribute__((always_inline)) {
 #pragma unroll
     for (int j = 0; j < 2 * GH; ++j) load_piece(n0, slot, j);
@@ -1094,7 +1111,15 @@ __global__ __launch_bounds__(64 * (8 / QB), QB == 1 ? 2 : 1) void flash_prefill_
         // past the last tile the same loads re-fetch it into a buffer nobody reads: no branches
         const int n2 = tile_n0(min(it + 2, it_hi - 1));
         const int s2 = slot_of(it + 2);
-        if (it + 1 < it_hi && is_active(tile_n0(it + 1))) {
+        const bool next_active = it + 1 < it_hi && is_active(tile_n0(it + 1));
+        if (n2 + kPfK - 1 <= m_hi) {                       // a whole tile (all but the last of the range)
+          if (next_active) {
+            scores_beside(tile_at(it + 1), 0, S, [&](int kk) __attribute__((always_inline)) { if (kk < 2 * GH) load_piece_full(n2, s2, kk); });
+          } else {
+#pragma unroll
+            for (int j = 0; j < 2 * GH; ++j) load_piece_full(n2, s2, j);
+          }
+        } else if (next_active) {
           scores_beside(tile_at(it + 1), 0, S, [&](int kk) __attribute__((always_inline)) { if (kk < 2 * GH) load_piece(n2, s2, kk); });
         } else {
           load_tile(n2, s2);
@@ -1304,6 +1329,8 @@ static int32_t check_prefill_common(const char* who, const void* q, const void* 
   if (!q || !K || !V || !out) return fail(RTP_ERR_INVALID_ARG, "%s: NULL tensor pointer", who);
   if (row_stride < kHeadDim || (row_stride & 7) || (head_stride & 7) || head_stride < 0)
     return fail(RTP_ERR_INVALID_ARG, "%s: kv_row_stride must be >= 128, strides multiples of 8", who);
+  if (row_stride > (1 << 24))   // a 64-row tile must span less than 4 GiB (32-bit lane offsets inside a tile)
+    return fail(RTP_ERR_INVALID_ARG, "%s: kv_row_stride must be at most 2^24 elements", who);
   if (((uintptr_t)q & 15) || ((uintptr_t)K & 15) || ((uintptr_t)V & 15) || ((uintptr_t)out & 15))
     return fail(RTP_ERR_INVALID_ARG, "%s: q, K, V and out must be 16-byte aligned", who);
   return RTP_OK;

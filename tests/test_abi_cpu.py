@@ -280,3 +280,19 @@ def test_missing_library_is_an_error_not_a_fallback(monkeypatch):
     monkeypatch.setattr(rtp, "LIB_PATH", "/nonexistent/librtp.so")
     with pytest.raises(rtp.RtpError):
         rtp.rtp_version()
+
+
+def test_prefill_calls_reject_a_row_stride_beyond_the_tile_offset_range():
+    """The prefill kernels address a lane's place inside a 64-row tile with 32 bits: kv_row_stride above 2^24
+    elements is refused before anything is launched."""
+    lib = rtp.lib()
+    L = _layer()
+    vp = C.c_void_p
+    need = rtp.rtp_dense_attn_workspace_bytes(L, 1, 64, 4096)
+
+    def dense(rs):
+        return lib.rtp_dense_attn(C.byref(L), vp(A), vp(A), vp(A), rs, 1 << 40, vp(A), vp(A), vp(A), 1, 64, 4096,
+                                  vp(A), None, vp(A), need, None)
+
+    assert dense((1 << 24) + 8) == rtp.RTP_ERR_INVALID_ARG
+    assert "2^24" in rtp.rtp_last_error()
