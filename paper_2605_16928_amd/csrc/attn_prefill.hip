@@ -716,7 +716,7 @@ __global__ __launch_bounds__(64 * (8 / QB), QB == 1 ? 2 : 1) void flash_prefill_
   const int64_t tok0 = a.seq_start ? a.seq_start[b] : 0;
   const float ninf = -__builtin_huge_valf();
 
-  // ---- this lane's two queries (column r of each of the wave's two blocks) ----
+  // ---- this lane's queries (column r of each of the wave's QB blocks) ----
   int tq[QB], mq[QB];
   bool qok[QB];
   int64_t qrow[QB];
@@ -860,7 +860,7 @@ __global__ __launch_bounds__(64 * (8 / QB), QB == 1 ? 2 : 1) void flash_prefill_
   };
 
   // ---- MFMA streams ----
-  // scores of key block kb of the staged tile, for both query blocks
+  // scores of key block kb of the staged tile, for the wave's query blocks
   auto mfma_S = [&](const unsigned char* tile, int kb, f32x16 (&S)[QB]) __attribute__((always_inline)) {
 #pragma unroll
     for (int qb = 0; qb < QB; ++qb)
@@ -1075,7 +1075,7 @@ __global__ __launch_bounds__(64 * (8 / QB), QB == 1 ? 2 : 1) void flash_prefill_
     // it + 2 go out during half 1 (their buffer held tile it - 1, last read in half 0) and every wave
     // waits for its own before the barrier that ends half 0 of tile it + 1.
     bool pend = false;
-    u32x4 ki0 = (u32x4){0u, 0u, 0u, 0u}, ki1 = ki0;       // index keys of the current tile's two blocks
+    u32x4 ki0 = (u32x4){0u, 0u, 0u, 0u}, ki1 = ki0;       // index keys of the current tile's two key blocks
     if (SPARSE) {
       ki0 = load_ki(tile_n0(it_lo));
       ki1 = load_ki(tile_n0(it_lo) + 32);
@@ -1295,14 +1295,44 @@ __global__ __launch_bounds__(256) void prefill_combine_kernel(const PrefillArgs 
   if (a.lse && d == 0) a.lse[o] = L > 0.f ? M * a.scale + logf(L) : ninf;
 }
 
-// Number of key-range splits for a dense launch with few workgroups (long context, few heads).
+// Compute units of the current device (256 on the target; also the answer where no device is visible,
+// as when only a workspace size is asked for).
+static int compute_units() {
+  static const int v = [] {
+    int dev = 0, n = 0;
+    if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0) {
+      (void)hipGetLastError();
+      n = 256;
+    }
+    return n;
+  }();
+  return v;
+}
+
+// Number of key-range splits for a dense launch with few workgroups (long context, few heads).  A
+// compute unit holds ONE workgroup of the wide kernel (its LDS), so a launch runs in rounds of as many
+// workgroups as there are compute units: the split count is the one that fills its last round best (at
+// most 8, at least 32 key tiles per part), a smaller count winning near-ties because every part costs a
+// partial result to write and merge.  Measured on the 131072- and 1048576-token configurations (64 and 128
+// query-tile workgroups): 4 and 2 parts beat the former 8 by 4 and 2 %, 3 or 6 parts lose 15 to 20 %.
 static int choose_splits(int n_heads, int32_t T, int64_t chunk_start) {
   const int64_t wgs = (int64_t)n_heads * ((T + kPwQ - 1) / kPwQ);
   const int64_t avg_tiles = (chunk_start + T / 2) / kPfK + 1;
-  int64_t s = 1024 / (wgs > 0 ? wgs : 1);
-  if (s > avg_tiles / 32) s = avg_tiles / 32;
-  if (s > 8) s = 8;
-  return s < 1 ? 1 : (int)s;
+  int64_t smax = avg_tiles / 32;
+  if (smax > 8) smax = 8;
+  if (wgs <= 0 || smax <= 1) return 1;
+  const int64_t cus = compute_units();
+  int best = 1;
+  double best_cost = 0.0;
+  for (int s = 1; s <= (int)smax; ++s) {
+    const int64_t total = wgs * s, rounds = (total + cus - 1) / cus;
+    const double cost = (double)(rounds * cus) / (double)total * (1.0 + 0.02 * (s - 1));
+    if (s == 1 || cost < best_cost) {
+      best = s;
+      best_cost = cost;
+    }
+  }
+  return best;
 }
 
 static int32_t launch_prefill(const char* who, bool local, PrefillArgs& a, int32_t B, hipStream_t s) {
