@@ -245,6 +245,24 @@ def main() -> int:
     del K_pool, V_pool
     r0.out.copy_(ref_out)
 
+    # ---- a score law whose kept tokens cluster: the last 8192 tokens of every row raised by 2 (recency).  The
+    # one-call form splits the gather by score chunk, the two-call form by equal shares of the index list ----
+    rc = DecodeRun(r0.w, fuse_level1=False)
+    rc.index_score()
+    rc.scores.view(-1, rc.stride)[:, N - 8192:N] += 2.0
+    rc.select_then_attend(True)
+    torch.cuda.synchronize()
+    c_cnt = rc.sel_count.flatten().cpu()
+    c_idx0 = rc.sel_idx.view(c_cnt.numel(), -1)[0, :int(c_cnt[0])].cpu()
+    clustered = {
+        "law": "configuration 2 with the scores of the last 8192 tokens of every row raised by 2",
+        "kept_tokens_mean": round(float(c_cnt.float().mean()), 1),
+        "row0_kept_in_last_chunk_of_16": int((c_idx0 >= N - 8192).sum()),
+        "select_attend_decode_us": round(timed(lambda i: rc.select_then_attend(True), it, wu), 2),
+        "topp_select_plus_sparse_attn_decode_us": round(timed(lambda i: rc.select_then_attend(False), it, wu), 2),
+    }
+    del rc
+
     # ---- algorithmic bytes per step (design notes: per-unit figures x units) ----
     sel_total = int(sel_counts.sum())
     bytes_index = B * n_ret * N * (32 + 4)
@@ -479,6 +497,7 @@ def main() -> int:
             "index_key_build": ib,
             "bounded_cache": bounded,
             "paged_cache": paged,
+            "clustered_law": clustered,
             "selected_tokens_per_row_mean": round(float(sel_counts.mean()), 1),
             "dense_attn_us": round(dense_us, 2),
             "dense_attn_GBps": round(bytes_dense / dense_us / 1e3, 1),

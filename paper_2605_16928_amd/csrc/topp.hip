@@ -69,6 +69,7 @@ struct TopPArgs {
   int32_t R;
   int32_t n_chunks;        // grid.x
   int32_t rezero;          // write launch leaves the histograms zeroed (level1_ready protocol)
+  int32_t balance;         // gathering write launch: rows with one overfull chunk share their ranks out equally
   const int32_t* kcount;   // NULL: top-p by softmax mass; else static top-k, every score weighs 1 and
                            // the target is kcount[r] (rtp_topk_select)
   int32_t* sel_idx;
@@ -562,9 +563,12 @@ __device__ __forceinline__ uint32_t keep_mask(const float4 (&v)[kTpVec], int n_h
 // Writes the kept positions of one chunk in ascending order starting at out[before].
 // Element order inside a chunk is (load round u, thread, k); per-round counts (0..4) travel as
 // 16-bit fields of two 64-bit words through one wave scan.
-// `local` (optional, LDS) receives the same positions starting at local[0].  Returns the chunk's kept count.
+// `local` (optional, LDS) receives the positions of ranks win_lo <= rank < win_hi at local[rank - win_lo]
+// (by default all of the chunk's, starting at local[0]).  Returns the chunk's kept count.
 __device__ __forceinline__ int write_ranked(uint32_t keep, int before, int32_t* out, int64_t n0,
-                                            uint64_t (*sh_tot)[2] /*[waves][2]*/, int32_t* local = nullptr) {
+                                            uint64_t (*sh_tot)[2] /*[waves][2]*/, int32_t* local = nullptr,
+                                            int win_lo = -1, int win_hi = 0x7fffffff) {
+  if (win_lo < 0) win_lo = before;
   const int tid = threadIdx.x;
   uint64_t lo = 0, hi = 0;
 #pragma unroll
@@ -594,7 +598,7 @@ __device__ __forceinline__ int write_ranked(uint32_t keep, int before, int32_t* 
       if (keep & (1u << (u * 4 + k))) {
         const int32_t where = (int32_t)(n0 + (u * kTpThreads + tid) * 4 + k);
         if (out) out[pos] = where;
-        if (local) local[pos - before] = where;
+        if (local && pos >= win_lo && pos < win_hi) local[pos - win_lo] = where;
         ++pos;
       }
     }
@@ -627,6 +631,7 @@ struct GatherArgs {
   int32_t ret_heads[64];
 };
 constexpr int kSaPart = kHeadDim + 4;      // m, l, 2 pad, acc[128]  (floats)
+constexpr int kScanCost = 128;             // repeating a chunk's compaction costs about what gathering this many rows does
 constexpr int kSaInFlight = 8;             // K/V rows in flight per 16-lane group (two register sets taking turns,
                                            // or more rows, measured no faster: the gather is bandwidth-bound)
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
@@ -683,13 +688,15 @@ __global__ __launch_bounds__(kTpThreads) void topp_write_kernel(const TopPArgs a
   load_chunk(reinterpret_cast<const float4*>(a.scores + (int64_t)r * a.score_stride + n0), n_here, tid, v);
   __shared__ uint64_t sh_part[kTpThreads / 64];
   __shared__ uint64_t sh_res[3];
-  __shared__ int sh_red[kTpThreads / 64][2];
+  __shared__ int sh_red[kTpThreads / 64][3];
   __shared__ uint64_t sh_tot[kTpThreads / 64][2];
+  __shared__ int sh_cnt[ATTEND ? kTpThreads : 1], sh_pre[ATTEND ? kTpThreads : 1];   // balanced gather: kept per chunk, and before it
   const uint64_t* hrow = a.hist + (int64_t)r * a.hist_stride;
   // level 2 always leaves st[0]; level 3 leaves st[1] (a copy of st[0] for rows that carry no search)
   const RowState prev = a.state[(int64_t)r * 3 + 1];
 
   int kept_here = 0, kept_base = 0;
+  bool balanced = false;          // ATTEND: gather an equal share of the row's ranks instead of this chunk's own tokens
   const bool empty_row = prev.flags < 0 || prev.flags == 2;      // the same in every workgroup of the row
   if (empty_row) {
     have_res = true;
@@ -748,20 +755,79 @@ __global__ __launch_bounds__(kTpThreads) void topp_write_kernel(const TopPArgs a
   }
   before = wave_sum(before);
   total = wave_sum(total);
-  if ((tid & 63) == 0) { sh_red[tid >> 6][0] = before; sh_red[tid >> 6][1] = total; }
+  // ATTEND: the fullest chunk of the row (certainly-kept counts; the short list adds at most kBucketCap)
+  const int fullest_w = ATTEND ? wave_max_ge_m1(cc_mine) : 0;
+  if ((tid & 63) == 0) { sh_red[tid >> 6][0] = before; sh_red[tid >> 6][1] = total; sh_red[tid >> 6][2] = fullest_w; }
   __syncthreads();
   before = 0;
   total = 0;
+  int fullest = 0;
 #pragma unroll
-  for (int i = 0; i < kTpThreads / 64; ++i) { before += sh_red[i][0]; total += sh_red[i][1]; }
+  for (int i = 0; i < kTpThreads / 64; ++i) { before += sh_red[i][0]; total += sh_red[i][1]; fullest = max(fullest, sh_red[i][2]); }
   res_count = total;
 
   const uint32_t keep = keep_mask(v, n_here, tid, prev.flags == 1, tkey);
-  // ATTEND: the positions go to LDS only for now and to memory after the gather (same reason as above: the
-  // gather starts behind a barrier, and every wait for a K/V row would also wait for stores in flight)
-  kept_here = write_ranked(keep, before, ATTEND ? nullptr : a.sel_idx + (int64_t)r * a.sel_stride, n0, sh_tot,
-                           ATTEND ? sh_list : nullptr);
-  kept_base = before;
+  // The gather below is split by chunk, which is even only as far as the kept tokens are spread over the
+  // row.  Where one chunk holds far more than its share (the same verdict in every workgroup of the row),
+  // each workgroup gathers an equal share of the row's RANKS instead: it finds the chunks that hold its
+  // ranks from the exact per-chunk counts and repeats their compaction (a 32 KB read each).
+  balanced = ATTEND && a.balance && prev.flags == 0 && listed <= kBucketCap && n_row_chunks > 1 && n_row_chunks <= kTpThreads &&
+             fullest > 2 * (total / n_row_chunks) + 512;
+  if (!balanced) {
+    // ATTEND: the positions go to LDS only for now and to memory after the gather (same reason as above: the
+    // gather starts behind a barrier, and every wait for a K/V row would also wait for stores in flight)
+    kept_here = write_ranked(keep, before, ATTEND ? nullptr : a.sel_idx + (int64_t)r * a.sel_stride, n0, sh_tot,
+                             ATTEND ? sh_list : nullptr);
+    kept_base = before;
+  } else {
+    write_ranked(keep, before, a.sel_idx + (int64_t)r * a.sel_stride, n0, sh_tot, nullptr);   // this chunk's part of the list
+    // exact kept count of every chunk: the level-3 launch's count + the kept members of the short list
+    sh_cnt[tid] = tid < n_row_chunks ? cc_mine : 0;
+    __syncthreads();
+#pragma unroll
+    for (int k = 0; k < kBucketCap / kTpThreads; ++k)
+      if (k * kTpThreads + tid < listed && be[k].x >= tkey) atomicAdd(&sh_cnt[be[k].y / kTpChunk], 1);
+    __syncthreads();
+    // Shares are equal in COST: a chunk that holds kept tokens costs its kept count plus kScanCost (what
+    // repeating its compaction takes, in gathered tokens), laid out along one axis in chunk order with the
+    // scan cost first; workgroup c takes the c-th of n_row_chunks equal pieces of that axis and with it the
+    // ranks of the tokens that lie inside -- a contiguous run of ranks, from one chunk or a few.
+    const int mine = sh_cnt[tid];
+    const int my_scan = mine > 0 ? kScanCost : 0;
+    const uint64_t packed = ((uint64_t)(uint32_t)(mine + my_scan) << 32) | (uint32_t)mine;
+    const uint64_t incl = wave_incl_scan(packed);
+    if ((tid & 63) == 63) sh_tot[tid >> 6][0] = incl;
+    __syncthreads();
+    uint64_t waves_before = 0, all = 0;
+#pragma unroll
+    for (int i = 0; i < kTpThreads / 64; ++i) {
+      waves_before += i < (tid >> 6) ? sh_tot[i][0] : 0;
+      all += sh_tot[i][0];
+    }
+    const uint64_t excl = waves_before + incl - packed;
+    const int q0 = (int)(excl >> 32);                    // cost before this thread's chunk
+    sh_pre[tid] = (int)(uint32_t)excl;                   // kept tokens before it
+    const int64_t cost_all = (int64_t)(all >> 32);
+    const int w_lo = (int)(cost_all * c / n_row_chunks), w_hi = (int)(cost_all * (c + 1) / n_row_chunks);
+    // ranks below a point x of the cost axis: this chunk's share, summed over the chunks
+    auto below = [&](int x) { return min(max(x - q0 - my_scan, 0), mine); };
+    const int lo_w = wave_sum(below(w_lo)), hi_w = wave_sum(below(w_hi));
+    if ((tid & 63) == 0) { sh_red[tid >> 6][0] = lo_w; sh_red[tid >> 6][1] = hi_w; }
+    __syncthreads();
+    int g_lo = 0, g_hi = 0;
+#pragma unroll
+    for (int i = 0; i < kTpThreads / 64; ++i) { g_lo += sh_red[i][0]; g_hi += sh_red[i][1]; }
+    for (int i = 0; i < n_row_chunks; ++i) {
+      __syncthreads();                                   // sh_pre written / sh_tot of the last compaction read
+      const int p0 = sh_pre[i], p1 = p0 + sh_cnt[i];
+      if (p1 == p0 || p1 <= g_lo || p0 >= g_hi) continue;   // (the same for every thread)
+      const int nh = (int)min((int64_t)kTpChunk, (int64_t)n - (int64_t)i * kTpChunk);
+      float4 vv[kTpVec];
+      load_chunk(reinterpret_cast<const float4*>(a.scores + (int64_t)r * a.score_stride + (int64_t)i * kTpChunk), nh, tid, vv);
+      write_ranked(keep_mask(vv, nh, tid, false, tkey), p0, nullptr, (int64_t)i * kTpChunk, sh_tot, sh_list, g_lo, g_hi);
+    }
+    kept_here = g_hi - g_lo;
+  }
   }
   if (!ATTEND) {
     rezero();
@@ -874,7 +940,7 @@ __global__ __launch_bounds__(kTpThreads) void topp_write_kernel(const TopPArgs a
     pout[4 + tid] = A;
     if (tid == 0) { pout[0] = M; pout[1] = L; }
   }
-  {   // the chunk's positions, in one coalesced piece (after the last barrier)
+  if (!balanced) {   // the chunk's positions, in one coalesced piece (after the last barrier)
     int32_t* dst = a.sel_idx + (int64_t)r * a.sel_stride + kept_base;
     for (int i = tid; i < kept_here; i += kTpThreads) dst[i] = sh_list[i];
   }
@@ -1006,6 +1072,7 @@ static int32_t run_select(const char* who, const float* scores, int64_t score_st
   a.R = R;
   a.n_chunks = (int32_t)((max_len + kTpChunk - 1) / kTpChunk);
   a.rezero = level1_ready;
+  a.balance = tune("RTP_TUNE_GATHER_BALANCE", 1) != 0;
   a.sel_idx = sel_idx;
   a.sel_stride = sel_stride;
   a.sel_count = sel_count;

@@ -419,3 +419,73 @@ def test_decode_step_replays_from_a_hip_graph():
         got = (run.out, run.lse, run.sel_idx, run.sel_count, run.tau)
         for a, b in zip(want, got):
             assert torch.equal(a, b), f"replay {rep} differs from the eager step"
+
+
+def test_select_attend_with_clustered_kept_tokens():
+    """Rows whose kept tokens sit mostly in one 8192-score chunk (recent tokens, or a run in the middle of the
+    context): the one-call forms then hand every workgroup of the row an equal share of the row's ranks, taken
+    from other chunks than its own.  Selection outputs must stay bit-identical to rtp_topp_select's, the
+    attention must be the oracle's over that set; rtp_decode_attention must agree with the two separate
+    calls on every head.  Rows of the same batch that stay spread out take the ordinary path."""
+    print("[case] select+attend clustered", flush=True)
+    w = wl.small_decode(DEV, seed=29, ctx=(40000, 70000, 9000, 33000))
+    L = w.layer
+    oi = oracle_inputs(w)
+
+    def boost(run):
+        s = run.scores
+        for r in range(run.R):
+            n = w.ctx_len[r // L.n_ret]
+            if r % 4 == 0:
+                s[r, max(0, n - 6000):n] += 4.0          # recency: the last chunk(s) hold nearly all of the set
+            elif r % 4 == 1:
+                s[r, 9000:15000] += 3.0                   # a run inside the second chunk
+            elif r % 4 == 2:
+                s[r, 100:300] += 8.0                      # a short run: few tokens, all in the first chunk
+            # r % 4 == 3: left as generated
+
+    two = DecodeRun(w, fuse_level1=False)
+    two.index_score()
+    boost(two)
+    two.topp()
+    two.sparse_attn()
+    two.local_attn()
+    torch.cuda.synchronize()
+    cnt2 = two.sel_count.cpu().numpy()
+    clustered_rows = 0
+    for r in range(two.R):
+        n = w.ctx_len[r // L.n_ret]
+        n_chunks = (n + 8191) // 8192
+        per_chunk = np.bincount(two.sel_idx[r, :cnt2[r]].cpu().numpy() // 8192, minlength=n_chunks)
+        clustered_rows += int(n_chunks > 1 and per_chunk.max() > 2 * (cnt2[r] // n_chunks) + 600)
+    assert clustered_rows >= 3, "the test's score laws no longer cluster the kept tokens"
+
+    for form in ("select_attend", "decode_attention"):
+        run = DecodeRun(w, fuse_level1=False)
+        for rep in range(2):
+            run.sel_idx.fill_(-1)
+            run.sel_count.fill_(-9)
+            run.out.zero_()
+            run.lse.zero_()
+            run.index_score()
+            boost(run)
+            getattr(run, form)()
+            sets, cnt = run.sel_sets()
+            assert torch.equal(run.sel_count, two.sel_count), form
+            for r in range(run.R):
+                assert torch.equal(run.sel_idx[r, :cnt[r]], two.sel_idx[r, :cnt[r]]), (form, r)
+            assert torch.equal(run.tau, two.tau) and torch.equal(run.mass, two.mass)
+            out, lse = run.out_f64(), run.lse.cpu().numpy()
+            ref = _attend_reference(w, oi, sets)
+            for (b, h), (o, l) in ref.items():
+                check_out(out[b, h], o, f"clustered {form} b{b} h{h}")
+                assert abs(lse[b, h] - l) < 2e-3
+            heads = list(L.ret_heads) if form == "select_attend" else list(range(L.n_q_heads))
+            assert (run.out[:, heads].float() - two.out[:, heads].float()).abs().max().item() <= 2e-2
+    s_gpu = two.scores.cpu().numpy()
+    sets, _ = two.sel_sets()
+    for r in range(two.R):
+        n = w.ctx_len[r // L.n_ret]
+        s64 = s_gpu[r, :n].astype(np.float64)
+        p = float(w.p_rows[r])
+        check_selection(sets[r], s64, orc.topp_select(s64, p), p, f"clustered row {r}")
