@@ -327,7 +327,7 @@ int32_t rtp_sparse_attn_decode_paged(const rtp_layer_desc* layer, const void* q,
  * positions of a chunk of the row (8192 scores) keeps them in LDS, gathers their K/V rows and leaves a partial softmax
  * state per (row, chunk); a merge launch finishes each row.
  * The gather is thereby split by score chunk, which is even as far as the kept tokens are spread over the
- * context.  A row with one overfull chunk (more than twice the mean + 512 kept tokens) is shared out
+ * context.  A row with one overfull chunk (more than 1.25 x the mean + 256 kept tokens) is shared out
  * differently: every workgroup of the row takes an equal share of the row's ranks -- weighed with the cost
  * of repeating a chunk's compaction -- and finds the positions in whichever chunks hold them.
  *

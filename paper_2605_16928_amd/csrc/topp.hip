@@ -770,9 +770,11 @@ __global__ __launch_bounds__(kTpThreads) void topp_write_kernel(const TopPArgs a
   // The gather below is split by chunk, which is even only as far as the kept tokens are spread over the
   // row.  Where one chunk holds far more than its share (the same verdict in every workgroup of the row),
   // each workgroup gathers an equal share of the row's RANKS instead: it finds the chunks that hold its
-  // ranks from the exact per-chunk counts and repeats their compaction (a 32 KB read each).
+  // ranks from the exact per-chunk counts and repeats their compaction (a 32 KB read each).  That costs
+  // about 6 us per call, what the fullest chunk's workgroup needs for some 400 rows more than its share:
+  // hence the threshold (configuration 2 itself: 575 kept tokens per chunk, 766 in the fullest).
   balanced = ATTEND && a.balance && prev.flags == 0 && listed <= kBucketCap && n_row_chunks > 1 && n_row_chunks <= kTpThreads &&
-             fullest > 2 * (total / n_row_chunks) + 512;
+             fullest > 5 * (total / n_row_chunks) / 4 + 256;
   if (!balanced) {
     // ATTEND: the positions go to LDS only for now and to memory after the gather (same reason as above: the
     // gather starts behind a barrier, and every wait for a K/V row would also wait for stores in flight)
