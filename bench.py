@@ -263,6 +263,14 @@ def main() -> int:
     }
     del rc
 
+    # ---- the same step with the head shape of the paper's model (32 query / 4 KV heads: groups of 8) ----
+    Lp = wl.Layer(32, 4, list(L.ret_heads), sink=L.sink, window=L.window)
+    rp = DecodeRun(wl.make_decode("c2_g8", Lp, [N] * B, args.p, 107, dev, index_mode="direct", n_planted=64, planted_frac=0.85))
+    groups_of_8 = {"workload": "configuration 2 with 4 KV heads instead of 8",
+                   "us_per_step_one_call": round(timed(lambda i: rp.step_one_stream(), it, wu), 2),
+                   "us_per_step_parts_in_turn": round(timed(lambda i: rp.step(), it, wu), 2)}
+    del rp
+
     # ---- algorithmic bytes per step (design notes: per-unit figures x units) ----
     sel_total = int(sel_counts.sum())
     bytes_index = B * n_ret * N * (32 + 4)
@@ -498,6 +506,7 @@ def main() -> int:
             "bounded_cache": bounded,
             "paged_cache": paged,
             "clustered_law": clustered,
+            "groups_of_8": groups_of_8,
             "selected_tokens_per_row_mean": round(float(sel_counts.mean()), 1),
             "dense_attn_us": round(dense_us, 2),
             "dense_attn_GBps": round(bytes_dense / dense_us / 1e3, 1),

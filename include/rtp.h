@@ -355,9 +355,10 @@ int32_t rtp_select_attend_decode(const rtp_layer_desc* layer, const float* score
  * other heads).
  *
  * The results are those of rtp_select_attend_decode followed by rtp_local_attn (n_q = 1) on the same
- * tensors.  With 2 or 4 query heads per KV head the local heads' work items are carried by the selector's
- * second launch, which is latency-bound and leaves HBM idle: one stream, no fork and join, four launches
- * after the score pass.  Other group sizes run the two parts one after the other.
+ * tensors.  With 2 or 4 query heads per KV head (and with 8 while the batch is small enough for one work
+ * item per carrying workgroup) the local heads' work items are carried by the selector's second launch,
+ * which is latency-bound and leaves HBM idle: one stream, no fork and join, four launches after the score
+ * pass.  Otherwise the two parts run one after the other.
  *
  *   ctx_len   device int32 [B]: cached tokens per sequence (row_len[b * n_ret + j] must equal ctx_len[b]).
  *   local_ws  rtp_local_attn_workspace_bytes(layer, B, 1, max_ctx) bytes, 256-byte aligned.

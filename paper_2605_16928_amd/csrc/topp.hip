@@ -1103,7 +1103,8 @@ static int32_t run_select(const char* who, const float* scores, int64_t score_st
     const int n_ride = n_items < 256 ? n_items : 256;
     const dim3 grid2((unsigned)(n_ride + a.n_chunks * R));
     if (ride_G == 2) hipLaunchKernelGGL((topp_level_ride_kernel<2, 2>), grid2, block, 0, s, a, *ride, n_ride, 0, n_items);
-    else hipLaunchKernelGGL((topp_level_ride_kernel<2, 4>), grid2, block, 0, s, a, *ride, n_ride, 0, n_items);
+    else if (ride_G == 4) hipLaunchKernelGGL((topp_level_ride_kernel<2, 4>), grid2, block, 0, s, a, *ride, n_ride, 0, n_items);
+    else hipLaunchKernelGGL((topp_level_ride_kernel<2, 8>), grid2, block, 0, s, a, *ride, n_ride, 0, n_items);
     hipLaunchKernelGGL(topp_level_kernel<3>, grid, block, 0, s, a);
   } else {
     hipLaunchKernelGGL(topp_level_kernel<2>, grid, block, 0, s, a);
@@ -1114,7 +1115,8 @@ static int32_t run_select(const char* who, const float* scores, int64_t score_st
     if (ride) {
       const dim3 cgrid((unsigned)(R + ride->units * ride_G));
       if (ride_G == 2) hipLaunchKernelGGL(select_attend_combine_kernel<2>, cgrid, dim3(256), 0, s, a, *attend, *ride);
-      else hipLaunchKernelGGL(select_attend_combine_kernel<4>, cgrid, dim3(256), 0, s, a, *attend, *ride);
+      else if (ride_G == 4) hipLaunchKernelGGL(select_attend_combine_kernel<4>, cgrid, dim3(256), 0, s, a, *attend, *ride);
+      else hipLaunchKernelGGL(select_attend_combine_kernel<8>, cgrid, dim3(256), 0, s, a, *attend, *ride);
     } else {
       hipLaunchKernelGGL(select_attend_combine_kernel<0>, dim3((unsigned)R), dim3(256), 0, s, a, *attend, AttnDecodeArgs{});
     }
@@ -1233,9 +1235,13 @@ extern "C" int32_t rtp_decode_attention(const rtp_layer_desc* layer, const float
                                           max_ctx, out, lse, local_ws, local_ws_bytes, s)
                       : RTP_OK;
   }
-  const bool ride = have_local && (G == 2 || G == 4);
+  // groups of 8 need 163 vector registers for a carried item, which costs the level-2 launch a resident
+  // workgroup per compute unit: worth it while every carrier has one item (batch 8 x 131072 with 32 query /
+  // 4 KV heads: 97 against 101 us per step), not for the long item chains of a large batch (a ragged batch of
+  // 32 with 64 / 8 heads: 1.21 against 1.15 ms)
+  const bool ride = have_local && (G == 2 || G == 4 || (G == 8 && (int64_t)la.units * la.n_splits <= 256));
   if (!ride) {
-    // group sizes the carried form does not cover: the two parts one after the other
+    // group sizes (or workloads) the carried form does not cover: the two parts one after the other
     rc = run_select(who, scores, score_stride, row_len, p, nullptr, (int32_t)R, max_ctx, sel_idx, sel_stride, sel_count, tau,
                     mass, level1_ready, topp_ws, topp_ws_bytes, stream, &ga);
     if (rc != RTP_OK || !have_local) return rc;

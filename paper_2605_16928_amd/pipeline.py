@@ -161,9 +161,10 @@ class DecodeRun:
     @property
     def carries_local_heads(self) -> bool:
         """Whether rtp_decode_attention carries the local heads inside the selector's launches for this layer
-        (2 or 4 query heads per KV head, at least one retrieval and one local head)."""
+        (2, 4 or 8 query heads per KV head -- 8 only for small batches, see the library --, at least one
+        retrieval and one local head); where it does not, the call still works and runs its parts in turn."""
         L = self.w.layer
-        return L.n_q_heads // L.n_kv_heads in (2, 4) and 0 < L.n_ret < L.n_q_heads
+        return L.n_q_heads // L.n_kv_heads in (2, 4, 8) and 0 < L.n_ret < L.n_q_heads
 
     def step_fastest(self, side: "torch.cuda.Stream"):
         """The step in the form the benchmark times: one stream where the local heads can be carried, else the

@@ -26,6 +26,8 @@ def _cases():
         "c2_small": lambda: wl.c2(DEV, ctx=20000, batch=3, p=0.9),
         # configuration 5, shrunk: G = 8, ragged lengths, per-row p, flat and peaked rows
         "c5_small": lambda: wl.c5(DEV, batch=5, lo=3000, hi=40000),
+        # the same head shape with a batch large enough for several local work items per carrying workgroup
+        "c5_many": lambda: wl.c5(DEV, seed=6, batch=40, lo=100, hi=2500),
     }
 
 
@@ -356,11 +358,11 @@ def test_select_attend_degenerate_rows():
                 assert abs(lse[b, h] - ref[(b, h)][1]) < 2e-3
 
 
-@pytest.mark.parametrize("name", ["small", "g1", "g2", "c2_small", "c5_small"])
+@pytest.mark.parametrize("name", ["small", "g1", "g2", "c2_small", "c5_small", "c5_many"])
 def test_decode_attention_in_one_call_matches_oracle(name):
     """rtp_decode_attention: everything after the score pass -- the layer's output (retrieval and local rows)
     against the oracle end to end, the selection bit-identical to rtp_topp_select's, twice in a row.  The cases
-    cover the carried form (G = 2, 4) and the fall-back (G = 1, 8)."""
+    cover the carried form (G = 2, 4, and 8 with a small batch) and the fall-back (G = 1; G = 8 with a large batch)."""
     print(f"[case] decode attention in one call {name}", flush=True)
     w = _cases()[name]()
     L = w.layer
