@@ -756,7 +756,7 @@ __global__ __launch_bounds__(kTpThreads) void topp_write_kernel(const TopPArgs a
   before = wave_sum(before);
   total = wave_sum(total);
   // ATTEND: the fullest chunk of the row (certainly-kept counts; the short list adds at most kBucketCap)
-  const int fullest_w = ATTEND ? wave_max_ge_m1(cc_mine) : 0;
+  const int fullest_w = ATTEND ? wave_max_ge_m1(tid < n_row_chunks ? cc_mine : 0) : 0;   // (counts past the row's own chunks are stale)
   if ((tid & 63) == 0) { sh_red[tid >> 6][0] = before; sh_red[tid >> 6][1] = total; sh_red[tid >> 6][2] = fullest_w; }
   __syncthreads();
   before = 0;
