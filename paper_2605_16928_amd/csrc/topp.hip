@@ -528,9 +528,10 @@ __global__ __launch_bounds__(kTpThreads) void topp_level_kernel(const TopPArgs a
 // (attn_decode_shared.h), the others are the level's own workgroups.  The selector's middle launches are
 // latency-bound and leave HBM idle, which is where the local heads' K/V rows get streamed; as riders they need
 // no second stream (a fork and a join per step cost more than the overlap they buy).  Two workgroups per
-// compute unit, i.e. at most 128 vector registers: one tile per wave in flight.
+// compute unit, i.e. at most 128 vector registers: one tile per wave in flight (groups of 8 need 163 and
+// get one workgroup per compute unit).
 template <int LEVEL, int G>
-__global__ __launch_bounds__(kTpThreads, 4) void topp_level_ride_kernel(const TopPArgs a, const AttnDecodeArgs la,
+__global__ __launch_bounds__(kTpThreads, G == 8 ? 2 : 4) void topp_level_ride_kernel(const TopPArgs a, const AttnDecodeArgs la,
                                                                         const int n_ride, const int item_lo,
                                                                         const int item_hi) {
   const int bid = blockIdx.x;
