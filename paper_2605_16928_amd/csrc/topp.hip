@@ -824,10 +824,14 @@ __global__ __launch_bounds__(kTpThreads) void topp_write_kernel(const TopPArgs a
       __syncthreads();                                   // sh_pre written / sh_tot of the last compaction read
       const int p0 = sh_pre[i], p1 = p0 + sh_cnt[i];
       if (p1 == p0 || p1 <= g_lo || p0 >= g_hi) continue;   // (the same for every thread)
-      const int nh = (int)min((int64_t)kTpChunk, (int64_t)n - (int64_t)i * kTpChunk);
-      float4 vv[kTpVec];
-      load_chunk(reinterpret_cast<const float4*>(a.scores + (int64_t)r * a.score_stride + (int64_t)i * kTpChunk), nh, tid, vv);
-      write_ranked(keep_mask(vv, nh, tid, false, tkey), p0, nullptr, (int64_t)i * kTpChunk, sh_tot, sh_list, g_lo, g_hi);
+      uint32_t kp = keep;                                // this workgroup's own chunk: already in registers
+      if (i != c) {
+        const int nh = (int)min((int64_t)kTpChunk, (int64_t)n - (int64_t)i * kTpChunk);
+        float4 vv[kTpVec];
+        load_chunk(reinterpret_cast<const float4*>(a.scores + (int64_t)r * a.score_stride + (int64_t)i * kTpChunk), nh, tid, vv);
+        kp = keep_mask(vv, nh, tid, false, tkey);
+      }
+      write_ranked(kp, p0, nullptr, (int64_t)i * kTpChunk, sh_tot, sh_list, g_lo, g_hi);
     }
     kept_here = g_hi - g_lo;
   }
