@@ -86,6 +86,54 @@ def test_c2_full_size(p):
     assert len(sizes) == 32
 
 
+def test_c2_full_size_with_clustered_kept_tokens():
+    """Configuration 2 at full size with the scores of every row's last 8192 tokens raised by 2 (what bench.py
+    reports as extra.clustered_law): most rows then have one overfull chunk and the one-call form shares the
+    gather out by rank.  Selection against the oracle on the same scores, attention against the oracle over
+    the selected rows, and both bit for bit / within tolerance of the two separate calls."""
+    print("[case] c2 full size, clustered law", flush=True)
+    w = wl.c2(DEV, seed=5)
+    L = w.layer
+    G = L.n_q_heads // L.n_kv_heads
+    N = w.ctx_len[0]
+    qb = wl.bf16_bits(w.q)
+
+    def prepared():
+        run = DecodeRun(w, fuse_level1=False)
+        run.index_score()
+        run.scores.view(-1, run.stride)[:, N - 8192:N] += 2.0
+        return run
+
+    two = prepared()
+    two.topp()
+    two.sparse_attn()
+    two.local_attn()
+    run = prepared()
+    run.decode_attention()
+    torch.cuda.synchronize()
+    sets, cnt = run.sel_sets()
+    assert torch.equal(run.sel_count, two.sel_count) and torch.equal(run.tau, two.tau)
+    overfull = 0
+    for r in range(run.R):
+        assert torch.equal(run.sel_idx[r, :cnt[r]], two.sel_idx[r, :cnt[r]])
+        per_chunk = np.bincount(np.asarray(sets[r]) // 8192, minlength=16)
+        overfull += int(per_chunk.max() > 5 * (cnt[r] // 16) // 4 + 400)
+    assert overfull >= run.R // 2, "the law no longer clusters the kept tokens"
+    assert (run.out.float() - two.out.float()).abs().max().item() <= 2e-2
+    s_gpu = run.scores.cpu().numpy()
+    out = run.out_f64()
+    for r in range(0, run.R, 5):                              # a sample of rows against the oracle
+        b, j = divmod(r, L.n_ret)
+        h = L.ret_heads[j]
+        s64 = s_gpu[r, :N].astype(np.float64)
+        pr = float(w.p_rows[r])
+        check_selection(sets[r], s64, orc.topp_select(s64, pr), pr, f"clustered row {r}")
+        ids_t = torch.as_tensor(np.asarray(sets[r]) + w.seq_start[b], device=DEV)
+        Ks, Vs = wl.bf16_bits(w.K[h // G].index_select(0, ids_t)), wl.bf16_bits(w.V[h // G].index_select(0, ids_t))
+        o, _ = orc.attend(qb[b, h], Ks, Vs, np.arange(len(sets[r])), SC)
+        check_out(out[b, h], o, f"clustered sparse b{b} h{h}")
+
+
 def test_c5_full_size():
     print("[case] c5 full size (ragged batch of 32, 64 query heads)", flush=True)
     w = wl.c5(DEV)
