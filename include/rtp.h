@@ -39,6 +39,10 @@
  *    the first launch; on error nothing has been enqueued.  rtp_last_error() gives a thread-local
  *    message for the last failing call of the calling thread.
  *  - Calls on different streams may overlap if their outputs and workspaces are disjoint.
+ *  - Size limits of the decode calls (n_q = 1): rtp_local_attn, rtp_dense_attn, rtp_local_attn_ring and
+ *    rtp_decode_attention serve at most 1024 (sequence, KV head) pairs per call (B * n_kv_heads <= 1024),
+ *    rtp_sparse_attn_decode and its paged form at most 1024 (sequence, retrieval head) rows (B * n_ret <= 1024):
+ *    RTP_ERR_UNSUPPORTED beyond that, before anything is enqueued -- split the batch.
  */
 #ifndef RTP_H_
 #define RTP_H_
@@ -120,14 +124,17 @@ int32_t rtp_index_score(const rtp_layer_desc* layer, const void* q_in, const flo
  * This is the smallest such set up to ties AT tau, all of which are kept.  The search is a three-level
  * radix histogram over the order-preserving 32-bit key of the fp32 score (exact: no sort, no sampling);
  * masses are accumulated as 64-bit fixed point of fp64 exponentials, so the result does not depend on
- * summation order.  Scores of magnitude >= 64 lose mass resolution gradually (the fixed-point reference
- * of a score is the upper edge of its coarse bin, and those bins are 16 or more wide).
+ * summation order.  The fixed-point reference of a score is the upper edge of its quarter binade, at most 16
+ * away while |s| < 128 (a weight then keeps a relative resolution of 2^-8 or far better for the longest row);
+ * a row whose LARGEST finite score lies outside (-128, 128) cannot be resolved that way and is reported as
+ * unsupported: sel_count = -2, nothing selected (lower scores of any magnitude are fine).
  *
  *   scores    fp32 [R, score_stride] (16-byte aligned, score_stride multiple of 4); row r uses
  *             entries [0, row_len[r]); -inf entries are never selected.
  *   row_len   device int32 [R], each <= max_len (host bound, <= RTP_MAX_ROW_LEN).
  *   p         device fp32 [R], one value per row; p >= 1 keeps every entry of the row (tau = -inf);
  *             p <= 0 or NaN marks the row invalid: sel_count = -1, nothing selected.
+ *             (sel_count = -2: the row's largest score lies outside (-128, 128), see above.)
  *   sel_idx   out, int32 [R, sel_stride], sel_stride >= max_len; the selected positions in
  *             ascending order (the result is deterministic: same inputs, same bits).
  *   sel_count out, int32 [R].   tau, mass: optional outputs fp32 [R] (threshold score; selected mass / Z).

@@ -375,7 +375,7 @@ struct DecodePlanHost {
 static DecodePlanHost plan_host_sparse(int32_t units, int64_t max_tok) {
   DecodePlanHost p = {};
   p.units = units;
-  const int64_t cap = tune("RTP_TUNE_SPARSE_ITEMS", 1024);
+  const int64_t cap = 1024;
   int64_t blocks128 = (int64_t)units * ((max_tok + 127) / 128);
   int64_t tgt = blocks128 < 1 ? 1 : (blocks128 > cap ? cap : blocks128);
   p.target_items = (int32_t)tgt;
@@ -393,7 +393,7 @@ static DecodePlanHost plan_host_range(int32_t units, int64_t max_tok, int32_t G)
   // buys launch and merge overhead (measured on batch 8: 2052 tokens per unit, 256 items 24.2 us, 1024 items 26.5 us)
   int64_t dflt = (int64_t)units * max_tok / 512;
   dflt = dflt < 256 ? 256 : (dflt > 1024 ? 1024 : dflt);
-  const int64_t cap = tune("RTP_TUNE_RANGE_ITEMS", (int)dflt);
+  const int64_t cap = dflt;
   const int64_t blocks = (max_tok + 127) / 128;
   int64_t ns = cap / units;
   if (ns < 1) ns = 1;
@@ -597,7 +597,7 @@ static int32_t sparse_attn_decode_impl(const char* who, const rtp_layer_desc* la
   a.sel_count = sel_count;
   a.units = p.units;
   a.target_items = p.target_items;
-  a.min_split_blocks = tune("RTP_TUNE_SPARSE_MIN_BLOCKS", 5);
+  a.min_split_blocks = 5;
   a.split_tokens = 0;
   a.n_splits = 0;
   a.page_table = page_table;

@@ -72,10 +72,7 @@ constexpr int kSelQMax = (1 << 21) - 1;
 constexpr int kTileHalfs = kPfK * kKsStride + kHeadDim * kVtStride;   // bf16 elements of one staged K + V^T tile
 constexpr int kSmemDense = kTileHalfs * 2 * 2;                        // two buffers
 constexpr int kSelListCap = 24;      // entries per lane; a tile adds at most 16, so lists are emptied above 8
-#ifndef RTP_SEL_RING
-#define RTP_SEL_RING 8
-#endif
-constexpr int kSelRing = RTP_SEL_RING;          // index-key tiles in flight per wave during the threshold search
+constexpr int kSelRing = 8;          // index-key tiles in flight per wave during the threshold search
 
 __device__ __forceinline__ int sel_q_of_t(float tt) {       // tt = M - s >= 0
   return (int)fminf(tt * kSelScale, (float)kSelQMax);
@@ -688,11 +685,6 @@ constexpr int kSmemWide = kPwTileBytes * kPwStages;
 typedef short s16x4 __attribute__((ext_vector_type(4)));
 typedef short s16x8 __attribute__((ext_vector_type(8)));
 
-// QB of the launch (RTP_TUNE_PREFILL_QUERY_BLOCKS=2 selects the four-wave shape, for measurements)
-static int wide_query_blocks() {
-  static const int v = tune("RTP_TUNE_PREFILL_QUERY_BLOCKS", 1) == 2 ? 2 : 1;
-  return v;
-}
 
 template <int MODE, int QB>
 __global__ __launch_bounds__(64 * (8 / QB), QB == 1 ? 2 : 1) void flash_prefill_wide_kernel(const PrefillArgs a) {
@@ -1345,10 +1337,7 @@ static int32_t launch_prefill(const char* who, bool local, PrefillArgs& a, int32
   dim3 grid((unsigned)a.n_heads, (unsigned)((a.n_q + qt - 1) / qt), (unsigned)(B * (local ? 1 : a.n_splits)));
   if (grid.y > 65535 || grid.z > 65535) return fail(RTP_ERR_INVALID_ARG, "%s: n_q / B too large for one launch", who);
   if (local) hipLaunchKernelGGL(flash_prefill_kernel<kModeLocal>, grid, dim3(kPfThreads), 0, s, a);
-  else {
-    if (wide_query_blocks() == 1) hipLaunchKernelGGL((flash_prefill_wide_kernel<kModeDense, 1>), grid, dim3(512), 0, s, a);
-    else hipLaunchKernelGGL((flash_prefill_wide_kernel<kModeDense, 2>), grid, dim3(256), 0, s, a);
-  }
+  else hipLaunchKernelGGL((flash_prefill_wide_kernel<kModeDense, 1>), grid, dim3(512), 0, s, a);
   if (!local && a.n_splits > 1)
     hipLaunchKernelGGL(prefill_combine_kernel, dim3((unsigned)((a.n_q + 1) / 2), (unsigned)a.n_heads), dim3(256), 0, s, a);
   return check_launch(who);
@@ -1433,6 +1422,7 @@ extern "C" int32_t rtp_sparse_attn_prefill(const rtp_layer_desc* layer, const vo
   if (T <= 0 || chunk_start < 0) return fail(RTP_ERR_INVALID_ARG, "%s: T must be positive and chunk_start >= 0", who);
   if (chunk_start + T > 0x7fffffffLL - kPwQ) return fail(RTP_ERR_INVALID_ARG, "%s: context too long", who);
   if (!(p > 0.f)) return fail(RTP_ERR_INVALID_ARG, "%s: p must be > 0", who);
+  if ((T + kPfQ - 1) / kPfQ > 65535) return fail(RTP_ERR_INVALID_ARG, "%s: T too large for one launch", who);
   const bool sparse = p < 1.f || tau || count || mass;
   if (sparse) {
     if (!q_pre || !kI) return fail(RTP_ERR_INVALID_ARG, "%s: NULL index tensors", who);
@@ -1504,12 +1494,10 @@ extern "C" int32_t rtp_sparse_attn_prefill(const rtp_layer_desc* layer, const vo
   a.sel_thr = (float*)((char*)ws + proj_bytes);
   a.part = (float*)((char*)ws + proj_bytes + state_bytes);
   a.n_splits = choose_splits(layer->n_ret, T, chunk_start);
-  if ((T + kPfQ - 1) / kPfQ > 65535) return fail(RTP_ERR_INVALID_ARG, "%s: T too large for one launch", who);
   if (p < 1.f) {
     // waves per 32-query group: as many as it takes to give each of the chip's 1024 SIMDs a wave
-    static const int force_ks = tune("RTP_TUNE_SELECT_KEY_SPLIT", 0);
     const int64_t groups = (int64_t)a.n_heads * ((T + 31) / 32);
-    const int ks = force_ks ? force_ks : (groups > 512 ? 1 : groups > 256 ? 2 : 4);
+    const int ks = groups > 512 ? 1 : groups > 256 ? 2 : 4;
     const unsigned n_qtiles = (unsigned)((T + 128 / ks - 1) / (128 / ks));
     // 1-D grid, padded so that every die gets whole (head, query tile) columns (see the kernel's decoding)
     unsigned wgs = (unsigned)a.n_heads * n_qtiles;
@@ -1522,8 +1510,7 @@ extern "C" int32_t rtp_sparse_attn_prefill(const rtp_layer_desc* layer, const vo
     else hipLaunchKernelGGL(prefill_select_kernel<4>, dim3(wgs), dim3(kPfThreads), 0, (hipStream_t)stream, a);
   }
   dim3 grid((unsigned)a.n_heads, (unsigned)((T + kPwQ - 1) / kPwQ), (unsigned)a.n_splits);
-  if (wide_query_blocks() == 1) hipLaunchKernelGGL((flash_prefill_wide_kernel<kModeSparse, 1>), grid, dim3(512), 0, (hipStream_t)stream, a);
-  else hipLaunchKernelGGL((flash_prefill_wide_kernel<kModeSparse, 2>), grid, dim3(256), 0, (hipStream_t)stream, a);
+  hipLaunchKernelGGL((flash_prefill_wide_kernel<kModeSparse, 1>), grid, dim3(512), 0, (hipStream_t)stream, a);
   if (a.n_splits > 1)
     hipLaunchKernelGGL(prefill_combine_kernel, dim3((unsigned)((T + 1) / 2), (unsigned)a.n_heads), dim3(256), 0,
                        (hipStream_t)stream, a);

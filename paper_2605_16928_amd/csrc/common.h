@@ -27,11 +27,6 @@ inline float softmax_scale_of(const rtp_layer_desc* L) {
 }
 inline float index_scale_of(const rtp_layer_desc* L) { return L->index_scale != 0.f ? L->index_scale : 1.f; }
 inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
-// Measurement override of a launch heuristic: the integer in environment variable `name`, else `dflt`.
-inline int tune(const char* name, int dflt) {
-  const char* e = getenv(name);
-  return e ? atoi(e) : dflt;
-}
 
 // Head-role tables passed to kernels by value (n_q_heads <= 128).
 struct HeadTable {

@@ -14,21 +14,12 @@
 
 namespace rtp {
 
-#ifndef RTP_IS_THREADS
-#define RTP_IS_THREADS 256
-#endif
 // tokens per workgroup: 2048 (64 KiB of index keys) for the plain pass; the pass that also builds the
 // histogram takes 4096 so that half as many workgroups zero, scan and flush a 2048-bin LDS histogram
 // (measured on batch 8 x 131072: 27.5 us against 28.4 us with 2048; the plain pass prefers 2048)
-constexpr int kIsThreads = RTP_IS_THREADS;
-#ifndef RTP_IS_HIST_MULT
-#define RTP_IS_HIST_MULT 16
-#endif
-constexpr int kIsChunkPlain = 8 * kIsThreads, kIsChunkHist = RTP_IS_HIST_MULT * kIsThreads;
-#ifndef RTP_IS_BATCH
-#define RTP_IS_BATCH 16
-#endif
-constexpr int kIsBatch = RTP_IS_BATCH;   // 16-byte loads in flight per lane
+constexpr int kIsThreads = 256;
+constexpr int kIsChunkPlain = 8 * kIsThreads, kIsChunkHist = 16 * kIsThreads;
+constexpr int kIsBatch = 16;             // 16-byte loads in flight per lane
 
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 

@@ -38,14 +38,8 @@ namespace rtp {
 // Every workgroup repeats the scan of the previous level, and the workgroups resident on a compute unit
 // run their phases in step and share its vector ALUs: fewer, larger workgroups repeat less (and start
 // sooner: a launch of 1024 workgroups takes 2.5 us to get them all going), smaller ones balance better.
-#ifndef RTP_TP_THREADS
-#define RTP_TP_THREADS 512
-#endif
-constexpr int kTpThreads = RTP_TP_THREADS;
-#ifndef RTP_TP_CHUNK
-#define RTP_TP_CHUNK 8192
-#endif
-constexpr int kTpChunk = RTP_TP_CHUNK;     // scores per workgroup
+constexpr int kTpThreads = 512;
+constexpr int kTpChunk = 8192;             // scores per workgroup
 constexpr int kTpVec = kTpChunk / (kTpThreads * 4);   // float4 loads per thread
 
 struct RowState {          // one per row and launch (levels 2 and 3 leave one each)
@@ -54,7 +48,8 @@ struct RowState {          // one per row and launch (levels 2 and 3 leave one e
   uint64_t above;          // integer mass above the current prefix range INSIDE the level-1 bin
   uint64_t target;         // integer mass to reach inside the level-1 bin
   uint32_t prefix;         // key bits resolved so far (right-aligned)
-  int32_t flags;           // 0 ok, 1 = keep everything (p >= 1), -1 = invalid p, 2 = no finite score
+  int32_t flags;           // 0 ok, 1 = keep everything (p >= 1), -1 = invalid p, 2 = no finite score,
+                           // -2 = the row's largest score lies outside (-128, 128)
   float ref;               // reference score of the level-1 threshold bin
   int32_t shift;
 };
@@ -104,6 +99,7 @@ TopPLayout topp_layout(int32_t R, int64_t max_len) {
 // ---- histogram scans -------------------------------------------------------------------------------
 struct Scan1Result {       // level 1: bins carry different references, the scan runs in fp64
   int bin;                 // threshold bin (-1: the row has no mass at all)
+  int top;                 // highest bin that holds a score
   double above_base, total_d;
   uint64_t target;         // integer mass still to reach inside the threshold bin (1 .. bin mass)
   float ref;
@@ -139,7 +135,7 @@ __device__ __forceinline__ Scan1Result scan_level1(const uint64_t (&loc)[kBins1 
 #pragma unroll
   for (int w = 1; w < kTpThreads / 64; ++w) top = max(top, sh_i[w]);
   Scan1Result res;
-  res.bin = -1; res.above_base = 0.0; res.total_d = 0.0; res.target = 1; res.ref = 0.f;
+  res.bin = -1; res.top = top; res.above_base = 0.0; res.total_d = 0.0; res.target = 1; res.ref = 0.f;
   if (top < 0) { __syncthreads(); return res; }       // uniform: every thread sees the same `top`
   const double R = (double)bin_ref(top);
   double md[per];
@@ -384,6 +380,8 @@ __device__ __forceinline__ void level_body(const TopPArgs& a, const int c, const
       const Scan1Result s1 = scan_level1(prev_bins, pr, sh_d, sh_i, sh_dres, tab);
       if (s1.bin < 0) {
         flags = 2;
+      } else if (level1_bin_is_wide(s1.top)) {
+        flags = -2;
       } else {
         prefix = (uint32_t)s1.bin;
         ref = s1.ref;
@@ -701,7 +699,7 @@ __global__ __launch_bounds__(kTpThreads) void topp_write_kernel(const TopPArgs a
   const bool empty_row = prev.flags < 0 || prev.flags == 2;      // the same in every workgroup of the row
   if (empty_row) {
     have_res = true;
-    res_count = prev.flags < 0 ? -1 : 0;
+    res_count = prev.flags < 0 ? prev.flags : 0;
     res_tau = prev.flags < 0 ? __builtin_nanf("") : ninf;
     res_mass = 0.f;
     if (!ATTEND) {
@@ -1079,7 +1077,7 @@ static int32_t run_select(const char* who, const float* scores, int64_t score_st
   a.R = R;
   a.n_chunks = (int32_t)((max_len + kTpChunk - 1) / kTpChunk);
   a.rezero = level1_ready;
-  a.balance = tune("RTP_TUNE_GATHER_BALANCE", 1) != 0;
+  a.balance = 1;
   a.sel_idx = sel_idx;
   a.sel_stride = sel_stride;
   a.sel_count = sel_count;

@@ -72,12 +72,22 @@ __device__ __forceinline__ uint64_t fixed_weight(float s, float ref, int shift, 
   return (uint64_t)__double_as_longlong(r) & 0xFFFFFFFFFFFFFull;
 }
 
+// Level-1 bins are quarter binades of the score.  While |s| < 128 a bin is at most 16 wide, so a weight is
+// at least e^-16 * 2^shift (>= 2^8 for the longest row) and keeps a relative resolution of 2^-8 or far better.
+// From |s| = 128 on the bins are 32 and more wide and a weight relative to the bin's edge can round to
+// nothing; a row whose LARGEST score lies out there cannot be resolved and is reported as unsupported
+// (sel_count = -2) instead: such scores still mark their bin (weight 1), so the scan sees where the row's top is.
+constexpr int kBin1FirstWidePos = 1024 + 134 * 4;     // first bin of s >= 128
+constexpr int kBin1LastWideNeg = 1023 - 134 * 4;      // last bin (from below) of s <= -128
+__device__ __forceinline__ bool level1_bin_is_wide(int bin) { return bin >= kBin1FirstWidePos || bin <= kBin1LastWideNeg; }
+
 // Adds one score to a level-1 LDS histogram (2048 x u64).  -inf scores carry no mass; +inf and NaN
 // scores are not supported (they land in the top bins with weight 2^shift).
 __device__ __forceinline__ void level1_add(uint64_t* lh, float s, int shift, const double* tab) {
   if (s == -__builtin_huge_valf()) return;
   const int bin = (int)(float_key(s) >> 21);
-  const uint64_t w = fixed_weight(s, fminf(score_ref(s), 3.4028234663852886e38f), shift, tab);
+  uint64_t w = fixed_weight(s, fminf(score_ref(s), 3.4028234663852886e38f), shift, tab);
+  if (!w && level1_bin_is_wide(bin)) w = 1;
   if (w) atomicAdd((unsigned long long*)&lh[bin], (unsigned long long)w);
 }
 

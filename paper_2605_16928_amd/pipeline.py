@@ -12,7 +12,8 @@ DEV = "cuda:0"
 
 
 def layer_desc_of(layer: wl.Layer):
-    return rtp.layer_desc(layer.n_q_heads, layer.n_kv_heads, layer.ret_heads, layer.sink, layer.window)
+    return rtp.layer_desc(layer.n_q_heads, layer.n_kv_heads, layer.ret_heads, layer.sink, layer.window,
+                          softmax_scale=layer.softmax_scale, index_scale=layer.index_scale)
 
 
 def ws_alloc(nbytes: int) -> torch.Tensor:

@@ -34,6 +34,8 @@ class Layer:
     window: int
     head_dim: int = HEAD_DIM
     index_dim: int = INDEX_DIM
+    softmax_scale: float = 0.0      # 0 = the paper's 1/sqrt(head_dim)
+    index_scale: float = 0.0        # 0 = 1 (the indexer equation has no scale)
 
     @property
     def n_ret(self) -> int:
@@ -63,6 +65,24 @@ class DecodeWorkload:
     @property
     def T_tot(self) -> int:
         return int(self.K.shape[1])
+
+    def to(self, device) -> "DecodeWorkload":
+        """The same workload with every tensor on `device` (a workload drawn on the CPU replays
+        bit for bit on any machine, which a device-side generator does not promise)."""
+        return _moved(self, device)
+
+
+def _moved(w, device):
+    import dataclasses
+    kw = {}
+    for f in dataclasses.fields(w):
+        v = getattr(w, f.name)
+        if isinstance(v, torch.Tensor):
+            v = v.to(device)
+        elif isinstance(v, dict):
+            v = {k: (x.to(device) if isinstance(x, torch.Tensor) else x) for k, x in v.items()}
+        kw[f.name] = v
+    return type(w)(**kw)
 
 
 def _gen(seed: int, device) -> torch.Generator:
@@ -278,6 +298,9 @@ class PrefillWorkload:
     q_pre: Optional[torch.Tensor] = None   # bf16 [T, Hq, D]
     cluster_start: Optional[torch.Tensor] = None
     cluster_size: Optional[torch.Tensor] = None
+
+    def to(self, device) -> "PrefillWorkload":
+        return _moved(self, device)
 
 
 def make_prefill(name: str, layer: Layer, chunk_start: int, T: int, p: float, seed: int, device="cpu", *,

@@ -296,3 +296,31 @@ def test_prefill_calls_reject_a_row_stride_beyond_the_tile_offset_range():
 
     assert dense((1 << 24) + 8) == rtp.RTP_ERR_INVALID_ARG
     assert "2^24" in rtp.rtp_last_error()
+
+
+def test_decode_range_calls_refuse_more_than_1024_units():
+    """The range-source decode calls plan at most 1024 (sequence, KV head) units per call: a larger batch is
+    refused as unsupported before anything is launched (the header states the limit)."""
+    lib = rtp.lib()
+    L = _layer()                      # 2 KV heads
+    vp = C.c_void_p
+    for name in ("rtp_local_attn", "rtp_dense_attn"):
+        fn = getattr(lib, name)
+        ok_B, bad_B = 512, 513
+        assert fn(C.byref(L), vp(A), vp(A), vp(A), 128, 128 * 100, vp(A), vp(A), None, bad_B, 1, 4096,
+                  vp(A), None, vp(A), 1 << 40, None) == rtp.RTP_ERR_UNSUPPORTED
+        assert "exceeds 1024" in rtp.rtp_last_error()
+        assert getattr(rtp, name + "_workspace_bytes")(L, ok_B, 1, 4096) > 0
+
+
+def test_sparse_prefill_refuses_an_oversized_chunk_before_any_launch():
+    """T beyond what one launch's grid holds is an argument error like the others: with index projections given
+    (WQ != NULL) the call must not have enqueued its projection launch first -- the pointers here are fake, a
+    launch would fault."""
+    lib = rtp.lib()
+    L = _layer()
+    vp = C.c_void_p
+    T = 128 * 65535 + 1
+    rc = lib.rtp_sparse_attn_prefill(C.byref(L), vp(A), vp(A), vp(A), vp(A), 16 * 64, vp(A), vp(A), 128, 1 << 40,
+                                     0, T, C.c_float(0.9), vp(A), None, None, None, None, vp(A), 1 << 50, None)
+    assert rc == rtp.RTP_ERR_INVALID_ARG and b"too large" in lib.rtp_last_error()

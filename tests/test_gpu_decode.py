@@ -6,7 +6,8 @@ import torch
 
 from oracle import rtp_oracle as orc
 from paper_2605_16928_amd import rtp, workloads as wl
-from gpu_util import DEV, DecodeRun, oracle_inputs, check_scores, check_selection, check_selection_valid, check_out, i32
+from gpu_util import (DEV, DecodeRun, oracle_inputs, check_scores, check_selection, check_selection_valid, check_out,
+                      check_layer, attend_reference, i32)
 
 pytestmark = pytest.mark.gpu
 
@@ -90,8 +91,7 @@ def test_decode_path_matches_oracle(name):
             assert abs(lse[b, h] - l) < 2e-3
 
     # ---- stage 4: whole layer (retrieval + local rows) against the oracle end to end ----
-    check_out(out, ref["out"], f"{name} layer")
-    assert np.allclose(lse, ref["lse"], atol=2e-3, rtol=0)
+    check_layer(out, lse, w, oi, ref, sets, f"{name} layer")
 
     # ---- dense comparison kernel ----
     dout = torch.zeros_like(run.out)
@@ -168,6 +168,101 @@ def test_topp_edge_rows():
             assert t[r] == np.float32(ref["tau"])
     assert c[0] == 5 and c[1] == 1 and c[2] == 2 and c[3] == 8 and c[8] == 1
     assert c[4] == 9001                        # all-equal row: every entry ties with the threshold
+
+
+def test_topp_large_score_magnitudes():
+    """The indexer equation (Sec. 3.2) has no scale, so scores far from 0 are reachable.  The selector's masses
+    are fixed point relative to the edge of a score's quarter binade: rows whose largest score lies inside
+    (-128, 128) must match the oracle as any other row (spread-out rows, rows sitting at +-100, a row whose
+    tail reaches below -128), rows whose largest score lies outside are reported with sel_count = -2."""
+    print("[case] topp large magnitudes", flush=True)
+    rng = np.random.default_rng(8)
+    n_max = 131072
+    stride = n_max
+    rows, ps = [], []
+
+    def add(s, p):
+        rows.append(np.asarray(s, dtype=np.float32))
+        ps.append(p)
+
+    add(rng.standard_normal(50000) * 20.0, 0.9)                      # spread over +-90
+    add(rng.standard_normal(50000) * 20.0, 0.999)
+    add(100.0 + rng.standard_normal(131072), 0.9)                    # everything in [96, 104]: bins 8 and 16 wide
+    add(100.0 + rng.standard_normal(131072) * 0.3, 0.95)
+    add(-100.0 + rng.standard_normal(70001), 0.9)
+    add(np.concatenate([[127.9], 64.5 + rng.standard_normal(30000) * 3.0]), 0.99)   # maximum just inside
+    add(np.concatenate([rng.standard_normal(9000) * 40.0 - 120.0, [5.0]]), 0.9)     # tail far below -128
+    add(64.01 + rng.random(131072) * 0.5, 0.5)                       # bottom of a 16-wide bin, flat
+    add(np.concatenate([[128.0], rng.standard_normal(5000)]), 0.9)   # unsupported: maximum at +128
+    add(rng.standard_normal(5000) * 50.0 + 200.0, 0.9)               # unsupported
+    add(-128.0 - rng.random(5000) * 30.0, 0.9)                       # unsupported: maximum <= -128
+    n_bad = 3
+    R = len(rows)
+    sc = torch.full((R, stride), float("nan"), dtype=torch.float32)
+    for r, s in enumerate(rows):
+        sc[r, :len(s)] = torch.from_numpy(s)
+    sc = sc.to(DEV)
+    row_len = i32([len(s) for s in rows])
+    p = torch.tensor(ps, dtype=torch.float32, device=DEV)
+    sel = torch.full((R, stride), -1, dtype=torch.int32, device=DEV)
+    cnt = torch.full((R,), -9, dtype=torch.int32, device=DEV)
+    tau = torch.zeros(R, device=DEV)
+    mass = torch.zeros(R, device=DEV)
+    ws = torch.empty(rtp.rtp_topp_workspace_bytes(R, n_max), dtype=torch.uint8, device=DEV)
+    rtp.rtp_topp_select(sc, stride, row_len, p, R, n_max, sel, stride, cnt, tau, mass, ws)
+    torch.cuda.synchronize()
+    c, idx, t, m = cnt.cpu().numpy(), sel.cpu().numpy(), tau.cpu().numpy(), mass.cpu().numpy()
+    for r, s in enumerate(rows):
+        if r >= R - n_bad:
+            assert c[r] == -2, f"row {r}: count {c[r]}, expected the unsupported-magnitude mark"
+            continue
+        s64 = s.astype(np.float64)
+        ref = orc.topp_select(s64, ps[r])
+        check_selection(np.sort(idx[r, :c[r]]), s64, ref, ps[r], f"row {r}")
+        assert t[r] == np.float32(ref["tau"]) and abs(m[r] - ref["mass"]) <= 1e-4, (r, t[r], ref["tau"], m[r], ref["mass"])
+
+
+def test_decode_step_with_an_index_scale():
+    """index_scale = 8 puts the planted scores of configuration 2's law near 80 and the background over +-35:
+    the whole step against the oracle; index_scale = 16 moves the planted scores past 128: every retrieval row
+    is reported unsupported (sel_count = -2, zero output rows), the local heads are served as always."""
+    print("[case] decode step with an index scale", flush=True)
+    w = wl.c2("cpu", ctx=20000, batch=2, p=0.9, seed=9)
+    w.layer.index_scale = 8.0
+    w = w.to(DEV)
+    oi = oracle_inputs(w)
+    ref = orc.decode_layer(**oi)
+    assert max(float(s.max()) for s in ref["scores"]) > 64.0
+    for fuse in (False, True):
+        run = DecodeRun(w, fuse_level1=fuse)
+        run.step_one_stream()
+        sets, cnt = run.sel_sets()
+        s_gpu = run.scores.cpu().numpy()
+        for r in range(run.R):
+            n = w.ctx_len[r // w.layer.n_ret]
+            slack = float(np.abs(s_gpu[r, :n] - ref["scores"][r]).max())
+            assert slack <= 1e-5 * 80.0
+            check_selection_valid(sets[r], ref["scores"][r], float(w.p_rows[r]), slack, f"scale 8 row {r}")
+        check_layer(run.out_f64(), run.lse.cpu().numpy(), w, oi, ref, sets, "scale 8")
+    w.layer.index_scale = 16.0
+    oi = oracle_inputs(w)
+    ref = orc.decode_layer(**oi)
+    assert min(float(s.max()) for s in ref["scores"]) > 128.0
+    L = w.layer
+    for form in ("five", "one_call"):
+        run = DecodeRun(w)
+        run.out.fill_(3.0)
+        if form == "five":
+            run.step()
+        else:
+            run.step_one_stream()
+        out = run.out_f64()
+        assert (run.sel_count == -2).all(), run.sel_count.tolist()
+        for h in range(L.n_q_heads):
+            if h in L.ret_heads:
+                assert np.all(out[:, h] == 0.0)
+            else:
+                check_out(out[:, h], ref["out"][:, h], f"scale 16 local head {h}")
 
 
 def test_sparse_attn_degenerate_sets():
@@ -262,20 +357,7 @@ def test_level1_in_score_pass_gives_the_same_selection():
             assert torch.equal(a, b, ) if a.dtype != torch.float32 else torch.equal(a.nan_to_num(), b.nan_to_num())
 
 
-def _attend_reference(w, oi, sets):
-    """The oracle's attention of every retrieval row over the given sets: {(b, h): (out, lse)}."""
-    L = w.layer
-    sc = 1.0 / np.sqrt(128.0)
-    ref = {}
-    for b in range(w.B):
-        t0, n = w.seq_start[b], w.ctx_len[b]
-        for j, h in enumerate(L.ret_heads):
-            kvh = h // (L.n_q_heads // L.n_kv_heads)
-            if len(sets[b * L.n_ret + j]) == 0:
-                continue
-            ref[(b, h)] = orc.attend(oi["q_bits"][b, h], oi["K_bits"][kvh, t0:t0 + n], oi["V_bits"][kvh, t0:t0 + n],
-                                     sets[b * L.n_ret + j], sc)
-    return ref
+_attend_reference = attend_reference
 
 
 @pytest.mark.parametrize("name", ["small", "small_proj", "g1", "g2", "c2_small", "c5_small"])
@@ -394,7 +476,7 @@ def test_decode_attention_in_one_call_matches_oracle(name):
                     o, l = ref["out"][b, h], ref["lse"][b, h]
                 check_out(out[b, h], o, f"{name} b{b} h{h}")
                 assert abs(lse[b, h] - l) < 2e-3
-        check_out(out, ref["out"], f"{name} layer")
+        check_layer(out, lse, w, oi, ref, sets, f"{name} layer")
 
 
 def test_decode_step_replays_from_a_hip_graph():

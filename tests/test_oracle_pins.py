@@ -670,3 +670,54 @@ def test_paged_rows_by_construction_and_attention_is_layout_independent():
         assert np.array_equal(o_p, o_c) and l_p == l_c
     # hand case: page size 4, table [2, 0]: token 5 -> page 0 of the pool ... row 0 * 4 + 1
     assert orc.paged_rows([2, 0], 4, [0, 3, 4, 5]).tolist() == [8, 11, 0, 1]
+
+
+# =====================================================================================================
+# the layer drivers' projection branch: which q_pre row meets which W^Q
+# =====================================================================================================
+def test_layer_drivers_project_the_retrieval_heads_own_pre_rope_query():
+    """Query side of the indexer equation (Sec. 3.2): the index query of retrieval head h = ret_heads[j] is
+    W^Q_j applied to q_pre of query head h -- not of head j, not of the KV head.  With one-hot projections the
+    index query must copy chosen columns of q_pre[., ret_heads[j]] bit for bit (every head's q_pre is different,
+    so any other pairing shows), in the decode driver and in the prefill driver; and the scores the drivers go
+    on to select from must be the plain dot products of those copied columns with the index keys."""
+    rng = np.random.default_rng(17)
+    B, Hq, Hkv, d, r = 3, 8, 2, 128, 16
+    ret = [1, 6, 7]                                      # none equal to its own position j in the list
+    ctx = [5, 9, 7]
+    start = [0, 5, 14]
+    T_tot = sum(ctx)
+    q_pre = rand_bf16(rng, (B, Hq, d))
+    cols = np.stack([rng.choice(d, size=r, replace=False) for _ in ret])
+    WQ = np.zeros((len(ret), r, d), dtype=np.float32)
+    for j in range(len(ret)):
+        WQ[j, np.arange(r), cols[j]] = 1.0
+    kI = rand_bf16(rng, (len(ret), T_tot, r))
+    common = dict(K_bits=rand_bf16(rng, (Hkv, T_tot, d)), V_bits=rand_bf16(rng, (Hkv, T_tot, d)), kI_bits=kI,
+                  n_q_heads=Hq, n_kv_heads=Hkv, ret_heads=ret, sink=1, window=3)
+    out = orc.decode_layer(q_bits=rand_bf16(rng, (B, Hq, d)), seq_start=start, ctx_len=ctx,
+                           p_rows=np.full(B * len(ret), 0.7), WQ=WQ, q_pre_bits=q_pre, **common)
+    for b in range(B):
+        for j, h in enumerate(ret):
+            assert np.array_equal(out["qI_bits"][b, j], q_pre[b, h][cols[j]]), (b, j, h)
+            for other in range(Hq):
+                if other != h:
+                    assert not np.array_equal(out["qI_bits"][b, j], q_pre[b, other][cols[j]])
+            # scores by exact rational arithmetic from the copied columns
+            row = b * len(ret) + j
+            n = 2
+            exact = sum(bf16_fraction(int(q_pre[b, h][cols[j][i]])) * bf16_fraction(int(kI[j, start[b] + n, i]))
+                        for i in range(r))
+            assert abs(Fraction(float(out["scores"][row][n])) - exact) <= abs(exact) * Fraction(1, 2 ** 48)
+    # prefill driver: q_pre is [T, Hq, d]; one sequence, queries at chunk_start + t
+    T = 4
+    q_pre_t = rand_bf16(rng, (T, Hq, d))
+    rows = [(t, h) for t in range(T) for h in ret]
+    res = orc.prefill_rows(rows=rows, q_bits=rand_bf16(rng, (T, Hq, d)), chunk_start=6, p=0.7, WQ=WQ,
+                           q_pre_bits=q_pre_t, **common)
+    for a in res:
+        j = ret.index(a["h"])
+        assert np.array_equal(a["qI_bits"], q_pre_t[a["t"], a["h"]][cols[j]]), (a["t"], a["h"])
+        exact = sum(bf16_fraction(int(q_pre_t[a["t"], a["h"]][cols[j][i]])) * bf16_fraction(int(kI[j, 3, i]))
+                    for i in range(r))
+        assert abs(Fraction(float(a["scores"][3])) - exact) <= abs(exact) * Fraction(1, 2 ** 48)
