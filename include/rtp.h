@@ -151,6 +151,21 @@ int32_t rtp_topp_select(const float* scores, int64_t score_stride, const int32_t
                         float* tau, float* mass, int32_t level1_ready,
                         void* ws, size_t ws_bytes, void* stream);
 
+/* rtp_topp_select for callers that cannot allocate device memory or pass a workspace (code under HIP graph
+ * capture, tight serving loops, harnesses that forbid allocation): the same kernels, results and argument
+ * rules as rtp_topp_select(..., level1_ready = 0, ...), with the scratch in a buffer built into the library
+ * (RTP_TOPP_NOALLOC_WS_BYTES of device memory per GPU, held until the process ends).  The call allocates
+ * nothing and records kernel launches only.  Shapes whose scratch, rtp_topp_workspace_bytes(R, max_len), exceeds
+ * the buffer are refused with RTP_ERR_WORKSPACE before anything is enqueued (32 rows of 131072 scores need
+ * 1.5 MiB, 64 rows 3.0 MiB, 8 rows of 1048576 scores 0.5 MiB).  Every call on a GPU uses that GPU's one buffer:
+ * calls that overlap in time on the same GPU (different streams or threads) race; calls on one stream are fine.
+ */
+#define RTP_TOPP_NOALLOC_WS_BYTES (4u << 20)
+int32_t rtp_topp_select_noalloc(const float* scores, int64_t score_stride, const int32_t* row_len,
+                                const float* p, int32_t R, int64_t max_len,
+                                int32_t* sel_idx, int64_t sel_stride, int32_t* sel_count,
+                                float* tau, float* mass, void* stream);
+
 /* ---------------------------------------------------------------------------------------------
  * (3) Exact softmax attention over the selected tokens, decode, retrieval heads only --
  * Sec. 3.2, sparse-attention equation.

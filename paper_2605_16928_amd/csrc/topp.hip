@@ -30,6 +30,8 @@
 
 #include <stdlib.h>
 
+#include <mutex>
+
 namespace rtp {
 
 // Workgroup shape, measured on batch 8 x 131072 and batch 1 x 1048576 (whole decode step, us):
@@ -1137,6 +1139,53 @@ extern "C" int32_t rtp_topp_select(const float* scores, int64_t score_stride, co
   if (!p) return fail(RTP_ERR_INVALID_ARG, "rtp_topp_select: NULL tensor pointer");
   return run_select("rtp_topp_select", scores, score_stride, row_len, p, nullptr, R, max_len, sel_idx, sel_stride,
                     sel_count, tau, mass, level1_ready, ws, ws_bytes, stream);
+}
+
+// ---- rtp_topp_select for callers that cannot allocate --------------------------------------------------
+// The workspace of the call is a file-scope device array instead of a caller buffer.  In host code the
+// array's name is only a stand-in: its device address is asked for once per device (with that device
+// current) and kept; every launch takes that address.
+constexpr size_t kNoAllocBytes = RTP_TOPP_NOALLOC_WS_BYTES;
+static __device__ __align__(256) unsigned char g_noalloc_scratch[kNoAllocBytes];
+constexpr int kNoAllocMaxDevices = 64;
+static void* g_noalloc_ptr[kNoAllocMaxDevices];          // per device; written once under the mutex below
+static std::mutex g_noalloc_mutex;
+
+static int32_t noalloc_scratch(const char* who, void** out) {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kNoAllocMaxDevices)
+    return fail(RTP_ERR_HIP, "%s: no current device (or device index >= %d)", who, kNoAllocMaxDevices);
+  std::lock_guard<std::mutex> lock(g_noalloc_mutex);
+  if (!g_noalloc_ptr[dev]) {
+    void* ptr = nullptr;
+    const hipError_t e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(g_noalloc_scratch));
+    if (e != hipSuccess || !ptr)
+      return fail(RTP_ERR_HIP, "%s: hipGetSymbolAddress failed: %s", who, hipGetErrorString(e));
+    g_noalloc_ptr[dev] = ptr;
+  }
+  *out = g_noalloc_ptr[dev];
+  return RTP_OK;
+}
+
+extern "C" int32_t rtp_topp_select_noalloc(const float* scores, int64_t score_stride, const int32_t* row_len,
+                                           const float* p, int32_t R, int64_t max_len,
+                                           int32_t* sel_idx, int64_t sel_stride, int32_t* sel_count,
+                                           float* tau, float* mass, void* stream) {
+  const char* who = "rtp_topp_select_noalloc";
+  if (!p) return fail(RTP_ERR_INVALID_ARG, "%s: NULL tensor pointer", who);
+  if (R <= 0 || R > 65535) return fail(RTP_ERR_INVALID_ARG, "%s: R must be in [1, 65535]", who);
+  if (max_len <= 0 || max_len > RTP_MAX_ROW_LEN)
+    return fail(RTP_ERR_INVALID_ARG, "%s: max_len must be in [1, %d]", who, RTP_MAX_ROW_LEN);
+  const size_t need = topp_layout(R, max_len).total;
+  if (need > kNoAllocBytes)
+    return fail(RTP_ERR_WORKSPACE, "%s: R = %d rows of up to %lld scores need %zu bytes of scratch, the built-in "
+                "buffer holds %zu (use rtp_topp_select with a workspace of your own)", who, R, (long long)max_len, need,
+                kNoAllocBytes);
+  void* ws = nullptr;
+  const int32_t rc = noalloc_scratch(who, &ws);
+  if (rc != RTP_OK) return rc;
+  return run_select(who, scores, score_stride, row_len, p, nullptr, R, max_len, sel_idx, sel_stride, sel_count, tau, mass,
+                    0, ws, kNoAllocBytes, stream);
 }
 
 extern "C" int32_t rtp_topk_select(const float* scores, int64_t score_stride, const int32_t* row_len,

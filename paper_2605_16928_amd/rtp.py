@@ -21,7 +21,7 @@ RTP_OK, RTP_ERR_INVALID_ARG, RTP_ERR_UNSUPPORTED, RTP_ERR_WORKSPACE, RTP_ERR_HIP
 EXPORTS = [
     "rtp_last_error", "rtp_version",
     "rtp_index_score",
-    "rtp_topp_workspace_bytes", "rtp_topp_workspace_init", "rtp_topp_select",
+    "rtp_topp_workspace_bytes", "rtp_topp_workspace_init", "rtp_topp_select", "rtp_topp_select_noalloc",
     "rtp_sparse_attn_decode_workspace_bytes", "rtp_sparse_attn_decode",
     "rtp_sparse_attn_prefill_workspace_bytes", "rtp_sparse_attn_prefill",
     "rtp_local_attn_workspace_bytes", "rtp_local_attn",
@@ -85,6 +85,8 @@ def lib() -> C.CDLL:
     L.rtp_topp_workspace_bytes.argtypes = [i32, i64]
     L.rtp_topp_select.restype = i32
     L.rtp_topp_select.argtypes = [vp, i64, vp, vp, i32, i64, vp, i64, vp, vp, vp, i32, vp, sz, vp]
+    L.rtp_topp_select_noalloc.restype = i32
+    L.rtp_topp_select_noalloc.argtypes = [vp, i64, vp, vp, i32, i64, vp, i64, vp, vp, vp, vp]
     L.rtp_topp_workspace_init.restype = i32
     L.rtp_topp_workspace_init.argtypes = [vp, sz, vp]
     L.rtp_sparse_attn_decode_workspace_bytes.restype = sz
@@ -190,6 +192,12 @@ def rtp_topp_select(scores, score_stride, row_len, p, R, max_len, sel_idx, sel_s
     _check(lib().rtp_topp_select(_ptr(scores), score_stride, _ptr(row_len), _ptr(p), R, max_len, _ptr(sel_idx),
                                  sel_stride, _ptr(sel_count), _ptr(tau), _ptr(mass), level1_ready, _ptr(ws),
                                  _nbytes(ws), _stream(stream)))
+
+
+def rtp_topp_select_noalloc(scores, score_stride, row_len, p, R, max_len, sel_idx, sel_stride, sel_count,
+                            tau, mass, stream=None):
+    _check(lib().rtp_topp_select_noalloc(_ptr(scores), score_stride, _ptr(row_len), _ptr(p), R, max_len, _ptr(sel_idx),
+                                         sel_stride, _ptr(sel_count), _ptr(tau), _ptr(mass), _stream(stream)))
 
 
 def rtp_sparse_attn_decode_workspace_bytes(layer, B, max_sel) -> int:
