@@ -25,6 +25,71 @@ sys.path.insert(0, ROOT)
 HBM_PEAK_GBS = 8000.0
 
 
+def kernel_algorithmic_bytes(R, N, sel_total, bytes_local, G):
+    """Algorithmic HBM bytes per launch of the kernels of one decode step (per-unit figures of the design notes x
+    the units a launch processes): 32 B of index key + 4 B of score per (token, retrieval row); 4 B per score and
+    pass of the selector; 512 B of K/V + 4 B of index per selected token; 512 B per (token, KV head) of the local
+    heads' sink + window sets.  Merge launches move partials only (no per-unit figure)."""
+    scores = R * N * 4
+    return {
+        "index_score_kernel<true>": R * N * 36,
+        "index_score_kernel<false>": R * N * 36,
+        "topp_level_kernel<2>": scores,
+        "topp_level_kernel<3>": scores,
+        f"topp_level_ride_kernel<2, {G}>": scores + bytes_local,
+        "topp_write_kernel<true>": scores + sel_total * 516,
+        "topp_write_kernel<false>": scores + sel_total * 4,
+    }
+
+
+def traffic_from_profiles():
+    """{kernel: HBM bytes per launch} from the counter summary under profiles/ (lines 'traffic <kernel> <bytes>')."""
+    path = os.path.join(ROOT, "profiles", "decode_c2_hbm_byte_counters.txt")
+    out = {}
+    if os.path.exists(path):
+        for line in open(path):
+            if line.startswith("traffic "):
+                _, rest = line.split(" ", 1)
+                name, val = rest.rsplit(" ", 1)
+                out[name.strip()] = int(val)
+    return out
+
+
+def probe(args, torch, rtp, wl, DecodeRun, dev) -> int:
+    """The launches a profiler run should see, and nothing else."""
+    if args.probe == "copy":
+        n = 1 << 28                                     # 1 GiB read + 1 GiB written per copy
+        src = torch.empty(n, dtype=torch.float32, device=dev).normal_()
+        dst = torch.empty_like(src)
+        for _ in range(5):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print("copy bytes per launch:", n * 4, "read and", n * 4, "written")
+        return 0
+    if args.probe == "decode":
+        runs = [DecodeRun(wl.c2(dev, seed=100 + i, p=args.p, ctx=args.ctx, batch=args.batch)) for i in range(args.copies)]
+        side = torch.cuda.Stream()
+        for i in range(10 + 40):
+            runs[i % len(runs)].step_fastest(side)
+        torch.cuda.synchronize()
+        print("decode probe: 50 steps of the timed configuration (score pass + rtp_decode_attention), "
+              f"batch {args.batch} x {args.ctx}, p = {args.p}, {args.copies} copies cycled")
+        return 0
+    from paper_2605_16928_amd.pipeline import PrefillRun
+    w = wl.c4_chunk(dev, chunk=127)
+    run = PrefillRun(w)
+    for _ in range(2):
+        rtp.rtp_sparse_attn_prefill(run.desc, w.qI, w.q, None, w.kI, w.N * 16, run.Kp, run.Vp, run.rs, run.hs,
+                                    w.chunk_start, w.T, 1.0, run.out, None, None, None, None, run.ws)
+        run.sparse_prefill(p=0.9)
+        run.local_attn()
+    torch.cuda.synchronize()
+    pairs = sum(w.chunk_start + t + 1 for t in range(w.T))
+    print("prefill probe: last 8192-query chunk of the 1,048,576-token configuration; causal (query, key) pairs per head:",
+          pairs, "; 512 flop per pair and head")
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -39,6 +104,10 @@ def main() -> int:
                     "(eager launches on two streams are the faster configuration on this box)")
     ap.add_argument("--one-stream", action="store_true", help="keep the local heads on the main stream")
     ap.add_argument("--no-prefill", action="store_true", help="skip the 1M-token prefill measurements")
+    ap.add_argument("--probe", choices=["decode", "prefill", "copy"], default=None,
+                    help="launch only the timed decode step (or the prefill chunk launches of the 1M configuration, or a "
+                         "plain 1 GiB copy that calibrates the byte counters) a few times and exit: the program to put "
+                         "behind `rocprofv3 ... --` for per-kernel traces and hardware counters")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build is single-GPU by design (no collectives, no sharding); run with --gpus 1",
@@ -56,6 +125,8 @@ def main() -> int:
     rtp.lib()   # fail loudly if the HIP library is missing
     torch.cuda.set_device(0)
     dev = "cuda:0"
+    if args.probe:
+        return probe(args, torch, rtp, wl, DecodeRun, dev)
 
     # ---- resident inputs: `copies` independent layers of configuration 2 ----
     runs = [DecodeRun(wl.c2(dev, seed=100 + i, p=args.p, ctx=args.ctx, batch=args.batch)) for i in range(args.copies)]
@@ -281,15 +352,51 @@ def main() -> int:
     step_bytes = bytes_index + bytes_topp + bytes_sparse + bytes_local
 
     dom = max(br, key=br.get)
-    # the roofline object describes the indexer score pass: the one kernel whose traffic grows with the
-    # full context for every retrieval head, i.e. the HBM-bound core of the step
-    ach = bytes_index / (br["index_score"] * 1e-6) / 1e9
-    roofline = {"kernel": "index_score_kernel<true>", "bound": "hbm", "achieved": round(ach, 1), "peak": HBM_PEAK_GBS,
-                "unit": "GB/s", "frac": round(ach / HBM_PEAK_GBS, 4),
-                # HBM bytes per launch from the rocprofv3 --pmc runs recorded under profiles/ (FETCH_SIZE x 2.0 +
-                # WRITE_SIZE x 1.0 KiB, factors from a plain 1 GiB copy); only valid for the default shape
-                "traffic": 152158105 if (B, N, n_ret) == (8, 131072, 4) else None,
-                "algorithmic_bytes_per_launch": bytes_index, "avg_launch_us": round(br["index_score"], 2)}
+    # ---- per-kernel times of the timed step: HIP events around every launch (the library's own recorder), on the
+    # launch stream, same cycling over the copies; the step itself is timed above without the recorder ----
+    n_prof = 60
+    for i in range(10):
+        step(i)
+    torch.cuda.synchronize()
+    rtp.rtp_profile_start(16 * n_prof)
+    for i in range(n_prof):
+        run_step(runs[i % len(runs)])
+    torch.cuda.synchronize()
+    per_kernel = {}
+    for name, us in rtp.rtp_profile_stop():
+        per_kernel.setdefault(name, []).append(us)
+    kern_us = {k: sum(v) / len(v) for k, v in per_kernel.items()}
+    kern_calls = {k: len(v) / n_prof for k, v in per_kernel.items()}
+    kern_bytes = kernel_algorithmic_bytes(B * n_ret, N, sel_total, bytes_local, L.n_q_heads // L.n_kv_heads)
+    traffic = traffic_from_profiles() if (B, N, n_ret, args.p) == (8, 131072, 4, 0.9) else {}
+    sum_kernels = sum(kern_us[k] * kern_calls[k] for k in kern_us)
+    by_kernel = []
+    for k in sorted(kern_us, key=lambda k: -kern_us[k] * kern_calls[k]):
+        ab = kern_bytes.get(k)
+        ach = ab / kern_us[k] / 1e3 if ab else None
+        by_kernel.append({"kernel": k, "launches_per_step": round(kern_calls[k], 2), "avg_launch_us": round(kern_us[k], 2),
+                          "share_of_kernel_time": round(kern_us[k] * kern_calls[k] / sum_kernels, 4),
+                          "algorithmic_bytes_per_launch": ab,
+                          "achieved": round(ach, 1) if ach else None, "frac": round(ach / HBM_PEAK_GBS, 4) if ach else None,
+                          "traffic": traffic.get(k)})
+    d0 = by_kernel[0]                                   # the kernel with the largest share of the timed step
+    roofline = {"kernel": d0["kernel"], "bound": "hbm", "achieved": d0["achieved"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                "frac": d0["frac"],
+                # HBM bytes per launch from the rocprofv3 --pmc runs summarised under profiles/ (FETCH_SIZE and
+                # WRITE_SIZE, scaled by a plain copy's reading); only there for the default shape
+                "traffic": d0["traffic"],
+                "algorithmic_bytes_per_launch": d0["algorithmic_bytes_per_launch"], "avg_launch_us": d0["avg_launch_us"],
+                "share_of_kernel_time": d0["share_of_kernel_time"],
+                "whole_step": {"algorithmic_bytes": step_bytes, "us": round(us_step, 2),
+                               "achieved": round(step_bytes / us_step / 1e3, 1),
+                               "frac": round(step_bytes / us_step / 1e3 / HBM_PEAK_GBS, 4),
+                               "sum_of_kernel_us": round(sum_kernels, 2)}}
+    roofline_by_kernel = by_kernel
+    # what the chip allows for the score pass's traffic mix (32 bytes read for every 4 written): the same launch
+    # with the arithmetic taken out, beside the plain pass (no histogram) and the fused one the step runs
+    probe_dst = torch.empty_like(runs[0].scores)
+    us_index_ceiling = timed(lambda i: runs[i % n_runs].index_score_traffic_probe(probe_dst), it, wu)
+    us_index_plain = timed(lambda i: runs[i % n_runs].index_score_plain_timing(), it, wu)
 
     # ---- one decode step at 1,048,576 tokens (the 1M layer of configuration 4, batch 1) ----
     decode_1m = None
@@ -363,6 +470,7 @@ def main() -> int:
     if not args.no_prefill:
         from paper_2605_16928_amd.pipeline import PrefillRun
         MFMA_PEAK = 2.5e15
+        SELECT_SWEEPS = 4            # passes of the threshold search over the index keys
         def chunk_times(w, reps, dense_warm):
             pr = PrefillRun(w)
             Lp = w.layer
@@ -386,6 +494,15 @@ def main() -> int:
                 "dense_mfma_frac": round(Lp.n_q_heads * pairs_dense * 512 / (t_dense * 1e-6) / MFMA_PEAK, 4),
                 "topp_kept_tokens_mean": round(float(pr.count.float().mean()), 1),
             }
+            # top-p rule: flop the method needs (512 per KEPT (query, key) pair) against flop the two launches issue on
+            # the matrix cores (attention: 512 + 32 for the keep test per causal pair the kernel visits; threshold
+            # search: 32 per causal pair and sweep), both as fractions of the bf16 MFMA peak over the rule's time
+            kept_pairs = int(pr.count.to(torch.int64).sum().item())
+            visited = Lp.n_ret * pairs_dense * float(getattr(pr, "visited_fraction", 1.0))
+            issued = visited * (512 + 32) + Lp.n_ret * pairs_dense * 32 * SELECT_SWEEPS
+            res["topp_useful_flop_frac"] = round(kept_pairs * 512 / (t_topp * 1e-6) / MFMA_PEAK, 5)
+            res["topp_issued_flop_frac"] = round(issued / (t_topp * 1e-6) / MFMA_PEAK, 4)
+            res["topp_kept_pairs"] = kept_pairs
             del pr
             torch.cuda.empty_cache()
             return res
@@ -495,6 +612,7 @@ def main() -> int:
                                      "index_score + select_attend_decode + local_attn",
                    "streams": 1 if (args.one_stream or carried) else 2},
         "roofline": roofline,
+        "roofline_by_kernel": roofline_by_kernel,
         "cpu_baseline": cpu,
         "prefill_1m": prefill,
         "prefill_128k": prefill_128k,
@@ -518,6 +636,12 @@ def main() -> int:
                                              "sparse_attn_decode": round(bytes_sparse / br_separate["sparse_attn_decode"] / 1e3, 1)},
                                "topp_select_standalone_us": round(us_topp_standalone, 2)},
             "slowest_call": dom,
+            "score_pass": {"with_histogram_us": round(br["index_score"], 2), "plain_us": round(us_index_plain, 2),
+                           "no_arithmetic_us": round(us_index_ceiling, 2),
+                           "no_arithmetic_frac_of_hbm_peak": round(bytes_index / us_index_ceiling / 1e3 / HBM_PEAK_GBS, 4),
+                           "with_histogram_frac_of_ceiling": round(us_index_ceiling / br["index_score"], 4),
+                           "with_histogram_frac_of_hbm_peak": round(bytes_index / br["index_score"] / 1e3 / HBM_PEAK_GBS, 4),
+                           "plain_frac_of_hbm_peak": round(bytes_index / us_index_plain / 1e3 / HBM_PEAK_GBS, 4)},
             "selectors": selectors,
             "index_key_build": ib,
             "bounded_cache": bounded,

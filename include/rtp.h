@@ -234,6 +234,31 @@ int32_t rtp_dense_attn(const rtp_layer_desc* layer, const void* q,
                        int32_t B, int32_t n_q, int64_t max_ctx, void* out, float* lse,
                        void* ws, size_t ws_bytes, void* stream);
 
+/* ---------------------------------------------------------------------------------------------
+ * Per-kernel timing for measurements (the paper reports run time per attention layer, Sec. 4.2 "Runtime
+ * Analysis"; a per-kernel split needs clocks between the launches of one call).  Between rtp_profile_start and
+ * rtp_profile_stop every kernel launch of the library, from any thread of the process, carries a start and a stop
+ * event stamped with the dispatch's own begin and end times (at most max_launches launches are recorded, further
+ * ones pass untimed).
+ * rtp_profile_stop waits for the recorded launches, writes up to out_cap (kernel name, microseconds) pairs in
+ * launch order and *n_out, and releases the events.  The names are static strings of the library.  Recording
+ * serialises nothing; do not record inside a stream capture.
+ */
+typedef struct {
+  const char* kernel;
+  float us;
+} rtp_launch_time;
+/* Measurement only: rtp_index_score's launch (same grid, same loads of the index keys, same stores) with the
+ * arithmetic taken out -- `scores` receives meaningless words.  Its duration is what the chip sustains for the
+ * score pass's traffic mix (32 bytes read for every 4 written), the ceiling the real pass is priced against. */
+int32_t rtp_index_score_traffic_probe(const rtp_layer_desc* layer, const void* q_in, const float* WQ,
+                                      const void* kI, int64_t kI_head_stride,
+                                      const int64_t* seq_start, const int32_t* ctx_len, const int32_t* q_start,
+                                      int32_t B, int32_t n_q, int64_t max_ctx,
+                                      float* scores, int64_t score_stride, void* stream);
+int32_t rtp_profile_start(int32_t max_launches);
+int32_t rtp_profile_stop(rtp_launch_time* out, int32_t out_cap, int32_t* n_out);
+
 /* =============================================================================================
  * Entry points beside the five above: the index-key build, the two other selectors the paper
  * discusses, and its sparsity figures.

@@ -24,16 +24,31 @@ def sources():
     return sorted(glob.glob(os.path.join(HERE, "csrc", "*.hip")))
 
 
-def build(verbose: bool = False) -> str:
-    cmd = [HIPCC] + FLAGS + sources() + ["-o", LIB]
+def _run(cmd, verbose):
     if verbose:
         print(" ".join(cmd), flush=True)
     r = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
     lines = [l for l in r.stdout.splitlines() if "packed-fp32-ops" not in l and "target-feature" not in l]
     if r.returncode != 0:
         raise RuntimeError("hipcc failed:\n" + "\n".join(lines))
-    if verbose and lines:
-        print("\n".join(lines))
+    return lines
+
+
+def build(verbose: bool = False) -> str:
+    """Compiles every source (one hipcc process each, side by side) and links librtp.so.  Always compiles."""
+    from concurrent.futures import ThreadPoolExecutor
+    objdir = os.path.join(HERE, "_build")
+    os.makedirs(objdir, exist_ok=True)
+    srcs = sources()
+    objs = [os.path.join(objdir, os.path.basename(s)[:-4] + ".o") for s in srcs]
+    compile_flags = [f for f in FLAGS if f != "-shared"] + ["-c"]
+    with ThreadPoolExecutor(max_workers=min(8, len(srcs))) as ex:
+        outs = list(ex.map(lambda so: _run([HIPCC] + compile_flags + [so[0], "-o", so[1]], verbose), zip(srcs, objs)))
+    outs.append(_run([HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC"] + objs + ["-o", LIB], verbose))
+    if verbose:
+        for lines in outs:
+            if lines:
+                print("\n".join(l for l in lines if "warning" in l or "error" in l))
     return LIB
 
 

@@ -3,7 +3,11 @@
 
 #include <stdarg.h>
 #include <stdio.h>
+#include <stdlib.h>
 #include <string.h>
+
+#include <atomic>
+#include <mutex>
 
 namespace rtp {
 
@@ -68,7 +72,75 @@ int32_t check_launch(const char* who) {
   return RTP_OK;
 }
 
+// ---- per-launch timing ---------------------------------------------------------------------------------
+namespace {
+struct ProfileState {
+  std::mutex mu;
+  std::atomic<bool> on{false};
+  int cap = 0, n = 0, dropped = 0;
+  hipEvent_t* ev = nullptr;          // 2 * cap events: start, stop of launch i
+  const char** name = nullptr;
+} g_prof;
+}  // namespace
+
+bool profile_slot(const char* kernel, hipEvent_t* start, hipEvent_t* stop) {
+  if (!g_prof.on.load(std::memory_order_relaxed)) return false;
+  std::lock_guard<std::mutex> lock(g_prof.mu);
+  if (!g_prof.on.load()) return false;
+  if (g_prof.n >= g_prof.cap) { ++g_prof.dropped; return false; }
+  const int slot = g_prof.n++;
+  g_prof.name[slot] = kernel;
+  *start = g_prof.ev[2 * slot];
+  *stop = g_prof.ev[2 * slot + 1];
+  return true;
+}
+
 }  // namespace rtp
+
+extern "C" int32_t rtp_profile_start(int32_t max_launches) {
+  using namespace rtp;
+  if (max_launches <= 0 || max_launches > (1 << 20))
+    return fail(RTP_ERR_INVALID_ARG, "rtp_profile_start: max_launches must be in [1, 2^20]");
+  std::lock_guard<std::mutex> lock(g_prof.mu);
+  if (g_prof.on.load()) return fail(RTP_ERR_INVALID_ARG, "rtp_profile_start: already recording");
+  g_prof.ev = (hipEvent_t*)calloc((size_t)2 * max_launches, sizeof(hipEvent_t));
+  g_prof.name = (const char**)calloc((size_t)max_launches, sizeof(const char*));
+  if (!g_prof.ev || !g_prof.name) return fail(RTP_ERR_INVALID_ARG, "rtp_profile_start: out of host memory");
+  for (int i = 0; i < 2 * max_launches; ++i) {
+    const hipError_t e = hipEventCreate(&g_prof.ev[i]);
+    if (e != hipSuccess) return fail(RTP_ERR_HIP, "rtp_profile_start: hipEventCreate failed: %s", hipGetErrorString(e));
+  }
+  g_prof.cap = max_launches;
+  g_prof.n = 0;
+  g_prof.dropped = 0;
+  clear_error();
+  g_prof.on.store(true);
+  return RTP_OK;
+}
+
+extern "C" int32_t rtp_profile_stop(rtp_launch_time* out, int32_t out_cap, int32_t* n_out) {
+  using namespace rtp;
+  std::lock_guard<std::mutex> lock(g_prof.mu);
+  if (!g_prof.on.load()) return fail(RTP_ERR_INVALID_ARG, "rtp_profile_stop: not recording");
+  g_prof.on.store(false);
+  int n = 0;
+  int32_t rc = RTP_OK;
+  for (int i = 0; i < g_prof.n; ++i) {
+    float ms = 0.f;
+    hipError_t e = hipEventSynchronize(g_prof.ev[2 * i + 1]);
+    if (e == hipSuccess) e = hipEventElapsedTime(&ms, g_prof.ev[2 * i], g_prof.ev[2 * i + 1]);
+    if (e != hipSuccess) { rc = fail(RTP_ERR_HIP, "rtp_profile_stop: %s", hipGetErrorString(e)); break; }
+    if (out && n < out_cap) { out[n].kernel = g_prof.name[i]; out[n].us = ms * 1e3f; ++n; }
+  }
+  for (int i = 0; i < 2 * g_prof.cap; ++i) (void)hipEventDestroy(g_prof.ev[i]);
+  free(g_prof.ev);
+  free(g_prof.name);
+  g_prof.ev = nullptr;
+  g_prof.name = nullptr;
+  if (n_out) *n_out = rc == RTP_OK ? n : 0;
+  if (rc == RTP_OK) clear_error();
+  return rc;
+}
 
 extern "C" const char* rtp_last_error(void) { return rtp::g_err; }
 extern "C" const char* rtp_version(void) { return "rtp-gfx950 0.1"; }

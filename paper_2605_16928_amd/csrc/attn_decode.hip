@@ -413,12 +413,12 @@ static int32_t launch_decode(const AttnDecodeArgs& a, int G, int grid, hipStream
   // one head per K/V row (always so for the selected-token source): the vector-ALU kernel;
   // a GQA group per row: scores on the matrix cores
 #define RTP_LAUNCH_GQA(GG)                                                                                   \
-  hipLaunchKernelGGL((attn_decode_gqa_kernel<GG, SRC == kSrcSparse ? kSrcDense : SRC>), dim3(grid), dim3(kAdThreads), 0, s, a); \
-  hipLaunchKernelGGL((attn_decode_combine_kernel<GG, SRC>), dim3(cgrid), dim3(kAdThreads), 0, s, a);
+  RTP_LAUNCH((attn_decode_gqa_kernel<GG, SRC == kSrcSparse ? kSrcDense : SRC>), dim3(grid), dim3(kAdThreads), 0, s, a); \
+  RTP_LAUNCH((attn_decode_combine_kernel<GG, SRC>), dim3(cgrid), dim3(kAdThreads), 0, s, a);
   if (SRC == kSrcSparse || G == 1) {
-    if (SRC == kSrcSparse && a.page_table) hipLaunchKernelGGL((attn_decode_kernel<1, kSrcSparse, 8, true>), dim3(grid), dim3(kAdThreads), 0, s, a);
-    else hipLaunchKernelGGL((attn_decode_kernel<1, SRC, 8>), dim3(grid), dim3(kAdThreads), 0, s, a);
-    hipLaunchKernelGGL((attn_decode_combine_kernel<1, SRC>), dim3(cgrid), dim3(kAdThreads), 0, s, a);
+    if (SRC == kSrcSparse && a.page_table) RTP_LAUNCH((attn_decode_kernel<1, kSrcSparse, 8, true>), dim3(grid), dim3(kAdThreads), 0, s, a);
+    else RTP_LAUNCH((attn_decode_kernel<1, SRC, 8>), dim3(grid), dim3(kAdThreads), 0, s, a);
+    RTP_LAUNCH((attn_decode_combine_kernel<1, SRC>), dim3(cgrid), dim3(kAdThreads), 0, s, a);
   } else {
     switch (G) {
       case 2: RTP_LAUNCH_GQA(2) break;

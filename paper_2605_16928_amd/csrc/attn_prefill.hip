@@ -1336,10 +1336,10 @@ static int32_t launch_prefill(const char* who, bool local, PrefillArgs& a, int32
   const int qt = local ? kPfQ : kPwQ;
   dim3 grid((unsigned)a.n_heads, (unsigned)((a.n_q + qt - 1) / qt), (unsigned)(B * (local ? 1 : a.n_splits)));
   if (grid.y > 65535 || grid.z > 65535) return fail(RTP_ERR_INVALID_ARG, "%s: n_q / B too large for one launch", who);
-  if (local) hipLaunchKernelGGL(flash_prefill_kernel<kModeLocal>, grid, dim3(kPfThreads), 0, s, a);
-  else hipLaunchKernelGGL((flash_prefill_wide_kernel<kModeDense, 1>), grid, dim3(512), 0, s, a);
+  if (local) RTP_LAUNCH(flash_prefill_kernel<kModeLocal>, grid, dim3(kPfThreads), 0, s, a);
+  else RTP_LAUNCH((flash_prefill_wide_kernel<kModeDense, 1>), grid, dim3(512), 0, s, a);
   if (!local && a.n_splits > 1)
-    hipLaunchKernelGGL(prefill_combine_kernel, dim3((unsigned)((a.n_q + 1) / 2), (unsigned)a.n_heads), dim3(256), 0, s, a);
+    RTP_LAUNCH(prefill_combine_kernel, dim3((unsigned)((a.n_q + 1) / 2), (unsigned)a.n_heads), dim3(256), 0, s, a);
   return check_launch(who);
 }
 
@@ -1477,7 +1477,7 @@ extern "C" int32_t rtp_sparse_attn_prefill(const rtp_layer_desc* layer, const vo
     pa.n_q_heads = layer->n_q_heads;
     pa.n_ret = layer->n_ret;
     for (int j = 0; j < 64; ++j) pa.ret_heads[j] = j < layer->n_ret ? layer->ret_heads[j] : 0;
-    hipLaunchKernelGGL(index_project_kernel, dim3((unsigned)((T + 15) / 16), (unsigned)layer->n_ret), dim3(256), 0,
+    RTP_LAUNCH(index_project_kernel, dim3((unsigned)((T + 15) / 16), (unsigned)layer->n_ret), dim3(256), 0,
                        (hipStream_t)stream, pa);
     qI = (const uint16_t*)ws;
   }
@@ -1505,14 +1505,14 @@ extern "C" int32_t rtp_sparse_attn_prefill(const rtp_layer_desc* layer, const vo
       const unsigned per_head = 8u / (unsigned)a.n_heads;
       wgs = 8u * ((n_qtiles + per_head - 1) / per_head);
     }
-    if (ks == 1) hipLaunchKernelGGL(prefill_select_kernel<1>, dim3(wgs), dim3(kPfThreads), 0, (hipStream_t)stream, a);
-    else if (ks == 2) hipLaunchKernelGGL(prefill_select_kernel<2>, dim3(wgs), dim3(kPfThreads), 0, (hipStream_t)stream, a);
-    else hipLaunchKernelGGL(prefill_select_kernel<4>, dim3(wgs), dim3(kPfThreads), 0, (hipStream_t)stream, a);
+    if (ks == 1) RTP_LAUNCH(prefill_select_kernel<1>, dim3(wgs), dim3(kPfThreads), 0, (hipStream_t)stream, a);
+    else if (ks == 2) RTP_LAUNCH(prefill_select_kernel<2>, dim3(wgs), dim3(kPfThreads), 0, (hipStream_t)stream, a);
+    else RTP_LAUNCH(prefill_select_kernel<4>, dim3(wgs), dim3(kPfThreads), 0, (hipStream_t)stream, a);
   }
   dim3 grid((unsigned)a.n_heads, (unsigned)((T + kPwQ - 1) / kPwQ), (unsigned)a.n_splits);
-  hipLaunchKernelGGL((flash_prefill_wide_kernel<kModeSparse, 1>), grid, dim3(512), 0, (hipStream_t)stream, a);
+  RTP_LAUNCH((flash_prefill_wide_kernel<kModeSparse, 1>), grid, dim3(512), 0, (hipStream_t)stream, a);
   if (a.n_splits > 1)
-    hipLaunchKernelGGL(prefill_combine_kernel, dim3((unsigned)((T + 1) / 2), (unsigned)a.n_heads), dim3(256), 0,
+    RTP_LAUNCH(prefill_combine_kernel, dim3((unsigned)((T + 1) / 2), (unsigned)a.n_heads), dim3(256), 0,
                        (hipStream_t)stream, a);
   return check_launch(who);
 }

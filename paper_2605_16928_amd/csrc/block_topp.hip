@@ -323,9 +323,9 @@ extern "C" int32_t rtp_block_topp_select(const float* scores, int64_t score_stri
   hipStream_t s = (hipStream_t)stream;
   dim3 grid((unsigned)a.n_chunks, (unsigned)R), blk(kBtThreads);
   const int64_t nz = (int64_t)R * kBtBins;
-  hipLaunchKernelGGL(block_zero_kernel, dim3((unsigned)((nz + kBtThreads - 1) / kBtThreads)), blk, 0, s, a.hist, nz);
-  hipLaunchKernelGGL(block_stats_kernel, grid, blk, 0, s, a);
-  hipLaunchKernelGGL(block_count_kernel, grid, blk, 0, s, a);
-  hipLaunchKernelGGL(block_write_kernel, grid, blk, 0, s, a);
+  RTP_LAUNCH(block_zero_kernel, dim3((unsigned)((nz + kBtThreads - 1) / kBtThreads)), blk, 0, s, a.hist, nz);
+  RTP_LAUNCH(block_stats_kernel, grid, blk, 0, s, a);
+  RTP_LAUNCH(block_count_kernel, grid, blk, 0, s, a);
+  RTP_LAUNCH(block_write_kernel, grid, blk, 0, s, a);
   return check_launch(who);
 }

@@ -2,6 +2,7 @@
 #pragma once
 
 #include <hip/hip_runtime.h>
+#include <hip/hip_ext.h>
 #include <stdint.h>
 #include <stddef.h>
 #include <stdlib.h>
@@ -27,6 +28,20 @@ inline float softmax_scale_of(const rtp_layer_desc* L) {
 }
 inline float index_scale_of(const rtp_layer_desc* L) { return L->index_scale != 0.f ? L->index_scale : 1.f; }
 inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+// Per-launch timing (rtp_profile_start / rtp_profile_stop): while it is on, every kernel launch of the library
+// carries a start and a stop event that the runtime stamps with the dispatch's own begin and end times (the
+// clocks a profiler reads), so the figures are kernel durations, not enqueue-to-enqueue gaps.  Off (the default) a
+// launch costs one load of a flag more.
+bool profile_slot(const char* kernel, hipEvent_t* start, hipEvent_t* stop);
+#define RTP_LAUNCH(kernel, grid, block, shmem, stream, ...)                                                  \
+  do {                                                                                                       \
+    hipEvent_t rtp_e0_ = nullptr, rtp_e1_ = nullptr;                                                         \
+    if (rtp::profile_slot(#kernel, &rtp_e0_, &rtp_e1_))                                                      \
+      hipExtLaunchKernelGGL(kernel, grid, block, shmem, stream, rtp_e0_, rtp_e1_, 0, __VA_ARGS__);          \
+    else                                                                                                     \
+      hipLaunchKernelGGL(kernel, grid, block, shmem, stream, __VA_ARGS__);                                   \
+  } while (0)
 
 // Head-role tables passed to kernels by value (n_q_heads <= 128).
 struct HeadTable {

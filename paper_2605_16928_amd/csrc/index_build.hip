@@ -93,7 +93,7 @@ extern "C" int32_t rtp_index_project(const rtp_layer_desc* layer, const float* W
     const int h = j < layer->n_ret ? layer->ret_heads[j] : 0;
     a.x_head[j] = side == RTP_SIDE_QUERY ? h : h / G;
   }
-  hipLaunchKernelGGL(index_build_kernel, dim3((unsigned)blocks, (unsigned)layer->n_ret), dim3(kIbThreads), 0,
+  RTP_LAUNCH(index_build_kernel, dim3((unsigned)blocks, (unsigned)layer->n_ret), dim3(kIbThreads), 0,
                      (hipStream_t)stream, a);
   return check_launch(who);
 }

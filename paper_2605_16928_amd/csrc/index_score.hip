@@ -54,7 +54,9 @@ __device__ __forceinline__ float dot8(const u32x4 v, const float (&q)[8]) {
   return acc;
 }
 
-template <bool HIST>
+// PROBE: the same grid, loads and stores with the arithmetic taken out (the stored word is a piece of the key
+// row): what the chip sustains for this traffic mix, 32 bytes read for every 4 written.
+template <bool HIST, bool PROBE = false>
 __global__ __launch_bounds__(kIsThreads) void index_score_kernel(const IndexScoreArgs a) {
   constexpr int kIsChunk = HIST ? kIsChunkHist : kIsChunkPlain;
   static_assert((kIsChunk * 2) % (kIsThreads * kIsBatch) == 0, "a chunk is a whole number of load batches");
@@ -136,8 +138,8 @@ __global__ __launch_bounds__(kIsThreads) void index_score_kernel(const IndexScor
     if (batch > 0) load_batch(batch);
 #pragma unroll
     for (int u = 0; u < kIsBatch; u += 2) {
-      const float d0 = pair_sum(dot8(v[u], qv));
-      const float d1 = pair_sum(dot8(v[u + 1], qv));
+      const float d0 = PROBE ? __uint_as_float(v[u].x & 0x3fffffffu) : pair_sum(dot8(v[u], qv));
+      const float d1 = PROBE ? __uint_as_float(v[u + 1].x & 0x3fffffffu) : pair_sum(dot8(v[u + 1], qv));
       const int tok = (((batch * kIsBatch + u + half) * kIsThreads) + tid) >> 1;
       float val = (half ? d1 : d0) * a.index_scale;
       if (tok >= lim_here) val = ninf;
@@ -158,13 +160,12 @@ __global__ __launch_bounds__(kIsThreads) void index_score_kernel(const IndexScor
 
 using namespace rtp;
 
-extern "C" int32_t rtp_index_score(const rtp_layer_desc* layer, const void* q_in, const float* WQ,
-                                   const void* kI, int64_t kI_head_stride,
-                                   const int64_t* seq_start, const int32_t* ctx_len, const int32_t* q_start,
-                                   int32_t B, int32_t n_q, int64_t max_ctx,
-                                   float* scores, int64_t score_stride, void* qI_out,
-                                   void* topp_ws, size_t topp_ws_bytes, void* stream) {
-  const char* who = "rtp_index_score";
+static int32_t run_index_score(const char* who, bool probe, const rtp_layer_desc* layer, const void* q_in, const float* WQ,
+                               const void* kI, int64_t kI_head_stride,
+                               const int64_t* seq_start, const int32_t* ctx_len, const int32_t* q_start,
+                               int32_t B, int32_t n_q, int64_t max_ctx,
+                               float* scores, int64_t score_stride, void* qI_out,
+                               void* topp_ws, size_t topp_ws_bytes, void* stream) {
   int32_t rc = check_layer(layer, who);
   if (rc != RTP_OK) return rc;
   if (!q_in || !kI || !seq_start || !ctx_len || !scores)
@@ -217,7 +218,27 @@ extern "C" int32_t rtp_index_score(const rtp_layer_desc* layer, const void* q_in
 
   const int64_t chunk = hist ? kIsChunkHist : kIsChunkPlain;
   dim3 grid((unsigned)((max_ctx + chunk - 1) / chunk), (unsigned)n_q, (unsigned)(B * layer->n_ret));
-  if (hist) hipLaunchKernelGGL(index_score_kernel<true>, grid, dim3(kIsThreads), 0, (hipStream_t)stream, a);
-  else hipLaunchKernelGGL(index_score_kernel<false>, grid, dim3(kIsThreads), 0, (hipStream_t)stream, a);
+  if (probe) RTP_LAUNCH((index_score_kernel<false, true>), grid, dim3(kIsThreads), 0, (hipStream_t)stream, a);
+  else if (hist) RTP_LAUNCH(index_score_kernel<true>, grid, dim3(kIsThreads), 0, (hipStream_t)stream, a);
+  else RTP_LAUNCH(index_score_kernel<false>, grid, dim3(kIsThreads), 0, (hipStream_t)stream, a);
   return check_launch(who);
+}
+
+extern "C" int32_t rtp_index_score(const rtp_layer_desc* layer, const void* q_in, const float* WQ,
+                                   const void* kI, int64_t kI_head_stride,
+                                   const int64_t* seq_start, const int32_t* ctx_len, const int32_t* q_start,
+                                   int32_t B, int32_t n_q, int64_t max_ctx,
+                                   float* scores, int64_t score_stride, void* qI_out,
+                                   void* topp_ws, size_t topp_ws_bytes, void* stream) {
+  return run_index_score("rtp_index_score", false, layer, q_in, WQ, kI, kI_head_stride, seq_start, ctx_len, q_start, B, n_q,
+                         max_ctx, scores, score_stride, qI_out, topp_ws, topp_ws_bytes, stream);
+}
+
+extern "C" int32_t rtp_index_score_traffic_probe(const rtp_layer_desc* layer, const void* q_in, const float* WQ,
+                                                 const void* kI, int64_t kI_head_stride,
+                                                 const int64_t* seq_start, const int32_t* ctx_len, const int32_t* q_start,
+                                                 int32_t B, int32_t n_q, int64_t max_ctx,
+                                                 float* scores, int64_t score_stride, void* stream) {
+  return run_index_score("rtp_index_score_traffic_probe", true, layer, q_in, WQ, kI, kI_head_stride, seq_start, ctx_len,
+                         q_start, B, n_q, max_ctx, scores, score_stride, nullptr, nullptr, 0, stream);
 }

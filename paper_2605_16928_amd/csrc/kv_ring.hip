@@ -146,7 +146,7 @@ extern "C" int32_t rtp_kv_ring_append(const rtp_layer_desc* layer, const void* k
   a.row_stride = a.head_stride = 0;
   a.seq_start = nullptr;
   a.n_or_pos = pos;
-  hipLaunchKernelGGL(kv_ring_append_kernel, dim3((unsigned)B), dim3(kRingThreads), 0, (hipStream_t)stream, a);
+  RTP_LAUNCH(kv_ring_append_kernel, dim3((unsigned)B), dim3(kRingThreads), 0, (hipStream_t)stream, a);
   return check_launch(who);
 }
 
@@ -176,7 +176,7 @@ extern "C" int32_t rtp_kv_ring_fill(const rtp_layer_desc* layer, const void* K, 
   a.n_or_pos = ctx_len;
   const int64_t cap = (int64_t)layer->sink + layer->window;
   const unsigned row_blocks = (unsigned)((cap + kRingThreads / 16 - 1) / (kRingThreads / 16));
-  hipLaunchKernelGGL(kv_ring_fill_kernel, dim3(row_blocks, (unsigned)B, (unsigned)a.n_ring), dim3(kRingThreads), 0,
+  RTP_LAUNCH(kv_ring_fill_kernel, dim3(row_blocks, (unsigned)B, (unsigned)a.n_ring), dim3(kRingThreads), 0,
                      (hipStream_t)stream, a);
   return check_launch(who);
 }

@@ -143,6 +143,6 @@ extern "C" int32_t rtp_sparsity_stats(const rtp_layer_desc* layer, const int32_t
   a.sink = layer->sink;
   a.window = layer->window;
   for (int j = 0; j < 64; ++j) a.ret_heads[j] = ht.ret_heads[j];
-  hipLaunchKernelGGL(sparsity_stats_kernel, dim3((unsigned)B), dim3(kStThreads), 0, (hipStream_t)stream, a);
+  RTP_LAUNCH(sparsity_stats_kernel, dim3((unsigned)B), dim3(kStThreads), 0, (hipStream_t)stream, a);
   return check_launch(who);
 }

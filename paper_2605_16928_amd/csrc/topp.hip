@@ -1043,7 +1043,7 @@ extern "C" int32_t rtp_topp_workspace_init(void* ws, size_t ws_bytes, void* stre
     return fail(RTP_ERR_WORKSPACE, "%s: workspace must be 256-byte aligned and a multiple of 8 bytes", who);
   clear_error();
   const int64_t n = (int64_t)(ws_bytes / 8);
-  hipLaunchKernelGGL(topp_zero_kernel, dim3((unsigned)((n + kTpThreads - 1) / kTpThreads)), dim3(kTpThreads), 0,
+  RTP_LAUNCH(topp_zero_kernel, dim3((unsigned)((n + kTpThreads - 1) / kTpThreads)), dim3(kTpThreads), 0,
                      (hipStream_t)stream, (uint64_t*)ws, n);
   return check_launch(who);
 }
@@ -1097,8 +1097,8 @@ static int32_t run_select(const char* who, const float* scores, int64_t score_st
   dim3 grid((unsigned)a.n_chunks, (unsigned)R), block(kTpThreads);
   if (!level1_ready) {
     const int64_t nz = (int64_t)R * l.hist_stride;
-    hipLaunchKernelGGL(topp_zero_kernel, dim3((unsigned)((nz + kTpThreads - 1) / kTpThreads)), block, 0, s, a.hist, nz);
-    hipLaunchKernelGGL(topp_level_kernel<1>, grid, block, 0, s, a);
+    RTP_LAUNCH(topp_zero_kernel, dim3((unsigned)((nz + kTpThreads - 1) / kTpThreads)), block, 0, s, a.hist, nz);
+    RTP_LAUNCH(topp_level_kernel<1>, grid, block, 0, s, a);
   }
   if (ride) {
     // the local heads' work items travel in the level-2 launch (the longer of the two middle launches; giving
@@ -1107,26 +1107,26 @@ static int32_t run_select(const char* who, const float* scores, int64_t score_st
     const int n_items = ride->units * ride->n_splits;
     const int n_ride = n_items < 256 ? n_items : 256;
     const dim3 grid2((unsigned)(n_ride + a.n_chunks * R));
-    if (ride_G == 2) hipLaunchKernelGGL((topp_level_ride_kernel<2, 2>), grid2, block, 0, s, a, *ride, n_ride, 0, n_items);
-    else if (ride_G == 4) hipLaunchKernelGGL((topp_level_ride_kernel<2, 4>), grid2, block, 0, s, a, *ride, n_ride, 0, n_items);
-    else hipLaunchKernelGGL((topp_level_ride_kernel<2, 8>), grid2, block, 0, s, a, *ride, n_ride, 0, n_items);
-    hipLaunchKernelGGL(topp_level_kernel<3>, grid, block, 0, s, a);
+    if (ride_G == 2) RTP_LAUNCH((topp_level_ride_kernel<2, 2>), grid2, block, 0, s, a, *ride, n_ride, 0, n_items);
+    else if (ride_G == 4) RTP_LAUNCH((topp_level_ride_kernel<2, 4>), grid2, block, 0, s, a, *ride, n_ride, 0, n_items);
+    else RTP_LAUNCH((topp_level_ride_kernel<2, 8>), grid2, block, 0, s, a, *ride, n_ride, 0, n_items);
+    RTP_LAUNCH(topp_level_kernel<3>, grid, block, 0, s, a);
   } else {
-    hipLaunchKernelGGL(topp_level_kernel<2>, grid, block, 0, s, a);
-    hipLaunchKernelGGL(topp_level_kernel<3>, grid, block, 0, s, a);
+    RTP_LAUNCH(topp_level_kernel<2>, grid, block, 0, s, a);
+    RTP_LAUNCH(topp_level_kernel<3>, grid, block, 0, s, a);
   }
   if (attend) {
-    hipLaunchKernelGGL(topp_write_kernel<true>, grid, block, 0, s, a, *attend);
+    RTP_LAUNCH(topp_write_kernel<true>, grid, block, 0, s, a, *attend);
     if (ride) {
       const dim3 cgrid((unsigned)(R + ride->units * ride_G));
-      if (ride_G == 2) hipLaunchKernelGGL(select_attend_combine_kernel<2>, cgrid, dim3(256), 0, s, a, *attend, *ride);
-      else if (ride_G == 4) hipLaunchKernelGGL(select_attend_combine_kernel<4>, cgrid, dim3(256), 0, s, a, *attend, *ride);
-      else hipLaunchKernelGGL(select_attend_combine_kernel<8>, cgrid, dim3(256), 0, s, a, *attend, *ride);
+      if (ride_G == 2) RTP_LAUNCH(select_attend_combine_kernel<2>, cgrid, dim3(256), 0, s, a, *attend, *ride);
+      else if (ride_G == 4) RTP_LAUNCH(select_attend_combine_kernel<4>, cgrid, dim3(256), 0, s, a, *attend, *ride);
+      else RTP_LAUNCH(select_attend_combine_kernel<8>, cgrid, dim3(256), 0, s, a, *attend, *ride);
     } else {
-      hipLaunchKernelGGL(select_attend_combine_kernel<0>, dim3((unsigned)R), dim3(256), 0, s, a, *attend, AttnDecodeArgs{});
+      RTP_LAUNCH(select_attend_combine_kernel<0>, dim3((unsigned)R), dim3(256), 0, s, a, *attend, AttnDecodeArgs{});
     }
   } else {
-    hipLaunchKernelGGL(topp_write_kernel<false>, grid, block, 0, s, a, GatherArgs{});
+    RTP_LAUNCH(topp_write_kernel<false>, grid, block, 0, s, a, GatherArgs{});
   }
   return check_launch(who);
 }

@@ -88,6 +88,20 @@ class DecodeRun:
         rtp.rtp_index_score(self.desc, q_in, w.WQ, w.kI, self.T_tot * 16, self.seq_start, self.ctx_len, None,
                             self.B, 1, self.max_ctx, self.scores, self.stride, self.qI_out, scratch)
 
+    def index_score_plain_timing(self):
+        """The score pass without the selector's histogram level, for timing."""
+        w = self.w
+        q_in = w.q_pre if w.WQ is not None else w.qI
+        rtp.rtp_index_score(self.desc, q_in, w.WQ, w.kI, self.T_tot * 16, self.seq_start, self.ctx_len, None,
+                            self.B, 1, self.max_ctx, self.scores, self.stride, self.qI_out, None)
+
+    def index_score_traffic_probe(self, dst):
+        """The score pass's loads and stores without its arithmetic (a measurement; dst gets meaningless words)."""
+        w = self.w
+        q_in = w.q_pre if w.WQ is not None else w.qI
+        rtp.rtp_index_score_traffic_probe(self.desc, q_in, w.WQ, w.kI, self.T_tot * 16, self.seq_start, self.ctx_len, None,
+                                          self.B, 1, self.max_ctx, dst, self.stride)
+
     def topp(self, scores=None, p_rows=None):
         s = self.scores if scores is None else scores
         p = self.w.p_rows if p_rows is None else p_rows

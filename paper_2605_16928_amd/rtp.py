@@ -19,7 +19,7 @@ LIB_PATH = os.environ.get("RTP_LIB", os.path.join(HERE, "librtp.so"))
 RTP_OK, RTP_ERR_INVALID_ARG, RTP_ERR_UNSUPPORTED, RTP_ERR_WORKSPACE, RTP_ERR_HIP = 0, -1, -2, -3, -4
 
 EXPORTS = [
-    "rtp_last_error", "rtp_version",
+    "rtp_last_error", "rtp_version", "rtp_profile_start", "rtp_profile_stop", "rtp_index_score_traffic_probe",
     "rtp_index_score",
     "rtp_topp_workspace_bytes", "rtp_topp_workspace_init", "rtp_topp_select", "rtp_topp_select_noalloc",
     "rtp_sparse_attn_decode_workspace_bytes", "rtp_sparse_attn_decode",
@@ -40,6 +40,10 @@ class RtpError(RuntimeError):
     def __init__(self, code: int, msg: str):
         super().__init__(f"rtp error {code}: {msg}")
         self.code = code
+
+
+class rtp_launch_time(C.Structure):
+    _fields_ = [("kernel", C.c_char_p), ("us", C.c_float)]
 
 
 class rtp_layer_desc(C.Structure):
@@ -85,6 +89,12 @@ def lib() -> C.CDLL:
     L.rtp_topp_workspace_bytes.argtypes = [i32, i64]
     L.rtp_topp_select.restype = i32
     L.rtp_topp_select.argtypes = [vp, i64, vp, vp, i32, i64, vp, i64, vp, vp, vp, i32, vp, sz, vp]
+    L.rtp_index_score_traffic_probe.restype = i32
+    L.rtp_index_score_traffic_probe.argtypes = [dp, vp, vp, vp, i64, vp, vp, vp, i32, i32, i64, vp, i64, vp]
+    L.rtp_profile_start.restype = i32
+    L.rtp_profile_start.argtypes = [i32]
+    L.rtp_profile_stop.restype = i32
+    L.rtp_profile_stop.argtypes = [C.POINTER(rtp_launch_time), i32, C.POINTER(i32)]
     L.rtp_topp_select_noalloc.restype = i32
     L.rtp_topp_select_noalloc.argtypes = [vp, i64, vp, vp, i32, i64, vp, i64, vp, vp, vp, vp]
     L.rtp_topp_workspace_init.restype = i32
@@ -192,6 +202,25 @@ def rtp_topp_select(scores, score_stride, row_len, p, R, max_len, sel_idx, sel_s
     _check(lib().rtp_topp_select(_ptr(scores), score_stride, _ptr(row_len), _ptr(p), R, max_len, _ptr(sel_idx),
                                  sel_stride, _ptr(sel_count), _ptr(tau), _ptr(mass), level1_ready, _ptr(ws),
                                  _nbytes(ws), _stream(stream)))
+
+
+def rtp_index_score_traffic_probe(layer, q_in, WQ, kI, kI_head_stride, seq_start, ctx_len, q_start, B, n_q, max_ctx,
+                                  scores, score_stride, stream=None):
+    _check(lib().rtp_index_score_traffic_probe(C.byref(layer), _ptr(q_in), _ptr(WQ), _ptr(kI), kI_head_stride,
+                                               _ptr(seq_start), _ptr(ctx_len), _ptr(q_start), B, n_q, max_ctx,
+                                               _ptr(scores), score_stride, _stream(stream)))
+
+
+def rtp_profile_start(max_launches: int) -> None:
+    _check(lib().rtp_profile_start(max_launches))
+
+
+def rtp_profile_stop(max_launches: int = 1 << 16):
+    """[(kernel name, microseconds)] of the launches recorded since rtp_profile_start, in launch order."""
+    buf = (rtp_launch_time * max_launches)()
+    n = C.c_int32(0)
+    _check(lib().rtp_profile_stop(buf, max_launches, C.byref(n)))
+    return [(buf[i].kernel.decode().strip("()"), float(buf[i].us)) for i in range(n.value)]
 
 
 def rtp_topp_select_noalloc(scores, score_stride, row_len, p, R, max_len, sel_idx, sel_stride, sel_count,
