@@ -60,7 +60,7 @@ from __future__ import annotations
 import numpy as np
 
 __all__ = [
-    "bf16_to_f64", "f64_to_bf16_bits", "index_project", "index_score",
+    "bf16_to_f64", "fp16_to_f64", "widen", "f64_to_bf16_bits", "index_project", "index_score",
     "topp_from_weights", "topp_select", "attend", "local_set", "kv_head_of",
     "decode_layer", "prefill_rows", "dense_rows",
     "build_index_keys", "topk_select", "block_topp_select", "attention_mass", "sparsity_stats",
@@ -78,6 +78,27 @@ def bf16_to_f64(bits) -> np.ndarray:
     if b.dtype != np.uint16:
         raise TypeError("bf16 tensors are passed as uint16 bit patterns")
     return (b.astype(np.uint32) << np.uint32(16)).view(np.float32).astype(np.float64)
+
+
+def fp16_to_f64(bits) -> np.ndarray:
+    """Widen IEEE binary16 bit patterns (uint16) to float64; exact (subnormals, infinities included).
+
+    The paper's own decode kernel reads its K and V as 16-bit halves (Sec. 3.4, "Bandwidth-optimized sparse
+    decoding"); the library accepts either 16-bit format for q, K and V.
+    """
+    b = np.asarray(bits)
+    if b.dtype != np.uint16:
+        raise TypeError("fp16 tensors are passed as uint16 bit patterns")
+    return b.view(np.float16).astype(np.float64)
+
+
+def widen(bits, kv_dtype: str = "bf16") -> np.ndarray:
+    """Bit patterns of the attention tensors (q, K, V) to float64, by their element type."""
+    if kv_dtype == "bf16":
+        return bf16_to_f64(bits)
+    if kv_dtype == "fp16":
+        return fp16_to_f64(bits)
+    raise ValueError(f"unknown element type {kv_dtype!r}")
 
 
 def f64_to_bf16_bits(x) -> np.ndarray:
@@ -168,16 +189,16 @@ def topp_select(scores, p: float) -> dict:
 # --------------------------------------------------------------------------
 # attention over a token set  (Sec. 3.2, sparse-attention equation)
 # --------------------------------------------------------------------------
-def attend(q_bits, K_bits, V_bits, token_ids, softmax_scale: float):
+def attend(q_bits, K_bits, V_bits, token_ids, softmax_scale: float, kv_dtype: str = "bf16"):
     """O = sum_{n in S} softmax_S(scale * q.k_n) v_n  and its log-sum-exp.
 
-    q [d] bf16 bits; K, V [N, d] bf16 bits (one KV head of one sequence);
-    token_ids: the set S.  Returns (O float64 [d], lse float64).
+    q [d] bit patterns; K, V [N, d] bit patterns (one KV head of one sequence), all of element type
+    kv_dtype ("bf16" or "fp16"); token_ids: the set S.  Returns (O float64 [d], lse float64).
     """
     ids = np.asarray(token_ids, dtype=np.int64)
-    q = bf16_to_f64(q_bits)
-    k = bf16_to_f64(K_bits[ids])
-    v = bf16_to_f64(V_bits[ids])
+    q = widen(q_bits, kv_dtype)
+    k = widen(K_bits[ids], kv_dtype)
+    v = widen(V_bits[ids], kv_dtype)
     logits = float(softmax_scale) * (k @ q)
     mx = np.max(logits)
     a = np.exp(logits - mx)
@@ -207,7 +228,7 @@ def _scale(softmax_scale, d):
 def decode_layer(*, q_bits, K_bits, V_bits, kI_bits, seq_start, ctx_len,
                  n_q_heads, n_kv_heads, ret_heads, sink, window, p_rows,
                  qI_bits=None, WQ=None, q_pre_bits=None,
-                 softmax_scale=0.0, index_scale=0.0, dense=False):
+                 softmax_scale=0.0, index_scale=0.0, dense=False, kv_dtype="bf16"):
     """One decode step of one layer.
 
     q_bits [B, Hq, d]; K_bits, V_bits [Hkv, T_tot, d]; kI_bits [n_ret, T_tot, r];
@@ -245,14 +266,14 @@ def decode_layer(*, q_bits, K_bits, V_bits, kI_bits, seq_start, ctx_len,
                 ids = sel["idx"]
             else:
                 ids = local_set(m, sink, window)
-            out[b, h], lse[b, h] = attend(q_bits[b, h], Kb, Vb, ids, sc)
+            out[b, h], lse[b, h] = attend(q_bits[b, h], Kb, Vb, ids, sc, kv_dtype)
     return dict(out=out, lse=lse, scores=scores, sel=sels, qI_bits=qI_bits)
 
 
 def prefill_rows(*, rows, q_bits, K_bits, V_bits, kI_bits, chunk_start,
                  n_q_heads, n_kv_heads, ret_heads, sink, window, p,
                  qI_bits=None, WQ=None, q_pre_bits=None,
-                 softmax_scale=0.0, index_scale=0.0):
+                 softmax_scale=0.0, index_scale=0.0, kv_dtype="bf16"):
     """Selected (t, h) rows of one causal prefill chunk of ONE sequence.
 
     q_bits [T, Hq, d] holds the chunk's queries, query t sits at position
@@ -280,13 +301,13 @@ def prefill_rows(*, rows, q_bits, K_bits, V_bits, kI_bits, chunk_start,
             r.update(scores=s, sel=sel, qI_bits=qi)
         else:
             ids = local_set(m, sink, window)
-        r["out"], r["lse"] = attend(q_bits[t, h], Kb, Vb, ids, sc)
+        r["out"], r["lse"] = attend(q_bits[t, h], Kb, Vb, ids, sc, kv_dtype)
         res.append(r)
     return res
 
 
 def dense_rows(*, rows, q_bits, K_bits, V_bits, chunk_start, n_q_heads, n_kv_heads,
-               softmax_scale=0.0):
+               softmax_scale=0.0, kv_dtype="bf16"):
     """Dense causal attention for selected (t, h) rows of a prefill chunk."""
     T, Hq, d = q_bits.shape
     sc = _scale(softmax_scale, d)
@@ -294,7 +315,7 @@ def dense_rows(*, rows, q_bits, K_bits, V_bits, chunk_start, n_q_heads, n_kv_hea
     for (t, h) in rows:
         m = int(chunk_start) + int(t)
         kvh = kv_head_of(h, Hq, n_kv_heads)
-        o, l = attend(q_bits[t, h], K_bits[kvh, :m + 1], V_bits[kvh, :m + 1], np.arange(m + 1), sc)
+        o, l = attend(q_bits[t, h], K_bits[kvh, :m + 1], V_bits[kvh, :m + 1], np.arange(m + 1), sc, kv_dtype)
         res.append(dict(t=t, h=h, m=m, out=o, lse=l))
     return res
 

@@ -721,3 +721,66 @@ def test_layer_drivers_project_the_retrieval_heads_own_pre_rope_query():
         exact = sum(bf16_fraction(int(q_pre_t[a["t"], a["h"]][cols[j][i]])) * bf16_fraction(int(kI[j, 3, i]))
                     for i in range(r))
         assert abs(Fraction(float(a["scores"][3])) - exact) <= abs(exact) * Fraction(1, 2 ** 48)
+
+
+# =====================================================================================================
+# fp16 attention tensors
+# =====================================================================================================
+def half_fraction(bits: int) -> Fraction:
+    """Exact rational value of one finite IEEE binary16 bit pattern, from its fields."""
+    sign = -1 if bits & 0x8000 else 1
+    e = (bits >> 10) & 0x1F
+    man = bits & 0x3FF
+    assert e != 31
+    if e == 0:
+        return Fraction(sign * man, 1 << 24)           # subnormal: man * 2^-10 * 2^-14
+    return sign * Fraction(1024 + man, 1024) * (Fraction(2) ** (e - 15))
+
+
+def test_fp16_widening_is_exact_for_every_finite_pattern():
+    """Every finite binary16 pattern against its value spelled out from sign, exponent and mantissa fields."""
+    bits = np.arange(1 << 16, dtype=np.uint32).astype(np.uint16)
+    vals = orc.fp16_to_f64(bits)
+    for b in range(1 << 16):
+        if (b >> 10) & 0x1F == 31:
+            assert not np.isfinite(vals[b])
+            continue
+        assert Fraction(float(vals[b])) == half_fraction(b), hex(b)
+    assert vals[0x3C00] == 1.0 and vals[0xC000] == -2.0 and vals[0x7BFF] == 65504.0 and vals[0x0001] == 2.0 ** -24
+    assert np.signbit(vals[0x8000]) and vals[0x8000] == 0.0
+    with pytest.raises(TypeError):
+        orc.fp16_to_f64(np.zeros(3, dtype=np.int16))
+    with pytest.raises(ValueError):
+        orc.widen(np.zeros(3, dtype=np.uint16), "fp8")
+
+
+def test_attend_and_layer_drivers_read_fp16_tensors_as_fp16():
+    """The same bit patterns mean different numbers in the two formats: with kv_dtype = "fp16" the attention must
+    be the brute-force attention over the binary16 VALUES (q, K and V alike), in attend and through the decode
+    and prefill drivers; index keys stay bf16."""
+    rng = np.random.default_rng(23)
+    N, d, Hq, Hkv = 40, 128, 4, 2
+    f16 = lambda shape: rng.standard_normal(shape).astype(np.float16).view(np.uint16)
+    q, K, V = f16((1, Hq, d)), f16((Hkv, N, d)), f16((Hkv, N, d))
+    val = lambda bits: [[float(half_fraction(int(x))) for x in row] for row in np.atleast_2d(bits)]
+    ids = [3, 7, 8, 20, 39]
+    o, lse = orc.attend(q[0, 1], K[0], V[0], ids, 0.11, kv_dtype="fp16")
+    bo, bl = brute_attention(val(q[0, 1])[0], val(K[0]), val(V[0]), ids, 0.11)
+    assert np.allclose(o, bo, rtol=1e-12, atol=1e-14) and abs(lse - bl) < 1e-12
+    o_bf, _ = orc.attend(q[0, 1], K[0], V[0], ids, 0.11)          # the same bits read as bf16: other numbers
+    assert not np.allclose(o, o_bf, atol=1e-3)
+    kI = rand_bf16(rng, (1, N, 16))
+    qI = rand_bf16(rng, (1, 1, 16))
+    common = dict(K_bits=K, V_bits=V, kI_bits=kI, n_q_heads=Hq, n_kv_heads=Hkv, ret_heads=[2], sink=2, window=5,
+                  kv_dtype="fp16")
+    dec = orc.decode_layer(q_bits=q, seq_start=[0], ctx_len=[N], p_rows=np.array([0.6]), qI_bits=qI, **common)
+    for h in range(Hq):
+        ids_h = dec["sel"][0]["idx"].tolist() if h == 2 else orc.local_set(N - 1, 2, 5).tolist()
+        bo, _ = brute_attention(val(q[0, h])[0], val(K[h // 2]), val(V[h // 2]), ids_h, 1.0 / math.sqrt(d))
+        assert np.allclose(dec["out"][0, h], bo, rtol=1e-12, atol=1e-14), h
+    rows = orc.prefill_rows(rows=[(0, 0), (0, 2)], q_bits=q, chunk_start=N - 1, p=0.6, qI_bits=qI.reshape(1, 1, 16), **common)
+    assert np.allclose(rows[0]["out"], dec["out"][0, 0], rtol=1e-12) and np.allclose(rows[1]["out"], dec["out"][0, 2], rtol=1e-12)
+    dr = orc.dense_rows(rows=[(0, 3)], q_bits=q, K_bits=K, V_bits=V, chunk_start=N - 1, n_q_heads=Hq, n_kv_heads=Hkv,
+                        kv_dtype="fp16")
+    bo, _ = brute_attention(val(q[0, 3])[0], val(K[1]), val(V[1]), list(range(N)), 1.0 / math.sqrt(d))
+    assert np.allclose(dr[0]["out"], bo, rtol=1e-12, atol=1e-14)
