@@ -313,6 +313,23 @@ def main() -> int:
     assert torch.equal(out_p[:, list(L.ret_heads)], r0.out[:, list(L.ret_heads)]), "paged gather differs from the contiguous one"
     paged = {"page_tokens": page, "sparse_attn_decode_paged_us": round(timed(lambda i: paged_call(), it, wu), 2),
              "sparse_attn_decode_us": round(timed(lambda i: r0.sparse_attn(), it, wu), 2)}
+
+    # the whole step from the paged pool (score pass + rtp_decode_attention_paged: the gather and the local heads'
+    # rows through the page table) against the step on contiguous sequences
+    def paged_step():
+        r0.index_score()
+        rtp.rtp_decode_attention_paged(r0.desc, r0.scores, r0.stride, r0.row_len, w0.p_rows, r0.ctx_len, B, r0.max_ctx, w0.q,
+                                       K_pool, V_pool, 128, K_pool.shape[1] * 128, table_d, pages_per_seq, page, r0.sel_idx,
+                                       r0.stride, r0.sel_count, r0.tau, r0.mass, out_p, None, r0.ws_topp, r0.ws_fused,
+                                       r0.ws_local, level1_ready=1)
+        r0._level1_pending = False
+
+    r0.step_one_stream()
+    paged_step()
+    torch.cuda.synchronize()
+    assert torch.equal(out_p, r0.out), "the step from the paged pool differs from the contiguous one"
+    paged["us_per_step_paged"] = round(timed(lambda i: paged_step(), it, wu), 2)
+    paged["us_per_step_contiguous_same_copy"] = round(timed(lambda i: r0.step_one_stream(), it, wu), 2)
     del K_pool, V_pool
     r0.out.copy_(ref_out)
 
@@ -341,6 +358,12 @@ def main() -> int:
                    "us_per_step_one_call": round(timed(lambda i: rp.step_one_stream(), it, wu), 2),
                    "us_per_step_parts_in_turn": round(timed(lambda i: rp.step(), it, wu), 2)}
     del rp
+
+    # ---- the same step with fp16 attention tensors (the format the paper's decode kernel loads) ----
+    rf = [DecodeRun(wl.c2(dev, seed=120 + i, p=args.p, ctx=args.ctx, batch=args.batch, kv_dtype="fp16")) for i in range(2)]
+    fp16 = {"us_per_step": round(timed(lambda i: rf[i % 2].step_fastest(side2), it, wu), 2),
+            "dense_attn_us": round(timed(lambda i: rf[i % 2].dense_attn(rf[i % 2].out), max(10, it // 10), 2), 2)}
+    del rf
 
     # ---- algorithmic bytes per step (design notes: per-unit figures x units) ----
     sel_total = int(sel_counts.sum())
@@ -646,6 +669,7 @@ def main() -> int:
             "index_key_build": ib,
             "bounded_cache": bounded,
             "paged_cache": paged,
+            "fp16": fp16,
             "clustered_law": clustered,
             "groups_of_8": groups_of_8,
             "selected_tokens_per_row_mean": round(float(sel_counts.mean()), 1),

@@ -19,7 +19,10 @@
  *  - `rtp_layer_desc` and its `ret_heads` array are HOST memory, read during the call only.
  *  - Scratch memory comes from the caller: `ws` (device, 256-byte aligned) of at least the size
  *    the matching *_workspace_bytes() function returns.  Contents are undefined before and after.
- *  - bf16 tensors are raw 16-bit patterns.  head_dim must be 128 and index_dim 16.
+ *  - 16-bit tensors are raw bit patterns.  The attention tensors q, K, V and out are bf16, or fp16 (IEEE binary16)
+ *    when the layer says kv_dtype = RTP_DTYPE_FP16; both are read exactly, accumulated in fp32 and the output is
+ *    rounded once to the same type.  Everything on the indexer side (q_pre, k_pre, kI, qI) is bf16 either way.
+ *    head_dim must be 128 and index_dim 16.
  *  - K and V caches: bf16, element (kvh, token, c) at  base[kvh * kv_head_stride + token * kv_row_stride + c],
  *    strides in ELEMENTS, kv_row_stride >= 128 and a multiple of 8 (256 with V = K + 128 gives
  *    interleaved K|V rows; the prefill calls also require kv_row_stride <= 2^24).  Sequences are packed along the token axis: sequence b owns tokens
@@ -60,6 +63,9 @@ extern "C" {
 #define RTP_ERR_WORKSPACE     (-3)   /* workspace missing, misaligned or too small */
 #define RTP_ERR_HIP           (-4)   /* a launch failed; the HIP error text is in rtp_last_error() */
 
+#define RTP_DTYPE_BF16  0
+#define RTP_DTYPE_FP16  1            /* IEEE binary16, the format the paper's decode kernel loads (Sec. 3.4) */
+
 #define RTP_HEAD_DIM   128
 #define RTP_INDEX_DIM  16
 #define RTP_MAX_ROW_LEN (1 << 24)    /* longest score row rtp_topp_select accepts */
@@ -77,6 +83,7 @@ typedef struct rtp_layer_desc {
   int32_t window;            /* ... plus the `window` most recent, own position included */
   float softmax_scale;       /* 0 => 1/sqrt(head_dim)   (sparse-attention equation) */
   float index_scale;         /* 0 => 1                  (the indexer equation has no scale) */
+  int32_t kv_dtype;          /* element type of q, K, V and out: RTP_DTYPE_BF16 (0, default) or RTP_DTYPE_FP16 */
 } rtp_layer_desc;
 
 /* Message for the last error on this thread ("" if none).  Never NULL. */
@@ -419,6 +426,24 @@ int32_t rtp_decode_attention(const rtp_layer_desc* layer, const float* scores, i
                              float* tau, float* mass, int32_t level1_ready, void* out, float* lse,
                              void* topp_ws, size_t topp_ws_bytes, void* attn_ws, size_t attn_ws_bytes,
                              void* local_ws, size_t local_ws_bytes, void* stream);
+
+/* rtp_decode_attention with the whole K/V cache held in pages (a storage layout; the arithmetic is that of
+ * Sec. 3.2 unchanged -- Sec. 2.1: the retrieval heads keep the full cache, which is the one a server pages).
+ * K and V address pools [n_kv_heads, pool rows, 128]; token t of sequence b lives in pool row
+ * page_table[b * pt_stride + t / page_size] * page_size + t % page_size for every KV head (page_table device int32,
+ * page_size a power of two in [16, 2^20], pt_stride >= ceil(max_ctx / page_size)).  Both the gathered rows of the
+ * retrieval heads and the sink + window rows of the local heads are read through the table; selections and
+ * outputs are bit-identical to rtp_decode_attention on the same tokens laid out contiguously.
+ */
+int32_t rtp_decode_attention_paged(const rtp_layer_desc* layer, const float* scores, int64_t score_stride,
+                                   const int32_t* row_len, const float* p, const int32_t* ctx_len, int32_t B,
+                                   int64_t max_ctx, const void* q, const void* K, const void* V,
+                                   int64_t kv_row_stride, int64_t kv_head_stride,
+                                   const int32_t* page_table, int64_t pt_stride, int32_t page_size,
+                                   int32_t* sel_idx, int64_t sel_stride, int32_t* sel_count,
+                                   float* tau, float* mass, int32_t level1_ready, void* out, float* lse,
+                                   void* topp_ws, size_t topp_ws_bytes, void* attn_ws, size_t attn_ws_bytes,
+                                   void* local_ws, size_t local_ws_bytes, void* stream);
 
 /* ---------------------------------------------------------------------------------------------
  * Bounded KV cache of the all-local KV heads, decode -- Sec. 2.1 (the full KV cache is kept for

@@ -493,10 +493,10 @@ def ring_fill(K_bits, V_bits, n: int, sink: int, window: int):
     return rk, rv, min(int(n), sink + window)
 
 
-def ring_local_attend(q_bits, ring_K_bits, ring_V_bits, rows: int, softmax_scale: float):
+def ring_local_attend(q_bits, ring_K_bits, ring_V_bits, rows: int, softmax_scale: float, kv_dtype: str = "bf16"):
     """A local head's attention at decode time read from the bounded cache: softmax attention over its
     first `rows` rows (a softmax over a set does not depend on the order of its members)."""
-    return attend(q_bits, ring_K_bits, ring_V_bits, np.arange(int(rows)), softmax_scale)
+    return attend(q_bits, ring_K_bits, ring_V_bits, np.arange(int(rows)), softmax_scale, kv_dtype)
 
 
 # ---- paged cache ------------------------------------------------------------------------------------
@@ -508,7 +508,8 @@ def paged_rows(page_table, page_size: int, token_ids) -> np.ndarray:
     return pt[t // int(page_size)] * int(page_size) + t % int(page_size)
 
 
-def paged_attend(q_bits, K_pool_bits, V_pool_bits, page_table, page_size: int, token_ids, softmax_scale: float):
+def paged_attend(q_bits, K_pool_bits, V_pool_bits, page_table, page_size: int, token_ids, softmax_scale: float,
+                 kv_dtype: str = "bf16"):
     """The sparse-attention equation over the set `token_ids` of a sequence whose K/V rows live in a paged
     pool (uint16 [pool_rows, d], one KV head)."""
-    return attend(q_bits, K_pool_bits, V_pool_bits, paged_rows(page_table, page_size, token_ids), softmax_scale)
+    return attend(q_bits, K_pool_bits, V_pool_bits, paged_rows(page_table, page_size, token_ids), softmax_scale, kv_dtype)

@@ -49,6 +49,8 @@ int32_t check_layer(const rtp_layer_desc* L, const char* who) {
   }
   if (L->sink < 0 || L->window < 0 || (int64_t)L->sink + L->window <= 0)
     return fail(RTP_ERR_INVALID_ARG, "%s: sink %d / window %d invalid", who, L->sink, L->window);
+  if (L->kv_dtype != RTP_DTYPE_BF16 && L->kv_dtype != RTP_DTYPE_FP16)
+    return fail(RTP_ERR_UNSUPPORTED, "%s: kv_dtype %d unsupported (RTP_DTYPE_BF16 or RTP_DTYPE_FP16)", who, L->kv_dtype);
   if (!(L->softmax_scale >= 0.f) || !(L->index_scale >= 0.f))
     return fail(RTP_ERR_INVALID_ARG, "%s: scales must be >= 0 (0 selects the default)", who);
   return RTP_OK;

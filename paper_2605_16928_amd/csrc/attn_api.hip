@@ -1,13 +1,9 @@
 // Entry points rtp_local_attn / rtp_dense_attn: dispatch between the decode kernels (one query per
 // sequence, HBM-bound row streaming) and the prefill kernels (query tiles on MFMA).
-#include "common.h"
+#include "attn_decode_shared.h"
 
 namespace rtp {
-int32_t decode_range_attn(const char* who, bool dense, const rtp_layer_desc* L, const void* q, const void* K,
-                          const void* V, int64_t row_stride, int64_t head_stride, const int64_t* seq_start,
-                          const int32_t* ctx_len, int32_t B, int64_t max_ctx, void* out, float* lse, void* ws,
-                          size_t ws_bytes, hipStream_t s);
-size_t decode_range_ws(bool dense, const rtp_layer_desc* L, int32_t B, int64_t max_ctx);
+
 int32_t prefill_range_attn(const char* who, bool dense, const rtp_layer_desc* L, const void* q, const void* K,
                            const void* V, int64_t row_stride, int64_t head_stride, const int64_t* seq_start,
                            const int32_t* ctx_len, const int32_t* q_start, int32_t B, int32_t n_q, int64_t max_ctx,

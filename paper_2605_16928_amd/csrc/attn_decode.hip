@@ -109,9 +109,9 @@ __device__ __forceinline__ void merge_state(float& m, float& l, float (&acc)[8],
 // page_table[b][p >> page_shift] * page_size + p % page_size of a pool shared by all sequences.  The lookup is
 // one more dependent load in front of the K/V rows, so the index list runs TWO rounds ahead and the page
 // lookups one round ahead: both stay in the shadow of the row loads.
-template <int G, int SRC, int U, bool PAGED = false>
+template <int G, int SRC, int U, bool PAGED = false, bool F16 = false>
 __global__ __launch_bounds__(kAdThreads) void attn_decode_kernel(const AttnDecodeArgs a) {
-  static_assert(!PAGED || SRC == kSrcSparse, "paging is implemented for the selected-token source");
+  static_assert(!PAGED || SRC != kSrcDense, "paging is implemented for the selected-token and the local source");
   __shared__ int sh_prefix[kAdMaxUnits + 1];
   __shared__ int sh_w[kAdThreads / 64];
   __shared__ float sh_m[kAdThreads / 64][G], sh_l[kAdThreads / 64][G];
@@ -168,8 +168,10 @@ __global__ __launch_bounds__(kAdThreads) void attn_decode_kernel(const AttnDecod
     const int32_t* pt = PAGED ? a.page_table + (int64_t)b * a.pt_stride : nullptr;
     const int page_mask = (1 << a.page_shift) - 1;
     auto pool_row = [&](int p) { return (pt[p >> a.page_shift] << a.page_shift) | (p & page_mask); };
+    bool paged_rows = PAGED;
     if (SRC == kSrcLocal && a.ringK && a.ring_of_kv[kvh] >= 0) {
       // bounded cache: its first n_tok rows are exactly this unit's tokens, in some order
+      paged_rows = false;
       const int64_t off = (int64_t)a.ring_of_kv[kvh] * a.ring_head_stride + a.ring_seq_start[b] * a.ring_row_stride + piece * 8;
       Kb = a.ringK + off;
       Vb = a.ringV + off;
@@ -181,7 +183,7 @@ __global__ __launch_bounds__(kAdThreads) void attn_decode_kernel(const AttnDecod
 #pragma unroll
     for (int hh = 0; hh < G; ++hh) {
       const u32x4 qraw = *reinterpret_cast<const u32x4*>(a.q + ((int64_t)b * a.n_q_heads + h0 + hh) * kHeadDim + piece * 8);
-      unpack8(qraw, qv[hh]);
+      unpack8<F16>(qraw, qv[hh]);
 #pragma unroll
       for (int c = 0; c < 8; ++c) qv[hh][c] *= a.scale_log2;
     }
@@ -218,6 +220,7 @@ __global__ __launch_bounds__(kAdThreads) void attn_decode_kernel(const AttnDecod
         if (SRC == kSrcSparse) pos = nxt[u];
         else if (SRC == kSrcLocal) pos = i < s0 ? i : w0 + (i - s0);
         else pos = i;
+        if (PAGED && SRC == kSrcLocal && paged_rows && ok[u]) pos = pool_row(pos);
         if (ok[u]) {
           kr[u] = *reinterpret_cast<const u32x4*>(Kb + (int64_t)pos * row_stride);
           vr[u] = *reinterpret_cast<const u32x4*>(Vb + (int64_t)pos * row_stride);
@@ -242,7 +245,7 @@ __global__ __launch_bounds__(kAdThreads) void attn_decode_kernel(const AttnDecod
 #pragma unroll
       for (int u = 0; u < U; ++u) {
         float kf[8];
-        unpack8(kr[u], kf);
+        unpack8<F16>(kr[u], kf);
 #pragma unroll
         for (int hh = 0; hh < G; ++hh) {
           float d = kf[0] * qv[hh][0];
@@ -269,7 +272,7 @@ __global__ __launch_bounds__(kAdThreads) void attn_decode_kernel(const AttnDecod
 #pragma unroll
       for (int u = 0; u < U; ++u) {
         float vf[8];
-        unpack8(vr[u], vf);
+        unpack8<F16>(vr[u], vf);
 #pragma unroll
         for (int hh = 0; hh < G; ++hh) {
           const float pw = (s[hh][u] == ninf) ? 0.f : fast_exp2(s[hh][u] - m[hh]);
@@ -335,9 +338,9 @@ __global__ __launch_bounds__(kAdThreads) void attn_decode_kernel(const AttnDecod
 // lane group grp in round j, so the probability it needs sits in ITS OWN 16-lane row at lane = head,
 // register j, and one DPP row_share brings it to all 16 lanes.  Work items, partials and the merge
 // launch are those of the kernel above.
-template <int G, int SRC>
+template <int G, int SRC, bool F16 = false, bool PAGED = false>
 __global__ __launch_bounds__(kAdThreads) void attn_decode_gqa_kernel(const AttnDecodeArgs a) {
-  gqa_decode_items<G, SRC, kAdThreads, 2>(a, blockIdx.x, gridDim.x);
+  gqa_decode_items<G, SRC, kAdThreads, 2, F16, PAGED>(a, blockIdx.x, gridDim.x);
 }
 
 // Merges the partials of one (unit, head) per workgroup: 8 slices of 32 lanes, each lane owns 4 of the
@@ -407,17 +410,21 @@ static DecodePlanHost plan_host_range(int32_t units, int64_t max_tok, int32_t G)
   return p;
 }
 
-template <int SRC>
-static int32_t launch_decode(const AttnDecodeArgs& a, int G, int grid, hipStream_t s, const char* who) {
+template <int SRC, bool F16>
+static int32_t launch_decode_t(const AttnDecodeArgs& a, int G, int grid, hipStream_t s, const char* who) {
   const int cgrid = a.units * G;
   // one head per K/V row (always so for the selected-token source): the vector-ALU kernel;
   // a GQA group per row: scores on the matrix cores
+  constexpr bool kCanPage = SRC != kSrcDense;
 #define RTP_LAUNCH_GQA(GG)                                                                                   \
-  RTP_LAUNCH((attn_decode_gqa_kernel<GG, SRC == kSrcSparse ? kSrcDense : SRC>), dim3(grid), dim3(kAdThreads), 0, s, a); \
+  if (kCanPage && a.page_table)                                                                              \
+    RTP_LAUNCH((attn_decode_gqa_kernel<GG, SRC == kSrcSparse ? kSrcDense : SRC, F16, kCanPage>), dim3(grid), dim3(kAdThreads), 0, s, a); \
+  else                                                                                                       \
+    RTP_LAUNCH((attn_decode_gqa_kernel<GG, SRC == kSrcSparse ? kSrcDense : SRC, F16>), dim3(grid), dim3(kAdThreads), 0, s, a); \
   RTP_LAUNCH((attn_decode_combine_kernel<GG, SRC>), dim3(cgrid), dim3(kAdThreads), 0, s, a);
   if (SRC == kSrcSparse || G == 1) {
-    if (SRC == kSrcSparse && a.page_table) RTP_LAUNCH((attn_decode_kernel<1, kSrcSparse, 8, true>), dim3(grid), dim3(kAdThreads), 0, s, a);
-    else RTP_LAUNCH((attn_decode_kernel<1, SRC, 8>), dim3(grid), dim3(kAdThreads), 0, s, a);
+    if (kCanPage && a.page_table) RTP_LAUNCH((attn_decode_kernel<1, SRC, 8, kCanPage, F16>), dim3(grid), dim3(kAdThreads), 0, s, a);
+    else RTP_LAUNCH((attn_decode_kernel<1, SRC, 8, false, F16>), dim3(grid), dim3(kAdThreads), 0, s, a);
     RTP_LAUNCH((attn_decode_combine_kernel<1, SRC>), dim3(cgrid), dim3(kAdThreads), 0, s, a);
   } else {
     switch (G) {
@@ -429,6 +436,10 @@ static int32_t launch_decode(const AttnDecodeArgs& a, int G, int grid, hipStream
   }
 #undef RTP_LAUNCH_GQA
   return check_launch(who);
+}
+template <int SRC>
+static int32_t launch_decode(const AttnDecodeArgs& a, int G, int grid, hipStream_t s, const char* who) {
+  return a.f16 ? launch_decode_t<SRC, true>(a, G, grid, s, who) : launch_decode_t<SRC, false>(a, G, grid, s, who);
 }
 
 static int32_t check_kv(const char* who, const void* q, const void* K, const void* V, int64_t row_stride,
@@ -463,6 +474,7 @@ static void fill_common(AttnDecodeArgs& a, const rtp_layer_desc* L, const HeadTa
   a.part = (float*)ws;
   a.out = (uint16_t*)out;
   a.lse = lse;
+  a.f16 = L->kv_dtype == RTP_DTYPE_FP16;
   for (int j = 0; j < 64; ++j) a.ret_heads[j] = ht.ret_heads[j];
   for (int h = 0; h < 128; ++h) a.is_ret[h] = ht.is_ret[h];
   a.ringK = a.ringV = nullptr;
@@ -483,15 +495,22 @@ int ring_heads_of(const rtp_layer_desc* L, int32_t* heads, int8_t* ring_of_kv);
 int32_t decode_range_prepare(const char* who, bool dense, const rtp_layer_desc* L, const void* q, const void* K,
                              const void* V, int64_t row_stride, int64_t head_stride, const int64_t* seq_start,
                              const int32_t* ctx_len, int32_t B, int64_t max_ctx, void* out, float* lse, void* ws,
-                             size_t ws_bytes, const RingSource* ring, AttnDecodeArgs* args, int* grid, bool* launch) {
+                             size_t ws_bytes, const RingSource* ring, AttnDecodeArgs* args, int* grid, bool* launch,
+                             const PageSource* pages) {
   *launch = false;
   HeadTable ht;
   int32_t rc = fill_head_table(L, &ht, who);
   if (rc != RTP_OK) return rc;
   rc = check_kv(who, q, K, V, row_stride, head_stride, out);
   if (rc != RTP_OK) return rc;
-  if (!seq_start || !ctx_len) return fail(RTP_ERR_INVALID_ARG, "%s: NULL seq_start/ctx_len", who);
+  if ((!seq_start && !pages) || !ctx_len) return fail(RTP_ERR_INVALID_ARG, "%s: NULL seq_start/ctx_len", who);
   if (B <= 0 || max_ctx <= 0) return fail(RTP_ERR_INVALID_ARG, "%s: B and max_ctx must be positive", who);
+  int page_shift = 0;
+  if (pages) {
+    if (dense) return fail(RTP_ERR_UNSUPPORTED, "%s: the dense comparison does not read a paged cache", who);
+    rc = check_pages(who, pages, max_ctx, &page_shift);
+    if (rc != RTP_OK) return rc;
+  }
   const int G = L->n_q_heads / L->n_kv_heads;
   const int64_t units = (int64_t)B * L->n_kv_heads;
   if (units > kAdMaxUnits) return fail(RTP_ERR_UNSUPPORTED, "%s: B * n_kv_heads = %lld exceeds %d", who, (long long)units, kAdMaxUnits);
@@ -508,6 +527,11 @@ int32_t decode_range_prepare(const char* who, bool dense, const rtp_layer_desc* 
   a.min_split_blocks = 1;
   a.split_tokens = p.split_tokens;
   a.n_splits = p.n_splits;
+  if (pages) {
+    a.page_table = pages->table;
+    a.pt_stride = pages->stride;
+    a.page_shift = page_shift;
+  }
   if (ring) {
     a.ringK = (const uint16_t*)ring->K;
     a.ringV = (const uint16_t*)ring->V;
@@ -524,12 +548,13 @@ int32_t decode_range_prepare(const char* who, bool dense, const rtp_layer_desc* 
 static int32_t decode_range_attn_from(const char* who, bool dense, const rtp_layer_desc* L, const void* q, const void* K,
                                       const void* V, int64_t row_stride, int64_t head_stride, const int64_t* seq_start,
                                       const int32_t* ctx_len, int32_t B, int64_t max_ctx, void* out, float* lse, void* ws,
-                                      size_t ws_bytes, hipStream_t s, const RingSource* ring) {
+                                      size_t ws_bytes, hipStream_t s, const RingSource* ring,
+                                      const PageSource* pages = nullptr) {
   AttnDecodeArgs a;
   int grid = 0;
   bool launch = false;
   const int32_t rc = decode_range_prepare(who, dense, L, q, K, V, row_stride, head_stride, seq_start, ctx_len, B, max_ctx,
-                                          out, lse, ws, ws_bytes, ring, &a, &grid, &launch);
+                                          out, lse, ws, ws_bytes, ring, &a, &grid, &launch, pages);
   if (rc != RTP_OK || !launch) return rc;
   const int G = L->n_q_heads / L->n_kv_heads;
   return dense ? launch_decode<kSrcDense>(a, G, grid, s, who) : launch_decode<kSrcLocal>(a, G, grid, s, who);
@@ -538,9 +563,21 @@ static int32_t decode_range_attn_from(const char* who, bool dense, const rtp_lay
 int32_t decode_range_attn(const char* who, bool dense, const rtp_layer_desc* L, const void* q, const void* K,
                           const void* V, int64_t row_stride, int64_t head_stride, const int64_t* seq_start,
                           const int32_t* ctx_len, int32_t B, int64_t max_ctx, void* out, float* lse, void* ws,
-                          size_t ws_bytes, hipStream_t s) {
+                          size_t ws_bytes, hipStream_t s, const PageSource* pages) {
   return decode_range_attn_from(who, dense, L, q, K, V, row_stride, head_stride, seq_start, ctx_len, B, max_ctx, out, lse,
-                                ws, ws_bytes, s, nullptr);
+                                ws, ws_bytes, s, nullptr, pages);
+}
+
+int32_t check_pages(const char* who, const PageSource* pages, int64_t max_ctx, int* page_shift) {
+  if (!pages->table) return fail(RTP_ERR_INVALID_ARG, "%s: NULL page_table", who);
+  const int32_t ps = pages->page_size;
+  if (ps < 16 || (ps & (ps - 1)) || ps > (1 << 20))
+    return fail(RTP_ERR_INVALID_ARG, "%s: page_size must be a power of two in [16, 2^20]", who);
+  int sh = 0;
+  while ((1 << sh) < ps) ++sh;
+  if (pages->stride < (max_ctx + ps - 1) / ps) return fail(RTP_ERR_INVALID_ARG, "%s: pt_stride must cover max_ctx tokens", who);
+  *page_shift = sh;
+  return RTP_OK;
 }
 
 size_t decode_range_ws(bool dense, const rtp_layer_desc* L, int32_t B, int64_t max_ctx) {

@@ -48,6 +48,7 @@ struct AttnDecodeArgs {
   const int32_t* page_table;   // [B, pt_stride] pool pages
   int64_t pt_stride;
   int32_t page_shift;          // log2(page size in tokens)
+  int32_t f16;                 // q, K, V and out are fp16 (else bf16)
 };
 
 template <int SRC>
@@ -60,14 +61,22 @@ __device__ __forceinline__ int unit_tokens(const AttnDecodeArgs& a, int unit) {
   return max(s0, 0) + max(0, n - w0);
 }
 
+template <bool F16 = false>
 __device__ __forceinline__ void unpack8(const u32x4 v, float (&f)[8]) {
-  f[0] = bf16_lo(v.x); f[1] = bf16_hi(v.x); f[2] = bf16_lo(v.y); f[3] = bf16_hi(v.y);
-  f[4] = bf16_lo(v.z); f[5] = bf16_hi(v.z); f[6] = bf16_lo(v.w); f[7] = bf16_hi(v.w);
+  f[0] = lo16<F16>(v.x); f[1] = hi16<F16>(v.x); f[2] = lo16<F16>(v.y); f[3] = hi16<F16>(v.y);
+  f[4] = lo16<F16>(v.z); f[5] = hi16<F16>(v.z); f[6] = lo16<F16>(v.w); f[7] = hi16<F16>(v.w);
 }
 
 
 typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
+typedef _Float16 f16x8_t __attribute__((ext_vector_type(8)));
 typedef float f32x4_t __attribute__((ext_vector_type(4)));
+// 16 x 16 x 32 MFMA on 16-bit operands of either format, fp32 accumulation
+template <bool F16>
+__device__ __forceinline__ f32x4_t mfma16(const u32x4 a, const u32x4 b, const f32x4_t c) {
+  if constexpr (F16) return __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(f16x8_t, a), __builtin_bit_cast(f16x8_t, b), c, 0, 0, 0);
+  else return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, a), __builtin_bit_cast(bf16x8_t, b), c, 0, 0, 0);
+}
 
 template <int H>
 __device__ __forceinline__ float row_share(float x) {      // every lane reads lane H of its own 16-lane row
@@ -76,7 +85,9 @@ __device__ __forceinline__ float row_share(float x) {      // every lane reads l
 
 // The work items first_item, first_item + item_step, ... of a workgroup of THREADS threads, TILES tiles per wave
 // in flight (alone in its launch the kernel runs 256 threads and 2 tiles: 1, 3 and 4 measured slower).
-template <int G, int SRC, int THREADS, int TILES>
+// PAGED: token position p of sequence b lives in pool row page_table[b][p >> page_shift] * page_size + p % page_size
+// (rows of a bounded cache are never paged).
+template <int G, int SRC, int THREADS, int TILES, bool F16 = false, bool PAGED = false>
 __device__ __forceinline__ void gqa_decode_items(const AttnDecodeArgs& a, const int first_item, const int item_step,
                                                  const int item_end = -1) {
   static_assert(SRC != kSrcSparse && G >= 2 && G <= 16, "range sources, GQA groups");
@@ -104,10 +115,14 @@ __device__ __forceinline__ void gqa_decode_items(const AttnDecodeArgs& a, const 
       s0 = max(min(a.sink, n), 0);
       w0 = max(a.sink, n - a.window);
     }
-    const uint16_t* Kb = a.K + (int64_t)kvh * a.head_stride + a.seq_start[b] * a.row_stride;
-    const uint16_t* Vb = a.V + (int64_t)kvh * a.head_stride + a.seq_start[b] * a.row_stride;
+    const int64_t seq0 = PAGED ? 0 : a.seq_start[b];
+    const uint16_t* Kb = a.K + (int64_t)kvh * a.head_stride + seq0 * a.row_stride;
+    const uint16_t* Vb = a.V + (int64_t)kvh * a.head_stride + seq0 * a.row_stride;
     int64_t row_stride = a.row_stride;
+    const int32_t* pt = PAGED ? a.page_table + (int64_t)b * a.pt_stride : nullptr;
+    const int page_mask = (1 << a.page_shift) - 1;
     if (SRC == kSrcLocal && a.ringK && a.ring_of_kv[kvh] >= 0) {
+      pt = nullptr;
       // bounded cache: its first n_tok rows are exactly this unit's tokens, in some order
       const int64_t off = (int64_t)a.ring_of_kv[kvh] * a.ring_head_stride + a.ring_seq_start[b] * a.ring_row_stride;
       Kb = a.ringK + off;
@@ -115,7 +130,11 @@ __device__ __forceinline__ void gqa_decode_items(const AttnDecodeArgs& a, const 
       row_stride = a.ring_row_stride;
       s0 = n_tok;                         // logical token i is row i
     }
-    auto pos_of = [&](int i) { return SRC == kSrcLocal ? (i < s0 ? i : w0 + (i - s0)) : i; };
+    auto pos_of = [&](int i) {
+      const int p = SRC == kSrcLocal ? (i < s0 ? i : w0 + (i - s0)) : i;
+      if (PAGED && pt) return (pt[p >> a.page_shift] << a.page_shift) | (p & page_mask);
+      return p;
+    };
 
     // B operand: column piece = head (zero beyond G), k slice grp * 8 .. + 7 of each 32-dim step
     u32x4 qB[4];
@@ -157,8 +176,7 @@ __device__ __forceinline__ void gqa_decode_items(const AttnDecodeArgs& a, const 
         f32x4_t S = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (int kk = 0; kk < 4; ++kk)
-          S = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, kr[tl][kk]),
-                                                      __builtin_bit_cast(bf16x8_t, qB[kk]), S, 0, 0, 0);
+          S = mfma16<F16>(kr[tl][kk], qB[kk], S);
         // lane (head piece, row group grp) holds tokens tb + 4 * grp + i, i < 4
         float sc[4];
         float mx = ninf;
@@ -192,7 +210,7 @@ __device__ __forceinline__ void gqa_decode_items(const AttnDecodeArgs& a, const 
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
           float vf[8];
-          unpack8(vr[tl][j], vf);
+          unpack8<F16>(vr[tl][j], vf);
           // probability of token 4 * grp + j for head hh: register j of lane hh of this lane's own row
           float ph[G];
           ph[0] = row_share<0>(pw[j]);
@@ -288,7 +306,7 @@ __device__ __forceinline__ void merge_partials_to_out(const AttnDecodeArgs& a, i
       }
     }
     const int64_t o = ((int64_t)b * a.n_q_heads + h);
-    a.out[o * kHeadDim + tid] = f32_to_bf16_rne(Lt > 0.f ? At / Lt : 0.f);
+    a.out[o * kHeadDim + tid] = f32_to_16(Lt > 0.f ? At / Lt : 0.f, a.f16 != 0);
     if (a.lse && tid == 0) a.lse[o] = Lt > 0.f ? (Mt + log2f(Lt)) * 0.6931471805599453f : ninf;
   }
 }
@@ -299,16 +317,24 @@ struct RingSource {       // bounded cache of the all-local KV heads (see kv_rin
   int64_t row_stride, head_stride;
   const int64_t* seq_start;
 };
+struct PageSource {       // K and V are pools of pages: sequence b's page i is pool page table[b * stride + i]
+  const int32_t* table;
+  int64_t stride;
+  int32_t page_size;
+};
+// checks a page table's shape for contexts of up to max_ctx tokens and gives log2(page_size)
+int32_t check_pages(const char* who, const PageSource* pages, int64_t max_ctx, int* page_shift);
 
 // attn_decode.hip: argument checks + plan of a range-source (local / dense) decode call, without the launch
 int32_t decode_range_prepare(const char* who, bool dense, const rtp_layer_desc* L, const void* q, const void* K,
                              const void* V, int64_t row_stride, int64_t head_stride, const int64_t* seq_start,
                              const int32_t* ctx_len, int32_t B, int64_t max_ctx, void* out, float* lse, void* ws,
-                             size_t ws_bytes, const RingSource* ring, AttnDecodeArgs* args, int* grid, bool* launch);
+                             size_t ws_bytes, const RingSource* ring, AttnDecodeArgs* args, int* grid, bool* launch,
+                             const PageSource* pages = nullptr);
 int32_t decode_range_attn(const char* who, bool dense, const rtp_layer_desc* L, const void* q, const void* K,
                           const void* V, int64_t row_stride, int64_t head_stride, const int64_t* seq_start,
                           const int32_t* ctx_len, int32_t B, int64_t max_ctx, void* out, float* lse, void* ws,
-                          size_t ws_bytes, hipStream_t s);
+                          size_t ws_bytes, hipStream_t s, const PageSource* pages = nullptr);
 size_t decode_range_ws(bool dense, const rtp_layer_desc* L, int32_t B, int64_t max_ctx);
 
 }  // namespace rtp

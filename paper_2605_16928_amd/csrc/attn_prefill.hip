@@ -59,6 +59,7 @@ struct PrefillArgs {
   int32_t* count;
   float* mass;
   float* sel_thr;               // [n_ret, n_q]: a candidate is kept iff its raw index product is >= this
+  int32_t f16;                  // q, K, V and out are fp16 (else bf16)
 };
 
 enum { kModeDense = 0, kModeLocal = 1, kModeSparse = 2 };
@@ -82,8 +83,24 @@ __device__ __forceinline__ uint32_t pack_bf16(float a, float b) {
   const f32x2 f = {a, b};
   return __builtin_bit_cast(uint32_t, __builtin_convertvector(f, bf16x2));
 }
+// The attention tensors' element type is a template flag of the kernels (F16 = IEEE binary16, else bf16): two
+// floats rounded (nearest even) and packed, and the 32 x 32 x 16 MFMA on 16-bit operands with fp32 accumulation.
+typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
+typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
+template <bool F16> __device__ __forceinline__ uint32_t pack16(float a, float b) {
+  if constexpr (F16) {
+    const f32x2 f = {a, b};
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(f, f16x2));
+  } else {
+    return pack_bf16(a, b);
+  }
+}
+template <bool F16> __device__ __forceinline__ f32x16 mfma32(const u32x4 a, const u32x4 b, const f32x16 c) {
+  if constexpr (F16) return __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8, a), __builtin_bit_cast(f16x8, b), c, 0, 0, 0);
+  else return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
+}
 
-template <int MODE>
+template <int MODE, bool F16 = false>
 __global__ __launch_bounds__(kPfThreads, 2) void flash_prefill_kernel(const PrefillArgs a) {
   constexpr bool LOCAL = MODE == kModeLocal;
   static_assert(MODE == kModeDense || MODE == kModeLocal, "the selecting mode lives in the wide kernel");
@@ -202,8 +219,7 @@ __global__ __launch_bounds__(kPfThreads, 2) void flash_prefill_kernel(const Pref
 #pragma unroll
       for (int kk = 0; kk < 8; ++kk) {
         const u32x4 ka = *reinterpret_cast<const u32x4*>(&ks[(kb * 32 + r) * kKsStride + kk * 16 + g * 8]);
-        S[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, ka),
-                                                        __builtin_bit_cast(bf16x8, qreg[kk]), S[kb], 0, 0, 0);
+        S[kb] = mfma32<F16>(ka, qreg[kk], S[kb]);
       }
     }
     // interior tiles (every key visible to every query of the wave) skip the mask arithmetic
@@ -245,7 +261,7 @@ __global__ __launch_bounds__(kPfThreads, 2) void flash_prefill_kernel(const Pref
           const float p0 = fast_exp2(fmaf(S[kb][i], c, -mc));
           const float p1 = fast_exp2(fmaf(S[kb][i + 1], c, -mc));
           lsum += p0 + p1;
-          P[kb][i >> 1] = pack_bf16(p0, p1);
+          P[kb][i >> 1] = pack16<F16>(p0, p1);
         }
       }
       const float corr = fast_exp2((mrow - mnew) * c);     // 1 where the maximum did not move
@@ -268,8 +284,7 @@ __global__ __launch_bounds__(kPfThreads, 2) void flash_prefill_kernel(const Pref
         for (int db = 0; db < 4; ++db) {
           const int d = db * 32 + r;
           const u32x4 va = *reinterpret_cast<const u32x4*>(&vt[d * kVtStride + ((pos8 ^ ((d >> 4) & 7)) << 3)]);
-          O[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, va),
-                                                          __builtin_bit_cast(bf16x8, pb), O[db], 0, 0, 0);
+          O[db] = mfma32<F16>(va, pb, O[db]);
         }
       }
     }
@@ -316,8 +331,8 @@ __global__ __launch_bounds__(kPfThreads, 2) void flash_prefill_kernel(const Pref
   for (int db = 0; db < 4; ++db) {
 #pragma unroll
     for (int i4 = 0; i4 < 4; ++i4) {
-      const u32x2 w = (u32x2){pack_bf16(O[db][i4 * 4] * inv, O[db][i4 * 4 + 1] * inv),
-                              pack_bf16(O[db][i4 * 4 + 2] * inv, O[db][i4 * 4 + 3] * inv)};
+      const u32x2 w = (u32x2){pack16<F16>(O[db][i4 * 4] * inv, O[db][i4 * 4 + 1] * inv),
+                              pack16<F16>(O[db][i4 * 4 + 2] * inv, O[db][i4 * 4 + 3] * inv)};
       *reinterpret_cast<u32x2*>(orow + db * 32 + i4 * 8 + g * 4) = w;
     }
   }
@@ -686,7 +701,7 @@ typedef short s16x4 __attribute__((ext_vector_type(4)));
 typedef short s16x8 __attribute__((ext_vector_type(8)));
 
 
-template <int MODE, int QB>
+template <int MODE, int QB, bool F16 = false>
 __global__ __launch_bounds__(64 * (8 / QB), QB == 1 ? 2 : 1) void flash_prefill_wide_kernel(const PrefillArgs a) {
   constexpr int NW = 8 / QB;                 // waves per workgroup; each owns QB blocks of 32 queries
   constexpr int RG = 4 * NW;                 // tile rows one load instruction of the whole workgroup covers
@@ -860,10 +875,9 @@ __global__ __launch_bounds__(64 * (8 / QB), QB == 1 ? 2 : 1) void flash_prefill_
       for (int i = 0; i < 16; ++i) S[qb][i] = 0.f;
 #pragma unroll
     for (int kk = 0; kk < 8; ++kk) {
-      const bf16x8 ka = __builtin_bit_cast(bf16x8, read_k(tile, kb, kk));
+      const u32x4 ka = read_k(tile, kb, kk);
 #pragma unroll
-      for (int qb = 0; qb < QB; ++qb)
-        S[qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka, __builtin_bit_cast(bf16x8, qreg[qb][kk]), S[qb], 0, 0, 0);
+      for (int qb = 0; qb < QB; ++qb) S[qb] = mfma32<F16>(ka, qreg[qb][kk], S[qb]);
     }
   };
   // The same MFMAs with their K operands read three steps ahead and a slice of other work (issuing
@@ -882,7 +896,7 @@ __global__ __launch_bounds__(64 * (8 / QB), QB == 1 ? 2 : 1) void flash_prefill_
       if (kk + 3 < 8) ka[kk + 3] = read_k(tile, kb, kk + 3);
 #pragma unroll
       for (int qb = 0; qb < QB; ++qb) {
-        S[qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, ka[kk]), __builtin_bit_cast(bf16x8, qreg[qb][kk]), S[qb], 0, 0, 0);
+        S[qb] = mfma32<F16>(ka[kk], qreg[qb][kk], S[qb]);
         if (qb == 0) work(kk);
         __builtin_amdgcn_sched_barrier(0);
       }
@@ -894,11 +908,11 @@ __global__ __launch_bounds__(64 * (8 / QB), QB == 1 ? 2 : 1) void flash_prefill_
     for (int tt = 0; tt < 2; ++tt) {
 #pragma unroll
       for (int db = 0; db < 4; ++db) {
-        const bf16x8 va = __builtin_bit_cast(bf16x8, read_v(tile, kb, tt, db));
+        const u32x4 va = __builtin_bit_cast(u32x4, read_v(tile, kb, tt, db));
 #pragma unroll
         for (int qb = 0; qb < QB; ++qb) {
-          const bf16x8 pb = __builtin_bit_cast(bf16x8, (u32x4){P[qb][4 * tt], P[qb][4 * tt + 1], P[qb][4 * tt + 2], P[qb][4 * tt + 3]});
-          O[qb][db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va, pb, O[qb][db], 0, 0, 0);
+          const u32x4 pb = (u32x4){P[qb][4 * tt], P[qb][4 * tt + 1], P[qb][4 * tt + 2], P[qb][4 * tt + 3]};
+          O[qb][db] = mfma32<F16>(va, pb, O[qb][db]);
         }
       }
     }
@@ -932,7 +946,7 @@ __global__ __launch_bounds__(64 * (8 / QB), QB == 1 ? 2 : 1) void flash_prefill_
         const float p0 = fast_exp2(fmaf(S[qb][i], c, -mc));
         const float p1 = fast_exp2(fmaf(S[qb][i + 1], c, -mc));
         lsum += p0 + p1;
-        P[qb][i >> 1] = pack_bf16(p0, p1);
+        P[qb][i >> 1] = pack16<F16>(p0, p1);
       }
       lrow[qb] += lsum;
     }
@@ -946,7 +960,8 @@ __global__ __launch_bounds__(64 * (8 / QB), QB == 1 ? 2 : 1) void flash_prefill_
   // row_sum_add and the first use.
   auto row_sum_settled = [&](float& l) __attribute__((always_inline)) { asm volatile("s_nop 3" : "+v"(l)); };
   auto row_sum_add = [&](float& l, uint32_t pk) __attribute__((always_inline)) {
-    asm volatile("v_dot2c_f32_bf16 %0, %1, %2" : "+v"(l) : "v"(pk), "v"(0x3f803f80u));
+    if constexpr (F16) asm volatile("v_dot2c_f32_f16 %0, %1, %2" : "+v"(l) : "v"(pk), "v"(0x3c003c00u));
+    else asm volatile("v_dot2c_f32_bf16 %0, %1, %2" : "+v"(l) : "v"(pk), "v"(0x3f803f80u));
   };
   // The steady-state step: the PV MFMAs of the previous block and the softmax of the current block as
   // ONE hand-interleaved instruction sequence -- per MFMA (32 cycles of the matrix pipe) one pair of
@@ -981,8 +996,8 @@ __global__ __launch_bounds__(64 * (8 / QB), QB == 1 ? 2 : 1) void flash_prefill_
       if (k + 2 < 8) read_va(k + 2);
 #pragma unroll
       for (int qb = 0; qb < QB; ++qb) {
-        const bf16x8 pb = __builtin_bit_cast(bf16x8, (u32x4){Pin[qb][4 * tt], Pin[qb][4 * tt + 1], Pin[qb][4 * tt + 2], Pin[qb][4 * tt + 3]});
-        O[qb][db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, va[k]), pb, O[qb][db], 0, 0, 0);
+        const u32x4 pb = (u32x4){Pin[qb][4 * tt], Pin[qb][4 * tt + 1], Pin[qb][4 * tt + 2], Pin[qb][4 * tt + 3]};
+        O[qb][db] = mfma32<F16>(__builtin_bit_cast(u32x4, va[k]), pb, O[qb][db]);
         {
           float p0 = fast_exp2(fmaf(S[qb][2 * k], c, -mc[qb]));
           float p1 = fast_exp2(fmaf(S[qb][2 * k + 1], c, -mc[qb]));
@@ -992,7 +1007,7 @@ __global__ __launch_bounds__(64 * (8 / QB), QB == 1 ? 2 : 1) void flash_prefill_
             p1 = k1 ? p1 : 0.f;
             cnt[qb] += (k0 ? 1 : 0) + (k1 ? 1 : 0);
           }
-          Pout[qb][k] = pack_bf16(p0, p1);
+          Pout[qb][k] = pack16<F16>(p0, p1);
           row_sum_add(l[qb], Pout[qb][k]);
         }
         __builtin_amdgcn_sched_barrier(0);
@@ -1135,7 +1150,9 @@ __global__ __launch_bounds__(64 * (8 / QB), QB == 1 ? 2 : 1) void flash_prefill_
       // selecting mode: a query that kept no key of this range legitimately sums to zero
       const bool sees_key = SPARSE ? (sel_cnt[qb] + __shfl_xor(sel_cnt[qb], 32) > 0)
                                    : (qok[qb] && (LOCAL || tile_n0(it_lo) <= mq[qb]));
-      bad = bad || (sees_key && !(ltot > 0x1p-60f && ltot < 0x1p100f));
+      // (fp16 probabilities: nothing above 65504 -- a larger one is infinite and shows in the sum -- and a
+      // row whose largest probability is below 2^-6 has most of its mass in subnormals or flushed to zero)
+      bad = bad || (sees_key && !(ltot > (F16 ? 0x1p-6f : 0x1p-60f) && ltot < 0x1p100f));
     }
     redo = __syncthreads_or(bad ? 1 : 0) != 0;
   }
@@ -1180,7 +1197,7 @@ __global__ __launch_bounds__(64 * (8 / QB), QB == 1 ? 2 : 1) void flash_prefill_
             const float p0 = fast_exp2(fmaf(S[qb][i], c, -mc));
             const float p1 = fast_exp2(fmaf(S[qb][i + 1], c, -mc));
             lsum += p0 + p1;
-            P[qb][i >> 1] = pack_bf16(p0, p1);
+            P[qb][i >> 1] = pack16<F16>(p0, p1);
           }
           const float corr = fast_exp2((mrow[qb] - msafe) * c);
           lrow[qb] = lrow[qb] * corr + lsum;
@@ -1225,8 +1242,8 @@ __global__ __launch_bounds__(64 * (8 / QB), QB == 1 ? 2 : 1) void flash_prefill_
     for (int db = 0; db < 4; ++db) {
 #pragma unroll
       for (int i4 = 0; i4 < 4; ++i4) {
-        const u32x2 w = ltot > 0.f ? (u32x2){pack_bf16(O[qb][db][i4 * 4] * inv, O[qb][db][i4 * 4 + 1] * inv),
-                                             pack_bf16(O[qb][db][i4 * 4 + 2] * inv, O[qb][db][i4 * 4 + 3] * inv)}
+        const u32x2 w = ltot > 0.f ? (u32x2){pack16<F16>(O[qb][db][i4 * 4] * inv, O[qb][db][i4 * 4 + 1] * inv),
+                                             pack16<F16>(O[qb][db][i4 * 4 + 2] * inv, O[qb][db][i4 * 4 + 3] * inv)}
                                    : (u32x2){0u, 0u};
         *reinterpret_cast<u32x2*>(orow + db * 32 + i4 * 8 + g * 4) = w;
       }
@@ -1283,7 +1300,7 @@ __global__ __launch_bounds__(256) void prefill_combine_kernel(const PrefillArgs 
   }
   const int h = a.heads[hs];
   const int64_t o = (int64_t)t * a.n_q_heads + h;        // single sequence
-  a.out[o * kHeadDim + d] = f32_to_bf16_rne(L > 0.f ? A / L : 0.f);
+  a.out[o * kHeadDim + d] = f32_to_16(L > 0.f ? A / L : 0.f, a.f16 != 0);
   if (a.lse && d == 0) a.lse[o] = L > 0.f ? M * a.scale + logf(L) : ninf;
 }
 
@@ -1336,7 +1353,10 @@ static int32_t launch_prefill(const char* who, bool local, PrefillArgs& a, int32
   const int qt = local ? kPfQ : kPwQ;
   dim3 grid((unsigned)a.n_heads, (unsigned)((a.n_q + qt - 1) / qt), (unsigned)(B * (local ? 1 : a.n_splits)));
   if (grid.y > 65535 || grid.z > 65535) return fail(RTP_ERR_INVALID_ARG, "%s: n_q / B too large for one launch", who);
-  if (local) RTP_LAUNCH(flash_prefill_kernel<kModeLocal>, grid, dim3(kPfThreads), 0, s, a);
+  if (local) {
+    if (a.f16) RTP_LAUNCH((flash_prefill_kernel<kModeLocal, true>), grid, dim3(kPfThreads), 0, s, a);
+    else RTP_LAUNCH(flash_prefill_kernel<kModeLocal>, grid, dim3(kPfThreads), 0, s, a);
+  } else if (a.f16) RTP_LAUNCH((flash_prefill_wide_kernel<kModeDense, 1, true>), grid, dim3(512), 0, s, a);
   else RTP_LAUNCH((flash_prefill_wide_kernel<kModeDense, 1>), grid, dim3(512), 0, s, a);
   if (!local && a.n_splits > 1)
     RTP_LAUNCH(prefill_combine_kernel, dim3((unsigned)((a.n_q + 1) / 2), (unsigned)a.n_heads), dim3(256), 0, s, a);
@@ -1383,6 +1403,7 @@ int32_t prefill_range_attn(const char* who, bool dense, const rtp_layer_desc* L,
   a.sink = L->sink;
   a.window = L->window;
   a.scale = softmax_scale_of(L);
+  a.f16 = L->kv_dtype == RTP_DTYPE_FP16;
   a.scale_log2 = a.scale * 1.4426950408889634f;
   a.out = (uint16_t*)out;
   a.lse = lse;
@@ -1451,6 +1472,7 @@ extern "C" int32_t rtp_sparse_attn_prefill(const rtp_layer_desc* layer, const vo
   a.sink = layer->sink;
   a.window = layer->window;
   a.scale = softmax_scale_of(layer);
+  a.f16 = layer->kv_dtype == RTP_DTYPE_FP16;
   a.scale_log2 = a.scale * 1.4426950408889634f;
   a.out = (uint16_t*)out;
   a.lse = lse;
@@ -1510,7 +1532,8 @@ extern "C" int32_t rtp_sparse_attn_prefill(const rtp_layer_desc* layer, const vo
     else RTP_LAUNCH(prefill_select_kernel<4>, dim3(wgs), dim3(kPfThreads), 0, (hipStream_t)stream, a);
   }
   dim3 grid((unsigned)a.n_heads, (unsigned)((T + kPwQ - 1) / kPwQ), (unsigned)a.n_splits);
-  RTP_LAUNCH((flash_prefill_wide_kernel<kModeSparse, 1>), grid, dim3(512), 0, (hipStream_t)stream, a);
+  if (a.f16) RTP_LAUNCH((flash_prefill_wide_kernel<kModeSparse, 1, true>), grid, dim3(512), 0, (hipStream_t)stream, a);
+  else RTP_LAUNCH((flash_prefill_wide_kernel<kModeSparse, 1>), grid, dim3(512), 0, (hipStream_t)stream, a);
   if (a.n_splits > 1)
     RTP_LAUNCH(prefill_combine_kernel, dim3((unsigned)((T + 1) / 2), (unsigned)a.n_heads), dim3(256), 0,
                        (hipStream_t)stream, a);

@@ -56,12 +56,27 @@ __device__ __forceinline__ float bf16_lo(uint32_t u) { return __uint_as_float(u 
 __device__ __forceinline__ float bf16_hi(uint32_t u) { return __uint_as_float(u & 0xffff0000u); }
 __device__ __forceinline__ float bf16_to_f32(uint16_t b) { return __uint_as_float(((uint32_t)b) << 16); }
 
+// The attention tensors come in one of two 16-bit formats (F16 = IEEE binary16, else bf16): the halves of a
+// 32-bit word as floats, and fp32 rounded to the format (nearest even).
+template <bool F16> __device__ __forceinline__ float lo16(uint32_t u) {
+  if constexpr (F16) return (float)__builtin_bit_cast(_Float16, (uint16_t)(u & 0xffffu));
+  else return bf16_lo(u);
+}
+template <bool F16> __device__ __forceinline__ float hi16(uint32_t u) {
+  if constexpr (F16) return (float)__builtin_bit_cast(_Float16, (uint16_t)(u >> 16));
+  else return bf16_hi(u);
+}
+
 // fp32 -> bf16 round-to-nearest-even (finite inputs).
 __device__ __forceinline__ uint16_t f32_to_bf16_rne(float x) {
   uint32_t u = __float_as_uint(x);
   u += 0x7fffu + ((u >> 16) & 1u);
   return (uint16_t)(u >> 16);
 }
+
+__device__ __forceinline__ uint16_t f32_to_f16_rne(float x) { return __builtin_bit_cast(uint16_t, (_Float16)x); }
+// by a run-time flag (merge launches: one conversion per output element)
+__device__ __forceinline__ uint16_t f32_to_16(float x, bool f16) { return f16 ? f32_to_f16_rne(x) : f32_to_bf16_rne(x); }
 
 // fp64 -> bf16 round-to-nearest-even in ONE rounding step (normal range; tiny values flush to 0,
 // huge ones saturate to the largest finite bf16).

@@ -530,13 +530,13 @@ __global__ __launch_bounds__(kTpThreads) void topp_level_kernel(const TopPArgs a
 // no second stream (a fork and a join per step cost more than the overlap they buy).  Two workgroups per
 // compute unit, i.e. at most 128 vector registers: one tile per wave in flight (groups of 8 need 163 and
 // get one workgroup per compute unit).
-template <int LEVEL, int G>
+template <int LEVEL, int G, bool F16 = false, bool PAGED = false>
 __global__ __launch_bounds__(kTpThreads, G == 8 ? 2 : 4) void topp_level_ride_kernel(const TopPArgs a, const AttnDecodeArgs la,
                                                                         const int n_ride, const int item_lo,
                                                                         const int item_hi) {
   const int bid = blockIdx.x;
   if (bid < n_ride) {
-    gqa_decode_items<G, kSrcLocal, kTpThreads, 1>(la, item_lo + bid, n_ride, item_hi);
+    gqa_decode_items<G, kSrcLocal, kTpThreads, 1, F16, PAGED>(la, item_lo + bid, n_ride, item_hi);
     return;
   }
   const int r = (bid - n_ride) / a.n_chunks;
@@ -629,6 +629,10 @@ struct GatherArgs {
   float* part;             // [R, n_chunks, kSaPart]
   uint16_t* out;
   float* lse;
+  int32_t f16;             // q, K, V and out are fp16 (else bf16)
+  const int32_t* page_table;   // paged cache: [B, pt_stride] pool pages (NULL: contiguous sequences at seq_start)
+  int64_t pt_stride;
+  int32_t page_shift;
   int32_t ret_heads[64];
 };
 constexpr int kSaPart = kHeadDim + 4;      // m, l, 2 pad, acc[128]  (floats)
@@ -637,15 +641,13 @@ constexpr int kSaInFlight = 8;             // K/V rows in flight per 16-lane gro
                                            // or more rows, measured no faster: the gather is bandwidth-bound)
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
-__device__ __forceinline__ void unpack_bf16x8(const u32x4 v, float (&f)[8]) {
-  f[0] = bf16_lo(v.x); f[1] = bf16_hi(v.x); f[2] = bf16_lo(v.y); f[3] = bf16_hi(v.y);
-  f[4] = bf16_lo(v.z); f[5] = bf16_hi(v.z); f[6] = bf16_lo(v.w); f[7] = bf16_hi(v.w);
-}
-
-template <bool ATTEND>
+// PAGED (ATTEND only): the K/V rows of a sequence live in pool pages; the kept positions are translated to pool
+// rows once, into a second LDS list, before the gather starts.
+template <bool ATTEND, bool F16 = false, bool PAGED = false>
 __global__ __launch_bounds__(kTpThreads) void topp_write_kernel(const TopPArgs a, const GatherArgs ga) {
   const int r = blockIdx.y, c = blockIdx.x, tid = threadIdx.x;
   __shared__ int32_t sh_list[ATTEND ? kTpChunk : 1];
+  __shared__ int32_t sh_rows[(ATTEND && PAGED) ? kTpChunk : 1];
   // Levels 1 and 2 were last read by the level-2 / level-3 launches; every workgroup of the grid clears its
   // share on its way out (not on its way in: the barriers below would wait for the stores).
   // The same goes for the row's scalar results (chunk 0 stores them at the end).
@@ -851,10 +853,21 @@ __global__ __launch_bounds__(kTpThreads) void topp_write_kernel(const TopPArgs a
   const int b = r / ga.n_ret;
   const int h = ga.ret_heads[r - b * ga.n_ret];
   const int kvh = h / (ga.n_q_heads / ga.n_kv_heads);
-  const uint16_t* Kb = ga.K + (int64_t)kvh * ga.head_stride + ga.seq_start[b] * ga.row_stride + piece * 8;
-  const uint16_t* Vb = ga.V + (int64_t)kvh * ga.head_stride + ga.seq_start[b] * ga.row_stride + piece * 8;
+  const int64_t seq0 = PAGED ? 0 : ga.seq_start[b];
+  const uint16_t* Kb = ga.K + (int64_t)kvh * ga.head_stride + seq0 * ga.row_stride + piece * 8;
+  const uint16_t* Vb = ga.V + (int64_t)kvh * ga.head_stride + seq0 * ga.row_stride + piece * 8;
+  if (PAGED) {
+    const int32_t* pt = ga.page_table + (int64_t)b * ga.pt_stride;
+    const int mask = (1 << ga.page_shift) - 1;
+    for (int i = tid; i < kept_here; i += kTpThreads) {
+      const int p = sh_list[i];
+      sh_rows[i] = (pt[p >> ga.page_shift] << ga.page_shift) | (p & mask);
+    }
+    __syncthreads();
+  }
+  const int32_t* rows = PAGED ? sh_rows : sh_list;
   float qv[8];
-  unpack_bf16x8(*reinterpret_cast<const u32x4*>(ga.q + ((int64_t)b * ga.n_q_heads + h) * kHeadDim + piece * 8), qv);
+  unpack8<F16>(*reinterpret_cast<const u32x4*>(ga.q + ((int64_t)b * ga.n_q_heads + h) * kHeadDim + piece * 8), qv);
 #pragma unroll
   for (int d = 0; d < 8; ++d) qv[d] *= ga.scale_log2;
   float m = ninf, l = 0.f, acc[8];
@@ -869,7 +882,7 @@ __global__ __launch_bounds__(kTpThreads) void topp_write_kernel(const TopPArgs a
       const int i = base + u * kGroups + grp;
       ok[u] = i < kept_here;
       if (ok[u]) {
-        const int64_t pos = sh_list[i];
+        const int64_t pos = rows[i];
         kr[u] = *reinterpret_cast<const u32x4*>(Kb + pos * ga.row_stride);
         vr[u] = *reinterpret_cast<const u32x4*>(Vb + pos * ga.row_stride);
       } else {
@@ -882,7 +895,7 @@ __global__ __launch_bounds__(kTpThreads) void topp_write_kernel(const TopPArgs a
 #pragma unroll
     for (int u = 0; u < kSaInFlight; ++u) {
       float kf[8];
-      unpack_bf16x8(kr[u], kf);
+      unpack8<F16>(kr[u], kf);
       float d = kf[0] * qv[0];
 #pragma unroll
       for (int e = 1; e < 8; ++e) d = fmaf(kf[e], qv[e], d);
@@ -901,7 +914,7 @@ __global__ __launch_bounds__(kTpThreads) void topp_write_kernel(const TopPArgs a
 #pragma unroll
     for (int u = 0; u < kSaInFlight; ++u) {
       float vf[8];
-      unpack_bf16x8(vr[u], vf);
+      unpack8<F16>(vr[u], vf);
       const float pw = (sc[u] == ninf) ? 0.f : fast_exp2(sc[u] - m);
       l += pw;
 #pragma unroll
@@ -1023,7 +1036,7 @@ __global__ __launch_bounds__(256) void select_attend_combine_kernel(const TopPAr
     }
     const int b = r / ga.n_ret;
     const int64_t o = (int64_t)b * ga.n_q_heads + ga.ret_heads[r - b * ga.n_ret];
-    ga.out[o * kHeadDim + tid] = f32_to_bf16_rne(Lt > 0.f ? At / Lt : 0.f);
+    ga.out[o * kHeadDim + tid] = f32_to_16(Lt > 0.f ? At / Lt : 0.f, ga.f16 != 0);
     if (ga.lse && tid == 0) ga.lse[o] = Lt > 0.f ? (Mt + log2f(Lt)) * 0.6931471805599453f : ninf;
   }
 }
@@ -1107,16 +1120,29 @@ static int32_t run_select(const char* who, const float* scores, int64_t score_st
     const int n_items = ride->units * ride->n_splits;
     const int n_ride = n_items < 256 ? n_items : 256;
     const dim3 grid2((unsigned)(n_ride + a.n_chunks * R));
-    if (ride_G == 2) RTP_LAUNCH((topp_level_ride_kernel<2, 2>), grid2, block, 0, s, a, *ride, n_ride, 0, n_items);
-    else if (ride_G == 4) RTP_LAUNCH((topp_level_ride_kernel<2, 4>), grid2, block, 0, s, a, *ride, n_ride, 0, n_items);
-    else RTP_LAUNCH((topp_level_ride_kernel<2, 8>), grid2, block, 0, s, a, *ride, n_ride, 0, n_items);
+    const bool paged = ride->page_table != nullptr;
+#define RTP_RIDE(GG)                                                                                                   \
+  do {                                                                                                                  \
+    if (ride->f16 && paged) RTP_LAUNCH((topp_level_ride_kernel<2, GG, true, true>), grid2, block, 0, s, a, *ride, n_ride, 0, n_items);        \
+    else if (ride->f16) RTP_LAUNCH((topp_level_ride_kernel<2, GG, true, false>), grid2, block, 0, s, a, *ride, n_ride, 0, n_items);           \
+    else if (paged) RTP_LAUNCH((topp_level_ride_kernel<2, GG, false, true>), grid2, block, 0, s, a, *ride, n_ride, 0, n_items);               \
+    else RTP_LAUNCH((topp_level_ride_kernel<2, GG>), grid2, block, 0, s, a, *ride, n_ride, 0, n_items);                                       \
+  } while (0)
+    if (ride_G == 2) RTP_RIDE(2);
+    else if (ride_G == 4) RTP_RIDE(4);
+    else RTP_RIDE(8);
+#undef RTP_RIDE
     RTP_LAUNCH(topp_level_kernel<3>, grid, block, 0, s, a);
   } else {
     RTP_LAUNCH(topp_level_kernel<2>, grid, block, 0, s, a);
     RTP_LAUNCH(topp_level_kernel<3>, grid, block, 0, s, a);
   }
   if (attend) {
-    RTP_LAUNCH(topp_write_kernel<true>, grid, block, 0, s, a, *attend);
+    const bool paged = attend->page_table != nullptr;
+    if (attend->f16 && paged) RTP_LAUNCH((topp_write_kernel<true, true, true>), grid, block, 0, s, a, *attend);
+    else if (attend->f16) RTP_LAUNCH((topp_write_kernel<true, true>), grid, block, 0, s, a, *attend);
+    else if (paged) RTP_LAUNCH((topp_write_kernel<true, false, true>), grid, block, 0, s, a, *attend);
+    else RTP_LAUNCH(topp_write_kernel<true>, grid, block, 0, s, a, *attend);
     if (ride) {
       const dim3 cgrid((unsigned)(R + ride->units * ride_G));
       if (ride_G == 2) RTP_LAUNCH(select_attend_combine_kernel<2>, cgrid, dim3(256), 0, s, a, *attend, *ride);
@@ -1207,11 +1233,17 @@ extern "C" size_t rtp_select_attend_decode_workspace_bytes(const rtp_layer_desc*
 static int32_t prepare_select_attend(const char* who, const rtp_layer_desc* layer, const float* p, int32_t B, int64_t max_ctx,
                                      const void* q, const void* K, const void* V, int64_t kv_row_stride,
                                      int64_t kv_head_stride, const int64_t* seq_start, void* out, float* lse,
-                                     void* attn_ws, size_t attn_ws_bytes, GatherArgs* ga, int64_t* R) {
+                                     void* attn_ws, size_t attn_ws_bytes, GatherArgs* ga, int64_t* R,
+                                     const PageSource* pages = nullptr) {
   HeadTable ht;
   int32_t rc = fill_head_table(layer, &ht, who);
   if (rc != RTP_OK) return rc;
-  if (!p || !q || !K || !V || !out || !seq_start) return fail(RTP_ERR_INVALID_ARG, "%s: NULL tensor pointer", who);
+  if (!p || !q || !K || !V || !out || (!seq_start && !pages)) return fail(RTP_ERR_INVALID_ARG, "%s: NULL tensor pointer", who);
+  int page_shift = 0;
+  if (pages) {
+    rc = check_pages(who, pages, max_ctx, &page_shift);
+    if (rc != RTP_OK) return rc;
+  }
   if (kv_row_stride < kHeadDim || (kv_row_stride & 7) || (kv_head_stride & 7) || kv_head_stride < 0)
     return fail(RTP_ERR_INVALID_ARG, "%s: kv_row_stride must be >= 128, strides multiples of 8", who);
   if (((uintptr_t)q & 15) || ((uintptr_t)K & 15) || ((uintptr_t)V & 15) || ((uintptr_t)out & 15))
@@ -1237,6 +1269,10 @@ static int32_t prepare_select_attend(const char* who, const rtp_layer_desc* laye
   ga->part = (float*)attn_ws;
   ga->out = (uint16_t*)out;
   ga->lse = lse;
+  ga->f16 = layer->kv_dtype == RTP_DTYPE_FP16;
+  ga->page_table = pages ? pages->table : nullptr;
+  ga->pt_stride = pages ? pages->stride : 0;
+  ga->page_shift = page_shift;
   for (int j = 0; j < 64; ++j) ga->ret_heads[j] = ht.ret_heads[j];
   return RTP_OK;
 }
@@ -1260,31 +1296,31 @@ extern "C" int32_t rtp_select_attend_decode(const rtp_layer_desc* layer, const f
                     tau, mass, level1_ready, topp_ws, topp_ws_bytes, stream, &ga);
 }
 
-extern "C" int32_t rtp_decode_attention(const rtp_layer_desc* layer, const float* scores, int64_t score_stride,
-                                        const int32_t* row_len, const float* p, const int32_t* ctx_len, int32_t B,
-                                        int64_t max_ctx, const void* q, const void* K, const void* V,
-                                        int64_t kv_row_stride, int64_t kv_head_stride, const int64_t* seq_start,
-                                        int32_t* sel_idx, int64_t sel_stride, int32_t* sel_count,
-                                        float* tau, float* mass, int32_t level1_ready, void* out, float* lse,
-                                        void* topp_ws, size_t topp_ws_bytes, void* attn_ws, size_t attn_ws_bytes,
-                                        void* local_ws, size_t local_ws_bytes, void* stream) {
-  const char* who = "rtp_decode_attention";
+static int32_t decode_attention_impl(const char* who, const PageSource* pages,
+                                     const rtp_layer_desc* layer, const float* scores, int64_t score_stride,
+                                     const int32_t* row_len, const float* p, const int32_t* ctx_len, int32_t B,
+                                     int64_t max_ctx, const void* q, const void* K, const void* V,
+                                     int64_t kv_row_stride, int64_t kv_head_stride, const int64_t* seq_start,
+                                     int32_t* sel_idx, int64_t sel_stride, int32_t* sel_count,
+                                     float* tau, float* mass, int32_t level1_ready, void* out, float* lse,
+                                     void* topp_ws, size_t topp_ws_bytes, void* attn_ws, size_t attn_ws_bytes,
+                                     void* local_ws, size_t local_ws_bytes, void* stream) {
   GatherArgs ga;
   int64_t R = 0;
   int32_t rc = prepare_select_attend(who, layer, p, B, max_ctx, q, K, V, kv_row_stride, kv_head_stride, seq_start, out, lse,
-                                     attn_ws, attn_ws_bytes, &ga, &R);
+                                     attn_ws, attn_ws_bytes, &ga, &R, pages);
   if (rc != RTP_OK) return rc;
   AttnDecodeArgs la;
   int lgrid = 0;
   bool have_local = false;
   rc = decode_range_prepare(who, false, layer, q, K, V, kv_row_stride, kv_head_stride, seq_start, ctx_len, B, max_ctx, out,
-                            lse, local_ws, local_ws_bytes, nullptr, &la, &lgrid, &have_local);
+                            lse, local_ws, local_ws_bytes, nullptr, &la, &lgrid, &have_local, pages);
   if (rc != RTP_OK) return rc;
   const int G = layer->n_q_heads / layer->n_kv_heads;
   hipStream_t s = (hipStream_t)stream;
   if (layer->n_ret == 0) {               // nothing to select: the local heads are the whole layer
     return have_local ? decode_range_attn(who, false, layer, q, K, V, kv_row_stride, kv_head_stride, seq_start, ctx_len, B,
-                                          max_ctx, out, lse, local_ws, local_ws_bytes, s)
+                                          max_ctx, out, lse, local_ws, local_ws_bytes, s, pages)
                       : RTP_OK;
   }
   // groups of 8 need 163 vector registers for a carried item, which costs the level-2 launch a resident
@@ -1298,8 +1334,39 @@ extern "C" int32_t rtp_decode_attention(const rtp_layer_desc* layer, const float
                     mass, level1_ready, topp_ws, topp_ws_bytes, stream, &ga);
     if (rc != RTP_OK || !have_local) return rc;
     return decode_range_attn(who, false, layer, q, K, V, kv_row_stride, kv_head_stride, seq_start, ctx_len, B, max_ctx, out,
-                             lse, local_ws, local_ws_bytes, s);
+                             lse, local_ws, local_ws_bytes, s, pages);
   }
   return run_select(who, scores, score_stride, row_len, p, nullptr, (int32_t)R, max_ctx, sel_idx, sel_stride, sel_count, tau,
                     mass, level1_ready, topp_ws, topp_ws_bytes, stream, &ga, &la, G);
+}
+
+extern "C" int32_t rtp_decode_attention(const rtp_layer_desc* layer, const float* scores, int64_t score_stride,
+                                        const int32_t* row_len, const float* p, const int32_t* ctx_len, int32_t B,
+                                        int64_t max_ctx, const void* q, const void* K, const void* V,
+                                        int64_t kv_row_stride, int64_t kv_head_stride, const int64_t* seq_start,
+                                        int32_t* sel_idx, int64_t sel_stride, int32_t* sel_count,
+                                        float* tau, float* mass, int32_t level1_ready, void* out, float* lse,
+                                        void* topp_ws, size_t topp_ws_bytes, void* attn_ws, size_t attn_ws_bytes,
+                                        void* local_ws, size_t local_ws_bytes, void* stream) {
+  if (!seq_start) return fail(RTP_ERR_INVALID_ARG, "rtp_decode_attention: NULL tensor pointer");
+  return decode_attention_impl("rtp_decode_attention", nullptr, layer, scores, score_stride, row_len, p, ctx_len, B, max_ctx, q,
+                               K, V, kv_row_stride, kv_head_stride, seq_start, sel_idx, sel_stride, sel_count, tau, mass,
+                               level1_ready, out, lse, topp_ws, topp_ws_bytes, attn_ws, attn_ws_bytes, local_ws,
+                               local_ws_bytes, stream);
+}
+
+extern "C" int32_t rtp_decode_attention_paged(const rtp_layer_desc* layer, const float* scores, int64_t score_stride,
+                                              const int32_t* row_len, const float* p, const int32_t* ctx_len, int32_t B,
+                                              int64_t max_ctx, const void* q, const void* K, const void* V,
+                                              int64_t kv_row_stride, int64_t kv_head_stride,
+                                              const int32_t* page_table, int64_t pt_stride, int32_t page_size,
+                                              int32_t* sel_idx, int64_t sel_stride, int32_t* sel_count,
+                                              float* tau, float* mass, int32_t level1_ready, void* out, float* lse,
+                                              void* topp_ws, size_t topp_ws_bytes, void* attn_ws, size_t attn_ws_bytes,
+                                              void* local_ws, size_t local_ws_bytes, void* stream) {
+  const PageSource pages = {page_table, pt_stride, page_size};
+  return decode_attention_impl("rtp_decode_attention_paged", &pages, layer, scores, score_stride, row_len, p, ctx_len, B,
+                               max_ctx, q, K, V, kv_row_stride, kv_head_stride, nullptr, sel_idx, sel_stride, sel_count, tau,
+                               mass, level1_ready, out, lse, topp_ws, topp_ws_bytes, attn_ws, attn_ws_bytes, local_ws,
+                               local_ws_bytes, stream);
 }

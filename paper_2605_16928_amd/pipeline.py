@@ -13,7 +13,8 @@ DEV = "cuda:0"
 
 def layer_desc_of(layer: wl.Layer):
     return rtp.layer_desc(layer.n_q_heads, layer.n_kv_heads, layer.ret_heads, layer.sink, layer.window,
-                          softmax_scale=layer.softmax_scale, index_scale=layer.index_scale)
+                          softmax_scale=layer.softmax_scale, index_scale=layer.index_scale,
+                          kv_dtype=rtp.RTP_DTYPE_FP16 if layer.kv_dtype == "fp16" else rtp.RTP_DTYPE_BF16)
 
 
 def ws_alloc(nbytes: int) -> torch.Tensor:
@@ -59,7 +60,7 @@ class DecodeRun:
         self.sel_count = torch.full((max(self.R, 1),), -7, dtype=torch.int32, device=DEV)
         self.tau = torch.zeros((max(self.R, 1),), dtype=torch.float32, device=DEV)
         self.mass = torch.zeros((max(self.R, 1),), dtype=torch.float32, device=DEV)
-        self.out = torch.zeros((self.B, L.n_q_heads, 128), dtype=torch.bfloat16, device=DEV)
+        self.out = torch.zeros((self.B, L.n_q_heads, 128), dtype=w.q.dtype, device=DEV)
         self.lse = torch.zeros((self.B, L.n_q_heads), dtype=torch.float32, device=DEV)
         self.ws_topp = ws_alloc(rtp.rtp_topp_workspace_bytes(max(self.R, 1), self.max_ctx))
         rtp.rtp_topp_workspace_init(self.ws_topp)
@@ -273,7 +274,7 @@ class PrefillRun:
         L = w.layer
         self.desc = layer_desc_of(L)
         self.seq_start, self.ctx_len, self.q_start = i64([0]), i32([w.N]), i32([w.chunk_start])
-        self.out = torch.zeros((w.T, L.n_q_heads, 128), dtype=torch.bfloat16, device=DEV)
+        self.out = torch.zeros((w.T, L.n_q_heads, 128), dtype=w.q.dtype, device=DEV)
         self.lse = torch.zeros((w.T, L.n_q_heads), dtype=torch.float32, device=DEV)
         self.tau = torch.zeros((max(L.n_ret, 1), w.T), dtype=torch.float32, device=DEV)
         self.mass = torch.zeros((max(L.n_ret, 1), w.T), dtype=torch.float32, device=DEV)

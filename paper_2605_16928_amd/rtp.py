@@ -29,11 +29,12 @@ EXPORTS = [
     "rtp_index_project", "rtp_topk_select",
     "rtp_block_topp_workspace_bytes", "rtp_block_topp_select", "rtp_sparsity_stats",
     "rtp_select_attend_decode_workspace_bytes", "rtp_select_attend_decode",
-    "rtp_decode_attention", "rtp_sparse_attn_decode_paged",
+    "rtp_decode_attention", "rtp_decode_attention_paged", "rtp_sparse_attn_decode_paged",
     "rtp_kv_ring_heads", "rtp_kv_ring_append", "rtp_kv_ring_fill",
     "rtp_local_attn_ring_workspace_bytes", "rtp_local_attn_ring",
 ]
 RTP_SIDE_QUERY, RTP_SIDE_KEY = 0, 1
+RTP_DTYPE_BF16, RTP_DTYPE_FP16 = 0, 1
 
 
 class RtpError(RuntimeError):
@@ -51,16 +52,16 @@ class rtp_layer_desc(C.Structure):
         ("n_q_heads", C.c_int32), ("n_kv_heads", C.c_int32), ("head_dim", C.c_int32), ("index_dim", C.c_int32),
         ("n_ret", C.c_int32), ("ret_heads", C.POINTER(C.c_int32)),
         ("sink", C.c_int32), ("window", C.c_int32),
-        ("softmax_scale", C.c_float), ("index_scale", C.c_float),
+        ("softmax_scale", C.c_float), ("index_scale", C.c_float), ("kv_dtype", C.c_int32),
     ]
 
 
 def layer_desc(n_q_heads: int, n_kv_heads: int, ret_heads: Sequence[int], sink: int, window: int,
                head_dim: int = 128, index_dim: int = 16, softmax_scale: float = 0.0,
-               index_scale: float = 0.0) -> rtp_layer_desc:
+               index_scale: float = 0.0, kv_dtype: int = 0) -> rtp_layer_desc:
     arr = (C.c_int32 * max(len(ret_heads), 1))(*ret_heads)
     d = rtp_layer_desc(n_q_heads, n_kv_heads, head_dim, index_dim, len(ret_heads),
-                       C.cast(arr, C.POINTER(C.c_int32)), sink, window, softmax_scale, index_scale)
+                       C.cast(arr, C.POINTER(C.c_int32)), sink, window, softmax_scale, index_scale, kv_dtype)
     d._keepalive = arr
     return d
 
@@ -132,6 +133,9 @@ def lib() -> C.CDLL:
     L.rtp_decode_attention.restype = i32
     L.rtp_decode_attention.argtypes = [dp, vp, i64, vp, vp, vp, i32, i64, vp, vp, vp, i64, i64, vp, vp, i64, vp, vp, vp,
                                        i32, vp, vp, vp, sz, vp, sz, vp, sz, vp]
+    L.rtp_decode_attention_paged.restype = i32
+    L.rtp_decode_attention_paged.argtypes = [dp, vp, i64, vp, vp, vp, i32, i64, vp, vp, vp, i64, i64, vp, i64, i32, vp, i64,
+                                             vp, vp, vp, i32, vp, vp, vp, sz, vp, sz, vp, sz, vp]
     L.rtp_kv_ring_heads.restype = i32
     L.rtp_kv_ring_heads.argtypes = [dp, vp]
     L.rtp_kv_ring_append.restype = i32
@@ -260,6 +264,17 @@ def rtp_sparse_attn_decode_paged(layer, q, K, V, kv_row_stride, kv_head_stride, 
                                               _ptr(page_table), pt_stride, page_size, _ptr(sel_idx), sel_stride,
                                               _ptr(sel_count), max_sel, B, _ptr(out), _ptr(lse), _ptr(ws), _nbytes(ws),
                                               _stream(stream)))
+
+
+def rtp_decode_attention_paged(layer, scores, score_stride, row_len, p, ctx_len, B, max_ctx, q, K, V, kv_row_stride,
+                               kv_head_stride, page_table, pt_stride, page_size, sel_idx, sel_stride, sel_count, tau, mass,
+                               out, lse, topp_ws, attn_ws, local_ws, level1_ready=0, stream=None):
+    _check(lib().rtp_decode_attention_paged(C.byref(layer), _ptr(scores), score_stride, _ptr(row_len), _ptr(p),
+                                            _ptr(ctx_len), B, max_ctx, _ptr(q), _ptr(K), _ptr(V), kv_row_stride,
+                                            kv_head_stride, _ptr(page_table), pt_stride, page_size, _ptr(sel_idx),
+                                            sel_stride, _ptr(sel_count), _ptr(tau), _ptr(mass), level1_ready, _ptr(out),
+                                            _ptr(lse), _ptr(topp_ws), _nbytes(topp_ws), _ptr(attn_ws), _nbytes(attn_ws),
+                                            _ptr(local_ws), _nbytes(local_ws), _stream(stream)))
 
 
 def rtp_decode_attention(layer, scores, score_stride, row_len, p, ctx_len, B, max_ctx, q, K, V, kv_row_stride,

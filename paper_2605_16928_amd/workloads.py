@@ -34,6 +34,7 @@ class Layer:
     window: int
     head_dim: int = HEAD_DIM
     index_dim: int = INDEX_DIM
+    kv_dtype: str = "bf16"          # element type of q, K, V and the output: "bf16" or "fp16"
     softmax_scale: float = 0.0      # 0 = the paper's 1/sqrt(head_dim)
     index_scale: float = 0.0        # 0 = 1 (the indexer equation has no scale)
 
@@ -91,17 +92,21 @@ def _gen(seed: int, device) -> torch.Generator:
     return g
 
 
-def _randn_bf16(shape, g, device, std: float = 1.0, chunk_rows: int = 1 << 20) -> torch.Tensor:
-    """N(0, std^2) in fp32, rounded to bf16; generated in slabs to bound the fp32 temporary."""
-    out = torch.empty(shape, dtype=torch.bfloat16, device=device)
+def _randn_bf16(shape, g, device, std: float = 1.0, chunk_rows: int = 1 << 20, dtype=torch.bfloat16) -> torch.Tensor:
+    """N(0, std^2) in fp32, rounded once to bf16 (or `dtype`); generated in slabs to bound the fp32 temporary."""
+    out = torch.empty(shape, dtype=dtype, device=device)
     flat = out.view(-1, shape[-1])
     for r0 in range(0, flat.shape[0], chunk_rows):
         r1 = min(flat.shape[0], r0 + chunk_rows)
         x = torch.randn((r1 - r0, shape[-1]), generator=g, device=device, dtype=torch.float32)
         if std != 1.0:
             x *= std
-        flat[r0:r1] = x.to(torch.bfloat16)
+        flat[r0:r1] = x.to(dtype)
     return out
+
+
+def _kv_torch_dtype(layer) -> torch.dtype:
+    return {"bf16": torch.bfloat16, "fp16": torch.float16}[layer.kv_dtype]
 
 
 def _unit(x: torch.Tensor) -> torch.Tensor:
@@ -156,9 +161,10 @@ def make_decode(name: str, layer: Layer, ctx_len: List[int], p, seed: int, devic
         seq_start.append(seq_start[-1] + int(n))
     T_tot = int(sum(ctx_len))
 
-    K = _randn_bf16((Hkv, T_tot, D), g, dev)
-    V = _randn_bf16((Hkv, T_tot, D), g, dev)
-    q = _randn_bf16((B, Hq, D), g, dev)
+    kvt = _kv_torch_dtype(layer)
+    K = _randn_bf16((Hkv, T_tot, D), g, dev, dtype=kvt)
+    V = _randn_bf16((Hkv, T_tot, D), g, dev, dtype=kvt)
+    q = _randn_bf16((B, Hq, D), g, dev, dtype=kvt)
     kI = torch.empty((n_ret, T_tot, r), dtype=torch.bfloat16, device=dev)
 
     WQ = q_pre = qI = None
@@ -218,11 +224,11 @@ def c1(device="cpu", seed: int = 0, ctx: int = 4096) -> DecodeWorkload:
     return make_decode("c1", layer, [ctx], 0.9, seed, device, index_mode="proj", n_planted=8, runs_of=0)
 
 
-def c2(device="cpu", seed: int = 1, p: float = 0.9, ctx: int = 131072, batch: int = 8) -> DecodeWorkload:
+def c2(device="cpu", seed: int = 1, p: float = 0.9, ctx: int = 131072, batch: int = 8, kv_dtype: str = "bf16") -> DecodeWorkload:
     """Decode, 32 query / 8 KV heads, 4 retrieval heads, batch 8 x 131072, 64 planted
     tokens per row holding ~85 % of the indexer mass, background scores ~ N(0,1),
     local heads 4 sink + 2048 window."""
-    layer = Layer(32, 8, [0, 8, 16, 24], sink=4, window=2048)
+    layer = Layer(32, 8, [0, 8, 16, 24], sink=4, window=2048, kv_dtype=kv_dtype)
     return make_decode("c2", layer, [ctx] * batch, p, seed, device, index_mode="direct",
                        n_planted=64, planted_frac=0.85)
 
@@ -259,11 +265,11 @@ def c5(device="cpu", seed: int = 4, batch: int = 32, lo: int = 16384, hi: int = 
 
 def small_decode(device="cpu", seed: int = 11, ctx=(700, 1531, 64, 2048), *, n_q_heads=8, n_kv_heads=2,
                  ret_heads=(0, 1, 5), sink=4, window=96, p=(0.8, 0.9, 0.95, 0.9),
-                 index_mode="direct", n_planted=8) -> DecodeWorkload:
+                 index_mode="direct", n_planted=8, kv_dtype="bf16") -> DecodeWorkload:
     """A shrunken ragged batch with every structural feature of the large ones:
     several sequences of unequal length, two retrieval heads sharing a KV head,
     contexts shorter and longer than sink + window."""
-    layer = Layer(n_q_heads, n_kv_heads, list(ret_heads), sink=sink, window=window)
+    layer = Layer(n_q_heads, n_kv_heads, list(ret_heads), sink=sink, window=window, kv_dtype=kv_dtype)
     p = [p[i % len(p)] for i in range(len(ctx))]          # one p per sequence, cycling the given ones
     return make_decode("small", layer, list(ctx), list(p), seed, device, index_mode=index_mode,
                        n_planted=n_planted, planted_frac=0.6)
@@ -273,7 +279,7 @@ def small_decode(device="cpu", seed: int = 11, ctx=(700, 1531, 64, 2048), *, n_q
 # helpers for handing tensors to numpy consumers
 # ---------------------------------------------------------------------------
 def bf16_bits(t: torch.Tensor):
-    """bf16 tensor -> numpy uint16 array of its bit patterns (a copy on the host)."""
+    """bf16 (or fp16) tensor -> numpy uint16 array of its bit patterns (a copy on the host)."""
     import numpy as np
     return t.detach().contiguous().view(torch.int16).cpu().numpy().view(np.uint16)
 
@@ -323,9 +329,10 @@ def make_prefill(name: str, layer: Layer, chunk_start: int, T: int, p: float, se
     g = _gen(seed, dev)
     Hq, Hkv, D, r, n_ret = layer.n_q_heads, layer.n_kv_heads, layer.head_dim, layer.index_dim, layer.n_ret
     N = int(chunk_start) + int(T)
-    K = _randn_bf16((Hkv, N, D), g, dev)
-    V = _randn_bf16((Hkv, N, D), g, dev)
-    q = _randn_bf16((T, Hq, D), g, dev)
+    kvt = _kv_torch_dtype(layer)
+    K = _randn_bf16((Hkv, N, D), g, dev, dtype=kvt)
+    V = _randn_bf16((Hkv, N, D), g, dev, dtype=kvt)
+    q = _randn_bf16((T, Hq, D), g, dev, dtype=kvt)
     WQ = q_pre = qI = cstart = csize = None
     if index_mode == "proj":
         WQ = torch.randn((n_ret, r, D), generator=g, device=dev, dtype=torch.float32) * (D ** -0.5)
@@ -389,7 +396,7 @@ def c4_chunk(device="cpu", seed: int = 3, chunk: int = 127, T: int = 8192, p: fl
 
 def small_prefill(device="cpu", seed: int = 41, chunk_start: int = 700, T: int = 200, p: float = 0.9, *,
                   n_q_heads=8, n_kv_heads=2, ret_heads=(0, 5), sink=4, window=160, index_mode="direct",
-                  tokens_per_cluster=128, cluster_len=8, zipf=0.0) -> PrefillWorkload:
-    layer = Layer(n_q_heads, n_kv_heads, list(ret_heads), sink=sink, window=window)
+                  tokens_per_cluster=128, cluster_len=8, zipf=0.0, kv_dtype="bf16") -> PrefillWorkload:
+    layer = Layer(n_q_heads, n_kv_heads, list(ret_heads), sink=sink, window=window, kv_dtype=kv_dtype)
     return make_prefill("small_prefill", layer, chunk_start, T, p, seed, device, index_mode=index_mode,
                         tokens_per_cluster=tokens_per_cluster, cluster_len=cluster_len, zipf=zipf, max_cluster=64)

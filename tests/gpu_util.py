@@ -22,7 +22,7 @@ def oracle_inputs(w: wl.DecodeWorkload) -> dict:
              kI_bits=wl.bf16_bits(w.kI), seq_start=w.seq_start, ctx_len=w.ctx_len,
              n_q_heads=L.n_q_heads, n_kv_heads=L.n_kv_heads, ret_heads=L.ret_heads, sink=L.sink,
              window=L.window, p_rows=w.p_rows.cpu().numpy().astype(np.float64),
-             softmax_scale=L.softmax_scale, index_scale=L.index_scale)
+             softmax_scale=L.softmax_scale, index_scale=L.index_scale, kv_dtype=L.kv_dtype)
     if w.WQ is not None:
         d.update(WQ=w.WQ.cpu().numpy(), q_pre_bits=wl.bf16_bits(w.q_pre))
     else:
@@ -100,7 +100,7 @@ def attend_reference(w: wl.DecodeWorkload, oi: dict, sets) -> dict:
             if len(sets[b * L.n_ret + j]) == 0:
                 continue
             ref[(b, h)] = orc.attend(oi["q_bits"][b, h], oi["K_bits"][kvh, t0:t0 + n], oi["V_bits"][kvh, t0:t0 + n],
-                                     sets[b * L.n_ret + j], sc)
+                                     sets[b * L.n_ret + j], sc, L.kv_dtype)
     return ref
 
 
@@ -172,7 +172,7 @@ def prefill_oracle_inputs(w: "wl.PrefillWorkload") -> dict:
     d = dict(q_bits=wl.bf16_bits(w.q), K_bits=wl.bf16_bits(w.K), V_bits=wl.bf16_bits(w.V),
              kI_bits=wl.bf16_bits(w.kI), chunk_start=w.chunk_start, n_q_heads=L.n_q_heads,
              n_kv_heads=L.n_kv_heads, ret_heads=L.ret_heads, sink=L.sink, window=L.window,
-             softmax_scale=L.softmax_scale, index_scale=L.index_scale)
+             softmax_scale=L.softmax_scale, index_scale=L.index_scale, kv_dtype=L.kv_dtype)
     if w.WQ is not None:
         d.update(WQ=w.WQ.cpu().numpy(), q_pre_bits=wl.bf16_bits(w.q_pre))
     else:

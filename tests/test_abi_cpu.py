@@ -324,3 +324,25 @@ def test_sparse_prefill_refuses_an_oversized_chunk_before_any_launch():
     rc = lib.rtp_sparse_attn_prefill(C.byref(L), vp(A), vp(A), vp(A), vp(A), 16 * 64, vp(A), vp(A), 128, 1 << 40,
                                      0, T, C.c_float(0.9), vp(A), None, None, None, None, vp(A), 1 << 50, None)
     assert rc == rtp.RTP_ERR_INVALID_ARG and b"too large" in lib.rtp_last_error()
+
+
+def test_paged_decode_attention_and_dtype_argument_checks():
+    lib = rtp.lib()
+    vp = C.c_void_p
+    L = _layer()
+    _expect(rtp.RTP_ERR_UNSUPPORTED, lambda: rtp.rtp_index_score(_layer(kv_dtype=7), q_in=A, WQ=None, kI=A, kI_head_stride=1024,
+                                                                  seq_start=A, ctx_len=A, q_start=None, B=1, n_q=1, max_ctx=64,
+                                                                  scores=A, score_stride=64, qI_out=None, stream=0))
+    assert "kv_dtype" in rtp.rtp_last_error()
+    ws = 1 << 30
+
+    def call(table=A, page_size=64, pt_stride=64, q=A):
+        return lib.rtp_decode_attention_paged(C.byref(L), vp(A), 4096, vp(A), vp(A), vp(A), 2, 4096, vp(q), vp(A), vp(A), 128,
+                                              128 * 100, vp(table), pt_stride, page_size, vp(A), 4096, vp(A), None, None, 0,
+                                              vp(A), None, vp(A), ws, vp(A), ws, vp(A), ws, None)
+
+    assert call(table=None) == rtp.RTP_ERR_INVALID_ARG
+    assert call(page_size=48) == rtp.RTP_ERR_INVALID_ARG and b"power of two" in lib.rtp_last_error()
+    assert call(page_size=8) == rtp.RTP_ERR_INVALID_ARG
+    assert call(pt_stride=63) == rtp.RTP_ERR_INVALID_ARG and b"pt_stride" in lib.rtp_last_error()
+    assert call(q=None) == rtp.RTP_ERR_INVALID_ARG

@@ -29,6 +29,13 @@ def _cases():
         "c5_small": lambda: wl.c5(DEV, batch=5, lo=3000, hi=40000),
         # the same head shape with a batch large enough for several local work items per carrying workgroup
         "c5_many": lambda: wl.c5(DEV, seed=6, batch=40, lo=100, hi=2500),
+        # fp16 attention tensors (q, K, V, output): G = 4 ragged, G = 1 and 2, G = 8, configuration 2 shrunk
+        "small_f16": lambda: wl.small_decode(DEV, seed=15, kv_dtype="fp16"),
+        "g1_f16": lambda: wl.small_decode(DEV, seed=16, n_q_heads=4, n_kv_heads=4, ret_heads=(1, 3), ctx=(300, 9000), kv_dtype="fp16"),
+        "g2_f16": lambda: wl.small_decode(DEV, seed=17, n_q_heads=8, n_kv_heads=4, ret_heads=(0, 1, 6), ctx=(4100, 77), kv_dtype="fp16"),
+        "g8_f16": lambda: wl.small_decode(DEV, seed=18, n_q_heads=16, n_kv_heads=2, ret_heads=(3, 8), ctx=(2500, 130, 9000),
+                                          sink=4, window=700, kv_dtype="fp16"),
+        "c2_small_f16": lambda: wl.c2(DEV, ctx=20000, batch=3, p=0.9, kv_dtype="fp16"),
     }
 
 
@@ -86,7 +93,7 @@ def test_decode_path_matches_oracle(name):
         for j, h in enumerate(L.ret_heads):
             kvh = h // (L.n_q_heads // L.n_kv_heads)
             o, l = orc.attend(oi["q_bits"][b, h], oi["K_bits"][kvh, t0:t0 + n], oi["V_bits"][kvh, t0:t0 + n],
-                              sets[b * L.n_ret + j], sc)
+                              sets[b * L.n_ret + j], sc, L.kv_dtype)
             check_out(out[b, h], o, f"{name} sparse b{b} h{h}")
             assert abs(lse[b, h] - l) < 2e-3
 
@@ -360,7 +367,7 @@ def test_level1_in_score_pass_gives_the_same_selection():
 _attend_reference = attend_reference
 
 
-@pytest.mark.parametrize("name", ["small", "small_proj", "g1", "g2", "c2_small", "c5_small"])
+@pytest.mark.parametrize("name", ["small", "small_proj", "g1", "g2", "c2_small", "c5_small", "small_f16", "g1_f16", "c2_small_f16"])
 @pytest.mark.parametrize("fuse", [False, True])
 def test_select_attend_in_one_call_matches_oracle_and_the_two_calls(name, fuse):
     """rtp_select_attend_decode: the selection must be the oracle's top-p set of the same scores, the
@@ -440,7 +447,8 @@ def test_select_attend_degenerate_rows():
                 assert abs(lse[b, h] - ref[(b, h)][1]) < 2e-3
 
 
-@pytest.mark.parametrize("name", ["small", "g1", "g2", "c2_small", "c5_small", "c5_many"])
+@pytest.mark.parametrize("name", ["small", "g1", "g2", "c2_small", "c5_small", "c5_many", "small_f16", "g1_f16", "g2_f16",
+                                  "g8_f16", "c2_small_f16"])
 def test_decode_attention_in_one_call_matches_oracle(name):
     """rtp_decode_attention: everything after the score pass -- the layer's output (retrieval and local rows)
     against the oracle end to end, the selection bit-identical to rtp_topp_select's, twice in a row.  The cases

@@ -45,7 +45,7 @@ def _decode_fullsize(w, n_local_samples=24, n_dense_samples=2, seed=0):
             check_selection(sets[r], s64, orc.topp_select(s64, p), p, f"row {r} (same scores)")
             check_selection_valid(sets[r], s_ref, p, float(np.abs(s64 - s_ref).max()), f"row {r} (end to end)")
             Ks, Vs = kv_slice(h // G, t0, sets[r])
-            o, _ = orc.attend(qb[b, h], Ks, Vs, np.arange(len(sets[r])), SC)
+            o, _ = orc.attend(qb[b, h], Ks, Vs, np.arange(len(sets[r])), SC, L.kv_dtype)
             check_out(out[b, h], o, f"sparse b{b} h{h}")
             sizes.append(len(sets[r]))
     local_heads = [h for h in range(L.n_q_heads) if h not in L.ret_heads]
@@ -54,7 +54,7 @@ def _decode_fullsize(w, n_local_samples=24, n_dense_samples=2, seed=0):
         h = int(rng.choice(local_heads))
         ids = orc.local_set(w.ctx_len[b] - 1, L.sink, L.window)
         Ks, Vs = kv_slice(h // G, w.seq_start[b], ids)
-        o, _ = orc.attend(qb[b, h], Ks, Vs, np.arange(len(ids)), SC)
+        o, _ = orc.attend(qb[b, h], Ks, Vs, np.arange(len(ids)), SC, L.kv_dtype)
         check_out(out[b, h], o, f"local b{b} h{h}")
     dout = torch.zeros_like(run.out)
     run.dense_attn(dout)
@@ -65,7 +65,7 @@ def _decode_fullsize(w, n_local_samples=24, n_dense_samples=2, seed=0):
         h = int(rng.integers(L.n_q_heads))
         t0, n = w.seq_start[b], w.ctx_len[b]
         o, _ = orc.attend(qb[b, h], wl.bf16_bits(w.K[h // G, t0:t0 + n]), wl.bf16_bits(w.V[h // G, t0:t0 + n]),
-                          np.arange(n), SC)
+                          np.arange(n), SC, L.kv_dtype)
         check_out(dgot[b, h], o, f"dense b{b} h{h}")
 
     # selection and attention as two calls: the same sets bit for bit, the same outputs up to summation order
@@ -247,3 +247,12 @@ def test_c4_last_chunk_sampled_rows():
                              "c4 last chunk")
     print(f"   kept tokens over {len(kept)} sampled retrieval rows: min {min(kept)} mean {np.mean(kept):.0f} "
           f"max {max(kept)}", flush=True)
+
+
+def test_c2_full_size_fp16():
+    """Configuration 2 with fp16 attention tensors (the format the paper's decode kernel loads): the timed
+    step, every row against the oracle."""
+    print("[case] c2 full size, fp16 K/V", flush=True)
+    w = wl.c2(DEV, p=0.9, kv_dtype="fp16")
+    sizes = _decode_fullsize(w, 9)
+    assert min(sizes) > 1000

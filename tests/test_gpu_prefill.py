@@ -29,6 +29,10 @@ def _cases():
         "g8": dict(n_q_heads=16, n_kv_heads=2, ret_heads=(0, 8), chunk_start=1000, T=96, seed=47),
         # a single query
         "one_query": dict(chunk_start=333, T=1, seed=48),
+        # fp16 attention tensors
+        "small_f16": dict(seed=49, kv_dtype="fp16"),
+        "g8_f16": dict(n_q_heads=16, n_kv_heads=2, ret_heads=(0, 8), chunk_start=1000, T=96, seed=50, kv_dtype="fp16"),
+        "first_chunk_f16": dict(chunk_start=0, T=130, seed=51, kv_dtype="fp16"),
     }
 
 
@@ -63,7 +67,7 @@ def test_prefill_local_dense_and_retrieval_p1(name):
     run.dense_attn(dout, dlse)
     torch.cuda.synchronize()
     dref = orc.dense_rows(rows=rows, q_bits=oi["q_bits"], K_bits=oi["K_bits"], V_bits=oi["V_bits"],
-                          chunk_start=w.chunk_start, n_q_heads=L.n_q_heads, n_kv_heads=L.n_kv_heads)
+                          chunk_start=w.chunk_start, n_q_heads=L.n_q_heads, n_kv_heads=L.n_kv_heads, kv_dtype=L.kv_dtype)
     o_ref = np.zeros_like(out)
     for r in dref:
         o_ref[r["t"], r["h"]] = r["out"]
@@ -170,6 +174,9 @@ def _sparse_cases():
         "proj": (dict(index_mode="proj", chunk_start=500, T=70, seed=64), 0.8),
         "zipf_g8": (dict(n_q_heads=16, n_kv_heads=2, ret_heads=(0, 8), chunk_start=1800, T=96, seed=65, zipf=1.1), 0.9),
         "p_to_one": (dict(chunk_start=300, T=40, seed=66), 0.9999999),
+        # fp16 attention tensors: the matrix-core variants on binary16 operands
+        "small_f16": (dict(seed=68, kv_dtype="fp16"), 0.9),
+        "g8_f16": (dict(n_q_heads=16, n_kv_heads=2, ret_heads=(0, 8), chunk_start=1800, T=96, seed=69, kv_dtype="fp16"), 0.8),
     }
 
 
@@ -243,10 +250,11 @@ def _check_sparse_prefill(w, name, p):
         kvh = h // (L.n_q_heads // L.n_kv_heads)
 
         def att(ids):
-            return orc.attend(oi["q_bits"][t, h], oi["K_bits"][kvh, :m + 1], oi["V_bits"][kvh, :m + 1], ids, sc)[0]
+            return orc.attend(oi["q_bits"][t, h], oi["K_bits"][kvh, :m + 1], oi["V_bits"][kvh, :m + 1], ids, sc, L.kv_dtype)[0]
 
         def att_abs(ids):
-            return orc.attend(oi["q_bits"][t, h], oi["K_bits"][kvh, :m + 1], oi["V_bits"][kvh, :m + 1] & 0x7fff, ids, sc)[0]
+            return orc.attend(oi["q_bits"][t, h], oi["K_bits"][kvh, :m + 1], oi["V_bits"][kvh, :m + 1] & 0x7fff, ids, sc,
+                              L.kv_dtype)[0]
 
         worst = max(worst, check_out_any(out[t, h], reported_sets(s, tg, int(cnt[j, t]), BAND, f"{name} t{t} h{h}"), att,
                                          f"{name} t{t} h{h} (same set)", att_abs))

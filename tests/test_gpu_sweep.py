@@ -117,7 +117,7 @@ def _decode_desc(rng):
                 p=tuple(float(x) for x in rng.choice([0.5, 0.8, 0.9, 0.95, 0.99, 1.0], size=4)),
                 mode=str(rng.choice(["direct", "proj"])), seed=int(rng.integers(1 << 30)),
                 n_planted=int(rng.choice([0, 1, 8])), fuse=bool(rng.integers(2)),
-                index_scale=float(rng.choice([0.0, 0.0, 0.5, 3.0])))
+                index_scale=float(rng.choice([0.0, 0.0, 0.5, 3.0])), kv_dtype=str(rng.choice(["bf16", "bf16", "fp16"])))
 
 
 def test_decode_sweep():
@@ -128,7 +128,7 @@ def test_decode_sweep():
         print("[case] decode sweep", case, json.dumps(d), flush=True)
         w = wl.small_decode("cpu", seed=d["seed"], ctx=d["ctx"], n_q_heads=d["nq"], n_kv_heads=d["nkv"],
                             ret_heads=d["ret"], sink=d["sink"], window=d["window"], p=d["p"], index_mode=d["mode"],
-                            n_planted=d["n_planted"])
+                            n_planted=d["n_planted"], kv_dtype=d["kv_dtype"])
         w.layer.index_scale = d["index_scale"]
         n_other += check_decode_case(w.to(DEV), f"sweep{case}", fuse_two=d["fuse"])
     print(f"   decode sweep: {n_other} retrieval rows differed from the oracle's set inside the band", flush=True)
@@ -182,7 +182,8 @@ def _prefill_desc(rng):
                 T=int(rng.choice([1, 17, 64, 100, 129, 200, 300])), start=int(rng.choice([0, 5, 100, 700, 1500, 3000])),
                 sink=int(rng.choice([0, 4, 40])), window=int(rng.choice([8, 100, 600, 8192])),
                 p=float(rng.choice([0.5, 0.8, 0.9, 0.99])), seed=int(rng.integers(1 << 30)),
-                mode=str(rng.choice(["direct", "proj"])), index_scale=float(rng.choice([0.0, 0.0, 0.5, 3.0])))
+                mode=str(rng.choice(["direct", "proj"])), index_scale=float(rng.choice([0.0, 0.0, 0.5, 3.0])),
+                kv_dtype=str(rng.choice(["bf16", "bf16", "fp16"])))
 
 
 def test_prefill_sweep():
@@ -192,6 +193,6 @@ def test_prefill_sweep():
         print("[case] prefill sweep", case, json.dumps(d), flush=True)
         w = wl.small_prefill("cpu", seed=d["seed"], chunk_start=d["start"], T=d["T"], p=d["p"], n_q_heads=d["nq"],
                              n_kv_heads=d["nkv"], ret_heads=d["ret"], sink=d["sink"], window=d["window"],
-                             index_mode=d["mode"])
+                             index_mode=d["mode"], kv_dtype=d["kv_dtype"])
         w.layer.index_scale = d["index_scale"]
         check_prefill_case(w.to(DEV), f"sweep{case}", d["p"])

@@ -263,7 +263,8 @@ def test_sparsity_stats_match_oracle(ret_heads):
 @pytest.mark.parametrize("heads", [dict(n_q_heads=8, n_kv_heads=4, ret_heads=(0, 5)),      # G = 2, bounded heads 1 and 3
                                    dict(n_q_heads=8, n_kv_heads=2, ret_heads=(1,)),        # G = 4, bounded head 1
                                    dict(n_q_heads=4, n_kv_heads=4, ret_heads=(1, 3)),      # G = 1, bounded heads 0 and 2
-                                   dict(n_q_heads=16, n_kv_heads=2, ret_heads=(9,))])      # G = 8, bounded head 0
+                                   dict(n_q_heads=16, n_kv_heads=2, ret_heads=(9,)),       # G = 8, bounded head 0
+                                   dict(n_q_heads=8, n_kv_heads=2, ret_heads=(1,), kv_dtype="fp16")])   # fp16 rows
 def test_bounded_cache_fill_append_and_local_attention(heads):
     """The bounded cache filled after "prefill" and extended token by token holds the oracle's rows bit for
     bit; local attention read from it matches the oracle's local attention over the full cache -- with the
@@ -277,7 +278,7 @@ def test_bounded_cache_fill_append_and_local_attention(heads):
     ring_heads = rtp.rtp_kv_ring_heads(run.desc)
     assert ring_heads == orc.ring_kv_heads(L.n_q_heads, L.n_kv_heads, L.ret_heads) and len(ring_heads) > 0
     n_ring, B = len(ring_heads), w.B
-    ring_K = torch.zeros((n_ring, B * cap + 5, 128), dtype=torch.bfloat16, device=DEV)
+    ring_K = torch.zeros((n_ring, B * cap + 5, 128), dtype=w.K.dtype, device=DEV)
     ring_V = torch.zeros_like(ring_K)
     ring_start = i64([b * cap + 5 for b in range(B)])                  # (an offset: the start array is honoured)
     hs = ring_K.shape[1] * 128
@@ -335,12 +336,12 @@ def test_bounded_cache_fill_append_and_local_attention(heads):
 # ---------------------------------------------------------------------------------------------------
 # retrieval heads' cache in pages
 # ---------------------------------------------------------------------------------------------------
-@pytest.mark.parametrize("page_size", [16, 64, 256])
-def test_paged_sparse_attention_matches_contiguous_and_oracle(page_size):
+@pytest.mark.parametrize("page_size,kv_dtype", [(16, "bf16"), (64, "bf16"), (256, "bf16"), (64, "fp16")])
+def test_paged_sparse_attention_matches_contiguous_and_oracle(page_size, kv_dtype):
     """The cache scattered into a shuffled page pool: the paged call must reproduce the contiguous call bit for
     bit (same rows, same order of arithmetic) and match the oracle's paged attention."""
     print(f"[case] paged sparse attention, page size {page_size}", flush=True)
-    w = wl.small_decode(DEV, seed=61, ctx=(700, 1531, 64, 2048, 5000))
+    w = wl.small_decode(DEV, seed=61, ctx=(700, 1531, 64, 2048, 5000), kv_dtype=kv_dtype)
     L = w.layer
     run = DecodeRun(w)
     run.index_score()
@@ -359,7 +360,7 @@ def test_paged_sparse_attention_matches_contiguous_and_oracle(page_size):
     for b in range(w.B):
         table[b, :n_pages[b]] = perm[at:at + n_pages[b]].to(torch.int32)
         at += n_pages[b]
-    K_pool = torch.full((L.n_kv_heads, pool_pages * page_size, 128), float("nan"), dtype=torch.bfloat16, device=DEV)
+    K_pool = torch.full((L.n_kv_heads, pool_pages * page_size, 128), float("nan"), dtype=w.K.dtype, device=DEV)
     V_pool = torch.full_like(K_pool, float("nan"))
     for b in range(w.B):
         t0, n = w.seq_start[b], w.ctx_len[b]
@@ -387,7 +388,81 @@ def test_paged_sparse_attention_matches_contiguous_and_oracle(page_size):
     for b in range(w.B):
         for j, h in enumerate(ret):
             o, l = orc.paged_attend(qb[b, h], Kb[h // G], Vb[h // G], table[b].numpy(), page_size, sets[b * L.n_ret + j],
-                                    1.0 / np.sqrt(128.0))
+                                    1.0 / np.sqrt(128.0), kv_dtype)
             err = np.abs(got[b, h] - o)
             assert (err <= 1e-3 + 2.0 ** -8 * np.abs(o)).all()
             assert abs(float(lse[b, h]) - l) < 2e-3
+
+
+@pytest.mark.parametrize("case", ["g4", "g8_f16", "g1", "g2_bigbatch"])
+def test_decode_attention_from_a_paged_cache(case):
+    """Everything after the score pass with the whole K/V cache in pages (retrieval heads' gather and the local
+    heads' sink + window rows through the page table): selections and outputs bit-identical to the contiguous
+    call, and every head against the oracle's attention read through the table.  The cases cover the carried
+    form (G = 2, 4, 8), the fall-back that runs the parts in turn (G = 1) and fp16 rows."""
+    print(f"[case] decode attention from a paged cache, {case}", flush=True)
+    kw = {"g4": dict(),
+          "g8_f16": dict(n_q_heads=16, n_kv_heads=2, ret_heads=(3, 8), sink=4, window=700, kv_dtype="fp16"),
+          "g1": dict(n_q_heads=4, n_kv_heads=4, ret_heads=(1, 3)),
+          "g2_bigbatch": dict(n_q_heads=8, n_kv_heads=4, ret_heads=(0, 1, 6))}[case]
+    ctx = (700, 1531, 64, 2048, 9000, 13) if case != "g2_bigbatch" else tuple(int(x) for x in
+                                                                             np.random.default_rng(3).integers(5, 3000, size=40))
+    page_size = 64 if case != "g1" else 16
+    w = wl.small_decode(DEV, seed=71, ctx=ctx, **kw)
+    L = w.layer
+    run = DecodeRun(w)
+    run.step_one_stream()
+    torch.cuda.synchronize()
+    want = (run.out.clone(), run.lse.clone(), run.sel_idx.clone(), run.sel_count.clone(), run.tau.clone(), run.mass.clone())
+    # one shuffled pool for all sequences and KV heads
+    g = torch.Generator().manual_seed(11)
+    n_pages = [-(-n // page_size) for n in w.ctx_len]
+    pool_pages = sum(n_pages) + 5
+    perm = torch.randperm(pool_pages, generator=g)
+    pt_stride = max(n_pages) + 1
+    table = torch.full((w.B, pt_stride), -1, dtype=torch.int32)
+    at = 0
+    for b in range(w.B):
+        table[b, :n_pages[b]] = perm[at:at + n_pages[b]].to(torch.int32)
+        at += n_pages[b]
+    K_pool = torch.full((L.n_kv_heads, pool_pages * page_size, 128), float("nan"), dtype=w.K.dtype, device=DEV)
+    V_pool = torch.full_like(K_pool, float("nan"))
+    for b in range(w.B):
+        t0, n = w.seq_start[b], w.ctx_len[b]
+        t = torch.arange(n)
+        rows = (table[b, t // page_size].long() * page_size + t % page_size).to(DEV)
+        K_pool[:, rows] = w.K[:, t0:t0 + n]
+        V_pool[:, rows] = w.V[:, t0:t0 + n]
+    table_d = table.to(DEV)
+    for rep in range(2):
+        run.out.fill_(3.0)
+        run.lse.fill_(3.0)
+        run.sel_idx.fill_(-1)
+        run.sel_count.fill_(-9)
+        run.index_score()
+        rtp.rtp_decode_attention_paged(run.desc, run.scores, run.stride, run.row_len, w.p_rows, run.ctx_len, w.B, run.max_ctx,
+                                       w.q, K_pool, V_pool, 128, K_pool.shape[1] * 128, table_d, pt_stride, page_size,
+                                       run.sel_idx, run.stride, run.sel_count, run.tau, run.mass, run.out, run.lse,
+                                       run.ws_topp, run.ws_fused, run.ws_local, level1_ready=1)
+        run._level1_pending = False
+        torch.cuda.synchronize()
+        got = (run.out, run.lse, run.sel_idx, run.sel_count, run.tau, run.mass)
+        for i, (a, b_) in enumerate(zip(want, got)):
+            if i == 2:                                     # index lists: the written part
+                cn = want[3].cpu().numpy()
+                assert all(torch.equal(a[r, :max(cn[r], 0)], b_[r, :max(cn[r], 0)]) for r in range(run.R))
+            else:
+                assert torch.equal(a, b_), f"paged call differs from the contiguous one (output {i}, repeat {rep})"
+    # and against the oracle reading through the table
+    sets, cnt = run.sel_sets()
+    qb, Kb, Vb = wl.bf16_bits(w.q), wl.bf16_bits(K_pool.nan_to_num(0.0)), wl.bf16_bits(V_pool.nan_to_num(0.0))
+    out = run.out_f64()
+    G = L.n_q_heads // L.n_kv_heads
+    for b in range(w.B):
+        for h in range(L.n_q_heads):
+            ids = sets[b * L.n_ret + list(L.ret_heads).index(h)] if h in L.ret_heads else orc.local_set(w.ctx_len[b] - 1, L.sink, L.window)
+            o, l = orc.paged_attend(qb[b, h], Kb[h // G], Vb[h // G], table[b].numpy(), page_size, ids, 1.0 / np.sqrt(128.0),
+                                    L.kv_dtype)
+            err = np.abs(out[b, h] - o)
+            assert (err <= 1e-3 + 2.0 ** -8 * np.abs(o)).all(), f"b{b} h{h}: {err.max()}"
+            assert abs(float(run.lse[b, h]) - l) < 2e-3
