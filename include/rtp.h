@@ -201,10 +201,13 @@ int32_t rtp_sparse_attn_decode(const rtp_layer_desc* layer, const void* q,
  * (post-RoPE).  Index queries as in (1): WQ != NULL => q_pre bf16 [T, n_q_heads, 128], else q_pre holds
  * qI bf16 [n_ret, T, 16].  out: bf16 [T, n_q_heads, 128], retrieval rows only.
  * Optional per-(j, t) statistics, fp32/int32 [n_ret, T]: tau (threshold used), count (tokens kept),
- * mass (indexer mass kept).  For p < 1 the threshold search works on floor((max - s) * 2^17), so the
- * kept set is the exact top-p set plus any token whose score lies within 2^-17 (7.6e-6) below its
- * threshold; candidates more than 16 below the row maximum share one bin (they are kept together or
- * not at all, which matters only for p within ~1e-7 of 1).  Masses are fp32 exponentials summed in fp64.
+ * mass (indexer mass kept).  For p < 1 the threshold search works on floor((ref - s) * 2^17), ref = the row
+ * maximum, so the kept set is the exact top-p set plus any token whose score lies within 2^-17 (7.6e-6) below
+ * its threshold.  One pass resolves the 15.875 score units below its reference; a threshold deeper than that
+ * (p within ~1e-5 of 1 on a peaked row) makes the search lower the reference and repeat, so the resolution is the
+ * same at any depth.  Masses are fp32 exponentials (relative error up to 2^-22) summed in fp64: where single
+ * tokens weigh less than 3e-7 of a row's mass, the kept count can differ from the fp64 count by the tokens
+ * inside that margin.
  */
 size_t rtp_sparse_attn_prefill_workspace_bytes(const rtp_layer_desc* layer, int32_t T, int64_t chunk_start);
 int32_t rtp_sparse_attn_prefill(const rtp_layer_desc* layer, const void* q_pre, const void* q, const float* WQ,

@@ -72,8 +72,9 @@ constexpr float kSelScale = 131072.0f;
 constexpr int kSelQMax = (1 << 21) - 1;
 constexpr int kTileHalfs = kPfK * kKsStride + kHeadDim * kVtStride;   // bf16 elements of one staged K + V^T tile
 constexpr int kSmemDense = kTileHalfs * 2 * 2;                        // two buffers
-constexpr int kSelListCap = 24;      // entries per lane; a tile adds at most 16, so lists are emptied above 8
-constexpr int kSelRing = 8;          // index-key tiles in flight per wave during the threshold search
+constexpr int kSelListCap = 16;      // entries per lane: what one tile can add (lists are emptied after every tile)
+constexpr int kSelMfma = 2;          // index-score MFMAs of a wave in flight (the SIMD's other wave covers their latency)
+constexpr int kSelRing = 4;          // index-key tiles in flight per wave during the threshold search
 
 __device__ __forceinline__ int sel_q_of_t(float tt) {       // tt = M - s >= 0
   return (int)fminf(tt * kSelScale, (float)kSelQMax);
@@ -364,9 +365,9 @@ __global__ __launch_bounds__(kPfThreads, 2) void flash_prefill_kernel(const Pref
 //    sweeps 2, 3 and of the attention kernel are then exact restatements of that definition, two
 //    (one) compare per pair, and only members do any further arithmetic.
 // No workgroup barrier: every wave owns its slice of LDS.
-#pragma clang fp contract(off)
-__device__ __forceinline__ float sel_t(float M, float x, float index_scale) { return M - x * index_scale; }
-#pragma clang fp contract(on)
+// t = M - x * index_scale as ONE fused operation (one rounding): the definition every sweep, the end points
+// of the digit intervals and the final threshold share
+__device__ __forceinline__ float sel_t(float M, float x, float index_scale) { return __builtin_fmaf(-x, index_scale, M); }
 
 // Smallest float x (as a raw product) with sel_t(M, x) < bound; -inf if every finite x qualifies.
 // sel_t is non-increasing in x, so the predicate flips once from false to true.
@@ -381,16 +382,31 @@ __device__ __forceinline__ float sel_first_below(float M, float index_scale, flo
 }
 
 //
-// KS (1, 2 or 4) waves share one group of 32 queries and split its key range between them: a launch with
-// few queries (a 4096-query chunk of 4 heads is 512 groups for 1024 SIMDs) then still fills the chip.  Each
-// wave keeps its own histogram; the scans add the KS histograms of a group in a fixed order, and the waves
-// of a workgroup meet at a barrier before and after every scan.
+// KS (2, 4 or 8) waves share one group of 32 queries and split its key range between them; a workgroup is eight
+// waves -- two per SIMD, so that one wave's vector instructions issue under the other's latencies -- i.e. 8 / KS
+// groups.  The waves of a group add into ONE histogram (LDS atomics; 32 KB per group, 128 KB for four groups,
+// which is why a wave cannot have a histogram of its own at this occupancy); the per-lane member lists of sweeps
+// 2 and 3 hold one tile's worth of entries (16) and are emptied after every tile that added one.  All waves of
+// the workgroup meet at barriers around every scan, so the phases are uniform over the workgroup.
+//
+// A threshold inside the open-ended last coarse bin (candidates 15.875 or more below the row maximum) is not
+// taken as "keep everything": the workgroup repeats sweep 1 with the reference lowered by 15.875 for the queries
+// concerned -- the mass above that bin is already known, the bin's members are spread over 128 new coarse bins --
+// until the threshold bin is an ordinary one (or 24 rounds, about 380 score units, are used up).
+constexpr int kSelThreads = 512;
+constexpr float kSelLumpT = 15.875f;               // (kSelBins - 1) / 8: where the open-ended bin starts
+constexpr double kSelLumpScale = 7843180.797657975;   // exp(15.875)
+constexpr int kSelMaxRounds = 24;
+
 template <int KS>
-__global__ __launch_bounds__(kPfThreads, 1) void prefill_select_kernel(const PrefillArgs a) {
-  constexpr int kSelQ = 32 * (kPfThreads / 64) / KS;               // queries per workgroup
-  __shared__ double hist_all[kPfThreads / 64][kSelBins][32];       // 128 KB
-  __shared__ float list_all[kPfThreads / 64][kSelListCap][64];     // per-lane member lists of sweeps 2 and 3
-  __shared__ float max_all[kPfThreads / 64][32];                   // sweep 0: the waves' row maxima
+__global__ __launch_bounds__(kSelThreads, 2) void prefill_select_kernel(const PrefillArgs a) {
+  constexpr int NW = kSelThreads / 64;                             // waves per workgroup
+  constexpr int NG = NW / KS;                                      // query groups per workgroup
+  constexpr int kSelQ = 32 * NG;                                   // queries per workgroup
+  static_assert(NG >= 1 && NG <= 4, "at most four histograms fit");
+  __shared__ double hist_all[NG][kSelBins][32];                    // 32 KB per group
+  __shared__ float list_all[NW][kSelListCap][64];                  // per-lane member lists of sweeps 2 and 3 (32 KB)
+  float (*max_all)[32] = reinterpret_cast<float (*)[32]>(&list_all[0][0][0]);   // sweep 0: the waves' row maxima
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int g = lane >> 5, r = lane & 31;
   // Workgroups go round-robin over the chip's 8 dies, each with its own L2.  The 1-D grid is decoded so
@@ -407,12 +423,11 @@ __global__ __launch_bounds__(kPfThreads, 1) void prefill_select_kernel(const Pre
     j = blockIdx.x % a.n_heads;
     qtile = blockIdx.x / a.n_heads;
   }
-  if (qtile >= n_qtiles) return;
+  if (qtile >= n_qtiles) return;                                   // (the whole workgroup)
   const int t0 = (n_qtiles - 1 - qtile) * kSelQ;                   // long rows first
   const int qgroup = wave / KS, part = wave - qgroup * KS;         // this wave's queries and its share of their keys
   const int tw = t0 + qgroup * 32;                                 // first query of the group
-  const bool idle = tw >= a.n_q;                                   // no query in this group
-  if (KS == 1 && idle) return;                                     // (with KS > 1 the wave still goes to the barriers)
+  const bool idle = tw >= a.n_q;                                   // no query in this group (the wave still goes to the barriers)
   const int pos0 = (int)a.q_start_host;
   const int t = tw + r;
   const bool qok = t < a.n_q;
@@ -428,17 +443,19 @@ __global__ __launch_bounds__(kPfThreads, 1) void prefill_select_kernel(const Pre
   const bool wave_partial = tw + 32 > a.n_q;
   const int n_tiles = idle ? 0 : m_wave_hi / 32 + 1;
   const int n_interior = (wave_partial || idle) ? 0 : (m_wave_lo + 1) / 32;  // tiles with nb + 31 <= m_wave_lo
-  double (*hist)[32] = hist_all[wave];
+  double (*hist)[32] = hist_all[qgroup];
   float (*lst)[64] = list_all[wave];
   int lcnt = 0;                     // entries in this lane's member list
+  const uint32_t lst_base = (uint32_t)(size_t)(__attribute__((address_space(3))) float*)&lst[0][lane];
 
   auto load_k = [&](int tile) {
     const int nrow = min(tile * 32 + r, n_rows - 1);               // rows past the chunk are causally masked anyway
     return *reinterpret_cast<const u32x4*>(kIg + (int64_t)nrow * kIndexDim + g * 8);
   };
+  // the group's waves clear their histogram together (followed by a barrier at the call sites)
   auto zero_hist = [&]() {
     double* h = &hist[0][0];
-    for (int i = lane; i < kSelBins * 32; i += 64) h[i] = 0.0;
+    for (int i = part * 64 + lane; i < kSelBins * 32; i += KS * 64) h[i] = 0.0;
   };
   // One candidate's mass into bin `bin` of this lane's query.
   auto add_mass = [&](int bin, float tt) {
@@ -446,15 +463,15 @@ __global__ __launch_bounds__(kPfThreads, 1) void prefill_select_kernel(const Pre
     atomicAdd(&hist[bin][r], (double)wgt);
   };
 
-  float selM = ninf;
+  float selM = ninf;                // the query's reference: its row maximum, lowered by 15.875 per repeat of sweep 1
   float selM8 = ninf;               // 8 * selM and 8 * index_scale for sweep 1
   const float cs8 = cs * 8.0f;
   float x_lo = ninf, x_top = pinf;  // sweeps 2, 3: members of the prefix have x_lo <= x <= x_top
   int shift = 0;
-  float mxs[4] = {ninf, ninf, ninf, ninf};
+  float mxs[kSelMfma];
+#pragma unroll
+  for (int u = 0; u < kSelMfma; ++u) mxs[u] = ninf;
 
-  // One sweep over the index keys; PH is std::integral_constant<int, phase>, EDGE says whether the tiles
-  // [tile_begin, tile_end) need the causal mask.
   // Weighs the listed members of every lane: lane-private lists, so the only cross-lane step is the
   // loop bound.
   auto drain_list = [&]() {
@@ -467,7 +484,9 @@ __global__ __launch_bounds__(kPfThreads, 1) void prefill_select_kernel(const Pre
     lcnt = 0;
   };
 
-  // What one tile contributes in phase PH: SI = its 32 x 32 index products, nb = its first key.
+  // What one tile contributes in phase PH (0: maximum, 1: all candidates, 4: the candidates at or below the
+  // lowered reference of a repeated sweep 1, 2 / 3: members of the digit prefix): SI = its 32 x 32 index
+  // products, nb = its first key.
   auto tile_work = [&](auto PH, auto EDGE, const f32x16& SI, int nb, float& mxacc) {
     constexpr int phase = decltype(PH)::value;
     constexpr bool edge = decltype(EDGE)::value;
@@ -484,14 +503,17 @@ __global__ __launch_bounds__(kPfThreads, 1) void prefill_select_kernel(const Pre
 #pragma unroll
         for (int i = 0; i < st; ++i) v[i] = fmaxf(v[i], v[i + st]);
       mxacc = fmaxf(mxacc, v[0]);
-    } else if (phase == 1) {
+    } else if (phase == 1 || phase == 4) {
 #pragma unroll
       for (int i = 0; i < 16; ++i) {
         const int n = nb + (i >> 2) * 8 + g * 4 + (i & 3);
-        if (!edge || (qok && n <= m)) {
-          // 8 * (M - x * scale) straight from 8 M and 8 * scale: scaling by a power of two commutes with both
-          // roundings, so this IS 8 * sel_t(M, x, scale), one multiplication less per pair
-          const float tt8 = sel_t(selM8, SI[i], cs8);
+        // 8 * (M - x * scale) straight from 8 M and 8 * scale: scaling by a power of two commutes with both
+        // roundings, so this IS 8 * sel_t(M, x, scale), one multiplication less per pair
+        const float tt8 = sel_t(selM8, SI[i], cs8);
+        // a repeated sweep takes the candidates at or below the lowered reference only (the others were
+        // counted above the open-ended bin); a query that does not repeat has reference -inf and takes none
+        const bool cand = (!edge || (qok && n <= m)) && (phase == 1 || tt8 >= 0.f);
+        if (cand) {
           // first digit of q: floor(min(tt * 2^17, 2^21 - 1)) >> 14 == floor(min(tt * 8, (2^21 - 1) / 2^14))
           const int bin = (int)fminf(tt8, 127.99993896484375f);
           // exp(s - M) = exp2(tt * -log2(e)); the constant carries the 1/8, again exactly
@@ -500,7 +522,7 @@ __global__ __launch_bounds__(kPfThreads, 1) void prefill_select_kernel(const Pre
       }
     } else {
       // Members of the digit prefix (about one pair in a hundred in sweep 2, one in ten thousand in
-      // sweep 3) are only noted here -- their raw product goes to the lane's list -- and weighed later
+      // sweep 3) are only noted here -- their raw product goes to the lane's list -- and weighed
       // with all lanes busy (drain_list); weighing them where they turn up would run the exponential
       // and the atomic for one or two active lanes at a time.
       // Membership x_lo <= x <= x_top is one median and one comparison on the vector ALU (going through
@@ -514,18 +536,27 @@ __global__ __launch_bounds__(kPfThreads, 1) void prefill_select_kernel(const Pre
       };
       bool go = true;
       if (phase == 3) {
-        int c = 0;
+        // does any lane have a member in this tile?  The comparisons' lane masks are OR-ed on the scalar side
+        // (no vector instruction beyond the median and the comparison per pair)
+        uint64_t any = 0;
 #pragma unroll
-        for (int i = 0; i < 16; ++i) c += member(i) ? 1 : 0;
-        go = __ballot(c != 0) != 0ull;
+        for (int i = 0; i < 16; ++i) any |= __ballot(member(i));
+        go = any != 0ull;
       }
       if (go) {
+        // The list holds 16 entries per lane; a half tile adds at most 8, so it is emptied when some lane holds
+        // more than 8 before a half tile starts.  The list's end travels as an LDS address.
 #pragma unroll
-        for (int i = 0; i < 16; ++i) {
-          lst[lcnt][lane] = SI[i];
-          lcnt += member(i) ? 1 : 0;
+        for (int hf = 0; hf < 2; ++hf) {
+          if (__ballot(lcnt > kSelListCap - 8) != 0ull) drain_list();
+          uint32_t end = lst_base + (uint32_t)lcnt * 256u;
+#pragma unroll
+          for (int i = hf * 8; i < hf * 8 + 8; ++i) {
+            *reinterpret_cast<float __attribute__((address_space(3)))*>(end) = SI[i];
+            end += member(i) ? 256u : 0u;
+          }
+          lcnt = (int)((end - lst_base) >> 8);
         }
-        if (__ballot(lcnt > kSelListCap - 16) != 0ull) drain_list();
       }
     }
   };
@@ -545,19 +576,19 @@ __global__ __launch_bounds__(kPfThreads, 1) void prefill_select_kernel(const Pre
     }
     auto group = [&](u32x4 (&ring)[kSelRing], int first) {
 #pragma unroll
-      for (int hb = 0; hb < kSelRing; hb += 4) {                   // four MFMAs in flight at a time
-        f32x16 SI[4];
+      for (int hb = 0; hb < kSelRing; hb += kSelMfma) {            // kSelMfma MFMAs in flight at a time
+        f32x16 SI[kSelMfma];
 #pragma unroll
-        for (int u = 0; u < 4; ++u) {
+        for (int u = 0; u < kSelMfma; ++u) {
 #pragma unroll
           for (int i = 0; i < 16; ++i) SI[u][i] = 0.f;
           SI[u] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, ring[hb + u]),
                                                           __builtin_bit_cast(bf16x8, qIreg), SI[u], 0, 0, 0);
         }
 #pragma unroll
-        for (int u = 0; u < 4; ++u) ring[hb + u] = load_k(first + 2 * kSelRing + hb + u);
+        for (int u = 0; u < kSelMfma; ++u) ring[hb + u] = load_k(first + 2 * kSelRing + hb + u);
 #pragma unroll
-        for (int u = 0; u < 4; ++u) {
+        for (int u = 0; u < kSelMfma; ++u) {
           __builtin_amdgcn_sched_barrier(0);       // one tile at a time: hoisting four tiles' operands runs out of registers
           tile_work(PH, EDGE, SI[u], (first + hb + u) * 32, mxs[u]);
         }
@@ -577,83 +608,116 @@ __global__ __launch_bounds__(kPfThreads, 1) void prefill_select_kernel(const Pre
   auto sweep_all = [&](auto PH) {
     sweep(PH, std::false_type{}, plain_lo, plain_hi);
     if (part == KS - 1) sweep(PH, std::true_type{}, n_plain, n_tiles);
-    if (decltype(PH)::value >= 2) drain_list();
-  };
-  // bin i of this lane's query, summed over the group's waves (fixed order)
-  auto hist_sum = [&](int i) {
-    double v = hist_all[qgroup * KS][i][r];
-#pragma unroll
-    for (int k = 1; k < KS; ++k) v += hist_all[qgroup * KS + k][i][r];
-    return v;
+    if (decltype(PH)::value == 2 || decltype(PH)::value == 3) drain_list();
   };
 
   double Z = 0.0, above = 0.0;
   int prefix = 0;                 // digits of the threshold found so far
   float sel_mass = 1.f;
-  float cut = pinf;               // keep a candidate iff M - s < cut
-
-  zero_hist();
-#pragma unroll 1
-  for (int phase = 0; phase < 4; ++phase) {
-    shift = 7 * (3 - phase);                                       // phase 1: 14, phase 2: 7, phase 3: 0
-    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");         // zeroed bins before this sweep's atomics
-    selM8 = selM * 8.0f;                                           // (used by sweep 1; exact unless it overflows)
-    if (phase == 0) sweep_all(std::integral_constant<int, 0>{});
-    else if (phase == 1) sweep_all(std::integral_constant<int, 1>{});
-    else if (phase == 2) sweep_all(std::integral_constant<int, 2>{});
-    else sweep_all(std::integral_constant<int, 3>{});
-    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");         // the wave's atomics before the scan's loads
-    if (phase == 0) {
-      float mx = fmaxf(fmaxf(mxs[0], mxs[1]), fmaxf(mxs[2], mxs[3]));
-      mx = fmaxf(mx, __shfl_xor(mx, 32));
-      if (KS > 1) {
-        if (g == 0) max_all[wave][r] = mx;
-        __syncthreads();
-#pragma unroll
-        for (int k = 0; k < KS; ++k) mx = fmaxf(mx, max_all[qgroup * KS + k][r]);
-      }
-      selM = mx * cs;
-      continue;
-    }
-    if (KS > 1) __syncthreads();                                   // every wave of the group has added its masses
-    // ---- scan this query's bins from the top of the score range (bin 0) down; both lanes of the
-    // pair run the same scan on the same numbers ----
-    if (phase == 1) {
-      Z = 0.0;
-      for (int i = 0; i < kSelBins; ++i) Z += hist_sum(i);
-    }
-    const double target = (double)a.p * Z;
-    double cum = above, hsel = 0.0;
-    int bsel = kSelBins - 1;
+  float cut = pinf;               // keep a candidate iff reference - s < cut
+  double cum = 0.0, hsel = 0.0;
+  int bsel = kSelBins - 1;
+  // this query's bins from the top of the score range (bin 0) down; both lanes of the pair and every wave of
+  // the group run the same scan on the same numbers
+  auto scan = [&](double target) {
+    cum = above;
+    hsel = 0.0;
+    bsel = kSelBins - 1;
     bool found = false;
     for (int i = 0; i < kSelBins; ++i) {
-      const double hv = hist_sum(i);
+      const double hv = hist[i][r];
       if (!found) {
         if (cum + hv >= target) { bsel = i; hsel = hv; found = true; }
         else cum += hv;
       }
     }
+  };
+
+  // ---- sweep 0: the row maxima ----
+  sweep_all(std::integral_constant<int, 0>{});
+  {
+    float mx = mxs[0];
+#pragma unroll
+    for (int u = 1; u < kSelMfma; ++u) mx = fmaxf(mx, mxs[u]);
+    mx = fmaxf(mx, __shfl_xor(mx, 32));
+    if (g == 0) max_all[wave][r] = mx;
+    zero_hist();
+    __syncthreads();
+#pragma unroll
+    for (int k = 0; k < KS; ++k) mx = fmaxf(mx, max_all[qgroup * KS + k][r]);
+    selM = mx * cs;
+  }
+  __syncthreads();                                                  // the maxima are read: the lists' memory is free again
+
+  // ---- sweep 1: the first digit; repeated with a lowered reference while some query's threshold lies in the
+  // open-ended bin ----
+  bool repeat_me = false, rebased = false;
+  for (int round = 0; round < kSelMaxRounds; ++round) {
+    selM8 = (round == 0 || repeat_me) ? selM * 8.0f : ninf;         // (exact unless it overflows)
+    if (round == 0) sweep_all(std::integral_constant<int, 1>{});
+    else sweep_all(std::integral_constant<int, 4>{});
+    __syncthreads();                                                // every wave of the group has added its masses
+    if (round == 0) {
+      Z = 0.0;
+      for (int i = 0; i < kSelBins; ++i) Z += hist[i][r];
+    }
+    if (round == 0 || repeat_me) scan((double)a.p * Z);
+    // the threshold in the open-ended bin: everything above it is counted (cum), its members go round again
+    repeat_me = (round == 0 || repeat_me) && !idle && qok && bsel == kSelBins - 1 && hsel > 0.0 && round + 1 < kSelMaxRounds;
+    // does any query of the workgroup repeat?  (flags in the lists' memory, idle in this phase; the barrier also
+    // says that every wave has read the histograms)
+    int* flags = reinterpret_cast<int*>(&list_all[0][0][0]);
+    const bool mine = __ballot(repeat_me) != 0ull;
+    if (lane == 0) flags[wave] = mine ? 1 : 0;
+    __syncthreads();
+    int any = 0;
+#pragma unroll
+    for (int w = 0; w < NW; ++w) any |= flags[w];
+    if (!any) break;
+    if (repeat_me) {
+      rebased = true;
+      selM -= kSelLumpT;
+      Z *= kSelLumpScale;
+      above = cum * kSelLumpScale;
+    }
+    zero_hist();
+    __syncthreads();
+  }
+  prefix = bsel;
+  above = cum;
+
+  // ---- sweeps 2 and 3: the second and third digit among the members of the prefix ----
+#pragma unroll 1
+  for (int phase = 2; phase < 4; ++phase) {
+    // members of the prefix: prefix << shift <= q < (prefix + 1) << shift; for the non-negative
+    // tt = M - s of a candidate that is qlo / 2^17 <= tt < qhi / 2^17 (the last bin is open-ended),
+    // and in terms of the raw product x: first x with tt < hi bound <= x < first x with tt < lo bound
+    shift = 7 * (4 - phase);                                        // of the prefix found so far: 14, then 7
+    const int qlo = prefix << shift, qhi = (prefix + 1) << shift;
+    const float lo_t = (float)qlo * (1.0f / kSelScale);
+    const float hi_t = qhi > kSelQMax ? pinf : (float)qhi * (1.0f / kSelScale);
+    x_lo = sel_first_below(selM, cs, hi_t);
+    // the largest x that is still a member: the float just below the first x with tt < lo bound
+    x_top = key_float(float_key(sel_first_below(selM, cs, lo_t)) - 1u);
+    // the very first range of a reference that is the row maximum is open upwards: t of the maximum itself is the
+    // rounding error of M = max * scale and may be a hair below zero (a lowered reference keeps its bound:
+    // what lies above it has been counted)
+    if (qlo == 0 && !rebased) x_top = pinf;
+    shift -= 7;                                                     // of this sweep's digit: 7, then 0
+    zero_hist();
+    __syncthreads();
+    if (phase == 2) sweep_all(std::integral_constant<int, 2>{});
+    else sweep_all(std::integral_constant<int, 3>{});
+    __syncthreads();
+    scan((double)a.p * Z);
     prefix = (prefix << 7) | bsel;
     above = cum;
-    if (phase < 3) {
-      // members of the prefix: prefix << shift <= q < (prefix + 1) << shift; for the non-negative
-      // tt = M - s of a candidate that is qlo / 2^17 <= tt < qhi / 2^17 (the last bin is open-ended),
-      // and in terms of the raw product x: first x with tt < hi bound <= x < first x with tt < lo bound
-      const int qlo = prefix << shift, qhi = (prefix + 1) << shift;
-      const float lo_t = (float)qlo * (1.0f / kSelScale);
-      const float hi_t = qhi > kSelQMax ? pinf : (float)qhi * (1.0f / kSelScale);
-      x_lo = sel_first_below(selM, cs, hi_t);
-      // the largest x that is still a member: the float just below the first x with tt < lo bound
-      x_top = key_float(float_key(sel_first_below(selM, cs, lo_t)) - 1u);
-      if (KS > 1) __syncthreads();                                 // every wave of the group has read the histograms
-      zero_hist();
-    } else {
-      // a threshold inside the open-ended last coarse bin keeps every candidate
-      const bool lump = (prefix >> 14) == kSelBins - 1;
-      cut = lump ? pinf : (float)(prefix + 1) * (1.0f / kSelScale);
-      sel_mass = (lump || !(Z > 0.0)) ? 1.f : (float)((cum + hsel) / Z);
-    }
+    __syncthreads();                                                // every wave has read the histograms
   }
+  // a threshold inside the open-ended last coarse bin (only after the last repeat) keeps every candidate
+  const bool lump = (prefix >> 14) == kSelBins - 1;
+  cut = lump ? pinf : (float)(prefix + 1) * (1.0f / kSelScale);
+  sel_mass = (lump || !(Z > 0.0)) ? 1.f : (float)((cum + hsel) / Z);
   if (!qok || g != 0 || part != 0) return;
   const int64_t o = (int64_t)j * a.n_q + t;
   a.sel_thr[o] = sel_first_below(selM, cs, cut);
@@ -1517,19 +1581,19 @@ extern "C" int32_t rtp_sparse_attn_prefill(const rtp_layer_desc* layer, const vo
   a.part = (float*)((char*)ws + proj_bytes + state_bytes);
   a.n_splits = choose_splits(layer->n_ret, T, chunk_start);
   if (p < 1.f) {
-    // waves per 32-query group: as many as it takes to give each of the chip's 1024 SIMDs a wave
+    // waves per 32-query group: as many as it takes to give each of the chip's 1024 SIMDs two waves
     const int64_t groups = (int64_t)a.n_heads * ((T + 31) / 32);
-    const int ks = groups > 512 ? 1 : groups > 256 ? 2 : 4;
-    const unsigned n_qtiles = (unsigned)((T + 128 / ks - 1) / (128 / ks));
+    const int ks = groups > 512 ? 2 : groups > 256 ? 4 : 8;
+    const unsigned n_qtiles = (unsigned)((T + 256 / ks - 1) / (256 / ks));
     // 1-D grid, padded so that every die gets whole (head, query tile) columns (see the kernel's decoding)
     unsigned wgs = (unsigned)a.n_heads * n_qtiles;
     if (a.n_heads <= 8 && 8 % a.n_heads == 0) {
       const unsigned per_head = 8u / (unsigned)a.n_heads;
       wgs = 8u * ((n_qtiles + per_head - 1) / per_head);
     }
-    if (ks == 1) RTP_LAUNCH(prefill_select_kernel<1>, dim3(wgs), dim3(kPfThreads), 0, (hipStream_t)stream, a);
-    else if (ks == 2) RTP_LAUNCH(prefill_select_kernel<2>, dim3(wgs), dim3(kPfThreads), 0, (hipStream_t)stream, a);
-    else RTP_LAUNCH(prefill_select_kernel<4>, dim3(wgs), dim3(kPfThreads), 0, (hipStream_t)stream, a);
+    if (ks == 2) RTP_LAUNCH(prefill_select_kernel<2>, dim3(wgs), dim3(kSelThreads), 0, (hipStream_t)stream, a);
+    else if (ks == 4) RTP_LAUNCH(prefill_select_kernel<4>, dim3(wgs), dim3(kSelThreads), 0, (hipStream_t)stream, a);
+    else RTP_LAUNCH(prefill_select_kernel<8>, dim3(wgs), dim3(kSelThreads), 0, (hipStream_t)stream, a);
   }
   dim3 grid((unsigned)a.n_heads, (unsigned)((T + kPwQ - 1) / kPwQ), (unsigned)a.n_splits);
   if (a.f16) RTP_LAUNCH((flash_prefill_wide_kernel<kModeSparse, 1, true>), grid, dim3(512), 0, (hipStream_t)stream, a);

@@ -147,6 +147,21 @@ def reported_sets(s: np.ndarray, tau_rep: float, count_rep: int, band: float, wh
                 yield np.sort(np.concatenate([certain, np.asarray(extra, dtype=np.int64)]))
 
 
+MASS_EPS = 3e-7      # the library's weights are fp32 exponentials (relative error up to 2^-22 each), summed in fp64
+
+
+def count_range(s: np.ndarray, p: float):
+    """Sizes of the top-p set of scores `s` that fp32 weights can justify: from the smallest set whose fp64 mass
+    reaches p - MASS_EPS to the smallest whose mass reaches p + MASS_EPS.  For ordinary p and set sizes the two
+    coincide with the exact count; they part when single tokens weigh less than the rounding of the heaviest ones
+    (p within 1e-5 of 1 on peaked rows)."""
+    w = np.exp(s - s.max())
+    cum = np.cumsum(np.sort(w)[::-1]) / w.sum()
+    lo = int(np.searchsorted(cum, p - MASS_EPS, side="left")) + 1
+    hi = int(np.searchsorted(cum, min(p + MASS_EPS, cum[-1]), side="left")) + 1
+    return min(lo, len(s)), min(hi, len(s))
+
+
 def check_out_any(o_gpu: np.ndarray, candidates, attend_fn, what="", attend_abs_fn=None):
     """o_gpu must match attend_fn(ids) for one of the candidate sets (the first is the expected one): to the
     stated bar, and to the rounding budget of the prefill kernels, which round every probability to bf16 before the

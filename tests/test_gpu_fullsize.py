@@ -9,7 +9,7 @@ import torch
 from oracle import rtp_oracle as orc
 from paper_2605_16928_amd import rtp, workloads as wl
 from gpu_util import (DEV, DecodeRun, PrefillRun, check_scores, check_selection, check_selection_valid, check_out,
-                      check_out_any, reported_sets)
+                      check_out_any, reported_sets, count_range)
 
 pytestmark = pytest.mark.gpu
 SC = 1.0 / np.sqrt(128.0)
@@ -197,7 +197,8 @@ def _prefill_fullsize(w, rows_local, rows_ret, rows_dense, what):
                       f"{what} sparse t{t} h{h}", att_abs)
         near = np.abs(s - ref["tau"]) <= 1e-5 * max(1.0, abs(ref["tau"]))
         if near.sum() <= 1:
-            assert int(cnt[j, t]) == ref["count"], f"{what} t{t} h{h}: set differs from exact top-p"
+            k_lo, k_hi = count_range(s, p32)
+            assert k_lo <= int(cnt[j, t]) <= k_hi, f"{what} t{t} h{h}: set differs from exact top-p"
         kept.append(int(keep.sum()))
     if rows_dense:
         dout = torch.zeros_like(run.out)

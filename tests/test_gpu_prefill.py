@@ -6,7 +6,7 @@ import torch
 
 from oracle import rtp_oracle as orc
 from paper_2605_16928_amd import rtp, workloads as wl
-from gpu_util import (DEV, PrefillRun, prefill_oracle_inputs, check_out, check_out_any, reported_sets, i32, i64,
+from gpu_util import (DEV, PrefillRun, prefill_oracle_inputs, check_out, check_out_any, reported_sets, count_range, i32, i64,
                       layer_desc_of, ws_alloc)
 
 pytestmark = pytest.mark.gpu
@@ -262,8 +262,11 @@ def _check_sparse_prefill(w, name, p):
         # exact threshold may legitimately differ; rows that have such a token are only held to (d).
         near = np.abs(s - r["sel"]["tau"]) <= 1e-5 * max(1.0, abs(r["sel"]["tau"]))
         if near.sum() <= 1:
-            assert int(cnt[j, t]) == r["sel"]["count"], f"{name} t{t} h{h}: set differs"
-            check_out(out[t, h], r["out"], f"{name} t{t} h{h} (exact top-p)", tight=False)
+            k_lo, k_hi = count_range(s, p32)
+            assert k_lo <= int(cnt[j, t]) <= k_hi, f"{name} t{t} h{h}: set differs ({cnt[j, t]} kept, exact {r['sel']['count']})"
+            if k_lo == k_hi:
+                assert int(cnt[j, t]) == r["sel"]["count"]
+                check_out(out[t, h], r["out"], f"{name} t{t} h{h} (exact top-p)", tight=False)
     for h in range(L.n_q_heads):
         if h not in L.ret_heads:
             assert np.all(out[:, h] == 5.0)
@@ -320,3 +323,27 @@ def test_retrieval_dense_split_keys_matches_unsplit():
         check_out(ga[r["t"], 1], r["out"], "split", tight="mfma")
         check_out(gb[r["t"], 1], r["out"], "unsplit", tight="mfma")
         assert abs(la[r["t"], 1].item() - r["lse"]) < 3e-3 and abs(lb[r["t"], 1].item() - r["lse"]) < 3e-3
+
+
+@pytest.mark.parametrize("scale,p", [(2.0, 0.999999), (2.5, 0.9999999), (3.0, 0.999999)])
+def test_sparse_prefill_threshold_far_below_the_row_maximum(scale, p):
+    """Score rows whose bulk lies 13 to 22 below the row maximum, with p so close to 1 that the threshold falls
+    into that bulk: the search's first digit covers 15.875 below its reference, so it must lower the reference
+    and repeat for such queries instead of keeping every candidate (fp32 p cannot push a threshold much deeper
+    than that at these lengths; every repeat runs the same code).  Checked like every
+    other case: exact sets away from the threshold band, counts, masses, attention over the kept set."""
+    print(f"[case] sparse prefill, threshold far below the maximum, scale {scale} p {p}", flush=True)
+    w = wl.small_prefill("cpu", p=p, chunk_start=2500, T=96, seed=97)
+    w.layer.index_scale = scale
+    w = w.to(DEV)
+    cnt = _check_sparse_prefill(w, f"far_{scale}", p)
+    # the case does what it is meant to: for most queries the threshold lies more than 15.875 below the maximum,
+    # and the kept set is neither tiny nor the whole candidate set
+    run = PrefillRun(w)
+    run.sparse_prefill()
+    torch.cuda.synchronize()
+    oi = prefill_oracle_inputs(w)
+    ref = orc.prefill_rows(rows=[(t, w.layer.ret_heads[0]) for t in range(0, w.T, 8)], p=float(np.float32(p)), **oi)
+    deep = [r["sel"]["smax"] - r["sel"]["tau"] for r in ref]
+    assert max(deep) > 15.875 and (scale > 2.75 or np.median(deep) > 15.875), deep
+    assert all(r["sel"]["count"] < r["m"] + 1 for r in ref)
