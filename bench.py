@@ -493,7 +493,39 @@ def main() -> int:
     if not args.no_prefill:
         from paper_2605_16928_amd.pipeline import PrefillRun
         MFMA_PEAK = 2.5e15
-        SELECT_SWEEPS = 4            # passes of the threshold search over the index keys
+
+        def ret_dense(pr, w):
+            """The paper's prefill rule for the retrieval heads: dense causal attention, no statistics asked for."""
+            rtp.rtp_sparse_attn_prefill(pr.desc, w.qI, w.q, None, w.kI, w.N * 16, pr.Kp, pr.Vp, pr.rs, pr.hs,
+                                        w.chunk_start, w.T, 1.0, pr.out, None, None, None, None, pr.ws)
+
+        def topp_account(pr, w, t_topp):
+            """What the top-p prefill rule needs against what it issues on the matrix cores, for the call just
+            timed (t_topp us): flop the method needs = 512 per KEPT (query, key) pair; the attention launch issues
+            512 + 32 (keep test) per pair of every 64-key tile it visits (whole 256 x 64 tiles, masked part
+            included); the threshold search issues 32 per causal pair in each of its first two sweeps and in the
+            stretches of the last two that it does not skip (not counted: between 2 and 4 sweeps)."""
+            Lp = w.layer
+            kept_pairs = int(pr.count.to(torch.int64).sum().item())
+            visited, causal = pr.tile_stats()
+            rtp.rtp_profile_start(16)
+            pr.sparse_prefill()
+            torch.cuda.synchronize()
+            by_kernel = {}
+            for name, us in rtp.rtp_profile_stop():
+                by_kernel[name.split("<")[0]] = by_kernel.get(name.split("<")[0], 0.0) + us
+            return {
+                "topp_kept_tokens_mean": round(float(pr.count.float().mean()), 1),
+                "topp_kept_tokens_median": float(pr.count.float().median()),
+                "topp_kept_pairs": kept_pairs,
+                "topp_tiles_visited_frac": round(visited / max(causal, 1), 5),
+                "topp_useful_flop_frac": round(kept_pairs * 512 / (t_topp * 1e-6) / MFMA_PEAK, 6),
+                "topp_attention_issued_flop_frac": round(visited * 256 * 64 * (512 + 32) / (t_topp * 1e-6) / MFMA_PEAK, 4),
+                "topp_threshold_search_ms": round(by_kernel.get("prefill_select_kernel", 0.0) / 1e3, 3),
+                "topp_attention_ms": round((by_kernel.get("flash_prefill_wide_kernel", 0.0)
+                                            + by_kernel.get("prefill_combine_kernel", 0.0)) / 1e3, 3),
+            }
+
         def chunk_times(w, reps, dense_warm):
             pr = PrefillRun(w)
             Lp = w.layer
@@ -501,12 +533,8 @@ def main() -> int:
             pairs_dense = sum(w.chunk_start + t + 1 for t in range(w.T))
             pairs_local = sum(min(w.chunk_start + t + 1, Lp.sink + Lp.window) for t in range(w.T))
 
-            def ret_dense():
-                rtp.rtp_sparse_attn_prefill(pr.desc, w.qI, w.q, None, w.kI, w.N * 16, pr.Kp, pr.Vp, pr.rs, pr.hs,
-                                            w.chunk_start, w.T, 1.0, pr.out, None, None, None, None, pr.ws)
-
             t_local = timed(lambda i: pr.local_attn(), reps, 1)
-            t_ret = timed(lambda i: ret_dense(), reps, 1)
+            t_ret = timed(lambda i: ret_dense(pr, w), reps, 1)
             t_topp = timed(lambda i: pr.sparse_prefill(), reps, 1)
             t_dense = timed(lambda i: pr.dense_attn(), 1, dense_warm)
             res = {
@@ -515,17 +543,8 @@ def main() -> int:
                 "local_mfma_frac": round(n_loc * pairs_local * 512 / (t_local * 1e-6) / MFMA_PEAK, 4),
                 "retrieval_dense_mfma_frac": round(Lp.n_ret * pairs_dense * 512 / (t_ret * 1e-6) / MFMA_PEAK, 4),
                 "dense_mfma_frac": round(Lp.n_q_heads * pairs_dense * 512 / (t_dense * 1e-6) / MFMA_PEAK, 4),
-                "topp_kept_tokens_mean": round(float(pr.count.float().mean()), 1),
             }
-            # top-p rule: flop the method needs (512 per KEPT (query, key) pair) against flop the two launches issue on
-            # the matrix cores (attention: 512 + 32 for the keep test per causal pair the kernel visits; threshold
-            # search: 32 per causal pair and sweep), both as fractions of the bf16 MFMA peak over the rule's time
-            kept_pairs = int(pr.count.to(torch.int64).sum().item())
-            visited = Lp.n_ret * pairs_dense * float(getattr(pr, "visited_fraction", 1.0))
-            issued = visited * (512 + 32) + Lp.n_ret * pairs_dense * 32 * SELECT_SWEEPS
-            res["topp_useful_flop_frac"] = round(kept_pairs * 512 / (t_topp * 1e-6) / MFMA_PEAK, 5)
-            res["topp_issued_flop_frac"] = round(issued / (t_topp * 1e-6) / MFMA_PEAK, 4)
-            res["topp_kept_pairs"] = kept_pairs
+            res.update(topp_account(pr, w, t_topp))
             del pr
             torch.cuda.empty_cache()
             return res
@@ -548,8 +567,23 @@ def main() -> int:
                 round(last3["dense_all_heads_ms"] / (last3["local_ms"] + last3["retrieval_topp_ms"]), 2),
             "by_chunk": depth3,
         }
+        # the last chunk under the peaked indexer laws: where per-query top-p leaves most key tiles unvisited
+        def law_times(law):
+            w = wl.c4_chunk(dev, chunk=127, law=law)
+            pr = PrefillRun(w)
+            t_ret = timed(lambda i: ret_dense(pr, w), 2, 1)
+            t_topp = timed(lambda i: pr.sparse_prefill(), 3, 1)
+            res = {"retrieval_dense_ms": round(t_ret / 1e3, 3), "retrieval_topp_ms": round(t_topp / 1e3, 3),
+                   "topp_speedup_vs_retrieval_dense": round(t_ret / t_topp, 2)}
+            res.update(topp_account(pr, w, t_topp))
+            del pr, w
+            torch.cuda.empty_cache()
+            return res
+        by_law = {law: law_times(law) for law in ("peaked", "peaked_hard")}
         T8 = 8192
         last = depth[127]
+        by_law["broad"] = {k: last[k] for k in by_law["peaked"] if k in last}
+        by_law["broad"]["topp_speedup_vs_retrieval_dense"] = round(last["retrieval_dense_ms"] / last["retrieval_topp_ms"], 2)
         # whole-sequence time: trapezoid over the five sampled depths, 128 chunks in total
         def integrate(key):
             cs = sorted(depth)
@@ -573,6 +607,7 @@ def main() -> int:
             "whole_sequence_tokens_per_s_dense": round((1 << 20) / (ms_dense * 1e-3), 1),
             "whole_sequence_speedup_vs_inhouse_dense_paper_rule": round(ms_dense / ms_paper, 2),
             "by_chunk": depth,
+            "last_chunk_by_indexer_law": by_law,
             "paper_context": "paper reports 9.36x prefill speedup over FlashAttention-2 at 1M on NVIDIA H20 with "
                              "retrieval heads dense (its prefill rule); relative only",
         }

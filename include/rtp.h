@@ -217,6 +217,18 @@ int32_t rtp_sparse_attn_prefill(const rtp_layer_desc* layer, const void* q_pre, 
                                 float* tau, int32_t* count, float* mass,
                                 void* ws, size_t ws_bytes, void* stream);
 
+/*
+ * How much of the causal key range the last rtp_sparse_attn_prefill call with p < 1 on this workspace visited
+ * (a measurement aid for the block-sparse prefill discussion of Sec. 3.4: the threshold search records the largest
+ * index score of every 32-query group in every 64-key tile, and the attention launch visits a tile only if some
+ * query of its 256-query tile can keep a key there).  layer, T and chunk_start as in that call; waits for `stream`,
+ * then writes two host values: tiles_visited (64-key tiles visited, summed over retrieval heads and 256-query
+ * tiles) and tiles_causal (what plain causal attention visits).  Allocates nothing on the device.
+ */
+int32_t rtp_sparse_attn_prefill_tile_stats(const rtp_layer_desc* layer, int32_t T, int64_t chunk_start,
+                                           const void* ws, size_t ws_bytes, void* stream,
+                                           int64_t* tiles_visited, int64_t* tiles_causal);
+
 /* ---------------------------------------------------------------------------------------------
  * (5) Sink + sliding-window attention for every NON-retrieval head -- Sec. 3.2 (first sentence),
  * Sec. 4.2 (the evaluated setting: sink = 4, window = 8192).

@@ -16,7 +16,9 @@
 // are adjacent in the grid so that they meet in L2; late (long) query tiles are scheduled first.
 #include "common.h"
 
+#include <algorithm>
 #include <type_traits>
+#include <vector>
 
 namespace rtp {
 
@@ -60,6 +62,11 @@ struct PrefillArgs {
   float* mass;
   float* sel_thr;               // [n_ret, n_q]: a candidate is kept iff its raw index product is >= this
   int32_t f16;                  // q, K, V and out are fp16 (else bf16)
+  // selecting mode: which key tiles can hold a kept pair at all
+  float* tile_max;              // [n_ret * ceil(n_q / 32), n_t64]: largest raw index product of a 32-query group in a 64-key tile
+  int32_t n_t64;                // row length of tile_max
+  int32_t* act_list;            // [n_ret, ceil(n_q / 256), n_t64]: the 64-key tiles a 256-query tile has to visit, ascending
+  int32_t* act_count;           // [n_ret, ceil(n_q / 256)]
 };
 
 enum { kModeDense = 0, kModeLocal = 1, kModeSparse = 2 };
@@ -382,12 +389,16 @@ __device__ __forceinline__ float sel_first_below(float M, float index_scale, flo
 }
 
 //
-// KS (2, 4 or 8) waves share one group of 32 queries and split its key range between them; a workgroup is eight
-// waves -- two per SIMD, so that one wave's vector instructions issue under the other's latencies -- i.e. 8 / KS
-// groups.  The waves of a group add into ONE histogram (LDS atomics; 32 KB per group, 128 KB for four groups,
-// which is why a wave cannot have a histogram of its own at this occupancy); the per-lane member lists of sweeps
-// 2 and 3 hold one tile's worth of entries (16) and are emptied after every tile that added one.  All waves of
-// the workgroup meet at barriers around every scan, so the phases are uniform over the workgroup.
+// KS waves share one group of 32 queries and split its key range between them; a workgroup is eight waves -- two
+// per SIMD, so that one wave's vector instructions issue under the other's latencies -- i.e. 8 / KS groups.  The
+// waves of a group add into ONE histogram (LDS atomics; 32 KB per group); the per-lane member lists of sweeps 2
+// and 3 hold one tile's worth of entries (16) and are emptied after every tile that added one.  All waves of the
+// workgroup meet at barriers around every scan, so the phases are uniform over the workgroup.
+// The library launches KS = 8, one group per workgroup: on score laws that keep thousands of tokens per query it
+// runs as fast as two or four groups per workgroup (25.6 ms against 25.7 and 25.6 on the last 8192-query chunk of
+// a 1,048,576-token context), and when a few queries of a chunk have their threshold deep in the background
+// while the others' sweeps 2 and 3 visit a handful of tiles, short workgroups in four times the number let the
+// dispatcher even the load out (19.0 ms against 24.1).
 //
 // A threshold inside the open-ended last coarse bin (candidates 15.875 or more below the row maximum) is not
 // taken as "keep everything": the workgroup repeats sweep 1 with the reference lowered by 15.875 for the queries
@@ -445,6 +456,15 @@ __global__ __launch_bounds__(kSelThreads, 2) void prefill_select_kernel(const Pr
   const int n_interior = (wave_partial || idle) ? 0 : (m_wave_lo + 1) / 32;  // tiles with nb + 31 <= m_wave_lo
   double (*hist)[32] = hist_all[qgroup];
   float (*lst)[64] = list_all[wave];
+  // this group's row of the tile-maximum table: written in sweep 0 (one entry per pair of key tiles, i.e. per 64
+  // keys), read in sweeps 2 and 3, whose members all lie at or above x_lo -- a tile pair whose maximum is below
+  // every query's x_lo holds none.  Sweep 3 replaces the entries of the pairs it visits by +inf (some query of
+  // the group has a product at or above its own x_lo there, so it may keep a key) or -inf (none can); the pairs
+  // it skips keep a maximum below every x_lo.  The attention launch's tile lists are built from the result.
+  float* tmx = a.tile_max + ((int64_t)j * ((a.n_q + 31) / 32) + (idle ? 0 : tw / 32)) * a.n_t64;
+  float xlo_wave = ninf;            // smallest x_lo over the wave's queries
+  float xlo_wave_top = ninf;        // and the largest
+  bool reach_known = false;         // sweep 3: the tile in hand is certain to hold a product at or above its query's x_lo
   int lcnt = 0;                     // entries in this lane's member list
   const uint32_t lst_base = (uint32_t)(size_t)(__attribute__((address_space(3))) float*)&lst[0][lane];
 
@@ -487,7 +507,7 @@ __global__ __launch_bounds__(kSelThreads, 2) void prefill_select_kernel(const Pr
   // What one tile contributes in phase PH (0: maximum, 1: all candidates, 4: the candidates at or below the
   // lowered reference of a repeated sweep 1, 2 / 3: members of the digit prefix): SI = its 32 x 32 index
   // products, nb = its first key.
-  auto tile_work = [&](auto PH, auto EDGE, const f32x16& SI, int nb, float& mxacc) {
+  auto tile_work = [&](auto PH, auto EDGE, const f32x16& SI, int nb, float& mxacc) -> float {
     constexpr int phase = decltype(PH)::value;
     constexpr bool edge = decltype(EDGE)::value;
     if (phase == 0) {
@@ -503,6 +523,7 @@ __global__ __launch_bounds__(kSelThreads, 2) void prefill_select_kernel(const Pr
 #pragma unroll
         for (int i = 0; i < st; ++i) v[i] = fmaxf(v[i], v[i + st]);
       mxacc = fmaxf(mxacc, v[0]);
+      return v[0];
     } else if (phase == 1 || phase == 4) {
 #pragma unroll
       for (int i = 0; i < 16; ++i) {
@@ -535,6 +556,7 @@ __global__ __launch_bounds__(kSelThreads, 2) void prefill_select_kernel(const Pr
         return edge ? (in && qok && n <= m) : in;
       };
       bool go = true;
+      float reach = 0.f;
       if (phase == 3) {
         // does any lane have a member in this tile?  The comparisons' lane masks are OR-ed on the scalar side
         // (no vector instruction beyond the median and the comparison per pair)
@@ -542,6 +564,21 @@ __global__ __launch_bounds__(kSelThreads, 2) void prefill_select_kernel(const Pr
 #pragma unroll
         for (int i = 0; i < 16; ++i) any |= __ballot(member(i));
         go = any != 0ull;
+        // can some query of the wave keep a key of this tile?  Its final threshold is at or above x_lo, so a
+        // tile whose largest visible product is below x_lo for every query holds no kept pair
+        reach = 1.f;
+        if (!reach_known) {
+        float v[16];
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+          const int n = nb + (i >> 2) * 8 + g * 4 + (i & 3);
+          v[i] = (!edge || (qok && n <= m)) ? SI[i] : ninf;
+        }
+        const float top = fmaxf(fmaxf(fmaxf(fmaxf(v[0], v[1]), v[2]), fmaxf(fmaxf(v[3], v[4]), v[5])),
+                                fmaxf(fmaxf(fmaxf(fmaxf(v[6], v[7]), v[8]), fmaxf(fmaxf(v[9], v[10]), v[11])),
+                                      fmaxf(fmaxf(fmaxf(v[12], v[13]), v[14]), v[15])));
+        reach = __ballot(top >= x_lo) != 0ull ? 1.f : 0.f;
+        }
       }
       if (go) {
         // The list holds 16 entries per lane; a half tile adds at most 8, so it is emptied when some lane holds
@@ -558,7 +595,9 @@ __global__ __launch_bounds__(kSelThreads, 2) void prefill_select_kernel(const Pr
           lcnt = (int)((end - lst_base) >> 8);
         }
       }
+      return reach;
     }
+    return 0.f;
   };
 
   // One sweep over the tiles [tile_begin, tile_end) in rounds of 2 * kSelRing: two groups of index-key
@@ -568,15 +607,40 @@ __global__ __launch_bounds__(kSelThreads, 2) void prefill_select_kernel(const Pr
   // rounds, and in the edge range a tile past the last one holds only keys n > m, which the causal mask drops.
   auto sweep = [&](auto PH, auto EDGE, int tile_begin, int tile_end) {
     if (tile_begin >= tile_end) return;
+    constexpr int phase_ = decltype(PH)::value;
+    constexpr bool kSkip = phase_ == 2 || phase_ == 3;
+    static_assert(kSelMfma == 2, "a batch of MFMAs is one 64-key tile of the maximum table");
     u32x4 ringA[kSelRing], ringB[kSelRing];
+    float tmA[kSelRing / 2], tmB[kSelRing / 2];                    // the table entries of the tile pairs in the rings
 #pragma unroll
     for (int u = 0; u < kSelRing; ++u) {
       ringA[u] = load_k(tile_begin + u);
       ringB[u] = load_k(tile_begin + kSelRing + u);
     }
-    auto group = [&](u32x4 (&ring)[kSelRing], int first) {
+    if (kSkip) {
+#pragma unroll
+      for (int u = 0; u < kSelRing / 2; ++u) {
+        tmA[u] = tmx[(tile_begin >> 1) + u];
+        tmB[u] = tmx[((tile_begin + kSelRing) >> 1) + u];
+      }
+    }
+    auto group = [&](u32x4 (&ring)[kSelRing], float (&tm)[kSelRing / 2], int first) {
 #pragma unroll
       for (int hb = 0; hb < kSelRing; hb += kSelMfma) {            // kSelMfma MFMAs in flight at a time
+        // no member possible in this pair of tiles: only the prefetches for two groups ahead are issued
+        bool skip = false;
+        if (kSkip) {
+          const float pair_max = __int_as_float(__builtin_amdgcn_readfirstlane(__float_as_int(tm[hb / 2])));
+          skip = pair_max < xlo_wave;
+          // a maximum at or above EVERY query's x_lo is at or above its own query's: no need to look
+          reach_known = pair_max >= xlo_wave_top;
+          tm[hb / 2] = tmx[((first + 2 * kSelRing + hb) >> 1)];
+        }
+        if (skip) {
+#pragma unroll
+          for (int u = 0; u < kSelMfma; ++u) ring[hb + u] = load_k(first + 2 * kSelRing + hb + u);
+          continue;
+        }
         f32x16 SI[kSelMfma];
 #pragma unroll
         for (int u = 0; u < kSelMfma; ++u) {
@@ -587,28 +651,84 @@ __global__ __launch_bounds__(kSelThreads, 2) void prefill_select_kernel(const Pr
         }
 #pragma unroll
         for (int u = 0; u < kSelMfma; ++u) ring[hb + u] = load_k(first + 2 * kSelRing + hb + u);
+        float tmax = ninf;
 #pragma unroll
         for (int u = 0; u < kSelMfma; ++u) {
           __builtin_amdgcn_sched_barrier(0);       // one tile at a time: hoisting four tiles' operands runs out of registers
-          tile_work(PH, EDGE, SI[u], (first + hb + u) * 32, mxs[u]);
+          tmax = fmaxf(tmax, tile_work(PH, EDGE, SI[u], (first + hb + u) * 32, mxs[u]));
         }
+        if (phase_ == 0) {                         // the pair's maximum over the wave's 32 queries x 64 keys
+          const float wm = wave_max_f32(tmax);
+          if (lane == 0) tmx[(first + hb) >> 1] = wm;
+        }
+        // the last sweep knows better than the maximum: can one of the wave's queries keep a key of the pair?
+        // (a pair known to reach keeps its maximum, which says the same)
+        if (phase_ == 3 && !reach_known && lane == 0) tmx[(first + hb) >> 1] = tmax > 0.f ? pinf : ninf;
         __builtin_amdgcn_sched_barrier(0);
       }
     };
 #pragma unroll 1
     for (int base = tile_begin; base < tile_end; base += 2 * kSelRing) {
-      group(ringA, base);
-      group(ringB, base + kSelRing);
+      group(ringA, tmA, base);
+      group(ringB, tmB, base + kSelRing);
     }
   };
   const int n_plain = n_interior / (2 * kSelRing) * (2 * kSelRing);   // whole rounds of interior tiles run without masks
   // this wave's share: an equal run of the mask-free rounds; the last wave of the group also takes the edge
   const int rounds = n_plain / (2 * kSelRing);
   const int plain_lo = (rounds * part / KS) * (2 * kSelRing), plain_hi = (rounds * (part + 1) / KS) * (2 * kSelRing);
+  // Sweeps 2 and 3 over the mask-free range, 512 tiles (256 entries of the maximum table) at a time: where at most
+  // a quarter of the tile pairs can hold a member, only those are fetched and looked at -- with a peaked score
+  // law that is a handful of pairs in a million keys -- otherwise the streaming sweep above runs over the stretch.
+  auto sweep_picked = [&](auto PH, int tile_begin, int tile_end) {
+    constexpr int phase_ = decltype(PH)::value;
+#pragma unroll 1
+    for (int tb = tile_begin; tb < tile_end; tb += 512) {
+      const int te = min(tb + 512, tile_end);
+      float tmv[4];
+      uint64_t on[4];
+      int n_on = 0;
+#pragma unroll
+      for (int k = 0; k < 4; ++k) {
+        const int pair = (tb >> 1) + k * 64 + lane;
+        tmv[k] = pair < (te >> 1) ? tmx[pair] : ninf;
+        on[k] = __ballot(tmv[k] >= xlo_wave);
+        n_on += __popcll(on[k]);
+      }
+      if (n_on > 64) {
+        sweep(PH, std::false_type{}, tb, te);
+        continue;
+      }
+#pragma unroll
+      for (int k = 0; k < 4; ++k) {
+        uint64_t todo = on[k];
+        while (todo != 0ull) {
+          const int pl = __builtin_ctzll(todo);
+          todo &= todo - 1ull;
+          const int tile = tb + 2 * (k * 64 + pl);
+          reach_known = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(tmv[k]), pl)) >= xlo_wave_top;
+          f32x16 SI[2];
+#pragma unroll
+          for (int u = 0; u < 2; ++u) {
+#pragma unroll
+            for (int i = 0; i < 16; ++i) SI[u][i] = 0.f;
+            SI[u] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, load_k(tile + u)),
+                                                            __builtin_bit_cast(bf16x8, qIreg), SI[u], 0, 0, 0);
+          }
+          float tmax = ninf;
+#pragma unroll
+          for (int u = 0; u < 2; ++u) tmax = fmaxf(tmax, tile_work(PH, std::false_type{}, SI[u], (tile + u) * 32, mxs[u]));
+          if (phase_ == 3 && !reach_known && lane == 0) tmx[tile >> 1] = tmax > 0.f ? pinf : ninf;
+        }
+      }
+    }
+  };
   auto sweep_all = [&](auto PH) {
-    sweep(PH, std::false_type{}, plain_lo, plain_hi);
+    constexpr int phase_ = decltype(PH)::value;
+    if constexpr (phase_ == 2 || phase_ == 3) sweep_picked(PH, plain_lo, plain_hi);
+    else sweep(PH, std::false_type{}, plain_lo, plain_hi);
     if (part == KS - 1) sweep(PH, std::true_type{}, n_plain, n_tiles);
-    if (decltype(PH)::value == 2 || decltype(PH)::value == 3) drain_list();
+    if (phase_ == 2 || phase_ == 3) drain_list();
   };
 
   double Z = 0.0, above = 0.0;
@@ -703,6 +823,8 @@ __global__ __launch_bounds__(kSelThreads, 2) void prefill_select_kernel(const Pr
     // rounding error of M = max * scale and may be a hair below zero (a lowered reference keeps its bound:
     // what lies above it has been counted)
     if (qlo == 0 && !rebased) x_top = pinf;
+    xlo_wave = -wave_max_f32((qok && !idle) ? -x_lo : ninf);
+    xlo_wave_top = wave_max_f32((qok && !idle) ? x_lo : ninf);
     shift -= 7;                                                     // of this sweep's digit: 7, then 0
     zero_hist();
     __syncthreads();
@@ -777,10 +899,15 @@ __global__ __launch_bounds__(64 * (8 / QB), QB == 1 ? 2 : 1) void flash_prefill_
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int g = lane >> 5, r = lane & 31;
-  const int h = a.heads[blockIdx.x];
+  // A selecting launch behind a threshold search (one sequence) is laid out (key range, query tile, head slot): the
+  // query tiles' lists differ wildly in length, and with the key range as the fastest index the ranges of a long
+  // list go round all eight dies (workgroups are dealt to the dies in turn) instead of piling up on one.
+  const bool listed = SPARSE && a.p < 1.f;
+  const int hslot = listed ? blockIdx.z : blockIdx.x;
+  const int h = a.heads[hslot];
   const int n_splits = LOCAL ? 1 : a.n_splits;
-  const int b = blockIdx.z / n_splits;
-  const int split = blockIdx.z - b * n_splits;
+  const int b = listed ? 0 : blockIdx.z / n_splits;
+  const int split = listed ? (int)blockIdx.x : (int)blockIdx.z - b * n_splits;
   const int t0 = ((int)gridDim.y - 1 - (int)blockIdx.y) * kPwQ;
   const int kvh = h / (a.n_q_heads / a.n_kv_heads);
   const int pos0 = a.q_start ? a.q_start[b] : (int)a.q_start_host;
@@ -813,7 +940,11 @@ __global__ __launch_bounds__(64 * (8 / QB), QB == 1 ? 2 : 1) void flash_prefill_
     kt_w0 = lo / kPfK;
     ks_end = min((a.sink + kPfK - 1) / kPfK, kt_w0);    // sink tiles not already inside the band
   }
-  const int n_tiles = ks_end + (kt_end - kt_w0 + 1);
+  // selecting mode with a threshold search in front: only the tiles on this query tile's list (ascending
+  // 64-key tile numbers, written by prefill_active_tiles_kernel) can hold a kept pair
+  const int qt_list = (int)gridDim.y - 1 - (int)blockIdx.y;
+  const int32_t* const alist = listed ? a.act_list + ((int64_t)hslot * gridDim.y + qt_list) * a.n_t64 : nullptr;
+  const int n_tiles = listed ? a.act_count[(int64_t)hslot * gridDim.y + qt_list] : ks_end + (kt_end - kt_w0 + 1);
   const uint16_t* Kg = a.K + (int64_t)kvh * a.head_stride + tok0 * a.row_stride;
   const uint16_t* Vg = a.V + (int64_t)kvh * a.head_stride + tok0 * a.row_stride;
 
@@ -839,7 +970,7 @@ __global__ __launch_bounds__(64 * (8 / QB), QB == 1 ? 2 : 1) void flash_prefill_
   const uint16_t* kIg = nullptr;
   const int n_rows = pos0 + a.n_q;                      // index-key rows that exist
   if (SPARSE) {
-    const int j = blockIdx.x;
+    const int j = hslot;
     kIg = a.kI + (int64_t)j * a.kI_head_stride;
 #pragma unroll
     for (int qb = 0; qb < QB; ++qb) {
@@ -1102,12 +1233,14 @@ __global__ __launch_bounds__(64 * (8 / QB), QB == 1 ? 2 : 1) void flash_prefill_
     return true;
   };
 
-  auto tile_n0 = [&](int it) __attribute__((always_inline)) { return (it < ks_end ? it : kt_w0 + (it - ks_end)) * kPfK; };
+  auto tile_n0 = [&](int it) __attribute__((always_inline)) {
+    if (SPARSE && listed) return alist[it] * kPfK;
+    return (it < ks_end ? it : kt_w0 + (it - ks_end)) * kPfK;
+  };
   const int it_lo = (int)((int64_t)n_tiles * split / n_splits);
   const int it_hi = (int)((int64_t)n_tiles * (split + 1) / n_splits);
   auto slot_of = [&](int it) __attribute__((always_inline)) { return (it - it_lo) % kPwStages; };
   auto tile_at = [&](int it) __attribute__((always_inline)) { return Ls + slot_of(it) * kPwTileBytes; };
-  auto block_n0 = [&](int it, int hf) __attribute__((always_inline)) { return tile_n0(it) + hf * 32; };
 
   bool redo = false;
   if (it_lo < it_hi) {
@@ -1121,8 +1254,12 @@ __global__ __launch_bounds__(64 * (8 / QB), QB == 1 ? 2 : 1) void flash_prefill_
 #pragma unroll
         for (int i = 0; i < 16; ++i) O[qb][db][i] = 0.f;
     }
-    load_tile(tile_n0(it_lo), 0);
-    load_tile(tile_n0(min(it_lo + 1, it_hi - 1)), 1);
+    // first keys of tiles it, it + 1, it + 2 (clamped to the range's last tile) and, one iteration ahead of its
+    // first use, it + 3: a listed tile's number comes from memory
+    int n_t0 = tile_n0(it_lo), n_t1 = tile_n0(min(it_lo + 1, it_hi - 1)), n_t2 = tile_n0(min(it_lo + 2, it_hi - 1));
+    int n_t3 = tile_n0(min(it_lo + 3, it_hi - 1));
+    load_tile(n_t0, 0);
+    load_tile(n_t1, 1);
     loads_landed();
     __syncthreads();
     // reference maxima: the largest score of the first tile, masks ignored (always finite)
@@ -1148,12 +1285,12 @@ __global__ __launch_bounds__(64 * (8 / QB), QB == 1 ? 2 : 1) void flash_prefill_
     bool pend = false;
     u32x4 ki0 = (u32x4){0u, 0u, 0u, 0u}, ki1 = ki0;       // index keys of the current tile's two key blocks
     if (SPARSE) {
-      ki0 = load_ki(tile_n0(it_lo));
-      ki1 = load_ki(tile_n0(it_lo) + 32);
+      ki0 = load_ki(n_t0);
+      ki1 = load_ki(n_t0 + 32);
     }
     auto half = [&](int it, auto hf_tag) __attribute__((always_inline)) {
       constexpr int hf = decltype(hf_tag)::value;
-      const int nb0 = block_n0(it, hf);
+      const int nb0 = n_t0 + hf * 32;
       const unsigned char* t_pend = hf == 0 ? tile_at(it - 1) : tile_at(it);
       const uint32_t (&Pin)[QB][8] = hf == 0 ? P1 : P0;
       uint32_t (&Pout)[QB][8] = hf == 0 ? P0 : P1;
@@ -1171,8 +1308,8 @@ __global__ __launch_bounds__(64 * (8 / QB), QB == 1 ? 2 : 1) void flash_prefill_
         pend = true;
       }
       if (SPARSE && hf == 1) {                             // the next tile's index keys: a tile's time to arrive
-        ki0 = load_ki(tile_n0(min(it + 1, it_hi - 1)));
-        ki1 = load_ki(tile_n0(min(it + 1, it_hi - 1)) + 32);
+        ki0 = load_ki(n_t1);
+        ki1 = load_ki(n_t1 + 32);
       }
       if (hf == 0) {
         if (is_active(nb0 + 32)) scores_beside(tile_at(it), 1, S, [&](int) __attribute__((always_inline)) {});
@@ -1180,9 +1317,9 @@ __global__ __launch_bounds__(64 * (8 / QB), QB == 1 ? 2 : 1) void flash_prefill_
         __syncthreads();
       } else {
         // past the last tile the same loads re-fetch it into a buffer nobody reads: no branches
-        const int n2 = tile_n0(min(it + 2, it_hi - 1));
+        const int n2 = n_t2;
         const int s2 = slot_of(it + 2);
-        const bool next_active = it + 1 < it_hi && is_active(tile_n0(it + 1));
+        const bool next_active = it + 1 < it_hi && is_active(n_t1);
         if (n2 + kPfK - 1 <= m_hi) {                       // a whole tile (all but the last of the range)
           if (next_active) {
             scores_beside(tile_at(it + 1), 0, S, [&](int kk) __attribute__((always_inline)) { if (kk < 2 * GH) load_piece_full(n2, s2, kk); });
@@ -1200,6 +1337,10 @@ __global__ __launch_bounds__(64 * (8 / QB), QB == 1 ? 2 : 1) void flash_prefill_
     for (int it = it_lo; it < it_hi; ++it) {
       half(it, std::integral_constant<int, 0>{});
       half(it, std::integral_constant<int, 1>{});
+      n_t0 = n_t1;
+      n_t1 = n_t2;
+      n_t2 = n_t3;
+      n_t3 = tile_n0(min(it + 4, it_hi - 1));
     }
     if (pend) mfma_PV(tile_at(it_hi - 1), 1, P1);        // drain: PV of the last block
     loads_landed();
@@ -1284,12 +1425,12 @@ __global__ __launch_bounds__(64 * (8 / QB), QB == 1 ? 2 : 1) void flash_prefill_
     const float mfin = (it_lo < it_hi && ltot > 0.f) ? mrow[qb] : ninf;
     const int kept = sel_cnt[qb] + __shfl_xor(sel_cnt[qb], 32);
     if (SPARSE && g == 0 && split == 0 && !(a.p < 1.f)) {   // keep-all: the threshold search did not run
-      const int64_t o = (int64_t)blockIdx.x * a.n_q + tq[qb];
+      const int64_t o = (int64_t)hslot * a.n_q + tq[qb];
       if (a.mass) a.mass[o] = 1.f;
       if (a.tau) a.tau[o] = ninf;
     }
     if (n_splits > 1) {
-      float* prow = a.part + (((int64_t)split * a.n_heads + blockIdx.x) * a.n_q + tq[qb]) * kPfPart;
+      float* prow = a.part + (((int64_t)split * a.n_heads + hslot) * a.n_q + tq[qb]) * kPfPart;
       if (g == 0) { prow[0] = mfin; prow[1] = ltot; prow[2] = __int_as_float(kept); }
 #pragma unroll
       for (int db = 0; db < 4; ++db)
@@ -1315,8 +1456,55 @@ __global__ __launch_bounds__(64 * (8 / QB), QB == 1 ? 2 : 1) void flash_prefill_
     if (a.lse && g == 0) {
       a.lse[((int64_t)b * a.n_q + tq[qb]) * a.n_q_heads + h] = ltot > 0.f ? mfin * a.scale + logf(ltot) : ninf;
     }
-    if (SPARSE && a.count && g == 0) a.count[(int64_t)blockIdx.x * a.n_q + tq[qb]] = kept;
+    if (SPARSE && a.count && g == 0) a.count[(int64_t)hslot * a.n_q + tq[qb]] = kept;
   }
+}
+
+// The 64-key tiles a 256-query tile of the selecting attention launch has to visit: tile n is on the list iff, for
+// one of the tile's eight 32-query groups, the group's largest index product in the tile (tile_max, written by the
+// first sweep of prefill_select_kernel) reaches the group's smallest threshold.  Every other tile holds no kept
+// pair -- the keep test is product >= threshold -- so leaving it out changes no output, count or sum.
+// Grid (query tiles, retrieval heads), 256 threads; the list is ascending.
+__global__ __launch_bounds__(256) void prefill_active_tiles_kernel(const PrefillArgs a) {
+  const int j = blockIdx.y, qt = blockIdx.x;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int t0 = qt * kPwQ;
+  __shared__ float thr[kPwQ / 32];
+  __shared__ int wave_n[4];
+  {
+    const int t = t0 + tid;
+    float v = t < a.n_q ? a.sel_thr[(int64_t)j * a.n_q + t] : __builtin_huge_valf();
+#pragma unroll
+    for (int o = 16; o > 0; o >>= 1) v = fminf(v, __shfl_xor(v, o));
+    if ((tid & 31) == 0) thr[tid >> 5] = v;
+  }
+  __syncthreads();
+  const int pos0 = (int)a.q_start_host;
+  const int n_pairs = (pos0 + min(t0 + kPwQ, a.n_q) - 1) / kPfK + 1;
+  const float* tm = a.tile_max + ((int64_t)j * ((a.n_q + 31) / 32) + t0 / 32) * a.n_t64;
+  int32_t* list = a.act_list + ((int64_t)j * gridDim.x + qt) * a.n_t64;
+  int base = 0;
+  for (int p0 = 0; p0 < n_pairs; p0 += 256) {
+    const int p = p0 + tid;
+    bool on = false;
+    if (p < n_pairs) {
+#pragma unroll
+      for (int i = 0; i < kPwQ / 32; ++i) {
+        const int tw = t0 + 32 * i;
+        // the group's row of the table reaches as far as its last query sees
+        if (tw < a.n_q && p * kPfK <= pos0 + min(tw + 32, a.n_q) - 1) on = on || tm[(int64_t)i * a.n_t64 + p] >= thr[i];
+      }
+    }
+    const uint64_t bal = __ballot(on);
+    if (lane == 0) wave_n[wave] = __popcll(bal);
+    __syncthreads();
+    int before = base;
+    for (int w = 0; w < wave; ++w) before += wave_n[w];
+    if (on) list[before + __popcll(bal & ((1ull << lane) - 1ull))] = p;
+    base += wave_n[0] + wave_n[1] + wave_n[2] + wave_n[3];
+    __syncthreads();
+  }
+  if (tid == 0) a.act_count[(int64_t)j * gridDim.x + qt] = base;
 }
 
 // qI[j, t, :] = bf16( W[j] . x[t, ret_heads[j], :] ), the 128-term sums in fp64, one rounding
@@ -1408,6 +1596,18 @@ static int choose_splits(int n_heads, int32_t T, int64_t chunk_start) {
   return best;
 }
 
+// Key ranges of a selecting launch that follows a threshold search: the query tiles' lists differ in length by
+// orders of magnitude (a tile with one hard query visits everything, its neighbour a few dozen tiles), and the
+// host does not see the lengths.  Ranges of at most ~512 listed tiles, many more workgroups than compute units:
+// the hardware's workgroup dispatch does the balancing, a workgroup with an empty range leaves at once.
+static int choose_splits_listed(int n_heads, int32_t T, int64_t chunk_start) {
+  const int64_t max_tiles = (chunk_start + T - 1) / kPfK + 1;
+  int64_t s = (max_tiles + 511) / 512;
+  if (s > 32) s = 32;
+  const int base = choose_splits(n_heads, T, chunk_start);
+  return s > base ? (int)s : base;
+}
+
 static int32_t launch_prefill(const char* who, bool local, PrefillArgs& a, int32_t B, hipStream_t s) {
   if (a.n_heads == 0) return RTP_OK;
   if (a.n_splits < 1) a.n_splits = 1;
@@ -1477,6 +1677,22 @@ int32_t prefill_range_attn(const char* who, bool dense, const rtp_layer_desc* L,
   return launch_prefill(who, !dense, a, B, s);
 }
 
+// Sizes of the tile bookkeeping of a selecting launch.  A table row has one entry per 64 keys of the context, plus
+// the entries the threshold search touches past a group's last tile (its sweeps run in whole rounds of 8 tiles of
+// 32 keys and read the table one round ahead).
+struct PrefillTileWs {
+  int32_t n_t64;
+  size_t table_bytes, list_bytes, count_bytes;
+};
+static PrefillTileWs prefill_tile_ws(int32_t n_ret, int32_t T, int64_t chunk_start) {
+  PrefillTileWs w;
+  w.n_t64 = (int32_t)(((chunk_start + T + 31) / 32 + 32) / 2 + 1);
+  w.table_bytes = align_up((size_t)n_ret * ((T + 31) / 32) * w.n_t64 * sizeof(float), 256);
+  w.list_bytes = align_up((size_t)n_ret * ((T + kPwQ - 1) / kPwQ) * w.n_t64 * sizeof(int32_t), 256);
+  w.count_bytes = align_up((size_t)n_ret * ((T + kPwQ - 1) / kPwQ) * sizeof(int32_t), 256);
+  return w;
+}
+
 }  // namespace rtp
 
 using namespace rtp;
@@ -1487,9 +1703,11 @@ extern "C" size_t rtp_sparse_attn_prefill_workspace_bytes(const rtp_layer_desc* 
   const size_t proj = align_up((size_t)layer->n_ret * T * kIndexDim * sizeof(uint16_t), 256);
   const size_t state = align_up((size_t)layer->n_ret * T * sizeof(float), 256);
   // both rules: key-range partials
-  const int ns = choose_splits(layer->n_ret, T, chunk_start < 0 ? 0 : chunk_start);
+  const int ns = choose_splits_listed(layer->n_ret, T, chunk_start < 0 ? 0 : chunk_start);   // (the larger of the two rules)
   const size_t part = ns > 1 ? align_up((size_t)ns * layer->n_ret * T * kPfPart * sizeof(float), 256) : 0;
-  return proj + state + part;
+  // selecting mode: the tile-maximum table and the query tiles' lists of tiles to visit
+  const PrefillTileWs tw = prefill_tile_ws(layer->n_ret, T, chunk_start < 0 ? 0 : chunk_start);
+  return proj + state + part + tw.table_bytes + tw.list_bytes + tw.count_bytes;
 }
 
 extern "C" int32_t rtp_sparse_attn_prefill(const rtp_layer_desc* layer, const void* q_pre, const void* q, const float* WQ,
@@ -1579,11 +1797,21 @@ extern "C" int32_t rtp_sparse_attn_prefill(const rtp_layer_desc* layer, const vo
   const size_t state_bytes = align_up((size_t)layer->n_ret * T * sizeof(float), 256);
   a.sel_thr = (float*)((char*)ws + proj_bytes);
   a.part = (float*)((char*)ws + proj_bytes + state_bytes);
-  a.n_splits = choose_splits(layer->n_ret, T, chunk_start);
+  a.n_splits = p < 1.f ? choose_splits_listed(layer->n_ret, T, chunk_start) : choose_splits(layer->n_ret, T, chunk_start);
+  {
+    // (the layout does not depend on p: the partials' region has the size of the larger rule)
+    const int ns_ws = choose_splits_listed(layer->n_ret, T, chunk_start);
+    const size_t part_bytes = ns_ws > 1 ? align_up((size_t)ns_ws * layer->n_ret * T * kPfPart * sizeof(float), 256) : 0;
+    const PrefillTileWs tw = prefill_tile_ws(layer->n_ret, T, chunk_start);
+    char* at = (char*)ws + proj_bytes + state_bytes + part_bytes;
+    a.n_t64 = tw.n_t64;
+    a.tile_max = (float*)at;
+    a.act_list = (int32_t*)(at + tw.table_bytes);
+    a.act_count = (int32_t*)(at + tw.table_bytes + tw.list_bytes);
+  }
   if (p < 1.f) {
-    // waves per 32-query group: as many as it takes to give each of the chip's 1024 SIMDs two waves
-    const int64_t groups = (int64_t)a.n_heads * ((T + 31) / 32);
-    const int ks = groups > 512 ? 2 : groups > 256 ? 4 : 8;
+    constexpr int ks = 8;                                  // waves per 32-query group (see the kernel's header)
+    static_assert(ks == 8, "the launch below names the instantiation");
     const unsigned n_qtiles = (unsigned)((T + 256 / ks - 1) / (256 / ks));
     // 1-D grid, padded so that every die gets whole (head, query tile) columns (see the kernel's decoding)
     unsigned wgs = (unsigned)a.n_heads * n_qtiles;
@@ -1591,15 +1819,52 @@ extern "C" int32_t rtp_sparse_attn_prefill(const rtp_layer_desc* layer, const vo
       const unsigned per_head = 8u / (unsigned)a.n_heads;
       wgs = 8u * ((n_qtiles + per_head - 1) / per_head);
     }
-    if (ks == 2) RTP_LAUNCH(prefill_select_kernel<2>, dim3(wgs), dim3(kSelThreads), 0, (hipStream_t)stream, a);
-    else if (ks == 4) RTP_LAUNCH(prefill_select_kernel<4>, dim3(wgs), dim3(kSelThreads), 0, (hipStream_t)stream, a);
-    else RTP_LAUNCH(prefill_select_kernel<8>, dim3(wgs), dim3(kSelThreads), 0, (hipStream_t)stream, a);
+    RTP_LAUNCH(prefill_select_kernel<8>, dim3(wgs), dim3(kSelThreads), 0, (hipStream_t)stream, a);
+    RTP_LAUNCH(prefill_active_tiles_kernel, dim3((unsigned)((T + kPwQ - 1) / kPwQ), (unsigned)a.n_heads), dim3(256), 0,
+               (hipStream_t)stream, a);
   }
   dim3 grid((unsigned)a.n_heads, (unsigned)((T + kPwQ - 1) / kPwQ), (unsigned)a.n_splits);
+  if (p < 1.f) grid = dim3((unsigned)a.n_splits, (unsigned)((T + kPwQ - 1) / kPwQ), (unsigned)a.n_heads);
   if (a.f16) RTP_LAUNCH((flash_prefill_wide_kernel<kModeSparse, 1, true>), grid, dim3(512), 0, (hipStream_t)stream, a);
   else RTP_LAUNCH((flash_prefill_wide_kernel<kModeSparse, 1>), grid, dim3(512), 0, (hipStream_t)stream, a);
   if (a.n_splits > 1)
     RTP_LAUNCH(prefill_combine_kernel, dim3((unsigned)((T + 1) / 2), (unsigned)a.n_heads), dim3(256), 0,
                        (hipStream_t)stream, a);
   return check_launch(who);
+}
+
+extern "C" int32_t rtp_sparse_attn_prefill_tile_stats(const rtp_layer_desc* layer, int32_t T, int64_t chunk_start,
+                                                      const void* ws, size_t ws_bytes, void* stream,
+                                                      int64_t* tiles_visited, int64_t* tiles_causal) {
+  const char* who = "rtp_sparse_attn_prefill_tile_stats";
+  HeadTable ht;
+  int32_t rc = fill_head_table(layer, &ht, who);
+  if (rc != RTP_OK) return rc;
+  if (T <= 0 || chunk_start < 0 || !tiles_visited || !tiles_causal)
+    return fail(RTP_ERR_INVALID_ARG, "%s: T must be positive, chunk_start >= 0, outputs non-NULL", who);
+  if (layer->n_ret <= 0) {
+    *tiles_visited = *tiles_causal = 0;
+    return RTP_OK;
+  }
+  const size_t need = rtp_sparse_attn_prefill_workspace_bytes(layer, T, chunk_start);
+  if (!ws || ((uintptr_t)ws & 255) || ws_bytes < need)
+    return fail(RTP_ERR_WORKSPACE, "%s: the workspace of the rtp_sparse_attn_prefill call (%zu bytes) is required", who, need);
+  clear_error();
+  const PrefillTileWs tw = prefill_tile_ws(layer->n_ret, T, chunk_start);
+  const int n_qt = (T + kPwQ - 1) / kPwQ;
+  std::vector<int32_t> counts((size_t)layer->n_ret * n_qt);
+  // the counts are the last region of the workspace
+  const char* at = (const char*)ws + need - tw.count_bytes;
+  hipError_t e = hipStreamSynchronize((hipStream_t)stream);
+  if (e == hipSuccess) e = hipMemcpy(counts.data(), at, counts.size() * sizeof(int32_t), hipMemcpyDeviceToHost);
+  if (e != hipSuccess) return fail(RTP_ERR_HIP, "%s: %s", who, hipGetErrorString(e));
+  int64_t vis = 0, causal = 0;
+  for (size_t i = 0; i < counts.size(); ++i) vis += counts[i];
+  for (int qt = 0; qt < n_qt; ++qt) {
+    const int64_t m_hi = chunk_start + (int64_t)std::min(qt * kPwQ + kPwQ, T) - 1;
+    causal += (m_hi / kPfK + 1) * layer->n_ret;
+  }
+  *tiles_visited = vis;
+  *tiles_causal = causal;
+  return RTP_OK;
 }

@@ -162,6 +162,14 @@ __device__ __forceinline__ double wave_incl_scan(double x) {
 __device__ __forceinline__ int wave_last(int x) { return __builtin_amdgcn_readlane(x, 63); }
 // Wave-wide sum / maximum of non-negative-or-(-1) ints, in every lane.
 __device__ __forceinline__ int wave_sum(int x) { return wave_last(wave_incl_scan(x)); }
+// Wave-wide maximum of floats, in every lane (same six steps; a lane without a source takes -inf).
+__device__ __forceinline__ float wave_max_f32(float x) {
+  const int ninf_bits = 0xff800000;
+#define RTP_STEP(CTRL, MASK) x = fmaxf(x, __int_as_float(__builtin_amdgcn_update_dpp(ninf_bits, __float_as_int(x), CTRL, MASK, 0xf, false)));
+  RTP_WAVE_SCAN_STEPS(RTP_STEP)
+#undef RTP_STEP
+  return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(x), 63));
+}
 __device__ __forceinline__ int wave_max_ge_m1(int x) {      // x >= -1 in every lane
 #define RTP_STEP(CTRL, MASK) x = max(x, __builtin_amdgcn_update_dpp(-1, x, CTRL, MASK, 0xf, false));
   RTP_WAVE_SCAN_STEPS(RTP_STEP)

@@ -305,3 +305,7 @@ class PrefillRun:
         rtp.rtp_sparse_attn_prefill(self.desc, q_in, w.q, w.WQ, w.kI, w.N * 16, self.Kp, self.Vp, self.rs, self.hs,
                                     w.chunk_start, w.T, w.p if p is None else p, self.out if out is None else out,
                                     self.lse if lse is None else lse, self.tau, self.count, self.mass, self.ws)
+
+    def tile_stats(self):
+        """(64-key tiles visited, tiles of plain causal attention) of the last sparse_prefill call with p < 1."""
+        return rtp.rtp_sparse_attn_prefill_tile_stats(self.desc, self.w.T, self.w.chunk_start, self.ws)

@@ -23,7 +23,7 @@ EXPORTS = [
     "rtp_index_score",
     "rtp_topp_workspace_bytes", "rtp_topp_workspace_init", "rtp_topp_select", "rtp_topp_select_noalloc",
     "rtp_sparse_attn_decode_workspace_bytes", "rtp_sparse_attn_decode",
-    "rtp_sparse_attn_prefill_workspace_bytes", "rtp_sparse_attn_prefill",
+    "rtp_sparse_attn_prefill_workspace_bytes", "rtp_sparse_attn_prefill", "rtp_sparse_attn_prefill_tile_stats",
     "rtp_local_attn_workspace_bytes", "rtp_local_attn",
     "rtp_dense_attn_workspace_bytes", "rtp_dense_attn",
     "rtp_index_project", "rtp_topk_select",
@@ -106,6 +106,8 @@ def lib() -> C.CDLL:
     L.rtp_sparse_attn_decode.argtypes = [dp, vp, vp, vp, i64, i64, vp, vp, i64, vp, i64, i32, vp, vp, vp, sz, vp]
     L.rtp_sparse_attn_prefill_workspace_bytes.restype = sz
     L.rtp_sparse_attn_prefill_workspace_bytes.argtypes = [dp, i32, i64]
+    L.rtp_sparse_attn_prefill_tile_stats.restype = i32
+    L.rtp_sparse_attn_prefill_tile_stats.argtypes = [dp, i32, i64, vp, sz, vp, C.POINTER(C.c_int64), C.POINTER(C.c_int64)]
     L.rtp_sparse_attn_prefill.restype = i32
     L.rtp_sparse_attn_prefill.argtypes = [dp, vp, vp, vp, vp, i64, vp, vp, i64, i64, i64, i32, C.c_float,
                                           vp, vp, vp, vp, vp, vp, sz, vp]
@@ -331,6 +333,14 @@ def rtp_sparse_attn_prefill(layer, q_pre, q, WQ, kI, kI_head_stride, K, V, kv_ro
                                          _ptr(K), _ptr(V), kv_row_stride, kv_head_stride, chunk_start, T, p,
                                          _ptr(out), _ptr(lse), _ptr(tau), _ptr(count), _ptr(mass), _ptr(ws),
                                          _nbytes(ws), _stream(stream)))
+
+
+def rtp_sparse_attn_prefill_tile_stats(layer, T, chunk_start, ws, stream=None):
+    """(tiles_visited, tiles_causal) of the last p < 1 call on this workspace."""
+    vis, causal = C.c_int64(0), C.c_int64(0)
+    _check(lib().rtp_sparse_attn_prefill_tile_stats(C.byref(layer), T, chunk_start, _ptr(ws), _nbytes(ws), _stream(stream),
+                                                    C.byref(vis), C.byref(causal)))
+    return vis.value, causal.value
 
 
 def rtp_local_attn_workspace_bytes(layer, B, n_q, max_ctx) -> int:

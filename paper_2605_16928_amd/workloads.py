@@ -312,15 +312,16 @@ class PrefillWorkload:
 def make_prefill(name: str, layer: Layer, chunk_start: int, T: int, p: float, seed: int, device="cpu", *,
                  index_mode: str = "direct", tokens_per_cluster: int = 1024, cluster_len=32,
                  own_frac: float = 0.8, q_noise: float = 0.3, zipf: float = 0.0, max_cluster: int = 4096,
-                 ) -> PrefillWorkload:
+                 pick_run: int = 1) -> PrefillWorkload:
     """One causal prefill chunk: queries at positions chunk_start .. chunk_start+T-1 of a sequence
     whose first chunk_start+T tokens are cached.
 
     Index side ("direct"): N / tokens_per_cluster planted clusters, each a run of consecutive tokens
     (length cluster_len, or Zipf(zipf)-distributed in [1, max_cluster]) whose index keys are
     a * u_c + N(0, sb^2 I) for a random unit direction u_c; background keys are N(0, sb^2 I).  Query m
-    picks one cluster that starts before m (probability proportional to its size) and gets
-    qI = g * u_c + N(0, q_noise^2 I).  g = a and sb are set so that background scores have unit
+    picks one cluster that starts before m (probability proportional to its size; with pick_run > 1 a run of
+    that many consecutive queries shares the pick of its first query, the way neighbouring prompt tokens ask for
+    the same passage) and gets qI = g * u_c + N(0, q_noise^2 I).  g = a and sb are set so that background scores have unit
     variance and the own cluster holds about own_frac of the indexer mass at the full context; the
     other clusters (random directions, cosine std 1/4) supply the tail.
     "proj": fp32 projections and pre-RoPE queries, index keys plain N(0, I) (no planted structure).
@@ -370,6 +371,8 @@ def make_prefill(name: str, layer: Layer, chunk_start: int, T: int, p: float, se
             w = csize.float()[None, :] * (cstart[None, :] < pos[:, None]).float()
             w[:, 0] += 1e-6
             pick = torch.multinomial(w, 1, generator=g).squeeze(1)
+            if pick_run > 1:
+                pick = pick[(torch.arange(T, device=dev) // pick_run) * pick_run]
             qq = a_lvl * u[pick] + q_noise * torch.randn((T, r), generator=g, device=dev, dtype=torch.float32)
             qI[j] = qq.to(torch.bfloat16)
     return PrefillWorkload(name=name, layer=layer, N=N, chunk_start=int(chunk_start), T=int(T), p=float(p),
@@ -386,17 +389,33 @@ def c3_chunk(device="cpu", seed: int = 2, chunk: int = 31, N_total: int = 131072
     return make_prefill("c3", layer, chunk * T, T, p, seed, device, cluster_len=32)
 
 
-def c4_chunk(device="cpu", seed: int = 3, chunk: int = 127, T: int = 8192, p: float = 0.9) -> PrefillWorkload:
+def c4_chunk(device="cpu", seed: int = 3, chunk: int = 127, T: int = 8192, p: float = 0.9, law: str = "broad") -> PrefillWorkload:
     """Configuration 4: one 8192-query chunk of a 1,048,576-token prefill (chunk index 0..127),
-    4 retrieval heads over the full cache, local heads 4 sink + 4096 window, cluster sizes
-    Zipf(1.1) in [1, 4096]."""
+    4 retrieval heads over the full cache, local heads 4 sink + 4096 window.
+    law "broad": cluster sizes Zipf(1.1) in [1, 4096], the own cluster holds about 0.8 of the indexer mass, every
+    query picks its own cluster: p = 0.9 reaches into the tail and keeps thousands of tokens per query.
+    law "peaked": one cluster of 32 tokens per 32768 (few enough that the other clusters' tails stay small) that
+    holds about 0.97 of its queries' mass, runs of 64 queries share a cluster, little query noise: p = 0.9 is
+    reached inside the cluster for every query, about 20 kept tokens.
+    law "peaked_hard": the same with the cluster at 0.995 of the mass and the query noise of the broad law: a
+    median of about 20 kept tokens, and one or two queries in a thousand with a weak cluster and up to hundreds
+    of thousands of kept tokens (a query tile with such a query has to visit every key tile)."""
     layer = Layer(32, 8, [0, 8, 16, 24], sink=4, window=4096)
+    if law == "peaked":
+        return make_prefill("c4_peaked", layer, chunk * T, T, p, seed, device, cluster_len=32, own_frac=0.97, pick_run=64,
+                            tokens_per_cluster=32768, q_noise=0.1)
+    if law == "peaked_hard":
+        return make_prefill("c4_peaked_hard", layer, chunk * T, T, p, seed, device, cluster_len=32, own_frac=0.995,
+                            pick_run=64, tokens_per_cluster=32768)
+    if law != "broad":
+        raise ValueError("law must be 'broad', 'peaked' or 'peaked_hard'")
     return make_prefill("c4", layer, chunk * T, T, p, seed, device, zipf=1.1)
 
 
 def small_prefill(device="cpu", seed: int = 41, chunk_start: int = 700, T: int = 200, p: float = 0.9, *,
                   n_q_heads=8, n_kv_heads=2, ret_heads=(0, 5), sink=4, window=160, index_mode="direct",
-                  tokens_per_cluster=128, cluster_len=8, zipf=0.0, kv_dtype="bf16") -> PrefillWorkload:
+                  tokens_per_cluster=128, cluster_len=8, zipf=0.0, kv_dtype="bf16", own_frac=0.8, pick_run=1) -> PrefillWorkload:
     layer = Layer(n_q_heads, n_kv_heads, list(ret_heads), sink=sink, window=window, kv_dtype=kv_dtype)
     return make_prefill("small_prefill", layer, chunk_start, T, p, seed, device, index_mode=index_mode,
-                        tokens_per_cluster=tokens_per_cluster, cluster_len=cluster_len, zipf=zipf, max_cluster=64)
+                        tokens_per_cluster=tokens_per_cluster, cluster_len=cluster_len, zipf=zipf, max_cluster=64,
+                        own_frac=own_frac, pick_run=pick_run)

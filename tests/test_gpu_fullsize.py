@@ -250,6 +250,31 @@ def test_c4_last_chunk_sampled_rows():
           f"max {max(kept)}", flush=True)
 
 
+@pytest.mark.parametrize("law", ["peaked", "peaked_hard"])
+def test_c4_last_chunk_peaked_laws_sampled_rows(law):
+    """Configuration 4 under the peaked indexer laws (about 20 kept tokens per query; "peaked_hard" adds a few
+    queries that keep up to hundreds of thousands): the launch that leaves out the key tiles without a kept pair,
+    sampled retrieval rows -- the rows with the most kept tokens among them -- against the oracle."""
+    print(f"[case] c4 last chunk, {law} law", flush=True)
+    rng = np.random.default_rng(9)
+    w = wl.c4_chunk(DEV, chunk=127, law=law)
+    L = w.layer
+    run = PrefillRun(w)
+    run.sparse_prefill()
+    cnt = run.count.cpu().numpy()
+    visited, causal = run.tile_stats()
+    print(f"   64-key tiles visited: {visited} of {causal}", flush=True)
+    assert visited < causal // 2
+    rows = _sample_rows(w, 60, L.ret_heads, rng)
+    order = np.argsort(cnt, axis=None)[::-1][:6]              # the deepest rows of the chunk
+    rows += [(int(i % w.T), int(L.ret_heads[i // w.T])) for i in order]
+    del run
+    kept = _prefill_fullsize(w, [], rows, [], f"c4 {law}")
+    print(f"   kept tokens over {len(kept)} sampled retrieval rows: min {min(kept)} median {np.median(kept):.0f} "
+          f"max {max(kept)}", flush=True)
+    assert np.median(kept) < 200
+
+
 def test_c2_full_size_fp16():
     """Configuration 2 with fp16 attention tensors (the format the paper's decode kernel loads): the timed
     step, every row against the oracle."""

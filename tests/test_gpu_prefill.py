@@ -188,6 +188,28 @@ def test_sparse_prefill_matches_oracle(name):
     _check_sparse_prefill(w, name, p)
 
 
+@pytest.mark.parametrize("kv_dtype", ["bf16", "fp16"])
+def test_sparse_prefill_peaked_law_skips_key_tiles(kv_dtype):
+    """A peaked indexer law: the own cluster of 8 tokens holds nearly all the mass, runs of 32 queries share a
+    cluster, so p = 0.9 keeps a handful of tokens per query and most 64-key tiles hold no kept pair of a whole
+    query tile.  The attention launch leaves those tiles out; everything it reports still matches the oracle,
+    and the tile statistics show the skipping."""
+    print(f"[case] sparse prefill, peaked law, {kv_dtype}", flush=True)
+    w = wl.small_prefill(DEV, p=0.9, chunk_start=9000, T=600, seed=70, own_frac=0.99, pick_run=32, kv_dtype=kv_dtype)
+    cnt = _check_sparse_prefill(w, f"peaked_{kv_dtype}", 0.9)
+    assert np.median(cnt) <= 16
+    run = PrefillRun(w)
+    run.sparse_prefill(p=0.9)
+    visited, causal = run.tile_stats()
+    n_ret = w.layer.n_ret
+    assert causal == n_ret * sum((9000 + min(t0 + 256, 600) - 1) // 64 + 1 for t0 in range(0, 600, 256))
+    print(f"   tiles visited {visited} of {causal}", flush=True)
+    assert 0 < visited < causal // 2
+    # p close to 1 reaches every tile: the list is the whole causal range again
+    run.sparse_prefill(p=0.9999999)
+    assert run.tile_stats()[0] > causal // 2
+
+
 def test_sparse_prefill_key_ranges_without_a_kept_key():
     """Long context, few heads: the launch cuts every query tile's key range in two, and with a small p the
     few kept tokens of a query leave whole ranges empty -- a legitimate zero partial, not a failed reference."""
