@@ -66,13 +66,26 @@ def probe(args, torch, rtp, wl, DecodeRun, dev) -> int:
         torch.cuda.synchronize()
         print("copy bytes per launch:", n * 4, "read and", n * 4, "written")
         return 0
-    if args.probe == "decode":
+    if args.probe in ("decode", "graph"):
         runs = [DecodeRun(wl.c2(dev, seed=100 + i, p=args.p, ctx=args.ctx, batch=args.batch)) for i in range(args.copies)]
         side = torch.cuda.Stream()
-        for i in range(10 + 40):
-            runs[i % len(runs)].step_fastest(side)
+        for r in runs:
+            r.step_fastest(side)
         torch.cuda.synchronize()
-        print("decode probe: 50 steps of the timed configuration (score pass + rtp_decode_attention), "
+        if args.probe == "graph":                       # the same step, captured once per copy and replayed
+            graphs = []
+            for r in runs:
+                g = torch.cuda.CUDAGraph()
+                with torch.cuda.graph(g, stream=side):
+                    r.step_fastest(side)
+                graphs.append(g)
+            for i in range(10 + 40):
+                graphs[i % len(graphs)].replay()
+        else:
+            for i in range(10 + 40):
+                runs[i % len(runs)].step_fastest(side)
+        torch.cuda.synchronize()
+        print(f"{args.probe} probe: 50 steps of the timed configuration (score pass + rtp_decode_attention), "
               f"batch {args.batch} x {args.ctx}, p = {args.p}, {args.copies} copies cycled")
         return 0
     from paper_2605_16928_amd.pipeline import PrefillRun
@@ -104,10 +117,11 @@ def main() -> int:
                     "(eager launches on two streams are the faster configuration on this box)")
     ap.add_argument("--one-stream", action="store_true", help="keep the local heads on the main stream")
     ap.add_argument("--no-prefill", action="store_true", help="skip the 1M-token prefill measurements")
-    ap.add_argument("--probe", choices=["decode", "prefill", "copy"], default=None,
-                    help="launch only the timed decode step (or the prefill chunk launches of the 1M configuration, or a "
-                         "plain 1 GiB copy that calibrates the byte counters) a few times and exit: the program to put "
-                         "behind `rocprofv3 ... --` for per-kernel traces and hardware counters")
+    ap.add_argument("--probe", choices=["decode", "graph", "prefill", "copy"], default=None,
+                    help="launch only the timed decode step (eagerly, or as replays of its HIP graph; or the prefill chunk "
+                         "launches of the 1M configuration, or a plain 1 GiB copy that calibrates the byte counters) a few "
+                         "times and exit: the program to put behind `rocprofv3 ... --` for per-kernel traces and hardware "
+                         "counters")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build is single-GPU by design (no collectives, no sharding); run with --gpus 1",
