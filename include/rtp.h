@@ -208,6 +208,11 @@ int32_t rtp_sparse_attn_decode(const rtp_layer_desc* layer, const void* q,
  * same at any depth.  Masses are fp32 exponentials (relative error up to 2^-22) summed in fp64: where single
  * tokens weigh less than 3e-7 of a row's mass, the kept count can differ from the fp64 count by the tokens
  * inside that margin.
+ * For p < 1 the attention visits only the 64-key tiles in which some query of a 256-query tile can keep a key (the
+ * search leaves, per 32-query group and tile, whether a product reaches the group's thresholds); outputs, counts and
+ * sums are those of visiting every tile.  The workspace holds that table (4 B per group and 64 keys of context),
+ * the tile lists and the key-range partials: about 630 MB for T = 8192 at chunk_start = 1,040,384 with 4
+ * retrieval heads, 40 MB for T = 4096 at 126,976.
  */
 size_t rtp_sparse_attn_prefill_workspace_bytes(const rtp_layer_desc* layer, int32_t T, int64_t chunk_start);
 int32_t rtp_sparse_attn_prefill(const rtp_layer_desc* layer, const void* q_pre, const void* q, const float* WQ,

@@ -352,7 +352,7 @@ __global__ __launch_bounds__(kPfThreads, 2) void flash_prefill_kernel(const Pref
 // ---- per-query top-p threshold search (selecting mode of rtp_sparse_attn_prefill) ---------------------
 // Sec. 3.2, S = Top-P(s(m, .), p), applied to every prefill query over its causal candidates n <= m.
 //
-// A wave works alone on 32 queries of one retrieval head and sweeps the index keys 0..m four times:
+// 32 queries of one retrieval head form a group, whose waves sweep the index keys 0..m up to four times:
 // sweep 0 finds the row maximum M; sweeps 1-3 histogram the softmax mass over the integer
 // q = floor(min((M - s) * 2^17, 2^21 - 1)) one base-128 digit at a time (all candidates in sweep 1, only
 // the members of the digit prefix found so far in sweeps 2 and 3) and scan the histogram from the top of
@@ -360,18 +360,19 @@ __global__ __launch_bounds__(kPfThreads, 2) void flash_prefill_kernel(const Pref
 // x 32 queries is ONE MFMA (K = 16) in the transposed layout, so a lane holds 16 keys of its own query.
 //
 // What makes the sweeps cheap:
-//  - index keys are fetched kSelRing tiles ahead into registers (the wave is alone on its SIMD, so
-//    nothing else hides the latency);
+//  - index keys are fetched kSelRing tiles ahead into registers (two waves share a SIMD: not enough to
+//    hide a load's latency by themselves);
 //  - interior tiles (every key a candidate of every query of the wave) carry no mask arithmetic;
-//  - the histogram of a wave is laid out [bin][query]: the 32 queries of a wave sit in 32 different
+//  - the histogram of a group is laid out [bin][query]: the 32 queries of a wave sit in 32 different
 //    LDS bank pairs whatever their bins, so an fp64 LDS atomic of the wave sees only the two-way
 //    conflict between the two lanes of one query;
 //  - q is a monotone function of the raw MFMA product x (s = x * index_scale), so "q lies in the digit
 //    prefix" is an interval of x.  Its two end points are found once per query and sweep by bisection
 //    over the float bit patterns, evaluating the very expression that defines q -- the comparisons of
 //    sweeps 2, 3 and of the attention kernel are then exact restatements of that definition, two
-//    (one) compare per pair, and only members do any further arithmetic.
-// No workgroup barrier: every wave owns its slice of LDS.
+//    (one) compare per pair, and only members do any further arithmetic;
+//  - sweep 0 records the largest product of the group in every pair of key tiles, and sweeps 2 and 3 -- whose
+//    members all lie at or above a known bound -- pass over the pairs that cannot hold one.
 // t = M - x * index_scale as ONE fused operation (one rounding): the definition every sweep, the end points
 // of the digit intervals and the final threshold share
 __device__ __forceinline__ float sel_t(float M, float x, float index_scale) { return __builtin_fmaf(-x, index_scale, M); }
