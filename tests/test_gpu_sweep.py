@@ -186,6 +186,16 @@ def _prefill_desc(rng):
                 kv_dtype=str(rng.choice(["bf16", "bf16", "fp16"])))
 
 
+def _peaked_prefill_desc(rng):
+    """Laws on which most key tiles hold no kept pair: a small own cluster with nearly all the mass, runs of
+    queries sharing a cluster, contexts of up to 200 key tiles, chunk lengths around the 256-query tile."""
+    d = _prefill_desc(rng)
+    d.update(T=int(rng.choice([31, 100, 256, 257, 300, 520])), start=int(rng.choice([0, 700, 4000, 9000, 12500])),
+             mode="direct", own_frac=float(rng.choice([0.97, 0.99, 0.995])), pick_run=int(rng.choice([1, 8, 32, 64])),
+             p=float(rng.choice([0.5, 0.8, 0.9])), cluster_len=int(rng.choice([4, 8, 32])))
+    return d
+
+
 def test_prefill_sweep():
     rng = np.random.default_rng(20260601)
     for case in range(100):
@@ -196,3 +206,28 @@ def test_prefill_sweep():
                              index_mode=d["mode"], kv_dtype=d["kv_dtype"])
         w.layer.index_scale = d["index_scale"]
         check_prefill_case(w.to(DEV), f"sweep{case}", d["p"])
+
+
+def test_prefill_sweep_peaked_laws():
+    """The tile lists of the selecting attention launch under random shapes: every case against the oracle, and
+    over the sweep most key tiles must have been left out."""
+    rng = np.random.default_rng(20260602)
+    visited = causal = 0
+    for case in range(40):
+        d = _peaked_prefill_desc(rng)
+        print("[case] prefill sweep, peaked", case, json.dumps(d), flush=True)
+        w = wl.small_prefill("cpu", seed=d["seed"], chunk_start=d["start"], T=d["T"], p=d["p"], n_q_heads=d["nq"],
+                             n_kv_heads=d["nkv"], ret_heads=d["ret"], sink=d["sink"], window=d["window"],
+                             index_mode="direct", kv_dtype=d["kv_dtype"], own_frac=d["own_frac"], pick_run=d["pick_run"],
+                             cluster_len=d["cluster_len"])
+        w.layer.index_scale = d["index_scale"]
+        w = w.to(DEV)
+        tp._check_sparse_prefill(w, f"peaked{case}", d["p"])
+        run = PrefillRun(w)
+        run.sparse_prefill()
+        v, c = run.tile_stats()
+        assert 0 < v <= c
+        visited += v
+        causal += c
+    print(f"   peaked sweep: {visited} of {causal} key tiles visited", flush=True)
+    assert visited < 0.8 * causal
