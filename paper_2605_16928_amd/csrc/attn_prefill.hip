@@ -67,7 +67,17 @@ struct PrefillArgs {
   int32_t n_t64;                // row length of tile_max
   int32_t* act_list;            // [n_ret, ceil(n_q / 256), n_t64]: the 64-key tiles a 256-query tile has to visit, ascending
   int32_t* act_count;           // [n_ret, ceil(n_q / 256)]
+  int32_t* act_range;           // {longest list, shortest list} of the launch (the search resets, the list kernel updates)
+  int32_t n_splits_even;        // key ranges per query tile when the lists are about equally long
 };
+
+// Key ranges a selecting launch behind a threshold search really uses: the grid is sized for lists that differ
+// wildly in length (many short ranges); when the shortest list is at least half the longest there is nothing to
+// even out and the few long ranges of the dense rule are cheaper (fewer partials to write and merge).
+__device__ __forceinline__ int listed_splits(const PrefillArgs& a) {
+  const int longest = a.act_range[0], shortest = a.act_range[1];
+  return (2 * shortest >= longest) ? min(a.n_splits_even, a.n_splits) : a.n_splits;
+}
 
 enum { kModeDense = 0, kModeLocal = 1, kModeSparse = 2 };
 // Per-query threshold search of the sparse mode: a score s is mapped to the integer
@@ -242,16 +252,16 @@ __global__ __launch_bounds__(kPfThreads, 2) void flash_prefill_kernel(const Pref
           bool ok = qok && n <= m;
           if (LOCAL) ok = ok && (n < a.sink || n > m - a.window);
           S[kb][i] = ok ? S[kb][i] : ninf;
-          mx = fmaxf(mx, S[kb][i]);
+          mx = max_nn(mx, S[kb][i]);
         }
       }
     } else {
 #pragma unroll
       for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
-        for (int i = 0; i < 16; ++i) mx = fmaxf(mx, S[kb][i]);
+        for (int i = 0; i < 16; ++i) mx = max_nn(mx, S[kb][i]);
     }
-    mx = fmaxf(mx, __shfl_xor(mx, 32));
+    mx = max_nn(mx, __shfl_xor(mx, 32));
     const float mnew = fmaxf(mrow, mx);
     uint32_t P[2][8];
     if (mnew == ninf) {
@@ -435,6 +445,10 @@ __global__ __launch_bounds__(kSelThreads, 2) void prefill_select_kernel(const Pr
     j = blockIdx.x % a.n_heads;
     qtile = blockIdx.x / a.n_heads;
   }
+  if (blockIdx.x == 0 && tid == 0) {                               // for prefill_active_tiles_kernel, which runs next
+    a.act_range[0] = 0;
+    a.act_range[1] = 0x7fffffff;
+  }
   if (qtile >= n_qtiles) return;                                   // (the whole workgroup)
   const int t0 = (n_qtiles - 1 - qtile) * kSelQ;                   // long rows first
   const int qgroup = wave / KS, part = wave - qgroup * KS;         // this wave's queries and its share of their keys
@@ -466,6 +480,7 @@ __global__ __launch_bounds__(kSelThreads, 2) void prefill_select_kernel(const Pr
   float xlo_wave = ninf;            // smallest x_lo over the wave's queries
   float xlo_wave_top = ninf;        // and the largest
   bool reach_known = false;         // sweep 3: the tile in hand is certain to hold a product at or above its query's x_lo
+  int n_looked = 0, n_needed = 0;   // sweep 3: tile pairs whose reach was worked out, and those found within reach
   int lcnt = 0;                     // entries in this lane's member list
   const uint32_t lst_base = (uint32_t)(size_t)(__attribute__((address_space(3))) float*)&lst[0][lane];
 
@@ -522,7 +537,7 @@ __global__ __launch_bounds__(kSelThreads, 2) void prefill_select_kernel(const Pr
 #pragma unroll
       for (int st = 8; st > 0; st >>= 1)
 #pragma unroll
-        for (int i = 0; i < st; ++i) v[i] = fmaxf(v[i], v[i + st]);
+        for (int i = 0; i < st; ++i) v[i] = max_nn(v[i], v[i + st]);
       mxacc = fmaxf(mxacc, v[0]);
       return v[0];
     } else if (phase == 1 || phase == 4) {
@@ -575,9 +590,11 @@ __global__ __launch_bounds__(kSelThreads, 2) void prefill_select_kernel(const Pr
           const int n = nb + (i >> 2) * 8 + g * 4 + (i & 3);
           v[i] = (!edge || (qok && n <= m)) ? SI[i] : ninf;
         }
-        const float top = fmaxf(fmaxf(fmaxf(fmaxf(v[0], v[1]), v[2]), fmaxf(fmaxf(v[3], v[4]), v[5])),
-                                fmaxf(fmaxf(fmaxf(fmaxf(v[6], v[7]), v[8]), fmaxf(fmaxf(v[9], v[10]), v[11])),
-                                      fmaxf(fmaxf(fmaxf(v[12], v[13]), v[14]), v[15])));
+#pragma unroll
+        for (int st = 8; st > 0; st >>= 1)
+#pragma unroll
+          for (int i = 0; i < st; ++i) v[i] = max_nn(v[i], v[i + st]);
+        const float top = v[0];
         reach = __ballot(top >= x_lo) != 0ull ? 1.f : 0.f;
         }
       }
@@ -606,10 +623,15 @@ __global__ __launch_bounds__(kSelThreads, 2) void prefill_select_kernel(const Pr
   // load has a whole group's arithmetic to land in; the kSelRing MFMAs of a group are issued together and
   // their latency hides behind one another.  No tail test: the interior range is a whole number of
   // rounds, and in the edge range a tile past the last one holds only keys n > m, which the causal mask drops.
-  auto sweep = [&](auto PH, auto EDGE, int tile_begin, int tile_end) {
+  // LOOK (sweeps 2 and 3): consult the maximum table pair by pair -- skip what cannot hold a member, and in sweep 3
+  // note which pairs a query can keep a key in.  Without it the sweep is the plain streaming one, which is what a
+  // stretch where nearly every pair can hold a member gets (looking would cost more than it saves there; the
+  // pairs keep their maxima in the table, which is the conservative answer).
+  auto sweep = [&](auto PH, auto EDGE, auto LOOK, int tile_begin, int tile_end) {
     if (tile_begin >= tile_end) return;
     constexpr int phase_ = decltype(PH)::value;
-    constexpr bool kSkip = phase_ == 2 || phase_ == 3;
+    constexpr bool kSkip = (phase_ == 2 || phase_ == 3) && decltype(LOOK)::value;
+    if (!kSkip) reach_known = true;
     static_assert(kSelMfma == 2, "a batch of MFMAs is one 64-key tile of the maximum table");
     u32x4 ringA[kSelRing], ringB[kSelRing];
     float tmA[kSelRing / 2], tmB[kSelRing / 2];                    // the table entries of the tile pairs in the rings
@@ -664,7 +686,11 @@ __global__ __launch_bounds__(kSelThreads, 2) void prefill_select_kernel(const Pr
         }
         // the last sweep knows better than the maximum: can one of the wave's queries keep a key of the pair?
         // (a pair known to reach keeps its maximum, which says the same)
-        if (phase_ == 3 && !reach_known && lane == 0) tmx[(first + hb) >> 1] = tmax > 0.f ? pinf : ninf;
+        if (phase_ == 3 && !reach_known) {
+          n_looked += 1;
+          n_needed += tmax > 0.f ? 1 : 0;
+          if (lane == 0) tmx[(first + hb) >> 1] = tmax > 0.f ? pinf : ninf;
+        }
         __builtin_amdgcn_sched_barrier(0);
       }
     };
@@ -680,7 +706,10 @@ __global__ __launch_bounds__(kSelThreads, 2) void prefill_select_kernel(const Pr
   const int plain_lo = (rounds * part / KS) * (2 * kSelRing), plain_hi = (rounds * (part + 1) / KS) * (2 * kSelRing);
   // Sweeps 2 and 3 over the mask-free range, 512 tiles (256 entries of the maximum table) at a time: where at most
   // a quarter of the tile pairs can hold a member, only those are fetched and looked at -- with a peaked score
-  // law that is a handful of pairs in a million keys -- otherwise the streaming sweep above runs over the stretch.
+  // law that is a handful of pairs in a million keys --; otherwise the streaming sweep above runs over the stretch,
+  // consulting the table per pair unless that can skip next to nothing and, in sweep 3, nine in ten of the pairs
+  // the wave has looked at turned out to hold a product some query can keep (a group with one moderately hard query
+  // among easy ones is not such a case: looking tells which pairs that query really keeps a key in).
   auto sweep_picked = [&](auto PH, int tile_begin, int tile_end) {
     constexpr int phase_ = decltype(PH)::value;
 #pragma unroll 1
@@ -696,8 +725,14 @@ __global__ __launch_bounds__(kSelThreads, 2) void prefill_select_kernel(const Pr
         on[k] = __ballot(tmv[k] >= xlo_wave);
         n_on += __popcll(on[k]);
       }
+      // next to nothing to skip, and (sweep 3) the pairs looked at so far nearly all turned out to be needed:
+      // stream, do not look
+      if (n_on > 240 && (phase_ == 2 || (n_looked >= 64 && 10 * n_needed >= 9 * n_looked))) {
+        sweep(PH, std::false_type{}, std::false_type{}, tb, te);
+        continue;
+      }
       if (n_on > 64) {
-        sweep(PH, std::false_type{}, tb, te);
+        sweep(PH, std::false_type{}, std::true_type{}, tb, te);
         continue;
       }
 #pragma unroll
@@ -727,8 +762,8 @@ __global__ __launch_bounds__(kSelThreads, 2) void prefill_select_kernel(const Pr
   auto sweep_all = [&](auto PH) {
     constexpr int phase_ = decltype(PH)::value;
     if constexpr (phase_ == 2 || phase_ == 3) sweep_picked(PH, plain_lo, plain_hi);
-    else sweep(PH, std::false_type{}, plain_lo, plain_hi);
-    if (part == KS - 1) sweep(PH, std::true_type{}, n_plain, n_tiles);
+    else sweep(PH, std::false_type{}, std::false_type{}, plain_lo, plain_hi);
+    if (part == KS - 1) sweep(PH, std::true_type{}, std::true_type{}, n_plain, n_tiles);
     if (phase_ == 2 || phase_ == 3) drain_list();
   };
 
@@ -903,13 +938,23 @@ __global__ __launch_bounds__(64 * (8 / QB), QB == 1 ? 2 : 1) void flash_prefill_
   // A selecting launch behind a threshold search (one sequence) is laid out (key range, query tile, head slot): the
   // query tiles' lists differ wildly in length, and with the key range as the fastest index the ranges of a long
   // list go round all eight dies (workgroups are dealt to the dies in turn) instead of piling up on one.
+  // The grid of such a launch is sized for the finer cut; the ranges really used (listed_splits) take the
+  // first workgroups of the grid in the same (key range, query tile, head slot) order, the others leave.
   const bool listed = SPARSE && a.p < 1.f;
-  const int hslot = listed ? blockIdx.z : blockIdx.x;
+  const int n_splits = LOCAL ? 1 : (listed ? listed_splits(a) : a.n_splits);
+  int hslot = blockIdx.x, split, qt_rev = blockIdx.y, b = 0;
+  if (listed) {
+    const int lin = (int)blockIdx.x + (int)gridDim.x * ((int)blockIdx.y + (int)gridDim.y * (int)blockIdx.z);
+    split = lin % n_splits;
+    qt_rev = (lin / n_splits) % (int)gridDim.y;
+    hslot = lin / (n_splits * (int)gridDim.y);
+    if (hslot >= (int)gridDim.z) return;
+  } else {
+    b = blockIdx.z / n_splits;
+    split = (int)blockIdx.z - b * n_splits;
+  }
   const int h = a.heads[hslot];
-  const int n_splits = LOCAL ? 1 : a.n_splits;
-  const int b = listed ? 0 : blockIdx.z / n_splits;
-  const int split = listed ? (int)blockIdx.x : (int)blockIdx.z - b * n_splits;
-  const int t0 = ((int)gridDim.y - 1 - (int)blockIdx.y) * kPwQ;
+  const int t0 = ((int)gridDim.y - 1 - qt_rev) * kPwQ;
   const int kvh = h / (a.n_q_heads / a.n_kv_heads);
   const int pos0 = a.q_start ? a.q_start[b] : (int)a.q_start_host;
   const int64_t tok0 = a.seq_start ? a.seq_start[b] : 0;
@@ -943,7 +988,7 @@ __global__ __launch_bounds__(64 * (8 / QB), QB == 1 ? 2 : 1) void flash_prefill_
   }
   // selecting mode with a threshold search in front: only the tiles on this query tile's list (ascending
   // 64-key tile numbers, written by prefill_active_tiles_kernel) can hold a kept pair
-  const int qt_list = (int)gridDim.y - 1 - (int)blockIdx.y;
+  const int qt_list = (int)gridDim.y - 1 - qt_rev;
   const int32_t* const alist = listed ? a.act_list + ((int64_t)hslot * gridDim.y + qt_list) * a.n_t64 : nullptr;
   const int n_tiles = listed ? a.act_count[(int64_t)hslot * gridDim.y + qt_list] : ks_end + (kt_end - kt_w0 + 1);
   const uint16_t* Kg = a.K + (int64_t)kvh * a.head_stride + tok0 * a.row_stride;
@@ -1505,7 +1550,11 @@ __global__ __launch_bounds__(256) void prefill_active_tiles_kernel(const Prefill
     base += wave_n[0] + wave_n[1] + wave_n[2] + wave_n[3];
     __syncthreads();
   }
-  if (tid == 0) a.act_count[(int64_t)j * gridDim.x + qt] = base;
+  if (tid == 0) {
+    a.act_count[(int64_t)j * gridDim.x + qt] = base;
+    atomicMax(&a.act_range[0], base);
+    atomicMin(&a.act_range[1], base);
+  }
 }
 
 // qI[j, t, :] = bf16( W[j] . x[t, ret_heads[j], :] ), the 128-term sums in fp64, one rounding
@@ -1534,16 +1583,17 @@ __global__ __launch_bounds__(256) void prefill_combine_kernel(const PrefillArgs 
   const int t = blockIdx.x * 2 + (threadIdx.x >> 7), d = threadIdx.x & 127, hs = blockIdx.y;
   if (t >= a.n_q) return;
   const float ninf = -__builtin_huge_valf();
+  const int n_splits = a.act_range ? listed_splits(a) : a.n_splits;     // (a listed launch decides on the device)
   float M = ninf;
-  for (int s = 0; s < a.n_splits; ++s) M = fmaxf(M, a.part[(((int64_t)s * a.n_heads + hs) * a.n_q + t) * kPfPart]);
+  for (int s = 0; s < n_splits; ++s) M = fmaxf(M, a.part[(((int64_t)s * a.n_heads + hs) * a.n_q + t) * kPfPart]);
   if (a.count && d == 0) {                                 // selecting mode: kept keys over all key ranges
     int kept = 0;
-    for (int s = 0; s < a.n_splits; ++s) kept += __float_as_int(a.part[(((int64_t)s * a.n_heads + hs) * a.n_q + t) * kPfPart + 2]);
+    for (int s = 0; s < n_splits; ++s) kept += __float_as_int(a.part[(((int64_t)s * a.n_heads + hs) * a.n_q + t) * kPfPart + 2]);
     a.count[(int64_t)hs * a.n_q + t] = kept;
   }
   float L = 0.f, A = 0.f;
   if (M != ninf) {
-    for (int s = 0; s < a.n_splits; ++s) {
+    for (int s = 0; s < n_splits; ++s) {
       const float* p = a.part + (((int64_t)s * a.n_heads + hs) * a.n_q + t) * kPfPart;
       if (p[0] == ninf) continue;
       const float cw = fast_exp2((p[0] - M) * a.scale_log2);
@@ -1690,7 +1740,7 @@ static PrefillTileWs prefill_tile_ws(int32_t n_ret, int32_t T, int64_t chunk_sta
   w.n_t64 = (int32_t)(((chunk_start + T + 31) / 32 + 32) / 2 + 1);
   w.table_bytes = align_up((size_t)n_ret * ((T + 31) / 32) * w.n_t64 * sizeof(float), 256);
   w.list_bytes = align_up((size_t)n_ret * ((T + kPwQ - 1) / kPwQ) * w.n_t64 * sizeof(int32_t), 256);
-  w.count_bytes = align_up((size_t)n_ret * ((T + kPwQ - 1) / kPwQ) * sizeof(int32_t), 256);
+  w.count_bytes = align_up(((size_t)n_ret * ((T + kPwQ - 1) / kPwQ) + 2) * sizeof(int32_t), 256);   // + {longest, shortest}
   return w;
 }
 
@@ -1809,6 +1859,11 @@ extern "C" int32_t rtp_sparse_attn_prefill(const rtp_layer_desc* layer, const vo
     a.tile_max = (float*)at;
     a.act_list = (int32_t*)(at + tw.table_bytes);
     a.act_count = (int32_t*)(at + tw.table_bytes + tw.list_bytes);
+    if (p < 1.f) {
+      // (the last two ints of the counts' region)
+      a.act_range = a.act_count + (tw.count_bytes / sizeof(int32_t) - 2);
+      a.n_splits_even = std::max(2, choose_splits(layer->n_ret, T, chunk_start));
+    }
   }
   if (p < 1.f) {
     constexpr int ks = 8;                                  // waves per 32-query group (see the kernel's header)

@@ -162,10 +162,15 @@ __device__ __forceinline__ double wave_incl_scan(double x) {
 __device__ __forceinline__ int wave_last(int x) { return __builtin_amdgcn_readlane(x, 63); }
 // Wave-wide sum / maximum of non-negative-or-(-1) ints, in every lane.
 __device__ __forceinline__ int wave_sum(int x) { return wave_last(wave_incl_scan(x)); }
+// max(a, b) of two values that are never NaN, as ONE vector instruction (the median of a, b and +inf).  fmaxf()
+// has to quiet signalling NaNs, which costs a canonicalising instruction for every operand the compiler cannot
+// prove quiet -- matrix-core results, cross-lane moves -- i.e. three instructions per maximum in such places.
+__device__ __forceinline__ float max_nn(float a, float b) { return __builtin_amdgcn_fmed3f(a, b, __builtin_huge_valf()); }
+
 // Wave-wide maximum of floats, in every lane (same six steps; a lane without a source takes -inf).
 __device__ __forceinline__ float wave_max_f32(float x) {
   const int ninf_bits = 0xff800000;
-#define RTP_STEP(CTRL, MASK) x = fmaxf(x, __int_as_float(__builtin_amdgcn_update_dpp(ninf_bits, __float_as_int(x), CTRL, MASK, 0xf, false)));
+#define RTP_STEP(CTRL, MASK) x = max_nn(x, __int_as_float(__builtin_amdgcn_update_dpp(ninf_bits, __float_as_int(x), CTRL, MASK, 0xf, false)));
   RTP_WAVE_SCAN_STEPS(RTP_STEP)
 #undef RTP_STEP
   return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(x), 63));
