@@ -165,7 +165,12 @@ __device__ __forceinline__ int wave_sum(int x) { return wave_last(wave_incl_scan
 // max(a, b) of two values that are never NaN, as ONE vector instruction (the median of a, b and +inf).  fmaxf()
 // has to quiet signalling NaNs, which costs a canonicalising instruction for every operand the compiler cannot
 // prove quiet -- matrix-core results, cross-lane moves -- i.e. three instructions per maximum in such places.
-__device__ __forceinline__ float max_nn(float a, float b) { return __builtin_amdgcn_fmed3f(a, b, __builtin_huge_valf()); }
+// (+inf comes out of an assembly statement: given the constant, the compiler turns the median back into a maximum.)
+__device__ __forceinline__ float max_nn(float a, float b) {
+  float pinf;
+  asm("s_mov_b32 %0, 0x7f800000" : "=s"(pinf));
+  return __builtin_amdgcn_fmed3f(a, b, pinf);
+}
 
 // Wave-wide maximum of floats, in every lane (same six steps; a lane without a source takes -inf).
 __device__ __forceinline__ float wave_max_f32(float x) {
