@@ -26,8 +26,8 @@ HBM_PEAK_GBS = 8000.0
 
 
 def kernel_algorithmic_bytes(R, N, sel_total, bytes_local, G):
-    """Algorithmic HBM bytes per launch of the kernels of one decode step (per-unit figures of the design notes x
-    the units a launch processes): 32 B of index key + 4 B of score per (token, retrieval row); 4 B per score and
+    """Algorithmic HBM bytes per launch of the kernels of one decode step (bytes per unit x the units a launch
+    processes): 32 B of index key + 4 B of score per (token, retrieval row); 4 B per score and
     pass of the selector; 512 B of K/V + 4 B of index per selected token; 512 B per (token, KV head) of the local
     heads' sink + window sets.  Merge launches move partials only (no per-unit figure)."""
     scores = R * N * 4
@@ -379,7 +379,7 @@ def main() -> int:
             "dense_attn_us": round(timed(lambda i: rf[i % 2].dense_attn(rf[i % 2].out), max(10, it // 10), 2), 2)}
     del rf
 
-    # ---- algorithmic bytes per step (design notes: per-unit figures x units) ----
+    # ---- algorithmic bytes per step (bytes per unit x units) ----
     sel_total = int(sel_counts.sum())
     bytes_index = B * n_ret * N * (32 + 4)
     bytes_topp = B * n_ret * N * 4 + sel_total * 4            # one read of the scores + the index list
