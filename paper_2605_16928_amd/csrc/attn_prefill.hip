@@ -916,7 +916,11 @@ constexpr int kPwStages = 3;
 // direct global->LDS loads (16 bytes per lane, a wave's 64 lanes fill 1 KiB contiguously), so bank
 // spreading comes from the order of the 16-byte chunks inside a row instead: K row n keeps chunk c at
 // position c ^ (n % 16) (the MFMA operand read takes one chunk of 16 consecutive rows), V row n keeps
-// 32-byte unit u at position u ^ (n % 8) (the transposing operand read takes 32 bytes of 8 rows).
+// 32-byte unit u at position u ^ 2 (n % 4): a transposing operand read has each half-wave take, from four rows,
+// the two units 2 db and 2 db + 1 (its two 16-lane groups), and with this order those eight (row, unit) pieces
+// land on the eight different bank groups of a row (u ^ (n % 8), the first layout, put the two groups' pieces on
+// the same four: a third of the kernel's LDS cycles were bank conflicts by the counters, none now; the kernel is
+// bound by instruction issue and runs as long).
 constexpr int kPwTileBytes = 2 * kPfK * kHeadDim * 2;
 constexpr int kSmemWide = kPwTileBytes * kPwStages;
 typedef short s16x4 __attribute__((ext_vector_type(4)));
@@ -1058,7 +1062,7 @@ __global__ __launch_bounds__(64 * (8 / QB), QB == 1 ? 2 : 1) void flash_prefill_
   const int ld_row = 4 * wave + (lane >> 4);
   const int ld_pos = lane & 15;
   const int ld_ck = ld_pos ^ (ld_row & 15);                                          // K chunk of this lane
-  const int ld_cv = ((((ld_pos >> 1) ^ (ld_row & 7)) << 1) | (ld_pos & 1));          // V chunk of this lane
+  const int ld_cv = ((((ld_pos >> 1) ^ (2 * (ld_row & 3))) << 1) | (ld_pos & 1));    // V chunk of this lane
   auto load_piece = [&](int n0, int slot, int j) __attribute__((always_inline)) {
     const int jj = j % GH;
     const int n = min(n0 + RG * jj + ld_row, m_hi);
@@ -1095,7 +1099,7 @@ __global__ __launch_bounds__(64 * (8 / QB), QB == 1 ? 2 : 1) void flash_prefill_
   const int rd_k = r * 256, rd_kx = (g ^ (r & 15)) << 4;                              // K: + kb * 8192, chunk (2 kk) ^ ...
   const int rd_j = lane & 15, rd_G = (lane >> 4) & 1;
   const int rd_v = kPwTileBytes / 2 + (4 * g + (rd_j >> 2)) * 256 + 8 * (rd_j & 3);   // V: + (kb * 32 + 16 tt + 8 h) * 256
-  const int rd_vx = (rd_G ^ (4 * g + (rd_j >> 2))) << 5;                              //    unit (2 db) ^ ...
+  const int rd_vx = (rd_G ^ (2 * (rd_j >> 2))) << 5;                                  //    unit (2 db) ^ ...
   auto read_k = [&](const unsigned char* tile, int kb, int kk) __attribute__((always_inline)) {
     return *reinterpret_cast<const u32x4*>(tile + kb * 8192 + rd_k + ((kk << 5) ^ rd_kx));
   };
