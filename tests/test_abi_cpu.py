@@ -346,3 +346,26 @@ def test_paged_decode_attention_and_dtype_argument_checks():
     assert call(page_size=8) == rtp.RTP_ERR_INVALID_ARG
     assert call(pt_stride=63) == rtp.RTP_ERR_INVALID_ARG and b"pt_stride" in lib.rtp_last_error()
     assert call(q=None) == rtp.RTP_ERR_INVALID_ARG
+
+
+def test_prefill_tile_statistics_argument_checks():
+    """rtp_sparse_attn_prefill_tile_stats checks its arguments and the workspace size before it touches the
+    device (the pointers here are fake)."""
+    lib = rtp.lib()
+    L = _layer()
+    vp = C.c_void_p
+    vis, causal = C.c_int64(-1), C.c_int64(-1)
+    need = lib.rtp_sparse_attn_prefill_workspace_bytes(C.byref(L), 300, 3000)
+    assert need > 0
+    rc = lib.rtp_sparse_attn_prefill_tile_stats(C.byref(L), 0, 3000, vp(A), need, None, C.byref(vis), C.byref(causal))
+    assert rc == rtp.RTP_ERR_INVALID_ARG
+    rc = lib.rtp_sparse_attn_prefill_tile_stats(C.byref(L), 300, 3000, vp(A), need, None, None, C.byref(causal))
+    assert rc == rtp.RTP_ERR_INVALID_ARG
+    rc = lib.rtp_sparse_attn_prefill_tile_stats(C.byref(L), 300, 3000, vp(A), need - 256, None, C.byref(vis), C.byref(causal))
+    assert rc == rtp.RTP_ERR_WORKSPACE and b"workspace" in lib.rtp_last_error()
+    rc = lib.rtp_sparse_attn_prefill_tile_stats(C.byref(L), 300, 3000, None, need, None, C.byref(vis), C.byref(causal))
+    assert rc == rtp.RTP_ERR_WORKSPACE
+    # a layer without retrieval heads has nothing to visit
+    L0 = _layer(ret_heads=[])
+    rc = lib.rtp_sparse_attn_prefill_tile_stats(C.byref(L0), 300, 3000, None, 0, None, C.byref(vis), C.byref(causal))
+    assert rc == rtp.RTP_OK and vis.value == 0 and causal.value == 0
