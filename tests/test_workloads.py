@@ -1,6 +1,7 @@
 """The seeded input generators: determinism, layout, and that the recipes give the
 indexer-mass structure they promise (checked with the oracle on small sizes)."""
 import numpy as np
+import pytest
 import torch
 
 from oracle import rtp_oracle as orc
@@ -60,3 +61,23 @@ def test_c5_recipe_spans_flat_to_peaked():
             s = orc.index_score(qI[b, j], kI[j, t0:t0 + n])
             fr.append(orc.topp_select(s, float(w.p_rows[b * w.layer.n_ret + j]))["count"] / n)
     assert max(fr) > 0.6 and min(fr) < 0.1
+
+
+def test_prefill_laws_broad_and_peaked():
+    """The prefill recipes at a size the oracle handles: with the own cluster at 99 % of the mass and runs of
+    queries sharing a cluster, top-p 0.9 stays inside the cluster (a handful of tokens, the same for the queries of
+    a run); with the broad law (own cluster 80 %) it reaches into the tail."""
+    kept = {}
+    for name, kw in (("peaked", dict(own_frac=0.99, pick_run=32)), ("broad", dict())):
+        w = wl.small_prefill("cpu", seed=70, chunk_start=6000, T=96, p=0.9, **kw)
+        kI, qI = wl.bf16_bits(w.kI), wl.bf16_bits(w.qI)
+        kept[name] = np.array([orc.topp_select(orc.index_score(qI[0, t], kI[0, :6000 + t + 1]), 0.9)["count"]
+                               for t in range(0, 96, 4)])
+    assert np.median(kept["peaked"]) <= 10 < np.median(kept["broad"])
+    # pick_run: the index queries of a run aim at one cluster
+    w = wl.small_prefill("cpu", seed=70, chunk_start=6000, T=96, p=0.9, own_frac=0.99, pick_run=32)
+    q = w.qI[0].float()
+    cos = torch.nn.functional.cosine_similarity(q[:32].mean(0, keepdim=True), q[:32]).min()
+    assert cos > 0.8
+    with pytest.raises(ValueError):
+        wl.c4_chunk("cpu", law="sharp", T=8, chunk=0)
